@@ -1,0 +1,273 @@
+"""Python face of the fp64 CPU oracle.
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  The product package never imports this module and
+this module never imports the product package.
+
+Contents
+  * word-set construction written independently of the GPU library's builder
+    (Section 3.1 prefix-closed sets; Appendix A canonical order; Definition 7.1
+    weighted degree),
+  * ctypes wrappers around sig_oracle.c (dense tensor-algebra route and
+    per-word eq.-3 route, forward and reverse-mode backward),
+  * the error measures used by the parity tests.
+
+Parity pins: every function here is pinned by tests/test_oracle_pins.py against
+closed forms, algebraic identities, brute-force iterated sums and fp64 finite
+differences.  Nothing is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Dict, Iterable, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+Word = Tuple[int, ...]
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sig_oracle.c")
+_LIB = os.path.join(_HERE, "libsig_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile sig_oracle.c with gcc (-O2, OpenMP).  Building the checker is not using it."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".{os.getpid()}.tmp"
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c99", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i64, i32, p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+        lib.sig_oracle_threads.restype = ctypes.c_int
+        lib.sig_oracle_set_threads.argtypes = [i32]
+        lib.sig_oracle_dense_size.restype = ctypes.c_size_t
+        lib.sig_oracle_dense_size.argtypes = [i32, i32]
+        lib.sig_oracle_tensor_product.argtypes = [i32, i32, p, p, p]
+        lib.sig_oracle_forward_dense.argtypes = [p, i64, i64, i32, i32, p]
+        lib.sig_oracle_backward_dense.argtypes = [p, p, i64, i64, i32, i32, p]
+        lib.sig_oracle_forward_words.argtypes = [p, i64, i64, i32, i64, p, p, p, p]
+        lib.sig_oracle_backward_words.argtypes = [p, p, i64, i64, i32, i64, p, p, p, p]
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    return int(_load().sig_oracle_threads())
+
+
+def set_threads(n: int) -> None:
+    _load().sig_oracle_set_threads(int(n))
+
+
+# ----------------------------------------------------------------------------------------------
+# word sets (independent of the GPU library's C++ builder)
+# ----------------------------------------------------------------------------------------------
+
+def truncated_words(d: int, depth: int) -> List[Word]:
+    """All non-empty words of length <= depth, level-major and lexicographic inside a
+    level, i.e. ordered by the base-d encoding plus level offset (Appendix A)."""
+    out: List[Word] = []
+    level: List[Word] = [()]
+    for _ in range(depth):
+        level = [w + (i,) for w in level for i in range(d)]
+        out.extend(level)
+    return out
+
+
+def anisotropic_words(d: int, weights: Sequence[float], cutoff: float) -> List[Word]:
+    """Non-empty words with weighted degree <= cutoff (Definition 7.1).  The degree is the
+    left-to-right fp64 sum of the letters' weights; a word is kept iff sum <= cutoff."""
+    if len(weights) != d or any(not (g > 0.0) for g in weights):
+        raise ValueError("weights must be d positive numbers")
+    out: List[Word] = []
+    level: List[Tuple[Word, float]] = [((), 0.0)]
+    while level:
+        nxt: List[Tuple[Word, float]] = []
+        for w, deg in level:
+            for i in range(d):
+                s = deg + float(weights[i])
+                if s <= cutoff:
+                    nxt.append((w + (i,), s))
+        out.extend(w for w, _ in nxt)
+        level = nxt
+    return sort_canonical(out)
+
+
+def sort_canonical(words: Iterable[Word]) -> List[Word]:
+    return sorted(set(tuple(int(c) for c in w) for w in words), key=lambda w: (len(w), w))
+
+
+def prefix_closure(words: Iterable[Word]) -> List[Word]:
+    """Smallest prefix-closed set containing the given words (Definition 3.3), canonical
+    order, the empty word left out."""
+    s = set()
+    for w in words:
+        w = tuple(int(c) for c in w)
+        for k in range(1, len(w) + 1):
+            s.add(w[:k])
+    return sort_canonical(s)
+
+
+def word_tables(closed: Sequence[Word], user: Optional[Sequence[Word]] = None) -> Dict[str, np.ndarray]:
+    """parent / last-letter / level-start tables of a canonical prefix-closed set, and the
+    canonical index of every user word."""
+    index = {w: k for k, w in enumerate(closed)}
+    n = len(closed)
+    parent = np.full(n, -1, dtype=np.int32)
+    letter = np.zeros(n, dtype=np.int32)
+    max_len = max((len(w) for w in closed), default=0)
+    level_start = np.zeros(max_len + 2, dtype=np.int32)
+    for k, w in enumerate(closed):
+        letter[k] = w[-1]
+        if len(w) > 1:
+            parent[k] = index[w[:-1]]
+        level_start[len(w) + 1] += 1
+    level_start = np.cumsum(level_start).astype(np.int32)
+    tabs = {"parent": parent, "letter": letter, "level_start": level_start}
+    if user is not None:
+        tabs["user_index"] = np.array([index[tuple(int(c) for c in w)] for w in user], dtype=np.int64)
+    return tabs
+
+
+def _csr(closed: Sequence[Word]):
+    index = {w: k for k, w in enumerate(closed)}
+    offs = np.zeros(len(closed) + 1, dtype=np.int64)
+    for k, w in enumerate(closed):
+        offs[k + 1] = offs[k] + len(w)
+    letters = np.zeros(max(int(offs[-1]), 1), dtype=np.int32)
+    pidx = np.zeros(max(int(offs[-1]), 1), dtype=np.int64)
+    for k, w in enumerate(closed):
+        o = int(offs[k])
+        for r, c in enumerate(w):
+            letters[o + r] = c
+            pidx[o + r] = index[w[: r + 1]]          # KeyError here means the set is not prefix-closed
+    return letters, offs, pidx
+
+
+# ----------------------------------------------------------------------------------------------
+# forward / backward
+# ----------------------------------------------------------------------------------------------
+
+def _as_path(path) -> np.ndarray:
+    a = np.ascontiguousarray(np.asarray(path), dtype=np.float32)
+    if a.ndim != 3:
+        raise ValueError("path must be [B, L+1, d]")
+    return a
+
+
+def dense_size(d: int, depth: int) -> int:
+    return int(_load().sig_oracle_dense_size(d, depth))
+
+
+def tensor_product(d: int, depth: int, A: np.ndarray, Bt: np.ndarray) -> np.ndarray:
+    """Truncated tensor product of two dense elements laid out [1 | level 1 | ... | level depth]."""
+    A = np.ascontiguousarray(A, dtype=np.float64)
+    Bt = np.ascontiguousarray(Bt, dtype=np.float64)
+    C = np.zeros_like(A)
+    _load().sig_oracle_tensor_product(d, depth, A.ctypes.data, Bt.ctypes.data, C.ctypes.data)
+    return C
+
+
+def forward_dense(path, depth: int, keep_level0: bool = False) -> np.ndarray:
+    """Truncated signature, fp64 [B, sum_{n=1..depth} d^n] in canonical order."""
+    X = _as_path(path)
+    B, P, d = X.shape
+    tot = dense_size(d, depth)
+    out = np.zeros((B, tot), dtype=np.float64)
+    rc = _load().sig_oracle_forward_dense(X.ctypes.data, B, P, d, depth, out.ctypes.data)
+    if rc:
+        raise RuntimeError(f"oracle forward_dense failed ({rc})")
+    return out if keep_level0 else out[:, 1:]
+
+
+def backward_dense(path, depth: int, grad_coeffs) -> np.ndarray:
+    """d(sum grad*S)/d path for the truncated signature, fp64 [B, L+1, d]."""
+    X = _as_path(path)
+    B, P, d = X.shape
+    tot = dense_size(d, depth)
+    g = np.zeros((B, tot), dtype=np.float64)
+    g[:, 1:] = np.asarray(grad_coeffs, dtype=np.float64)
+    gp = np.zeros((B, P, d), dtype=np.float64)
+    rc = _load().sig_oracle_backward_dense(X.ctypes.data, g.ctypes.data, B, P, d, depth, gp.ctypes.data)
+    if rc:
+        raise RuntimeError(f"oracle backward_dense failed ({rc})")
+    return gp
+
+
+def forward_words(path, closed: Sequence[Word]) -> np.ndarray:
+    """Coefficients of a canonical prefix-closed word set via eq. 3, fp64 [B, |W|]."""
+    X = _as_path(path)
+    B, P, d = X.shape
+    letters, offs, pidx = _csr(closed)
+    out = np.zeros((B, len(closed)), dtype=np.float64)
+    rc = _load().sig_oracle_forward_words(X.ctypes.data, B, P, d, len(closed), letters.ctypes.data,
+                                          offs.ctypes.data, pidx.ctypes.data, out.ctypes.data)
+    if rc:
+        raise RuntimeError(f"oracle forward_words failed ({rc})")
+    return out
+
+
+def backward_words(path, closed: Sequence[Word], grad_coeffs) -> np.ndarray:
+    X = _as_path(path)
+    B, P, d = X.shape
+    letters, offs, pidx = _csr(closed)
+    g = np.ascontiguousarray(np.asarray(grad_coeffs, dtype=np.float64))
+    assert g.shape == (B, len(closed))
+    gp = np.zeros((B, P, d), dtype=np.float64)
+    rc = _load().sig_oracle_backward_words(X.ctypes.data, g.ctypes.data, B, P, d, len(closed), letters.ctypes.data,
+                                           offs.ctypes.data, pidx.ctypes.data, gp.ctypes.data)
+    if rc:
+        raise RuntimeError(f"oracle backward_words failed ({rc})")
+    return gp
+
+
+def gather_from_dense(dense: np.ndarray, d: int, words: Sequence[Word]) -> np.ndarray:
+    """Pick the coefficients of `words` out of a dense truncated result (level 0 dropped):
+    index = level offset + base-d encoding (Appendix A)."""
+    idx = np.empty(len(words), dtype=np.int64)
+    for k, w in enumerate(words):
+        n = len(w)
+        off = sum(d ** m for m in range(1, n))
+        phi = 0
+        for c in w:
+            phi = phi * d + c
+        idx[k] = off + phi
+    return dense[:, idx]
+
+
+# ----------------------------------------------------------------------------------------------
+# error measures used by the parity tests
+# ----------------------------------------------------------------------------------------------
+
+def level_errors(test: np.ndarray, ref: np.ndarray, lengths: np.ndarray) -> Dict[int, float]:
+    """For every word length n: max over paths of  max_{|w|=n} |test-ref| / ||ref restricted to
+    length n||_2  (per path).  A level whose reference is identically zero must match exactly."""
+    out: Dict[int, float] = {}
+    test = np.asarray(test, dtype=np.float64)
+    for n in sorted(set(int(x) for x in lengths)):
+        m = lengths == n
+        num = np.abs(test[:, m] - ref[:, m]).max(axis=1)
+        den = np.sqrt((ref[:, m] ** 2).sum(axis=1))
+        with np.errstate(divide="ignore", invalid="ignore"):
+            r = np.where(den > 0, num / den, np.where(num == 0, 0.0, np.inf))
+        out[n] = float(r.max()) if r.size else 0.0
+    return out
+
+
+def grad_errors(test: np.ndarray, ref: np.ndarray) -> np.ndarray:
+    """Per path  ||test-ref||_inf / ||ref||_inf."""
+    test = np.asarray(test, dtype=np.float64)
+    B = ref.shape[0]
+    num = np.abs(test - ref).reshape(B, -1).max(axis=1)
+    den = np.abs(ref).reshape(B, -1).max(axis=1)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        return np.where(den > 0, num / den, np.where(num == 0, 0.0, np.inf))
