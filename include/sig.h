@@ -1,0 +1,153 @@
+/*
+ * sig.h - C ABI of the MI355X (gfx950) path-signature library.
+ *
+ * What it computes: coefficients S_{0,T}(X, w) of the signature of batched
+ * piecewise-linear paths for all words w of a prefix-closed word set W
+ * (Section 3.1), and the gradient of a scalar loss with respect to the path
+ * points given the gradient with respect to those coefficients (Section 4).
+ *
+ * Conventions
+ *   - Letters are 0-based: {0, .., d-1} (Appendix A).
+ *   - W never contains the empty word; its coefficient is the constant 1.
+ *   - Canonical order of W: by word length, then lexicographic.  For a full
+ *     depth-N truncation this is "cumulative level offset + base-d encoding"
+ *     (Appendix A, word integer encoding), i.e. levels 1..N concatenated,
+ *     each row-major.
+ *   - A path is float32 [B, n_points, d], row-major, n_points = L + 1 >= 1.
+ *   - coeffs / grad_coeffs are float32 [B, |W|] in canonical order.
+ *   - Every function returns 0 on success and a negative SIG_E* code on
+ *     failure; nothing is printed, no exception or abort crosses the ABI.
+ *   - "host" / "device" on a pointer says where the memory lives.  The library
+ *     owns only sig_wordset objects (host memory).  All device memory is the
+ *     caller's; the library never allocates or frees device memory.
+ *   - sig_forward / sig_backward only enqueue work on the given HIP stream
+ *     (hipStream_t passed as void*; NULL = the null stream) and return
+ *     without synchronising.  Outputs are overwritten, never accumulated into.
+ *   - The kernels are compiled for gfx950 only.
+ */
+#ifndef SIG_MI355X_H
+#define SIG_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SIG_OK            0
+#define SIG_EINVAL       (-1)  /* null pointer, d < 1, negative size, depth < 1, bad weights/cutoff, ... */
+#define SIG_ELETTER      (-2)  /* a letter outside [0, d)                                                */
+#define SIG_EEMPTYWORD   (-3)  /* the word list contains an empty word, or no word at all               */
+#define SIG_ENOMEM       (-4)  /* host allocation failed                                                 */
+#define SIG_EWORKSPACE   (-5)  /* workspace / table buffer missing or too small                          */
+#define SIG_EHIP         (-6)  /* a HIP runtime call failed; see sig_last_hip_error()                    */
+#define SIG_ETOOLARGE    (-7)  /* word set exceeds a format limit (see SIG_MAX_*)                        */
+#define SIG_ENOTUPLOADED (-8)  /* sig_forward/sig_backward called before sig_wordset_upload              */
+#define SIG_EUNSUPPORTED (-9)  /* word length above what the kernels handle (SIG_MAX_KERNEL_LEN)         */
+
+#define SIG_MAX_WORD_LEN    32          /* table format limit on |w|                                     */
+#define SIG_MAX_KERNEL_LEN  12          /* longest word the GPU kernels handle                           */
+#define SIG_MAX_WORDS       0x7fffffff  /* |W| < 2^31                                                    */
+
+typedef struct sig_wordset sig_wordset;   /* opaque, host-owned */
+
+/* ---- word-set construction (host, integer only; Section 3.1, Section 7, Appendix A) -------------------
+ *
+ * Each builder produces the canonical tables of a prefix-closed set:
+ *   parent[w]      index of the word with the last letter removed, -1 if that is the empty word
+ *   letter[w]      last letter of w
+ *   level_start[n] index of the first word of length n, n = 1..max_len; level_start[0] = 0,
+ *                  level_start[max_len + 1] = |W|
+ * plus the launch plan the kernels use.  *out is set only on success and must be released
+ * with sig_wordset_free.
+ */
+
+/* All words of length 1..depth over d letters (truncation pi_{<=N}, Section 2.1).  |W| = sum d^n. */
+int sig_wordset_build_truncated(int d, int depth, sig_wordset** out);
+
+/* All non-empty words with weighted degree <= cutoff (Definition 7.1).  weights: host, d doubles, each > 0.
+ * The degree is accumulated left to right in double; a word is kept iff degree <= cutoff, no tolerance. */
+int sig_wordset_build_anisotropic(int d, const double* weights, double cutoff, sig_wordset** out);
+
+/* Arbitrary word list (word projection, Section 7.1) in CSR form: word k has letters
+ * letters[offsets[k] .. offsets[k+1]).  Both arrays are host memory; offsets has n_words + 1
+ * non-decreasing entries starting at 0.  Any order, duplicates allowed.  The list is closed under
+ * prefixes; user_index[k] is the canonical index of word k in the closed set. */
+int sig_wordset_build(int d, const int32_t* letters, const int64_t* offsets, int64_t n_words, sig_wordset** out);
+
+void sig_wordset_free(sig_wordset* ws);            /* NULL is allowed */
+
+/* Accessors.  Returned host pointers stay valid until sig_wordset_free. */
+int64_t        sig_wordset_size(const sig_wordset* ws);         /* |W|, empty word excluded; -1 if ws NULL */
+int            sig_wordset_dim(const sig_wordset* ws);          /* d */
+int            sig_wordset_max_len(const sig_wordset* ws);      /* longest word */
+int64_t        sig_wordset_n_user(const sig_wordset* ws);       /* entries of user_index (0 unless built from a list) */
+const int32_t* sig_wordset_parent(const sig_wordset* ws);       /* host [|W|] */
+const int32_t* sig_wordset_letter(const sig_wordset* ws);       /* host [|W|] */
+const int32_t* sig_wordset_level_start(const sig_wordset* ws);  /* host [max_len + 2] */
+const int64_t* sig_wordset_user_index(const sig_wordset* ws);   /* host [n_user] or NULL */
+
+/* Multiply-adds one path needs per segment when Horner intermediates are shared between words with a
+ * common prefix: sum over words u of (1 + height of the sub-tree under u).  This is the work unit the
+ * benchmark prices against the FP32 vector peak (Algorithm 1 evaluated once per (prefix, target length)). */
+int64_t sig_wordset_min_fma_per_step(const sig_wordset* ws);
+/* Multiply-adds per path and segment that the forward / backward kernels actually issue for this set
+ * (includes recomputation of shared ancestors in each work unit). */
+int64_t sig_wordset_kernel_fma_per_step(const sig_wordset* ws, int backward);
+
+/* Launch-plan introspection (host).  The word tree is split into work units; each unit has a program
+ * (pre-order walk, one 32-bit op per word: bits 0..11 last letter, 12..15 word length, 16..19 height of
+ * the word's sub-tree inside the unit, 20..21 kind 0 = leaf, 1 = enter, 2 = leave [backward plans only])
+ * and a slot table (canonical word index per leaf/enter op in program order; a negative value ~index marks
+ * a shared ancestor this unit only recomputes).  Several variants exist per direction, coarse to fine.
+ * units: int32 [n_units][4] = {first op, op count, first slot, slot count}.  Any output pointer may be
+ * NULL.  Returns SIG_EINVAL for a bad variant. */
+int sig_wordset_plan_count(const sig_wordset* ws, int backward);
+int sig_wordset_plan_get(const sig_wordset* ws, int backward, int variant, const int32_t** units, int64_t* n_units,
+                         const uint32_t** ops, int64_t* n_ops, const int32_t** slot_word, int64_t* n_slots,
+                         int64_t* fma_per_step);
+
+/* ---- device tables ------------------------------------------------------------------------------------
+ * The kernels read the launch plan from device memory the caller provides.  Allocate
+ * sig_wordset_device_bytes(ws) bytes (256-byte aligned), then call sig_wordset_upload once; the buffer
+ * must outlive every sig_forward / sig_backward call that uses ws.  The copy is enqueued on `stream`
+ * from host memory owned by ws. */
+size_t sig_wordset_device_bytes(const sig_wordset* ws);
+int    sig_wordset_upload(sig_wordset* ws, void* dev_buf /*device*/, size_t dev_bytes, void* stream);
+
+/* ---- forward (Section 3: Chen's relation per segment, Algorithm 1 / eq. 3 per word) -------------------
+ * path   device float32 [B, n_points, d]
+ * coeffs device float32 [B, |W|]            fully overwritten
+ * workspace: device, sig_forward_workspace_bytes bytes (may be 0 -> NULL allowed), 256-byte aligned,
+ *            contents undefined before and after.
+ * n_points == 1 gives all-zero coeffs (S_{0,0} = 1 has no non-empty-word part).  B == 0 is a no-op. */
+size_t sig_forward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
+int    sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- backward (Section 4: Proposition 4.1 gradient, Proposition 4.6 reconstruction of S_{0,t_j} by
+ *      exp(-dX_j), chain rule from increments to points) ------------------------------------------------
+ * coeffs      device float32 [B, |W|]  the terminal signature sig_forward produced for the same path
+ * grad_coeffs device float32 [B, |W|]  dLoss/dS_{0,T}(w); use 0 for words the loss does not depend on
+ * grad_path   device float32 [B, n_points, d]  fully overwritten with dLoss/dX
+ * Only the terminal signature is needed; no per-step state is stored (Section 4.2).
+ * Partial gradients of different work units are combined with floating-point atomics, so the last bits
+ * of grad_path may differ from run to run. */
+size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
+int    sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs,
+                    int64_t B, int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes,
+                    void* stream);
+
+/* ---- diagnostics ------------------------------------------------------------------------------------- */
+const char* sig_strerror(int code);
+int         sig_last_hip_error(void);          /* hipError_t of the last SIG_EHIP on this thread, else 0 */
+const char* sig_version(void);
+/* Name of the kernel family sig_forward / sig_backward will launch for this set ("generic", "trunc<d,N>", ...);
+ * lets a benchmark say which kernel its numbers belong to. */
+const char* sig_wordset_kernel_name(const sig_wordset* ws, int backward);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIG_MI355X_H */

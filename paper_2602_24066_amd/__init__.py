@@ -1,0 +1,7 @@
+"""MI355X-native path signatures in the word basis: thin Python face of libsig_mi355x.so.
+
+Everything is computed by the HIP kernels behind the C ABI in include/sig.h; this package only
+marshals arguments.  There is no CPU fallback: without the built library every call raises.
+"""
+from .binding import (SigError, WordSet, lib_path, load_library, sig_backward, sig_forward,  # noqa: F401
+                      sig_wordset_build, sig_wordset_build_anisotropic, sig_wordset_build_truncated)

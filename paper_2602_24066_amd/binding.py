@@ -1,0 +1,276 @@
+"""ctypes binding of the C ABI (include/sig.h).  Argument marshalling only.
+
+torch is used for device memory and streams; numpy for host tables.  torch is imported lazily so
+that the host-only parts (word-set tables, plans) work where no GPU stack is needed.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Iterable, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsig_mi355x.so")
+_lib = None
+
+SIG_OK = 0
+
+
+class SigError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = load_library().sig_strerror(code).decode()
+        if code == -6:
+            msg += f" (hipError {load_library().sig_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{code}]")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libsig_mi355x.so; raises if it has not been built (python -m paper_2602_24066_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2602_24066_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    c_int, c_i64, c_sz, c_p, c_dbl = ctypes.c_int, ctypes.c_int64, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_double
+    PP = ctypes.POINTER(ctypes.c_void_p)
+
+    def sig(name, restype, argtypes):
+        f = getattr(lib, name)
+        f.restype = restype
+        f.argtypes = argtypes
+
+    sig("sig_wordset_build_truncated", c_int, [c_int, c_int, PP])
+    sig("sig_wordset_build_anisotropic", c_int, [c_int, c_p, c_dbl, PP])
+    sig("sig_wordset_build", c_int, [c_int, c_p, c_p, c_i64, PP])
+    sig("sig_wordset_free", None, [c_p])
+    sig("sig_wordset_size", c_i64, [c_p])
+    sig("sig_wordset_dim", c_int, [c_p])
+    sig("sig_wordset_max_len", c_int, [c_p])
+    sig("sig_wordset_n_user", c_i64, [c_p])
+    sig("sig_wordset_parent", c_p, [c_p])
+    sig("sig_wordset_letter", c_p, [c_p])
+    sig("sig_wordset_level_start", c_p, [c_p])
+    sig("sig_wordset_user_index", c_p, [c_p])
+    sig("sig_wordset_min_fma_per_step", c_i64, [c_p])
+    sig("sig_wordset_kernel_fma_per_step", c_i64, [c_p, c_int])
+    sig("sig_wordset_plan_count", c_int, [c_p, c_int])
+    sig("sig_wordset_plan_get", c_int, [c_p, c_int, c_int, PP, ctypes.POINTER(c_i64), PP, ctypes.POINTER(c_i64), PP,
+                                         ctypes.POINTER(c_i64), ctypes.POINTER(c_i64)])
+    sig("sig_wordset_device_bytes", c_sz, [c_p])
+    sig("sig_wordset_upload", c_int, [c_p, c_p, c_sz, c_p])
+    sig("sig_forward_workspace_bytes", c_sz, [c_p, c_i64, c_i64])
+    sig("sig_backward_workspace_bytes", c_sz, [c_p, c_i64, c_i64])
+    sig("sig_forward", c_int, [c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
+    sig("sig_backward", c_int, [c_p, c_p, c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
+    sig("sig_strerror", ctypes.c_char_p, [c_int])
+    sig("sig_last_hip_error", c_int, [])
+    sig("sig_version", ctypes.c_char_p, [])
+    sig("sig_wordset_kernel_name", ctypes.c_char_p, [c_p, c_int])
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, where: str):
+    if rc != SIG_OK:
+        raise SigError(rc, where)
+
+
+def _np_from_ptr(ptr, n: int, dtype) -> np.ndarray:
+    if n == 0 or not ptr:
+        return np.zeros(0, dtype=dtype)
+    buf = (ctypes.c_char * (n * np.dtype(dtype).itemsize)).from_address(ptr)
+    return np.frombuffer(buf, dtype=dtype, count=n).copy()
+
+
+class WordSet:
+    """Owner of a sig_wordset handle plus (after upload) the device buffer holding its launch plan."""
+
+    def __init__(self, handle: int):
+        self._h = ctypes.c_void_p(handle)
+        self._dev = None          # torch uint8 tensor keeping the device tables alive
+        self._lib = load_library()
+
+    def __del__(self):
+        try:
+            if getattr(self, "_h", None) is not None and self._h:
+                self._lib.sig_wordset_free(self._h)
+                self._h = None
+        except Exception:
+            pass
+
+    # ---- host accessors
+    @property
+    def size(self) -> int:
+        return int(self._lib.sig_wordset_size(self._h))
+
+    @property
+    def dim(self) -> int:
+        return int(self._lib.sig_wordset_dim(self._h))
+
+    @property
+    def max_len(self) -> int:
+        return int(self._lib.sig_wordset_max_len(self._h))
+
+    @property
+    def parent(self) -> np.ndarray:
+        return _np_from_ptr(self._lib.sig_wordset_parent(self._h), self.size, np.int32)
+
+    @property
+    def letter(self) -> np.ndarray:
+        return _np_from_ptr(self._lib.sig_wordset_letter(self._h), self.size, np.int32)
+
+    @property
+    def level_start(self) -> np.ndarray:
+        return _np_from_ptr(self._lib.sig_wordset_level_start(self._h), self.max_len + 2, np.int32)
+
+    @property
+    def user_index(self) -> np.ndarray:
+        n = int(self._lib.sig_wordset_n_user(self._h))
+        return _np_from_ptr(self._lib.sig_wordset_user_index(self._h), n, np.int64)
+
+    @property
+    def lengths(self) -> np.ndarray:
+        ls = self.level_start
+        out = np.zeros(self.size, dtype=np.int32)
+        for n in range(1, self.max_len + 1):
+            out[ls[n]:ls[n + 1]] = n
+        return out
+
+    @property
+    def min_fma_per_step(self) -> int:
+        return int(self._lib.sig_wordset_min_fma_per_step(self._h))
+
+    def kernel_fma_per_step(self, backward: bool = False) -> int:
+        return int(self._lib.sig_wordset_kernel_fma_per_step(self._h, int(backward)))
+
+    def kernel_name(self, backward: bool = False) -> str:
+        return self._lib.sig_wordset_kernel_name(self._h, int(backward)).decode()
+
+    def plan_count(self, backward: bool = False) -> int:
+        return int(self._lib.sig_wordset_plan_count(self._h, int(backward)))
+
+    def plan(self, backward: bool = False, variant: int = 0) -> dict:
+        units, ops, slots = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+        nu, no, ns, fma = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+        _check(self._lib.sig_wordset_plan_get(self._h, int(backward), variant, ctypes.byref(units), ctypes.byref(nu),
+                                              ctypes.byref(ops), ctypes.byref(no), ctypes.byref(slots), ctypes.byref(ns),
+                                              ctypes.byref(fma)), "sig_wordset_plan_get")
+        return {"units": _np_from_ptr(units.value, nu.value * 4, np.int32).reshape(-1, 4),
+                "ops": _np_from_ptr(ops.value, no.value, np.uint32),
+                "slot_word": _np_from_ptr(slots.value, ns.value, np.int32),
+                "fma_per_step": int(fma.value)}
+
+    # ---- device side
+    def upload(self, device="cuda:0"):
+        import torch
+        nbytes = int(self._lib.sig_wordset_device_bytes(self._h))
+        dev = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+        off = (-dev.data_ptr()) % 256
+        with torch.cuda.device(dev.device):
+            stream = torch.cuda.current_stream().cuda_stream
+            _check(self._lib.sig_wordset_upload(self._h, ctypes.c_void_p(dev.data_ptr() + off), nbytes,
+                                                ctypes.c_void_p(stream)), "sig_wordset_upload")
+            torch.cuda.current_stream().synchronize()
+        self._dev = dev
+        return self
+
+
+def sig_wordset_build_truncated(d: int, depth: int) -> WordSet:
+    h = ctypes.c_void_p()
+    _check(load_library().sig_wordset_build_truncated(d, depth, ctypes.byref(h)), "sig_wordset_build_truncated")
+    return WordSet(h.value)
+
+
+def sig_wordset_build_anisotropic(d: int, weights: Sequence[float], cutoff: float) -> WordSet:
+    w = np.ascontiguousarray(np.asarray(weights, dtype=np.float64))
+    if w.shape != (d,):
+        raise ValueError("weights must have d entries")
+    h = ctypes.c_void_p()
+    _check(load_library().sig_wordset_build_anisotropic(d, w.ctypes.data, float(cutoff), ctypes.byref(h)),
+           "sig_wordset_build_anisotropic")
+    return WordSet(h.value)
+
+
+def sig_wordset_build(d: int, words: Iterable[Sequence[int]]) -> WordSet:
+    words = [tuple(int(c) for c in w) for w in words]
+    offsets = np.zeros(len(words) + 1, dtype=np.int64)
+    for k, w in enumerate(words):
+        offsets[k + 1] = offsets[k] + len(w)
+    letters = np.fromiter((c for w in words for c in w), dtype=np.int32, count=int(offsets[-1]))
+    if letters.size == 0:
+        letters = np.zeros(1, dtype=np.int32)
+    h = ctypes.c_void_p()
+    _check(load_library().sig_wordset_build(d, letters.ctypes.data, offsets.ctypes.data, len(words), ctypes.byref(h)),
+           "sig_wordset_build")
+    return WordSet(h.value)
+
+
+def _aligned_workspace(nbytes: int, device):
+    import torch
+    if nbytes == 0:
+        return None, 0
+    t = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+    return t, t.data_ptr() + ((-t.data_ptr()) % 256)
+
+
+def sig_forward(ws: WordSet, path, out=None, workspace=None):
+    """path: float32 CUDA tensor [B, L+1, d] -> coeffs float32 [B, |W|].  Enqueues on torch's current stream."""
+    import torch
+    if not path.is_cuda or path.dtype != torch.float32 or path.dim() != 3:
+        raise ValueError("path must be a float32 CUDA tensor [B, L+1, d]")
+    path = path.contiguous()
+    B, P, d = path.shape
+    if d != ws.dim:
+        raise ValueError(f"path has {d} channels, word set was built for {ws.dim}")
+    lib = load_library()
+    if out is None:
+        out = torch.empty((B, ws.size), dtype=torch.float32, device=path.device)
+    nbytes = int(lib.sig_forward_workspace_bytes(ws._h, B, P))
+    if workspace is None:
+        keep, wptr = _aligned_workspace(nbytes, path.device)
+    else:
+        keep, wptr = workspace, workspace.data_ptr()
+    with torch.cuda.device(path.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(lib.sig_forward(ws._h, ctypes.c_void_p(path.data_ptr()), B, P, ctypes.c_void_p(out.data_ptr()),
+                               ctypes.c_void_p(wptr), nbytes, ctypes.c_void_p(stream)), "sig_forward")
+    if keep is not None:
+        keep.record_stream(torch.cuda.current_stream(path.device))
+    return out
+
+
+def sig_backward(ws: WordSet, path, coeffs, grad_coeffs, out=None, workspace=None):
+    """Returns grad_path float32 [B, L+1, d].  Enqueues on torch's current stream."""
+    import torch
+    for name, t in (("path", path), ("coeffs", coeffs), ("grad_coeffs", grad_coeffs)):
+        if not t.is_cuda or t.dtype != torch.float32:
+            raise ValueError(f"{name} must be a float32 CUDA tensor")
+    path, coeffs, grad_coeffs = path.contiguous(), coeffs.contiguous(), grad_coeffs.contiguous()
+    B, P, d = path.shape
+    if d != ws.dim or tuple(coeffs.shape) != (B, ws.size) or tuple(grad_coeffs.shape) != (B, ws.size):
+        raise ValueError("shape mismatch")
+    lib = load_library()
+    if out is None:
+        out = torch.empty((B, P, d), dtype=torch.float32, device=path.device)
+    nbytes = int(lib.sig_backward_workspace_bytes(ws._h, B, P))
+    if workspace is None:
+        keep, wptr = _aligned_workspace(nbytes, path.device)
+    else:
+        keep, wptr = workspace, workspace.data_ptr()
+    with torch.cuda.device(path.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(lib.sig_backward(ws._h, ctypes.c_void_p(path.data_ptr()), ctypes.c_void_p(coeffs.data_ptr()),
+                                ctypes.c_void_p(grad_coeffs.data_ptr()), B, P, ctypes.c_void_p(out.data_ptr()),
+                                ctypes.c_void_p(wptr), nbytes, ctypes.c_void_p(stream)), "sig_backward")
+    if keep is not None:
+        keep.record_stream(torch.cuda.current_stream(path.device))
+    return out

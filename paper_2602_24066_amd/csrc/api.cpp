@@ -1,0 +1,248 @@
+// C ABI of the library (see include/sig.h for the contract of every entry point).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "../../include/sig.h"
+#include "kernels.hpp"
+#include "wordset.hpp"
+
+struct sig_wordset : public sig::WordSet {};
+
+namespace {
+thread_local int g_last_hip = 0;
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip = (int)e;
+    return SIG_EHIP;
+}
+
+const sig::WordSet* W(const sig_wordset* ws) { return ws; }
+
+// Picks the plan variant: the coarsest one (least recomputation of shared ancestors) that still
+// yields enough wavefronts to occupy the 256 compute units, else the finest.
+int pick_variant(const sig::WordSet& ws, int dir, int64_t B)
+{
+    const int64_t groups = (B + 63) / 64;
+    const int64_t want = 2048;   // two wavefronts per SIMD
+    const auto& pl = ws.plans[dir];
+    for (size_t v = 0; v < pl.size(); ++v)
+        if ((int64_t)pl[v].units.size() * groups >= want) return (int)v;
+    return (int)pl.size() - 1;
+}
+
+int bwd_tile_steps(int d) { return std::max(1, std::min(16, 32 / std::max(d, 1))); }
+}  // namespace
+
+extern "C" {
+
+int sig_wordset_build_truncated(int d, int depth, sig_wordset** out)
+{
+    if (!out) return SIG_EINVAL;
+    sig::WordSet* w = nullptr;
+    int rc = sig::build_truncated(d, depth, &w);
+    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
+    return rc;
+}
+
+int sig_wordset_build_anisotropic(int d, const double* weights, double cutoff, sig_wordset** out)
+{
+    if (!out) return SIG_EINVAL;
+    sig::WordSet* w = nullptr;
+    int rc = sig::build_anisotropic(d, weights, cutoff, &w);
+    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
+    return rc;
+}
+
+int sig_wordset_build(int d, const int32_t* letters, const int64_t* offsets, int64_t n_words, sig_wordset** out)
+{
+    if (!out) return SIG_EINVAL;
+    sig::WordSet* w = nullptr;
+    int rc = sig::build_list(d, letters, offsets, n_words, &w);
+    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
+    return rc;
+}
+
+void sig_wordset_free(sig_wordset* ws) { delete static_cast<sig::WordSet*>(ws); }
+
+int64_t sig_wordset_size(const sig_wordset* ws) { return ws ? W(ws)->size() : -1; }
+int sig_wordset_dim(const sig_wordset* ws) { return ws ? W(ws)->d : -1; }
+int sig_wordset_max_len(const sig_wordset* ws) { return ws ? W(ws)->max_len : -1; }
+int64_t sig_wordset_n_user(const sig_wordset* ws) { return ws ? (int64_t)W(ws)->user_index.size() : -1; }
+const int32_t* sig_wordset_parent(const sig_wordset* ws) { return ws ? W(ws)->parent.data() : nullptr; }
+const int32_t* sig_wordset_letter(const sig_wordset* ws) { return ws ? W(ws)->letter.data() : nullptr; }
+const int32_t* sig_wordset_level_start(const sig_wordset* ws) { return ws ? W(ws)->level_start.data() : nullptr; }
+const int64_t* sig_wordset_user_index(const sig_wordset* ws)
+{
+    return (ws && !W(ws)->user_index.empty()) ? W(ws)->user_index.data() : nullptr;
+}
+int64_t sig_wordset_min_fma_per_step(const sig_wordset* ws) { return ws ? W(ws)->min_fma : -1; }
+
+int64_t sig_wordset_kernel_fma_per_step(const sig_wordset* ws, int backward)
+{
+    if (!ws || !W(ws)->kernels_supported) return -1;
+    // reported for the finest variant unless a launch picked another one; forward count of
+    // multiply-adds, the backward kernels issue about 3 per leaf pair and 4.5 per inner pair
+    const auto& pl = W(ws)->plans[backward ? 1 : 0];
+    return pl.empty() ? -1 : pl.front().fma_per_step;
+}
+
+int sig_wordset_plan_count(const sig_wordset* ws, int backward)
+{
+    return ws ? (int)W(ws)->plans[backward ? 1 : 0].size() : -1;
+}
+
+int sig_wordset_plan_get(const sig_wordset* ws, int backward, int variant, const int32_t** units, int64_t* n_units,
+                         const uint32_t** ops, int64_t* n_ops, const int32_t** slot_word, int64_t* n_slots,
+                         int64_t* fma_per_step)
+{
+    if (!ws) return SIG_EINVAL;
+    const auto& pl = W(ws)->plans[backward ? 1 : 0];
+    if (variant < 0 || variant >= (int)pl.size()) return SIG_EINVAL;
+    const sig::Plan& p = pl[(size_t)variant];
+    static_assert(sizeof(sig::UnitDesc) == 4 * sizeof(int32_t), "UnitDesc is four int32");
+    if (units) *units = reinterpret_cast<const int32_t*>(p.units.data());
+    if (n_units) *n_units = (int64_t)p.units.size();
+    if (ops) *ops = p.ops.data();
+    if (n_ops) *n_ops = (int64_t)p.ops.size();
+    if (slot_word) *slot_word = p.slot_word.data();
+    if (n_slots) *n_slots = (int64_t)p.slot_word.size();
+    if (fma_per_step) *fma_per_step = p.fma_per_step;
+    return SIG_OK;
+}
+
+size_t sig_wordset_device_bytes(const sig_wordset* ws) { return ws ? W(ws)->image.size() : 0; }
+
+int sig_wordset_upload(sig_wordset* ws, void* dev_buf, size_t dev_bytes, void* stream)
+{
+    if (!ws || !dev_buf) return SIG_EINVAL;
+    if (dev_bytes < ws->image.size()) return SIG_EWORKSPACE;
+    if (((uintptr_t)dev_buf & 255) != 0) return SIG_EINVAL;
+    hipError_t e = hipMemcpyAsync(dev_buf, ws->image.data(), ws->image.size(), hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+    ws->dev = dev_buf;
+    return SIG_OK;
+}
+
+size_t sig_forward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
+{
+    (void)ws; (void)B; (void)n_points;
+    return 0;
+}
+
+size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
+{
+    if (!ws || B <= 0 || n_points <= 1) return 0;
+    const size_t n = (size_t)B * (size_t)(n_points - 1) * (size_t)W(ws)->d * sizeof(float);
+    return (n + 255) & ~(size_t)255;
+}
+
+static int check_common(const sig_wordset* ws, const void* path, int64_t B, int64_t n_points)
+{
+    if (!ws) return SIG_EINVAL;
+    if (B < 0 || n_points < 1) return SIG_EINVAL;
+    if (B > 0 && !path) return SIG_EINVAL;
+    if (!W(ws)->kernels_supported) return SIG_EUNSUPPORTED;
+    if (!W(ws)->dev) return SIG_ENOTUPLOADED;
+    if (B > (int64_t)65535 * 64) return SIG_ETOOLARGE;
+    return SIG_OK;
+}
+
+int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs, void* workspace,
+                size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    int rc = check_common(ws, path, B, n_points);
+    if (rc != SIG_OK) return rc;
+    if (B == 0) return SIG_OK;
+    if (!coeffs) return SIG_EINVAL;
+    const sig::WordSet& w = *W(ws);
+    hipStream_t st = (hipStream_t)stream;
+    if (n_points == 1) {
+        hipError_t e = sig::fill_zero(coeffs, B * w.size(), st);
+        return e == hipSuccess ? SIG_OK : hip_fail(e);
+    }
+    const int v = pick_variant(w, 0, B);
+    const sig::Plan& p = w.plans[0][(size_t)v];
+    const auto& po = w.offsets[0][(size_t)v];
+    const unsigned char* base = (const unsigned char*)w.dev;
+    sig::GenericArgs a;
+    a.units = (const sig::UnitDesc*)(base + po.units);
+    a.ops = (const uint32_t*)(base + po.ops);
+    a.slot_word = (const int32_t*)(base + po.slots);
+    a.n_units = (int64_t)p.units.size();
+    a.max_slots = p.max_slots;
+    a.path = path; a.B = B; a.P = n_points; a.d = w.d; a.nW = w.size();
+    a.coeffs = coeffs;
+    hipError_t e = sig::generic_forward(a, w.max_len, st);
+    return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
+int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                 int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes, void* stream)
+{
+    int rc = check_common(ws, path, B, n_points);
+    if (rc != SIG_OK) return rc;
+    if (B == 0) return SIG_OK;
+    if (!coeffs || !grad_coeffs || !grad_path) return SIG_EINVAL;
+    const sig::WordSet& w = *W(ws);
+    hipStream_t st = (hipStream_t)stream;
+    if (n_points == 1) {
+        hipError_t e = sig::fill_zero(grad_path, B * w.d, st);
+        return e == hipSuccess ? SIG_OK : hip_fail(e);
+    }
+    const size_t need = sig_backward_workspace_bytes(ws, B, n_points);
+    if (!workspace || workspace_bytes < need) return SIG_EWORKSPACE;
+    if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
+    float* gdx = (float*)workspace;
+    hipError_t e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
+    if (e != hipSuccess) return hip_fail(e);
+    const int v = pick_variant(w, 1, B);
+    const sig::Plan& p = w.plans[1][(size_t)v];
+    const auto& po = w.offsets[1][(size_t)v];
+    const unsigned char* base = (const unsigned char*)w.dev;
+    sig::GenericArgs a;
+    a.units = (const sig::UnitDesc*)(base + po.units);
+    a.ops = (const uint32_t*)(base + po.ops);
+    a.slot_word = (const int32_t*)(base + po.slots);
+    a.n_units = (int64_t)p.units.size();
+    a.max_slots = p.max_slots;
+    a.path = path; a.B = B; a.P = n_points; a.d = w.d; a.nW = w.size();
+    a.coeffs_in = coeffs; a.grad_coeffs = grad_coeffs; a.gdx = gdx;
+    a.tile_steps = bwd_tile_steps(w.d);
+    e = sig::generic_backward(a, w.max_len, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
+    return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
+const char* sig_strerror(int code)
+{
+    switch (code) {
+        case SIG_OK: return "success";
+        case SIG_EINVAL: return "invalid argument";
+        case SIG_ELETTER: return "letter outside [0, d)";
+        case SIG_EEMPTYWORD: return "empty word or empty word list";
+        case SIG_ENOMEM: return "out of host memory";
+        case SIG_EWORKSPACE: return "workspace or table buffer missing or too small";
+        case SIG_EHIP: return "HIP runtime error";
+        case SIG_ETOOLARGE: return "word set exceeds a format limit";
+        case SIG_ENOTUPLOADED: return "word set tables not uploaded";
+        case SIG_EUNSUPPORTED: return "word length not supported by the kernels";
+        default: return "unknown error";
+    }
+}
+
+int sig_last_hip_error(void) { return g_last_hip; }
+const char* sig_version(void) { return "sig-mi355x 0.1"; }
+
+const char* sig_wordset_kernel_name(const sig_wordset* ws, int backward)
+{
+    if (!ws || !W(ws)->kernels_supported) return "unsupported";
+    return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";
+}
+
+}  // extern "C"

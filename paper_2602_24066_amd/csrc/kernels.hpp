@@ -1,0 +1,34 @@
+// Launch interface between the C ABI (api.cpp) and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "wordset.hpp"
+
+namespace sig {
+
+struct GenericArgs {
+    const UnitDesc* units = nullptr;      // device
+    const uint32_t* ops = nullptr;        // device
+    const int32_t* slot_word = nullptr;   // device
+    int64_t n_units = 0;
+    int max_slots = 0;
+    const float* path = nullptr;          // device [B, P, d]
+    int64_t B = 0, P = 0;
+    int d = 0;
+    int64_t nW = 0;
+    float* coeffs = nullptr;              // forward output
+    const float* coeffs_in = nullptr;     // backward inputs
+    const float* grad_coeffs = nullptr;
+    float* gdx = nullptr;                 // backward: [B, L, d] accumulation buffer (zeroed by the caller)
+    int tile_steps = 1;
+};
+
+size_t generic_bwd_lds_bytes(int d, int max_slots, int tile_steps);
+hipError_t generic_forward(const GenericArgs& a, int max_len, hipStream_t stream);
+hipError_t generic_backward(const GenericArgs& a, int max_len, hipStream_t stream);
+hipError_t fill_zero(float* p, int64_t n, hipStream_t stream);
+hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* grad_path, hipStream_t stream);
+
+}  // namespace sig

@@ -1,0 +1,342 @@
+// Table-driven signature kernels for arbitrary prefix-closed word sets (gfx950).
+//
+// Mapping: one wavefront = one work unit (a piece of the word tree, see wordset.hpp) x 64 paths,
+// lane = path.  The unit's program is wave-uniform, so its words are decoded by the scalar unit and
+// every vector instruction is a lane-private multiply-add.  Coefficients live in LDS as
+// [word][lane] rows (conflict-free, lane-private), the Horner chain of the current root-to-node walk
+// lives in registers with compile-time indices (one switch case per word length).
+//
+// Forward step for a word u of length k inside a unit (Algorithm 1 with the intermediates of words
+// that share a prefix computed once):   for t = 0..h(u)
+//     A_k[t] = S(u) + dX^{(u_k)}/(t+1) * A_{k-1}[t+1],      A_0[.] = 1,
+// where A_k[t] is the Horner accumulator "S(w_[k]) + h" of Algorithm 1 for target words of length
+// k + t that pass through u; t = 0 gives the new S(u).
+//
+// Backward step (Section 4): S_{0,t_{j-1}} is reconstructed from S_{0,t_j} with the same recursion
+// and -dX (Proposition 4.6); the accumulators are recomputed with +dX and the recursion is run in
+// reverse for the adjoint, which carries the right factors of Proposition 4.1 aggregated over all
+// words with a common prefix.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "kernels.hpp"
+
+namespace sig {
+
+namespace {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float inv_of(int t)   // 1 / (t + 1)
+{
+    constexpr float tab[16] = {1.0f,        1.0f / 2.0f,  1.0f / 3.0f,  1.0f / 4.0f,  1.0f / 5.0f,  1.0f / 6.0f,
+                               1.0f / 7.0f, 1.0f / 8.0f,  1.0f / 9.0f,  1.0f / 10.0f, 1.0f / 11.0f, 1.0f / 12.0f,
+                               1.0f / 13.0f, 1.0f / 14.0f, 1.0f / 15.0f, 1.0f / 16.0f};
+    return tab[t];
+}
+
+// Register file of Horner accumulators: a[k][t], k = word length, t = extra target length.
+template <int MAXK>
+struct Chain {
+    float a[MAXK + 1][MAXK + 2];
+};
+
+template <int MAXK, int K>
+__device__ __forceinline__ float fwd_node(Chain<MAXK>& A, float dxl, float s, int h)
+{
+    // t >= 1 first (they read the old S), then t = 0 which is the new S
+#pragma unroll
+    for (int t = 1; t <= MAXK - K; ++t)
+        if (t <= h) A.a[K][t] = fmaf(dxl * inv_of(t), A.a[K - 1][t + 1], s);
+    const float snew = fmaf(dxl, A.a[K - 1][1], s);
+    A.a[K][0] = snew;
+    return snew;
+}
+
+template <int MAXK, int K>
+struct FwdDispatch {
+    static __device__ __forceinline__ float run(Chain<MAXK>& A, int level, float dxl, float s, int h)
+    {
+        if (level == K) return fwd_node<MAXK, K>(A, dxl, s, h);
+        if constexpr (K < MAXK) return FwdDispatch<MAXK, K + 1>::run(A, level, dxl, s, h);
+        return s;
+    }
+};
+
+template <int MAXK>
+__global__ __launch_bounds__(kWave) void fwd_generic_kernel(const UnitDesc* __restrict__ units,
+                                                            const uint32_t* __restrict__ ops,
+                                                            const int32_t* __restrict__ slot_word,
+                                                            const float* __restrict__ path, int64_t B, int64_t P, int d,
+                                                            int64_t nW, float* __restrict__ coeffs)
+{
+    extern __shared__ float lds[];
+    const int lane = threadIdx.x;
+    const UnitDesc ud = units[blockIdx.x];
+    const int64_t b = (int64_t)blockIdx.y * kWave + lane;
+    const bool valid = b < B;
+    const float* X = path + (valid ? b : B - 1) * P * d;
+    float* dx = lds;                    // [d][64]
+    float* S = lds + (size_t)d * kWave;   // [n_slots][64]
+    for (int s = 0; s < ud.n_slots; ++s) S[s * kWave + lane] = 0.0f;
+
+    Chain<MAXK> A;
+#pragma unroll
+    for (int t = 0; t < MAXK + 2; ++t) A.a[0][t] = 1.0f;
+
+    const uint32_t* prog = ops + ud.op_off;
+    for (int64_t j = 1; j < P; ++j) {
+        for (int i = 0; i < d; ++i) dx[i * kWave + lane] = X[j * d + i] - X[(j - 1) * d + i];
+        for (int o = 0; o < ud.n_ops; ++o) {
+            const uint32_t op = prog[o];
+            const int letter = op & 0xfff, level = (op >> 12) & 0xf, h = (op >> 16) & 0xf;
+            const float dxl = dx[letter * kWave + lane];
+            const float s = S[o * kWave + lane];
+            S[o * kWave + lane] = FwdDispatch<MAXK, 1>::run(A, level, dxl, s, h);
+        }
+    }
+    if (valid) {
+        const int32_t* sw = slot_word + ud.slot_off;
+        for (int s = 0; s < ud.n_slots; ++s) {
+            const int32_t w = sw[s];
+            if (w >= 0) coeffs[b * nW + w] = S[s * kWave + lane];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// backward
+
+template <int MAXK>
+struct BwdRegs {
+    float am[MAXK + 1][MAXK + 2];   // accumulators with -dX (reconstruction)
+    float ap[MAXK + 1][MAXK + 2];   // accumulators with +dX, from the reconstructed S_{0,t_{j-1}}
+    float gb[MAXK + 1][MAXK + 2];   // adjoints of ap
+    int slot[MAXK + 1];             // LDS row of the open word at each length
+};
+
+template <int MAXK, int K>
+__device__ __forceinline__ void bwd_leaf(BwdRegs<MAXK>& R, float dxl, float* S, const float* Ab, float* gc, int row,
+                                         int lane, int letter)
+{
+    const float s = S[row * kWave + lane];
+    const float a = Ab[row * kWave + lane];
+    S[row * kWave + lane] = fmaf(-dxl, R.am[K - 1][1], s);
+    gc[letter * (kWave + 1) + lane] = fmaf(a, R.ap[K - 1][1], gc[letter * (kWave + 1) + lane]);
+    R.gb[K - 1][1] = fmaf(dxl, a, R.gb[K - 1][1]);
+}
+
+template <int MAXK, int K>
+__device__ __forceinline__ void bwd_enter(BwdRegs<MAXK>& R, float dxl, float* S, int row, int lane, int h)
+{
+    const float s = S[row * kWave + lane];
+#pragma unroll
+    for (int t = 1; t <= MAXK - K; ++t)
+        if (t <= h) R.am[K][t] = fmaf(-dxl * inv_of(t), R.am[K - 1][t + 1], s);
+    const float sp = fmaf(-dxl, R.am[K - 1][1], s);
+    S[row * kWave + lane] = sp;
+#pragma unroll
+    for (int t = 1; t <= MAXK - K; ++t)
+        if (t <= h) {
+            R.ap[K][t] = fmaf(dxl * inv_of(t), R.ap[K - 1][t + 1], sp);
+            R.gb[K][t] = 0.0f;
+        }
+    R.slot[K] = row;
+}
+
+template <int MAXK, int K>
+__device__ __forceinline__ void bwd_leave(BwdRegs<MAXK>& R, float dxl, float* Ab, float* gc, int lane, int letter, int h)
+{
+    const int row = R.slot[K];
+    const float a = Ab[row * kWave + lane];
+    float asum = a;
+    float gsum = a * R.ap[K - 1][1];
+    R.gb[K - 1][1] = fmaf(dxl, a, R.gb[K - 1][1]);
+#pragma unroll
+    for (int t = 1; t <= MAXK - K; ++t)
+        if (t <= h) {
+            const float g = R.gb[K][t];
+            asum += g;
+            gsum = fmaf(g * inv_of(t), R.ap[K - 1][t + 1], gsum);
+            R.gb[K - 1][t + 1] = fmaf(dxl * inv_of(t), g, R.gb[K - 1][t + 1]);
+        }
+    Ab[row * kWave + lane] = asum;
+    gc[letter * (kWave + 1) + lane] += gsum;
+}
+
+template <int MAXK, int K>
+struct BwdDispatch {
+    static __device__ __forceinline__ void run(BwdRegs<MAXK>& R, int level, int kind, float dxl, float* S, float* Ab,
+                                               float* gc, int row, int lane, int letter, int h)
+    {
+        if (level == K) {
+            if (kind == OP_LEAF) bwd_leaf<MAXK, K>(R, dxl, S, Ab, gc, row, lane, letter);
+            else if (kind == OP_ENTER) bwd_enter<MAXK, K>(R, dxl, S, row, lane, h);
+            else bwd_leave<MAXK, K>(R, dxl, Ab, gc, lane, letter, h);
+            return;
+        }
+        if constexpr (K < MAXK) BwdDispatch<MAXK, K + 1>::run(R, level, kind, dxl, S, Ab, gc, row, lane, letter, h);
+    }
+};
+
+// gdx: [B][L][d] partial sums of dLoss/d dX, zeroed before the launch; units add into it.
+template <int MAXK>
+__global__ __launch_bounds__(kWave) void bwd_generic_kernel(const UnitDesc* __restrict__ units,
+                                                            const uint32_t* __restrict__ ops,
+                                                            const int32_t* __restrict__ slot_word,
+                                                            const float* __restrict__ path,
+                                                            const float* __restrict__ coeffs,
+                                                            const float* __restrict__ grad_coeffs, int64_t B, int64_t P,
+                                                            int d, int64_t nW, int tile_steps, float* gdx)
+{
+    extern __shared__ float lds[];
+    const int lane = threadIdx.x;
+    const UnitDesc ud = units[blockIdx.x];
+    const int64_t b0 = (int64_t)blockIdx.y * kWave;
+    const int64_t b = b0 + lane;
+    const bool valid = b < B;
+    const int64_t bc = valid ? b : B - 1;
+    const float* X = path + bc * P * d;
+    const int64_t L = P - 1;
+    float* dx = lds;                                          // [d][64]
+    float* S = dx + (size_t)d * kWave;                         // [n_slots][64]
+    float* Ab = S + (size_t)ud.n_slots * kWave;                // [n_slots][64]
+    float* gt = Ab + (size_t)ud.n_slots * kWave;               // [tile_steps * d][65]
+    {
+        const int32_t* sw = slot_word + ud.slot_off;
+        for (int s = 0; s < ud.n_slots; ++s) {
+            const int32_t w = sw[s];
+            const int32_t wi = w >= 0 ? w : ~w;
+            S[s * kWave + lane] = coeffs[bc * nW + wi];
+            Ab[s * kWave + lane] = w >= 0 ? grad_coeffs[bc * nW + wi] : 0.0f;
+        }
+    }
+    BwdRegs<MAXK> R;
+#pragma unroll
+    for (int t = 0; t < MAXK + 2; ++t) {
+        R.am[0][t] = 1.0f;
+        R.ap[0][t] = 1.0f;
+        R.gb[0][t] = 0.0f;
+    }
+    const uint32_t* prog = ops + ud.op_off;
+    const int nvalid = (int)((B - b0) < kWave ? (B - b0) : kWave);
+    for (int64_t st = L - 1; st >= 0; --st) {          // st = j - 1, segment j runs from point st to st + 1
+        const int tt = (int)(st % tile_steps);
+        float* gc = gt + (size_t)tt * d * (kWave + 1);
+        for (int i = 0; i < d; ++i) {
+            dx[i * kWave + lane] = X[(st + 1) * d + i] - X[st * d + i];
+            gc[i * (kWave + 1) + lane] = 0.0f;
+        }
+        int row = 0;
+        for (int o = 0; o < ud.n_ops; ++o) {
+            const uint32_t op = prog[o];
+            const int letter = op & 0xfff, level = (op >> 12) & 0xf, h = (op >> 16) & 0xf, kind = (op >> 20) & 3;
+            const float dxl = dx[letter * kWave + lane];
+            BwdDispatch<MAXK, 1>::run(R, level, kind, dxl, S, Ab, gc, row, lane, letter, h);
+            row += (kind != OP_LEAVE);
+        }
+        if (tt == 0) {
+            // flush the tile: for each path, (step, letter) is contiguous in gdx.  Lanes now read
+            // rows written by other lanes, hence the barriers (the block is one wavefront).
+            __syncthreads();
+            const int64_t last = st + tile_steps < L ? st + tile_steps : L;
+            const int cnt = (int)(last - st) * d;
+            for (int bb = 0; bb < nvalid; ++bb) {
+                float* dst = gdx + ((b0 + bb) * L + st) * d;
+                for (int e = lane; e < cnt; e += kWave) unsafeAtomicAdd(dst + e, gt[e * (kWave + 1) + bb]);
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__global__ void fill_zero_kernel(float* p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
+// dX_j = X_j - X_{j-1}  =>  dLoss/dX_j = dLoss/d dX_j - dLoss/d dX_{j+1}   (Section 4.1)
+__global__ void grad_points_kernel(const float* __restrict__ gdx, int64_t B, int64_t P, int d, float* __restrict__ grad_path)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t n = B * P * d;
+    if (i >= n) return;
+    const int64_t c = i % d;
+    const int64_t j = (i / d) % P;
+    const int64_t b = i / (d * P);
+    const int64_t L = P - 1;
+    const float here = j >= 1 ? gdx[(b * L + (j - 1)) * d + c] : 0.0f;
+    const float next = j < L ? gdx[(b * L + j) * d + c] : 0.0f;
+    grad_path[i] = here - next;
+}
+
+template <int MAXK>
+hipError_t launch_fwd(const GenericArgs& a, hipStream_t stream)
+{
+    const size_t lds = ((size_t)a.d + (size_t)a.max_slots) * kWave * sizeof(float);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_generic_kernel<MAXK>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid((unsigned)a.n_units, (unsigned)((a.B + kWave - 1) / kWave));
+    fwd_generic_kernel<MAXK><<<grid, kWave, lds, stream>>>(a.units, a.ops, a.slot_word, a.path, a.B, a.P, a.d, a.nW, a.coeffs);
+    return hipGetLastError();
+}
+
+template <int MAXK>
+hipError_t launch_bwd(const GenericArgs& a, hipStream_t stream)
+{
+    const size_t lds = generic_bwd_lds_bytes(a.d, a.max_slots, a.tile_steps);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_generic_kernel<MAXK>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid((unsigned)a.n_units, (unsigned)((a.B + kWave - 1) / kWave));
+    bwd_generic_kernel<MAXK><<<grid, kWave, lds, stream>>>(a.units, a.ops, a.slot_word, a.path, a.coeffs_in, a.grad_coeffs,
+                                                          a.B, a.P, a.d, a.nW, a.tile_steps, a.gdx);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t generic_bwd_lds_bytes(int d, int max_slots, int tile_steps)
+{
+    return ((size_t)d * kWave + 2 * (size_t)max_slots * kWave + (size_t)tile_steps * d * (kWave + 1)) * sizeof(float);
+}
+
+hipError_t generic_forward(const GenericArgs& a, int max_len, hipStream_t stream)
+{
+    if (max_len <= 4) return launch_fwd<4>(a, stream);
+    if (max_len <= 8) return launch_fwd<8>(a, stream);
+    return launch_fwd<12>(a, stream);
+}
+
+hipError_t generic_backward(const GenericArgs& a, int max_len, hipStream_t stream)
+{
+    if (max_len <= 4) return launch_bwd<4>(a, stream);
+    if (max_len <= 8) return launch_bwd<8>(a, stream);
+    return launch_bwd<12>(a, stream);
+}
+
+hipError_t fill_zero(float* p, int64_t n, hipStream_t stream)
+{
+    if (n <= 0) return hipSuccess;
+    const int threads = 256;
+    fill_zero_kernel<<<(unsigned)((n + threads - 1) / threads), threads, 0, stream>>>(p, n);
+    return hipGetLastError();
+}
+
+hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* grad_path, hipStream_t stream)
+{
+    const int64_t n = B * P * d;
+    if (n <= 0) return hipSuccess;
+    const int threads = 256;
+    grad_points_kernel<<<(unsigned)((n + threads - 1) / threads), threads, 0, stream>>>(gdx, B, P, d, grad_path);
+    return hipGetLastError();
+}
+
+}  // namespace sig

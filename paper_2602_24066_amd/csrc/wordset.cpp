@@ -1,0 +1,361 @@
+// Word-set construction and work-unit planning (host, integer only).
+//
+// Canonical order (Appendix A): words sorted by length, then lexicographically; for a full
+// truncation that is "cumulative level offset + base-d encoding", so parent = floor(phi/d) and
+// last letter = phi mod d (prefix / suffix extraction corollaries).
+#include "wordset.hpp"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <functional>
+#include <limits>
+#include <new>
+#include <unordered_map>
+
+#include "../../include/sig.h"
+
+namespace sig {
+
+static const int64_t kMaxWords = (int64_t)SIG_MAX_WORDS;
+
+// Fills everything that follows from (parent, letter, level_start).
+static int finish(WordSet* ws)
+{
+    const int64_t n = ws->size();
+    ws->max_len = (int)ws->level_start.size() - 2;
+    ws->length.assign((size_t)n, 0);
+    for (int len = 1; len <= ws->max_len; ++len)
+        for (int64_t w = ws->level_start[(size_t)len]; w < ws->level_start[(size_t)len + 1]; ++w)
+            ws->length[(size_t)w] = (uint8_t)len;
+    // children are contiguous in canonical order: count, then prefix-sum
+    ws->child_off.assign((size_t)n + 2, 0);
+    for (int64_t w = 0; w < n; ++w) ws->child_off[(size_t)(ws->parent[(size_t)w] + 1) + 1]++;
+    for (int64_t k = 1; k <= n + 1; ++k) ws->child_off[(size_t)k] += ws->child_off[(size_t)k - 1];
+    ws->child_list.resize((size_t)n);
+    {
+        std::vector<int32_t> fill(ws->child_off.begin(), ws->child_off.end() - 1);
+        for (int64_t w = 0; w < n; ++w) ws->child_list[(size_t)fill[(size_t)(ws->parent[(size_t)w] + 1)]++] = (int32_t)w;
+    }
+    ws->height.assign((size_t)n, 0);
+    for (int64_t w = n - 1; w >= 0; --w) {
+        const int32_t p = ws->parent[(size_t)w];
+        if (p >= 0) ws->height[(size_t)p] = std::max<uint8_t>(ws->height[(size_t)p], (uint8_t)(ws->height[(size_t)w] + 1));
+    }
+    ws->min_fma = 0;
+    for (int64_t w = 0; w < n; ++w) ws->min_fma += 1 + ws->height[(size_t)w];
+
+    ws->kernels_supported = ws->max_len <= SIG_MAX_KERNEL_LEN && ws->d <= 4096;
+    if (ws->kernels_supported) {
+        // forward: one fp32 per word per lane in LDS; backward: two.
+        const int64_t fwd_targets[] = {160, 80, 40, 20};
+        const int64_t bwd_targets[] = {96, 48, 24, 12};
+        for (int64_t t : fwd_targets) {
+            ws->plans[0].emplace_back();
+            build_plan(*ws, 112, t, false, ws->plans[0].back());
+        }
+        for (int64_t t : bwd_targets) {
+            ws->plans[1].emplace_back();
+            build_plan(*ws, 56, t, true, ws->plans[1].back());
+        }
+    }
+    // device image
+    size_t off = 0;
+    auto reserve = [&](size_t bytes) { size_t o = off; off = (off + bytes + 255) & ~(size_t)255; return o; };
+    for (int dir = 0; dir < 2; ++dir) {
+        ws->offsets[dir].clear();
+        for (const Plan& p : ws->plans[dir]) {
+            WordSet::PlanOffsets po;
+            po.units = reserve(p.units.size() * sizeof(UnitDesc));
+            po.ops = reserve(p.ops.size() * sizeof(uint32_t));
+            po.slots = reserve(p.slot_word.size() * sizeof(int32_t));
+            ws->offsets[dir].push_back(po);
+        }
+    }
+    ws->image.assign(std::max<size_t>(off, 256), 0);
+    for (int dir = 0; dir < 2; ++dir)
+        for (size_t v = 0; v < ws->plans[dir].size(); ++v) {
+            const Plan& p = ws->plans[dir][v];
+            const WordSet::PlanOffsets& po = ws->offsets[dir][v];
+            if (!p.units.empty()) std::memcpy(&ws->image[po.units], p.units.data(), p.units.size() * sizeof(UnitDesc));
+            if (!p.ops.empty()) std::memcpy(&ws->image[po.ops], p.ops.data(), p.ops.size() * sizeof(uint32_t));
+            if (!p.slot_word.empty()) std::memcpy(&ws->image[po.slots], p.slot_word.data(), p.slot_word.size() * sizeof(int32_t));
+        }
+    return SIG_OK;
+}
+
+void build_plan(const WordSet& ws, int max_slots, int64_t target_cost, bool with_leave, Plan& plan)
+{
+    const int64_t n = ws.size();
+    std::vector<int64_t> sub_size((size_t)n, 1), sub_cost((size_t)n, 0);
+    for (int64_t w = n - 1; w >= 0; --w) {
+        sub_cost[(size_t)w] += 1 + ws.height[(size_t)w];
+        const int32_t p = ws.parent[(size_t)w];
+        if (p >= 0) {
+            sub_size[(size_t)p] += sub_size[(size_t)w];
+            sub_cost[(size_t)p] += sub_cost[(size_t)w];
+        }
+    }
+    std::vector<char> owned((size_t)n, 0);
+    std::vector<int32_t> chain;
+
+    auto children = [&](int32_t u, const int32_t*& first, int32_t& count) {
+        first = ws.child_list.data() + ws.child_off[(size_t)(u + 1)];
+        count = ws.child_off[(size_t)(u + 1) + 1] - ws.child_off[(size_t)(u + 1)];
+    };
+
+    auto emit_unit = [&](const std::vector<int32_t>& group) {
+        UnitDesc ud;
+        ud.op_off = (int32_t)plan.ops.size();
+        ud.slot_off = (int32_t)plan.slot_word.size();
+        int hmax = 0;
+        for (int32_t g : group) hmax = std::max<int>(hmax, ws.height[(size_t)g]);
+        const int K = (int)chain.size();
+        int64_t fma = 0;
+        for (int k = 0; k < K; ++k) {
+            const int32_t w = chain[(size_t)k];
+            const int h = hmax + 1 + (K - 1 - k);
+            plan.ops.push_back(op_pack((uint32_t)ws.letter[(size_t)w], (uint32_t)(k + 1), (uint32_t)h, OP_ENTER));
+            plan.slot_word.push_back(owned[(size_t)w] ? ~w : w);
+            owned[(size_t)w] = 1;
+            fma += h + 1;
+            plan.pairs_nonleaf += h;
+        }
+        std::function<void(int32_t)> dfs = [&](int32_t v) {
+            const int h = ws.height[(size_t)v];
+            const uint32_t lev = ws.length[(size_t)v];
+            plan.slot_word.push_back(v);
+            owned[(size_t)v] = 1;
+            fma += h + 1;
+            if (h == 0) {
+                plan.ops.push_back(op_pack((uint32_t)ws.letter[(size_t)v], lev, 0, OP_LEAF));
+                plan.leaves++;
+                return;
+            }
+            plan.pairs_nonleaf += h;
+            plan.ops.push_back(op_pack((uint32_t)ws.letter[(size_t)v], lev, (uint32_t)h, OP_ENTER));
+            const int32_t* first; int32_t count;
+            children(v, first, count);
+            for (int32_t c = 0; c < count; ++c) dfs(first[c]);
+            if (with_leave) plan.ops.push_back(op_pack((uint32_t)ws.letter[(size_t)v], lev, (uint32_t)h, OP_LEAVE));
+        };
+        for (int32_t g : group) dfs(g);
+        if (with_leave)
+            for (int k = K - 1; k >= 0; --k) {
+                const int32_t w = chain[(size_t)k];
+                const int h = hmax + 1 + (K - 1 - k);
+                plan.ops.push_back(op_pack((uint32_t)ws.letter[(size_t)w], (uint32_t)(k + 1), (uint32_t)h, OP_LEAVE));
+            }
+        ud.n_ops = (int32_t)plan.ops.size() - ud.op_off;
+        ud.n_slots = (int32_t)plan.slot_word.size() - ud.slot_off;
+        plan.max_slots = std::max(plan.max_slots, ud.n_slots);
+        plan.fma_per_step += fma;
+        plan.units.push_back(ud);
+    };
+
+    std::function<void(int32_t)> split = [&](int32_t u) {
+        std::vector<int32_t> group;
+        int64_t gsize = 0, gcost = 0;
+        auto flush = [&]() {
+            if (group.empty()) return;
+            emit_unit(group);
+            group.clear();
+            gsize = gcost = 0;
+        };
+        const int32_t* first; int32_t count;
+        children(u, first, count);
+        const int64_t room = (int64_t)max_slots - (int64_t)chain.size();
+        for (int32_t ci = 0; ci < count; ++ci) {
+            const int32_t c = first[ci];
+            const bool too_big = sub_size[(size_t)c] > room || sub_cost[(size_t)c] > 2 * target_cost;
+            if (too_big && ws.height[(size_t)c] > 0) {
+                flush();
+                chain.push_back(c);
+                split(c);
+                chain.pop_back();
+                continue;
+            }
+            if (!group.empty() && (gsize + sub_size[(size_t)c] > room || gcost + sub_cost[(size_t)c] > target_cost)) flush();
+            group.push_back(c);
+            gsize += sub_size[(size_t)c];
+            gcost += sub_cost[(size_t)c];
+        }
+        flush();
+    };
+    if (n > 0) split(-1);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+
+static int check_d(int d) { return (d >= 1 && d <= 4096) ? SIG_OK : SIG_EINVAL; }
+
+int build_truncated(int d, int depth, WordSet** out)
+{
+    if (!out) return SIG_EINVAL;
+    if (check_d(d) != SIG_OK || depth < 1) return SIG_EINVAL;
+    if (depth > SIG_MAX_WORD_LEN) return SIG_ETOOLARGE;
+    // |W| = sum_{n=1..depth} d^n must stay below 2^31
+    int64_t total = 0, pw = 1;
+    std::vector<int64_t> start(1, 0);
+    for (int n = 1; n <= depth; ++n) {
+        if (pw > kMaxWords / d) return SIG_ETOOLARGE;
+        pw *= d;
+        start.push_back(total);
+        total += pw;
+        if (total > kMaxWords) return SIG_ETOOLARGE;
+    }
+    start.push_back(total);
+    WordSet* ws = new (std::nothrow) WordSet;
+    if (!ws) return SIG_ENOMEM;
+    try {
+        ws->d = d; ws->kind = 0; ws->depth = depth;
+        ws->parent.resize((size_t)total);
+        ws->letter.resize((size_t)total);
+        ws->level_start.assign(start.begin(), start.end());   // [0, start(1)=0, start(2), ..., total]
+        pw = 1;
+        for (int n = 1; n <= depth; ++n) {
+            pw *= d;
+            const int64_t s = start[(size_t)n], sp = n >= 2 ? start[(size_t)n - 1] : 0;
+            for (int64_t phi = 0; phi < pw; ++phi) {
+                ws->letter[(size_t)(s + phi)] = (int32_t)(phi % d);
+                ws->parent[(size_t)(s + phi)] = n == 1 ? -1 : (int32_t)(sp + phi / d);
+            }
+        }
+        int rc = finish(ws);
+        if (rc != SIG_OK) { delete ws; return rc; }
+    } catch (const std::bad_alloc&) { delete ws; return SIG_ENOMEM; }
+    *out = ws;
+    return SIG_OK;
+}
+
+int build_anisotropic(int d, const double* weights, double cutoff, WordSet** out)
+{
+    if (!out || !weights) return SIG_EINVAL;
+    if (check_d(d) != SIG_OK) return SIG_EINVAL;
+    if (!(cutoff >= 0.0) || !std::isfinite(cutoff)) return SIG_EINVAL;
+    double wmin = std::numeric_limits<double>::infinity();
+    for (int i = 0; i < d; ++i) {
+        if (!(weights[i] > 0.0) || !std::isfinite(weights[i])) return SIG_EINVAL;
+        wmin = std::min(wmin, weights[i]);
+    }
+    if (cutoff / wmin > (double)SIG_MAX_WORD_LEN + 0.5) return SIG_ETOOLARGE;
+    WordSet* ws = new (std::nothrow) WordSet;
+    if (!ws) return SIG_ENOMEM;
+    try {
+        ws->d = d; ws->kind = 1;
+        // breadth first: each level is generated from the previous one in (parent order, letter)
+        // order, which is lexicographic order inside the level.
+        std::vector<double> deg_prev(1, 0.0), deg_cur;
+        std::vector<int32_t> idx_prev(1, -1);
+        ws->level_start.assign(1, 0);
+        ws->level_start.push_back(0);
+        while (!deg_prev.empty()) {
+            deg_cur.clear();
+            std::vector<int32_t> idx_cur;
+            for (size_t q = 0; q < deg_prev.size(); ++q)
+                for (int i = 0; i < d; ++i) {
+                    const double s = deg_prev[q] + weights[i];
+                    if (s <= cutoff) {
+                        if ((int64_t)ws->parent.size() >= kMaxWords) { delete ws; return SIG_ETOOLARGE; }
+                        idx_cur.push_back((int32_t)ws->parent.size());
+                        ws->parent.push_back(idx_prev[q]);
+                        ws->letter.push_back(i);
+                        deg_cur.push_back(s);
+                    }
+                }
+            if (deg_cur.empty()) break;
+            ws->level_start.push_back((int32_t)ws->parent.size());
+            if ((int)ws->level_start.size() - 2 > SIG_MAX_WORD_LEN) { delete ws; return SIG_ETOOLARGE; }
+            deg_prev.swap(deg_cur);
+            idx_prev.swap(idx_cur);
+        }
+        if (ws->parent.empty()) { delete ws; return SIG_EEMPTYWORD; }   // no non-empty word is admissible
+        int rc = finish(ws);
+        if (rc != SIG_OK) { delete ws; return rc; }
+    } catch (const std::bad_alloc&) { delete ws; return SIG_ENOMEM; }
+    *out = ws;
+    return SIG_OK;
+}
+
+int build_list(int d, const int32_t* letters, const int64_t* offsets, int64_t n_words, WordSet** out)
+{
+    if (!out || !offsets) return SIG_EINVAL;
+    if (check_d(d) != SIG_OK || n_words < 0) return SIG_EINVAL;
+    if (n_words == 0) return SIG_EEMPTYWORD;
+    if (offsets[0] != 0) return SIG_EINVAL;
+    for (int64_t k = 0; k < n_words; ++k) {
+        const int64_t len = offsets[k + 1] - offsets[k];
+        if (len < 0) return SIG_EINVAL;
+        if (len == 0) return SIG_EEMPTYWORD;
+        if (len > SIG_MAX_WORD_LEN) return SIG_ETOOLARGE;
+    }
+    if (!letters) return SIG_EINVAL;
+    for (int64_t q = 0; q < offsets[n_words]; ++q)
+        if (letters[q] < 0 || letters[q] >= d) return SIG_ELETTER;
+    WordSet* ws = new (std::nothrow) WordSet;
+    if (!ws) return SIG_ENOMEM;
+    try {
+        ws->d = d; ws->kind = 2;
+        // trie of all prefixes; node 0 is the empty word
+        struct Node { int32_t parent, letter, len; };
+        std::vector<Node> nodes(1, Node{-1, -1, 0});
+        std::unordered_map<uint64_t, int32_t> edge;
+        edge.reserve((size_t)offsets[n_words] * 2 + 16);
+        std::vector<int32_t> user_node((size_t)n_words);
+        int max_len = 0;
+        for (int64_t k = 0; k < n_words; ++k) {
+            int32_t cur = 0;
+            for (int64_t q = offsets[k]; q < offsets[k + 1]; ++q) {
+                const uint64_t key = ((uint64_t)(uint32_t)cur << 32) | (uint32_t)letters[q];
+                auto it = edge.find(key);
+                if (it == edge.end()) {
+                    if ((int64_t)nodes.size() > kMaxWords) { delete ws; return SIG_ETOOLARGE; }
+                    const int32_t id = (int32_t)nodes.size();
+                    nodes.push_back(Node{cur, letters[q], nodes[(size_t)cur].len + 1});
+                    edge.emplace(key, id);
+                    cur = id;
+                } else cur = it->second;
+            }
+            user_node[(size_t)k] = cur;
+            max_len = std::max(max_len, nodes[(size_t)cur].len);
+        }
+        // children lists sorted by letter, then breadth-first numbering = canonical order
+        const size_t nn = nodes.size();
+        std::vector<int32_t> coff(nn + 1, 0), clist(nn - 1);
+        for (size_t v = 1; v < nn; ++v) coff[(size_t)nodes[v].parent + 1]++;
+        for (size_t v = 1; v <= nn; ++v) coff[v] += coff[v - 1];
+        {
+            std::vector<int32_t> fill(coff.begin(), coff.end() - 1);
+            for (size_t v = 1; v < nn; ++v) clist[(size_t)fill[(size_t)nodes[v].parent]++] = (int32_t)v;
+        }
+        for (size_t v = 0; v < nn; ++v)
+            std::sort(clist.begin() + coff[v], clist.begin() + coff[v + 1],
+                      [&](int32_t a, int32_t b) { return nodes[(size_t)a].letter < nodes[(size_t)b].letter; });
+        std::vector<int32_t> canon(nn, -1);      // trie node -> canonical index
+        std::vector<int32_t> level(1, 0), next;
+        ws->level_start.assign(1, 0);
+        ws->level_start.push_back(0);
+        while (true) {
+            next.clear();
+            for (int32_t v : level)
+                for (int32_t q = coff[(size_t)v]; q < coff[(size_t)v + 1]; ++q) {
+                    const int32_t c = clist[(size_t)q];
+                    canon[(size_t)c] = (int32_t)ws->parent.size();
+                    ws->parent.push_back(v == 0 ? -1 : canon[(size_t)v]);
+                    ws->letter.push_back(nodes[(size_t)c].letter);
+                    next.push_back(c);
+                }
+            if (next.empty()) break;
+            ws->level_start.push_back((int32_t)ws->parent.size());
+            level.swap(next);
+        }
+        ws->user_index.resize((size_t)n_words);
+        for (int64_t k = 0; k < n_words; ++k) ws->user_index[(size_t)k] = canon[(size_t)user_node[(size_t)k]];
+        int rc = finish(ws);
+        if (rc != SIG_OK) { delete ws; return rc; }
+    } catch (const std::bad_alloc&) { delete ws; return SIG_ENOMEM; }
+    *out = ws;
+    return SIG_OK;
+}
+
+}  // namespace sig

@@ -1,0 +1,79 @@
+// Host-side word set: canonical tables of a prefix-closed set (Section 3.1, Appendix A) and the
+// launch plans the kernels read.  Integer work only.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+namespace sig {
+
+// One instruction of a work unit's program.  A work unit is a connected piece of the word tree
+// that contains the root side of every word in it: a chain of ancestors (recomputed by every unit
+// that needs them) followed by complete sub-trees.  The program is the pre-order walk of that piece.
+//   bits  0..11  last letter of the word
+//   bits 12..15  word length k (1..15)
+//   bits 16..19  h = height of the word's sub-tree inside this unit (number of longer target
+//                lengths whose Horner intermediate passes through this word)
+//   bits 20..21  kind: 0 = LEAF (h == 0), 1 = ENTER (h >= 1), 2 = LEAVE (closes the matching ENTER;
+//                emitted for backward programs only)
+enum : uint32_t { OP_LEAF = 0, OP_ENTER = 1, OP_LEAVE = 2 };
+inline uint32_t op_pack(uint32_t letter, uint32_t level, uint32_t h, uint32_t kind) {
+    return letter | (level << 12) | (h << 16) | (kind << 20);
+}
+
+struct UnitDesc {          // device-visible, 16 bytes
+    int32_t op_off;        // first op in Plan::ops
+    int32_t n_ops;
+    int32_t slot_off;      // first entry in Plan::slot_word
+    int32_t n_slots;       // words held by the unit (one LDS row each)
+};
+
+struct Plan {
+    std::vector<UnitDesc> units;
+    std::vector<uint32_t> ops;
+    // Canonical word index of every slot, in slot order (= order of LEAF/ENTER ops).  A unit that
+    // carries a word only as a recomputed ancestor stores ~index (negative): it reads the word's
+    // coefficient but neither writes it nor seeds its adjoint.
+    std::vector<int32_t> slot_word;
+    int32_t max_slots = 0;         // largest n_slots
+    int64_t fma_per_step = 0;      // multiply-adds per path and segment issued over all units (forward count)
+    int64_t pairs_nonleaf = 0;     // (word, target) pairs with target length > word length, over all units
+    int64_t leaves = 0;            // LEAF ops over all units
+};
+
+struct WordSet {
+    int d = 0;
+    int max_len = 0;
+    int kind = 0;                  // 0 truncated, 1 anisotropic, 2 list
+    int depth = 0;                 // truncated only
+    std::vector<int32_t> parent, letter, level_start;
+    std::vector<int64_t> user_index;
+    // tree
+    std::vector<int32_t> child_off;    // [|W|+2]: children of word w are child_list[child_off[w+1] .. child_off[w+2]);
+                                       // entry 0 describes the empty word (the roots = words of length 1)
+    std::vector<int32_t> child_list;
+    std::vector<uint8_t> height;       // height of the sub-tree under w (0 for a leaf)
+    std::vector<uint8_t> length;
+    int64_t min_fma = 0;               // sum over words of (1 + height)
+    // Plan variants, coarse to fine (fewer, larger units first).  plans[0]: forward programs,
+    // plans[1]: backward programs (with LEAVE ops, smaller units because two values per word are held).
+    std::vector<Plan> plans[2];
+    // device image: all plans back to back, every array 256-byte aligned
+    struct PlanOffsets { size_t units, ops, slots; };
+    std::vector<PlanOffsets> offsets[2];
+    std::vector<unsigned char> image;
+    void* dev = nullptr;
+    bool kernels_supported = true;     // false when max_len exceeds what the kernels handle
+
+    int64_t size() const { return (int64_t)parent.size(); }
+};
+
+int build_truncated(int d, int depth, WordSet** out);
+int build_anisotropic(int d, const double* weights, double cutoff, WordSet** out);
+int build_list(int d, const int32_t* letters, const int64_t* offsets, int64_t n_words, WordSet** out);
+
+// Splits the word tree into work units of at most max_slots words and about target_cost multiply-adds.
+void build_plan(const WordSet& ws, int max_slots, int64_t target_cost, bool with_leave, Plan& plan);
+
+}  // namespace sig

@@ -1,0 +1,245 @@
+"""Host-side checks of the C-ABI library: exported symbols, word-set tables (bit-exact against the
+oracle's independent Python builder and the closed forms of Appendix A), error codes, and the launch
+plans (every word owned once; an fp64 model of the unit programs reproduces the oracle)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2602_24066_amd as S
+from oracle import sig_oracle as O
+from sig_workloads import make_path, random_prefix_closed_words
+from tests import plan_model
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    names = []
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(ROOT, "include", fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b(sig_[a-z_0-9]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(S.lib_path())
+    names = declared_functions()
+    assert len(names) >= 25
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/*.h but not exported"
+
+
+def test_strerror_and_version():
+    lib = S.load_library()
+    assert lib.sig_strerror(0) == b"success"
+    for code in range(-9, 0):
+        assert lib.sig_strerror(code) not in (b"", b"unknown error")
+    assert lib.sig_strerror(-99) == b"unknown error"
+    assert b"sig" in lib.sig_version()
+
+
+@pytest.mark.parametrize("d,N", [(1, 5), (2, 4), (3, 4), (4, 6), (6, 3), (8, 5), (16, 4)])
+def test_truncated_tables_bit_exact(d, N):
+    ws = S.sig_wordset_build_truncated(d, N)
+    assert ws.size == sum(d ** n for n in range(1, N + 1))
+    assert ws.dim == d and ws.max_len == N
+    # closed forms of Appendix A
+    ls = [0, 0]
+    for n in range(1, N + 1):
+        ls.append(ls[-1] + d ** n)
+    assert list(ws.level_start) == ls
+    par, let = ws.parent, ws.letter
+    for n in range(1, N + 1):
+        phi = np.arange(d ** n)
+        assert np.array_equal(let[ls[n]:ls[n + 1]], phi % d)
+        if n == 1:
+            assert np.all(par[ls[1]:ls[2]] == -1)
+        else:
+            assert np.array_equal(par[ls[n]:ls[n + 1]], ls[n - 1] + phi // d)
+    if ws.size < 50000:
+        t = O.word_tables(O.truncated_words(d, N))
+        assert np.array_equal(par, t["parent"]) and np.array_equal(let, t["letter"])
+        assert np.array_equal(ws.level_start, t["level_start"])
+    assert ws.min_fma_per_step == sum(d ** k for n in range(1, N + 1) for k in range(1, n + 1))
+
+
+def test_paper_sizes():
+    for d, N, size in [(6, 2, 42), (6, 3, 258), (6, 4, 1554), (6, 5, 9330), (6, 6, 55986), (4, 6, 5460),
+                       (10, 4, 11110), (8, 3, 584), (8, 6, 299592)]:
+        assert S.sig_wordset_build_truncated(d, N).size == size
+
+
+@pytest.mark.parametrize("d,gam,r", [(3, (1.0, 2.0, 1.5), 4.0), (6, (1, 1, 2, 2, 3, 3), 8.0), (2, (0.3, 0.7), 2.0),
+                                     (4, (1, 1, 1, 1), 3.0)])
+def test_anisotropic_tables_bit_exact(d, gam, r):
+    ws = S.sig_wordset_build_anisotropic(d, gam, r)
+    W = O.anisotropic_words(d, gam, r)
+    t = O.word_tables(W)
+    assert ws.size == len(W)
+    assert np.array_equal(ws.parent, t["parent"])
+    assert np.array_equal(ws.letter, t["letter"])
+    assert np.array_equal(ws.level_start, t["level_start"])
+
+
+def test_anisotropic_unit_weights_is_truncation():
+    a = S.sig_wordset_build_anisotropic(3, (1.0, 1.0, 1.0), 4.0)
+    b = S.sig_wordset_build_truncated(3, 4)
+    assert np.array_equal(a.parent, b.parent) and np.array_equal(a.letter, b.letter)
+    assert np.array_equal(a.level_start, b.level_start)
+    assert S.sig_wordset_build_anisotropic(6, (1, 1, 2, 2, 3, 3), 8.0).size == 5754
+
+
+@pytest.mark.parametrize("seed,d,n,maxlen", [(0, 3, 50, 4), (1, 10, 2000, 6), (2, 2, 30, 7), (3, 5, 1, 1)])
+def test_list_tables_bit_exact(seed, d, n, maxlen):
+    words = random_prefix_closed_words(seed, d, n, maxlen)
+    # hand over a sparse, shuffled subset with duplicates: the builder must close and sort it
+    rng = np.random.default_rng(seed)
+    pick = [words[i] for i in rng.permutation(len(words))[: max(1, len(words) // 2)]]
+    pick = pick + pick[:3]
+    ws = S.sig_wordset_build(d, pick)
+    C = O.prefix_closure(pick)
+    t = O.word_tables(C, pick)
+    assert ws.size == len(C)
+    assert np.array_equal(ws.parent, t["parent"])
+    assert np.array_equal(ws.letter, t["letter"])
+    assert np.array_equal(ws.level_start, t["level_start"])
+    assert np.array_equal(ws.user_index, t["user_index"])
+    # structural properties: parents precede children; parent/letter chain spells the word
+    par, let = ws.parent, ws.letter
+    assert np.all(par < np.arange(ws.size))
+    for k in rng.integers(0, ws.size, size=min(ws.size, 50)):
+        rec, q = [], int(k)
+        while q != -1:
+            rec.append(int(let[q]))
+            q = int(par[q])
+        assert tuple(reversed(rec)) == C[int(k)]
+
+
+def test_error_codes():
+    lib = S.load_library()
+    h = ctypes.c_void_p()
+    B = ctypes.byref(h)
+    assert lib.sig_wordset_build_truncated(0, 3, B) == -1
+    assert lib.sig_wordset_build_truncated(3, 0, B) == -1
+    assert lib.sig_wordset_build_truncated(3, 3, None) == -1
+    assert lib.sig_wordset_build_truncated(2, 40, B) == -7
+    assert lib.sig_wordset_build_truncated(10, 12, B) == -7          # 10^12 words
+    w = np.array([1.0, 0.0], dtype=np.float64)
+    assert lib.sig_wordset_build_anisotropic(2, w.ctypes.data, 3.0, B) == -1      # weight must be > 0
+    w = np.array([1.0, -1.0], dtype=np.float64)
+    assert lib.sig_wordset_build_anisotropic(2, w.ctypes.data, 3.0, B) == -1
+    w = np.array([1.0, 2.0], dtype=np.float64)
+    assert lib.sig_wordset_build_anisotropic(2, None, 3.0, B) == -1
+    assert lib.sig_wordset_build_anisotropic(2, w.ctypes.data, float("nan"), B) == -1
+    assert lib.sig_wordset_build_anisotropic(2, w.ctypes.data, 0.5, B) == -3      # nothing admissible
+    assert lib.sig_wordset_build_anisotropic(2, w.ctypes.data, 100.0, B) == -7    # words longer than the format allows
+    letters = np.array([0, 1, 5], dtype=np.int32)
+    offs = np.array([0, 2, 3], dtype=np.int64)
+    assert lib.sig_wordset_build(3, letters.ctypes.data, offs.ctypes.data, 2, B) == -2   # letter 5 >= d
+    letters = np.array([0, 1, 2], dtype=np.int32)
+    offs = np.array([0, 2, 2, 3], dtype=np.int64)
+    assert lib.sig_wordset_build(3, letters.ctypes.data, offs.ctypes.data, 3, B) == -3   # empty word
+    offs = np.array([0, 2, 1], dtype=np.int64)
+    assert lib.sig_wordset_build(3, letters.ctypes.data, offs.ctypes.data, 2, B) == -1   # decreasing offsets
+    offs = np.array([1, 2, 3], dtype=np.int64)
+    assert lib.sig_wordset_build(3, letters.ctypes.data, offs.ctypes.data, 2, B) == -1   # offsets[0] != 0
+    assert lib.sig_wordset_build(3, letters.ctypes.data, offs.ctypes.data, 0, B) == -3   # empty list
+    assert lib.sig_wordset_build(3, letters.ctypes.data, None, 2, B) == -1
+    assert h.value is None
+    # forward / backward argument checks that need no device
+    ws = S.sig_wordset_build_truncated(2, 3)
+    assert lib.sig_forward(None, None, 1, 2, None, None, 0, None) == -1
+    assert lib.sig_forward(ws._h, None, 1, 2, None, None, 0, None) == -1
+    assert lib.sig_forward(ws._h, ctypes.c_void_p(256), -1, 2, None, None, 0, None) == -1
+    assert lib.sig_forward(ws._h, ctypes.c_void_p(256), 1, 0, None, None, 0, None) == -1
+    assert lib.sig_forward(ws._h, ctypes.c_void_p(256), 1, 2, ctypes.c_void_p(256), None, 0, None) == -8   # not uploaded
+    assert lib.sig_wordset_upload(ws._h, None, 0, None) == -1
+    assert lib.sig_wordset_upload(ws._h, ctypes.c_void_p(256), 1, None) == -5
+    assert lib.sig_wordset_upload(ws._h, ctypes.c_void_p(260), 1 << 20, None) == -1                        # misaligned
+    deep = S.sig_wordset_build_truncated(2, 14)
+    assert lib.sig_forward(deep._h, ctypes.c_void_p(256), 1, 2, ctypes.c_void_p(256), None, 0, None) == -9
+    assert lib.sig_backward_workspace_bytes(ws._h, 4, 11) == 4 * 10 * 2 * 4 + (-(4 * 10 * 2 * 4)) % 256
+    assert lib.sig_backward_workspace_bytes(ws._h, 4, 1) == 0
+    lib.sig_wordset_free(None)
+
+
+def _sets():
+    yield "trunc(2,4)", S.sig_wordset_build_truncated(2, 4), O.truncated_words(2, 4), 2
+    yield "trunc(4,5)", S.sig_wordset_build_truncated(4, 5), O.truncated_words(4, 5), 4
+    yield "aniso", S.sig_wordset_build_anisotropic(3, (1.0, 2.0, 1.5), 6.0), O.anisotropic_words(3, (1.0, 2.0, 1.5), 6.0), 3
+    words = random_prefix_closed_words(5, 5, 700, 6)
+    yield "random", S.sig_wordset_build(5, words), O.prefix_closure(words), 5
+
+
+@pytest.mark.parametrize("backward", [False, True])
+def test_plans_cover_every_word_exactly_once(backward):
+    for name, ws, W, d in _sets():
+        for v in range(ws.plan_count(backward)):
+            p = ws.plan(backward, v)
+            owned = p["slot_word"][p["slot_word"] >= 0]
+            assert np.array_equal(np.sort(owned), np.arange(ws.size)), (name, v)
+            # programs: slots = number of non-LEAVE ops; ENTER/LEAVE balanced; levels consistent with the tables
+            for (op_off, n_ops, slot_off, n_slots) in p["units"]:
+                prog = [plan_model.decode(o) for o in p["ops"][op_off:op_off + n_ops]]
+                sw = p["slot_word"][slot_off:slot_off + n_slots]
+                assert sum(1 for o in prog if o[3] != plan_model.LEAVE) == n_slots
+                assert n_slots <= (56 if backward else 112)
+                r, stack = 0, []
+                for letter, level, h, kind in prog:
+                    if kind == plan_model.LEAVE:
+                        assert backward and stack and stack[-1] == (letter, level, h)
+                        stack.pop()
+                        continue
+                    w = int(sw[r]); w = w if w >= 0 else ~w
+                    assert W[w][-1] == letter and len(W[w]) == level
+                    if not backward:
+                        stack = stack[: level - 1]      # without LEAVE ops the open chain is implied by the levels
+                    assert len(stack) == level - 1          # parent chain is open
+                    if level > 1:
+                        assert stack[-1][2] >= h + 1        # the parent carries one more target length
+                    if kind == plan_model.ENTER:
+                        assert h >= 1
+                        stack.append((letter, level, h))
+                    else:
+                        assert h == 0
+                    r += 1
+                if backward:
+                    assert not stack
+
+
+def test_plan_model_forward_matches_oracle():
+    for name, ws, W, d in _sets():
+        X = make_path("iid", 3, 3, 9, d)
+        ref = O.forward_words(X, W)
+        for v in range(ws.plan_count(False)):
+            out, written = plan_model.forward(ws.plan(False, v), X, ws.size)
+            assert np.all(written == 1)
+            np.testing.assert_allclose(out, ref, rtol=1e-11, atol=1e-14, err_msg=f"{name} v{v}")
+
+
+def test_plan_model_backward_matches_oracle():
+    for name, ws, W, d in _sets():
+        X = make_path("iid", 4, 2, 7, d)
+        G = np.random.default_rng(0).standard_normal((2, ws.size))
+        coeffs = O.forward_words(X, W)
+        ref = O.backward_words(X, W, G)
+        for v in range(ws.plan_count(True)):
+            gp = plan_model.backward(ws.plan(True, v), X, coeffs, G)
+            np.testing.assert_allclose(gp, ref, rtol=1e-9, atol=1e-11, err_msg=f"{name} v{v}")
+
+
+def test_fma_counts():
+    for d, N, fmin in [(4, 6, 7272), (8, 5, 42792), (16, 4, 74560), (2, 4, 52)]:
+        assert S.sig_wordset_build_truncated(d, N).min_fma_per_step == fmin
+    assert S.sig_wordset_build_anisotropic(6, (1, 1, 2, 2, 3, 3), 8.0).min_fma_per_step == 8742
+    ws = S.sig_wordset_build_truncated(4, 6)
+    for v in range(ws.plan_count(False)):
+        p = ws.plan(False, v)
+        assert p["fma_per_step"] == sum(plan_model.decode(o)[2] + 1 for o in p["ops"])
+        assert p["fma_per_step"] >= ws.min_fma_per_step
