@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the signature hot path on one MI355X.
+
+A step = sig_forward + sig_backward over one batch of the headline workload (c2: B=256, L=256, d=4,
+depth 6, 5460 coefficients; synthetic random-walk paths with a time channel).  All buffers live in HBM
+before the timed region; nothing is allocated inside it.
+
+Prints ONE JSON line:
+  value        coefficient-steps/s for forward + backward = B * L * |W| / (time of one step)
+  roofline     the dominant kernel (backward main kernel) against the FP32 vector peak: algorithmic
+               flops per launch / average kernel duration measured with HIP events in the timed region
+  cpu_baseline the fp64 oracle timed on the host cores on a bounded sample of the same workload
+  per_workload forward / backward kernel times and roofline fractions of all six workloads
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_VECTOR_TFLOPS = 157.3     # 256 CU x 4 SIMD x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
+HEADLINE = "c2"
+
+
+def flops_forward(ws, B, L):
+    """2 flops per multiply-add, one multiply-add per (word, longer-or-equal target length) pair."""
+    return 2.0 * ws.min_fma_per_step * B * L
+
+
+def flops_backward(ws, B, L):
+    """Adjoint scheme: 3 multiply-adds per pair with target length = word length (reconstruct, adjoint push,
+    gradient bucket), 4 multiply-adds + 1 add per pair with a longer target (those plus the recomputed
+    accumulator and the adjoint sum)."""
+    fmin, nw = ws.min_fma_per_step, ws.size
+    return 2.0 * (3.0 * nw + 4.5 * (fmin - nw)) * B * L
+
+
+def setup(name, S, torch):
+    from sig_workloads import WORKLOADS, make_grad_coeffs, workload_path, workload_word_list
+    wl = WORKLOADS[name]
+    if wl.kind == "truncated":
+        ws = S.sig_wordset_build_truncated(wl.d, wl.depth)
+    elif wl.kind == "anisotropic":
+        ws = S.sig_wordset_build_anisotropic(wl.d, wl.weights, wl.cutoff)
+    else:
+        ws = S.sig_wordset_build(wl.d, workload_word_list(wl))
+    ws.upload("cuda:0")
+    X = workload_path(wl)
+    G = make_grad_coeffs(wl.seed, wl.B, ws.size)
+    lib = S.load_library()
+    st = {
+        "wl": wl, "ws": ws, "X": X, "G": G,
+        "path": torch.from_numpy(X).cuda(),
+        "grad": torch.from_numpy(G).cuda(),
+        "coeffs": torch.empty((wl.B, ws.size), dtype=torch.float32, device="cuda"),
+        "gpath": torch.empty((wl.B, wl.L + 1, wl.d), dtype=torch.float32, device="cuda"),
+    }
+    nf = int(lib.sig_forward_workspace_bytes(ws._h, wl.B, wl.L + 1))
+    nb = int(lib.sig_backward_workspace_bytes(ws._h, wl.B, wl.L + 1))
+    st["wf"] = torch.empty(max(nf, 256), dtype=torch.uint8, device="cuda")
+    st["wb"] = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
+    assert st["wf"].data_ptr() % 256 == 0 and st["wb"].data_ptr() % 256 == 0
+    return st
+
+
+def step(S, st):
+    S.sig_forward(st["ws"], st["path"], out=st["coeffs"], workspace=st["wf"])
+    S.sig_backward(st["ws"], st["path"], st["coeffs"], st["grad"], out=st["gpath"], workspace=st["wb"])
+
+
+def time_steps(S, torch, st, steps, warmup):
+    """Returns (seconds per step by the host clock, forward kernel ms, backward kernel ms) over `steps` steps."""
+    for _ in range(warmup):
+        step(S, st)
+    torch.cuda.synchronize()
+    S.sig_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(S, st)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    nf, msf = S.sig_profile_read(False)
+    nb, msb = S.sig_profile_read(True)
+    S.sig_profile_enable(False)
+    assert nf == steps and nb == steps
+    return (t1 - t0) / steps, msf / nf, msb / nb
+
+
+def roofline_entry(flops, ms):
+    ach = flops / (ms * 1e-3) / 1e12
+    return {"bound": "alu", "achieved": round(ach, 3), "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(ach / PEAK_FP32_VECTOR_TFLOPS, 4), "traffic": None}
+
+
+def cpu_baseline(st, sample_paths):
+    """The oracle as it stands (fp64, one path per thread) on the first `sample_paths` paths."""
+    import numpy as np
+    from oracle import sig_oracle as O
+    wl, ws = st["wl"], st["ws"]
+    X = np.ascontiguousarray(st["X"][:sample_paths])
+    G = st["G"][:sample_paths].astype(np.float64)
+    O.forward_dense(X[:1], wl.depth)                       # load + warm
+    t0 = time.perf_counter()
+    O.forward_dense(X, wl.depth)
+    t1 = time.perf_counter()
+    O.backward_dense(X, wl.depth, G)
+    t2 = time.perf_counter()
+    work = sample_paths * wl.L * ws.size
+    return {"value": round(work / (t2 - t0), 1), "unit": "coefficient-steps/s", "cores": O.threads(), "kind": "oracle",
+            "sample": f"first {sample_paths} of {wl.B} paths of {wl.name}, full length L={wl.L}; fp64 dense tensor-algebra "
+                      f"forward {t1 - t0:.2f} s + reverse-mode backward {t2 - t1:.2f} s",
+            "forward_value": round(work / (t1 - t0), 1)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=HEADLINE)
+    ap.add_argument("--no-others", action="store_true", help="skip the per-workload table")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--cpu-sample", type=int, default=64)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (paths are independent; sharding over the batch needs no "
+              "exchange). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    if args.steps > 4096:
+        print("bench.py: --steps is limited to 4096 (kernel timer capacity)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2602_24066_amd as S
+    S.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    st = setup(args.workload, S, torch)
+    wl, ws = st["wl"], st["ws"]
+    sec, ms_f, ms_b = time_steps(S, torch, st, args.steps, args.warmup)
+    work = wl.B * wl.L * ws.size
+    ff, fb = flops_forward(ws, wl.B, wl.L), flops_backward(ws, wl.B, wl.L)
+    rf, rb = roofline_entry(ff, ms_f), roofline_entry(fb, ms_b)
+    dominant = rb if ms_b >= ms_f else rf
+    dominant = dict(dominant)
+    dominant["kernel"] = ws.kernel_name(ms_b >= ms_f)
+
+    out = {
+        "metric": "signature coeff-steps/sec (fwd, fwd+bwd) + % of FP32 vector roofline, 1 GPU",
+        "value": round(work / sec, 1),
+        "unit": "coefficient-steps/s (forward + backward)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={wl.B} L={wl.L} d={wl.d} {wl.kind}"
+                               + (f" depth={wl.depth}" if wl.depth else "") + f" |W|={ws.size}",
+                   "min_fma_per_path_step": ws.min_fma_per_step},
+        "forward": {"kernel": ws.kernel_name(False), "kernel_ms": round(ms_f, 4),
+                    "coeff_steps_per_s": round(work / (ms_f * 1e-3), 1), "roofline_frac": rf["frac"],
+                    "achieved_tflops": rf["achieved"]},
+        "backward": {"kernel": ws.kernel_name(True), "kernel_ms": round(ms_b, 4),
+                     "coeff_steps_per_s": round(work / (ms_b * 1e-3), 1), "roofline_frac": rb["frac"],
+                     "achieved_tflops": rb["achieved"]},
+        "roofline": dominant,
+    }
+
+    if not args.no_others:
+        per = {}
+        for name in ("c1", "c2", "c3", "c4a", "c4b", "c5"):
+            torch.cuda.reset_peak_memory_stats()
+            base = torch.cuda.memory_allocated()
+            s2 = st if name == args.workload else setup(name, S, torch)
+            n = 10 if name != "c5" else 5
+            sec2, f2, b2 = time_steps(S, torch, s2, n, 2)
+            w2, wl2 = s2["ws"], s2["wl"]
+            wk = wl2.B * wl2.L * w2.size
+            per[name] = {
+                "coeffs": w2.size, "fwd_ms": round(f2, 4), "bwd_ms": round(b2, 4),
+                "fwd_coeff_steps_per_s": round(wk / (f2 * 1e-3), 1),
+                "fwd_bwd_coeff_steps_per_s": round(wk / ((f2 + b2) * 1e-3), 1),
+                "fwd_roofline_frac": roofline_entry(flops_forward(w2, wl2.B, wl2.L), f2)["frac"],
+                "bwd_roofline_frac": roofline_entry(flops_backward(w2, wl2.B, wl2.L), b2)["frac"],
+                "kernels": [w2.kernel_name(False), w2.kernel_name(True)],
+            }
+            if name == "c5":
+                per[name]["peak_device_bytes"] = int(torch.cuda.max_memory_allocated() - base)
+                per[name]["mem_out_bytes"] = 4 * wl2.B * w2.size
+            if s2 is not st:
+                del s2
+                torch.cuda.empty_cache()
+        out["per_workload"] = per
+
+    if not args.no_cpu and wl.kind == "truncated":
+        out["cpu_baseline"] = cpu_baseline(st, min(args.cpu_sample, wl.B))
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -139,6 +139,17 @@ int    sig_backward(const sig_wordset* ws, const float* path, const float* coeff
                     int64_t B, int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes,
                     void* stream);
 
+/* ---- kernel timer ----------------------------------------------------------------------------------------
+ * For benchmarks: while enabled, sig_forward / sig_backward record a HIP event pair on the caller's stream
+ * around their main kernel only (the hot loop over segments; not the small fill / chain-rule kernels).
+ * sig_profile_read synchronises with the recorded events and returns the number of launches recorded for
+ * `backward` (0 or 1) since sig_profile_enable(1) and the sum of their durations in milliseconds.  At most
+ * SIG_PROFILE_MAX_LAUNCHES launches per direction are kept; later ones are not recorded.  Not thread-safe;
+ * events are created on first use (no device memory is allocated). */
+#define SIG_PROFILE_MAX_LAUNCHES 4096
+int sig_profile_enable(int on);
+int sig_profile_read(int backward, int64_t* n_launches, double* total_ms);
+
 /* ---- diagnostics ------------------------------------------------------------------------------------- */
 const char* sig_strerror(int code);
 int         sig_last_hip_error(void);          /* hipError_t of the last SIG_EHIP on this thread, else 0 */

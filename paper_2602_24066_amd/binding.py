@@ -71,6 +71,8 @@ def load_library():
     sig("sig_backward_workspace_bytes", c_sz, [c_p, c_i64, c_i64])
     sig("sig_forward", c_int, [c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
     sig("sig_backward", c_int, [c_p, c_p, c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
+    sig("sig_profile_enable", c_int, [c_int])
+    sig("sig_profile_read", c_int, [c_int, ctypes.POINTER(c_i64), ctypes.POINTER(c_dbl)])
     sig("sig_strerror", ctypes.c_char_p, [c_int])
     sig("sig_last_hip_error", c_int, [])
     sig("sig_version", ctypes.c_char_p, [])
@@ -274,3 +276,14 @@ def sig_backward(ws: WordSet, path, coeffs, grad_coeffs, out=None, workspace=Non
     if keep is not None:
         keep.record_stream(torch.cuda.current_stream(path.device))
     return out
+
+
+def sig_profile_enable(on: bool) -> None:
+    _check(load_library().sig_profile_enable(int(on)), "sig_profile_enable")
+
+
+def sig_profile_read(backward: bool) -> Tuple[int, float]:
+    """(launches recorded, summed main-kernel time in ms) since sig_profile_enable(True)."""
+    n, ms = ctypes.c_int64(), ctypes.c_double()
+    _check(load_library().sig_profile_read(int(backward), ctypes.byref(n), ctypes.byref(ms)), "sig_profile_read")
+    return int(n.value), float(ms.value)

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "../../include/sig.h"
 #include "kernels.hpp"
@@ -33,6 +34,26 @@ int pick_variant(const sig::WordSet& ws, int dir, int64_t B)
         if ((int64_t)pl[v].units.size() * groups >= want) return (int)v;
     return (int)pl.size() - 1;
 }
+
+// kernel timer (see sig_profile_enable)
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> ev[2];    // start/stop interleaved
+    size_t used[2] = {0, 0};
+    hipEvent_t* next(int dir)
+    {
+        if (!on || used[dir] >= SIG_PROFILE_MAX_LAUNCHES) return nullptr;
+        if (ev[dir].size() < 2 * (used[dir] + 1)) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess) return nullptr;
+            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return nullptr; }
+            ev[dir].push_back(a);
+            ev[dir].push_back(b);
+        }
+        return &ev[dir][2 * used[dir]++];
+    }
+};
+Profiler g_prof;
 
 int bwd_tile_steps(int d) { return std::max(1, std::min(16, 32 / std::max(d, 1))); }
 }  // namespace
@@ -177,7 +198,10 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
     a.max_slots = p.max_slots;
     a.path = path; a.B = B; a.P = n_points; a.d = w.d; a.nW = w.size();
     a.coeffs = coeffs;
+    hipEvent_t* pe = g_prof.next(0);
+    if (pe) (void)hipEventRecord(pe[0], st);
     hipError_t e = sig::generic_forward(a, w.max_len, st);
+    if (pe) (void)hipEventRecord(pe[1], st);
     return e == hipSuccess ? SIG_OK : hip_fail(e);
 }
 
@@ -213,10 +237,37 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     a.path = path; a.B = B; a.P = n_points; a.d = w.d; a.nW = w.size();
     a.coeffs_in = coeffs; a.grad_coeffs = grad_coeffs; a.gdx = gdx;
     a.tile_steps = bwd_tile_steps(w.d);
+    hipEvent_t* pe = g_prof.next(1);
+    if (pe) (void)hipEventRecord(pe[0], st);
     e = sig::generic_backward(a, w.max_len, st);
+    if (pe) (void)hipEventRecord(pe[1], st);
     if (e != hipSuccess) return hip_fail(e);
     e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
     return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
+int sig_profile_enable(int on)
+{
+    g_prof.on = on != 0;
+    g_prof.used[0] = g_prof.used[1] = 0;
+    return SIG_OK;
+}
+
+int sig_profile_read(int backward, int64_t* n_launches, double* total_ms)
+{
+    const int dir = backward ? 1 : 0;
+    double sum = 0.0;
+    for (size_t k = 0; k < g_prof.used[dir]; ++k) {
+        hipError_t e = hipEventSynchronize(g_prof.ev[dir][2 * k + 1]);
+        if (e != hipSuccess) return hip_fail(e);
+        float ms = 0.0f;
+        e = hipEventElapsedTime(&ms, g_prof.ev[dir][2 * k], g_prof.ev[dir][2 * k + 1]);
+        if (e != hipSuccess) return hip_fail(e);
+        sum += ms;
+    }
+    if (n_launches) *n_launches = (int64_t)g_prof.used[dir];
+    if (total_ms) *total_ms = sum;
+    return SIG_OK;
 }
 
 const char* sig_strerror(int code)

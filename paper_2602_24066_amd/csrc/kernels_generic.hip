@@ -27,6 +27,7 @@ namespace sig {
 namespace {
 
 constexpr int kWave = 64;
+constexpr size_t kMaxLds = 160 * 1024;   // LDS per compute unit on gfx950
 
 __device__ __forceinline__ float inv_of(int t)   // 1 / (t + 1)
 {
@@ -276,6 +277,7 @@ template <int MAXK>
 hipError_t launch_fwd(const GenericArgs& a, hipStream_t stream)
 {
     const size_t lds = ((size_t)a.d + (size_t)a.max_slots) * kWave * sizeof(float);
+    if (lds > kMaxLds) return hipErrorInvalidValue;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_generic_kernel<MAXK>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -290,6 +292,7 @@ template <int MAXK>
 hipError_t launch_bwd(const GenericArgs& a, hipStream_t stream)
 {
     const size_t lds = generic_bwd_lds_bytes(a.d, a.max_slots, a.tile_steps);
+    if (lds > kMaxLds) return hipErrorInvalidValue;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_generic_kernel<MAXK>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

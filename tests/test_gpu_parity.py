@@ -1,0 +1,160 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+
+import paper_2602_24066_amd as S
+from oracle import sig_oracle as O
+from sig_workloads import (WORKLOADS, make_grad_coeffs, make_path, random_prefix_closed_words, workload_path)
+from tests.gpu_common import BWD_TOL, FWD_TOL, build_both, build_for_workload, check_parity, gpu_forward_backward
+
+pytestmark = pytest.mark.gpu
+
+
+# small cases: spans several work units, a ragged last group of paths (B not a multiple of 64),
+# single-segment and single-path inputs
+SMALL = [
+    ("truncated", dict(d=2, depth=4), 32, 64, "iid"),
+    ("truncated", dict(d=3, depth=5), 70, 33, "scaled"),
+    ("truncated", dict(d=4, depth=6), 5, 17, "time0"),
+    ("truncated", dict(d=8, depth=3), 129, 9, "iid"),
+    ("truncated", dict(d=16, depth=3), 3, 40, "ar1"),
+    # d = 1: a level is a single number (X_L - X_0)^n / n!; a path that returns towards its start cancels
+    # it in fp32, so the one-letter case uses the monotone time channel (level n = 1/n!)
+    ("truncated", dict(d=1, depth=6), 2, 12, "time0"),
+    ("truncated", dict(d=5, depth=1), 65, 12, "iid"),
+    ("truncated", dict(d=3, depth=4), 1, 1, "iid"),
+    ("truncated", dict(d=2, depth=10), 4, 25, "iid"),
+    ("anisotropic", dict(d=6, weights=(1, 1, 2, 2, 3, 3), cutoff=6.0), 66, 30, "iid"),
+    # the only word of length 7 here is letter 0 seven times, (X_L - X_0)^7 / 7!: as for d = 1 the channel must
+    # be monotone for that level to be well conditioned in fp32
+    ("anisotropic", dict(d=3, weights=(1.0, 2.0, 1.5), cutoff=7.0), 10, 21, "time0"),
+    ("words", dict(d=10, n_words=1500, max_len=6), 67, 20, "iid"),
+    ("words", dict(d=4, n_words=400, max_len=9), 12, 15, "iid"),
+    ("words", dict(d=40, n_words=300, max_len=3), 9, 10, "iid"),
+]
+
+
+@pytest.mark.parametrize("case", range(len(SMALL)))
+def test_small_cases_elementwise(case):
+    kind, kw, B, L, dist = SMALL[case]
+    d = kw["d"]
+    words = None
+    if kind == "words":
+        words = random_prefix_closed_words(100 + case, d, kw["n_words"], kw["max_len"])
+    ws, W = build_both(kind, d, depth=kw.get("depth"), weights=kw.get("weights"), cutoff=kw.get("cutoff"), words=words)
+    X = make_path(dist, 200 + case, B, L, d)
+    G = make_grad_coeffs(300 + case, B, ws.size)
+    check_parity(ws, W, kind, kw.get("depth"), X, G, what=f"small[{case}]")
+
+
+def test_one_point_paths_give_zero():
+    import torch
+    ws, W = build_both("truncated", 3, depth=3)
+    X = np.random.default_rng(0).standard_normal((5, 1, 3)).astype(np.float32)
+    G = make_grad_coeffs(1, 5, ws.size)
+    coeffs, gp = gpu_forward_backward(ws, X, G)
+    assert coeffs.shape == (5, ws.size) and np.all(coeffs == 0.0)
+    assert gp.shape == (5, 1, 3) and np.all(gp == 0.0)
+
+
+def test_empty_batch_is_a_noop():
+    import torch
+    ws, W = build_both("truncated", 3, depth=3)
+    xp = torch.zeros((0, 4, 3), dtype=torch.float32, device="cuda")
+    out = S.sig_forward(ws, xp)
+    assert tuple(out.shape) == (0, ws.size)
+    gp = S.sig_backward(ws, xp, out, out.clone())
+    assert tuple(gp.shape) == (0, 4, 3)
+    torch.cuda.synchronize()
+
+
+def test_repeated_points_change_nothing():
+    ws, W = build_both("truncated", 3, depth=4)
+    X = make_path("iid", 5, 4, 12, 3)
+    Xr = np.ascontiguousarray(np.insert(X, 6, X[:, 6], axis=1))
+    a, _ = gpu_forward_backward(ws, X, None)
+    b, _ = gpu_forward_backward(ws, Xr, None)
+    assert np.array_equal(a, b)        # exp(0) = 1: the extra segment adds exact zeros
+
+
+def test_forward_is_deterministic_and_outputs_fully_overwritten():
+    import torch
+    wl = WORKLOADS["c1"]
+    ws, W = build_for_workload(wl)
+    X = workload_path(wl)
+    xp = torch.from_numpy(X).cuda()
+    out1 = torch.full((wl.B, ws.size), float("nan"), device="cuda")
+    S.sig_forward(ws, xp, out=out1)
+    out2 = S.sig_forward(ws, xp)
+    torch.cuda.synchronize()
+    assert torch.equal(out1, out2)
+    g = torch.from_numpy(make_grad_coeffs(wl.seed, wl.B, ws.size)).cuda()
+    gp = torch.full((wl.B, wl.L + 1, wl.d), float("nan"), device="cuda")
+    S.sig_backward(ws, xp, out1, g, out=gp)
+    torch.cuda.synchronize()
+    assert torch.isfinite(gp).all()
+
+
+def test_gradient_against_finite_differences_of_the_oracle_forward():
+    # the benchmark spec of the gradient tolerance: fp64 central differences, 1e-3 relative
+    wl = WORKLOADS["c1"]
+    ws, W = build_for_workload(wl)
+    B = 4
+    X = workload_path(wl)[:B].astype(np.float64)
+    X = np.round(X * 128) / 128                      # +-2^-12 steps stay exact in fp32
+    G = make_grad_coeffs(wl.seed, B, ws.size)
+    _, gp = gpu_forward_backward(ws, X.astype(np.float32), G)
+    h = 2.0 ** -12
+    rng = np.random.default_rng(0)
+    fun = lambda Y: (O.forward_dense(Y.astype(np.float32), wl.depth) * G.astype(np.float64)).sum(axis=1)
+    for _ in range(6):
+        V = np.sign(rng.standard_normal(X.shape))    # +-1 directions keep the perturbed points on the grid
+        num = (fun(X + h * V) - fun(X - h * V)) / (2 * h)
+        ana = (gp.astype(np.float64) * V).reshape(B, -1).sum(axis=1)
+        scale = np.abs(gp).reshape(B, -1).sum(axis=1)
+        assert np.all(np.abs(num - ana) <= 1e-3 * scale)
+
+
+def test_projection_equals_gather_of_truncation():
+    # a word-projected coefficient is the same number as that word's coefficient in the full truncation
+    d, depth = 4, 5
+    words = random_prefix_closed_words(9, d, 200, depth)
+    wsp, Wp = build_both("words", d, words=words)
+    wst, Wt = build_both("truncated", d, depth=depth)
+    X = make_path("iid", 77, 20, 30, d)
+    a, _ = gpu_forward_backward(wsp, X, None)
+    b, _ = gpu_forward_backward(wst, X, None)
+    index = {w: k for k, w in enumerate(Wt)}
+    pick = np.array([index[w] for w in Wp])
+    ref = O.forward_dense(X, depth)[:, pick]
+    lengths = np.array([len(w) for w in Wp])
+    assert max(O.level_errors(a, ref, lengths).values()) <= FWD_TOL
+    np.testing.assert_allclose(a, b[:, pick], rtol=2e-5, atol=1e-7)
+    assert np.array_equal(wsp.user_index, np.array([{w: k for k, w in enumerate(Wp)}[w] for w in words]))
+
+
+# full-size workloads in the launch configuration the benchmark times; the oracle is run on a sample
+# of paths (paths are independent, so a sampled path is checked exactly as in a full comparison)
+FULL = {
+    "c1": None,                       # all 32 paths
+    "c2": [0, 1, 63, 64, 127, 128, 200, 255],
+    "c3": [0, 63, 64, 127],
+    "c4a": [0, 63, 64, 300, 511],
+    "c4b": [0, 63, 64, 300, 511],
+    "c5": [0, 63],
+}
+
+
+@pytest.mark.parametrize("name", list(FULL))
+def test_full_size_workloads(name):
+    wl = WORKLOADS[name]
+    ws, W = build_for_workload(wl)
+    X = workload_path(wl)
+    G = make_grad_coeffs(wl.seed, wl.B, ws.size)
+    if name == "c5":
+        O.set_threads(2)              # the oracle's backward keeps every intermediate signature: 2.3 GB per path
+    try:
+        errs, gerr = check_parity(ws, W, wl.kind, wl.depth, X, G, sample=FULL[name], what=name)
+    finally:
+        O.set_threads(16)
+    print(f"{name}: forward level errors {errs}; gradient error max {gerr.max():.3e}")
