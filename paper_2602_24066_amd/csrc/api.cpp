@@ -55,6 +55,11 @@ struct Profiler {
 };
 Profiler g_prof;
 
+bool use_trunc_forward(const sig::WordSet& w, int64_t B)
+{
+    return w.kind == 0 && B <= 65535 && sig::trunc_forward_available(w.d, w.depth);
+}
+
 int bwd_tile_steps(int d) { return std::max(1, std::min(16, 32 / std::max(d, 1))); }
 }  // namespace
 
@@ -186,6 +191,13 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
         hipError_t e = sig::fill_zero(coeffs, B * w.size(), st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
+    if (use_trunc_forward(w, B)) {
+        hipEvent_t* pe = g_prof.next(0);
+        if (pe) (void)hipEventRecord(pe[0], st);
+        hipError_t e = sig::trunc_forward(w.d, w.depth, path, B, n_points, coeffs, st);
+        if (pe) (void)hipEventRecord(pe[1], st);
+        return e == hipSuccess ? SIG_OK : hip_fail(e);
+    }
     const int v = pick_variant(w, 0, B);
     const sig::Plan& p = w.plans[0][(size_t)v];
     const auto& po = w.offsets[0][(size_t)v];
@@ -293,6 +305,7 @@ const char* sig_version(void) { return "sig-mi355x 0.1"; }
 const char* sig_wordset_kernel_name(const sig_wordset* ws, int backward)
 {
     if (!ws || !W(ws)->kernels_supported) return "unsupported";
+    if (!backward && use_trunc_forward(*W(ws), 1)) return "trunc_mfma_fwd_kernel";
     return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";
 }
 

@@ -31,4 +31,8 @@ hipError_t generic_backward(const GenericArgs& a, int max_len, hipStream_t strea
 hipError_t fill_zero(float* p, int64_t n, hipStream_t stream);
 hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* grad_path, hipStream_t stream);
 
+// Register-resident kernels for full truncations (kernels_trunc.hip)
+bool trunc_forward_available(int d, int depth);
+hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t P, float* coeffs, hipStream_t stream);
+
 }  // namespace sig
