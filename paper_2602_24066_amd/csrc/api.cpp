@@ -60,6 +60,11 @@ bool use_trunc_forward(const sig::WordSet& w, int64_t B)
     return w.kind == 0 && B <= 65535 && sig::trunc_forward_available(w.d, w.depth);
 }
 
+bool use_trunc_backward(const sig::WordSet& w, int64_t B)
+{
+    return w.kind == 0 && B <= 65535 && sig::trunc_backward_available(w.d, w.depth);
+}
+
 int bwd_tile_steps(int d) { return std::max(1, std::min(16, 32 / std::max(d, 1))); }
 }  // namespace
 
@@ -236,6 +241,15 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     float* gdx = (float*)workspace;
     hipError_t e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
     if (e != hipSuccess) return hip_fail(e);
+    if (use_trunc_backward(w, B)) {
+        hipEvent_t* pe = g_prof.next(1);
+        if (pe) (void)hipEventRecord(pe[0], st);
+        e = sig::trunc_backward(w.d, w.depth, path, coeffs, grad_coeffs, B, n_points, gdx, st);
+        if (pe) (void)hipEventRecord(pe[1], st);
+        if (e != hipSuccess) return hip_fail(e);
+        e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
+        return e == hipSuccess ? SIG_OK : hip_fail(e);
+    }
     const int v = pick_variant(w, 1, B);
     const sig::Plan& p = w.plans[1][(size_t)v];
     const auto& po = w.offsets[1][(size_t)v];
@@ -306,6 +320,7 @@ const char* sig_wordset_kernel_name(const sig_wordset* ws, int backward)
 {
     if (!ws || !W(ws)->kernels_supported) return "unsupported";
     if (!backward && use_trunc_forward(*W(ws), 1)) return "trunc_mfma_fwd_kernel";
+    if (backward && use_trunc_backward(*W(ws), 1)) return "trunc_mfma_bwd_kernel";
     return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";
 }
 

@@ -33,6 +33,9 @@ hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* gra
 
 // Register-resident kernels for full truncations (kernels_trunc.hip)
 bool trunc_forward_available(int d, int depth);
+bool trunc_backward_available(int d, int depth);
+hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                          int64_t P, float* gdx, hipStream_t stream);
 hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t P, float* coeffs, hipStream_t stream);
 
 }  // namespace sig

@@ -461,6 +461,453 @@ hipError_t launch_trunc_mfma_fwd(const float* path, int64_t B, int64_t P, float*
     return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------------------------------------
+// Backward for units whose cascade has exactly two levels below the chain (K = N - 2): the slice level holds
+// the words of length N - 1 and their children are the words of length N (leaves).
+//
+// Per segment j = L..1 (Section 4):
+//   1. S_{0,t_{j-1}} = S_{0,t_j} (x) exp(-dX_j)  (Proposition 4.6): the forward update with -dX, chain on the
+//      vector ALU, slice and leaves on the matrix cores.
+//   2. the Horner accumulators A+ are recomputed from the reconstructed signature with +dX (chain: vector ALU,
+//      slice: one matrix instruction per letter group).
+//   3. adjoint of the update, bottom up.  For a word u with parent p, target offset t and c = dX^{(u_k)}/(t+1):
+//         dLoss/d dX^{(u_k)} += gbar_u[t] * A+_p[t+1] / (t+1),   gbar_p[t+1] += c * gbar_u[t],
+//         Abar_{j-1}(u) = sum_t gbar_u[t],                        gbar_u[0] = Abar_j(u),
+//      which is Proposition 4.1 with the right factors S_{t_j,T} aggregated over all words sharing a prefix.
+//      The adjoints of the leaves are constant (= grad_coeffs) and kept twice: in the layout of the parent word
+//      vector ("node layout": lane = parent, one register per letter) for the contraction over letters, and in
+//      the matrix cores' result layout ("child layout") for the contraction over parents, where every lane
+//      accumulates the gradient of a single letter.  Parent values are brought into the child layout by a
+//      matrix instruction with B = 1 (a broadcast inside each block).
+// Gradient contributions are summed per wavefront in an LDS tile [T][D] with LDS atomics and flushed per tile
+// with global atomics (several wavefronts work on one path).
+
+__device__ __forceinline__ float dpp_quad(float v, int /*ctrl: compile-time*/ which)
+{
+    // which = 1: lanes (0,1)(2,3) swapped; which = 2: lanes (0,2)(1,3) swapped, inside each group of four
+    const int x = __builtin_bit_cast(int, v);
+    const int y = which == 1 ? __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xf, 0xf, true)
+                             : __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xf, 0xf, true);
+    return __builtin_bit_cast(float, y);
+}
+
+// M[r] in lane 4*blk + j is a contribution to the word of lane 4*blk + r; returns, in lane 4*blk + i, the sum
+// over the four lanes of the block of M[i].
+__device__ __forceinline__ float quad_transpose_reduce(const float (&M)[4], int lane)
+{
+    const bool o1 = (lane & 1) != 0, o2 = (lane & 2) != 0;
+    const float keep0 = o1 ? M[1] : M[0], send0 = o1 ? M[0] : M[1];
+    const float keep1 = o1 ? M[3] : M[2], send1 = o1 ? M[2] : M[3];
+    const float u0 = keep0 + dpp_quad(send0, 1);
+    const float u1 = keep1 + dpp_quad(send1, 1);
+    const float keep = o2 ? u1 : u0, send = o2 ? u0 : u1;
+    return keep + dpp_quad(send, 2);
+}
+
+__host__ __device__ constexpr int ilog2(int x)
+{
+    int r = 0;
+    while ((1 << (r + 1)) <= x) ++r;
+    return r;
+}
+
+__host__ __device__ constexpr int popcount6(int x)
+{
+    int r = 0;
+    for (int bit = 0; bit < 6; ++bit) r += (x >> bit) & 1;
+    return r;
+}
+// deposit the low bits of i into the lane-number bits that are NOT in keep / collect them back
+__host__ __device__ constexpr int spread_bits(int keep, int i)
+{
+    int r = 0, src = 0;
+    for (int bit = 0; bit < 6; ++bit)
+        if (!((keep >> bit) & 1)) { r |= ((i >> src) & 1) << bit; ++src; }
+    return r;
+}
+__device__ __forceinline__ int gather_bits(int keep, int lane)
+{
+    int r = 0, dst = 0;
+#pragma unroll
+    for (int bit = 0; bit < 6; ++bit)
+        if (!((keep >> bit) & 1)) { r |= ((lane >> bit) & 1) << dst; ++dst; }
+    return r;
+}
+
+// V[T][64]: one value per (segment, lane).  Lanes that agree on the lane-number bits in KEEP contribute to the same
+// letter (my_letter, valid in every lane of the class).  Each class sums its values per segment and adds the
+// result to gt[segment][letter]; the lanes of a class split the segments between them.
+template <int KEEP, int T>
+__device__ __forceinline__ void tile_reduce(const float* V, float* gt, int D, int lane, int my_letter)
+{
+    constexpr int NL = 1 << (6 - popcount6(KEEP));     // lanes per class
+    const int m = gather_bits(KEEP, lane);
+#pragma unroll
+    for (int t0 = 0; t0 < T; t0 += NL) {
+        const int tt = t0 + m;
+        if (tt < T) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NL; ++i) acc += V[tt * kWave + ((lane & KEEP) | spread_bits(KEEP, i))];
+            __hip_atomic_fetch_add(gt + tt * D + my_letter, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    }
+}
+
+// chain letter k (0-based) of K: bit field of the lane number, or empty when the letter is the same in the whole wavefront
+__host__ __device__ constexpr int chain_keep_mask(int LB, int K, int k)
+{
+    const int lo = LB * (K - 1 - k);
+    return lo >= 6 ? 0 : ((((1 << LB) - 1) << lo) & 63);
+}
+
+template <int D, int K, int T, int KI>
+__device__ __forceinline__ void chain_tile_reduce(const float* Vsrc, float* gt, int lane, const int (&letter)[K])
+{
+    if constexpr (KI < K - 1) {
+        tile_reduce<chain_keep_mask(ilog2(D), K, KI), T>(Vsrc + KI * T * kWave, gt, D, lane, letter[KI]);
+        chain_tile_reduce<D, K, T, KI + 1>(Vsrc, gt, lane, letter);
+    }
+}
+
+__device__ __forceinline__ void lds_add(float* p, float v)
+{
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+template <int D, int N, int WQ, int T>
+__global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
+    const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
+    int64_t P, float* gdx)
+{
+    static_assert((D & (D - 1)) == 0, "the gradient reduction takes letters as bit fields of the lane number");
+    constexpr int K = N - 2;
+    using G = MGeo<D, N, K, WQ>;
+    constexpr int Q = G::Q;
+    constexpr bool WIDE = G::WIDE;
+    constexpr int NBS = G::NBS;                       // slice combinations: index t * WQ + g, t in {0, 1}
+    constexpr int NBU = G::NBU;                       // leaf combinations: WIDE 1, else Q
+    constexpr int NC = (N + 3) / 4 * 4;
+    constexpr int NSV = WQ * 4;                       // slice word vectors
+    constexpr int NL4 = WIDE ? 1 : NSV * Q;           // leaf 4-vectors
+    constexpr int NL16 = WIDE ? NSV : 1;              // leaf 16-vectors
+    constexpr int EPL = (T * D + kWave - 1) / kWave;
+    constexpr int NSRC0 = 1 + (WIDE ? WQ : Q);        // sources before the earlier chain letters
+    constexpr int NSRC = NSRC0 + (K - 1);
+    constexpr int LB = ilog2(D);
+    __shared__ float E_all[kWavesPerBlock][T][2][D];
+    __shared__ __attribute__((aligned(16))) float Ec_all[kWavesPerBlock][T][D][NC];
+    __shared__ float gt_all[kWavesPerBlock][T * D];
+    __shared__ float Vb_all[kWavesPerBlock][NSRC * T * kWave];
+
+    const int lane = threadIdx.x % kWave;
+    const int wib = threadIdx.x / kWave;
+    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
+    if (wave >= B * G::WAVES) return;
+    float (*E)[2][D] = E_all[wib];
+    float (*Ec)[D][NC] = Ec_all[wib];
+    float* gt = gt_all[wib];
+    float* Vb = Vb_all[wib];
+    const int64_t b = wave / G::WAVES;
+    const int wip = (int)(wave % G::WAVES);
+    const int slice = wip % G::NSL;
+    const int p = (wip / G::NSL) * kWave + lane;
+    int letter[K];
+    {
+        int q = p;
+#pragma unroll
+        for (int k = K - 1; k >= 0; --k) { letter[k] = q % D; q /= D; }
+    }
+    const int g0 = slice * WQ;
+    const float* X = path + b * P * D;
+    const int64_t L = P - 1;
+    const int64_t nW = level_start(D, N) + ipow(D, N);
+    const float* cf = coeffs + b * nW;
+    const float* gr = grad + b * nW;
+
+    int offS[NBS], offU[NBU];
+#pragma unroll
+    for (int r = 0; r < NBS; ++r) {
+        const int c = 4 * r + lane / 16;
+        offS[r] = c < 2 * WQ ? (c / WQ) * D + 4 * (g0 + c % WQ) + (lane & 3) : 0;
+    }
+#pragma unroll
+    for (int r = 0; r < NBU; ++r) {
+        const int c = 4 * r + lane / 16;
+        if constexpr (WIDE) offU[r] = c < 1 ? (lane & 15) : 0;
+        else offU[r] = c < Q ? 4 * c + (lane & 3) : 0;
+    }
+
+    // ---- state: terminal signature and adjoints
+    float Sc[K], Ac[K];
+    v4f S1[WQ], A1[WQ];
+    v4f S2[NL4], Ac4[NL4];            // leaves, child layout (4x4x1)
+    v16f S2w[NL16], Ac16[NL16];       // leaves, child layout (16x16x1)
+    float An[NSV][D];                 // leaf adjoints, node layout
+    int phi = 0;
+#pragma unroll
+    for (int k = 1; k <= K; ++k) {
+        phi = phi * D + letter[k - 1];
+        const bool owner = (p % ipow(D, K - k) == 0) && slice == 0;
+        Sc[k - 1] = cf[level_start(D, k) + phi];
+        Ac[k - 1] = owner ? gr[level_start(D, k) + phi] : 0.0f;
+    }
+#pragma unroll
+    for (int g = 0; g < WQ; ++g)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int ph = __shfl(phi, (lane & ~3) + r) * D + 4 * (g0 + g) + (lane & 3);   // word of slice vector (g, r) in this lane
+            S1[g][r] = cf[level_start(D, N - 1) + ph];
+            A1[g][r] = gr[level_start(D, N - 1) + ph];
+            const int v = g * 4 + r;
+#pragma unroll
+            for (int j = 0; j < D; ++j) An[v][j] = gr[level_start(D, N) + ph * D + j];
+            if constexpr (WIDE) {
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr) {
+                    const int src = 16 * (rr / 4) + 4 * (lane / 16) + (rr % 4);
+                    const int pl = __shfl(ph, src) * D + (lane & 15);
+                    S2w[v][rr] = cf[level_start(D, N) + pl];
+                    Ac16[v][rr] = gr[level_start(D, N) + pl];
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        const int pl = __shfl(ph, (lane & ~3) + rr) * D + 4 * q + (lane & 3);
+                        S2[v * Q + q][rr] = cf[level_start(D, N) + pl];
+                        Ac4[v * Q + q][rr] = gr[level_start(D, N) + pl];
+                    }
+            }
+        }
+
+    float dxn[EPL];
+    auto fetch = [&](int64_t j0) {
+#pragma unroll
+        for (int q = 0; q < EPL; ++q) {
+            const int e = (lane + q * kWave) < T * D ? lane + q * kWave : T * D - 1;
+            int64_t jj = j0 + e / D;
+            const bool ok = jj >= 0 && jj < L;
+            jj = jj < 0 ? 0 : (jj < L ? jj : L - 1);
+            const int i = e % D;
+            const float x1 = X[(jj + 1) * D + i], x0 = X[jj * D + i];
+            dxn[q] = ok ? x1 - x0 : 0.0f;
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int q = 0; q < EPL; ++q) {
+            const int e = lane + q * kWave;
+            if (e < T * D) {
+#pragma unroll
+                for (int t = 0; t < N; ++t) {
+                    const float v = dxn[q] * inv1(t);
+                    if (t < 2) E[e / D][t][e % D] = v;
+                    Ec[e / D][e % D][t] = v;
+                }
+            }
+        }
+    };
+    const v4f zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    v16f zero16;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) zero16[q] = 0.0f;
+    const float one = 1.0f;
+
+    auto step = [&](int row) {
+        const float* Et = &E[row][0][0];
+        float ec[K][NC];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const float* src = &Ec[row][letter[k]][0];
+#pragma unroll
+            for (int t = 0; t <= N - (k + 1); ++t) ec[k][t] = src[t];
+        }
+        float bs[NBS], nbs[NBS], bu[NBU], nbu[NBU], b0v[WQ], dxu[D];
+#pragma unroll
+        for (int r = 0; r < NBS; ++r) { bs[r] = Et[offS[r]]; nbs[r] = -bs[r]; }
+#pragma unroll
+        for (int r = 0; r < NBU; ++r) { bu[r] = Et[offU[r]]; nbu[r] = -bu[r]; }
+#pragma unroll
+        for (int g = 0; g < WQ; ++g) b0v[g] = Et[4 * (g0 + g) + (lane & 3)];
+#pragma unroll
+        for (int j = 0; j < D; ++j) dxu[j] = Et[j];
+
+        // 1. reconstruction with -dX
+        float am[K + 1][N + 2];
+#pragma unroll
+        for (int t = 0; t < N + 2; ++t) am[0][t] = 1.0f;
+#pragma unroll
+        for (int k = 1; k <= K; ++k) {
+#pragma unroll
+            for (int t = 1; t <= N - k; ++t) am[k][t] = fmaf(-ec[k - 1][t], am[k - 1][t + 1], Sc[k - 1]);
+            Sc[k - 1] = fmaf(-ec[k - 1][0], am[k - 1][1], Sc[k - 1]);
+        }
+        v4f Gm[WQ];
+#pragma unroll
+        for (int g = 0; g < WQ; ++g) {
+            Gm[g] = mfma4(am[K][2], nbs[(WQ + g) / 4], S1[g], (WQ + g) % 4);
+            S1[g] = mfma4(am[K][1], nbs[g / 4], S1[g], g % 4);
+        }
+#pragma unroll
+        for (int v = 0; v < NSV; ++v) {
+            if constexpr (WIDE) {
+                S2w[v] = mfma16(Gm[v / 4][v % 4], nbu[0], S2w[v], 0);
+            } else {
+#pragma unroll
+                for (int q = 0; q < Q; ++q) S2[v * Q + q] = mfma4(Gm[v / 4][v % 4], nbu[q / 4], S2[v * Q + q], q % 4);
+            }
+        }
+        // 2. accumulators with +dX from the reconstructed signature
+        float ap[K + 1][N + 2];
+#pragma unroll
+        for (int t = 0; t < N + 2; ++t) ap[0][t] = 1.0f;
+#pragma unroll
+        for (int k = 1; k <= K; ++k)
+#pragma unroll
+            for (int t = 1; t <= N - k; ++t) ap[k][t] = fmaf(ec[k - 1][t], ap[k - 1][t + 1], Sc[k - 1]);
+        v4f Gp[WQ];
+#pragma unroll
+        for (int g = 0; g < WQ; ++g) Gp[g] = mfma4(ap[K][2], bs[(WQ + g) / 4], S1[g], (WQ + g) % 4);
+        // chain values A+_K[1], A+_K[2]/2 of the parent of every slice word, in the child layout
+        const v4f Pb1 = __builtin_amdgcn_mfma_f32_4x4x1f32(ap[K][1], one, zero4, 0, 0, 0);
+        const v4f Pb2 = __builtin_amdgcn_mfma_f32_4x4x1f32(0.5f * ap[K][2], one, zero4, 0, 0, 0);
+
+        // 3a. leaves
+        float gcl[WIDE ? 1 : Q];
+#pragma unroll
+        for (int q = 0; q < (WIDE ? 1 : Q); ++q) gcl[q] = 0.0f;
+        v4f g1[WQ];
+#pragma unroll
+        for (int v = 0; v < NSV; ++v) {
+            const float a = Gp[v / 4][v % 4];            // A+_{N-1}[1] of the slice word in this lane
+            float h = 0.0f;
+#pragma unroll
+            for (int j = 0; j < D; ++j) h = fmaf(dxu[j], An[v][j], h);
+            g1[v / 4][v % 4] = h;                        // gbar[1] of the slice word
+            if constexpr (WIDE) {
+                const v16f Pb = __builtin_amdgcn_mfma_f32_16x16x1f32(a, one, zero16, 0, 0, 0);
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr) gcl[0] = fmaf(Ac16[v][rr], Pb[rr], gcl[0]);
+            } else {
+                const v4f Pb = __builtin_amdgcn_mfma_f32_4x4x1f32(a, one, zero4, 0, 0, 0);
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) gcl[q] = fmaf(Ac4[v * Q + q][rr], Pb[rr], gcl[q]);
+            }
+        }
+        // 3b. slice words
+        float gcs[WQ], M1[4], M2[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) M1[r] = M2[r] = 0.0f;
+#pragma unroll
+        for (int g = 0; g < WQ; ++g) {
+            gcs[g] = 0.0f;
+            const float b1v = 0.5f * b0v[g];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float q0 = A1[g][r], q1 = g1[g][r];
+                gcs[g] = fmaf(q0, Pb1[r], gcs[g]);
+                gcs[g] = fmaf(q1, Pb2[r], gcs[g]);
+                M1[r] = fmaf(b0v[g], q0, M1[r]);
+                M2[r] = fmaf(b1v, q1, M2[r]);
+                A1[g][r] = q0 + q1;
+            }
+        }
+        // 3c. chain
+        float gb[K + 1][N + 2];
+#pragma unroll
+        for (int k = 0; k <= K; ++k)
+#pragma unroll
+            for (int t = 0; t < N + 2; ++t) gb[k][t] = 0.0f;
+        gb[K][1] = quad_transpose_reduce(M1, lane);
+        gb[K][2] = quad_transpose_reduce(M2, lane);
+        float gck[K];
+#pragma unroll
+        for (int k = K; k >= 1; --k) {
+            gb[k][0] = Ac[k - 1];
+            float gc = 0.0f, asum = 0.0f;
+#pragma unroll
+            for (int t = 0; t <= N - k; ++t) {
+                const float q = gb[k][t];
+                asum += q;
+                gc = fmaf(q * inv1(t), ap[k - 1][t + 1], gc);
+                gb[k - 1][t + 1] = fmaf(ec[k - 1][t], q, gb[k - 1][t + 1]);
+            }
+            Ac[k - 1] = asum;
+            gck[k - 1] = gc;
+        }
+        // 4. gradient contributions of this segment: every lane parks its values in private LDS slots
+        //    Vb[source][segment][lane]; they are summed over lanes once per tile (tile_reduce), which keeps
+        //    dependent cross-lane chains out of the segment loop.
+        float* vb = Vb + row * kWave + lane;
+        {
+            float x = gck[K - 1];
+            if constexpr (WIDE) x += gcl[0];
+            vb[0] = x;                                            // source 0: letters = lane bits [0, LB)
+        }
+        if constexpr (!WIDE) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {                         // sources 1..Q: letters 4 q + lane % 4
+                float y = gcl[q];
+#pragma unroll
+                for (int g = 0; g < WQ; ++g) y += (g0 + g == q) ? gcs[g] : 0.0f;
+                vb[(1 + q) * T * kWave] = y;
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < WQ; ++g) vb[(1 + g) * T * kWave] = gcs[g];   // sources 1..WQ: letters 4 (g0 + g) + lane % 4
+        }
+#pragma unroll
+        for (int k = 0; k < K - 1; ++k) vb[(NSRC0 + k) * T * kWave] = gck[k];   // earlier chain letters
+    };
+
+    const int64_t ntiles = (L + T - 1) / T;
+    for (int e = lane; e < T * D; e += kWave) gt[e] = 0.0f;
+    fetch((ntiles - 1) * T);
+    for (int64_t n = ntiles - 1; n >= 0; --n) {
+        wave_lds_fence();
+        stage();
+        wave_lds_fence();
+        fetch((n - 1) * T);                            // n = 0: out of range, zeros
+#pragma unroll 1
+        for (int tt = T - 1; tt >= 0; --tt) step(tt);
+        wave_lds_fence();
+        tile_reduce<(1 << LB) - 1, T>(Vb, gt, D, lane, letter[K - 1]);
+        if constexpr (!WIDE) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) tile_reduce<3, T>(Vb + (1 + q) * T * kWave, gt, D, lane, 4 * q + (lane & 3));
+        } else {
+#pragma unroll
+            for (int g = 0; g < WQ; ++g) tile_reduce<3, T>(Vb + (1 + g) * T * kWave, gt, D, lane, 4 * (g0 + g) + (lane & 3));
+        }
+        chain_tile_reduce<D, K, T, 0>(Vb + NSRC0 * T * kWave, gt, lane, letter);
+        wave_lds_fence();
+        // flush: (segment, letter) is contiguous in gdx
+        for (int e = lane; e < T * D; e += kWave) {
+            const int64_t s = n * T + e / D;
+            if (s < L) unsafeAtomicAdd(gdx + (b * L + n * T) * D + e, gt[e]);
+            gt[e] = 0.0f;
+        }
+    }
+}
+
+template <int D, int N, int WQ>
+hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
+                                 float* gdx, hipStream_t stream)
+{
+    using G = MGeo<D, N, N - 2, WQ>;
+    constexpr int T = 8;
+    const int64_t waves = B * G::WAVES;
+    const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    trunc_mfma_bwd_kernel<D, N, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, 0, stream>>>(path, coeffs, grad, B, P, gdx);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 // (D, N) pairs with a register-resident kernel, and the unit shape used for each.
@@ -475,6 +922,21 @@ hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t
     if (d == 4 && depth == 6) return launch_trunc_mfma_fwd<4, 6, 4, 1>(path, B, P, coeffs, stream);
     if (d == 8 && depth == 5) return launch_trunc_mfma_fwd<8, 5, 3, 2>(path, B, P, coeffs, stream);
     if (d == 16 && depth == 4) return launch_trunc_mfma_fwd<16, 4, 2, 1>(path, B, P, coeffs, stream);
+    return hipErrorInvalidValue;
+}
+
+bool trunc_backward_available(int d, int depth)
+{
+    return (d == 4 && depth == 6) || (d == 8 && depth == 5) || (d == 16 && depth == 4);
+}
+
+// gdx: [B, L, d] accumulation buffer, zeroed by the caller
+hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                          int64_t P, float* gdx, hipStream_t stream)
+{
+    if (d == 4 && depth == 6) return launch_trunc_mfma_bwd<4, 6, 1>(path, coeffs, grad_coeffs, B, P, gdx, stream);
+    if (d == 8 && depth == 5) return launch_trunc_mfma_bwd<8, 5, 2>(path, coeffs, grad_coeffs, B, P, gdx, stream);
+    if (d == 16 && depth == 4) return launch_trunc_mfma_bwd<16, 4, 1>(path, coeffs, grad_coeffs, B, P, gdx, stream);
     return hipErrorInvalidValue;
 }
 
