@@ -108,6 +108,18 @@ int sig_wordset_plan_get(const sig_wordset* ws, int backward, int variant, const
                          const uint32_t** ops, int64_t* n_ops, const int32_t** slot_word, int64_t* n_slots,
                          int64_t* fma_per_step);
 
+/* Run-time specialisation.  For word sets without a precompiled register-resident kernel, sig_forward and
+ * sig_backward print the work units as straight-line HIP source (one multiply-add per (word, target length)
+ * pair) and compile it with hiprtc for gfx950 on first use; the compiled kernel is cached in ws.  The first call
+ * for a word set therefore takes seconds.  sig_wordset_jit_prepare does that compilation ahead of time for the
+ * plan variant a batch of B paths would use (host only, no device needed); it returns SIG_OK, SIG_EUNSUPPORTED if
+ * this word set is not run through specialised kernels, or SIG_EJIT if hiprtc failed (sig_forward / sig_backward
+ * then fall back to the table-driven kernels).  Setting the environment variable SIG_NO_JIT=1 disables it. */
+#define SIG_EJIT (-10)
+int sig_wordset_jit_prepare(sig_wordset* ws, int backward, int64_t B);
+/* Copies the generated source (NUL-terminated, truncated to n bytes) and returns its full length, 0 if none. */
+size_t sig_wordset_jit_source(sig_wordset* ws, int backward, int64_t B, char* buf, size_t n);
+
 /* ---- device tables ------------------------------------------------------------------------------------
  * The kernels read the launch plan from device memory the caller provides.  Allocate
  * sig_wordset_device_bytes(ws) bytes (256-byte aligned), then call sig_wordset_upload once; the buffer

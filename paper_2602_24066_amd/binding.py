@@ -65,6 +65,8 @@ def load_library():
     sig("sig_wordset_plan_count", c_int, [c_p, c_int])
     sig("sig_wordset_plan_get", c_int, [c_p, c_int, c_int, PP, ctypes.POINTER(c_i64), PP, ctypes.POINTER(c_i64), PP,
                                          ctypes.POINTER(c_i64), ctypes.POINTER(c_i64)])
+    sig("sig_wordset_jit_prepare", c_int, [c_p, c_int, c_i64])
+    sig("sig_wordset_jit_source", c_sz, [c_p, c_int, c_i64, c_p, c_sz])
     sig("sig_wordset_device_bytes", c_sz, [c_p])
     sig("sig_wordset_upload", c_int, [c_p, c_p, c_sz, c_p])
     sig("sig_forward_workspace_bytes", c_sz, [c_p, c_i64, c_i64])
@@ -170,6 +172,16 @@ class WordSet:
                 "ops": _np_from_ptr(ops.value, no.value, np.uint32),
                 "slot_word": _np_from_ptr(slots.value, ns.value, np.int32),
                 "fma_per_step": int(fma.value)}
+
+    def jit_prepare(self, backward: bool, B: int) -> int:
+        """Compiles the specialised kernel a batch of B paths would use; returns the library's status code."""
+        return int(self._lib.sig_wordset_jit_prepare(self._h, int(backward), B))
+
+    def jit_source(self, backward: bool, B: int) -> str:
+        n = int(self._lib.sig_wordset_jit_source(self._h, int(backward), B, None, 0))
+        buf = ctypes.create_string_buffer(n + 1)
+        self._lib.sig_wordset_jit_source(self._h, int(backward), B, buf, n + 1)
+        return buf.value.decode()
 
     # ---- device side
     def upload(self, device="cuda:0"):

@@ -6,7 +6,12 @@
 #include <new>
 #include <vector>
 
+#include <cstdlib>
+#include <mutex>
+#include <string>
+
 #include "../../include/sig.h"
+#include "jit.hpp"
 #include "kernels.hpp"
 #include "wordset.hpp"
 
@@ -25,10 +30,9 @@ const sig::WordSet* W(const sig_wordset* ws) { return ws; }
 
 // Picks the plan variant: the coarsest one (least recomputation of shared ancestors) that still
 // yields enough wavefronts to occupy the 256 compute units, else the finest.
-int pick_variant(const sig::WordSet& ws, int dir, int64_t B)
+int pick_variant(const sig::WordSet& ws, int dir, int64_t B, int64_t want = 2048 /* two wavefronts per SIMD */)
 {
     const int64_t groups = (B + 63) / 64;
-    const int64_t want = 2048;   // two wavefronts per SIMD
     const auto& pl = ws.plans[dir];
     for (size_t v = 0; v < pl.size(); ++v)
         if ((int64_t)pl[v].units.size() * groups >= want) return (int)v;
@@ -63,6 +67,87 @@ bool use_trunc_forward(const sig::WordSet& w, int64_t B)
 bool use_trunc_backward(const sig::WordSet& w, int64_t B)
 {
     return w.kind == 0 && B <= 65535 && sig::trunc_backward_available(w.d, w.depth);
+}
+
+// ---- run-time specialised kernels ------------------------------------------------------------------------
+std::mutex g_jit_mutex;
+
+// larger units than the table-driven kernels want: registers hold the coefficients, and fewer units mean less
+// recomputation of shared ancestors and less code to compile; one wavefront per SIMD is enough to start with
+int jit_variant(const sig::WordSet& w, int dir, int64_t B)
+{
+    int64_t want = 1024;
+    if (const char* e = std::getenv("SIG_JIT_WAVES")) want = std::max(1, std::atoi(e));   // tuning knob
+    return pick_variant(w, dir, B, want);
+}
+
+int jit_tile_steps(int d) { return std::min(8, 120 / std::max(d, 1)); }
+
+bool jit_enabled(const sig::WordSet& w)
+{
+    const char* off = std::getenv("SIG_NO_JIT");
+    if (off && off[0] && off[0] != '0') return false;
+    return w.kernels_supported && !w.plans[0].empty() && jit_tile_steps(w.d) >= 1;
+}
+
+// Source of the specialised kernel for (direction, variant); fills nw / tile.
+std::string jit_source(const sig::WordSet& w, int dir, int v, int& nw, int& tile)
+{
+    const sig::Plan& p = w.plans[dir][(size_t)v];
+    // Four wavefronts per workgroup = one per SIMD, so a workgroup's registers fit whatever a unit needs (up to 256
+    // VGPRs).  (A 512-thread workgroup of a 248-VGPR kernel was refused at dispatch on gfx950.)
+    int max_nw = 4;
+    if (const char* e = std::getenv("SIG_JIT_NW")) max_nw = std::max(1, std::min(4, std::atoi(e)));   // tuning knob
+    nw = (int)std::min<size_t>((size_t)max_nw, std::max<size_t>(1, p.units.size()));
+    tile = jit_tile_steps(w.d);
+    return dir ? sig::jit_backward_source(w, p, nw, tile) : sig::jit_forward_source(w, p, nw, tile);
+}
+
+// Compiled (and, if load is set, loaded) kernel for (direction, variant), or nullptr if specialisation is off or
+// failed.  Compilation happens once; the outcome is remembered.
+sig::JitKernel* ensure_jit(const sig::WordSet& cw, int dir, int v, bool load)
+{
+    if (!jit_enabled(cw)) return nullptr;
+    sig::WordSet& w = const_cast<sig::WordSet&>(cw);     // the cache is logically mutable
+    std::lock_guard<std::mutex> lock(g_jit_mutex);
+    auto& vec = w.jit[dir];
+    if (vec.size() < w.plans[dir].size()) vec.resize(w.plans[dir].size(), nullptr);
+    if (!vec[(size_t)v]) vec[(size_t)v] = new (std::nothrow) sig::JitKernel;
+    sig::JitKernel* k = vec[(size_t)v];
+    if (!k) return nullptr;
+    if (!k->tried) {
+        k->tried = true;
+        try {
+            const std::string src = jit_source(w, dir, v, k->nw, k->tile);
+            (void)sig::jit_compile(src, dir ? "sig_bwd_jit" : "sig_fwd_jit", *k);
+        } catch (const std::bad_alloc&) { k->ok = false; }
+    }
+    if (!k->ok) return nullptr;
+    if (load && !k->fn && sig::jit_load(*k) != hipSuccess) {
+        k->ok = false;
+        return nullptr;
+    }
+    return k;
+}
+
+hipError_t launch_jit_forward(sig::JitKernel& k, const sig::Plan& p, const float* path, int64_t B, int64_t P, float* coeffs,
+                              int64_t nW, hipStream_t st)
+{
+    long lB = (long)B, lP = (long)P, lW = (long)nW;
+    void* args[] = {(void*)&path, (void*)&lB, (void*)&lP, (void*)&coeffs, (void*)&lW};
+    const unsigned gx = (unsigned)((p.units.size() + (size_t)k.nw - 1) / (size_t)k.nw);
+    const unsigned gy = (unsigned)((B + 63) / 64);
+    return hipModuleLaunchKernel(k.fn, gx, gy, 1, (unsigned)k.nw * 64, 1, 1, 0, st, args, nullptr);
+}
+
+hipError_t launch_jit_backward(sig::JitKernel& k, const sig::Plan& p, const float* path, const float* coeffs,
+                               const float* grad, int64_t B, int64_t P, int64_t nW, float* gdx, hipStream_t st)
+{
+    long lB = (long)B, lP = (long)P, lW = (long)nW;
+    void* args[] = {(void*)&path, (void*)&coeffs, (void*)&grad, (void*)&lB, (void*)&lP, (void*)&lW, (void*)&gdx};
+    const unsigned gx = (unsigned)((p.units.size() + (size_t)k.nw - 1) / (size_t)k.nw);
+    const unsigned gy = (unsigned)((B + 63) / 64);
+    return hipModuleLaunchKernel(k.fn, gx, gy, 1, (unsigned)k.nw * 64, 1, 1, 0, st, args, nullptr);
 }
 
 int bwd_tile_steps(int d) { return std::max(1, std::min(16, 32 / std::max(d, 1))); }
@@ -145,6 +230,32 @@ int sig_wordset_plan_get(const sig_wordset* ws, int backward, int variant, const
     return SIG_OK;
 }
 
+int sig_wordset_jit_prepare(sig_wordset* ws, int backward, int64_t B)
+{
+    if (!ws || B < 1) return SIG_EINVAL;
+    const sig::WordSet& w = *W(ws);
+    const int dir = backward ? 1 : 0;
+    if (!jit_enabled(w)) return SIG_EUNSUPPORTED;
+    if (dir == 0 ? use_trunc_forward(w, B) : use_trunc_backward(w, B)) return SIG_EUNSUPPORTED;
+    return ensure_jit(w, dir, jit_variant(w, dir, B), false) ? SIG_OK : SIG_EJIT;
+}
+
+size_t sig_wordset_jit_source(sig_wordset* ws, int backward, int64_t B, char* buf, size_t n)
+{
+    if (!ws || B < 1) return 0;
+    const sig::WordSet& w = *W(ws);
+    const int dir = backward ? 1 : 0;
+    if (!w.kernels_supported || w.plans[dir].empty()) return 0;
+    int nw = 0, tile = 0;
+    const std::string src = jit_source(w, dir, jit_variant(w, dir, B), nw, tile);
+    if (buf && n > 0) {
+        const size_t c = std::min(n - 1, src.size());
+        std::memcpy(buf, src.data(), c);
+        buf[c] = 0;
+    }
+    return src.size();
+}
+
 size_t sig_wordset_device_bytes(const sig_wordset* ws) { return ws ? W(ws)->image.size() : 0; }
 
 int sig_wordset_upload(sig_wordset* ws, void* dev_buf, size_t dev_bytes, void* stream)
@@ -203,6 +314,14 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
         if (pe) (void)hipEventRecord(pe[1], st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
+    const int vj = jit_variant(w, 0, B);
+    if (sig::JitKernel* jk = ensure_jit(w, 0, vj, true)) {
+        hipEvent_t* pe = g_prof.next(0);
+        if (pe) (void)hipEventRecord(pe[0], st);
+        hipError_t e = launch_jit_forward(*jk, w.plans[0][(size_t)vj], path, B, n_points, coeffs, w.size(), st);
+        if (pe) (void)hipEventRecord(pe[1], st);
+        return e == hipSuccess ? SIG_OK : hip_fail(e);
+    }
     const int v = pick_variant(w, 0, B);
     const sig::Plan& p = w.plans[0][(size_t)v];
     const auto& po = w.offsets[0][(size_t)v];
@@ -245,6 +364,16 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
         hipEvent_t* pe = g_prof.next(1);
         if (pe) (void)hipEventRecord(pe[0], st);
         e = sig::trunc_backward(w.d, w.depth, path, coeffs, grad_coeffs, B, n_points, gdx, st);
+        if (pe) (void)hipEventRecord(pe[1], st);
+        if (e != hipSuccess) return hip_fail(e);
+        e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
+        return e == hipSuccess ? SIG_OK : hip_fail(e);
+    }
+    const int vj = jit_variant(w, 1, B);
+    if (sig::JitKernel* jk = ensure_jit(w, 1, vj, true)) {
+        hipEvent_t* pe = g_prof.next(1);
+        if (pe) (void)hipEventRecord(pe[0], st);
+        e = launch_jit_backward(*jk, w.plans[1][(size_t)vj], path, coeffs, grad_coeffs, B, n_points, w.size(), gdx, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
         e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
@@ -308,7 +437,8 @@ const char* sig_strerror(int code)
         case SIG_EHIP: return "HIP runtime error";
         case SIG_ETOOLARGE: return "word set exceeds a format limit";
         case SIG_ENOTUPLOADED: return "word set tables not uploaded";
-        case SIG_EUNSUPPORTED: return "word length not supported by the kernels";
+        case SIG_EUNSUPPORTED: return "not supported for this word set";
+        case SIG_EJIT: return "run-time compilation failed";
         default: return "unknown error";
     }
 }
@@ -321,6 +451,7 @@ const char* sig_wordset_kernel_name(const sig_wordset* ws, int backward)
     if (!ws || !W(ws)->kernels_supported) return "unsupported";
     if (!backward && use_trunc_forward(*W(ws), 1)) return "trunc_mfma_fwd_kernel";
     if (backward && use_trunc_backward(*W(ws), 1)) return "trunc_mfma_bwd_kernel";
+    if (jit_enabled(*W(ws))) return backward ? "sig_bwd_jit" : "sig_fwd_jit";
     return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";
 }
 

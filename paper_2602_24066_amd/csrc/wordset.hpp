@@ -22,6 +22,8 @@ inline uint32_t op_pack(uint32_t letter, uint32_t level, uint32_t h, uint32_t ki
     return letter | (level << 12) | (h << 16) | (kind << 20);
 }
 
+struct JitKernel;          // jit.hpp
+
 struct UnitDesc {          // device-visible, 16 bytes
     int32_t op_off;        // first op in Plan::ops
     int32_t n_ops;
@@ -65,6 +67,12 @@ struct WordSet {
     std::vector<unsigned char> image;
     void* dev = nullptr;
     bool kernels_supported = true;     // false when max_len exceeds what the kernels handle
+    // run-time specialised kernels, one per plan variant and direction, built on first use
+    std::vector<JitKernel*> jit[2];
+    WordSet() = default;
+    WordSet(const WordSet&) = delete;
+    WordSet& operator=(const WordSet&) = delete;
+    ~WordSet();                        // defined in jit.cpp (releases the compiled kernels)
 
     int64_t size() const { return (int64_t)parent.size(); }
 };
