@@ -81,13 +81,14 @@ int jit_variant(const sig::WordSet& w, int dir, int64_t B)
     return pick_variant(w, dir, B, want);
 }
 
-int jit_tile_steps(int d) { return std::min(8, 120 / std::max(d, 1)); }
+// segments per LDS tile; backward also keeps four gradient tiles [T][d][65] in the 64 KB of static LDS
+int jit_tile_steps(int d, int dir) { return std::min(8, (dir ? 48 : 240) / std::max(d, 1)); }
 
 bool jit_enabled(const sig::WordSet& w)
 {
     const char* off = std::getenv("SIG_NO_JIT");
     if (off && off[0] && off[0] != '0') return false;
-    return w.kernels_supported && !w.plans[0].empty() && jit_tile_steps(w.d) >= 1;
+    return w.kernels_supported && !w.plans[0].empty() && jit_tile_steps(w.d, 1) >= 1;
 }
 
 // Source of the specialised kernel for (direction, variant); fills nw / tile.
@@ -99,7 +100,7 @@ std::string jit_source(const sig::WordSet& w, int dir, int v, int& nw, int& tile
     int max_nw = 4;
     if (const char* e = std::getenv("SIG_JIT_NW")) max_nw = std::max(1, std::min(4, std::atoi(e)));   // tuning knob
     nw = (int)std::min<size_t>((size_t)max_nw, std::max<size_t>(1, p.units.size()));
-    tile = jit_tile_steps(w.d);
+    tile = jit_tile_steps(w.d, dir);
     return dir ? sig::jit_backward_source(w, p, nw, tile) : sig::jit_forward_source(w, p, nw, tile);
 }
 
@@ -130,21 +131,45 @@ sig::JitKernel* ensure_jit(const sig::WordSet& cw, int dir, int v, bool load)
     return k;
 }
 
-hipError_t launch_jit_forward(sig::JitKernel& k, const sig::Plan& p, const float* path, int64_t B, int64_t P, float* coeffs,
+// bytes of the transposed increments the specialised kernels read: [groups][Lpad][d][64] floats
+int64_t jit_lpad(const sig::WordSet& w, int64_t n_points, int dir)
+{
+    const int64_t T = jit_tile_steps(w.d, dir), L = n_points - 1;
+    return (L + T - 1) / T * T;
+}
+size_t jit_dxt_bytes(const sig::WordSet& w, int64_t B, int64_t n_points, int dir)
+{
+    const size_t n = (size_t)((B + 63) / 64) * (size_t)jit_lpad(w, n_points, dir) * (size_t)w.d * 64 * sizeof(float);
+    return (n + 255) & ~(size_t)255;
+}
+
+// workgroup columns of the specialised backward kernel (each writes its own gradient slice)
+int jit_bwd_columns(const sig::WordSet& w, int64_t B)
+{
+    const sig::Plan& p = w.plans[1][(size_t)jit_variant(w, 1, B)];
+    int nw = 0, tile = 0;
+    (void)tile;
+    int max_nw = 4;
+    if (const char* e = std::getenv("SIG_JIT_NW")) max_nw = std::max(1, std::min(4, std::atoi(e)));
+    nw = (int)std::min<size_t>((size_t)max_nw, std::max<size_t>(1, p.units.size()));
+    return (int)((p.units.size() + (size_t)nw - 1) / (size_t)nw);
+}
+
+hipError_t launch_jit_forward(sig::JitKernel& k, const sig::Plan& p, const float* dxT, int64_t B, int64_t ntiles, float* coeffs,
                               int64_t nW, hipStream_t st)
 {
-    long lB = (long)B, lP = (long)P, lW = (long)nW;
-    void* args[] = {(void*)&path, (void*)&lB, (void*)&lP, (void*)&coeffs, (void*)&lW};
+    long lB = (long)B, lT = (long)ntiles, lW = (long)nW;
+    void* args[] = {(void*)&dxT, (void*)&lB, (void*)&lT, (void*)&coeffs, (void*)&lW};
     const unsigned gx = (unsigned)((p.units.size() + (size_t)k.nw - 1) / (size_t)k.nw);
     const unsigned gy = (unsigned)((B + 63) / 64);
     return hipModuleLaunchKernel(k.fn, gx, gy, 1, (unsigned)k.nw * 64, 1, 1, 0, st, args, nullptr);
 }
 
-hipError_t launch_jit_backward(sig::JitKernel& k, const sig::Plan& p, const float* path, const float* coeffs,
-                               const float* grad, int64_t B, int64_t P, int64_t nW, float* gdx, hipStream_t st)
+hipError_t launch_jit_backward(sig::JitKernel& k, const sig::Plan& p, const float* dxT, const float* coeffs, const float* grad,
+                               int64_t B, int64_t L, int64_t ntiles, int64_t nW, float* gdx, hipStream_t st)
 {
-    long lB = (long)B, lP = (long)P, lW = (long)nW;
-    void* args[] = {(void*)&path, (void*)&coeffs, (void*)&grad, (void*)&lB, (void*)&lP, (void*)&lW, (void*)&gdx};
+    long lB = (long)B, lL = (long)L, lT = (long)ntiles, lW = (long)nW;
+    void* args[] = {(void*)&dxT, (void*)&coeffs, (void*)&grad, (void*)&lB, (void*)&lL, (void*)&lT, (void*)&lW, (void*)&gdx};
     const unsigned gx = (unsigned)((p.units.size() + (size_t)k.nw - 1) / (size_t)k.nw);
     const unsigned gy = (unsigned)((B + 63) / 64);
     return hipModuleLaunchKernel(k.fn, gx, gy, 1, (unsigned)k.nw * 64, 1, 1, 0, st, args, nullptr);
@@ -271,15 +296,21 @@ int sig_wordset_upload(sig_wordset* ws, void* dev_buf, size_t dev_bytes, void* s
 
 size_t sig_forward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
 {
-    (void)ws; (void)B; (void)n_points;
-    return 0;
+    if (!ws || B <= 0 || n_points <= 1) return 0;
+    const sig::WordSet& w = *W(ws);
+    if (use_trunc_forward(w, B) || !jit_enabled(w)) return 0;
+    return jit_dxt_bytes(w, B, n_points, 0);
 }
 
 size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
 {
     if (!ws || B <= 0 || n_points <= 1) return 0;
-    const size_t n = (size_t)B * (size_t)(n_points - 1) * (size_t)W(ws)->d * sizeof(float);
-    return (n + 255) & ~(size_t)255;
+    const sig::WordSet& w = *W(ws);
+    size_t n = (size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float);
+    n = (n + 255) & ~(size_t)255;                                   // gradient with respect to the increments
+    if (!use_trunc_backward(w, B) && jit_enabled(w))                // one gradient slice per workgroup column + increments
+        n = n * (size_t)jit_bwd_columns(w, B) + jit_dxt_bytes(w, B, n_points, 1);
+    return n;
 }
 
 static int check_common(const sig_wordset* ws, const void* path, int64_t B, int64_t n_points)
@@ -296,7 +327,6 @@ static int check_common(const sig_wordset* ws, const void* path, int64_t B, int6
 int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs, void* workspace,
                 size_t workspace_bytes, void* stream)
 {
-    (void)workspace; (void)workspace_bytes;
     int rc = check_common(ws, path, B, n_points);
     if (rc != SIG_OK) return rc;
     if (B == 0) return SIG_OK;
@@ -316,9 +346,15 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
     }
     const int vj = jit_variant(w, 0, B);
     if (sig::JitKernel* jk = ensure_jit(w, 0, vj, true)) {
+        if (!workspace || workspace_bytes < jit_dxt_bytes(w, B, n_points, 0)) return SIG_EWORKSPACE;
+        if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
+        float* dxT = (float*)workspace;
+        const int64_t Lpad = jit_lpad(w, n_points, 0);
+        hipError_t e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, st);
+        if (e != hipSuccess) return hip_fail(e);
         hipEvent_t* pe = g_prof.next(0);
         if (pe) (void)hipEventRecord(pe[0], st);
-        hipError_t e = launch_jit_forward(*jk, w.plans[0][(size_t)vj], path, B, n_points, coeffs, w.size(), st);
+        e = launch_jit_forward(*jk, w.plans[0][(size_t)vj], dxT, B, Lpad / jk->tile, coeffs, w.size(), st);
         if (pe) (void)hipEventRecord(pe[1], st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
@@ -371,12 +407,19 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     }
     const int vj = jit_variant(w, 1, B);
     if (sig::JitKernel* jk = ensure_jit(w, 1, vj, true)) {
+        const int ncol = jit_bwd_columns(w, B);
+        const size_t gdx_bytes = ((size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;
+        float* dxT = (float*)((unsigned char*)workspace + gdx_bytes * (size_t)ncol);
+        const int64_t Lpad = jit_lpad(w, n_points, 1);
+        e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, st);
+        if (e != hipSuccess) return hip_fail(e);
         hipEvent_t* pe = g_prof.next(1);
         if (pe) (void)hipEventRecord(pe[0], st);
-        e = launch_jit_backward(*jk, w.plans[1][(size_t)vj], path, coeffs, grad_coeffs, B, n_points, w.size(), gdx, st);
+        e = launch_jit_backward(*jk, w.plans[1][(size_t)vj], dxT, coeffs, grad_coeffs, B, n_points - 1, Lpad / jk->tile, w.size(),
+                                gdx, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
-        e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
+        e = sig::grad_points_sum(gdx, ncol, B, n_points, w.d, grad_path, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
     const int v = pick_variant(w, 1, B);

@@ -44,85 +44,88 @@ std::string dxn(int i, int t) { return t == 0 ? "dx" + std::to_string(i) : "dx" 
 void emit_prelude(std::ostringstream& o, int D, int T, int NW, bool backward)
 {
     o << "#define D " << D << "\n#define T " << T << "\n#define NW " << NW << "\n";
-    o << "#define EPW ((T * D + NW - 1) / NW)\n";
+    o << "#define TILE_F4 (T * D * 16)\n";                         // float4 per tile (T * D rows of 64 floats)
+    o << "#define EPT ((TILE_F4 + NW * 64 - 1) / (NW * 64))\n";    // float4 per thread
     o << "#define LP 65\n";
     o << R"SRC(
-// increments of one tile for the 64 paths of the workgroup: tile[(tt * D + i) * 64 + lane]; every wavefront
-// fetches a share of the (segment, letter) pairs one tile ahead into registers and parks them in LDS later
-// (not inlined: the same code in every unit function would dominate the compile time)
-__device__ __attribute__((noinline)) void tile_fetch(const float* __restrict__ X, long L, long j0, int wib, float (&r)[EPW])
+typedef float f4 __attribute__((ext_vector_type(4)));
+// The increments arrive differenced and transposed (increments_transposed_kernel): for the 64 paths of the
+// workgroup, dxg[(j * D + i) * 64 + lane], zero for segments j >= L, and the segment count padded to a multiple
+// of T, so a tile is one contiguous block that the workgroup copies to LDS with 16-byte accesses.
+__device__ __forceinline__ void tile_fetch(const float* __restrict__ dxg, long tile_idx, int tid, f4 (&r)[EPT])
 {
+    const f4* p = (const f4*)dxg + (tile_idx < 0 ? 0 : tile_idx) * TILE_F4;
 #pragma unroll
-    for (int q = 0; q < EPW; ++q) {
-        int e = wib + q * NW;
-        if (e >= T * D) e = T * D - 1;
-        const long jj = j0 + e / D;
-        const long jc = jj < 0 ? 0 : (jj < L ? jj : L - 1);
-        const int i = e % D;
-        const float x1 = X[(jc + 1) * D + i], x0 = X[jc * D + i];
-        r[q] = (jj >= 0 && jj < L) ? x1 - x0 : 0.0f;
+    for (int q = 0; q < EPT; ++q) {
+        const int e = tid + q * NW * 64;
+        r[q] = p[e < TILE_F4 ? e : TILE_F4 - 1];
     }
 }
-__device__ __attribute__((noinline)) void tile_stage(float* tile, int lane, int wib, const float (&r)[EPW])
+__device__ __forceinline__ void tile_stage(float* tile, int tid, const f4 (&r)[EPT])
 {
 #pragma unroll
-    for (int q = 0; q < EPW; ++q) {
-        const int e = wib + q * NW;
-        if (e < T * D) tile[e * 64 + lane] = r[q];
+    for (int q = 0; q < EPT; ++q) {
+        const int e = tid + q * NW * 64;
+        if (e < TILE_F4) ((f4*)tile)[e] = r[q];
     }
 }
 )SRC";
     if (!backward) {
         o << R"SRC(
 // a wavefront without a unit still takes part in loading the tiles and in the barriers
-__device__ __attribute__((noinline)) void idle_unit(const float* __restrict__ X, long L, float* tile, int lane, int wib)
+__device__ __attribute__((noinline)) void idle_unit(const float* __restrict__ dxg, long ntiles, float* tile, int tid)
 {
-    float r[EPW];
-    tile_fetch(X, L, 0, wib, r);
-    tile_stage(tile, lane, wib, r);
+    f4 r[EPT];
+    tile_fetch(dxg, 0, tid, r);
+    tile_stage(tile, tid, r);
     __syncthreads();
-    for (long j0 = 0; j0 < L; j0 += T) {
-        tile_fetch(X, L, j0 + T, wib, r);
+    for (long n = 0; n < ntiles; ++n) {
+        tile_fetch(dxg, n + 1 < ntiles ? n + 1 : n, tid, r);
         __syncthreads();
-        tile_stage(tile, lane, wib, r);
+        tile_stage(tile, tid, r);
         __syncthreads();
     }
 }
 )SRC";
     } else {
         o << R"SRC(
-// gradient tile gt[(tt * D + i) * LP + lane], shared by the units of the workgroup; flushed per tile with one
-// path per pass so that (segment, letter) runs are contiguous in gdx
-__device__ __attribute__((noinline)) void grad_flush(float* gt, float* gdx, long L, long j0, long b0, long B, int lane, int wib)
+// Gradient tiles: every wavefront (unit) has its own gt[(tt * D + i) * LP + lane] in LDS and overwrites all of it
+// in every tile with plain stores (LDS floating-point atomics turned out to be far slower than the arithmetic).
+// At the end of a tile the NW tiles are added up and written out with one path per pass, so that (segment,
+// letter) runs are contiguous.  Every workgroup column (blockIdx.x) owns a private slice gpart[blockIdx.x][B][L][D]
+// that it fills with plain stores; the slices are summed by a later kernel.
+#define GT_F (T * D * LP)
+__device__ __attribute__((noinline)) void grad_flush(const float* gt_all, float* gpart, long L, long j0, long b0, long B, int lane,
+                                                     int wib)
 {
     for (int bb = wib; bb < 64; bb += NW) {
         if (b0 + bb < B) {
-            float* dst = gdx + ((b0 + bb) * L + j0) * D;
+            float* dst = gpart + ((b0 + bb) * L + j0) * D;
             for (int e = lane; e < T * D; e += 64)
-                if (j0 + e / D < L) unsafeAtomicAdd(dst + e, gt[e * LP + bb]);
+                if (j0 + e / D < L) {
+                    float v = 0.0f;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) v += gt_all[w * GT_F + e * LP + bb];
+                    dst[e] = v;
+                }
         }
     }
 }
-__device__ __attribute__((noinline)) void grad_zero(float* gt, int tid)
+__device__ __attribute__((noinline)) void idle_unit(const float* __restrict__ dxg, long ntiles, long L, float* tile, float* gt_all,
+                                                    float* gpart, long b0, long B, int lane, int wib)
 {
-    for (int e = tid; e < T * D * LP; e += NW * 64) gt[e] = 0.0f;
-}
-__device__ __attribute__((noinline)) void idle_unit(const float* __restrict__ X, long L, float* tile, float* gt, float* gdx,
-                                                    long b0, long B, int lane, int wib)
-{
-    float r[EPW];
-    const long ntiles = (L + T - 1) / T;
-    grad_zero(gt, wib * 64 + lane);
-    tile_fetch(X, L, (ntiles - 1) * T, wib, r);
+    f4 r[EPT];
+    const int tid = wib * 64 + lane;
+    float* gt = gt_all + wib * GT_F;
+    for (int e = lane; e < GT_F; e += 64) gt[e] = 0.0f;       // this wavefront contributes nothing
+    tile_fetch(dxg, ntiles - 1, tid, r);
     for (long n = ntiles - 1; n >= 0; --n) {
         __syncthreads();
-        tile_stage(tile, lane, wib, r);
+        tile_stage(tile, tid, r);
         __syncthreads();
-        tile_fetch(X, L, (n - 1) * T, wib, r);
+        tile_fetch(dxg, n - 1, tid, r);
         __syncthreads();
-        grad_flush(gt, gdx, L, n * T, b0, B, lane, wib);
-        __syncthreads();
-        grad_zero(gt, wib * 64 + lane);
+        grad_flush(gt_all, gpart, L, n * T, b0, B, lane, wib);
     }
 }
 )SRC";
@@ -159,15 +162,15 @@ void emit_forward_unit(std::ostringstream& o, const Plan& plan, int uidx)
     const UnitDesc& ud = plan.units[(size_t)uidx];
     const Uses uses = collect_uses(plan, ud);
     o << "__device__ __attribute__((noinline)) void fwd_unit_" << uidx
-      << "(const float* __restrict__ X, long L, float* tile, int lane, int wib, float* __restrict__ out)\n{\n";
+      << "(const float* __restrict__ dxg, long ntiles, float* tile, int lane, int wib, float* __restrict__ out)\n{\n";
     o << "    float";
     for (int r = 0; r < ud.n_slots; ++r) o << (r ? ", " : " ") << "s" << r << " = 0.0f";
     o << ";\n";
-    o << "    float r[EPW];\n    tile_fetch(X, L, 0, wib, r);\n    tile_stage(tile, lane, wib, r);\n    __syncthreads();\n";
-    o << "    for (long j0 = 0; j0 < L; j0 += T) {\n";
-    o << "        tile_fetch(X, L, j0 + T, wib, r);\n";
-    o << "        const int nt = (L - j0) < T ? (int)(L - j0) : T;\n";
-    o << "        for (int tt = 0; tt < nt; ++tt) {\n";
+    o << "    const int tid = wib * 64 + lane;\n";
+    o << "    f4 r[EPT];\n    tile_fetch(dxg, 0, tid, r);\n    tile_stage(tile, tid, r);\n    __syncthreads();\n";
+    o << "    for (long n = 0; n < ntiles; ++n) {\n";
+    o << "        tile_fetch(dxg, n + 1 < ntiles ? n + 1 : n, tid, r);\n";
+    o << "        for (int tt = 0; tt < T; ++tt) {\n";
     o << "            const float* dxp = tile + tt * D * 64 + lane;\n";
     emit_step_loads(o, uses, "            ");
     int depth = 0;   // open scopes = length of the current word chain
@@ -189,7 +192,7 @@ void emit_forward_unit(std::ostringstream& o, const Plan& plan, int uidx)
         ++slot;
     }
     while (depth > 0) { o << "            }\n"; --depth; }
-    o << "        }\n        __syncthreads();\n        tile_stage(tile, lane, wib, r);\n        __syncthreads();\n    }\n";
+    o << "        }\n        __syncthreads();\n        tile_stage(tile, tid, r);\n        __syncthreads();\n    }\n";
     o << "    if (out) {\n";
     for (int r = 0; r < ud.n_slots; ++r) {
         const int32_t w = plan.slot_word[(size_t)(ud.slot_off + r)];
@@ -198,13 +201,13 @@ void emit_forward_unit(std::ostringstream& o, const Plan& plan, int uidx)
     o << "    }\n}\n\n";
 }
 
-void emit_backward_unit(std::ostringstream& o, const Plan& plan, int uidx)
+void emit_backward_unit(std::ostringstream& o, const Plan& plan, int uidx, int D_of_plan)
 {
     const UnitDesc& ud = plan.units[(size_t)uidx];
     const Uses uses = collect_uses(plan, ud);
     o << "__device__ __attribute__((noinline)) void bwd_unit_" << uidx
-      << "(const float* __restrict__ X, long L, float* tile, float* gt, float* gdx, long b0, long B, int lane, int wib,\n"
-         "     const float* __restrict__ cf, const float* __restrict__ gr)\n{\n";
+      << "(const float* __restrict__ dxg, long ntiles, long L, float* tile, float* gt_all, float* gdx, long b0, long B, int lane,\n"
+         "     int wib, const float* __restrict__ cf, const float* __restrict__ gr)\n{\n";
     for (int r = 0; r < ud.n_slots; ++r) {
         const int32_t w = plan.slot_word[(size_t)(ud.slot_off + r)];
         const int32_t wi = w >= 0 ? w : ~w;
@@ -212,11 +215,12 @@ void emit_backward_unit(std::ostringstream& o, const Plan& plan, int uidx)
         if (w >= 0) o << "gr[" << wi << "];\n";
         else o << "0.0f;\n";
     }
-    o << "    float r[EPW];\n    const long ntiles = (L + T - 1) / T;\n    grad_zero(gt, wib * 64 + lane);\n";
-    o << "    tile_fetch(X, L, (ntiles - 1) * T, wib, r);\n";
+    o << "    const int tid = wib * 64 + lane;\n";
+    o << "    f4 r[EPT];\n    float* gt = gt_all + wib * GT_F;\n";
+    o << "    tile_fetch(dxg, ntiles - 1, tid, r);\n";
     o << "    for (long n = ntiles - 1; n >= 0; --n) {\n";
-    o << "        __syncthreads();\n        tile_stage(tile, lane, wib, r);\n        __syncthreads();\n";
-    o << "        tile_fetch(X, L, (n - 1) * T, wib, r);\n";
+    o << "        __syncthreads();\n        tile_stage(tile, tid, r);\n        __syncthreads();\n";
+    o << "        tile_fetch(dxg, n - 1, tid, r);\n";
     o << "        for (int tt = T - 1; tt >= 0; --tt) {\n";
     o << "            const float* dxp = tile + tt * D * 64 + lane;\n";
     emit_step_loads(o, uses, "            ");
@@ -280,11 +284,12 @@ void emit_backward_unit(std::ostringstream& o, const Plan& plan, int uidx)
         }
     }
     o << "            float* gp = gt + tt * D * LP + lane;\n";
-    for (int i : uses.letters)
-        o << "            __hip_atomic_fetch_add(gp + " << i << " * LP, g" << i << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);\n";
+    for (int i = 0; i < D_of_plan; ++i) {
+        if (uses.letters.count(i)) o << "            gp[" << i << " * LP] = g" << i << ";\n";
+        else o << "            gp[" << i << " * LP] = 0.0f;\n";
+    }
     o << "        }\n";
-    o << "        __syncthreads();\n        grad_flush(gt, gdx, L, n * T, b0, B, lane, wib);\n        __syncthreads();\n";
-    o << "        grad_zero(gt, wib * 64 + lane);\n    }\n}\n\n";
+    o << "        __syncthreads();\n        grad_flush(gt_all, gdx, L, n * T, b0, B, lane, wib);\n    }\n}\n\n";
 }
 
 }  // namespace
@@ -295,16 +300,16 @@ std::string jit_forward_source(const WordSet& ws, const Plan& plan, int NW, int 
     emit_prelude(o, ws.d, T, NW, false);
     const int nu = (int)plan.units.size();
     for (int u = 0; u < nu; ++u) emit_forward_unit(o, plan, u);
-    o << "extern \"C\" __global__ __launch_bounds__(NW * 64) void sig_fwd_jit(const float* __restrict__ path, long B, long P,\n"
+    o << "extern \"C\" __global__ __launch_bounds__(NW * 64) void sig_fwd_jit(const float* __restrict__ dxT, long B, long ntiles,\n"
          "                                                                  float* __restrict__ coeffs, long nW)\n{\n";
-    o << "    __shared__ float tile[T * D * 64];\n";
+    o << "    __shared__ __attribute__((aligned(16))) float tile[T * D * 64];\n";
     o << "    const int lane = threadIdx.x & 63;\n    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);\n";
     o << "    const long b = (long)blockIdx.y * 64 + lane;\n    const bool valid = b < B;\n";
-    o << "    const float* X = path + (valid ? b : B - 1) * P * D;\n    const long L = P - 1;\n";
+    o << "    const float* dxg = dxT + (long)blockIdx.y * ntiles * (T * D * 64);\n";
     o << "    float* out = valid ? coeffs + b * nW : nullptr;\n";
     o << "    const int unit = blockIdx.x * NW + wib;\n    switch (unit) {\n";
-    for (int u = 0; u < nu; ++u) o << "        case " << u << ": fwd_unit_" << u << "(X, L, tile, lane, wib, out); break;\n";
-    o << "        default: idle_unit(X, L, tile, lane, wib); break;\n    }\n}\n";
+    for (int u = 0; u < nu; ++u) o << "        case " << u << ": fwd_unit_" << u << "(dxg, ntiles, tile, lane, wib, out); break;\n";
+    o << "        default: idle_unit(dxg, ntiles, tile, wib * 64 + lane); break;\n    }\n}\n";
     return o.str();
 }
 
@@ -313,18 +318,19 @@ std::string jit_backward_source(const WordSet& ws, const Plan& plan, int NW, int
     std::ostringstream o;
     emit_prelude(o, ws.d, T, NW, true);
     const int nu = (int)plan.units.size();
-    for (int u = 0; u < nu; ++u) emit_backward_unit(o, plan, u);
-    o << "extern \"C\" __global__ __launch_bounds__(NW * 64) void sig_bwd_jit(const float* __restrict__ path,\n"
-         "        const float* __restrict__ coeffs, const float* __restrict__ grad, long B, long P, long nW, float* gdx)\n{\n";
-    o << "    __shared__ float tile[T * D * 64];\n    __shared__ float gt[T * D * LP];\n";
+    for (int u = 0; u < nu; ++u) emit_backward_unit(o, plan, u, ws.d);
+    o << "extern \"C\" __global__ __launch_bounds__(NW * 64) void sig_bwd_jit(const float* __restrict__ dxT,\n"
+         "        const float* __restrict__ coeffs, const float* __restrict__ grad, long B, long L, long ntiles, long nW, float* gdx)\n{\n";
+    o << "    __shared__ __attribute__((aligned(16))) float tile[T * D * 64];\n    __shared__ float gt[NW * GT_F];\n";
     o << "    const int lane = threadIdx.x & 63;\n    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);\n";
     o << "    const long b0 = (long)blockIdx.y * 64;\n    const long b = b0 + lane;\n    const long bc = b < B ? b : B - 1;\n";
-    o << "    const float* X = path + bc * P * D;\n    const long L = P - 1;\n";
+    o << "    const float* dxg = dxT + (long)blockIdx.y * ntiles * (T * D * 64);\n";
     o << "    const float* cf = coeffs + bc * nW;\n    const float* gr = grad + bc * nW;\n";
+    o << "    gdx += (long)blockIdx.x * B * L * D;\n";
     o << "    const int unit = blockIdx.x * NW + wib;\n    switch (unit) {\n";
     for (int u = 0; u < nu; ++u)
-        o << "        case " << u << ": bwd_unit_" << u << "(X, L, tile, gt, gdx, b0, B, lane, wib, cf, gr); break;\n";
-    o << "        default: idle_unit(X, L, tile, gt, gdx, b0, B, lane, wib); break;\n    }\n}\n";
+        o << "        case " << u << ": bwd_unit_" << u << "(dxg, ntiles, L, tile, gt, gdx, b0, B, lane, wib, cf, gr); break;\n";
+    o << "        default: idle_unit(dxg, ntiles, L, tile, gt, gdx, b0, B, lane, wib); break;\n    }\n}\n";
     return o.str();
 }
 

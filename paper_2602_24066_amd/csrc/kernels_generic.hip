@@ -252,6 +252,25 @@ __global__ __launch_bounds__(kWave) void bwd_generic_kernel(const UnitDesc* __re
     }
 }
 
+// Increments, differenced and transposed for the run-time specialised kernels (lane = path):
+//   dxT[((g * Lpad + j) * d + i) * 64 + lane] = X[b][j+1][i] - X[b][j][i],  b = 64 g + lane,
+// zero for padded segments j >= L and for b >= B.
+__global__ void increments_transposed_kernel(const float* __restrict__ path, int64_t B, int64_t P, int d, int64_t Lpad,
+                                             int64_t total, float* __restrict__ dxT)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int lane = (int)(idx % kWave);
+    const int64_t r = idx / kWave;
+    const int i = (int)(r % d);
+    const int64_t j = (r / d) % Lpad;
+    const int64_t g = r / ((int64_t)d * Lpad);
+    const int64_t b = g * kWave + lane;
+    float v = 0.0f;
+    if (b < B && j < P - 1) v = path[(b * P + j + 1) * d + i] - path[(b * P + j) * d + i];
+    dxT[idx] = v;
+}
+
 __global__ void fill_zero_kernel(float* p, int64_t n)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -270,6 +289,30 @@ __global__ void grad_points_kernel(const float* __restrict__ gdx, int64_t B, int
     const int64_t L = P - 1;
     const float here = j >= 1 ? gdx[(b * L + (j - 1)) * d + c] : 0.0f;
     const float next = j < L ? gdx[(b * L + j) * d + c] : 0.0f;
+    grad_path[i] = here - next;
+}
+
+// As grad_points_kernel, for n_part partial gradients [n_part][B][L][d] that still have to be added up.
+__global__ void grad_points_sum_kernel(const float* __restrict__ gpart, int n_part, int64_t B, int64_t P, int d,
+                                       float* __restrict__ grad_path)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t n = B * P * d;
+    if (i >= n) return;
+    const int64_t c = i % d;
+    const int64_t j = (i / d) % P;
+    const int64_t b = i / (d * P);
+    const int64_t L = P - 1;
+    const int64_t stride = B * L * d;
+    float here = 0.0f, next = 0.0f;
+    if (j >= 1) {
+        const float* p = gpart + (b * L + (j - 1)) * d + c;
+        for (int w = 0; w < n_part; ++w) here += p[w * stride];
+    }
+    if (j < L) {
+        const float* p = gpart + (b * L + j) * d + c;
+        for (int w = 0; w < n_part; ++w) next += p[w * stride];
+    }
     grad_path[i] = here - next;
 }
 
@@ -325,6 +368,17 @@ hipError_t generic_backward(const GenericArgs& a, int max_len, hipStream_t strea
     return launch_bwd<12>(a, stream);
 }
 
+hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d, int64_t Lpad, float* dxT, hipStream_t stream)
+{
+    const int64_t total = ((B + kWave - 1) / kWave) * Lpad * d * kWave;
+    if (total <= 0) return hipSuccess;
+    const int threads = 256;
+    const int64_t blocks = (total + threads - 1) / threads;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    increments_transposed_kernel<<<(unsigned)blocks, threads, 0, stream>>>(path, B, P, d, Lpad, total, dxT);
+    return hipGetLastError();
+}
+
 hipError_t fill_zero(float* p, int64_t n, hipStream_t stream)
 {
     if (n <= 0) return hipSuccess;
@@ -339,6 +393,15 @@ hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* gra
     if (n <= 0) return hipSuccess;
     const int threads = 256;
     grad_points_kernel<<<(unsigned)((n + threads - 1) / threads), threads, 0, stream>>>(gdx, B, P, d, grad_path);
+    return hipGetLastError();
+}
+
+hipError_t grad_points_sum(const float* gpart, int n_part, int64_t B, int64_t P, int d, float* grad_path, hipStream_t stream)
+{
+    const int64_t n = B * P * d;
+    if (n <= 0) return hipSuccess;
+    const int threads = 256;
+    grad_points_sum_kernel<<<(unsigned)((n + threads - 1) / threads), threads, 0, stream>>>(gpart, n_part, B, P, d, grad_path);
     return hipGetLastError();
 }
 

@@ -164,7 +164,17 @@ def test_error_codes():
     assert lib.sig_wordset_upload(ws._h, ctypes.c_void_p(260), 1 << 20, None) == -1                        # misaligned
     deep = S.sig_wordset_build_truncated(2, 14)
     assert lib.sig_forward(deep._h, ctypes.c_void_p(256), 1, 2, ctypes.c_void_p(256), None, 0, None) == -9
-    assert lib.sig_backward_workspace_bytes(ws._h, 4, 11) == 4 * 10 * 2 * 4 + (-(4 * 10 * 2 * 4)) % 256
+    gdx = 4 * 10 * 2 * 4 + (-(4 * 10 * 2 * 4)) % 256          # dLoss/d dX: B * L * d floats, rounded up to 256 bytes
+    os.environ["SIG_NO_JIT"] = "1"
+    try:
+        assert lib.sig_backward_workspace_bytes(ws._h, 4, 11) == gdx
+        assert lib.sig_forward_workspace_bytes(ws._h, 4, 11) == 0
+    finally:
+        del os.environ["SIG_NO_JIT"]
+    # with run-time specialisation: one gradient slice per workgroup column plus the transposed increments
+    nb = lib.sig_backward_workspace_bytes(ws._h, 4, 11)
+    nf = lib.sig_forward_workspace_bytes(ws._h, 4, 11)
+    assert nf > 0 and nf % 256 == 0 and nb % 256 == 0 and nb >= gdx + nf and (nb - nf) % gdx == 0
     assert lib.sig_backward_workspace_bytes(ws._h, 4, 1) == 0
     lib.sig_wordset_free(None)
 
