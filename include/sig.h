@@ -14,7 +14,7 @@
  *     (Appendix A, word integer encoding), i.e. levels 1..N concatenated,
  *     each row-major.
  *   - A path is float32 [B, n_points, d], row-major, n_points = L + 1 >= 1.
- *   - coeffs / grad_coeffs are float32 [B, |W|] in canonical order.
+ *   - coeffs / grad_coeffs are float32 [B, |W|] in canonical order, 16-byte aligned.
  *   - Every function returns 0 on success and a negative SIG_E* code on
  *     failure; nothing is printed, no exception or abort crosses the ABI.
  *   - "host" / "device" on a pointer says where the memory lives.  The library
@@ -117,6 +117,13 @@ int sig_wordset_plan_get(const sig_wordset* ws, int backward, int variant, const
  * then fall back to the table-driven kernels).  Setting the environment variable SIG_NO_JIT=1 disables it. */
 #define SIG_EJIT (-10)
 int sig_wordset_jit_prepare(sig_wordset* ws, int backward, int64_t B);
+/* The plan the specialised kernel for a batch of B paths is generated from, in the format of sig_wordset_plan_get.
+ * Here the words in depth-first order are cut into consecutive runs of nearly equal cost, one per wavefront, as
+ * many as the batch needs to occupy the chip; a unit is one run plus the ancestors of its first word.  Pointers
+ * stay valid until sig_wordset_free.  Host only. */
+int sig_wordset_jit_plan_get(sig_wordset* ws, int backward, int64_t B, const int32_t** units, int64_t* n_units,
+                             const uint32_t** ops, int64_t* n_ops, const int32_t** slot_word, int64_t* n_slots,
+                             int64_t* fma_per_step);
 /* Copies the generated source (NUL-terminated, truncated to n bytes) and returns its full length, 0 if none. */
 size_t sig_wordset_jit_source(sig_wordset* ws, int backward, int64_t B, char* buf, size_t n);
 
@@ -133,6 +140,9 @@ int    sig_wordset_upload(sig_wordset* ws, void* dev_buf /*device*/, size_t dev_
  * coeffs device float32 [B, |W|]            fully overwritten
  * workspace: device, sig_forward_workspace_bytes bytes (may be 0 -> NULL allowed), 256-byte aligned,
  *            contents undefined before and after.
+ * Full truncations with few paths are cut into time chunks that run side by side and are multiplied together
+ * afterwards (Chen's relation, eq. 2, is associative); sig_backward does the same and recomputes the chunk
+ * signatures from the path.
  * n_points == 1 gives all-zero coeffs (S_{0,0} = 1 has no non-empty-word part).  B == 0 is a no-op. */
 size_t sig_forward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
 int    sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs,
@@ -152,15 +162,16 @@ int    sig_backward(const sig_wordset* ws, const float* path, const float* coeff
                     void* stream);
 
 /* ---- kernel timer ----------------------------------------------------------------------------------------
- * For benchmarks: while enabled, sig_forward / sig_backward record a HIP event pair on the caller's stream
- * around their main kernel only (the hot loop over segments; not the small fill / chain-rule kernels).
- * sig_profile_read synchronises with the recorded events and returns the number of launches recorded for
- * `backward` (0 or 1) since sig_profile_enable(1) and the sum of their durations in milliseconds.  At most
- * SIG_PROFILE_MAX_LAUNCHES launches per direction are kept; later ones are not recorded.  Not thread-safe;
- * events are created on first use (no device memory is allocated). */
+ * For benchmarks: while enabled, sig_forward / sig_backward record two HIP event pairs on the caller's stream:
+ * one around their main kernel (the hot loop over segments) and one around everything the call enqueues (with
+ * the small fill / transpose / chunk-product / chain-rule kernels).  sig_profile_read synchronises with the
+ * recorded events and returns the number of calls recorded since sig_profile_enable(1) and the sum of the
+ * durations in milliseconds for `which` = 0 forward main kernel, 1 backward main kernel, 2 whole forward call,
+ * 3 whole backward call.  At most SIG_PROFILE_MAX_LAUNCHES calls per direction are kept; later ones are not
+ * recorded.  Not thread-safe; events are created on first use (no device memory is allocated). */
 #define SIG_PROFILE_MAX_LAUNCHES 4096
 int sig_profile_enable(int on);
-int sig_profile_read(int backward, int64_t* n_launches, double* total_ms);
+int sig_profile_read(int which, int64_t* n_launches, double* total_ms);
 
 /* ---- diagnostics ------------------------------------------------------------------------------------- */
 const char* sig_strerror(int code);

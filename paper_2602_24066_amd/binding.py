@@ -65,6 +65,8 @@ def load_library():
     sig("sig_wordset_plan_count", c_int, [c_p, c_int])
     sig("sig_wordset_plan_get", c_int, [c_p, c_int, c_int, PP, ctypes.POINTER(c_i64), PP, ctypes.POINTER(c_i64), PP,
                                          ctypes.POINTER(c_i64), ctypes.POINTER(c_i64)])
+    sig("sig_wordset_jit_plan_get", c_int, [c_p, c_int, c_i64, PP, ctypes.POINTER(c_i64), PP, ctypes.POINTER(c_i64), PP,
+                                             ctypes.POINTER(c_i64), ctypes.POINTER(c_i64)])
     sig("sig_wordset_jit_prepare", c_int, [c_p, c_int, c_i64])
     sig("sig_wordset_jit_source", c_sz, [c_p, c_int, c_i64, c_p, c_sz])
     sig("sig_wordset_device_bytes", c_sz, [c_p])
@@ -173,6 +175,18 @@ class WordSet:
                 "slot_word": _np_from_ptr(slots.value, ns.value, np.int32),
                 "fma_per_step": int(fma.value)}
 
+    def jit_plan(self, backward: bool, B: int) -> dict:
+        """The balanced plan the specialised kernel for a batch of B paths is generated from (same format as plan)."""
+        units, ops, slots = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+        nu, no, ns, fma = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+        _check(self._lib.sig_wordset_jit_plan_get(self._h, int(backward), B, ctypes.byref(units), ctypes.byref(nu),
+                                                  ctypes.byref(ops), ctypes.byref(no), ctypes.byref(slots), ctypes.byref(ns),
+                                                  ctypes.byref(fma)), "sig_wordset_jit_plan_get")
+        return {"units": _np_from_ptr(units.value, nu.value * 4, np.int32).reshape(-1, 4),
+                "ops": _np_from_ptr(ops.value, no.value, np.uint32),
+                "slot_word": _np_from_ptr(slots.value, ns.value, np.int32),
+                "fma_per_step": int(fma.value)}
+
     def jit_prepare(self, backward: bool, B: int) -> int:
         """Compiles the specialised kernel a batch of B paths would use; returns the library's status code."""
         return int(self._lib.sig_wordset_jit_prepare(self._h, int(backward), B))
@@ -252,7 +266,7 @@ def sig_forward(ws: WordSet, path, out=None, workspace=None):
     if workspace is None:
         keep, wptr = _aligned_workspace(nbytes, path.device)
     else:
-        keep, wptr = workspace, workspace.data_ptr()
+        keep, wptr, nbytes = workspace, workspace.data_ptr(), workspace.numel() * workspace.element_size()
     with torch.cuda.device(path.device):
         stream = torch.cuda.current_stream().cuda_stream
         _check(lib.sig_forward(ws._h, ctypes.c_void_p(path.data_ptr()), B, P, ctypes.c_void_p(out.data_ptr()),
@@ -279,7 +293,7 @@ def sig_backward(ws: WordSet, path, coeffs, grad_coeffs, out=None, workspace=Non
     if workspace is None:
         keep, wptr = _aligned_workspace(nbytes, path.device)
     else:
-        keep, wptr = workspace, workspace.data_ptr()
+        keep, wptr, nbytes = workspace, workspace.data_ptr(), workspace.numel() * workspace.element_size()
     with torch.cuda.device(path.device):
         stream = torch.cuda.current_stream().cuda_stream
         _check(lib.sig_backward(ws._h, ctypes.c_void_p(path.data_ptr()), ctypes.c_void_p(coeffs.data_ptr()),
@@ -294,8 +308,10 @@ def sig_profile_enable(on: bool) -> None:
     _check(load_library().sig_profile_enable(int(on)), "sig_profile_enable")
 
 
-def sig_profile_read(backward: bool) -> Tuple[int, float]:
-    """(launches recorded, summed main-kernel time in ms) since sig_profile_enable(True)."""
+def sig_profile_read(backward: bool, whole_call: bool = False) -> Tuple[int, float]:
+    """(calls recorded, summed time in ms) since sig_profile_enable(True): of the main kernel, or with whole_call of
+    everything the call enqueued."""
     n, ms = ctypes.c_int64(), ctypes.c_double()
-    _check(load_library().sig_profile_read(int(backward), ctypes.byref(n), ctypes.byref(ms)), "sig_profile_read")
+    which = int(bool(backward)) + (2 if whole_call else 0)
+    _check(load_library().sig_profile_read(which, ctypes.byref(n), ctypes.byref(ms)), "sig_profile_read")
     return int(n.value), float(ms.value)

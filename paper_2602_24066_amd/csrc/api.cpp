@@ -39,11 +39,11 @@ int pick_variant(const sig::WordSet& ws, int dir, int64_t B, int64_t want = 2048
     return (int)pl.size() - 1;
 }
 
-// kernel timer (see sig_profile_enable)
+// kernel timer (see sig_profile_enable); channels 0/1: main kernel of forward/backward, 2/3: whole call
 struct Profiler {
     bool on = false;
-    std::vector<hipEvent_t> ev[2];    // start/stop interleaved
-    size_t used[2] = {0, 0};
+    std::vector<hipEvent_t> ev[4];    // start/stop interleaved
+    size_t used[4] = {0, 0, 0, 0};
     hipEvent_t* next(int dir)
     {
         if (!on || used[dir] >= SIG_PROFILE_MAX_LAUNCHES) return nullptr;
@@ -59,6 +59,43 @@ struct Profiler {
 };
 Profiler g_prof;
 
+// brackets everything a call enqueues
+struct CallTimer {
+    hipEvent_t* pe;
+    hipStream_t st;
+    CallTimer(int dir, hipStream_t s) : pe(g_prof.next(2 + dir)), st(s) { if (pe) (void)hipEventRecord(pe[0], st); }
+    ~CallTimer() { if (pe) (void)hipEventRecord(pe[1], st); }
+};
+
+// Time chunks for full truncations: with few paths the sequential kernels leave wavefront slots empty, so the
+// segments of every path are cut into C chunks that run as independent rows and are combined afterwards with Chen's
+// relation.  Measured on the three instantiated shapes this pays off for the forward kernels once a chunk is a
+// few hundred segments long (the chunk products and the second launch cost about as much as 100 segments); the
+// backward kernels already fill their register budget with one wavefront per SIMD and would in addition have to
+// recompute the chunk signatures, so they are chunked only on request (SIG_CHUNKS, used by the tests).
+struct Chunks { int64_t C, Lc; };
+Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points)
+{
+    const int64_t L = n_points - 1;
+    int64_t C = 1;
+    if (L >= 64 && sig::chunking_available(w.d, w.depth)) {
+        const char* e = std::getenv("SIG_CHUNKS");                                        // tuning knob
+        if (e && e[0]) {
+            C = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(std::atoi(e), 64), L / 32));
+        } else if (dir == 0) {
+            const int64_t slots = (int64_t)1024 * sig::trunc_occupancy(w.d, w.depth, dir);
+            C = slots / sig::trunc_waves_per_row(w.d, w.depth, dir) / std::max<int64_t>(B, 1);
+            C = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(C, 64), L / 256));
+        }
+    }
+    const int64_t Lc = (L + C - 1) / C;
+    return Chunks{(L + Lc - 1) / Lc, Lc};
+}
+size_t chunk_array_bytes(const sig::WordSet& w, int64_t B, int64_t C)
+{
+    return ((size_t)B * (size_t)C * (size_t)w.size() * sizeof(float) + 255) & ~(size_t)255;
+}
+
 bool use_trunc_forward(const sig::WordSet& w, int64_t B)
 {
     return w.kind == 0 && B <= 65535 && sig::trunc_forward_available(w.d, w.depth);
@@ -72,13 +109,18 @@ bool use_trunc_backward(const sig::WordSet& w, int64_t B)
 // ---- run-time specialised kernels ------------------------------------------------------------------------
 std::mutex g_jit_mutex;
 
-// larger units than the table-driven kernels want: registers hold the coefficients, and fewer units mean less
-// recomputation of shared ancestors and less code to compile; one wavefront per SIMD is enough to start with
-int jit_variant(const sig::WordSet& w, int dir, int64_t B)
+// Work units asked of the balanced planner for a batch of B paths: one wavefront per SIMD (1,024 on the chip)
+// over the path groups, a whole number of workgroups, and not so many that units shrink to a handful of words
+// (every unit recomputes the ancestors of its first word).
+constexpr int kJitWaves = 4;           // wavefronts (units) per workgroup
+int64_t jit_units(const sig::WordSet& w, int /*dir*/, int64_t B)
 {
     int64_t want = 1024;
     if (const char* e = std::getenv("SIG_JIT_WAVES")) want = std::max(1, std::atoi(e));   // tuning knob
-    return pick_variant(w, dir, B, want);
+    const int64_t groups = (B + 63) / 64;
+    int64_t n = std::max<int64_t>(1, want / groups);
+    n = std::min(n, std::max<int64_t>(1, w.size() / 8));
+    return (n + kJitWaves - 1) / kJitWaves * kJitWaves;
 }
 
 // segments per LDS tile; backward also keeps four gradient tiles [T][d][65] in the 64 KB of static LDS
@@ -88,38 +130,58 @@ bool jit_enabled(const sig::WordSet& w)
 {
     const char* off = std::getenv("SIG_NO_JIT");
     if (off && off[0] && off[0] != '0') return false;
-    return w.kernels_supported && !w.plans[0].empty() && jit_tile_steps(w.d, 1) >= 1;
+    return w.kernels_supported && w.size() > 0 && jit_tile_steps(w.d, 1) >= 1;
 }
 
-// Source of the specialised kernel for (direction, variant); fills nw / tile.
-std::string jit_source(const sig::WordSet& w, int dir, int v, int& nw, int& tile)
+// The balanced plan (and kernel slot) for (direction, batch size); created on first use.  Registers bound the unit
+// size: a forward unit keeps one value per word, a backward unit two, next to the Horner intermediates.
+sig::WordSet::JitEntry* jit_entry(const sig::WordSet& cw, int dir, int64_t B)
 {
-    const sig::Plan& p = w.plans[dir][(size_t)v];
-    // Four wavefronts per workgroup = one per SIMD, so a workgroup's registers fit whatever a unit needs (up to 256
-    // VGPRs).  (A 512-thread workgroup of a 248-VGPR kernel was refused at dispatch on gfx950.)
-    int max_nw = 4;
-    if (const char* e = std::getenv("SIG_JIT_NW")) max_nw = std::max(1, std::min(4, std::atoi(e)));   // tuning knob
-    nw = (int)std::min<size_t>((size_t)max_nw, std::max<size_t>(1, p.units.size()));
+    sig::WordSet& w = const_cast<sig::WordSet&>(cw);     // the cache is logically mutable
+    const int64_t n_units = jit_units(w, dir, B);
+    std::lock_guard<std::mutex> lock(g_jit_mutex);
+    for (auto* e : w.jit[dir])
+        if (e->n_units == n_units) return e;
+    auto* e = new (std::nothrow) sig::WordSet::JitEntry;
+    if (!e) return nullptr;
+    try {
+        e->n_units = n_units;
+        if (dir == 0) sig::build_plan_balanced(w, n_units, 320, false, 1, 1, e->plan);
+        else sig::build_plan_balanced(w, n_units, 160, true, 6, 9, e->plan);
+        w.jit[dir].push_back(e);
+    } catch (const std::bad_alloc&) {
+        delete e;
+        return nullptr;
+    }
+    return e;
+}
+
+// Source of the specialised kernel of an entry; fills nw / tile.
+std::string jit_source(const sig::WordSet& w, int dir, const sig::Plan& p, int& nw, int& tile)
+{
+    // Four wavefronts per workgroup = one per SIMD, so a workgroup's registers fit whatever a unit needs.  (A
+    // 512-thread workgroup of a 248-VGPR kernel was refused at dispatch on gfx950.)
+    nw = (int)std::min<size_t>((size_t)kJitWaves, std::max<size_t>(1, p.units.size()));
     tile = jit_tile_steps(w.d, dir);
     return dir ? sig::jit_backward_source(w, p, nw, tile) : sig::jit_forward_source(w, p, nw, tile);
 }
 
-// Compiled (and, if load is set, loaded) kernel for (direction, variant), or nullptr if specialisation is off or
-// failed.  Compilation happens once; the outcome is remembered.
-sig::JitKernel* ensure_jit(const sig::WordSet& cw, int dir, int v, bool load)
+// Compiled (and, if load is set, loaded) kernel for (direction, batch size), or nullptr if specialisation is off or
+// failed.  Compilation happens once per entry; the outcome is remembered.  *plan receives the entry's plan.
+sig::JitKernel* ensure_jit(const sig::WordSet& cw, int dir, int64_t B, bool load, const sig::Plan** plan = nullptr)
 {
     if (!jit_enabled(cw)) return nullptr;
-    sig::WordSet& w = const_cast<sig::WordSet&>(cw);     // the cache is logically mutable
+    sig::WordSet::JitEntry* e = jit_entry(cw, dir, B);
+    if (!e) return nullptr;
+    if (plan) *plan = &e->plan;
     std::lock_guard<std::mutex> lock(g_jit_mutex);
-    auto& vec = w.jit[dir];
-    if (vec.size() < w.plans[dir].size()) vec.resize(w.plans[dir].size(), nullptr);
-    if (!vec[(size_t)v]) vec[(size_t)v] = new (std::nothrow) sig::JitKernel;
-    sig::JitKernel* k = vec[(size_t)v];
+    if (!e->kernel) e->kernel = new (std::nothrow) sig::JitKernel;
+    sig::JitKernel* k = e->kernel;
     if (!k) return nullptr;
     if (!k->tried) {
         k->tried = true;
         try {
-            const std::string src = jit_source(w, dir, v, k->nw, k->tile);
+            const std::string src = jit_source(cw, dir, e->plan, k->nw, k->tile);
             (void)sig::jit_compile(src, dir ? "sig_bwd_jit" : "sig_fwd_jit", *k);
         } catch (const std::bad_alloc&) { k->ok = false; }
     }
@@ -146,13 +208,10 @@ size_t jit_dxt_bytes(const sig::WordSet& w, int64_t B, int64_t n_points, int dir
 // workgroup columns of the specialised backward kernel (each writes its own gradient slice)
 int jit_bwd_columns(const sig::WordSet& w, int64_t B)
 {
-    const sig::Plan& p = w.plans[1][(size_t)jit_variant(w, 1, B)];
-    int nw = 0, tile = 0;
-    (void)tile;
-    int max_nw = 4;
-    if (const char* e = std::getenv("SIG_JIT_NW")) max_nw = std::max(1, std::min(4, std::atoi(e)));
-    nw = (int)std::min<size_t>((size_t)max_nw, std::max<size_t>(1, p.units.size()));
-    return (int)((p.units.size() + (size_t)nw - 1) / (size_t)nw);
+    sig::WordSet::JitEntry* e = jit_entry(w, 1, B);
+    if (!e) return 1;
+    const size_t nw = std::min<size_t>((size_t)kJitWaves, std::max<size_t>(1, e->plan.units.size()));
+    return (int)((e->plan.units.size() + nw - 1) / nw);
 }
 
 hipError_t launch_jit_forward(sig::JitKernel& k, const sig::Plan& p, const float* dxT, int64_t B, int64_t ntiles, float* coeffs,
@@ -255,6 +314,26 @@ int sig_wordset_plan_get(const sig_wordset* ws, int backward, int variant, const
     return SIG_OK;
 }
 
+int sig_wordset_jit_plan_get(sig_wordset* ws, int backward, int64_t B, const int32_t** units, int64_t* n_units,
+                             const uint32_t** ops, int64_t* n_ops, const int32_t** slot_word, int64_t* n_slots,
+                             int64_t* fma_per_step)
+{
+    if (!ws || B < 1) return SIG_EINVAL;
+    const sig::WordSet& w = *W(ws);
+    if (!w.kernels_supported || w.size() == 0) return SIG_EUNSUPPORTED;
+    sig::WordSet::JitEntry* e = jit_entry(w, backward ? 1 : 0, B);
+    if (!e) return SIG_ENOMEM;
+    const sig::Plan& p = e->plan;
+    if (units) *units = reinterpret_cast<const int32_t*>(p.units.data());
+    if (n_units) *n_units = (int64_t)p.units.size();
+    if (ops) *ops = p.ops.data();
+    if (n_ops) *n_ops = (int64_t)p.ops.size();
+    if (slot_word) *slot_word = p.slot_word.data();
+    if (n_slots) *n_slots = (int64_t)p.slot_word.size();
+    if (fma_per_step) *fma_per_step = p.fma_per_step;
+    return SIG_OK;
+}
+
 int sig_wordset_jit_prepare(sig_wordset* ws, int backward, int64_t B)
 {
     if (!ws || B < 1) return SIG_EINVAL;
@@ -262,7 +341,7 @@ int sig_wordset_jit_prepare(sig_wordset* ws, int backward, int64_t B)
     const int dir = backward ? 1 : 0;
     if (!jit_enabled(w)) return SIG_EUNSUPPORTED;
     if (dir == 0 ? use_trunc_forward(w, B) : use_trunc_backward(w, B)) return SIG_EUNSUPPORTED;
-    return ensure_jit(w, dir, jit_variant(w, dir, B), false) ? SIG_OK : SIG_EJIT;
+    return ensure_jit(w, dir, B, false) ? SIG_OK : SIG_EJIT;
 }
 
 size_t sig_wordset_jit_source(sig_wordset* ws, int backward, int64_t B, char* buf, size_t n)
@@ -270,9 +349,11 @@ size_t sig_wordset_jit_source(sig_wordset* ws, int backward, int64_t B, char* bu
     if (!ws || B < 1) return 0;
     const sig::WordSet& w = *W(ws);
     const int dir = backward ? 1 : 0;
-    if (!w.kernels_supported || w.plans[dir].empty()) return 0;
+    if (!jit_enabled(w)) return 0;
+    sig::WordSet::JitEntry* e = jit_entry(w, dir, B);
+    if (!e) return 0;
     int nw = 0, tile = 0;
-    const std::string src = jit_source(w, dir, jit_variant(w, dir, B), nw, tile);
+    const std::string src = jit_source(w, dir, e->plan, nw, tile);
     if (buf && n > 0) {
         const size_t c = std::min(n - 1, src.size());
         std::memcpy(buf, src.data(), c);
@@ -298,7 +379,11 @@ size_t sig_forward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_p
 {
     if (!ws || B <= 0 || n_points <= 1) return 0;
     const sig::WordSet& w = *W(ws);
-    if (use_trunc_forward(w, B) || !jit_enabled(w)) return 0;
+    if (use_trunc_forward(w, B)) {
+        const Chunks ch = trunc_chunks(w, 0, B, n_points);
+        return ch.C > 1 ? 2 * chunk_array_bytes(w, B, ch.C) : 0;      // chunk signatures + partial products
+    }
+    if (!jit_enabled(w)) return 0;
     return jit_dxt_bytes(w, B, n_points, 0);
 }
 
@@ -308,8 +393,12 @@ size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_
     const sig::WordSet& w = *W(ws);
     size_t n = (size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float);
     n = (n + 255) & ~(size_t)255;                                   // gradient with respect to the increments
-    if (!use_trunc_backward(w, B) && jit_enabled(w))                // one gradient slice per workgroup column + increments
+    if (use_trunc_backward(w, B)) {
+        const Chunks ch = trunc_chunks(w, 1, B, n_points);
+        if (ch.C > 1) n += 4 * chunk_array_bytes(w, B, ch.C);       // chunk signatures, prefixes, suffixes, adjoints
+    } else if (jit_enabled(w)) {                                    // one gradient slice per workgroup column + increments
         n = n * (size_t)jit_bwd_columns(w, B) + jit_dxt_bytes(w, B, n_points, 1);
+    }
     return n;
 }
 
@@ -337,15 +426,28 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
         hipError_t e = sig::fill_zero(coeffs, B * w.size(), st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
+    CallTimer whole(0, st);
     if (use_trunc_forward(w, B)) {
+        const Chunks ch = trunc_chunks(w, 0, B, n_points);
+        float* Sc = coeffs;
+        float* Pfx = nullptr;
+        if (ch.C > 1) {
+            const size_t nb = chunk_array_bytes(w, B, ch.C);
+            if (!workspace || workspace_bytes < 2 * nb) return SIG_EWORKSPACE;
+            if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)coeffs & 15) != 0) return SIG_EINVAL;
+            Sc = (float*)workspace;
+            Pfx = (float*)((unsigned char*)workspace + nb);
+        }
         hipEvent_t* pe = g_prof.next(0);
         if (pe) (void)hipEventRecord(pe[0], st);
-        hipError_t e = sig::trunc_forward(w.d, w.depth, path, B, n_points, coeffs, st);
+        hipError_t e = sig::trunc_forward(w.d, w.depth, path, B, n_points, ch.C, ch.Lc, Sc, st);
         if (pe) (void)hipEventRecord(pe[1], st);
+        if (e == hipSuccess && ch.C > 1)
+            e = sig::chunk_scan(w.d, w.depth, Sc, Pfx, nullptr, nullptr, coeffs, B, (int)ch.C, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
-    const int vj = jit_variant(w, 0, B);
-    if (sig::JitKernel* jk = ensure_jit(w, 0, vj, true)) {
+    const sig::Plan* jp = nullptr;
+    if (sig::JitKernel* jk = ensure_jit(w, 0, B, true, &jp)) {
         if (!workspace || workspace_bytes < jit_dxt_bytes(w, B, n_points, 0)) return SIG_EWORKSPACE;
         if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
         float* dxT = (float*)workspace;
@@ -354,7 +456,7 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
         if (e != hipSuccess) return hip_fail(e);
         hipEvent_t* pe = g_prof.next(0);
         if (pe) (void)hipEventRecord(pe[0], st);
-        e = launch_jit_forward(*jk, w.plans[0][(size_t)vj], dxT, B, Lpad / jk->tile, coeffs, w.size(), st);
+        e = launch_jit_forward(*jk, *jp, dxT, B, Lpad / jk->tile, coeffs, w.size(), st);
         if (pe) (void)hipEventRecord(pe[1], st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
@@ -394,19 +496,41 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     if (!workspace || workspace_bytes < need) return SIG_EWORKSPACE;
     if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
     float* gdx = (float*)workspace;
+    CallTimer whole(1, st);
     hipError_t e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
     if (e != hipSuccess) return hip_fail(e);
     if (use_trunc_backward(w, B)) {
+        const Chunks ch = trunc_chunks(w, 1, B, n_points);
+        const float* row_coeffs = coeffs;
+        const float* row_grad = grad_coeffs;
+        if (ch.C > 1) {
+            if ((((uintptr_t)coeffs | (uintptr_t)grad_coeffs) & 15) != 0) return SIG_EINVAL;
+            // chunk signatures (recomputed: only the terminal signature was kept), then the signature and the
+            // adjoint at the end of every chunk
+            const size_t gb = ((size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;
+            const size_t nb = chunk_array_bytes(w, B, ch.C);
+            unsigned char* base = (unsigned char*)workspace + gb;
+            float* Sc = (float*)base;
+            float* Pfx = (float*)(base + nb);
+            float* Q = (float*)(base + 2 * nb);
+            float* Abar = (float*)(base + 3 * nb);
+            e = sig::trunc_forward(w.d, w.depth, path, B, n_points, ch.C, ch.Lc, Sc, st);
+            if (e == hipSuccess) e = sig::chunk_scan(w.d, w.depth, Sc, Pfx, Q, coeffs, nullptr, B, (int)ch.C, st);
+            if (e == hipSuccess) e = sig::chunk_adjoint(w.d, w.depth, grad_coeffs, Q, Abar, B, (int)ch.C, st);
+            if (e != hipSuccess) return hip_fail(e);
+            row_coeffs = Pfx;
+            row_grad = Abar;
+        }
         hipEvent_t* pe = g_prof.next(1);
         if (pe) (void)hipEventRecord(pe[0], st);
-        e = sig::trunc_backward(w.d, w.depth, path, coeffs, grad_coeffs, B, n_points, gdx, st);
+        e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
         e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
-    const int vj = jit_variant(w, 1, B);
-    if (sig::JitKernel* jk = ensure_jit(w, 1, vj, true)) {
+    const sig::Plan* jp = nullptr;
+    if (sig::JitKernel* jk = ensure_jit(w, 1, B, true, &jp)) {
         const int ncol = jit_bwd_columns(w, B);
         const size_t gdx_bytes = ((size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;
         float* dxT = (float*)((unsigned char*)workspace + gdx_bytes * (size_t)ncol);
@@ -415,7 +539,7 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
         if (e != hipSuccess) return hip_fail(e);
         hipEvent_t* pe = g_prof.next(1);
         if (pe) (void)hipEventRecord(pe[0], st);
-        e = launch_jit_backward(*jk, w.plans[1][(size_t)vj], dxT, coeffs, grad_coeffs, B, n_points - 1, Lpad / jk->tile, w.size(),
+        e = launch_jit_backward(*jk, *jp, dxT, coeffs, grad_coeffs, B, n_points - 1, Lpad / jk->tile, w.size(),
                                 gdx, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
@@ -447,13 +571,14 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
 int sig_profile_enable(int on)
 {
     g_prof.on = on != 0;
-    g_prof.used[0] = g_prof.used[1] = 0;
+    for (size_t& u : g_prof.used) u = 0;
     return SIG_OK;
 }
 
-int sig_profile_read(int backward, int64_t* n_launches, double* total_ms)
+int sig_profile_read(int which, int64_t* n_launches, double* total_ms)
 {
-    const int dir = backward ? 1 : 0;
+    if (which < 0 || which > 3) return SIG_EINVAL;
+    const int dir = which;
     double sum = 0.0;
     for (size_t k = 0; k < g_prof.used[dir]; ++k) {
         hipError_t e = hipEventSynchronize(g_prof.ev[dir][2 * k + 1]);

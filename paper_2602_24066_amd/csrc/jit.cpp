@@ -378,11 +378,13 @@ hipError_t jit_load(JitKernel& k)
 WordSet::~WordSet()
 {
     for (int dir = 0; dir < 2; ++dir)
-        for (JitKernel* k : jit[dir])
-            if (k) {
-                jit_release(*k);
-                delete k;
+        for (JitEntry* e : jit[dir]) {
+            if (e->kernel) {
+                jit_release(*e->kernel);
+                delete e->kernel;
             }
+            delete e;
+        }
 }
 
 void jit_release(JitKernel& k)

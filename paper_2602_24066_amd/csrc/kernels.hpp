@@ -36,8 +36,24 @@ hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* gra
 // Register-resident kernels for full truncations (kernels_trunc.hip)
 bool trunc_forward_available(int d, int depth);
 bool trunc_backward_available(int d, int depth);
+int trunc_occupancy(int d, int depth, int backward);        // workgroups (of four wavefronts) resident per compute unit
+int trunc_waves_per_row(int d, int depth, int backward);    // wavefronts per (path, chunk) row
+// A path may be cut into C chunks of Lc segments (the last one shorter); every (path, chunk) pair is a row of its
+// own in coeffs / grad_coeffs ([B * C, |W|]).  C = 1, Lc = P - 1 treats whole paths.
+hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t P, int64_t C, int64_t Lc, float* coeffs,
+                         hipStream_t stream);
 hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
-                          int64_t P, float* gdx, hipStream_t stream);
-hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t P, float* coeffs, hipStream_t stream);
+                          int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream);
+
+// Time chunks (kernels_chunk.hip): products of chunk signatures and adjoints at chunk boundaries, d a power of two
+bool chunking_available(int d, int depth);
+// forward: Q = terminal = nullptr, coeffs_out [B, |W|] receives the product of the C chunk signatures Sc [B, C, |W|];
+// backward: coeffs_out = nullptr, Pfx [B, C, |W|] receives the signatures up to the end of every chunk (the last one
+// is copied from terminal [B, |W|]) and Q [B, C, |W|] the signatures of the rest of the path after every chunk.
+hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, const float* terminal, float* coeffs_out,
+                      int64_t B, int C, hipStream_t stream);
+// Abar [B, C, |W|]: adjoint of the signature at the end of every chunk, from grad [B, |W|] and Q
+hipError_t chunk_adjoint(int d, int depth, const float* grad, const float* Q, float* Abar, int64_t B, int C,
+                         hipStream_t stream);
 
 }  // namespace sig

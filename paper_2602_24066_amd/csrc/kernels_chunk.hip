@@ -1,0 +1,277 @@
+// Time chunks for full truncations.
+//
+// Chen's relation (Section 3, eq. 2) is associative, so a path may be cut into C consecutive chunks whose
+// signatures S_1 .. S_C are computed independently (C times as many wavefronts for the sequential kernels) and
+// multiplied afterwards:  S_{0,T} = S_1 (x) S_2 (x) .. (x) S_C,  where in the word basis
+//     (a (x) b)(w) = sum_{k=0..n} a(w_1..w_k) b(w_{k+1}..w_n),   a(empty) = b(empty) = 1        (Section 2.1).
+// The backward pass of chunk c needs the signature up to the end of the chunk, P_c = S_1 (x) .. (x) S_c, and the
+// adjoint there, Abar_c(u) = sum_v grad(u v) Q_c(v) with Q_c = S_{c+1} (x) .. (x) S_C the signature of the rest
+// of the path (Proposition 4.1 with the right factor taken at a chunk boundary).
+//
+// All arrays are [B][C][W] floats (W = d + d^2 + .. + d^N coefficients, levels concatenated, each row-major);
+// d is a power of two so that prefixes and suffixes of a word index are shifts and masks.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "kernels.hpp"
+
+namespace sig {
+namespace {
+
+struct Levels {
+    int N;            // depth
+    int lb;           // log2(d), >= 2
+    int W;            // coefficients (a multiple of 4)
+    int ls[14];       // ls[n] = index of the first word of length n, n = 1..N (multiples of 4); ls[N + 1] = W
+};
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// Four consecutive coefficients (word length n, indices i .. i + 3 inside the level, i a multiple of 4) of a (x) b.
+// The four words differ in their last letter only, so every prefix is shared and the suffixes are contiguous.
+__device__ __forceinline__ f4 quad_product(const float* a, const float* b, const Levels& g, int n, int i)
+{
+    f4 acc = *(const f4*)(a + g.ls[n] + i) + *(const f4*)(b + g.ls[n] + i);
+    for (int k = 1; k < n; ++k) {
+        const int sh = g.lb * (n - k);
+        const float av = a[g.ls[k] + (i >> sh)];
+        const f4 bv = *(const f4*)(b + g.ls[n - k] + (i & ((1 << sh) - 1)));
+        acc += av * bv;
+    }
+    return acc;
+}
+
+// out = a (x) b by the whole workgroup; out2 (may be null) receives a second copy.  Level by level, so that the
+// level offsets and shifts are uniform.
+__device__ __forceinline__ void tensor_product(const float* a, const float* b, float* out, float* out2, const Levels& g)
+{
+    for (int n = 1; n <= g.N; ++n) {
+        const int quads = (g.ls[n + 1] - g.ls[n]) >> 2;
+        for (int qd = threadIdx.x; qd < quads; qd += blockDim.x) {
+            const f4 r = quad_product(a, b, g, n, 4 * qd);
+            *(f4*)(out + g.ls[n] + 4 * qd) = r;
+            if (out2) *(f4*)(out2 + g.ls[n] + 4 * qd) = r;
+        }
+    }
+}
+
+__device__ __forceinline__ void copy_row(const float* src, float* dst, float* dst2, int W)
+{
+    for (int o = 4 * threadIdx.x; o < W; o += 4 * blockDim.x) {
+        const f4 v = *(const f4*)(src + o);
+        *(f4*)(dst + o) = v;
+        if (dst2) *(f4*)(dst2 + o) = v;
+    }
+}
+
+// One workgroup per path.  Forward (Q == nullptr): coeffs_out[b] = S_1 (x) .. (x) S_C.  Backward: Pfx[c] =
+// S_1 (x) .. (x) S_c for c < C and Pfx[C] = terminal[b] (the signature the caller kept), Q[c] = S_{c+1} (x) .. (x) S_C
+// for c < C.  With LDS the running product and the next factor are staged in three rotating LDS buffers of W floats
+// (small signatures); without, the operands are read from the global arrays written in earlier steps, which
+// __syncthreads() makes visible inside the workgroup.
+template <bool LDS>
+__global__ __launch_bounds__(1024) void chunk_scan_kernel(const float* __restrict__ Sc, float* Pfx, float* Q,
+                                                          const float* __restrict__ terminal, float* coeffs_out, int C,
+                                                          Levels g)
+{
+    extern __shared__ f4 smem4[];
+    float* sm = (float*)smem4;
+    const int64_t b = blockIdx.x;
+    const int64_t W = g.W;
+    const float* S = Sc + b * C * W;
+    float* P = Pfx + b * C * W;
+    const bool bwd = Q != nullptr;
+    float* Qb = bwd ? Q + b * C * W : nullptr;
+    if constexpr (LDS) {
+        float* buf[3] = {sm, sm + W, sm + 2 * W};
+        // prefix products
+        copy_row(S, buf[0], bwd ? P : nullptr, (int)W);
+        const int lastp = bwd ? C - 2 : C - 1;
+        int cur = 0;
+        for (int s = 1; s <= lastp; ++s) {
+            const int nb = (cur + 1) % 3, no = (cur + 2) % 3;
+            copy_row(S + (int64_t)s * W, buf[nb], nullptr, (int)W);
+            __syncthreads();
+            float* dst = (!bwd && s == C - 1) ? coeffs_out + b * W : (bwd ? P + (int64_t)s * W : nullptr);
+            tensor_product(buf[cur], buf[nb], buf[no], dst, g);
+            cur = no;
+            __syncthreads();
+        }
+        if (bwd) {
+            copy_row(terminal + b * W, P + (int64_t)(C - 1) * W, nullptr, (int)W);
+            // suffix products
+            __syncthreads();
+            copy_row(S + (int64_t)(C - 1) * W, buf[0], Qb + (int64_t)(C - 2) * W, (int)W);
+            cur = 0;
+            for (int q = C - 3; q >= 0; --q) {
+                const int nb = (cur + 1) % 3, no = (cur + 2) % 3;
+                copy_row(S + (int64_t)(q + 1) * W, buf[nb], nullptr, (int)W);
+                __syncthreads();
+                tensor_product(buf[nb], buf[cur], buf[no], Qb + (int64_t)q * W, g);
+                cur = no;
+                __syncthreads();
+            }
+        }
+    } else {
+        copy_row(S, P, nullptr, (int)W);
+        if (bwd) {
+            copy_row(terminal + b * W, P + (int64_t)(C - 1) * W, nullptr, (int)W);
+            copy_row(S + (int64_t)(C - 1) * W, Qb + (int64_t)(C - 2) * W, nullptr, (int)W);
+        }
+        const int last = bwd ? C - 2 : C - 1;
+        for (int s = 1; s <= last; ++s) {
+            __syncthreads();
+            float* dst = (!bwd && s == C - 1) ? coeffs_out + b * W : P + (int64_t)s * W;
+            tensor_product(P + (int64_t)(s - 1) * W, S + (int64_t)s * W, dst, nullptr, g);
+            if (bwd) {
+                const int q = C - 2 - s;              // >= 0 because s <= C - 2
+                tensor_product(S + (int64_t)(q + 1) * W, Qb + (int64_t)(q + 1) * W, Qb + (int64_t)q * W, nullptr, g);
+            }
+        }
+    }
+}
+
+// out[b] = a[b] (x) bfac[b] for every path, spread over the whole grid: blockIdx.y = path, blockIdx.x covers the
+// quads of all levels.  Row strides are given in floats.
+__global__ __launch_bounds__(256) void chunk_product_kernel(const float* __restrict__ a, int64_t a_stride,
+                                                            const float* __restrict__ bfac, int64_t b_stride,
+                                                            float* __restrict__ out, int64_t out_stride, Levels g)
+{
+    const int64_t b = blockIdx.y;
+    const int o = 4 * (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (o >= g.W) return;
+    int n = 1;
+    while (o >= g.ls[n + 1]) ++n;
+    *(f4*)(out + b * out_stride + o) = quad_product(a + b * a_stride, bfac + b * b_stride, g, n, o - g.ls[n]);
+}
+
+// One workgroup per (path, chunk): Abar[b][c](u) = grad[b](u) + sum_{m >= 1} sum_{|v| = m} grad[b](u v) Q[b][c](v);
+// the last chunk's adjoint is grad itself.  The words of one length k are spread over the whole workgroup, with
+// blockDim / d^k threads (at most 64, at least 1) sharing the inner sums of a word; for a fixed m the terms of a
+// word are contiguous in grad and in Q.
+template <bool LDS>
+__global__ __launch_bounds__(512) void chunk_adjoint_kernel(const float* __restrict__ grad, const float* __restrict__ Q,
+                                                            float* __restrict__ Abar, int C, Levels g)
+{
+    extern __shared__ f4 smem4[];
+    float* sm = (float*)smem4;
+    const int64_t row = blockIdx.x;
+    const int64_t b = row / C;
+    const int c = (int)(row - b * C);
+    const int W = g.W;
+    const float* gr = grad + b * W;
+    float* out = Abar + row * W;
+    if (c == C - 1) {
+        copy_row(gr, out, nullptr, W);
+        return;
+    }
+    const float* q = Q + row * W;
+    if constexpr (LDS) {
+        copy_row(gr, sm, nullptr, W);
+        copy_row(q, sm + W, nullptr, W);
+        __syncthreads();
+        gr = sm;
+        q = sm + W;
+    }
+    const int N = g.N;
+    copy_row(gr + g.ls[N], out + g.ls[N], nullptr, W - g.ls[N]);       // words of length N
+    for (int k = 1; k < N; ++k) {
+        const int nk = g.ls[k + 1] - g.ls[k];                           // words of length k
+        int tpw = (int)blockDim.x / nk;                                 // threads per word (power of two)
+        tpw = tpw > 64 ? 64 : (tpw < 1 ? 1 : tpw);
+        const int wpp = (int)blockDim.x / tpw;                          // words per pass
+        const int t = threadIdx.x % tpw;
+        for (int i0 = 0; i0 < nk; i0 += wpp) {
+            const int i = i0 + threadIdx.x / tpw;
+            float acc = 0.0f;
+            if (i < nk)
+                for (int m = 1; m <= N - k; ++m) {
+                    const int cnt = 1 << (g.lb * m);
+                    const float* src = gr + g.ls[k + m] + (i << (g.lb * m));
+                    const float* qv = q + g.ls[m];
+                    for (int v = t; v < cnt; v += tpw) acc = fmaf(src[v], qv[v], acc);
+                }
+            for (int off = tpw >> 1; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+            if (i < nk && t == 0) out[g.ls[k] + i] = gr[g.ls[k] + i] + acc;
+        }
+    }
+}
+
+constexpr size_t kMaxChunkLds = 96 * 1024;       // three signatures of up to 8,192 coefficients
+
+bool make_levels(int d, int depth, Levels& g)
+{
+    if (d < 4 || (d & (d - 1)) != 0 || depth < 2 || depth > 12) return false;
+    g.N = depth;
+    g.lb = 0;
+    while ((1 << g.lb) < d) ++g.lb;
+    if (g.lb * depth > 30) return false;
+    int64_t off = 0;
+    g.ls[0] = 0;
+    for (int n = 1; n <= depth; ++n) {
+        g.ls[n] = (int)off;
+        off += (int64_t)1 << (g.lb * n);
+    }
+    if (off > 0x7fffffff) return false;
+    g.ls[depth + 1] = (int)off;
+    g.W = (int)off;
+    return true;
+}
+
+}  // namespace
+
+bool chunking_available(int d, int depth)
+{
+    Levels g;
+    return make_levels(d, depth, g);
+}
+
+hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, const float* terminal, float* coeffs_out,
+                      int64_t B, int C, hipStream_t stream)
+{
+    Levels g;
+    if (!make_levels(d, depth, g) || C < 2 || B < 1 || B > 0x7fffffff) return hipErrorInvalidValue;
+    if ((Q != nullptr) != (terminal != nullptr) || (Q == nullptr) == (coeffs_out == nullptr)) return hipErrorInvalidValue;
+    const size_t lds = 3 * (size_t)g.W * sizeof(float);
+    if (lds <= kMaxChunkLds) {
+        static bool attr_set = false;            // raising the dynamic LDS limit is needed once per process
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunk_scan_kernel<true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxChunkLds);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        chunk_scan_kernel<true><<<(unsigned)B, 1024, lds, stream>>>(Sc, Pfx, Q, terminal, coeffs_out, C, g);
+    } else if (Q == nullptr && B <= 65535) {
+        // forward with large signatures: one grid-wide product per chunk boundary
+        const int64_t W = g.W;
+        const dim3 grid((unsigned)((W / 4 + 255) / 256), (unsigned)B);
+        const float* acc = Sc;                       // S_1 of every path, row stride C W
+        int64_t acc_stride = (int64_t)C * W;
+        for (int s = 1; s < C; ++s) {
+            float* dst = s == C - 1 ? coeffs_out : Pfx + (int64_t)s * W;
+            const int64_t dst_stride = s == C - 1 ? W : (int64_t)C * W;
+            chunk_product_kernel<<<grid, 256, 0, stream>>>(acc, acc_stride, Sc + (int64_t)s * W, (int64_t)C * W, dst,
+                                                           dst_stride, g);
+            acc = dst;
+            acc_stride = dst_stride;
+        }
+    } else {
+        chunk_scan_kernel<false><<<(unsigned)B, 1024, 0, stream>>>(Sc, Pfx, Q, terminal, coeffs_out, C, g);
+    }
+    return hipGetLastError();
+}
+
+hipError_t chunk_adjoint(int d, int depth, const float* grad, const float* Q, float* Abar, int64_t B, int C,
+                         hipStream_t stream)
+{
+    Levels g;
+    if (!make_levels(d, depth, g) || C < 2 || B < 1 || B * C > 0x7fffffff) return hipErrorInvalidValue;
+    const size_t lds = 2 * (size_t)g.W * sizeof(float);
+    if (lds <= 64 * 1024) chunk_adjoint_kernel<true><<<(unsigned)(B * C), 512, lds, stream>>>(grad, Q, Abar, C, g);
+    else chunk_adjoint_kernel<false><<<(unsigned)(B * C), 512, 0, stream>>>(grad, Q, Abar, C, g);
+    return hipGetLastError();
+}
+
+}  // namespace sig

@@ -238,7 +238,7 @@ __device__ __forceinline__ void wave_lds_fence()
 
 template <int D, int N, int K, int WQ, int T>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_fwd_kernel(const float* __restrict__ path,
-                                                                                int64_t B, int64_t P,
+                                                                                int64_t B, int64_t P, int64_t C, int64_t Lc,
                                                                                 float* __restrict__ coeffs)
 {
     using G = MGeo<D, N, K, WQ>;
@@ -258,10 +258,14 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_fwd_kernel(
     const int lane = threadIdx.x % kWave;
     const int wib = threadIdx.x / kWave;
     const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
-    if (wave >= B * G::WAVES) return;                     // no barriers below: a whole wavefront may leave
+    if (wave >= B * C * G::WAVES) return;                 // no barriers below: a whole wavefront may leave
     float (*E)[N][D] = E_all[wib];
     float (*Ec)[D][NC] = Ec_all[wib];
-    const int64_t b = wave / G::WAVES;
+    // row = (path, chunk): chunk c of a path covers its segments [c Lc, min((c + 1) Lc, P - 1)) and is treated as
+    // a path of its own whose signature goes to row `row` of coeffs (C = 1: the whole path)
+    const int64_t row = wave / G::WAVES;
+    const int64_t b = row / C;
+    const int64_t seg0 = (row - b * C) * Lc;
     const int wip = (int)(wave % G::WAVES);               // wavefront inside the path
     const int slice = wip % G::NSL;
     const int p = (wip / G::NSL) * kWave + lane;          // this lane's prefix (base-D number of K letters)
@@ -272,8 +276,8 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_fwd_kernel(
         for (int k = K - 1; k >= 0; --k) { letter[k] = q % D; q /= D; }
     }
     const int g0 = slice * WQ;
-    const float* X = path + b * P * D;
-    const int64_t L = P - 1;
+    const float* X = path + (b * P + seg0) * D;
+    const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
 
     // per-lane offsets (in floats, inside one row of E) of the matrix-core B operands: register r serves the
     // combinations 4r..4r+3, one per group of 16 lanes
@@ -425,7 +429,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_fwd_kernel(
         wave_lds_fence();
     }
 
-    float* out = coeffs + b * (int64_t)(level_start(D, N) + ipow(D, N));
+    float* out = coeffs + row * (int64_t)(level_start(D, N) + ipow(D, N));
     {
         int phi = 0;
 #pragma unroll
@@ -450,14 +454,15 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_fwd_kernel(
 }
 
 template <int D, int N, int K, int WQ>
-hipError_t launch_trunc_mfma_fwd(const float* path, int64_t B, int64_t P, float* coeffs, hipStream_t stream)
+hipError_t launch_trunc_mfma_fwd(const float* path, int64_t B, int64_t P, int64_t C, int64_t Lc, float* coeffs,
+                                 hipStream_t stream)
 {
     using G = MGeo<D, N, K, WQ>;
     constexpr int T = 16;
-    const int64_t waves = B * G::WAVES;
+    const int64_t waves = B * C * G::WAVES;
     const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    trunc_mfma_fwd_kernel<D, N, K, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, 0, stream>>>(path, B, P, coeffs);
+    trunc_mfma_fwd_kernel<D, N, K, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, 0, stream>>>(path, B, P, C, Lc, coeffs);
     return hipGetLastError();
 }
 
@@ -576,10 +581,32 @@ __device__ __forceinline__ void lds_add(float* p, float v)
     __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
+// LDS of one wavefront of the backward kernel, in floats.  GEMM: the leaf level (adjoints constant in time) is
+// handled by time-batched matrix products over a tile of 16 segments, which need the slice-level values of the
+// tile in LDS (HA).
+template <int D, int N, int WQ, int T>
+struct BwdLds {
+    using G = MGeo<D, N, N - 2, WQ>;
+    static constexpr bool GEMM = G::WIDE;
+    static constexpr int NC = (N + 3) / 4 * 4;
+    static constexpr int NSV = WQ * 4;
+    static constexpr int NSRC = 1 + (G::WIDE ? WQ : G::Q) + (N - 2 - 1);
+    static constexpr int SP = 68;                       // row stride of HA: 64 parents + 4 (keeps 16-byte alignment)
+    static constexpr int OFF_E = 0;
+    static constexpr int OFF_EC = OFF_E + T * 2 * D;
+    static constexpr int OFF_GT = OFF_EC + T * D * NC;
+    static constexpr int OFF_VB = OFF_GT + T * D;
+    static constexpr int OFF_HA = OFF_VB + NSRC * T * kWave;
+    static constexpr int PER_WAVE = OFF_HA + (GEMM ? NSV * T * SP : 0);
+    static_assert(OFF_EC % 4 == 0 && OFF_GT % 4 == 0 && OFF_VB % 4 == 0 && OFF_HA % 4 == 0 && PER_WAVE % 4 == 0,
+                  "16-byte alignment of the LDS regions");
+    static constexpr size_t BYTES = (size_t)kWavesPerBlock * PER_WAVE * sizeof(float);
+};
+
 template <int D, int N, int WQ, int T>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
-    int64_t P, float* gdx)
+    int64_t P, int64_t C, int64_t Lc, float* gdx)
 {
     static_assert((D & (D - 1)) == 0, "the gradient reduction takes letters as bit fields of the lane number");
     constexpr int K = N - 2;
@@ -596,20 +623,28 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     constexpr int NSRC0 = 1 + (WIDE ? WQ : Q);        // sources before the earlier chain letters
     constexpr int NSRC = NSRC0 + (K - 1);
     constexpr int LB = ilog2(D);
-    __shared__ float E_all[kWavesPerBlock][T][2][D];
-    __shared__ __attribute__((aligned(16))) float Ec_all[kWavesPerBlock][T][D][NC];
-    __shared__ float gt_all[kWavesPerBlock][T * D];
-    __shared__ float Vb_all[kWavesPerBlock][NSRC * T * kWave];
+    using LY = BwdLds<D, N, WQ, T>;
+    static_assert(!LY::GEMM || T == 16, "the time-batched leaf products take 16 segments per matrix instruction");
+    extern __shared__ v4f bwd_smem[];
 
     const int lane = threadIdx.x % kWave;
     const int wib = threadIdx.x / kWave;
     const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
-    if (wave >= B * G::WAVES) return;
-    float (*E)[2][D] = E_all[wib];
-    float (*Ec)[D][NC] = Ec_all[wib];
-    float* gt = gt_all[wib];
-    float* Vb = Vb_all[wib];
-    const int64_t b = wave / G::WAVES;
+    if (wave >= B * C * G::WAVES) return;
+    float* const lds = (float*)bwd_smem + wib * LY::PER_WAVE;            // wave-private
+    float (*E)[2][D] = (float (*)[2][D])(lds + LY::OFF_E);
+    float (*Ec)[D][NC] = (float (*)[D][NC])(lds + LY::OFF_EC);
+    float* gt = lds + LY::OFF_GT;
+    float* Vb = lds + LY::OFF_VB;
+    float* HA = lds + LY::OFF_HA;                                       // [NSV][T][SP], GEMM only
+    constexpr bool GEMM = LY::GEMM;
+    constexpr int SP = LY::SP;
+    constexpr int KS = D / 4;
+    // row = (path, chunk): walks the segments [c Lc, min((c + 1) Lc, P - 1)) of path b backwards, starting from
+    // row `row` of coeffs (signature up to the end of the chunk) and of grad (adjoint at the end of the chunk)
+    const int64_t row = wave / G::WAVES;
+    const int64_t b = row / C;
+    const int64_t seg0 = (row - b * C) * Lc;
     const int wip = (int)(wave % G::WAVES);
     const int slice = wip % G::NSL;
     const int p = (wip / G::NSL) * kWave + lane;
@@ -620,11 +655,11 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         for (int k = K - 1; k >= 0; --k) { letter[k] = q % D; q /= D; }
     }
     const int g0 = slice * WQ;
-    const float* X = path + b * P * D;
-    const int64_t L = P - 1;
+    const float* X = path + (b * P + seg0) * D;
+    const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
     const int64_t nW = level_start(D, N) + ipow(D, N);
-    const float* cf = coeffs + b * nW;
-    const float* gr = grad + b * nW;
+    const float* cf = coeffs + row * nW;
+    const float* gr = grad + row * nW;
 
     int offS[NBS], offU[NBU];
 #pragma unroll
@@ -644,7 +679,12 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     v4f S1[WQ], A1[WQ];
     v4f S2[NL4], Ac4[NL4];            // leaves, child layout (4x4x1)
     v16f S2w[NL16], Ac16[NL16];       // leaves, child layout (16x16x1)
-    float An[NSV][D];                 // leaf adjoints, node layout
+    float An[GEMM ? 1 : NSV][D];      // leaf adjoints, node layout
+    // GEMM: leaf adjoints G[v][parent][letter] as A operands of the 16x16x4 matrix instruction (lane l supplies
+    // row l % 16, k = l / 16).  Ga: rows = parents 16 mb + l % 16, k = letters 4 ks + l / 16 (contraction over letters);
+    // Gt: rows = letters l % 16, k = parents 4 ks + l / 16 (contraction over parents).
+    float Ga[GEMM ? NSV : 1][4][KS];
+    float Gt[GEMM ? NSV : 1][16];
     int phi = 0;
 #pragma unroll
     for (int k = 1; k <= K; ++k) {
@@ -661,15 +701,28 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             S1[g][r] = cf[level_start(D, N - 1) + ph];
             A1[g][r] = gr[level_start(D, N - 1) + ph];
             const int v = g * 4 + r;
+            if constexpr (GEMM) {
 #pragma unroll
-            for (int j = 0; j < D; ++j) An[v][j] = gr[level_start(D, N) + ph * D + j];
+                for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        Ga[v][mb][ks] = gr[level_start(D, N) + __shfl(ph, 16 * mb + (lane & 15)) * D + 4 * ks + lane / 16];
+#pragma unroll
+                for (int ks = 0; ks < 16; ++ks) {
+                    const int pw = __shfl(ph, 4 * ks + lane / 16);
+                    Gt[v][ks] = (lane & 15) < D ? gr[level_start(D, N) + pw * D + (lane & 15)] : 0.0f;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < D; ++j) An[v][j] = gr[level_start(D, N) + ph * D + j];
+            }
             if constexpr (WIDE) {
 #pragma unroll
                 for (int rr = 0; rr < 16; ++rr) {
                     const int src = 16 * (rr / 4) + 4 * (lane / 16) + (rr % 4);
                     const int pl = __shfl(ph, src) * D + (lane & 15);
                     S2w[v][rr] = cf[level_start(D, N) + pl];
-                    Ac16[v][rr] = gr[level_start(D, N) + pl];
+                    if constexpr (!GEMM) Ac16[v][rr] = gr[level_start(D, N) + pl];
                 }
             } else {
 #pragma unroll
@@ -716,24 +769,36 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     for (int q = 0; q < 16; ++q) zero16[q] = 0.0f;
     const float one = 1.0f;
 
-    auto step = [&](int row) {
-        const float* Et = &E[row][0][0];
+    // A segment is processed in two phases.  recon: steps 1 and 2 of the list above (they only depend on the
+    // signature); adjoint: step 3 (depends on the adjoints and on what recon left in `Saved`).  The tile loop runs
+    // recon one segment ahead of adjoint, so that the two dependent chains of a lone wavefront overlap.
+    struct Saved {
         float ec[K][NC];
+        float ap[K + 1][N + 2];
+        v4f Gp[WQ];
+        v4f Pb1, Pb2;
+        float b0v[WQ];
+        float dxu[GEMM ? 1 : D];
+    };
+    auto recon = [&](int row, Saved& sv) {
+        const float* Et = &E[row][0][0];
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const float* src = &Ec[row][letter[k]][0];
 #pragma unroll
-            for (int t = 0; t <= N - (k + 1); ++t) ec[k][t] = src[t];
+            for (int t = 0; t <= N - (k + 1); ++t) sv.ec[k][t] = src[t];
         }
-        float bs[NBS], nbs[NBS], bu[NBU], nbu[NBU], b0v[WQ], dxu[D];
+        float bs[NBS], nbs[NBS], bu[NBU], nbu[NBU];
 #pragma unroll
         for (int r = 0; r < NBS; ++r) { bs[r] = Et[offS[r]]; nbs[r] = -bs[r]; }
 #pragma unroll
         for (int r = 0; r < NBU; ++r) { bu[r] = Et[offU[r]]; nbu[r] = -bu[r]; }
 #pragma unroll
-        for (int g = 0; g < WQ; ++g) b0v[g] = Et[4 * (g0 + g) + (lane & 3)];
+        for (int g = 0; g < WQ; ++g) sv.b0v[g] = Et[4 * (g0 + g) + (lane & 3)];
+        if constexpr (!GEMM) {
 #pragma unroll
-        for (int j = 0; j < D; ++j) dxu[j] = Et[j];
+            for (int j = 0; j < D; ++j) sv.dxu[j] = Et[j];
+        }
 
         // 1. reconstruction with -dX
         float am[K + 1][N + 2];
@@ -742,8 +807,8 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
 #pragma unroll
         for (int k = 1; k <= K; ++k) {
 #pragma unroll
-            for (int t = 1; t <= N - k; ++t) am[k][t] = fmaf(-ec[k - 1][t], am[k - 1][t + 1], Sc[k - 1]);
-            Sc[k - 1] = fmaf(-ec[k - 1][0], am[k - 1][1], Sc[k - 1]);
+            for (int t = 1; t <= N - k; ++t) am[k][t] = fmaf(-sv.ec[k - 1][t], am[k - 1][t + 1], Sc[k - 1]);
+            Sc[k - 1] = fmaf(-sv.ec[k - 1][0], am[k - 1][1], Sc[k - 1]);
         }
         v4f Gm[WQ];
 #pragma unroll
@@ -761,20 +826,20 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             }
         }
         // 2. accumulators with +dX from the reconstructed signature
-        float ap[K + 1][N + 2];
 #pragma unroll
-        for (int t = 0; t < N + 2; ++t) ap[0][t] = 1.0f;
+        for (int t = 0; t < N + 2; ++t) sv.ap[0][t] = 1.0f;
 #pragma unroll
         for (int k = 1; k <= K; ++k)
 #pragma unroll
-            for (int t = 1; t <= N - k; ++t) ap[k][t] = fmaf(ec[k - 1][t], ap[k - 1][t + 1], Sc[k - 1]);
-        v4f Gp[WQ];
+            for (int t = 1; t <= N - k; ++t) sv.ap[k][t] = fmaf(sv.ec[k - 1][t], sv.ap[k - 1][t + 1], Sc[k - 1]);
 #pragma unroll
-        for (int g = 0; g < WQ; ++g) Gp[g] = mfma4(ap[K][2], bs[(WQ + g) / 4], S1[g], (WQ + g) % 4);
+        for (int g = 0; g < WQ; ++g) sv.Gp[g] = mfma4(sv.ap[K][2], bs[(WQ + g) / 4], S1[g], (WQ + g) % 4);
         // chain values A+_K[1], A+_K[2]/2 of the parent of every slice word, in the child layout
-        const v4f Pb1 = __builtin_amdgcn_mfma_f32_4x4x1f32(ap[K][1], one, zero4, 0, 0, 0);
-        const v4f Pb2 = __builtin_amdgcn_mfma_f32_4x4x1f32(0.5f * ap[K][2], one, zero4, 0, 0, 0);
+        sv.Pb1 = __builtin_amdgcn_mfma_f32_4x4x1f32(sv.ap[K][1], one, zero4, 0, 0, 0);
+        sv.Pb2 = __builtin_amdgcn_mfma_f32_4x4x1f32(0.5f * sv.ap[K][2], one, zero4, 0, 0, 0);
+    };
 
+    auto adjoint = [&](int row, const Saved& sv) {
         // 3a. leaves
         float gcl[WIDE ? 1 : Q];
 #pragma unroll
@@ -782,10 +847,18 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         v4f g1[WQ];
 #pragma unroll
         for (int v = 0; v < NSV; ++v) {
-            const float a = Gp[v / 4][v % 4];            // A+_{N-1}[1] of the slice word in this lane
+            const float a = sv.Gp[v / 4][v % 4];         // A+_{N-1}[1] of the slice word in this lane
+            if constexpr (GEMM) {
+                // gbar[1] of the slice word was computed for the whole tile before the segment loop; its slot
+                // takes A+ for the product over parents after the loop
+                float* slot = HA + (v * T + row) * SP + lane;
+                g1[v / 4][v % 4] = *slot;
+                *slot = a;
+                continue;
+            }
             float h = 0.0f;
 #pragma unroll
-            for (int j = 0; j < D; ++j) h = fmaf(dxu[j], An[v][j], h);
+            for (int j = 0; j < D; ++j) h = fmaf(sv.dxu[j], An[v][j], h);
             g1[v / 4][v % 4] = h;                        // gbar[1] of the slice word
             if constexpr (WIDE) {
                 const v16f Pb = __builtin_amdgcn_mfma_f32_16x16x1f32(a, one, zero16, 0, 0, 0);
@@ -806,13 +879,13 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
 #pragma unroll
         for (int g = 0; g < WQ; ++g) {
             gcs[g] = 0.0f;
-            const float b1v = 0.5f * b0v[g];
+            const float b1v = 0.5f * sv.b0v[g];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float q0 = A1[g][r], q1 = g1[g][r];
-                gcs[g] = fmaf(q0, Pb1[r], gcs[g]);
-                gcs[g] = fmaf(q1, Pb2[r], gcs[g]);
-                M1[r] = fmaf(b0v[g], q0, M1[r]);
+                gcs[g] = fmaf(q0, sv.Pb1[r], gcs[g]);
+                gcs[g] = fmaf(q1, sv.Pb2[r], gcs[g]);
+                M1[r] = fmaf(sv.b0v[g], q0, M1[r]);
                 M2[r] = fmaf(b1v, q1, M2[r]);
                 A1[g][r] = q0 + q1;
             }
@@ -834,8 +907,8 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             for (int t = 0; t <= N - k; ++t) {
                 const float q = gb[k][t];
                 asum += q;
-                gc = fmaf(q * inv1(t), ap[k - 1][t + 1], gc);
-                gb[k - 1][t + 1] = fmaf(ec[k - 1][t], q, gb[k - 1][t + 1]);
+                gc = fmaf(q * inv1(t), sv.ap[k - 1][t + 1], gc);
+                gb[k - 1][t + 1] = fmaf(sv.ec[k - 1][t], q, gb[k - 1][t + 1]);
             }
             Ac[k - 1] = asum;
             gck[k - 1] = gc;
@@ -873,9 +946,59 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         stage();
         wave_lds_fence();
         fetch((n - 1) * T);                            // n = 0: out of range, zeros
+        if constexpr (GEMM) {
+            // gbar[1](slice word p, segment s) = sum_j dX_s^{(j)} G[p][j] for the 16 segments of the tile:
+            // [64 parents x D letters] . [D letters x 16 segments] per slice vector; the result (row = parent
+            // 4 (l / 16) + r of block mb, column = segment l % 16) goes to HA[v][segment][parent]
+            float Bx[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) Bx[ks] = E[lane & 15][0][4 * ks + lane / 16];
+#pragma unroll
+            for (int v = 0; v < NSV; ++v)
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) {
+                    v4f acc = zero4;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Ga[v][mb][ks], Bx[ks], acc, 0, 0, 0);
+                    *(v4f*)(HA + (v * T + (lane & 15)) * SP + 16 * mb + 4 * (lane / 16)) = acc;
+                }
+            wave_lds_fence();
+        }
+        {
+            static_assert(T % 2 == 0, "the segment loop is unrolled by two");
+            Saved SA, SB;
+            recon(T - 1, SA);
 #pragma unroll 1
-        for (int tt = T - 1; tt >= 0; --tt) step(tt);
+            for (int tt = T - 1; tt >= 3; tt -= 2) {
+                recon(tt - 1, SB);
+                adjoint(tt, SA);
+                recon(tt - 2, SA);
+                adjoint(tt - 1, SB);
+            }
+            recon(0, SB);
+            adjoint(1, SA);
+            adjoint(0, SB);
+        }
         wave_lds_fence();
+        if constexpr (GEMM) {
+            // dLoss/d dX_s^{(j)} += sum_p G[p][j] A+(p, s): [D letters x 64 parents] . [64 parents x 16 segments] per
+            // slice vector; row = letter 4 (l / 16) + r, column = segment l % 16
+            v4f acc[4] = {zero4, zero4, zero4, zero4};
+#pragma unroll
+            for (int v = 0; v < NSV; ++v)
+#pragma unroll
+                for (int ks = 0; ks < 16; ++ks) {
+                    const float bv = HA[(v * T + (lane & 15)) * SP + 4 * ks + lane / 16];
+                    acc[ks % 4] = __builtin_amdgcn_mfma_f32_16x16x4f32(Gt[v][ks], bv, acc[ks % 4], 0, 0, 0);
+                }
+            const v4f sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+            if (4 * (lane / 16) < D) {
+                v4f* dst = (v4f*)(gt + (lane & 15) * D + 4 * (lane / 16));
+                *dst = *dst + sum;
+            }
+            wave_lds_fence();
+        }
         tile_reduce<(1 << LB) - 1, T>(Vb, gt, D, lane, letter[K - 1]);
         if constexpr (!WIDE) {
 #pragma unroll
@@ -889,7 +1012,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         // flush: (segment, letter) is contiguous in gdx
         for (int e = lane; e < T * D; e += kWave) {
             const int64_t s = n * T + e / D;
-            if (s < L) unsafeAtomicAdd(gdx + (b * L + n * T) * D + e, gt[e]);
+            if (s < L) unsafeAtomicAdd(gdx + (b * (P - 1) + seg0 + n * T) * D + e, gt[e]);
             gt[e] = 0.0f;
         }
     }
@@ -897,14 +1020,26 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
 
 template <int D, int N, int WQ>
 hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
-                                 float* gdx, hipStream_t stream)
+                                 int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
 {
     using G = MGeo<D, N, N - 2, WQ>;
-    constexpr int T = 8;
-    const int64_t waves = B * G::WAVES;
+    constexpr int T = G::WIDE ? 16 : 8;
+    using LY = BwdLds<D, N, WQ, T>;
+    static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
+    const int64_t waves = B * C * G::WAVES;
     const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    trunc_mfma_bwd_kernel<D, N, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, 0, stream>>>(path, coeffs, grad, B, P, gdx);
+    if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_mfma_bwd_kernel<D, N, WQ, T>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+    }
+    trunc_mfma_bwd_kernel<D, N, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(path, coeffs, grad, B,
+                                                                                                      P, C, Lc, gdx);
     return hipGetLastError();
 }
 
@@ -916,12 +1051,39 @@ bool trunc_forward_available(int d, int depth)
     return (d == 4 && depth == 6) || (d == 8 && depth == 5) || (d == 16 && depth == 4);
 }
 
-hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t P, float* coeffs, hipStream_t stream)
+// d = 4, depth 6 forward: chain of four letters on the vector ALU, two cascade levels on the matrix cores, four
+// wavefronts per path.  (A chain of three letters - one wavefront per path, three cascade levels, 168 registers -
+// also works with this kernel; with time chunks it was no faster on 256 paths of 256 segments.)
+constexpr int kChainFwd46 = 4;
+constexpr int kOccFwd46 = 4;
+
+// Workgroups of the kernels that fit on one compute unit at a time (= wavefronts per SIMD), from the registers
+// and LDS each instantiation uses; the launcher of time chunks sizes the number of chunks with it.
+int trunc_occupancy(int d, int depth, int backward)
 {
-    if (B > 65535) return hipErrorInvalidValue;
-    if (d == 4 && depth == 6) return launch_trunc_mfma_fwd<4, 6, 4, 1>(path, B, P, coeffs, stream);
-    if (d == 8 && depth == 5) return launch_trunc_mfma_fwd<8, 5, 3, 2>(path, B, P, coeffs, stream);
-    if (d == 16 && depth == 4) return launch_trunc_mfma_fwd<16, 4, 2, 1>(path, B, P, coeffs, stream);
+    if (d == 4 && depth == 6) return backward ? 3 : kOccFwd46;
+    if (d == 8 && depth == 5) return backward ? 1 : 3;
+    if (d == 16 && depth == 4) return backward ? 1 : 2;
+    return 1;
+}
+
+// wavefronts one (path, chunk) row occupies
+int trunc_waves_per_row(int d, int depth, int backward)
+{
+    if (d == 4 && depth == 6) return backward ? MGeo<4, 6, 4, 1>::WAVES : MGeo<4, 6, kChainFwd46, 1>::WAVES;
+    if (d == 8 && depth == 5) return backward ? MGeo<8, 5, 3, 2>::WAVES : MGeo<8, 5, 3, 2>::WAVES;
+    if (d == 16 && depth == 4) return backward ? MGeo<16, 4, 2, 1>::WAVES : MGeo<16, 4, 2, 1>::WAVES;
+    return 1;
+}
+
+// C chunks of Lc segments per path (C = 1, Lc = P - 1: whole paths); coeffs has B * C rows
+hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t P, int64_t C, int64_t Lc, float* coeffs,
+                         hipStream_t stream)
+{
+    if (B * C > 65535 * 16) return hipErrorInvalidValue;
+    if (d == 4 && depth == 6) return launch_trunc_mfma_fwd<4, 6, kChainFwd46, 1>(path, B, P, C, Lc, coeffs, stream);
+    if (d == 8 && depth == 5) return launch_trunc_mfma_fwd<8, 5, 3, 2>(path, B, P, C, Lc, coeffs, stream);
+    if (d == 16 && depth == 4) return launch_trunc_mfma_fwd<16, 4, 2, 1>(path, B, P, C, Lc, coeffs, stream);
     return hipErrorInvalidValue;
 }
 
@@ -932,11 +1094,11 @@ bool trunc_backward_available(int d, int depth)
 
 // gdx: [B, L, d] accumulation buffer, zeroed by the caller
 hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
-                          int64_t P, float* gdx, hipStream_t stream)
+                          int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
 {
-    if (d == 4 && depth == 6) return launch_trunc_mfma_bwd<4, 6, 1>(path, coeffs, grad_coeffs, B, P, gdx, stream);
-    if (d == 8 && depth == 5) return launch_trunc_mfma_bwd<8, 5, 2>(path, coeffs, grad_coeffs, B, P, gdx, stream);
-    if (d == 16 && depth == 4) return launch_trunc_mfma_bwd<16, 4, 1>(path, coeffs, grad_coeffs, B, P, gdx, stream);
+    if (d == 4 && depth == 6) return launch_trunc_mfma_bwd<4, 6, 1>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (d == 8 && depth == 5) return launch_trunc_mfma_bwd<8, 5, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (d == 16 && depth == 4) return launch_trunc_mfma_bwd<16, 4, 1>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
     return hipErrorInvalidValue;
 }
 

@@ -185,6 +185,130 @@ void build_plan(const WordSet& ws, int max_slots, int64_t target_cost, bool with
     if (n > 0) split(-1);
 }
 
+void build_plan_balanced(const WordSet& ws, int64_t n_units, int max_slots, bool with_leave, int cost_word, int cost_pair,
+                         Plan& plan)
+{
+    const int64_t n = ws.size();
+    plan = Plan();
+    if (n == 0) return;
+    n_units = std::max<int64_t>(1, std::min(n_units, n));
+    max_slots = std::max(max_slots, ws.max_len + 1);
+
+    // depth-first order, children by letter
+    std::vector<int32_t> order;
+    order.reserve((size_t)n);
+    {
+        std::vector<int32_t> stack;
+        const int32_t r0 = ws.child_off[0], r1 = ws.child_off[1];
+        for (int32_t c = r1 - 1; c >= r0; --c) stack.push_back(ws.child_list[(size_t)c]);
+        while (!stack.empty()) {
+            const int32_t w = stack.back();
+            stack.pop_back();
+            order.push_back(w);
+            const int32_t c0 = ws.child_off[(size_t)(w + 1)], c1 = ws.child_off[(size_t)(w + 1) + 1];
+            for (int32_t c = c1 - 1; c >= c0; --c) stack.push_back(ws.child_list[(size_t)c]);
+        }
+    }
+
+    // One sweep: closes a unit before the word that would push its cost above `limit` (or its size above
+    // max_slots).  path_h[m] = height, inside the current unit, of the word at level m on the current root path.
+    // Returns the number of units; fills `cuts` (first position of every unit) when asked.
+    std::vector<int> path_h((size_t)ws.max_len + 2, 0);
+    auto sweep = [&](int64_t limit, std::vector<int64_t>* cuts) -> int64_t {
+        int64_t units = 0, i = 0;
+        while (i < n) {
+            ++units;
+            if (cuts) cuts->push_back(i);
+            const int k0 = ws.length[(size_t)order[(size_t)i]];
+            int64_t cost = 0, slots = k0 - 1;
+            for (int m = 1; m < k0; ++m) {
+                path_h[(size_t)m] = k0 - m;
+                cost += cost_word + (int64_t)cost_pair * (k0 - m);
+            }
+            const int64_t start = i;
+            for (int64_t j = start; j < n; ++j) {
+                const int k = ws.length[(size_t)order[(size_t)j]];
+                int64_t delta = cost_word;
+                for (int m = 1; m < k; ++m)
+                    if (k - m > path_h[(size_t)m]) delta += (int64_t)cost_pair * (k - m - path_h[(size_t)m]);
+                if (j > start && (cost + delta > limit || slots + 1 > max_slots)) break;
+                for (int m = 1; m < k; ++m) path_h[(size_t)m] = std::max(path_h[(size_t)m], k - m);
+                path_h[(size_t)k] = 0;
+                cost += delta;
+                ++slots;
+                i = j + 1;
+            }
+        }
+        return units;
+    };
+    int64_t total = 0;
+    for (int64_t w = 0; w < n; ++w) total += cost_word + (int64_t)cost_pair * ws.height[(size_t)w];
+    int64_t lo = std::max<int64_t>(1, total / n_units), hi = total + (int64_t)ws.max_len * ws.max_len * (cost_word + cost_pair);
+    while (lo < hi) {                               // smallest limit that needs no more than n_units units
+        const int64_t mid = lo + (hi - lo) / 2;
+        if (sweep(mid, nullptr) <= n_units) hi = mid; else lo = mid + 1;
+    }
+    std::vector<int64_t> cuts;
+    sweep(lo, &cuts);
+    cuts.push_back(n);
+
+    struct Elem { int32_t word; int level; int h; bool own; };
+    std::vector<Elem> el;
+    std::vector<int> path_el((size_t)ws.max_len + 2, -1);
+    std::vector<int> open;                          // indices into el of the ENTER ops not yet closed
+    for (size_t u = 0; u + 1 < cuts.size(); ++u) {
+        el.clear();
+        const int32_t first = order[(size_t)cuts[u]];
+        const int k0 = ws.length[(size_t)first];
+        el.resize((size_t)k0 - 1);
+        for (int32_t a = ws.parent[(size_t)first], m = k0 - 1; m >= 1; a = ws.parent[(size_t)a], --m) {
+            el[(size_t)m - 1] = Elem{a, m, 0, false};
+            path_el[(size_t)m] = m - 1;
+        }
+        for (int64_t j = cuts[u]; j < cuts[u + 1]; ++j) {
+            const int32_t w = order[(size_t)j];
+            const int k = ws.length[(size_t)w];
+            for (int m = 1; m < k; ++m) {
+                Elem& a = el[(size_t)path_el[(size_t)m]];
+                a.h = std::max(a.h, k - m);
+            }
+            path_el[(size_t)k] = (int)el.size();
+            el.push_back(Elem{w, k, 0, true});
+        }
+        UnitDesc ud;
+        ud.op_off = (int32_t)plan.ops.size();
+        ud.slot_off = (int32_t)plan.slot_word.size();
+        open.clear();
+        auto close_to = [&](int level) {            // closes every open ENTER at `level` or deeper
+            while (!open.empty() && el[(size_t)open.back()].level >= level) {
+                const Elem& e = el[(size_t)open.back()];
+                if (with_leave)
+                    plan.ops.push_back(op_pack((uint32_t)ws.letter[(size_t)e.word], (uint32_t)e.level, (uint32_t)e.h, OP_LEAVE));
+                open.pop_back();
+            }
+        };
+        for (size_t x = 0; x < el.size(); ++x) {
+            const Elem& e = el[x];
+            close_to(e.level);
+            plan.slot_word.push_back(e.own ? e.word : ~e.word);
+            plan.fma_per_step += 1 + e.h;
+            plan.pairs_nonleaf += e.h;
+            if (e.h == 0) {
+                plan.ops.push_back(op_pack((uint32_t)ws.letter[(size_t)e.word], (uint32_t)e.level, 0, OP_LEAF));
+                plan.leaves++;
+            } else {
+                plan.ops.push_back(op_pack((uint32_t)ws.letter[(size_t)e.word], (uint32_t)e.level, (uint32_t)e.h, OP_ENTER));
+                open.push_back((int)x);
+            }
+        }
+        close_to(0);
+        ud.n_ops = (int32_t)plan.ops.size() - ud.op_off;
+        ud.n_slots = (int32_t)plan.slot_word.size() - ud.slot_off;
+        plan.max_slots = std::max(plan.max_slots, ud.n_slots);
+        plan.units.push_back(ud);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------
 
 static int check_d(int d) { return (d >= 1 && d <= 4096) ? SIG_OK : SIG_EINVAL; }

@@ -67,8 +67,14 @@ struct WordSet {
     std::vector<unsigned char> image;
     void* dev = nullptr;
     bool kernels_supported = true;     // false when max_len exceeds what the kernels handle
-    // run-time specialised kernels, one per plan variant and direction, built on first use
-    std::vector<JitKernel*> jit[2];
+    // run-time specialised kernels with the balanced plan each was generated from, per direction, keyed by the
+    // number of work units asked for; built on first use
+    struct JitEntry {
+        int64_t n_units = 0;
+        Plan plan;
+        JitKernel* kernel = nullptr;
+    };
+    std::vector<JitEntry*> jit[2];
     WordSet() = default;
     WordSet(const WordSet&) = delete;
     WordSet& operator=(const WordSet&) = delete;
@@ -83,5 +89,13 @@ int build_list(int d, const int32_t* letters, const int64_t* offsets, int64_t n_
 
 // Splits the word tree into work units of at most max_slots words and about target_cost multiply-adds.
 void build_plan(const WordSet& ws, int max_slots, int64_t target_cost, bool with_leave, Plan& plan);
+
+
+// Balanced split for the run-time specialised kernels: the words in depth-first order are cut into at most
+// n_units consecutive runs of (nearly) equal cost; a unit is one run plus the ancestors of its first word
+// (recomputed, owned by an earlier unit).  Cost of a word = cost_word + cost_pair * (height of its sub-tree inside
+// the unit).  No unit holds more than max_slots words.
+void build_plan_balanced(const WordSet& ws, int64_t n_units, int max_slots, bool with_leave, int cost_word, int cost_pair,
+                         Plan& plan);
 
 }  // namespace sig

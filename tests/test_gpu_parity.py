@@ -47,6 +47,40 @@ def test_small_cases_elementwise(case):
     check_parity(ws, W, kind, kw.get("depth"), X, G, what=f"small[{case}]")
 
 
+# Time chunks (Chen's relation between chunk signatures): forced chunk counts, including chunk lengths that do not
+# divide L and a last chunk of a single segment; the automatic choice is exercised by the small batches below.
+@pytest.mark.parametrize("d,depth,B,L,chunks", [(4, 6, 3, 97, 3), (4, 6, 2, 65, 2), (4, 6, 1, 160, 5), (8, 5, 2, 100, 3),
+                                                (16, 4, 1, 129, 4), (4, 6, 2, 600, 0), (16, 4, 3, 700, 0)])
+def test_time_chunks(monkeypatch, d, depth, B, L, chunks):
+    if chunks:
+        monkeypatch.setenv("SIG_CHUNKS", str(chunks))
+    else:
+        monkeypatch.delenv("SIG_CHUNKS", raising=False)
+    ws, W = build_both("truncated", d, depth=depth)
+    X = make_path("time0" if d == 4 else "iid", 500 + L, B, L, d)
+    G = make_grad_coeffs(600 + L, B, ws.size)
+    lib = S.load_library()
+    if chunks:
+        assert lib.sig_forward_workspace_bytes(ws._h, B, L + 1) >= 2 * 4 * B * chunks * ws.size
+    else:
+        assert lib.sig_forward_workspace_bytes(ws._h, B, L + 1) > 0      # few paths: chunking is chosen by itself
+    check_parity(ws, W, "truncated", depth, X, G, what=f"chunks d={d} N={depth} L={L} C={chunks}")
+
+
+def test_chunked_and_unchunked_agree(monkeypatch):
+    ws, W = build_both("truncated", 4, depth=6)
+    X = make_path("time0", 11, 4, 128, 4)
+    G = make_grad_coeffs(12, 4, ws.size)
+    monkeypatch.setenv("SIG_CHUNKS", "1")
+    c1, g1 = gpu_forward_backward(ws, X, G)
+    monkeypatch.setenv("SIG_CHUNKS", "4")
+    c4, g4 = gpu_forward_backward(ws, X, G)
+    lengths = np.array([len(w) for w in W])
+    for n, e in O.level_errors(c4, c1.astype(np.float64), lengths).items():
+        assert e <= 1e-5, (n, e)
+    assert O.grad_errors(g4, g1.astype(np.float64)).max() <= 1e-4
+
+
 def test_one_point_paths_give_zero():
     import torch
     ws, W = build_both("truncated", 3, depth=3)

@@ -187,11 +187,18 @@ def _sets():
     yield "random", S.sig_wordset_build(5, words), O.prefix_closure(words), 5
 
 
+def _all_plans(ws, backward):
+    """Static variants (table-driven kernels) and balanced plans (specialised kernels) for several batch sizes."""
+    for v in range(ws.plan_count(backward)):
+        yield f"v{v}", ws.plan(backward, v), (56 if backward else 112)
+    for B in (1, 64, 512, 5000, 200000):
+        yield f"balanced B={B}", ws.jit_plan(backward, B), (160 if backward else 320)
+
+
 @pytest.mark.parametrize("backward", [False, True])
 def test_plans_cover_every_word_exactly_once(backward):
     for name, ws, W, d in _sets():
-        for v in range(ws.plan_count(backward)):
-            p = ws.plan(backward, v)
+        for v, p, slot_limit in _all_plans(ws, backward):
             owned = p["slot_word"][p["slot_word"] >= 0]
             assert np.array_equal(np.sort(owned), np.arange(ws.size)), (name, v)
             # programs: slots = number of non-LEAVE ops; ENTER/LEAVE balanced; levels consistent with the tables
@@ -199,7 +206,7 @@ def test_plans_cover_every_word_exactly_once(backward):
                 prog = [plan_model.decode(o) for o in p["ops"][op_off:op_off + n_ops]]
                 sw = p["slot_word"][slot_off:slot_off + n_slots]
                 assert sum(1 for o in prog if o[3] != plan_model.LEAVE) == n_slots
-                assert n_slots <= (56 if backward else 112)
+                assert n_slots <= slot_limit
                 r, stack = 0, []
                 for letter, level, h, kind in prog:
                     if kind == plan_model.LEAVE:
@@ -227,10 +234,10 @@ def test_plan_model_forward_matches_oracle():
     for name, ws, W, d in _sets():
         X = make_path("iid", 3, 3, 9, d)
         ref = O.forward_words(X, W)
-        for v in range(ws.plan_count(False)):
-            out, written = plan_model.forward(ws.plan(False, v), X, ws.size)
+        for v, p, _ in _all_plans(ws, False):
+            out, written = plan_model.forward(p, X, ws.size)
             assert np.all(written == 1)
-            np.testing.assert_allclose(out, ref, rtol=1e-11, atol=1e-14, err_msg=f"{name} v{v}")
+            np.testing.assert_allclose(out, ref, rtol=1e-11, atol=1e-14, err_msg=f"{name} {v}")
 
 
 def test_plan_model_backward_matches_oracle():
@@ -239,9 +246,9 @@ def test_plan_model_backward_matches_oracle():
         G = np.random.default_rng(0).standard_normal((2, ws.size))
         coeffs = O.forward_words(X, W)
         ref = O.backward_words(X, W, G)
-        for v in range(ws.plan_count(True)):
-            gp = plan_model.backward(ws.plan(True, v), X, coeffs, G)
-            np.testing.assert_allclose(gp, ref, rtol=1e-9, atol=1e-11, err_msg=f"{name} v{v}")
+        for v, p, _ in _all_plans(ws, True):
+            gp = plan_model.backward(p, X, coeffs, G)
+            np.testing.assert_allclose(gp, ref, rtol=1e-9, atol=1e-11, err_msg=f"{name} {v}")
 
 
 def test_fma_counts():
@@ -249,7 +256,20 @@ def test_fma_counts():
         assert S.sig_wordset_build_truncated(d, N).min_fma_per_step == fmin
     assert S.sig_wordset_build_anisotropic(6, (1, 1, 2, 2, 3, 3), 8.0).min_fma_per_step == 8742
     ws = S.sig_wordset_build_truncated(4, 6)
-    for v in range(ws.plan_count(False)):
-        p = ws.plan(False, v)
+    for v, p, _ in _all_plans(ws, False):
         assert p["fma_per_step"] == sum(plan_model.decode(o)[2] + 1 for o in p["ops"])
         assert p["fma_per_step"] >= ws.min_fma_per_step
+
+
+def test_balanced_plans_are_balanced():
+    """Units of a balanced plan have nearly equal cost: no unit is cheaper than the costliest one by more than one
+    word's worth of multiply-adds plus the ancestor chain (the last unit takes what is left)."""
+    ws = S.sig_wordset_build_anisotropic(6, (1, 1, 2, 2, 3, 3), 8.0)
+    p = ws.jit_plan(False, 512)
+    cost = []
+    for (op_off, n_ops, slot_off, n_slots) in p["units"]:
+        cost.append(sum(plan_model.decode(o)[2] + 1 for o in p["ops"][op_off:op_off + n_ops]))
+    cost = np.array(cost)
+    assert 120 <= len(cost) <= 128
+    assert cost.max() - np.sort(cost)[1] <= 8 * 9 // 2 + 8
+    assert p["fma_per_step"] <= 1.35 * ws.min_fma_per_step
