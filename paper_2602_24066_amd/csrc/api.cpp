@@ -109,13 +109,14 @@ bool use_trunc_backward(const sig::WordSet& w, int64_t B)
 // ---- run-time specialised kernels ------------------------------------------------------------------------
 std::mutex g_jit_mutex;
 
-// Work units asked of the balanced planner for a batch of B paths: one wavefront per SIMD (1,024 on the chip)
-// over the path groups, a whole number of workgroups, and not so many that units shrink to a handful of words
+// Work units asked of the balanced planner for a batch of B paths: one or two wavefronts per SIMD (1,024 on the
+// chip) over the path groups, a whole number of workgroups, and not so many that units shrink to a handful of words
 // (every unit recomputes the ancestors of its first word).
 constexpr int kJitWaves = 4;           // wavefronts (units) per workgroup
-int64_t jit_units(const sig::WordSet& w, int /*dir*/, int64_t B)
+int64_t jit_units(const sig::WordSet& w, int dir, int64_t B)
 {
-    int64_t want = 1024;
+    // forward units keep one value per word and fit two wavefronts per SIMD; backward units keep two
+    int64_t want = dir ? 1024 : 2048;
     if (const char* e = std::getenv("SIG_JIT_WAVES")) want = std::max(1, std::atoi(e));   // tuning knob
     const int64_t groups = (B + 63) / 64;
     int64_t n = std::max<int64_t>(1, want / groups);
@@ -203,15 +204,6 @@ size_t jit_dxt_bytes(const sig::WordSet& w, int64_t B, int64_t n_points, int dir
 {
     const size_t n = (size_t)((B + 63) / 64) * (size_t)jit_lpad(w, n_points, dir) * (size_t)w.d * 64 * sizeof(float);
     return (n + 255) & ~(size_t)255;
-}
-
-// workgroup columns of the specialised backward kernel (each writes its own gradient slice)
-int jit_bwd_columns(const sig::WordSet& w, int64_t B)
-{
-    sig::WordSet::JitEntry* e = jit_entry(w, 1, B);
-    if (!e) return 1;
-    const size_t nw = std::min<size_t>((size_t)kJitWaves, std::max<size_t>(1, e->plan.units.size()));
-    return (int)((e->plan.units.size() + nw - 1) / nw);
 }
 
 hipError_t launch_jit_forward(sig::JitKernel& k, const sig::Plan& p, const float* dxT, int64_t B, int64_t ntiles, float* coeffs,
@@ -396,8 +388,8 @@ size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_
     if (use_trunc_backward(w, B)) {
         const Chunks ch = trunc_chunks(w, 1, B, n_points);
         if (ch.C > 1) n += 4 * chunk_array_bytes(w, B, ch.C);       // chunk signatures, prefixes, suffixes, adjoints
-    } else if (jit_enabled(w)) {                                    // one gradient slice per workgroup column + increments
-        n = n * (size_t)jit_bwd_columns(w, B) + jit_dxt_bytes(w, B, n_points, 1);
+    } else if (jit_enabled(w)) {                                    // + transposed increments
+        n += jit_dxt_bytes(w, B, n_points, 1);
     }
     return n;
 }
@@ -531,9 +523,8 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     }
     const sig::Plan* jp = nullptr;
     if (sig::JitKernel* jk = ensure_jit(w, 1, B, true, &jp)) {
-        const int ncol = jit_bwd_columns(w, B);
         const size_t gdx_bytes = ((size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;
-        float* dxT = (float*)((unsigned char*)workspace + gdx_bytes * (size_t)ncol);
+        float* dxT = (float*)((unsigned char*)workspace + gdx_bytes);
         const int64_t Lpad = jit_lpad(w, n_points, 1);
         e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, st);
         if (e != hipSuccess) return hip_fail(e);
@@ -543,7 +534,7 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
                                 gdx, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
-        e = sig::grad_points_sum(gdx, ncol, B, n_points, w.d, grad_path, st);
+        e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
     const int v = pick_variant(w, 1, B);

@@ -91,28 +91,28 @@ __device__ __attribute__((noinline)) void idle_unit(const float* __restrict__ dx
         o << R"SRC(
 // Gradient tiles: every wavefront (unit) has its own gt[(tt * D + i) * LP + lane] in LDS and overwrites all of it
 // in every tile with plain stores (LDS floating-point atomics turned out to be far slower than the arithmetic).
-// At the end of a tile the NW tiles are added up and written out with one path per pass, so that (segment,
-// letter) runs are contiguous.  Every workgroup column (blockIdx.x) owns a private slice gpart[blockIdx.x][B][L][D]
-// that it fills with plain stores; the slices are summed by a later kernel.
+// At the end of a tile the NW tiles are added up and added to gdx [B][L][D] (zeroed by the caller) with one path per
+// pass, so that a wavefront's floating-point atomics cover contiguous (segment, letter) runs; all workgroup columns
+// (blockIdx.x) add into the same array.
 #define GT_F (T * D * LP)
-__device__ __attribute__((noinline)) void grad_flush(const float* gt_all, float* gpart, long L, long j0, long b0, long B, int lane,
+__device__ __attribute__((noinline)) void grad_flush(const float* gt_all, float* gdx, long L, long j0, long b0, long B, int lane,
                                                      int wib)
 {
     for (int bb = wib; bb < 64; bb += NW) {
         if (b0 + bb < B) {
-            float* dst = gpart + ((b0 + bb) * L + j0) * D;
+            float* dst = gdx + ((b0 + bb) * L + j0) * D;
             for (int e = lane; e < T * D; e += 64)
                 if (j0 + e / D < L) {
                     float v = 0.0f;
 #pragma unroll
                     for (int w = 0; w < NW; ++w) v += gt_all[w * GT_F + e * LP + bb];
-                    dst[e] = v;
+                    __hip_atomic_fetch_add(dst + e, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
         }
     }
 }
 __device__ __attribute__((noinline)) void idle_unit(const float* __restrict__ dxg, long ntiles, long L, float* tile, float* gt_all,
-                                                    float* gpart, long b0, long B, int lane, int wib)
+                                                    float* gdx, long b0, long B, int lane, int wib)
 {
     f4 r[EPT];
     const int tid = wib * 64 + lane;
@@ -125,7 +125,7 @@ __device__ __attribute__((noinline)) void idle_unit(const float* __restrict__ dx
         __syncthreads();
         tile_fetch(dxg, n - 1, tid, r);
         __syncthreads();
-        grad_flush(gt_all, gpart, L, n * T, b0, B, lane, wib);
+        grad_flush(gt_all, gdx, L, n * T, b0, B, lane, wib);
     }
 }
 )SRC";
@@ -326,7 +326,6 @@ std::string jit_backward_source(const WordSet& ws, const Plan& plan, int NW, int
     o << "    const long b0 = (long)blockIdx.y * 64;\n    const long b = b0 + lane;\n    const long bc = b < B ? b : B - 1;\n";
     o << "    const float* dxg = dxT + (long)blockIdx.y * ntiles * (T * D * 64);\n";
     o << "    const float* cf = coeffs + bc * nW;\n    const float* gr = grad + bc * nW;\n";
-    o << "    gdx += (long)blockIdx.x * B * L * D;\n";
     o << "    const int unit = blockIdx.x * NW + wib;\n    switch (unit) {\n";
     for (int u = 0; u < nu; ++u)
         o << "        case " << u << ": bwd_unit_" << u << "(dxg, ntiles, L, tile, gt, gdx, b0, B, lane, wib, cf, gr); break;\n";
@@ -342,7 +341,8 @@ int jit_compile(const std::string& src, const char* kernel_name, JitKernel& out)
         out.log = "hiprtcCreateProgram failed";
         return -1;
     }
-    const char* opts[] = {"--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+    const char* opts[] = {"--offload-arch=gfx950", "-O3", "-munsafe-fp-atomics", "-Xclang", "-target-feature", "-Xclang",
+                          "-packed-fp32-ops"};
     const hiprtcResult rc = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
     size_t logsz = 0;
     if (hiprtcGetProgramLogSize(prog, &logsz) == HIPRTC_SUCCESS && logsz > 1) {

@@ -292,30 +292,6 @@ __global__ void grad_points_kernel(const float* __restrict__ gdx, int64_t B, int
     grad_path[i] = here - next;
 }
 
-// As grad_points_kernel, for n_part partial gradients [n_part][B][L][d] that still have to be added up.
-__global__ void grad_points_sum_kernel(const float* __restrict__ gpart, int n_part, int64_t B, int64_t P, int d,
-                                       float* __restrict__ grad_path)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t n = B * P * d;
-    if (i >= n) return;
-    const int64_t c = i % d;
-    const int64_t j = (i / d) % P;
-    const int64_t b = i / (d * P);
-    const int64_t L = P - 1;
-    const int64_t stride = B * L * d;
-    float here = 0.0f, next = 0.0f;
-    if (j >= 1) {
-        const float* p = gpart + (b * L + (j - 1)) * d + c;
-        for (int w = 0; w < n_part; ++w) here += p[w * stride];
-    }
-    if (j < L) {
-        const float* p = gpart + (b * L + j) * d + c;
-        for (int w = 0; w < n_part; ++w) next += p[w * stride];
-    }
-    grad_path[i] = here - next;
-}
-
 template <int MAXK>
 hipError_t launch_fwd(const GenericArgs& a, hipStream_t stream)
 {
@@ -393,15 +369,6 @@ hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* gra
     if (n <= 0) return hipSuccess;
     const int threads = 256;
     grad_points_kernel<<<(unsigned)((n + threads - 1) / threads), threads, 0, stream>>>(gdx, B, P, d, grad_path);
-    return hipGetLastError();
-}
-
-hipError_t grad_points_sum(const float* gpart, int n_part, int64_t B, int64_t P, int d, float* grad_path, hipStream_t stream)
-{
-    const int64_t n = B * P * d;
-    if (n <= 0) return hipSuccess;
-    const int threads = 256;
-    grad_points_sum_kernel<<<(unsigned)((n + threads - 1) / threads), threads, 0, stream>>>(gpart, n_part, B, P, d, grad_path);
     return hipGetLastError();
 }
 

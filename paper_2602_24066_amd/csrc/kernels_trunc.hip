@@ -458,7 +458,7 @@ hipError_t launch_trunc_mfma_fwd(const float* path, int64_t B, int64_t P, int64_
                                  hipStream_t stream)
 {
     using G = MGeo<D, N, K, WQ>;
-    constexpr int T = 16;
+    constexpr int T = G::WIDE ? 8 : 16;          // d = 16: 32 KB of LDS per workgroup, so that three fit on a compute unit
     const int64_t waves = B * C * G::WAVES;
     const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
@@ -1063,7 +1063,7 @@ int trunc_occupancy(int d, int depth, int backward)
 {
     if (d == 4 && depth == 6) return backward ? 3 : kOccFwd46;
     if (d == 8 && depth == 5) return backward ? 1 : 3;
-    if (d == 16 && depth == 4) return backward ? 1 : 2;
+    if (d == 16 && depth == 4) return backward ? 1 : 3;
     return 1;
 }
 
