@@ -115,8 +115,7 @@ std::mutex g_jit_mutex;
 constexpr int kJitWaves = 4;           // wavefronts (units) per workgroup
 int64_t jit_units(const sig::WordSet& w, int dir, int64_t B)
 {
-    // forward units keep one value per word and fit two wavefronts per SIMD; backward units keep two
-    int64_t want = dir ? 1024 : 2048;
+    int64_t want = 2048;               // two wavefronts per SIMD
     if (const char* e = std::getenv("SIG_JIT_WAVES")) want = std::max(1, std::atoi(e));   // tuning knob
     const int64_t groups = (B + 63) / 64;
     int64_t n = std::max<int64_t>(1, want / groups);

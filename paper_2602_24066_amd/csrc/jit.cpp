@@ -161,7 +161,7 @@ void emit_forward_unit(std::ostringstream& o, const Plan& plan, int uidx)
 {
     const UnitDesc& ud = plan.units[(size_t)uidx];
     const Uses uses = collect_uses(plan, ud);
-    o << "__device__ __attribute__((noinline)) void fwd_unit_" << uidx
+    o << "__device__ __forceinline__ void fwd_unit_" << uidx
       << "(const float* __restrict__ dxg, long ntiles, float* tile, int lane, int wib, float* __restrict__ out)\n{\n";
     o << "    float";
     for (int r = 0; r < ud.n_slots; ++r) o << (r ? ", " : " ") << "s" << r << " = 0.0f";
@@ -170,7 +170,8 @@ void emit_forward_unit(std::ostringstream& o, const Plan& plan, int uidx)
     o << "    f4 r[EPT];\n    tile_fetch(dxg, 0, tid, r);\n    tile_stage(tile, tid, r);\n    __syncthreads();\n";
     o << "    for (long n = 0; n < ntiles; ++n) {\n";
     o << "        tile_fetch(dxg, n + 1 < ntiles ? n + 1 : n, tid, r);\n";
-    o << "        for (int tt = 0; tt < T; ++tt) {\n";
+    // the segment loop stays rolled: the bodies of all units together must fit the instruction cache
+    o << "#pragma unroll 1\n        for (int tt = 0; tt < T; ++tt) {\n";
     o << "            const float* dxp = tile + tt * D * 64 + lane;\n";
     emit_step_loads(o, uses, "            ");
     int depth = 0;   // open scopes = length of the current word chain
@@ -205,7 +206,7 @@ void emit_backward_unit(std::ostringstream& o, const Plan& plan, int uidx, int D
 {
     const UnitDesc& ud = plan.units[(size_t)uidx];
     const Uses uses = collect_uses(plan, ud);
-    o << "__device__ __attribute__((noinline)) void bwd_unit_" << uidx
+    o << "__device__ __forceinline__ void bwd_unit_" << uidx
       << "(const float* __restrict__ dxg, long ntiles, long L, float* tile, float* gt_all, float* gdx, long b0, long B, int lane,\n"
          "     int wib, const float* __restrict__ cf, const float* __restrict__ gr)\n{\n";
     for (int r = 0; r < ud.n_slots; ++r) {
@@ -221,7 +222,7 @@ void emit_backward_unit(std::ostringstream& o, const Plan& plan, int uidx, int D
     o << "    for (long n = ntiles - 1; n >= 0; --n) {\n";
     o << "        __syncthreads();\n        tile_stage(tile, tid, r);\n        __syncthreads();\n";
     o << "        tile_fetch(dxg, n - 1, tid, r);\n";
-    o << "        for (int tt = T - 1; tt >= 0; --tt) {\n";
+    o << "#pragma unroll 1\n        for (int tt = T - 1; tt >= 0; --tt) {\n";
     o << "            const float* dxp = tile + tt * D * 64 + lane;\n";
     emit_step_loads(o, uses, "            ");
     for (int i : uses.letters) o << "            float g" << i << " = 0.0f;\n";
