@@ -81,6 +81,20 @@ def test_chunked_and_unchunked_agree(monkeypatch):
     assert O.grad_errors(g4, g1.astype(np.float64)).max() <= 1e-4
 
 
+@pytest.mark.parametrize("kind", ["anisotropic", "words"])
+def test_table_driven_kernels(monkeypatch, kind):
+    """With run-time specialisation switched off the table-driven kernels serve the same word sets."""
+    monkeypatch.setenv("SIG_NO_JIT", "1")
+    if kind == "anisotropic":
+        ws, W = build_both(kind, 4, weights=(1.0, 1.0, 2.0, 3.0), cutoff=5.0)
+    else:
+        ws, W = build_both(kind, 6, words=random_prefix_closed_words(77, 6, 800, 5))
+    assert ws.kernel_name(False) == "fwd_generic_kernel" and ws.kernel_name(True) == "bwd_generic_kernel"
+    X = make_path("iid", 78, 70, 19, ws.dim)
+    G = make_grad_coeffs(79, 70, ws.size)
+    check_parity(ws, W, kind, None, X, G, what=f"table-driven {kind}")
+
+
 def test_one_point_paths_give_zero():
     import torch
     ws, W = build_both("truncated", 3, depth=3)

@@ -273,3 +273,32 @@ def test_balanced_plans_are_balanced():
     assert 0.9 * len(cost) <= 4 * ((2048 // 8 + 3) // 4) and len(cost) <= 4 * ((2048 // 8 + 3) // 4)
     assert cost.max() - np.sort(cost)[1] <= 8 * 9 // 2 + 8
     assert p["fma_per_step"] <= 1.6 * ws.min_fma_per_step
+
+
+def test_runtime_compilation_without_a_device():
+    """hiprtc needs no GPU: the specialised kernels of a small word set compile, and the generated source holds one
+    body per work unit of the balanced plan."""
+    ws = S.sig_wordset_build(5, random_prefix_closed_words(9, 5, 200, 5))
+    for backward in (False, True):
+        plan = ws.jit_plan(backward, 128)
+        src = ws.jit_source(backward, 128)
+        name = "bwd_unit_" if backward else "fwd_unit_"
+        assert src.count("void " + name) == len(plan["units"])
+        assert ("sig_bwd_jit" if backward else "sig_fwd_jit") in src
+        assert ws.jit_prepare(backward, 128) == 0
+    full = S.sig_wordset_build_truncated(4, 6)                  # served by a precompiled kernel instead
+    assert full.jit_prepare(False, 128) == -9
+
+
+def test_time_chunk_workspace():
+    """Few long paths of a full truncation are cut into time chunks: the forward workspace holds the chunk
+    signatures and the partial products; many paths, or short ones, need none."""
+    lib = S.load_library()
+    ws = S.sig_wordset_build_truncated(4, 6)
+    rows = 2 * 4                                               # B = 2 paths, L = 1024 -> 4 chunks of 256 segments
+    per_array = (4 * rows * ws.size + 255) // 256 * 256
+    assert lib.sig_forward_workspace_bytes(ws._h, 2, 1025) == 2 * per_array
+    assert lib.sig_forward_workspace_bytes(ws._h, 2, 300) == 0
+    assert lib.sig_forward_workspace_bytes(ws._h, 4096, 1025) == 0
+    gdx = (4 * 2 * 1024 * 4 + 255) // 256 * 256
+    assert lib.sig_backward_workspace_bytes(ws._h, 2, 1025) == gdx       # backward is not chunked by itself
