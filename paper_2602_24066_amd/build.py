@@ -11,7 +11,10 @@ LIB = os.path.join(HERE, "libsig_mi355x.so")
 SOURCES = ["api.cpp", "wordset.cpp", "jit.cpp", "kernels_generic.hip", "kernels_trunc.hip", "kernels_chunk.hip"]
 # -packed-fp32-ops is switched off on purpose: the packed FP32 forms are not used by this library.
 HIPCC_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
-               "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
+               "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument",
+               # matrix-instruction results stay in ordinary vector registers: the vector ALU reads them without
+               # v_accvgpr_read copies (a quarter of the instructions of the backward kernels otherwise)
+               "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 
 def hipcc() -> str:
