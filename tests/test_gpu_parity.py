@@ -95,6 +95,17 @@ def test_table_driven_kernels(monkeypatch, kind):
     check_parity(ws, W, kind, None, X, G, what=f"table-driven {kind}")
 
 
+def test_many_short_paths():
+    """More paths than the register-resident kernels take in one launch (65,535): the specialised kernels serve a
+    full truncation too.  Sampled paths against the oracle."""
+    ws, W = build_both("truncated", 4, depth=6)
+    B, L = 66000, 3
+    X = make_path("iid", 41, B, L, 4)
+    G = make_grad_coeffs(42, B, ws.size)
+    sample = [0, 1, 63, 64, 4095, 65535, 65536, B - 1]
+    check_parity(ws, W, "truncated", 6, X, G, sample=sample, what="B=66000")
+
+
 def test_one_point_paths_give_zero():
     import torch
     ws, W = build_both("truncated", 3, depth=3)
