@@ -91,6 +91,30 @@ Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points)
     const int64_t Lc = (L + C - 1) / C;
     return Chunks{(L + Lc - 1) / Lc, Lc};
 }
+// Backward launch shape for a full truncation.  d = 4 has a second kernel with one wavefront per (path, chunk) row
+// that does half the vector work per path; it needs about a thousand rows to fill the chip, so shorter batches are
+// cut into time chunks for it (SIG_BWD_TAILS=0/1 forces the choice).
+struct BwdShape { bool tails; int64_t C, Lc; };
+BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points)
+{
+    const int64_t L = n_points - 1;
+    const Chunks ch = trunc_chunks(w, 1, B, n_points);
+    BwdShape s{false, ch.C, ch.Lc};
+    if (!sig::trunc_backward_tails_available(w.d, w.depth)) return s;
+    const char* force = std::getenv("SIG_BWD_TAILS");
+    if (force && force[0] == '0') return s;
+    const char* ce = std::getenv("SIG_CHUNKS");
+    int64_t C = ch.C;
+    if (!(ce && ce[0])) {
+        C = std::max<int64_t>(1, std::min<int64_t>((1024 + B - 1) / std::max<int64_t>(B, 1), L / 32));
+        C = std::min<int64_t>(C, 64);
+        if (!sig::chunking_available(w.d, w.depth)) C = 1;
+    }
+    const int64_t Lc = (L + C - 1) / C;
+    C = (L + Lc - 1) / Lc;
+    if (!(force && force[0] == '1') && B * C < 768) return s;
+    return BwdShape{true, C, Lc};
+}
 size_t chunk_array_bytes(const sig::WordSet& w, int64_t B, int64_t C)
 {
     return ((size_t)B * (size_t)C * (size_t)w.size() * sizeof(float) + 255) & ~(size_t)255;
@@ -385,7 +409,7 @@ size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_
     size_t n = (size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float);
     n = (n + 255) & ~(size_t)255;                                   // gradient with respect to the increments
     if (use_trunc_backward(w, B)) {
-        const Chunks ch = trunc_chunks(w, 1, B, n_points);
+        const BwdShape ch = trunc_backward_shape(w, B, n_points);
         if (ch.C > 1) n += 4 * chunk_array_bytes(w, B, ch.C);       // chunk signatures, prefixes, suffixes, adjoints
     } else if (jit_enabled(w)) {                                    // + transposed increments
         n += jit_dxt_bytes(w, B, n_points, 1);
@@ -434,7 +458,7 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
         hipError_t e = sig::trunc_forward(w.d, w.depth, path, B, n_points, ch.C, ch.Lc, Sc, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e == hipSuccess && ch.C > 1)
-            e = sig::chunk_scan(w.d, w.depth, Sc, Pfx, nullptr, nullptr, coeffs, B, (int)ch.C, st);
+            e = sig::chunk_scan(w.d, w.depth, Sc, Pfx, nullptr, nullptr, coeffs, nullptr, nullptr, B, (int)ch.C, nullptr, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
     const sig::Plan* jp = nullptr;
@@ -488,10 +512,14 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
     float* gdx = (float*)workspace;
     CallTimer whole(1, st);
-    hipError_t e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
-    if (e != hipSuccess) return hip_fail(e);
-    if (use_trunc_backward(w, B)) {
-        const Chunks ch = trunc_chunks(w, 1, B, n_points);
+    hipError_t e = hipSuccess;
+    const bool trunc = use_trunc_backward(w, B);
+    const BwdShape ch = trunc ? trunc_backward_shape(w, B, n_points) : BwdShape{false, 1, n_points - 1};
+    if (!ch.tails) {                     // the one-wavefront-per-row kernel stores every entry itself
+        e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    if (trunc) {
         const float* row_coeffs = coeffs;
         const float* row_grad = grad_coeffs;
         if (ch.C > 1) {
@@ -506,15 +534,18 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
             float* Q = (float*)(base + 2 * nb);
             float* Abar = (float*)(base + 3 * nb);
             e = sig::trunc_forward(w.d, w.depth, path, B, n_points, ch.C, ch.Lc, Sc, st);
-            if (e == hipSuccess) e = sig::chunk_scan(w.d, w.depth, Sc, Pfx, Q, coeffs, nullptr, B, (int)ch.C, st);
-            if (e == hipSuccess) e = sig::chunk_adjoint(w.d, w.depth, grad_coeffs, Q, Abar, B, (int)ch.C, st);
+            bool adjoints_done = false;
+            if (e == hipSuccess)
+                e = sig::chunk_scan(w.d, w.depth, Sc, Pfx, Q, coeffs, nullptr, grad_coeffs, Abar, B, (int)ch.C, &adjoints_done, st);
+            if (e == hipSuccess && !adjoints_done) e = sig::chunk_adjoint(w.d, w.depth, grad_coeffs, Q, Abar, B, (int)ch.C, st);
             if (e != hipSuccess) return hip_fail(e);
             row_coeffs = Pfx;
             row_grad = Abar;
         }
         hipEvent_t* pe = g_prof.next(1);
         if (pe) (void)hipEventRecord(pe[0], st);
-        e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
+        if (ch.tails) e = sig::trunc_backward_tails(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
+        else e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
         e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);

@@ -44,13 +44,21 @@ hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t
 hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
                           int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream);
 
+// d = 4: backward with one wavefront per row (a lane holds a word of length N - 3 and its four children); stores
+// the gradient of the increments instead of accumulating, so the rows must tile every path exactly
+bool trunc_backward_tails_available(int d, int depth);
+hipError_t trunc_backward_tails(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                                int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream);
+
 // Time chunks (kernels_chunk.hip): products of chunk signatures and adjoints at chunk boundaries, d a power of two
 bool chunking_available(int d, int depth);
 // forward: Q = terminal = nullptr, coeffs_out [B, |W|] receives the product of the C chunk signatures Sc [B, C, |W|];
 // backward: coeffs_out = nullptr, Pfx [B, C, |W|] receives the signatures up to the end of every chunk (the last one
 // is copied from terminal [B, |W|]) and Q [B, C, |W|] the signatures of the rest of the path after every chunk.
 hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, const float* terminal, float* coeffs_out,
-                      int64_t B, int C, hipStream_t stream);
+                      const float* grad, float* Abar, int64_t B, int C, bool* adjoints_done, hipStream_t stream);
+// (backward, small signatures: when grad [B, |W|] and Abar [B, C, |W|] are given the kernel also forms the boundary
+// adjoints and *adjoints_done is set; otherwise call chunk_adjoint afterwards)
 // Abar [B, C, |W|]: adjoint of the signature at the end of every chunk, from grad [B, |W|] and Q
 hipError_t chunk_adjoint(int d, int depth, const float* grad, const float* Q, float* Abar, int64_t B, int C,
                          hipStream_t stream);

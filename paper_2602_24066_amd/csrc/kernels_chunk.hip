@@ -65,15 +65,46 @@ __device__ __forceinline__ void copy_row(const float* src, float* dst, float* ds
     }
 }
 
+// out(u) = gr(u) + sum_{m >= 1} sum_{|v| = m} gr(u v) q(v) for every word u, by the whole workgroup.  The words of
+// one length k are spread over the workgroup, with blockDim / d^k threads (at most 64, at least 1) sharing the
+// inner sums of a word; for a fixed m the terms of a word are contiguous in gr and in q.
+__device__ __forceinline__ void adjoint_contract(const float* gr, const float* q, float* __restrict__ out, const Levels& g)
+{
+    const int N = g.N;
+    copy_row(gr + g.ls[N], out + g.ls[N], nullptr, g.W - g.ls[N]);       // words of length N
+    for (int k = 1; k < N; ++k) {
+        const int nk = g.ls[k + 1] - g.ls[k];                           // words of length k
+        int tpw = (int)blockDim.x / nk;                                 // threads per word (power of two)
+        tpw = tpw > 64 ? 64 : (tpw < 1 ? 1 : tpw);
+        const int wpp = (int)blockDim.x / tpw;                          // words per pass
+        const int t = threadIdx.x % tpw;
+        for (int i0 = 0; i0 < nk; i0 += wpp) {
+            const int i = i0 + threadIdx.x / tpw;
+            float acc = 0.0f;
+            if (i < nk)
+                for (int m = 1; m <= N - k; ++m) {
+                    const int cnt = 1 << (g.lb * m);
+                    const float* src = gr + g.ls[k + m] + (i << (g.lb * m));
+                    const float* qv = q + g.ls[m];
+                    for (int v = t; v < cnt; v += tpw) acc = fmaf(src[v], qv[v], acc);
+                }
+            for (int off = tpw >> 1; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+            if (i < nk && t == 0) out[g.ls[k] + i] = gr[g.ls[k] + i] + acc;
+        }
+    }
+}
+
 // One workgroup per path.  Forward (Q == nullptr): coeffs_out[b] = S_1 (x) .. (x) S_C.  Backward: Pfx[c] =
 // S_1 (x) .. (x) S_c for c < C and Pfx[C] = terminal[b] (the signature the caller kept), Q[c] = S_{c+1} (x) .. (x) S_C
 // for c < C.  With LDS the running product and the next factor are staged in three rotating LDS buffers of W floats
 // (small signatures); without, the operands are read from the global arrays written in earlier steps, which
-// __syncthreads() makes visible inside the workgroup.
+// __syncthreads() makes visible inside the workgroup.  With LDS and Abar != nullptr the adjoints at the chunk
+// boundaries, Abar[c](u) = sum_v grad(u v) Q[c](v), are formed here as well and Q is
+// not written out; grad is read from global memory there (consecutive threads read consecutive coefficients).
 template <bool LDS>
 __global__ __launch_bounds__(1024) void chunk_scan_kernel(const float* __restrict__ Sc, float* Pfx, float* Q,
-                                                          const float* __restrict__ terminal, float* coeffs_out, int C,
-                                                          Levels g)
+                                                          const float* __restrict__ terminal, float* coeffs_out,
+                                                          const float* __restrict__ grad, float* Abar, int C, Levels g)
 {
     extern __shared__ f4 smem4[];
     float* sm = (float*)smem4;
@@ -84,33 +115,46 @@ __global__ __launch_bounds__(1024) void chunk_scan_kernel(const float* __restric
     const bool bwd = Q != nullptr;
     float* Qb = bwd ? Q + b * C * W : nullptr;
     if constexpr (LDS) {
+        // gridDim.y == 2 (backward): workgroup 0 of a path does the prefix products, workgroup 1 the suffix products
+        // and the adjoints, side by side; otherwise one workgroup does everything in turn
+        const bool do_prefix = gridDim.y == 1 || blockIdx.y == 0;
+        const bool do_suffix = bwd && (gridDim.y == 1 || blockIdx.y == 1);
         float* buf[3] = {sm, sm + W, sm + 2 * W};
-        // prefix products
-        copy_row(S, buf[0], bwd ? P : nullptr, (int)W);
-        const int lastp = bwd ? C - 2 : C - 1;
         int cur = 0;
-        for (int s = 1; s <= lastp; ++s) {
-            const int nb = (cur + 1) % 3, no = (cur + 2) % 3;
-            copy_row(S + (int64_t)s * W, buf[nb], nullptr, (int)W);
-            __syncthreads();
-            float* dst = (!bwd && s == C - 1) ? coeffs_out + b * W : (bwd ? P + (int64_t)s * W : nullptr);
-            tensor_product(buf[cur], buf[nb], buf[no], dst, g);
-            cur = no;
-            __syncthreads();
+        if (do_prefix) {
+            copy_row(S, buf[0], bwd ? P : nullptr, (int)W);
+            const int lastp = bwd ? C - 2 : C - 1;
+            for (int s = 1; s <= lastp; ++s) {
+                const int nb = (cur + 1) % 3, no = (cur + 2) % 3;
+                copy_row(S + (int64_t)s * W, buf[nb], nullptr, (int)W);
+                __syncthreads();
+                float* dst = (!bwd && s == C - 1) ? coeffs_out + b * W : (bwd ? P + (int64_t)s * W : nullptr);
+                tensor_product(buf[cur], buf[nb], buf[no], dst, g);
+                cur = no;
+                __syncthreads();
+            }
+            if (bwd) copy_row(terminal + b * W, P + (int64_t)(C - 1) * W, nullptr, (int)W);
         }
-        if (bwd) {
-            copy_row(terminal + b * W, P + (int64_t)(C - 1) * W, nullptr, (int)W);
+        if (do_suffix) {
+            const float* const gb = grad ? grad + b * W : nullptr;
+            float* const Ab = Abar ? Abar + b * C * W : nullptr;
+            if (Ab) copy_row(gb, Ab + (int64_t)(C - 1) * W, nullptr, (int)W);     // the last chunk's adjoint is grad
             // suffix products
             __syncthreads();
-            copy_row(S + (int64_t)(C - 1) * W, buf[0], Qb + (int64_t)(C - 2) * W, (int)W);
+            copy_row(S + (int64_t)(C - 1) * W, buf[0], Ab ? nullptr : Qb + (int64_t)(C - 2) * W, (int)W);
             cur = 0;
+            if (Ab) {
+                __syncthreads();
+                adjoint_contract(gb, buf[0], Ab + (int64_t)(C - 2) * W, g);
+            }
             for (int q = C - 3; q >= 0; --q) {
                 const int nb = (cur + 1) % 3, no = (cur + 2) % 3;
                 copy_row(S + (int64_t)(q + 1) * W, buf[nb], nullptr, (int)W);
                 __syncthreads();
-                tensor_product(buf[nb], buf[cur], buf[no], Qb + (int64_t)q * W, g);
+                tensor_product(buf[nb], buf[cur], buf[no], Ab ? nullptr : Qb + (int64_t)q * W, g);
                 cur = no;
                 __syncthreads();
+                if (Ab) adjoint_contract(gb, buf[cur], Ab + (int64_t)q * W, g);
             }
         }
     } else {
@@ -174,28 +218,7 @@ __global__ __launch_bounds__(512) void chunk_adjoint_kernel(const float* __restr
         gr = sm;
         q = sm + W;
     }
-    const int N = g.N;
-    copy_row(gr + g.ls[N], out + g.ls[N], nullptr, W - g.ls[N]);       // words of length N
-    for (int k = 1; k < N; ++k) {
-        const int nk = g.ls[k + 1] - g.ls[k];                           // words of length k
-        int tpw = (int)blockDim.x / nk;                                 // threads per word (power of two)
-        tpw = tpw > 64 ? 64 : (tpw < 1 ? 1 : tpw);
-        const int wpp = (int)blockDim.x / tpw;                          // words per pass
-        const int t = threadIdx.x % tpw;
-        for (int i0 = 0; i0 < nk; i0 += wpp) {
-            const int i = i0 + threadIdx.x / tpw;
-            float acc = 0.0f;
-            if (i < nk)
-                for (int m = 1; m <= N - k; ++m) {
-                    const int cnt = 1 << (g.lb * m);
-                    const float* src = gr + g.ls[k + m] + (i << (g.lb * m));
-                    const float* qv = q + g.ls[m];
-                    for (int v = t; v < cnt; v += tpw) acc = fmaf(src[v], qv[v], acc);
-                }
-            for (int off = tpw >> 1; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-            if (i < nk && t == 0) out[g.ls[k] + i] = gr[g.ls[k] + i] + acc;
-        }
-    }
+    adjoint_contract(gr, q, out, g);
 }
 
 constexpr size_t kMaxChunkLds = 96 * 1024;       // three signatures of up to 8,192 coefficients
@@ -228,11 +251,13 @@ bool chunking_available(int d, int depth)
 }
 
 hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, const float* terminal, float* coeffs_out,
-                      int64_t B, int C, hipStream_t stream)
+                      const float* grad, float* Abar, int64_t B, int C, bool* adjoints_done, hipStream_t stream)
 {
+    if (adjoints_done) *adjoints_done = false;
     Levels g;
     if (!make_levels(d, depth, g) || C < 2 || B < 1 || B > 0x7fffffff) return hipErrorInvalidValue;
     if ((Q != nullptr) != (terminal != nullptr) || (Q == nullptr) == (coeffs_out == nullptr)) return hipErrorInvalidValue;
+    const bool fuse = Q != nullptr && grad != nullptr && Abar != nullptr;
     const size_t lds = 3 * (size_t)g.W * sizeof(float);
     if (lds <= kMaxChunkLds) {
         static bool attr_set = false;            // raising the dynamic LDS limit is needed once per process
@@ -242,7 +267,9 @@ hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, c
             if (e != hipSuccess) return e;
             attr_set = true;
         }
-        chunk_scan_kernel<true><<<(unsigned)B, 1024, lds, stream>>>(Sc, Pfx, Q, terminal, coeffs_out, C, g);
+        chunk_scan_kernel<true><<<dim3((unsigned)B, fuse ? 2 : 1), 1024, lds, stream>>>(
+            Sc, Pfx, Q, terminal, coeffs_out, fuse ? grad : nullptr, fuse ? Abar : nullptr, C, g);
+        if (fuse && adjoints_done) *adjoints_done = true;
     } else if (Q == nullptr && B <= 65535) {
         // forward with large signatures: one grid-wide product per chunk boundary
         const int64_t W = g.W;
@@ -258,7 +285,7 @@ hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, c
             acc_stride = dst_stride;
         }
     } else {
-        chunk_scan_kernel<false><<<(unsigned)B, 1024, 0, stream>>>(Sc, Pfx, Q, terminal, coeffs_out, C, g);
+        chunk_scan_kernel<false><<<(unsigned)B, 1024, 0, stream>>>(Sc, Pfx, Q, terminal, coeffs_out, nullptr, nullptr, C, g);
     }
     return hipGetLastError();
 }

@@ -1018,6 +1018,310 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Backward with one wavefront per row for d = 4: a lane holds a word of length N - 3 (64 of them) and, in
+// registers, its D children of length N - 2 ("tails", letter = register index, the same in every lane); the two
+// levels below every tail run on the matrix cores as in trunc_mfma_bwd_kernel.  Compared with four wavefronts per
+// row that each hold one tail per lane, the chain above the tails is computed once instead of four times and
+// the four tails are independent instruction streams for the lone wavefront; rows are (path, time chunk) pairs,
+// so the launcher cuts short batches into chunks to fill the chip.  No other wavefront writes the gradient of
+// this row's segments: the tile is flushed with plain stores.
+template <int D, int N, int T>
+struct TailsLds {
+    static constexpr int KL = N - 3;
+    static constexpr int NC = (N + 3) / 4 * 4;
+    static constexpr int NSRC = D + 1 + KL;             // tails, slice/leaf letters, per-lane chain letters
+    static constexpr int OFF_E = 0;
+    static constexpr int OFF_EC = OFF_E + T * 2 * D;
+    static constexpr int OFF_GT = OFF_EC + T * D * NC;
+    static constexpr int OFF_VB = OFF_GT + T * D;
+    static constexpr int PER_WAVE = OFF_VB + NSRC * T * kWave;
+    static_assert(OFF_EC % 4 == 0 && OFF_GT % 4 == 0 && OFF_VB % 4 == 0 && PER_WAVE % 4 == 0, "16-byte alignment");
+    static constexpr size_t BYTES = (size_t)kWavesPerBlock * PER_WAVE * sizeof(float);
+};
+
+// V[NS][T][64]: source s holds, for every segment, one value per lane, and all 64 lanes contribute to letter s.
+// Lane s T + tt sums the row (s, tt) and adds it to gt[tt][s].
+template <int NS, int T>
+__device__ __forceinline__ void tile_reduce_uniform(const float* V, float* gt, int D, int lane)
+{
+    static_assert(NS * T <= kWave, "one lane per (source, segment)");
+    if (lane < NS * T) {
+        const v4f* row = (const v4f*)(V + lane * kWave);
+        v4f acc = row[0];
+#pragma unroll
+        for (int i = 1; i < kWave / 4; ++i) acc += row[i];
+        gt[(lane % T) * D + lane / T] += (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    }
+}
+
+template <int D, int KL, int T, int KI>
+__device__ __forceinline__ void lane_chain_tile_reduce(const float* Vsrc, float* gt, int lane, const int (&letter)[KL])
+{
+    if constexpr (KI < KL) {
+        tile_reduce<chain_keep_mask(ilog2(D), KL, KI), T>(Vsrc + KI * T * kWave, gt, D, lane, letter[KI]);
+        lane_chain_tile_reduce<D, KL, T, KI + 1>(Vsrc, gt, lane, letter);
+    }
+}
+
+template <int D, int N, int T>
+__global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_tails_bwd_kernel(
+    const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
+    int64_t P, int64_t C, int64_t Lc, float* __restrict__ gdx)
+{
+    static_assert(D == 4, "one group of four letters");
+    constexpr int K = N - 2;                          // length of the tail words
+    constexpr int KL = K - 1;                         // letters held per lane
+    static_assert(ipow(D, KL) == kWave, "64 words of length N - 3, one per lane");
+    constexpr int NC = (N + 3) / 4 * 4;
+    constexpr int EPL = (T * D + kWave - 1) / kWave;
+    using LY = TailsLds<D, N, T>;
+    extern __shared__ v4f bwd_smem[];
+
+    const int lane = threadIdx.x % kWave;
+    const int wib = threadIdx.x / kWave;
+    const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + wib;
+    if (row >= B * C) return;                         // no workgroup barriers below
+    float* const lds = (float*)bwd_smem + wib * LY::PER_WAVE;            // wave-private
+    float (*E)[2][D] = (float (*)[2][D])(lds + LY::OFF_E);
+    float (*Ec)[D][NC] = (float (*)[D][NC])(lds + LY::OFF_EC);
+    float* gt = lds + LY::OFF_GT;
+    float* Vb = lds + LY::OFF_VB;
+    const int64_t b = row / C;
+    const int64_t seg0 = (row - b * C) * Lc;
+    int letter[KL];
+    {
+        int q = lane;
+#pragma unroll
+        for (int k = KL - 1; k >= 0; --k) { letter[k] = q % D; q /= D; }
+    }
+    const float* X = path + (b * P + seg0) * D;
+    const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
+    const int64_t nW = level_start(D, N) + ipow(D, N);
+    const float* cf = coeffs + row * nW;
+    const float* gr = grad + row * nW;
+
+    // ---- state
+    float Sc[KL], Ac[KL];                  // per-lane chain: signature and adjoint (adjoint only in the owning lane)
+    float St[D], At[D];                    // tails
+    v4f S1[D], A1[D];                      // slice level: children of the tails (child layout)
+    v4f S2[D][4], Ac4[D][4];               // leaves (child layout); their adjoints are constant
+    float An[D][4][D];                     // leaf adjoints, node layout (lane = slice word)
+    {
+        int phi = 0;
+#pragma unroll
+        for (int k = 1; k <= KL; ++k) {
+            phi = phi * D + letter[k - 1];
+            const bool owner = lane % ipow(D, KL - k) == 0;
+            Sc[k - 1] = cf[level_start(D, k) + phi];
+            Ac[k - 1] = owner ? gr[level_start(D, k) + phi] : 0.0f;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+        St[i] = cf[level_start(D, K) + lane * D + i];
+        At[i] = gr[level_start(D, K) + lane * D + i];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            // slice word of register r in this lane: child (letter lane % 4) of tail i of lane 4 blk + r
+            const int ph = (((lane & ~3) + r) * D + i) * D + (lane & 3);
+            S1[i][r] = cf[level_start(D, N - 1) + ph];
+            A1[i][r] = gr[level_start(D, N - 1) + ph];
+#pragma unroll
+            for (int j = 0; j < D; ++j) An[i][r][j] = gr[level_start(D, N) + ph * D + j];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                // leaf of register (r, rr) in this lane: child (letter lane % 4) of the slice word (r, lane 4 blk + rr)
+                const int pl = ((((lane & ~3) + r) * D + i) * D + rr) * D + (lane & 3);
+                S2[i][r][rr] = cf[level_start(D, N) + pl];
+                Ac4[i][r][rr] = gr[level_start(D, N) + pl];
+            }
+        }
+    }
+
+    float dxn[EPL];
+    auto fetch = [&](int64_t j0) {
+#pragma unroll
+        for (int q = 0; q < EPL; ++q) {
+            const int e = (lane + q * kWave) < T * D ? lane + q * kWave : T * D - 1;
+            int64_t jj = j0 + e / D;
+            const bool ok = jj >= 0 && jj < L;
+            jj = jj < 0 ? 0 : (jj < L ? jj : L - 1);
+            const int i = e % D;
+            const float x1 = X[(jj + 1) * D + i], x0 = X[jj * D + i];
+            dxn[q] = ok ? x1 - x0 : 0.0f;
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int q = 0; q < EPL; ++q) {
+            const int e = lane + q * kWave;
+            if (e < T * D) {
+#pragma unroll
+                for (int t = 0; t < N; ++t) {
+                    const float v = dxn[q] * inv1(t);
+                    if (t < 2) E[e / D][t][e % D] = v;
+                    Ec[e / D][e % D][t] = v;
+                }
+            }
+        }
+    };
+    const v4f zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    const float one = 1.0f;
+    // matrix-core B operand: lanes 0..15 carry dX^{(lane % 4)}, lanes 16..31 dX^{(lane % 4)} / 2
+    const int offB = lane < 32 ? (lane / 16) * D + (lane & 3) : 0;
+
+    auto step = [&](int row_t) {
+        const float* Et = &E[row_t][0][0];
+        float ec[KL][NC];
+#pragma unroll
+        for (int k = 0; k < KL; ++k) {
+            const float* src = &Ec[row_t][letter[k]][0];
+#pragma unroll
+            for (int t = 0; t <= N - (k + 1); ++t) ec[k][t] = src[t];
+        }
+        float e4[D][3];                               // dX^{(i)} / (t + 1), the same in every lane
+#pragma unroll
+        for (int i = 0; i < D; ++i)
+#pragma unroll
+            for (int t = 0; t < 3; ++t) e4[i][t] = Ec[row_t][i][t];
+        const float bs = Et[offB], nbs = -bs;
+        const float b0v = Et[lane & 3], b1v = 0.5f * b0v;
+
+        // 1. reconstruction with -dX, 2. accumulators with +dX (per-lane chain)
+        float am[KL + 1][N + 2], ap[KL + 1][N + 2];
+#pragma unroll
+        for (int t = 0; t < N + 2; ++t) am[0][t] = ap[0][t] = 1.0f;
+#pragma unroll
+        for (int k = 1; k <= KL; ++k) {
+#pragma unroll
+            for (int t = 1; t <= N - k; ++t) am[k][t] = fmaf(-ec[k - 1][t], am[k - 1][t + 1], Sc[k - 1]);
+            Sc[k - 1] = fmaf(-ec[k - 1][0], am[k - 1][1], Sc[k - 1]);
+#pragma unroll
+            for (int t = 1; t <= N - k; ++t) ap[k][t] = fmaf(ec[k - 1][t], ap[k - 1][t + 1], Sc[k - 1]);
+        }
+        float gbL[4] = {0.0f, 0.0f, 0.0f, 0.0f};      // gbar of the lane's word from its tails, t = 1..3
+        float ysum = 0.0f;                            // gradient of letter lane % 4 from slice words and leaves
+        float* vb = Vb + row_t * kWave + lane;
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            // tail i: reconstruction
+            const float am1 = fmaf(-e4[i][1], am[KL][2], St[i]);
+            const float am2 = fmaf(-e4[i][2], am[KL][3], St[i]);
+            St[i] = fmaf(-e4[i][0], am[KL][1], St[i]);
+            const v4f Gm = mfma4(am2, nbs, S1[i], 1);
+            S1[i] = mfma4(am1, nbs, S1[i], 0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S2[i][r] = mfma4(Gm[r], nbs, S2[i][r], 0);
+            // accumulators
+            const float ap1 = fmaf(e4[i][1], ap[KL][2], St[i]);
+            const float ap2 = fmaf(e4[i][2], ap[KL][3], St[i]);
+            const v4f Gp = mfma4(ap2, bs, S1[i], 1);                          // A+[1] of the slice words
+            const v4f Pb1 = __builtin_amdgcn_mfma_f32_4x4x1f32(ap1, one, zero4, 0, 0, 0);          // parent values in
+            const v4f Pb2 = __builtin_amdgcn_mfma_f32_4x4x1f32(0.5f * ap2, one, zero4, 0, 0, 0);   // the child layout
+            // 3a. leaves, 3b. slice words
+            float gc = 0.0f, M1[4], M2[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float h = 0.0f;
+#pragma unroll
+                for (int j = 0; j < D; ++j) h = fmaf(e4[j][0], An[i][r][j], h);    // gbar[1] of the slice word
+                const v4f Pb = __builtin_amdgcn_mfma_f32_4x4x1f32(Gp[r], one, zero4, 0, 0, 0);
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) gc = fmaf(Ac4[i][r][rr], Pb[rr], gc);
+                const float q0 = A1[i][r];
+                gc = fmaf(q0, Pb1[r], gc);
+                gc = fmaf(h, Pb2[r], gc);
+                M1[r] = b0v * q0;
+                M2[r] = b1v * h;
+                A1[i][r] = q0 + h;
+            }
+            ysum += gc;
+            // 3c. the tail word itself: gbar[0] = its adjoint, gbar[1], gbar[2] pushed up from its children
+            const float g0 = At[i];
+            const float g1 = quad_transpose_reduce(M1, lane);
+            const float g2 = quad_transpose_reduce(M2, lane);
+            At[i] = g0 + g1 + g2;
+            float gct = g0 * ap[KL][1];
+            gct = fmaf(g1 * inv1(1), ap[KL][2], gct);
+            gct = fmaf(g2 * inv1(2), ap[KL][3], gct);
+            vb[i * T * kWave] = gct;                                          // letter i, every lane
+            gbL[1] = fmaf(e4[i][0], g0, gbL[1]);
+            gbL[2] = fmaf(e4[i][1], g1, gbL[2]);
+            gbL[3] = fmaf(e4[i][2], g2, gbL[3]);
+        }
+        vb[D * T * kWave] = ysum;                                             // letter lane % 4
+        // 3d. per-lane chain
+        float gb[KL + 1][N + 2];
+#pragma unroll
+        for (int k = 0; k <= KL; ++k)
+#pragma unroll
+            for (int t = 0; t < N + 2; ++t) gb[k][t] = 0.0f;
+#pragma unroll
+        for (int t = 1; t <= 3; ++t) gb[KL][t] = gbL[t];
+#pragma unroll
+        for (int k = KL; k >= 1; --k) {
+            gb[k][0] = Ac[k - 1];
+            float gc = 0.0f, asum = 0.0f;
+#pragma unroll
+            for (int t = 0; t <= N - k; ++t) {
+                const float q = gb[k][t];
+                asum += q;
+                gc = fmaf(q * inv1(t), ap[k - 1][t + 1], gc);
+                gb[k - 1][t + 1] = fmaf(ec[k - 1][t], q, gb[k - 1][t + 1]);
+            }
+            Ac[k - 1] = asum;
+            vb[(D + 1 + (k - 1)) * T * kWave] = gc;                            // letter[k - 1]
+        }
+    };
+
+    const int64_t ntiles = (L + T - 1) / T;
+    for (int e = lane; e < T * D; e += kWave) gt[e] = 0.0f;
+    fetch((ntiles - 1) * T);
+    for (int64_t n = ntiles - 1; n >= 0; --n) {
+        wave_lds_fence();
+        stage();
+        wave_lds_fence();
+        fetch((n - 1) * T);                            // n = 0: out of range, zeros
+#pragma unroll 1
+        for (int tt = T - 1; tt >= 0; --tt) step(tt);
+        wave_lds_fence();
+        tile_reduce_uniform<D, T>(Vb, gt, D, lane);        // the only writer of gt so far: plain read-modify-write
+        wave_lds_fence();
+        tile_reduce<3, T>(Vb + D * T * kWave, gt, D, lane, lane & 3);
+        lane_chain_tile_reduce<D, KL, T, 0>(Vb + (D + 1) * T * kWave, gt, lane, letter);
+        wave_lds_fence();
+        for (int e = lane; e < T * D; e += kWave) {
+            const int64_t sgm = n * T + e / D;
+            if (sgm < L) gdx[(b * (P - 1) + seg0 + n * T) * D + e] = gt[e];
+            gt[e] = 0.0f;
+        }
+    }
+}
+
+template <int D, int N>
+hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
+                                  int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
+{
+    constexpr int T = 8;
+    using LY = TailsLds<D, N, T>;
+    static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
+    const int64_t blocks = (B * C + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    if (LY::BYTES > 64 * 1024) {
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+    }
+    trunc_tails_bwd_kernel<D, N, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C,
+                                                                                                   Lc, gdx);
+    return hipGetLastError();
+}
+
 template <int D, int N, int WQ>
 hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
                                  int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
@@ -1090,6 +1394,17 @@ hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t
 bool trunc_backward_available(int d, int depth)
 {
     return (d == 4 && depth == 6) || (d == 8 && depth == 5) || (d == 16 && depth == 4);
+}
+
+// One wavefront per (path, chunk) row; every segment of every path must be covered by exactly one row (the kernel
+// stores, it does not accumulate).
+bool trunc_backward_tails_available(int d, int depth) { return d == 4 && depth == 6; }
+
+hipError_t trunc_backward_tails(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                                int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
+{
+    if (d == 4 && depth == 6) return launch_trunc_tails_bwd<4, 6>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    return hipErrorInvalidValue;
 }
 
 // gdx: [B, L, d] accumulation buffer, zeroed by the caller

@@ -67,6 +67,20 @@ def test_time_chunks(monkeypatch, d, depth, B, L, chunks):
     check_parity(ws, W, "truncated", depth, X, G, what=f"chunks d={d} N={depth} L={L} C={chunks}")
 
 
+# d = 4 backward with one wavefront per (path, chunk) row, forced for batches that would not select it
+@pytest.mark.parametrize("B,L,chunks", [(3, 97, 3), (5, 17, 0), (130, 40, 0), (2, 160, 5), (1, 1, 0), (70, 64, 2)])
+def test_backward_one_wavefront_per_row(monkeypatch, B, L, chunks):
+    monkeypatch.setenv("SIG_BWD_TAILS", "1")
+    if chunks:
+        monkeypatch.setenv("SIG_CHUNKS", str(chunks))
+    else:
+        monkeypatch.delenv("SIG_CHUNKS", raising=False)
+    ws, W = build_both("truncated", 4, depth=6)
+    X = make_path("time0", 700 + L, B, L, 4)
+    G = make_grad_coeffs(800 + L, B, ws.size)
+    check_parity(ws, W, "truncated", 6, X, G, what=f"tails B={B} L={L} C={chunks}")
+
+
 def test_chunked_and_unchunked_agree(monkeypatch):
     ws, W = build_both("truncated", 4, depth=6)
     X = make_path("time0", 11, 4, 128, 4)
