@@ -99,7 +99,7 @@ def roofline_entry(flops, ms, kernel=""):
     their multiply-adds as fp32 matrix-core instructions (dense fp32 MFMA peak = FP32 vector peak = 157.3 TFLOP/s);
     the run-time specialised and table-driven kernels use the vector ALU only."""
     ach = flops / (ms * 1e-3) / 1e12
-    return {"bound": "mfma" if kernel.startswith("trunc_mfma") else "alu", "achieved": round(ach, 3),
+    return {"bound": "mfma" if kernel.startswith("trunc_") else "alu", "achieved": round(ach, 3),
             "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_FP32_VECTOR_TFLOPS, 4),
             "traffic": None}
 
@@ -178,10 +178,11 @@ def main():
     sec, ms_f, ms_b, call_f, call_b = time_steps(S, torch, st, args.steps, args.warmup)
     work = wl.B * wl.L * ws.size
     ff, fb = flops_forward(ws, wl.B, wl.L), flops_backward(ws, wl.B, wl.L)
-    rf, rb = roofline_entry(ff, ms_f, ws.kernel_name(False)), roofline_entry(fb, ms_b, ws.kernel_name(True))
+    kn_f, kn_b = ws.kernel_name(False, wl.B, wl.L + 1), ws.kernel_name(True, wl.B, wl.L + 1)
+    rf, rb = roofline_entry(ff, ms_f, kn_f), roofline_entry(fb, ms_b, kn_b)
     dominant = rb if ms_b >= ms_f else rf
     dominant = dict(dominant)
-    dominant["kernel"] = ws.kernel_name(ms_b >= ms_f)
+    dominant["kernel"] = kn_b if ms_b >= ms_f else kn_f
     dominant["kernel_ms"] = round(max(ms_b, ms_f), 4)
     dominant["algorithmic_flops_per_launch"] = fb if ms_b >= ms_f else ff
     dominant["traffic"] = measured_traffic(dominant["kernel"], wl.name)
@@ -199,10 +200,10 @@ def main():
                    "min_fma_per_path_step": ws.min_fma_per_step},
         # call_ms: GPU time of everything sig_forward / sig_backward enqueue (main kernel + transposes, chunk products,
         # chain rule); roofline_frac prices the algorithmic flops against that whole time
-        "forward": {"kernel": ws.kernel_name(False), "kernel_ms": round(ms_f, 4), "call_ms": round(call_f, 4),
+        "forward": {"kernel": kn_f, "kernel_ms": round(ms_f, 4), "call_ms": round(call_f, 4),
                     "coeff_steps_per_s": round(work / (call_f * 1e-3), 1),
                     "roofline_frac": roofline_entry(ff, call_f)["frac"], "main_kernel_roofline_frac": rf["frac"]},
-        "backward": {"kernel": ws.kernel_name(True), "kernel_ms": round(ms_b, 4), "call_ms": round(call_b, 4),
+        "backward": {"kernel": kn_b, "kernel_ms": round(ms_b, 4), "call_ms": round(call_b, 4),
                      "coeff_steps_per_s": round(work / (call_b * 1e-3), 1),
                      "roofline_frac": roofline_entry(fb, call_b)["frac"], "main_kernel_roofline_frac": rb["frac"]},
         "roofline": dominant,
@@ -225,7 +226,7 @@ def main():
                 "fwd_bwd_coeff_steps_per_s": round(wk / ((f2 + b2) * 1e-3), 1),
                 "fwd_roofline_frac": roofline_entry(flops_forward(w2, wl2.B, wl2.L), f2)["frac"],
                 "bwd_roofline_frac": roofline_entry(flops_backward(w2, wl2.B, wl2.L), b2)["frac"],
-                "kernels": [w2.kernel_name(False), w2.kernel_name(True)],
+                "kernels": [w2.kernel_name(False, wl2.B, wl2.L + 1), w2.kernel_name(True, wl2.B, wl2.L + 1)],
             }
             if name == "c5":
                 per[name]["peak_device_bytes"] = int(torch.cuda.max_memory_allocated() - base)

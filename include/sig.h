@@ -180,6 +180,8 @@ const char* sig_version(void);
 /* Name of the kernel family sig_forward / sig_backward will launch for this set ("generic", "trunc<d,N>", ...);
  * lets a benchmark say which kernel its numbers belong to. */
 const char* sig_wordset_kernel_name(const sig_wordset* ws, int backward);
+/* The same for a given batch: which main kernel sig_forward / sig_backward launch for B paths of n_points points. */
+const char* sig_kernel_name(const sig_wordset* ws, int backward, int64_t B, int64_t n_points);
 
 #ifdef __cplusplus
 }

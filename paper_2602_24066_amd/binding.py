@@ -81,6 +81,7 @@ def load_library():
     sig("sig_last_hip_error", c_int, [])
     sig("sig_version", ctypes.c_char_p, [])
     sig("sig_wordset_kernel_name", ctypes.c_char_p, [c_p, c_int])
+    sig("sig_kernel_name", ctypes.c_char_p, [c_p, c_int, c_i64, c_i64])
     _lib = lib
     return lib
 
@@ -158,7 +159,10 @@ class WordSet:
     def kernel_fma_per_step(self, backward: bool = False) -> int:
         return int(self._lib.sig_wordset_kernel_fma_per_step(self._h, int(backward)))
 
-    def kernel_name(self, backward: bool = False) -> str:
+    def kernel_name(self, backward: bool = False, B: int = 0, n_points: int = 0) -> str:
+        """Kernel family for this set; with B and n_points the main kernel that batch would launch."""
+        if B > 0 and n_points > 1:
+            return self._lib.sig_kernel_name(self._h, int(backward), B, n_points).decode()
         return self._lib.sig_wordset_kernel_name(self._h, int(backward)).decode()
 
     def plan_count(self, backward: bool = False) -> int:

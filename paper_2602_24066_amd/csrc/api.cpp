@@ -92,28 +92,30 @@ Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points)
     return Chunks{(L + Lc - 1) / Lc, Lc};
 }
 // Backward launch shape for a full truncation.  d = 4 has a second kernel with one wavefront per (path, chunk) row
-// that does half the vector work per path; it needs about a thousand rows to fill the chip, so shorter batches are
-// cut into time chunks for it (SIG_BWD_TAILS=0/1 forces the choice).
-struct BwdShape { bool tails; int64_t C, Lc; };
+// that does half the vector work per path; it needs about a thousand rows to fill the chip.  Batches of up to 768
+// paths take its fused form (2 or 4 chunks of a path in one workgroup, everything between the chunks in LDS); larger
+// ones run it unchunked.  SIG_BWD_TAILS=0 switches it off, =1 takes the unfused form with chunk arrays in HBM
+// (SIG_CHUNKS chunks), =2 / =4 force the fused form with that many chunks.
+struct BwdShape { bool tails, fused; int64_t C, Lc; };
 BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points)
 {
     const int64_t L = n_points - 1;
     const Chunks ch = trunc_chunks(w, 1, B, n_points);
-    BwdShape s{false, ch.C, ch.Lc};
+    BwdShape s{false, false, ch.C, ch.Lc};
     if (!sig::trunc_backward_tails_available(w.d, w.depth)) return s;
     const char* force = std::getenv("SIG_BWD_TAILS");
-    if (force && force[0] == '0') return s;
-    const char* ce = std::getenv("SIG_CHUNKS");
-    int64_t C = ch.C;
-    if (!(ce && ce[0])) {
-        C = std::max<int64_t>(1, std::min<int64_t>((1024 + B - 1) / std::max<int64_t>(B, 1), L / 32));
-        C = std::min<int64_t>(C, 64);
-        if (!sig::chunking_available(w.d, w.depth)) C = 1;
+    const int f = (force && force[0]) ? std::atoi(force) : -1;
+    if (f == 0) return s;
+    if (f == 1) return BwdShape{true, false, ch.C, ch.Lc};
+    int64_t C = f == 2 || f == 4 ? f : (B <= 384 ? 4 : (B < 768 ? 2 : 1));
+    while (C > 1 && L < 8 * C) C /= 2;                       // chunks of at least 8 segments
+    if (C == 1) {
+        if (f == -1 && B < 768 && ch.C == 1) return s;       // too few rows for one wavefront per path
+        return BwdShape{true, false, f == -1 ? 1 : ch.C, f == -1 ? L : ch.Lc};
     }
     const int64_t Lc = (L + C - 1) / C;
-    C = (L + Lc - 1) / Lc;
-    if (!(force && force[0] == '1') && B * C < 768) return s;
-    return BwdShape{true, C, Lc};
+    if ((C - 1) * Lc >= L) return s;
+    return BwdShape{true, true, C, Lc};
 }
 size_t chunk_array_bytes(const sig::WordSet& w, int64_t B, int64_t C)
 {
@@ -410,7 +412,7 @@ size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_
     n = (n + 255) & ~(size_t)255;                                   // gradient with respect to the increments
     if (use_trunc_backward(w, B)) {
         const BwdShape ch = trunc_backward_shape(w, B, n_points);
-        if (ch.C > 1) n += 4 * chunk_array_bytes(w, B, ch.C);       // chunk signatures, prefixes, suffixes, adjoints
+        if (ch.C > 1 && !ch.fused) n += 4 * chunk_array_bytes(w, B, ch.C);   // chunk signatures, prefixes, suffixes, adjoints
     } else if (jit_enabled(w)) {                                    // + transposed increments
         n += jit_dxt_bytes(w, B, n_points, 1);
     }
@@ -514,7 +516,7 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     CallTimer whole(1, st);
     hipError_t e = hipSuccess;
     const bool trunc = use_trunc_backward(w, B);
-    const BwdShape ch = trunc ? trunc_backward_shape(w, B, n_points) : BwdShape{false, 1, n_points - 1};
+    const BwdShape ch = trunc ? trunc_backward_shape(w, B, n_points) : BwdShape{false, false, 1, n_points - 1};
     if (!ch.tails) {                     // the one-wavefront-per-row kernel stores every entry itself
         e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
         if (e != hipSuccess) return hip_fail(e);
@@ -522,7 +524,7 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     if (trunc) {
         const float* row_coeffs = coeffs;
         const float* row_grad = grad_coeffs;
-        if (ch.C > 1) {
+        if (ch.C > 1 && !ch.fused) {
             if ((((uintptr_t)coeffs | (uintptr_t)grad_coeffs) & 15) != 0) return SIG_EINVAL;
             // chunk signatures (recomputed: only the terminal signature was kept), then the signature and the
             // adjoint at the end of every chunk
@@ -544,7 +546,8 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
         }
         hipEvent_t* pe = g_prof.next(1);
         if (pe) (void)hipEventRecord(pe[0], st);
-        if (ch.tails) e = sig::trunc_backward_tails(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
+        if (ch.fused) e = sig::trunc_backward_tails_fused(w.d, w.depth, path, coeffs, grad_coeffs, B, n_points, ch.C, ch.Lc, gdx, st);
+        else if (ch.tails) e = sig::trunc_backward_tails(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
         else e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
@@ -641,6 +644,20 @@ const char* sig_wordset_kernel_name(const sig_wordset* ws, int backward)
     if (!backward && use_trunc_forward(*W(ws), 1)) return "trunc_mfma_fwd_kernel";
     if (backward && use_trunc_backward(*W(ws), 1)) return "trunc_mfma_bwd_kernel";
     if (jit_enabled(*W(ws))) return backward ? "sig_bwd_jit" : "sig_fwd_jit";
+    return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";
+}
+
+const char* sig_kernel_name(const sig_wordset* ws, int backward, int64_t B, int64_t n_points)
+{
+    if (!ws || !W(ws)->kernels_supported) return "unsupported";
+    const sig::WordSet& w = *W(ws);
+    if (B < 1 || n_points < 2) return sig_wordset_kernel_name(ws, backward);
+    if (!backward && use_trunc_forward(w, B)) return "trunc_mfma_fwd_kernel";
+    if (backward && use_trunc_backward(w, B)) {
+        const BwdShape sh = trunc_backward_shape(w, B, n_points);
+        return sh.tails ? "trunc_tails_bwd_kernel" : "trunc_mfma_bwd_kernel";
+    }
+    if (jit_enabled(w)) return backward ? "sig_bwd_jit" : "sig_fwd_jit";
     return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";
 }
 

@@ -1026,18 +1026,27 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
 // the four tails are independent instruction streams for the lone wavefront; rows are (path, time chunk) pairs,
 // so the launcher cuts short batches into chunks to fill the chip.  No other wavefront writes the gradient of
 // this row's segments: the tile is flushed with plain stores.
-template <int D, int N, int T>
+// CW = 0: rows are (path, chunk) pairs whose start signature and adjoint come from global arrays; every wavefront
+// of a workgroup is an independent row.  CW = 2 or 4 ("fused"): a workgroup is one path and its CW wavefronts are
+// the CW chunks of it; the chunk signatures, their products and the adjoints at the chunk boundaries are formed inside
+// the kernel and exchanged through LDS, so that nothing but path, terminal signature and gradient is read from HBM.
+template <int D, int N, int T, int CW>
 struct TailsLds {
     static constexpr int KL = N - 3;
     static constexpr int NC = (N + 3) / 4 * 4;
+    static constexpr int NWV = CW ? CW : kWavesPerBlock;                     // wavefronts per workgroup
     static constexpr int NSRC = D + 1 + KL;             // tails, slice/leaf letters, per-lane chain letters
-    static constexpr int OFF_E = 0;
-    static constexpr int OFF_EC = OFF_E + T * 2 * D;
-    static constexpr int OFF_GT = OFF_EC + T * D * NC;
-    static constexpr int OFF_VB = OFF_GT + T * D;
-    static constexpr int PER_WAVE = OFF_VB + NSRC * T * kWave;
-    static_assert(OFF_EC % 4 == 0 && OFF_GT % 4 == 0 && OFF_VB % 4 == 0 && PER_WAVE % 4 == 0, "16-byte alignment");
-    static constexpr size_t BYTES = (size_t)kWavesPerBlock * PER_WAVE * sizeof(float);
+    static constexpr int W = level_start(D, N) + ipow(D, N);
+    static constexpr int TILE = T * 2 * D + T * D * NC;                      // E, Ec of one wavefront
+    static constexpr int RED = T * D + NSRC * T * kWave;                     // gt, Vb of one wavefront
+    // fused: area A holds first the CW + 2 signature buffers, later the reduction regions; the tiles come after it
+    static constexpr int AREA_A = CW ? ((CW + 2) * W > CW * RED ? (CW + 2) * W : CW * RED) : 0;
+    static constexpr int OFF_G = AREA_A + CW * TILE;                          // fused: the gradient row of the path
+    static constexpr int TOTAL = CW ? OFF_G + W : NWV * (TILE + RED);
+    static_assert(TILE % 4 == 0 && RED % 4 == 0 && AREA_A % 4 == 0 && W % 4 == 0, "16-byte alignment");
+    static constexpr size_t BYTES = (size_t)TOTAL * sizeof(float);
+    __device__ static float* tile(float* base, int wib) { return base + (CW ? AREA_A + wib * TILE : wib * (TILE + RED)); }
+    __device__ static float* red(float* base, int wib) { return base + (CW ? wib * RED : wib * (TILE + RED) + TILE); }
 };
 
 // V[NS][T][64]: source s holds, for every segment, one value per lane, and all 64 lanes contribute to letter s.
@@ -1064,8 +1073,63 @@ __device__ __forceinline__ void lane_chain_tile_reduce(const float* Vsrc, float*
     }
 }
 
-template <int D, int N, int T>
-__global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_tails_bwd_kernel(
+// out = a (x) b for signatures in LDS (canonical order), by nthreads threads; four consecutive words of a level
+// share all prefixes and have contiguous suffixes (D = 4: one quad per parent).
+template <int D, int N>
+__device__ __forceinline__ void lds_tensor_product(const float* a, const float* b, float* out, int tid, int nthreads)
+{
+    constexpr int LB = ilog2(D);
+#pragma unroll
+    for (int n = 1; n <= N; ++n) {
+        const int ls_n = level_start(D, n);
+        const int quads = ipow(D, n) / 4;
+        for (int qd = tid; qd < quads; qd += nthreads) {
+            const int i = 4 * qd;
+            v4f acc = *(const v4f*)(a + ls_n + i) + *(const v4f*)(b + ls_n + i);
+#pragma unroll
+            for (int k = 1; k < n; ++k) {
+                const int sh = LB * (n - k);
+                acc += a[level_start(D, k) + (i >> sh)] * *(const v4f*)(b + level_start(D, n - k) + (i & ((1 << sh) - 1)));
+            }
+            *(v4f*)(out + ls_n + i) = acc;
+        }
+    }
+}
+// coefficient of the word (length n, index i) of a (x) b
+template <int D, int N>
+__device__ __forceinline__ float word_product(const float* a, const float* b, int n, int i)
+{
+    constexpr int LB = ilog2(D);
+    float acc = a[level_start(D, n) + i] + b[level_start(D, n) + i];
+#pragma unroll
+    for (int k = 1; k < N; ++k)
+        if (k < n) {
+            const int sh = LB * (n - k);
+            acc = fmaf(a[level_start(D, k) + (i >> sh)], b[level_start(D, n - k) + (i & ((1 << sh) - 1))], acc);
+        }
+    return acc;
+}
+// adjoint of the word u (length n, index i) at a chunk boundary: g(u) + sum_{m >= 1} sum_{|v| = m} g(u v) q(v).
+// `share` lanes (a power of two, consecutive, all holding the same u) split the sums; `sub` is the lane's rank.
+template <int D, int N>
+__device__ __forceinline__ float word_contract(const float* g, const float* q, int n, int i, int sub, int share)
+{
+    constexpr int LB = ilog2(D);
+    float acc = 0.0f;
+#pragma unroll
+    for (int m = 1; m < N; ++m)
+        if (m <= N - n) {
+            const int cnt = 1 << (LB * m);
+            const float* src = g + level_start(D, n + m) + (i << (LB * m));
+            const float* qv = q + level_start(D, m);
+            for (int v = sub; v < cnt; v += share) acc = fmaf(src[v], qv[v], acc);
+        }
+    for (int off = share >> 1; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    return g[level_start(D, n) + i] + acc;
+}
+
+template <int D, int N, int T, int CW>
+__global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tails_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
     int64_t P, int64_t C, int64_t Lc, float* __restrict__ gdx)
 {
@@ -1075,18 +1139,20 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_tails_bwd_kernel
     static_assert(ipow(D, KL) == kWave, "64 words of length N - 3, one per lane");
     constexpr int NC = (N + 3) / 4 * 4;
     constexpr int EPL = (T * D + kWave - 1) / kWave;
-    using LY = TailsLds<D, N, T>;
+    using LY = TailsLds<D, N, T, CW>;
     extern __shared__ v4f bwd_smem[];
 
     const int lane = threadIdx.x % kWave;
     const int wib = threadIdx.x / kWave;
-    const int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + wib;
-    if (row >= B * C) return;                         // no workgroup barriers below
-    float* const lds = (float*)bwd_smem + wib * LY::PER_WAVE;            // wave-private
-    float (*E)[2][D] = (float (*)[2][D])(lds + LY::OFF_E);
-    float (*Ec)[D][NC] = (float (*)[D][NC])(lds + LY::OFF_EC);
-    float* gt = lds + LY::OFF_GT;
-    float* Vb = lds + LY::OFF_VB;
+    const int64_t row = CW ? (int64_t)blockIdx.x * C + wib : (int64_t)blockIdx.x * kWavesPerBlock + wib;
+    if constexpr (CW == 0) {
+        if (row >= B * C) return;                     // no workgroup barriers in this mode
+    }
+    float* const smem = (float*)bwd_smem;
+    float (*E)[2][D] = (float (*)[2][D])(LY::tile(smem, wib));            // wave-private
+    float (*Ec)[D][NC] = (float (*)[D][NC])(LY::tile(smem, wib) + T * 2 * D);
+    float* gt = LY::red(smem, wib);                                       // fused: valid after the signature buffers
+    float* Vb = gt + T * D;                                               // are dead
     const int64_t b = row / C;
     const int64_t seg0 = (row - b * C) * Lc;
     int letter[KL];
@@ -1098,8 +1164,9 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_tails_bwd_kernel
     const float* X = path + (b * P + seg0) * D;
     const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
     const int64_t nW = level_start(D, N) + ipow(D, N);
-    const float* cf = coeffs + row * nW;
-    const float* gr = grad + row * nW;
+    // CW = 0: row arrays; fused: the terminal signature and the gradient of the path
+    const float* cf = coeffs + (CW ? b : row) * nW;
+    const float* gr = grad + (CW ? b : row) * nW;
 
     // ---- state
     float Sc[KL], Ac[KL];                  // per-lane chain: signature and adjoint (adjoint only in the owning lane)
@@ -1107,37 +1174,6 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_tails_bwd_kernel
     v4f S1[D], A1[D];                      // slice level: children of the tails (child layout)
     v4f S2[D][4], Ac4[D][4];               // leaves (child layout); their adjoints are constant
     float An[D][4][D];                     // leaf adjoints, node layout (lane = slice word)
-    {
-        int phi = 0;
-#pragma unroll
-        for (int k = 1; k <= KL; ++k) {
-            phi = phi * D + letter[k - 1];
-            const bool owner = lane % ipow(D, KL - k) == 0;
-            Sc[k - 1] = cf[level_start(D, k) + phi];
-            Ac[k - 1] = owner ? gr[level_start(D, k) + phi] : 0.0f;
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < D; ++i) {
-        St[i] = cf[level_start(D, K) + lane * D + i];
-        At[i] = gr[level_start(D, K) + lane * D + i];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            // slice word of register r in this lane: child (letter lane % 4) of tail i of lane 4 blk + r
-            const int ph = (((lane & ~3) + r) * D + i) * D + (lane & 3);
-            S1[i][r] = cf[level_start(D, N - 1) + ph];
-            A1[i][r] = gr[level_start(D, N - 1) + ph];
-#pragma unroll
-            for (int j = 0; j < D; ++j) An[i][r][j] = gr[level_start(D, N) + ph * D + j];
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-                // leaf of register (r, rr) in this lane: child (letter lane % 4) of the slice word (r, lane 4 blk + rr)
-                const int pl = ((((lane & ~3) + r) * D + i) * D + rr) * D + (lane & 3);
-                S2[i][r][rr] = cf[level_start(D, N) + pl];
-                Ac4[i][r][rr] = gr[level_start(D, N) + pl];
-            }
-        }
-    }
 
     float dxn[EPL];
     auto fetch = [&](int64_t j0) {
@@ -1170,6 +1206,150 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_tails_bwd_kernel
     const float one = 1.0f;
     // matrix-core B operand: lanes 0..15 carry dX^{(lane % 4)}, lanes 16..31 dX^{(lane % 4)} / 2
     const int offB = lane < 32 ? (lane / 16) * D + (lane & 3) : 0;
+
+    // ---- initial state.  sig(n, i): coefficient of the word (length n, index i) the row starts from;
+    // adj(n, i, sub, share): its adjoint (length < N), where `share` consecutive lanes hold the same word.
+    auto load_signature = [&](auto&& sig) {
+        int phi = 0;
+#pragma unroll
+        for (int k = 1; k <= KL; ++k) {
+            phi = phi * D + letter[k - 1];
+            Sc[k - 1] = sig(k, phi);
+        }
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            St[i] = sig(K, lane * D + i);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                // slice word of register r in this lane: child (letter lane % 4) of tail i of lane 4 blk + r
+                const int ph = (((lane & ~3) + r) * D + i) * D + (lane & 3);
+                S1[i][r] = sig(N - 1, ph);
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr)
+                    // leaf of register (r, rr): child (letter lane % 4) of the slice word (r, lane 4 blk + rr)
+                    S2[i][r][rr] = sig(N, ((((lane & ~3) + r) * D + i) * D + rr) * D + (lane & 3));
+            }
+        }
+    };
+    auto load_adjoint = [&](auto&& adj) {
+        int phi = 0;
+#pragma unroll
+        for (int k = 1; k <= KL; ++k) {
+            phi = phi * D + letter[k - 1];
+            const int share = ipow(D, KL - k);                    // lanes holding this word
+            const float v = adj(k, phi, lane % share, share);
+            Ac[k - 1] = lane % share == 0 ? v : 0.0f;             // the adjoint lives in the owning lane only
+        }
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            At[i] = adj(K, lane * D + i, 0, 1);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) A1[i][r] = adj(N - 1, (((lane & ~3) + r) * D + i) * D + (lane & 3), 0, 1);
+        }
+    };
+    // leaf adjoints are the gradient itself at every chunk boundary
+#pragma unroll
+    for (int i = 0; i < D; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int ph = (((lane & ~3) + r) * D + i) * D + (lane & 3);
+#pragma unroll
+            for (int j = 0; j < D; ++j) An[i][r][j] = gr[level_start(D, N) + ph * D + j];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr)
+                Ac4[i][r][rr] = gr[level_start(D, N) + ((((lane & ~3) + r) * D + i) * D + rr) * D + (lane & 3)];
+        }
+
+    if constexpr (CW == 0) {
+        load_signature([&](int n, int i) { return cf[level_start(D, n) + i]; });
+        load_adjoint([&](int n, int i, int, int) { return gr[level_start(D, n) + i]; });
+    } else {
+        constexpr int W = LY::W;
+        float* const SB = smem;                        // SB[c] = signature of chunk c, later partly reused
+        float* const TB = smem + CW * W;               // two more buffers
+        float* const GB = smem + LY::OFF_G;            // the gradient row, read many times by the boundary adjoints
+        for (int o = 4 * (int)threadIdx.x; o < W; o += 4 * CW * kWave) *(v4f*)(GB + o) = *(const v4f*)(gr + o);
+        // phase 1: signature of the own chunk, S <- S (x) exp(dX) segment by segment from the identity
+        load_signature([&](int, int) { return 0.0f; });
+        {
+            const int64_t nt = (L + T - 1) / T;
+            fetch(0);
+            for (int64_t n = 0; n < nt; ++n) {
+                wave_lds_fence();
+                stage();
+                wave_lds_fence();
+                fetch((n + 1) * T);                    // beyond the chunk: zeros
+#pragma unroll 1
+                for (int tt = 0; tt < T; ++tt) {
+                    const float* Et = &E[tt][0][0];
+                    const float bs = Et[offB];
+                    float a[KL + 1][N + 2];
+#pragma unroll
+                    for (int t = 0; t < N + 2; ++t) a[0][t] = 1.0f;
+#pragma unroll
+                    for (int k = 1; k <= KL; ++k) {
+                        const float* src = &Ec[tt][letter[k - 1]][0];
+#pragma unroll
+                        for (int t = 1; t <= N - k; ++t) a[k][t] = fmaf(src[t], a[k - 1][t + 1], Sc[k - 1]);
+                        Sc[k - 1] = fmaf(src[0], a[k - 1][1], Sc[k - 1]);
+                    }
+#pragma unroll
+                    for (int i = 0; i < D; ++i) {
+                        const float a1 = fmaf(Ec[tt][i][1], a[KL][2], St[i]);
+                        const float a2 = fmaf(Ec[tt][i][2], a[KL][3], St[i]);
+                        St[i] = fmaf(Ec[tt][i][0], a[KL][1], St[i]);
+                        const v4f Gq = mfma4(a2, bs, S1[i], 1);
+                        S1[i] = mfma4(a1, bs, S1[i], 0);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) S2[i][r] = mfma4(Gq[r], bs, S2[i][r], 0);
+                    }
+                }
+            }
+        }
+        {   // publish it in canonical order
+            float* out = SB + wib * W;
+            int phi = 0;
+#pragma unroll
+            for (int k = 1; k <= KL; ++k) {
+                phi = phi * D + letter[k - 1];
+                if (lane % ipow(D, KL - k) == 0) out[level_start(D, k) + phi] = Sc[k - 1];
+            }
+#pragma unroll
+            for (int i = 0; i < D; ++i) {
+                out[level_start(D, K) + lane * D + i] = St[i];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    out[level_start(D, N - 1) + (((lane & ~3) + r) * D + i) * D + (lane & 3)] = S1[i][r];
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr)
+                        out[level_start(D, N) + ((((lane & ~3) + r) * D + i) * D + rr) * D + (lane & 3)] = S2[i][r][rr];
+                }
+            }
+        }
+        __syncthreads();
+        // phase 2: what every chunk starts from.  P_c = S_1 (x) .. (x) S_c, Q_c = S_{c+1} (x) .. (x) S_CW.
+        const float* qbuf = nullptr;                   // Q of the own chunk (not for the last one)
+        if constexpr (CW == 4) {
+            lds_tensor_product<D, N>(SB, SB + W, TB, threadIdx.x, CW * kWave);                      // P_2
+            lds_tensor_product<D, N>(SB + 2 * W, SB + 3 * W, TB + W, threadIdx.x, CW * kWave);      // Q_2
+            __syncthreads();
+            lds_tensor_product<D, N>(SB + W, TB + W, SB, threadIdx.x, CW * kWave);                  // Q_1 over S_1: chunk 0
+            __syncthreads();                                                                        // keeps S_1 in registers
+            if (wib == 1) load_signature([&](int n, int i) { return TB[level_start(D, n) + i]; });
+            if (wib == 2) load_signature([&](int n, int i) { return word_product<D, N>(TB, SB + 2 * W, n, i); });
+            qbuf = wib == 0 ? SB : (wib == 1 ? TB + W : SB + 3 * W);
+        } else {
+            static_assert(CW == 2, "two or four chunks per workgroup");
+            qbuf = SB + W;                                                                          // Q_1 = S_2
+        }
+        if (wib == CW - 1) {
+            load_signature([&](int n, int i) { return cf[level_start(D, n) + i]; });                // terminal signature
+            load_adjoint([&](int n, int i, int, int) { return gr[level_start(D, n) + i]; });
+        } else {
+            load_adjoint([&](int n, int i, int sub, int share) { return word_contract<D, N>(GB, qbuf, n, i, sub, share); });
+        }
+        __syncthreads();                               // the buffers are dead: their space takes gt / Vb from here on
+    }
 
     auto step = [&](int row_t) {
         const float* Et = &E[row_t][0][0];
@@ -1299,26 +1479,27 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_tails_bwd_kernel
     }
 }
 
-template <int D, int N>
+template <int D, int N, int CW>
 hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
                                   int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
 {
     constexpr int T = 8;
-    using LY = TailsLds<D, N, T>;
+    using LY = TailsLds<D, N, T, CW>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
-    const int64_t blocks = (B * C + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (CW && C != CW) return hipErrorInvalidValue;
+    const int64_t blocks = CW ? B : (B * C + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    if (LY::BYTES > 64 * 1024) {
+    if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
         static bool attr_set = false;
         if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T, CW>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
             if (e != hipSuccess) return e;
             attr_set = true;
         }
     }
-    trunc_tails_bwd_kernel<D, N, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C,
-                                                                                                   Lc, gdx);
+    trunc_tails_bwd_kernel<D, N, T, CW><<<(unsigned)blocks, kWave * LY::NWV, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C, Lc,
+                                                                                                gdx);
     return hipGetLastError();
 }
 
@@ -1403,7 +1584,18 @@ bool trunc_backward_tails_available(int d, int depth) { return d == 4 && depth =
 hipError_t trunc_backward_tails(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
                                 int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
 {
-    if (d == 4 && depth == 6) return launch_trunc_tails_bwd<4, 6>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (d == 4 && depth == 6) return launch_trunc_tails_bwd<4, 6, 0>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    return hipErrorInvalidValue;
+}
+
+// Fused form: the C (2 or 4) chunks of a path are the wavefronts of one workgroup; coeffs / grad_coeffs are the
+// terminal signature and its gradient [B, |W|], nothing else is needed.  Every chunk must hold at least one segment.
+hipError_t trunc_backward_tails_fused(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs,
+                                      int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
+{
+    if ((C - 1) * Lc >= P - 1) return hipErrorInvalidValue;
+    if (d == 4 && depth == 6 && C == 4) return launch_trunc_tails_bwd<4, 6, 4>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (d == 4 && depth == 6 && C == 2) return launch_trunc_tails_bwd<4, 6, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
     return hipErrorInvalidValue;
 }
 

@@ -81,6 +81,21 @@ def test_backward_one_wavefront_per_row(monkeypatch, B, L, chunks):
     check_parity(ws, W, "truncated", 6, X, G, what=f"tails B={B} L={L} C={chunks}")
 
 
+# ... and its fused form: the 2 or 4 chunks of a path in one workgroup, chunk signatures and boundary adjoints in LDS
+@pytest.mark.parametrize("B,L,chunks", [(3, 97, 4), (1, 33, 4), (5, 64, 4), (2, 35, 4), (3, 17, 2), (70, 40, 2),
+                                        (2, 16, 2), (1, 300, 4)])
+def test_backward_chunks_in_one_workgroup(monkeypatch, B, L, chunks):
+    monkeypatch.setenv("SIG_BWD_TAILS", str(chunks))
+    monkeypatch.delenv("SIG_CHUNKS", raising=False)
+    ws, W = build_both("truncated", 4, depth=6)
+    X = make_path("time0", 900 + L, B, L, 4)
+    G = make_grad_coeffs(950 + L, B, ws.size)
+    lib = S.load_library()
+    gdx = (4 * B * L * 4 + 255) // 256 * 256
+    assert lib.sig_backward_workspace_bytes(ws._h, B, L + 1) == gdx       # no chunk arrays in device memory
+    check_parity(ws, W, "truncated", 6, X, G, what=f"fused tails B={B} L={L} C={chunks}")
+
+
 def test_chunked_and_unchunked_agree(monkeypatch):
     ws, W = build_both("truncated", 4, depth=6)
     X = make_path("time0", 11, 4, 128, 4)
