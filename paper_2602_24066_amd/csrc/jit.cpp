@@ -170,8 +170,9 @@ void emit_forward_unit(std::ostringstream& o, const Plan& plan, int uidx)
     o << "    f4 r[EPT];\n    tile_fetch(dxg, 0, tid, r);\n    tile_stage(tile, tid, r);\n    __syncthreads();\n";
     o << "    for (long n = 0; n < ntiles; ++n) {\n";
     o << "        tile_fetch(dxg, n + 1 < ntiles ? n + 1 : n, tid, r);\n";
-    // the segment loop stays rolled: the bodies of all units together must fit the instruction cache
-    o << "#pragma unroll 1\n        for (int tt = 0; tt < T; ++tt) {\n";
+    // the segment loop is unrolled by two only: the loop bodies of all resident units together must fit the
+    // instruction cache
+    o << "#pragma unroll 2\n        for (int tt = 0; tt < T; ++tt) {\n";
     o << "            const float* dxp = tile + tt * D * 64 + lane;\n";
     emit_step_loads(o, uses, "            ");
     int depth = 0;   // open scopes = length of the current word chain
@@ -222,7 +223,7 @@ void emit_backward_unit(std::ostringstream& o, const Plan& plan, int uidx, int D
     o << "    for (long n = ntiles - 1; n >= 0; --n) {\n";
     o << "        __syncthreads();\n        tile_stage(tile, tid, r);\n        __syncthreads();\n";
     o << "        tile_fetch(dxg, n - 1, tid, r);\n";
-    o << "#pragma unroll 1\n        for (int tt = T - 1; tt >= 0; --tt) {\n";
+    o << "#pragma unroll 2\n        for (int tt = T - 1; tt >= 0; --tt) {\n";
     o << "            const float* dxp = tile + tt * D * 64 + lane;\n";
     emit_step_loads(o, uses, "            ");
     for (int i : uses.letters) o << "            float g" << i << " = 0.0f;\n";
