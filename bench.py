@@ -187,6 +187,10 @@ def main():
     dominant["algorithmic_flops_per_launch"] = fb if ms_b >= ms_f else ff
     dominant["traffic"] = measured_traffic(dominant["kernel"], wl.name)
 
+    # plain v_fma_f32 rate of this chip, measured in the same run (register-only kernel, 32 wavefronts per compute unit):
+    # the roof for vector code that does not use packed FP32
+    dominant["measured_unpacked_fma_tflops"] = round(S.sig_probe_fma_tflops(), 1)
+
     out = {
         "metric": "signature coeff-steps/sec (fwd, fwd+bwd) + % of FP32 vector roofline, 1 GPU",
         "value": round(work / sec, 1),

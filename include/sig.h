@@ -173,6 +173,11 @@ int    sig_backward(const sig_wordset* ws, const float* path, const float* coeff
 int sig_profile_enable(int on);
 int sig_profile_read(int which, int64_t* n_launches, double* total_ms);
 
+/* Vector-ALU rate probe for benchmarks: enqueues a register-only kernel of `blocks` workgroups of 256 threads in
+ * which every thread performs iters * 16 dependent-chain-free fmaf operations (2 * 16 * iters * 256 * blocks
+ * floating-point operations in all) and stores one float; out: device, blocks * 256 floats.  The caller times it. */
+int sig_probe_fma(void* out /*device*/, size_t out_bytes, int blocks, int iters, void* stream);
+
 /* ---- diagnostics ------------------------------------------------------------------------------------- */
 const char* sig_strerror(int code);
 int         sig_last_hip_error(void);          /* hipError_t of the last SIG_EHIP on this thread, else 0 */

@@ -4,5 +4,5 @@ Everything is computed by the HIP kernels behind the C ABI in include/sig.h; thi
 marshals arguments.  There is no CPU fallback: without the built library every call raises.
 """
 from .binding import (SigError, WordSet, lib_path, load_library, sig_backward, sig_forward,  # noqa: F401
-                      sig_profile_enable, sig_profile_read,
+                      sig_probe_fma_tflops, sig_profile_enable, sig_profile_read,
                       sig_wordset_build, sig_wordset_build_anisotropic, sig_wordset_build_truncated)

@@ -82,6 +82,7 @@ def load_library():
     sig("sig_version", ctypes.c_char_p, [])
     sig("sig_wordset_kernel_name", ctypes.c_char_p, [c_p, c_int])
     sig("sig_kernel_name", ctypes.c_char_p, [c_p, c_int, c_i64, c_i64])
+    sig("sig_probe_fma", c_int, [c_p, c_sz, c_int, c_int, c_p])
     _lib = lib
     return lib
 
@@ -306,6 +307,25 @@ def sig_backward(ws: WordSet, path, coeffs, grad_coeffs, out=None, workspace=Non
     if keep is not None:
         keep.record_stream(torch.cuda.current_stream(path.device))
     return out
+
+
+def sig_probe_fma_tflops(blocks: int = 256 * 32, iters: int = 4096, repeats: int = 5) -> float:
+    """Measured rate of plain (unpacked) FP32 multiply-adds: a register-only kernel timed with events on the current
+    stream, best of `repeats`."""
+    import torch
+    lib = load_library()
+    out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    best = float("inf")
+    for _ in range(repeats + 1):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        _check(lib.sig_probe_fma(ctypes.c_void_p(out.data_ptr()), out.numel() * 4, blocks, iters, ctypes.c_void_p(stream)),
+               "sig_probe_fma")
+        e1.record()
+        e1.synchronize()
+        best = min(best, e0.elapsed_time(e1))
+    return 2.0 * 16 * iters * 256 * blocks / (best * 1e-3) / 1e12
 
 
 def sig_profile_enable(on: bool) -> None:

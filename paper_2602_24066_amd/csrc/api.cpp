@@ -647,6 +647,14 @@ const char* sig_wordset_kernel_name(const sig_wordset* ws, int backward)
     return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";
 }
 
+int sig_probe_fma(void* out, size_t out_bytes, int blocks, int iters, void* stream)
+{
+    if (!out || blocks < 1 || iters < 1) return SIG_EINVAL;
+    if (out_bytes < (size_t)blocks * 256 * sizeof(float)) return SIG_EWORKSPACE;
+    hipError_t e = sig::fma_probe((float*)out, blocks, iters, (hipStream_t)stream);
+    return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
 const char* sig_kernel_name(const sig_wordset* ws, int backward, int64_t B, int64_t n_points)
 {
     if (!ws || !W(ws)->kernels_supported) return "unsupported";

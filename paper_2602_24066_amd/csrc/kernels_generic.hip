@@ -355,6 +355,30 @@ hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d,
     return hipGetLastError();
 }
 
+// Register-only multiply-add loop for the benchmark: every thread runs `iters` rounds of 16 independent fmaf chains
+// (no memory traffic inside the loop) and stores one value so that nothing is optimised away.
+__global__ __launch_bounds__(256) void fma_probe_kernel(float* out, int iters, float a, float b)
+{
+    float x[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x[i] = (float)(threadIdx.x + i);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = fmaf(x[i], a, b);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += x[i];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+hipError_t fma_probe(float* out, int blocks, int iters, hipStream_t stream)
+{
+    if (blocks <= 0 || iters <= 0) return hipErrorInvalidValue;
+    fma_probe_kernel<<<(unsigned)blocks, 256, 0, stream>>>(out, iters, 0.999f, 0.001f);
+    return hipGetLastError();
+}
+
 hipError_t fill_zero(float* p, int64_t n, hipStream_t stream)
 {
     if (n <= 0) return hipSuccess;
