@@ -42,18 +42,21 @@ def flops_backward(ws, B, L):
 def setup(name, S, torch):
     from sig_workloads import WORKLOADS, make_grad_coeffs, workload_path, workload_word_list
     wl = WORKLOADS[name]
+    words = workload_word_list(wl) if wl.kind == "words" else None
+    t0 = time.perf_counter()
     if wl.kind == "truncated":
         ws = S.sig_wordset_build_truncated(wl.d, wl.depth)
     elif wl.kind == "anisotropic":
         ws = S.sig_wordset_build_anisotropic(wl.d, wl.weights, wl.cutoff)
     else:
-        ws = S.sig_wordset_build(wl.d, workload_word_list(wl))
+        ws = S.sig_wordset_build(wl.d, words)
+    build_ms = (time.perf_counter() - t0) * 1e3        # host: tables + launch plans, once per word set
     ws.upload("cuda:0")
     X = workload_path(wl)
     G = make_grad_coeffs(wl.seed, wl.B, ws.size)
     lib = S.load_library()
     st = {
-        "wl": wl, "ws": ws, "X": X, "G": G,
+        "wl": wl, "ws": ws, "X": X, "G": G, "build_ms": build_ms,
         "path": torch.from_numpy(X).cuda(),
         "grad": torch.from_numpy(G).cuda(),
         "coeffs": torch.empty((wl.B, ws.size), dtype=torch.float32, device="cuda"),
@@ -231,6 +234,7 @@ def main():
                 "fwd_roofline_frac": roofline_entry(flops_forward(w2, wl2.B, wl2.L), f2)["frac"],
                 "bwd_roofline_frac": roofline_entry(flops_backward(w2, wl2.B, wl2.L), b2)["frac"],
                 "kernels": [w2.kernel_name(False, wl2.B, wl2.L + 1), w2.kernel_name(True, wl2.B, wl2.L + 1)],
+                "wordset_build_ms": round(s2["build_ms"], 3),
             }
             if name == "c5":
                 per[name]["peak_device_bytes"] = int(torch.cuda.max_memory_allocated() - base)
@@ -239,6 +243,15 @@ def main():
                 del s2
                 torch.cuda.empty_cache()
         out["per_workload"] = per
+
+        # the other word-set builders (host only): graph-induced set and the sparse lead-lag set of a 5-dimensional path
+        t0 = time.perf_counter()
+        g = S.sig_wordset_build_graph(10, [(a, b) for a in range(10) for b in range(10) if 0 < b - a <= 3], 6)
+        t1 = time.perf_counter()
+        ll = S.sig_wordset_build_leadlag_sparse(5, 4)
+        t2 = time.perf_counter()
+        out["other_word_sets"] = {"graph(d=10, edges i->i+1..i+3, depth 6)": {"words": g.size, "build_ms": round((t1 - t0) * 1e3, 3)},
+                                  "leadlag_sparse(d=5, depth 4)": {"words": ll.size, "build_ms": round((t2 - t1) * 1e3, 3)}}
 
     if not args.no_cpu and wl.kind == "truncated":
         out["cpu_baseline"] = cpu_baseline(st, min(args.cpu_sample, wl.B) if args.cpu_sample > 0 else wl.B)

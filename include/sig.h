@@ -76,6 +76,17 @@ int sig_wordset_build_anisotropic(int d, const double* weights, double cutoff, s
  * prefixes; user_index[k] is the canonical index of word k in the closed set. */
 int sig_wordset_build(int d, const int32_t* letters, const int64_t* offsets, int64_t n_words, sig_wordset** out);
 
+/* Graph-induced set (Section 7.1): all words i_1..i_n, n <= depth, with (i_k, i_{k+1}) an edge for every k.
+ * edges: host, n_edges pairs (from, to) of 0-based letters, duplicates allowed, any directed graph accepted.  Every
+ * single letter is a word.  The set is prefix-closed by construction; user_index lists its words in canonical order. */
+int sig_wordset_build_graph(int d, const int32_t* edges, int64_t n_edges, int depth, sig_wordset** out);
+
+/* Sparse lead-lag set (Section 8) for a d-dimensional path after sig_leadlag_transform: alphabet of 2 d letters
+ * (letter i = lag channel of coordinate i, letter d + i = its lead channel); all concatenations, of length <= depth,
+ * of the generators (L_i), (l_i L_i), (L_i l_i).  That set is not prefix-closed: it is closed like any word list and
+ * user_index gives the columns of the generated words (in order of the number of generators, then generator order). */
+int sig_wordset_build_leadlag_sparse(int d, int depth, sig_wordset** out);
+
 void sig_wordset_free(sig_wordset* ws);            /* NULL is allowed */
 
 /* Accessors.  Returned host pointers stay valid until sig_wordset_free. */
@@ -160,6 +171,13 @@ size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_
 int    sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs,
                     int64_t B, int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes,
                     void* stream);
+
+/* ---- lead-lag transform (Section 8, Definition of the lead-lag path) ------------------------------------------
+ * path device float32 [B, n_points, d] -> out device float32 [B, 2 n_points - 1, 2 d]:
+ * out[2k] = (X_k, X_k), out[2k+1] = (X_k, X_{k+1}); channels 0..d-1 lag, d..2d-1 lead.  sig_leadlag_backward maps
+ * grad_out [B, 2 n_points - 1, 2 d] to grad_path [B, n_points, d] (overwritten).  Both only enqueue on `stream`. */
+int sig_leadlag_transform(const float* path, int64_t B, int64_t n_points, int d, float* out, void* stream);
+int sig_leadlag_backward(const float* grad_out, int64_t B, int64_t n_points, int d, float* grad_path, void* stream);
 
 /* ---- kernel timer ----------------------------------------------------------------------------------------
  * For benchmarks: while enabled, sig_forward / sig_backward record two HIP event pairs on the caller's stream:

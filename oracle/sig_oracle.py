@@ -102,6 +102,68 @@ def anisotropic_words(d: int, weights: Sequence[float], cutoff: float) -> List[W
     return sort_canonical(out)
 
 
+def graph_words(d: int, edges: Iterable[Tuple[int, int]], depth: int) -> List[Word]:
+    """Words of length <= depth in which every pair of consecutive letters is an edge of the given directed graph
+    (Section 7.1); all single letters are words."""
+    E = set((int(a), int(b)) for a, b in edges)
+    out: List[Word] = [(i,) for i in range(d)]
+    level = list(out)
+    for _ in range(2, depth + 1):
+        level = [w + (j,) for w in level for j in range(d) if (w[-1], j) in E]
+        out.extend(level)
+    return sort_canonical(out)
+
+
+def leadlag_sparse_words(d: int, depth: int) -> List[Word]:
+    """Sparse lead-lag word set of Section 8 over the alphabet (lag_0..lag_{d-1}, lead_0..lead_{d-1}) = (0..2d-1): every
+    concatenation of the generators (lead_i), (lag_i, lead_i), (lead_i, lag_i) with at most `depth` letters, found here
+    by testing every candidate word for such a factorisation (no enumeration by generators)."""
+    gens = set()
+    for i in range(d):
+        gens.update({(d + i,), (i, d + i), (d + i, i)})
+
+    def factorises(w: Word) -> bool:
+        ok = [False] * (len(w) + 1)
+        ok[0] = True
+        for e in range(1, len(w) + 1):
+            ok[e] = (ok[e - 1] and w[e - 1:e] in gens) or (e >= 2 and ok[e - 2] and w[e - 2:e] in gens)
+        return ok[len(w)]
+
+    out: List[Word] = []
+    level: List[Word] = [()]
+    for _ in range(depth):
+        # a word can only factorise if each of its letters sits next to its partner or is a lead letter; grow by one
+        # letter and keep every prefix of a factorising word as a candidate (prefixes of prefixes are candidates too)
+        level = [w + (c,) for w in level for c in range(2 * d)
+                 if _leadlag_prefix_possible(w + (c,), d)]
+        out.extend(w for w in level if factorises(w))
+    return sort_canonical(out)
+
+
+def _leadlag_prefix_possible(w: Word, d: int) -> bool:
+    """True if w is a prefix of some concatenation of generators: w minus a possibly dangling last letter factorises."""
+    gens = set()
+    for i in range(d):
+        gens.update({(d + i,), (i, d + i), (d + i, i)})
+    ok = [False] * (len(w) + 1)
+    ok[0] = True
+    for e in range(1, len(w) + 1):
+        ok[e] = (ok[e - 1] and w[e - 1:e] in gens) or (e >= 2 and ok[e - 2] and w[e - 2:e] in gens)
+    return ok[len(w)] or ok[len(w) - 1]
+
+
+def leadlag_transform(X: np.ndarray) -> np.ndarray:
+    """Lead-lag path of Section 8: X [B, n, d] -> [B, 2 n - 1, 2 d], rows (X_k, X_k) and (X_k, X_{k+1}) alternating;
+    channels 0..d-1 are the lag copy, d..2d-1 the lead copy."""
+    B, n, d = X.shape
+    out = np.empty((B, 2 * n - 1, 2 * d), dtype=X.dtype)
+    out[:, 0::2, :d] = X
+    out[:, 0::2, d:] = X
+    out[:, 1::2, :d] = X[:, :-1]
+    out[:, 1::2, d:] = X[:, 1:]
+    return out
+
+
 def sort_canonical(words: Iterable[Word]) -> List[Word]:
     return sorted(set(tuple(int(c) for c in w) for w in words), key=lambda w: (len(w), w))
 

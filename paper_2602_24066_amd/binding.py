@@ -51,6 +51,10 @@ def load_library():
     sig("sig_wordset_build_truncated", c_int, [c_int, c_int, PP])
     sig("sig_wordset_build_anisotropic", c_int, [c_int, c_p, c_dbl, PP])
     sig("sig_wordset_build", c_int, [c_int, c_p, c_p, c_i64, PP])
+    sig("sig_wordset_build_graph", c_int, [c_int, c_p, c_i64, c_int, PP])
+    sig("sig_wordset_build_leadlag_sparse", c_int, [c_int, c_int, PP])
+    sig("sig_leadlag_transform", c_int, [c_p, c_i64, c_i64, c_int, c_p, c_p])
+    sig("sig_leadlag_backward", c_int, [c_p, c_i64, c_i64, c_int, c_p, c_p])
     sig("sig_wordset_free", None, [c_p])
     sig("sig_wordset_size", c_i64, [c_p])
     sig("sig_wordset_dim", c_int, [c_p])
@@ -245,6 +249,57 @@ def sig_wordset_build(d: int, words: Iterable[Sequence[int]]) -> WordSet:
     _check(load_library().sig_wordset_build(d, letters.ctypes.data, offsets.ctypes.data, len(words), ctypes.byref(h)),
            "sig_wordset_build")
     return WordSet(h.value)
+
+
+def sig_wordset_build_graph(d: int, edges: Iterable[Sequence[int]], depth: int) -> WordSet:
+    """Words of length <= depth whose consecutive letters are joined by an edge (from, to)."""
+    e = np.ascontiguousarray(np.array([tuple(int(c) for c in ed) for ed in edges], dtype=np.int32).reshape(-1, 2))
+    h = ctypes.c_void_p()
+    _check(load_library().sig_wordset_build_graph(d, e.ctypes.data if e.size else None, e.shape[0], depth, ctypes.byref(h)),
+           "sig_wordset_build_graph")
+    return WordSet(h.value)
+
+
+def sig_wordset_build_leadlag_sparse(d: int, depth: int) -> WordSet:
+    """Sparse lead-lag word set over 2 d letters (lag i -> letter i, lead i -> letter d + i)."""
+    h = ctypes.c_void_p()
+    _check(load_library().sig_wordset_build_leadlag_sparse(d, depth, ctypes.byref(h)), "sig_wordset_build_leadlag_sparse")
+    return WordSet(h.value)
+
+
+def sig_leadlag_transform(path, out=None):
+    """path float32 CUDA [B, n, d] -> lead-lag path [B, 2 n - 1, 2 d]."""
+    import torch
+    if not path.is_cuda or path.dtype != torch.float32 or path.dim() != 3:
+        raise ValueError("path must be a float32 CUDA tensor [B, n, d]")
+    path = path.contiguous()
+    B, P, d = path.shape
+    if out is None:
+        out = torch.empty((B, 2 * P - 1, 2 * d), dtype=torch.float32, device=path.device)
+    with torch.cuda.device(path.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(load_library().sig_leadlag_transform(ctypes.c_void_p(path.data_ptr()), B, P, d, ctypes.c_void_p(out.data_ptr()),
+                                                    ctypes.c_void_p(stream)), "sig_leadlag_transform")
+    return out
+
+
+def sig_leadlag_backward(grad_out, out=None):
+    """Gradient of the lead-lag transform: [B, 2 n - 1, 2 d] -> [B, n, d]."""
+    import torch
+    if not grad_out.is_cuda or grad_out.dtype != torch.float32 or grad_out.dim() != 3:
+        raise ValueError("grad_out must be a float32 CUDA tensor [B, 2 n - 1, 2 d]")
+    grad_out = grad_out.contiguous()
+    B, M, d2 = grad_out.shape
+    if M % 2 != 1 or d2 % 2 != 0:
+        raise ValueError("not the shape of a lead-lag path")
+    P, d = (M + 1) // 2, d2 // 2
+    if out is None:
+        out = torch.empty((B, P, d), dtype=torch.float32, device=grad_out.device)
+    with torch.cuda.device(grad_out.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(load_library().sig_leadlag_backward(ctypes.c_void_p(grad_out.data_ptr()), B, P, d, ctypes.c_void_p(out.data_ptr()),
+                                                   ctypes.c_void_p(stream)), "sig_leadlag_backward")
+    return out
 
 
 def _aligned_workspace(nbytes: int, device):

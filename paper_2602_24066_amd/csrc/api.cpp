@@ -283,6 +283,42 @@ int sig_wordset_build(int d, const int32_t* letters, const int64_t* offsets, int
     return rc;
 }
 
+int sig_wordset_build_graph(int d, const int32_t* edges, int64_t n_edges, int depth, sig_wordset** out)
+{
+    if (!out) return SIG_EINVAL;
+    sig::WordSet* w = nullptr;
+    int rc = sig::build_graph(d, edges, n_edges, depth, &w);
+    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
+    return rc;
+}
+
+int sig_wordset_build_leadlag_sparse(int d, int depth, sig_wordset** out)
+{
+    if (!out) return SIG_EINVAL;
+    sig::WordSet* w = nullptr;
+    int rc = sig::build_leadlag_sparse(d, depth, &w);
+    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
+    return rc;
+}
+
+int sig_leadlag_transform(const float* path, int64_t B, int64_t n_points, int d, float* out, void* stream)
+{
+    if (B < 0 || n_points < 1 || d < 1) return SIG_EINVAL;
+    if (B == 0) return SIG_OK;
+    if (!path || !out) return SIG_EINVAL;
+    hipError_t e = sig::leadlag(path, B, n_points, d, out, (hipStream_t)stream);
+    return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
+int sig_leadlag_backward(const float* grad_out, int64_t B, int64_t n_points, int d, float* grad_path, void* stream)
+{
+    if (B < 0 || n_points < 1 || d < 1) return SIG_EINVAL;
+    if (B == 0) return SIG_OK;
+    if (!grad_out || !grad_path) return SIG_EINVAL;
+    hipError_t e = sig::leadlag_backward(grad_out, B, n_points, d, grad_path, (hipStream_t)stream);
+    return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
 void sig_wordset_free(sig_wordset* ws) { delete static_cast<sig::WordSet*>(ws); }
 
 int64_t sig_wordset_size(const sig_wordset* ws) { return ws ? W(ws)->size() : -1; }

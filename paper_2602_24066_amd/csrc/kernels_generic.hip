@@ -355,6 +355,51 @@ hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d,
     return hipGetLastError();
 }
 
+// Lead-lag transform (Section 8): out[b][2k] = (X_k, X_k), out[b][2k+1] = (X_k, X_{k+1}); channels 0..d-1 lag,
+// d..2d-1 lead.  out: [B, 2P - 1, 2d].
+__global__ void leadlag_kernel(const float* __restrict__ path, int64_t B, int64_t P, int d, float* __restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t n = B * (2 * P - 1) * 2 * d;
+    if (i >= n) return;
+    const int c = (int)(i % (2 * d));
+    const int64_t m = (i / (2 * d)) % (2 * P - 1);
+    const int64_t b = i / (2 * d) / (2 * P - 1);
+    const int64_t k = c < d ? m / 2 : (m + 1) / 2;      // lag stays at X_{floor(m/2)}, lead moves on at odd m
+    out[i] = path[(b * P + k) * d + (c < d ? c : c - d)];
+}
+// its adjoint: every point gathers the gradients of its (up to four) copies
+__global__ void leadlag_backward_kernel(const float* __restrict__ gout, int64_t B, int64_t P, int d, float* __restrict__ gpath)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t n = B * P * d;
+    if (i >= n) return;
+    const int c = (int)(i % d);
+    const int64_t k = (i / d) % P;
+    const int64_t b = i / d / P;
+    const int64_t M2 = 2 * P - 1;
+    const float* g = gout + b * M2 * 2 * d;
+    float acc = g[(2 * k) * 2 * d + c] + g[(2 * k) * 2 * d + d + c];        // row 2k: lag and lead
+    if (2 * k + 1 < M2) acc += g[(2 * k + 1) * 2 * d + c];                      // row 2k+1: lag
+    if (k > 0) acc += g[(2 * k - 1) * 2 * d + d + c];                            // row 2k-1: lead
+    gpath[i] = acc;
+}
+
+hipError_t leadlag(const float* path, int64_t B, int64_t P, int d, float* out, hipStream_t stream)
+{
+    const int64_t n = B * (2 * P - 1) * 2 * d;
+    if (n <= 0) return hipSuccess;
+    leadlag_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(path, B, P, d, out);
+    return hipGetLastError();
+}
+hipError_t leadlag_backward(const float* gout, int64_t B, int64_t P, int d, float* gpath, hipStream_t stream)
+{
+    const int64_t n = B * P * d;
+    if (n <= 0) return hipSuccess;
+    leadlag_backward_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(gout, B, P, d, gpath);
+    return hipGetLastError();
+}
+
 // Register-only multiply-add loop for the benchmark: every thread runs `iters` rounds of 16 independent fmaf chains
 // (no memory traffic inside the loop) and stores one value so that nothing is optimised away.
 __global__ __launch_bounds__(256) void fma_probe_kernel(float* out, int iters, float a, float b)

@@ -482,4 +482,86 @@ int build_list(int d, const int32_t* letters, const int64_t* offsets, int64_t n_
     return SIG_OK;
 }
 
+// Words of length <= depth whose consecutive letters are joined by an edge (Section 7.1, graph-induced word set).
+// Generated level by level from the canonically ordered previous level with the successors of the last letter in
+// increasing order, which is the canonical order already; build_list then makes the tables.
+int build_graph(int d, const int32_t* edges, int64_t n_edges, int depth, WordSet** out)
+{
+    if (!out || check_d(d) != SIG_OK || n_edges < 0 || depth < 1 || (n_edges > 0 && !edges)) return SIG_EINVAL;
+    if (depth > SIG_MAX_WORD_LEN) return SIG_ETOOLARGE;
+    try {
+        std::vector<std::vector<int32_t>> succ((size_t)d);
+        for (int64_t e = 0; e < n_edges; ++e) {
+            const int32_t a = edges[2 * e], b = edges[2 * e + 1];
+            if (a < 0 || a >= d || b < 0 || b >= d) return SIG_ELETTER;
+            succ[(size_t)a].push_back(b);
+        }
+        for (auto& v : succ) {
+            std::sort(v.begin(), v.end());
+            v.erase(std::unique(v.begin(), v.end()), v.end());
+        }
+        std::vector<int32_t> letters;
+        std::vector<int64_t> offsets(1, 0);
+        size_t lev_begin = 0;                        // first word of the previous level in `offsets`
+        for (int i = 0; i < d; ++i) { letters.push_back(i); offsets.push_back((int64_t)letters.size()); }
+        for (int n = 2; n <= depth; ++n) {
+            const size_t lev_end = offsets.size() - 1;
+            for (size_t w = lev_begin; w < lev_end; ++w) {
+                const int64_t a = offsets[w], b = offsets[w + 1];
+                const int32_t last = letters[(size_t)b - 1];
+                for (int32_t nx : succ[(size_t)last]) {
+                    if ((int64_t)offsets.size() > kMaxWords) return SIG_ETOOLARGE;
+                    // the range is copied by index: letters may reallocate while it grows
+                    for (int64_t q = a; q < b; ++q) letters.push_back(letters[(size_t)q]);
+                    letters.push_back(nx);
+                    offsets.push_back((int64_t)letters.size());
+                }
+            }
+            if (offsets.size() - 1 == lev_end) break;      // no word of this length
+            lev_begin = lev_end;
+        }
+        return build_list(d, letters.data(), offsets.data(), (int64_t)offsets.size() - 1, out);
+    } catch (const std::bad_alloc&) { return SIG_ENOMEM; }
+}
+
+// Sparse lead-lag word set (Section 8): alphabet of 2 d letters, lag channel of coordinate i = letter i, lead channel
+// = letter d + i; all concatenations of the generators (L_i), (l_i L_i), (L_i l_i) of length <= depth.  The set is
+// not prefix-closed (l_i alone is not in it); build_list closes it and user_index locates the generated words.
+int build_leadlag_sparse(int d, int depth, WordSet** out)
+{
+    if (!out || d < 1 || d > 2048 || depth < 1) return SIG_EINVAL;
+    if (depth > SIG_MAX_WORD_LEN) return SIG_ETOOLARGE;
+    try {
+        std::vector<int32_t> letters;
+        std::vector<int64_t> offsets(1, 0);
+        // breadth-first over the number of generators; words can be reached in several ways (never, in fact: the
+        // factorisation is unique, but duplicates would be harmless)
+        size_t begin = 0, end = 0;                   // frontier = words [begin, end) of `offsets`; starts with the empty word
+        bool first = true;
+        while (first || begin < end) {
+            const size_t nb = offsets.size() - 1;
+            const size_t count = first ? 1 : end - begin;
+            for (size_t f = 0; f < count; ++f) {
+                const int64_t a = first ? 0 : offsets[begin + f], b = first ? 0 : offsets[begin + f + 1];
+                const int64_t len = b - a;
+                for (int g = 0; g < 3 * d; ++g) {
+                    const int i = g % d, kind = g / d;            // 0: (L_i), 1: (l_i, L_i), 2: (L_i, l_i)
+                    const int glen = kind == 0 ? 1 : 2;
+                    if (len + glen > depth) continue;
+                    if ((int64_t)offsets.size() > kMaxWords) return SIG_ETOOLARGE;
+                    for (int64_t q = a; q < b; ++q) letters.push_back(letters[(size_t)q]);
+                    if (kind == 0) letters.push_back(d + i);
+                    else if (kind == 1) { letters.push_back(i); letters.push_back(d + i); }
+                    else { letters.push_back(d + i); letters.push_back(i); }
+                    offsets.push_back((int64_t)letters.size());
+                }
+            }
+            first = false;
+            begin = nb;
+            end = offsets.size() - 1;
+        }
+        return build_list(2 * d, letters.data(), offsets.data(), (int64_t)offsets.size() - 1, out);
+    } catch (const std::bad_alloc&) { return SIG_ENOMEM; }
+}
+
 }  // namespace sig

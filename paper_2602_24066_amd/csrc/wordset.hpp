@@ -86,6 +86,8 @@ struct WordSet {
 int build_truncated(int d, int depth, WordSet** out);
 int build_anisotropic(int d, const double* weights, double cutoff, WordSet** out);
 int build_list(int d, const int32_t* letters, const int64_t* offsets, int64_t n_words, WordSet** out);
+int build_graph(int d, const int32_t* edges, int64_t n_edges, int depth, WordSet** out);
+int build_leadlag_sparse(int d, int depth, WordSet** out);
 
 // Splits the word tree into work units of at most max_slots words and about target_cost multiply-adds.
 void build_plan(const WordSet& ws, int max_slots, int64_t target_cost, bool with_leave, Plan& plan);

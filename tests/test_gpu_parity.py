@@ -135,6 +135,42 @@ def test_many_short_paths():
     check_parity(ws, W, "truncated", 6, X, G, sample=sample, what="B=66000")
 
 
+def test_graph_induced_word_set():
+    edges = [(0, 1), (0, 2), (1, 3), (2, 3), (3, 4), (3, 5), (1, 5), (4, 5), (2, 4)]
+    ws = S.sig_wordset_build_graph(6, edges, 5)
+    ws.upload("cuda:0")
+    W = O.graph_words(6, edges, 5)
+    assert ws.size == len(W)
+    X = make_path("iid", 61, 70, 33, 6)
+    G = make_grad_coeffs(62, 70, ws.size)
+    check_parity(ws, W, "words", None, X, G, what="graph-induced set")
+
+
+def test_leadlag_transform_and_sparse_word_set():
+    import torch
+    d, depth, B, n = 3, 4, 9, 12
+    X = make_path("iid", 63, B, n - 1, d)
+    xp = torch.from_numpy(X).cuda()
+    yp = S.sig_leadlag_transform(xp)
+    Y = O.leadlag_transform(X)
+    assert np.array_equal(yp.cpu().numpy(), Y)                       # copies only: exact
+    # its adjoint against the transpose of the (linear) oracle transform, applied to a random cotangent
+    Gy = np.random.default_rng(64).standard_normal(Y.shape).astype(np.float32)
+    gx = S.sig_leadlag_backward(torch.from_numpy(Gy).cuda()).cpu().numpy()
+    ref = np.zeros(X.shape, dtype=np.float64)
+    ref += Gy[:, 0::2, :d] + Gy[:, 0::2, d:]
+    ref[:, :-1] += Gy[:, 1::2, :d]
+    ref[:, 1:] += Gy[:, 1::2, d:]
+    np.testing.assert_allclose(gx, ref, rtol=1e-6, atol=1e-6)
+    # signatures of the lead-lag path on the sparse set
+    ws = S.sig_wordset_build_leadlag_sparse(d, depth)
+    ws.upload("cuda:0")
+    W = O.prefix_closure(O.leadlag_sparse_words(d, depth))
+    assert ws.size == len(W)
+    G = make_grad_coeffs(65, B, ws.size)
+    check_parity(ws, W, "words", None, Y, G, what="sparse lead-lag set")
+
+
 def test_one_point_paths_give_zero():
     import torch
     ws, W = build_both("truncated", 3, depth=3)

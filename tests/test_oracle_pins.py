@@ -453,3 +453,47 @@ def test_error_measures():
     assert abs(e[1] - 0.1) < 1e-15 and abs(e[2] - 0.1) < 1e-15
     g = O.grad_errors(np.array([[[1.0, 2.5]]]), np.array([[[1.0, 2.0]]]))
     assert abs(g[0] - 0.25) < 1e-15
+
+
+def test_leadlag_sparse_words_against_brute_force():
+    """The sparse lead-lag set (Section 8) by its definition: all products of generators, enumerated by brute force
+    over sequences of generators, against the oracle's membership test."""
+    import itertools
+    for d, depth in [(1, 4), (2, 4), (3, 3)]:
+        gens = [(d + i,) for i in range(d)] + [(i, d + i) for i in range(d)] + [(d + i, i) for i in range(d)]
+        brute = set()
+        for p in range(1, depth + 1):
+            for combo in itertools.product(gens, repeat=p):
+                w = tuple(c for g in combo for c in g)
+                if len(w) <= depth:
+                    brute.add(w)
+        assert O.leadlag_sparse_words(d, depth) == sorted(brute, key=lambda w: (len(w), w))
+
+
+def test_graph_words_special_cases():
+    # the complete graph with loops gives the truncation; a graph without edges only the letters
+    full = [(a, b) for a in range(3) for b in range(3)]
+    assert O.graph_words(3, full, 4) == O.truncated_words(3, 4)
+    assert O.graph_words(4, [], 5) == [(i,) for i in range(4)]
+    # a chain 0 -> 1 -> 2: words are the runs
+    assert O.graph_words(3, [(0, 1), (1, 2)], 3) == [(0,), (1,), (2,), (0, 1), (1, 2), (0, 1, 2)]
+
+
+def test_leadlag_area_is_quadratic_variation():
+    """Level 2 of the lead-lag path holds the discrete quadratic (co)variation (the property Section 8 recalls; the
+    lead copy moves first): S(lead_i, lag_j) - S(lag_i, lead_j) = sum_k dX^i_k dX^j_k, for i = j the antisymmetric
+    part between the two copies of a coordinate."""
+    rng = np.random.default_rng(5)
+    X = np.cumsum(rng.standard_normal((2, 9, 2)), axis=1).astype(np.float32)
+    Y = O.leadlag_transform(X)
+    assert Y.shape == (2, 17, 4)
+    assert np.array_equal(Y[:, 0], np.concatenate([X[:, 0], X[:, 0]], axis=-1))
+    assert np.array_equal(Y[:, -1], np.concatenate([X[:, -1], X[:, -1]], axis=-1))
+    d = 2
+    W = O.truncated_words(2 * d, 2)
+    Sg = O.forward_words(Y, W)
+    dX = np.diff(X.astype(np.float64), axis=1)
+    for i in range(d):
+        for j in range(d):
+            a = Sg[:, W.index((d + i, j))] - Sg[:, W.index((i, d + j))]
+            np.testing.assert_allclose(a, (dX[:, :, i] * dX[:, :, j]).sum(axis=1), rtol=1e-10, atol=1e-12)

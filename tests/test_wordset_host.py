@@ -302,3 +302,57 @@ def test_time_chunk_workspace():
     assert lib.sig_forward_workspace_bytes(ws._h, 4096, 1025) == 0
     gdx = (4 * 2 * 1024 * 4 + 255) // 256 * 256
     assert lib.sig_backward_workspace_bytes(ws._h, 2, 1025) == gdx       # backward is not chunked by itself
+
+
+GRAPHS = [
+    (4, [(a, b) for a in range(4) for b in range(4)], 4),                      # complete graph with loops: the truncation
+    (5, [(i, i + 1) for i in range(4)], 5),                                    # a chain
+    (6, [(0, 1), (0, 2), (1, 3), (2, 3), (3, 4), (3, 5), (1, 5)], 6),           # a DAG
+    (3, [(0, 1), (1, 0), (1, 2), (2, 2)], 5),                                  # cycles and a loop are accepted too
+    (4, [], 3),                                                                # no edges: single letters only
+]
+
+
+@pytest.mark.parametrize("case", range(len(GRAPHS)))
+def test_graph_tables_bit_exact(case):
+    d, edges, depth = GRAPHS[case]
+    ws = S.sig_wordset_build_graph(d, edges, depth)
+    W = O.graph_words(d, edges, depth)
+    t = O.word_tables(W)
+    parent, letter, level_start = t["parent"], t["letter"], t["level_start"]
+    assert ws.size == len(W)
+    assert np.array_equal(ws.parent, parent) and np.array_equal(ws.letter, letter)
+    assert np.array_equal(ws.level_start, level_start)
+    assert np.array_equal(ws.user_index, np.arange(len(W)))                     # generated in canonical order already
+    if case == 0:
+        full = S.sig_wordset_build_truncated(4, 4)
+        assert np.array_equal(ws.parent, full.parent) and np.array_equal(ws.letter, full.letter)
+    if case == 1:
+        assert ws.size == sum(5 - n + 1 for n in range(1, 6))                   # runs i, i+1, .., i+n-1
+
+
+def test_graph_and_leadlag_error_codes():
+    lib = S.load_library()
+    h = ctypes.c_void_p()
+    bad = np.array([[0, 7]], dtype=np.int32)
+    assert lib.sig_wordset_build_graph(3, bad.ctypes.data, 1, 2, ctypes.byref(h)) == -2
+    assert lib.sig_wordset_build_graph(3, None, 0, 0, ctypes.byref(h)) == -1
+    assert lib.sig_wordset_build_graph(3, None, 1, 2, ctypes.byref(h)) == -1
+    assert lib.sig_wordset_build_leadlag_sparse(0, 3, ctypes.byref(h)) == -1
+    assert lib.sig_wordset_build_leadlag_sparse(2, 0, ctypes.byref(h)) == -1
+    assert lib.sig_wordset_build_leadlag_sparse(2, 40, ctypes.byref(h)) == -7
+
+
+@pytest.mark.parametrize("d,depth", [(1, 5), (2, 5), (3, 4), (5, 4)])
+def test_leadlag_sparse_tables_bit_exact(d, depth):
+    ws = S.sig_wordset_build_leadlag_sparse(d, depth)
+    words = O.leadlag_sparse_words(d, depth)
+    W = O.prefix_closure(words)
+    t = O.word_tables(W)
+    parent, letter, level_start = t["parent"], t["letter"], t["level_start"]
+    assert ws.dim == 2 * d and ws.size == len(W)
+    assert np.array_equal(ws.parent, parent) and np.array_equal(ws.letter, letter)
+    assert np.array_equal(ws.level_start, level_start)
+    assert [W[i] for i in np.unique(ws.user_index)] == words                   # exactly the generated words
+    if (d, depth) == (5, 4):
+        assert len(words) == 1685 and len(W) == 1860
