@@ -244,6 +244,35 @@ def main():
                 torch.cuda.empty_cache()
         out["per_workload"] = per
 
+        # signatures over windows (Section 5 of the paper): 32 paths of 1,024 segments, 64 sliding windows of 128
+        # segments each, the headline word set; all 2,048 (path, window) pairs advance in one launch
+        try:
+            from sig_workloads import make_path
+            wsw = st["ws"] if args.workload == HEADLINE else setup(HEADLINE, S, torch)["ws"]
+            Bw, Lw, Kw, lenw = 32, 1024, 64, 128
+            Xw = torch.from_numpy(make_path("time0", 77, Bw, Lw, wsw.dim)).cuda()
+            wins = [(k * (Lw - lenw) // (Kw - 1), k * (Lw - lenw) // (Kw - 1) + lenw) for k in range(Kw)]
+            cw = S.sig_forward_windows(wsw, Xw, wins)
+            gw = torch.randn_like(cw)
+            S.sig_backward_windows(wsw, Xw, wins, cw, gw)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                cw = S.sig_forward_windows(wsw, Xw, wins)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(10):
+                S.sig_backward_windows(wsw, Xw, wins, cw, gw)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            wk = Bw * Kw * lenw * wsw.size
+            out["windows"] = {"workload": f"B={Bw} L={Lw} d={wsw.dim} |W|={wsw.size}, {Kw} sliding windows of {lenw} segments",
+                              "fwd_ms": round((t1 - t0) * 100, 4), "bwd_ms": round((t2 - t1) * 100, 4),
+                              "fwd_bwd_coeff_steps_per_s": round(wk / ((t2 - t0) / 10), 1),
+                              "note": "host clock, includes the per-call workspace allocation of the Python wrapper"}
+        except Exception as e:                       # an optional extra must not take the benchmark line down
+            out["windows"] = {"error": str(e)[:200]}
+
         # the other word-set builders (host only): graph-induced set and the sparse lead-lag set of a 5-dimensional path
         t0 = time.perf_counter()
         g = S.sig_wordset_build_graph(10, [(a, b) for a in range(10) for b in range(10) if 0 < b - a <= 3], 6)

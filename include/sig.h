@@ -172,6 +172,24 @@ int    sig_backward(const sig_wordset* ws, const float* path, const float* coeff
                     int64_t B, int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes,
                     void* stream);
 
+/* ---- signatures over windows (Section 5) -------------------------------------------------------------------
+ * windows: device int64 [K][2], point indices (l_k, r_k) with 0 <= l_k <= r_k < n_points; window k is the path
+ *          restricted to the points l_k .. r_k (segments l_k .. r_k - 1; l_k == r_k gives the zero signature).
+ *          Indices outside the path are clamped.  max_window_len (host) >= max_k (r_k - l_k): the library cannot
+ *          read the device array, a longer window is cut after max_window_len segments.
+ * coeffs / grad_coeffs: device float32 [B, K, |W|];  grad_path: device float32 [B, n_points, d], overwritten with
+ *          the sum over the windows (floating-point atomics).
+ * Every (path, window) pair is run as a path of its own of max_window_len + 1 points (shorter windows padded with
+ * their last point), so all windows of all paths advance side by side in one launch; workspace sizes from the two
+ * functions below (256-byte aligned). */
+size_t sig_forward_windows_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points, int64_t K, int64_t max_window_len);
+size_t sig_backward_windows_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points, int64_t K, int64_t max_window_len);
+int sig_forward_windows(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, const int64_t* windows, int64_t K,
+                        int64_t max_window_len, float* coeffs, void* workspace, size_t workspace_bytes, void* stream);
+int sig_backward_windows(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                         int64_t n_points, const int64_t* windows, int64_t K, int64_t max_window_len, float* grad_path,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- lead-lag transform (Section 8, Definition of the lead-lag path) ------------------------------------------
  * path device float32 [B, n_points, d] -> out device float32 [B, 2 n_points - 1, 2 d]:
  * out[2k] = (X_k, X_k), out[2k+1] = (X_k, X_{k+1}); channels 0..d-1 lag, d..2d-1 lead.  sig_leadlag_backward maps

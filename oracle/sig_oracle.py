@@ -102,6 +102,25 @@ def anisotropic_words(d: int, weights: Sequence[float], cutoff: float) -> List[W
     return sort_canonical(out)
 
 
+def forward_windows(X: np.ndarray, W: Sequence[Word], windows: Sequence[Tuple[int, int]]) -> np.ndarray:
+    """Signatures over windows (Section 5): window (l, r) is the path restricted to its points l..r.  One plain forward
+    evaluation per window on the sliced path; [B, K, |W|]."""
+    B = X.shape[0]
+    out = np.zeros((B, len(windows), len(W)))
+    for k, (l, r) in enumerate(windows):
+        out[:, k, :] = forward_words(np.ascontiguousarray(X[:, l:r + 1]), W)
+    return out
+
+
+def backward_windows(X: np.ndarray, W: Sequence[Word], windows: Sequence[Tuple[int, int]], G: np.ndarray) -> np.ndarray:
+    """Gradient of sum_{b,k,w} G[b,k,w] S_{t_l,t_r}(X_b, w) with respect to the points: the per-window gradients added
+    into the points they came from."""
+    out = np.zeros(X.shape, dtype=np.float64)
+    for k, (l, r) in enumerate(windows):
+        out[:, l:r + 1] += backward_words(np.ascontiguousarray(X[:, l:r + 1]), W, np.ascontiguousarray(G[:, k, :]))
+    return out
+
+
 def graph_words(d: int, edges: Iterable[Tuple[int, int]], depth: int) -> List[Word]:
     """Words of length <= depth in which every pair of consecutive letters is an edge of the given directed graph
     (Section 7.1); all single letters are words."""

@@ -51,6 +51,10 @@ def load_library():
     sig("sig_wordset_build_truncated", c_int, [c_int, c_int, PP])
     sig("sig_wordset_build_anisotropic", c_int, [c_int, c_p, c_dbl, PP])
     sig("sig_wordset_build", c_int, [c_int, c_p, c_p, c_i64, PP])
+    sig("sig_forward_windows_workspace_bytes", c_sz, [c_p, c_i64, c_i64, c_i64, c_i64])
+    sig("sig_backward_windows_workspace_bytes", c_sz, [c_p, c_i64, c_i64, c_i64, c_i64])
+    sig("sig_forward_windows", c_int, [c_p, c_p, c_i64, c_i64, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
+    sig("sig_backward_windows", c_int, [c_p, c_p, c_p, c_p, c_i64, c_i64, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
     sig("sig_wordset_build_graph", c_int, [c_int, c_p, c_i64, c_int, PP])
     sig("sig_wordset_build_leadlag_sparse", c_int, [c_int, c_int, PP])
     sig("sig_leadlag_transform", c_int, [c_p, c_i64, c_i64, c_int, c_p, c_p])
@@ -299,6 +303,67 @@ def sig_leadlag_backward(grad_out, out=None):
         stream = torch.cuda.current_stream().cuda_stream
         _check(load_library().sig_leadlag_backward(ctypes.c_void_p(grad_out.data_ptr()), B, P, d, ctypes.c_void_p(out.data_ptr()),
                                                    ctypes.c_void_p(stream)), "sig_leadlag_backward")
+    return out
+
+
+def _windows_tensor(windows, device):
+    """(device int64 [K, 2] tensor, K, longest window in segments) from a sequence of (l, r) point-index pairs."""
+    import torch
+    w = np.ascontiguousarray(np.asarray(windows, dtype=np.int64).reshape(-1, 2))
+    if w.shape[0] and (np.any(w[:, 0] < 0) or np.any(w[:, 1] < w[:, 0])):
+        raise ValueError("windows must be pairs 0 <= l <= r")
+    max_len = int((w[:, 1] - w[:, 0]).max()) if w.shape[0] else 0
+    return torch.from_numpy(w).to(device), int(w.shape[0]), max_len
+
+
+def sig_forward_windows(ws: WordSet, path, windows):
+    """Signatures over windows: path float32 CUDA [B, n, d], windows (l, r) point indices -> coeffs [B, K, |W|]."""
+    import torch
+    if not path.is_cuda or path.dtype != torch.float32 or path.dim() != 3:
+        raise ValueError("path must be a float32 CUDA tensor [B, n, d]")
+    path = path.contiguous()
+    B, P, d = path.shape
+    if d != ws.dim:
+        raise ValueError(f"path has {d} channels, word set was built for {ws.dim}")
+    wt, K, max_len = _windows_tensor(windows, path.device)
+    if K and int(np.asarray(windows).reshape(-1, 2)[:, 1].max()) >= P:
+        raise ValueError("window end beyond the path")
+    lib = load_library()
+    out = torch.empty((B, K, ws.size), dtype=torch.float32, device=path.device)
+    nbytes = int(lib.sig_forward_windows_workspace_bytes(ws._h, B, P, K, max_len))
+    keep, wptr = _aligned_workspace(nbytes, path.device)
+    with torch.cuda.device(path.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(lib.sig_forward_windows(ws._h, ctypes.c_void_p(path.data_ptr()), B, P, ctypes.c_void_p(wt.data_ptr()), K, max_len,
+                                       ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(wptr), nbytes, ctypes.c_void_p(stream)),
+               "sig_forward_windows")
+    for t in (keep, wt):
+        if t is not None:
+            t.record_stream(torch.cuda.current_stream(path.device))
+    return out
+
+
+def sig_backward_windows(ws: WordSet, path, windows, coeffs, grad_coeffs):
+    """Gradient with respect to the path of a loss on the windowed signatures: grad_coeffs [B, K, |W|] -> [B, n, d]."""
+    import torch
+    path, coeffs, grad_coeffs = path.contiguous(), coeffs.contiguous(), grad_coeffs.contiguous()
+    B, P, d = path.shape
+    wt, K, max_len = _windows_tensor(windows, path.device)
+    if tuple(coeffs.shape) != (B, K, ws.size) or tuple(grad_coeffs.shape) != (B, K, ws.size):
+        raise ValueError("shape mismatch")
+    lib = load_library()
+    out = torch.empty((B, P, d), dtype=torch.float32, device=path.device)
+    nbytes = int(lib.sig_backward_windows_workspace_bytes(ws._h, B, P, K, max_len))
+    keep, wptr = _aligned_workspace(nbytes, path.device)
+    with torch.cuda.device(path.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(lib.sig_backward_windows(ws._h, ctypes.c_void_p(path.data_ptr()), ctypes.c_void_p(coeffs.data_ptr()),
+                                        ctypes.c_void_p(grad_coeffs.data_ptr()), B, P, ctypes.c_void_p(wt.data_ptr()), K, max_len,
+                                        ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(wptr), nbytes, ctypes.c_void_p(stream)),
+               "sig_backward_windows")
+    for t in (keep, wt):
+        if t is not None:
+            t.record_stream(torch.cuda.current_stream(path.device))
     return out
 
 

@@ -628,6 +628,78 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     return e == hipSuccess ? SIG_OK : hip_fail(e);
 }
 
+// ---- windows: every (path, window) pair is gathered into a path of its own (padded with its last point), the
+// ordinary forward / backward runs on those B * K paths, and the gradient is scattered back.
+static size_t win_sub_bytes(const sig::WordSet& w, int64_t B, int64_t K, int64_t n_sub)
+{
+    return ((size_t)B * (size_t)K * (size_t)n_sub * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;
+}
+
+size_t sig_forward_windows_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points, int64_t K, int64_t max_window_len)
+{
+    if (!ws || B <= 0 || K <= 0 || n_points < 1 || max_window_len < 0) return 0;
+    const int64_t n_sub = max_window_len + 1;
+    return win_sub_bytes(*W(ws), B, K, n_sub) + sig_forward_workspace_bytes(ws, B * K, n_sub);
+}
+
+size_t sig_backward_windows_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points, int64_t K, int64_t max_window_len)
+{
+    if (!ws || B <= 0 || K <= 0 || n_points < 1 || max_window_len < 0) return 0;
+    const int64_t n_sub = max_window_len + 1;
+    return 2 * win_sub_bytes(*W(ws), B, K, n_sub) + sig_backward_workspace_bytes(ws, B * K, n_sub);
+}
+
+int sig_forward_windows(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, const int64_t* windows, int64_t K,
+                        int64_t max_window_len, float* coeffs, void* workspace, size_t workspace_bytes, void* stream)
+{
+    int rc = check_common(ws, path, B, n_points);
+    if (rc != SIG_OK) return rc;
+    if (K < 0 || max_window_len < 0 || max_window_len > n_points - 1) return SIG_EINVAL;
+    if (B == 0 || K == 0) return SIG_OK;
+    if (!windows || !coeffs) return SIG_EINVAL;
+    if (B * K > (int64_t)65535 * 64) return SIG_ETOOLARGE;
+    const sig::WordSet& w = *W(ws);
+    const int64_t n_sub = max_window_len + 1;
+    const size_t sb = win_sub_bytes(w, B, K, n_sub);
+    if (!workspace || workspace_bytes < sig_forward_windows_workspace_bytes(ws, B, n_points, K, max_window_len)) return SIG_EWORKSPACE;
+    if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
+    float* sub = (float*)workspace;
+    hipError_t e = sig::window_gather(path, B, n_points, w.d, windows, K, n_sub, sub, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return sig_forward(ws, sub, B * K, n_sub, coeffs, (unsigned char*)workspace + sb, workspace_bytes - sb, stream);
+}
+
+int sig_backward_windows(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                         int64_t n_points, const int64_t* windows, int64_t K, int64_t max_window_len, float* grad_path,
+                         void* workspace, size_t workspace_bytes, void* stream)
+{
+    int rc = check_common(ws, path, B, n_points);
+    if (rc != SIG_OK) return rc;
+    if (K < 0 || max_window_len < 0 || max_window_len > n_points - 1) return SIG_EINVAL;
+    if (B == 0) return SIG_OK;
+    if (!grad_path) return SIG_EINVAL;
+    const sig::WordSet& w = *W(ws);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = sig::fill_zero(grad_path, B * n_points * w.d, st);
+    if (e != hipSuccess) return hip_fail(e);
+    if (K == 0) return SIG_OK;
+    if (!windows || !coeffs || !grad_coeffs) return SIG_EINVAL;
+    if (B * K > (int64_t)65535 * 64) return SIG_ETOOLARGE;
+    const int64_t n_sub = max_window_len + 1;
+    const size_t sb = win_sub_bytes(w, B, K, n_sub);
+    if (!workspace || workspace_bytes < sig_backward_windows_workspace_bytes(ws, B, n_points, K, max_window_len)) return SIG_EWORKSPACE;
+    if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
+    float* sub = (float*)workspace;
+    float* gsub = (float*)((unsigned char*)workspace + sb);
+    e = sig::window_gather(path, B, n_points, w.d, windows, K, n_sub, sub, st);
+    if (e != hipSuccess) return hip_fail(e);
+    rc = sig_backward(ws, sub, coeffs, grad_coeffs, B * K, n_sub, gsub, (unsigned char*)workspace + 2 * sb, workspace_bytes - 2 * sb,
+                      stream);
+    if (rc != SIG_OK) return rc;
+    e = sig::window_scatter(gsub, B, n_points, w.d, windows, K, n_sub, grad_path, st);
+    return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
 int sig_profile_enable(int on)
 {
     g_prof.on = on != 0;

@@ -32,6 +32,11 @@ hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d,
 hipError_t fill_zero(float* p, int64_t n, hipStream_t stream);
 hipError_t leadlag(const float* path, int64_t B, int64_t P, int d, float* out, hipStream_t stream);            // out [B, 2P-1, 2d]
 hipError_t leadlag_backward(const float* gout, int64_t B, int64_t P, int d, float* gpath, hipStream_t stream);
+// windows: (path, window) pairs as paths of n_sub points each, and the adjoint of that gather
+hipError_t window_gather(const float* path, int64_t B, int64_t P, int d, const int64_t* win, int64_t K, int64_t n_sub, float* sub,
+                         hipStream_t stream);
+hipError_t window_scatter(const float* gsub, int64_t B, int64_t P, int d, const int64_t* win, int64_t K, int64_t n_sub,
+                          float* gpath, hipStream_t stream);
 hipError_t fma_probe(float* out, int blocks, int iters, hipStream_t stream);   // out: blocks * 256 floats
 hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* grad_path, hipStream_t stream);
 

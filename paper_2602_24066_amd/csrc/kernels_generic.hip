@@ -400,6 +400,60 @@ hipError_t leadlag_backward(const float* gout, int64_t B, int64_t P, int d, floa
     return hipGetLastError();
 }
 
+// Windows (Section 5): window k of a path covers the points l_k .. r_k (segments l_k .. r_k - 1).  Every (path,
+// window) pair becomes a path of its own with n_sub points: sub[b K + k][j] = X[b][min(l_k + j, r_k)] - the tail is
+// padded with the last point, i.e. with zero increments, which leave a signature unchanged.
+__global__ void window_gather_kernel(const float* __restrict__ path, int64_t B, int64_t P, int d, const int64_t* __restrict__ win,
+                                     int64_t K, int64_t n_sub, float* __restrict__ sub)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t n = B * K * n_sub * d;
+    if (i >= n) return;
+    const int c = (int)(i % d);
+    const int64_t j = (i / d) % n_sub;
+    const int64_t row = i / d / n_sub;
+    const int64_t b = row / K, k = row - b * K;
+    int64_t l = win[2 * k], r = win[2 * k + 1];
+    l = l < 0 ? 0 : (l > P - 1 ? P - 1 : l);
+    r = r < l ? l : (r > P - 1 ? P - 1 : r);
+    const int64_t src = l + j < r ? l + j : r;
+    sub[i] = path[(b * P + src) * d + c];
+}
+// adjoint of the gather: grad_path[b][min(l_k + j, r_k)] += grad_sub[b K + k][j]; grad_path zeroed by the caller
+__global__ void window_scatter_kernel(const float* __restrict__ gsub, int64_t B, int64_t P, int d, const int64_t* __restrict__ win,
+                                      int64_t K, int64_t n_sub, float* __restrict__ gpath)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t n = B * K * n_sub * d;
+    if (i >= n) return;
+    const int c = (int)(i % d);
+    const int64_t j = (i / d) % n_sub;
+    const int64_t row = i / d / n_sub;
+    const int64_t b = row / K, k = row - b * K;
+    int64_t l = win[2 * k], r = win[2 * k + 1];
+    l = l < 0 ? 0 : (l > P - 1 ? P - 1 : l);
+    r = r < l ? l : (r > P - 1 ? P - 1 : r);
+    const int64_t dst = l + j < r ? l + j : r;
+    unsafeAtomicAdd(gpath + (b * P + dst) * d + c, gsub[i]);
+}
+
+hipError_t window_gather(const float* path, int64_t B, int64_t P, int d, const int64_t* win, int64_t K, int64_t n_sub, float* sub,
+                         hipStream_t stream)
+{
+    const int64_t n = B * K * n_sub * d;
+    if (n <= 0) return hipSuccess;
+    window_gather_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(path, B, P, d, win, K, n_sub, sub);
+    return hipGetLastError();
+}
+hipError_t window_scatter(const float* gsub, int64_t B, int64_t P, int d, const int64_t* win, int64_t K, int64_t n_sub,
+                          float* gpath, hipStream_t stream)
+{
+    const int64_t n = B * K * n_sub * d;
+    if (n <= 0) return hipSuccess;
+    window_scatter_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(gsub, B, P, d, win, K, n_sub, gpath);
+    return hipGetLastError();
+}
+
 // Register-only multiply-add loop for the benchmark: every thread runs `iters` rounds of 16 independent fmaf chains
 // (no memory traffic inside the loop) and stores one value so that nothing is optimised away.
 __global__ __launch_bounds__(256) void fma_probe_kernel(float* out, int iters, float a, float b)

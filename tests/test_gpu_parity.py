@@ -171,6 +171,45 @@ def test_leadlag_transform_and_sparse_word_set():
     check_parity(ws, W, "words", None, Y, G, what="sparse lead-lag set")
 
 
+WINDOW_SETS = [
+    ("truncated", dict(d=3, depth=4)),
+    ("truncated", dict(d=4, depth=6)),
+    ("anisotropic", dict(d=4, weights=(1.0, 1.0, 2.0, 3.0), cutoff=5.0)),
+    ("words", dict(d=6, n_words=500, max_len=5)),
+]
+
+
+@pytest.mark.parametrize("case", range(len(WINDOW_SETS)))
+def test_windows(case):
+    """Signatures over user-given windows (expanding, sliding, overlapping, single-segment, empty, whole path) against
+    one oracle evaluation per window, forward and backward."""
+    import torch
+    kind, kw = WINDOW_SETS[case]
+    d = kw["d"]
+    words = random_prefix_closed_words(400 + case, d, kw["n_words"], kw["max_len"]) if kind == "words" else None
+    ws, W = build_both(kind, d, depth=kw.get("depth"), weights=kw.get("weights"), cutoff=kw.get("cutoff"), words=words)
+    B, L = 5, 40
+    X = make_path("time0" if kind == "truncated" and d == 4 else "iid", 410 + case, B, L, d)
+    windows = [(0, L), (0, 1), (0, 7), (0, 23), (5, 15), (10, 20), (15, 25), (39, 40), (17, 17), (3, 38), (5, 15)]
+    K = len(windows)
+    G = make_grad_coeffs(420 + case, B * K, ws.size).reshape(B, K, ws.size)
+    xp = torch.from_numpy(X).cuda()
+    coeffs = S.sig_forward_windows(ws, xp, windows)
+    gp = S.sig_backward_windows(ws, xp, windows, coeffs, torch.from_numpy(G).cuda())
+    torch.cuda.synchronize()
+    coeffs, gp = coeffs.cpu().numpy(), gp.cpu().numpy()
+    ref = O.forward_windows(X, W, windows)
+    lengths = np.array([len(w) for w in W])
+    for k, (l, r) in enumerate(windows):
+        if l == r:
+            assert np.all(coeffs[:, k] == 0.0)
+            continue
+        for n, e in O.level_errors(coeffs[:, k], ref[:, k], lengths).items():
+            assert e <= FWD_TOL, f"window {k} level {n}: {e:.3e}"
+    gref = O.backward_windows(X, W, windows, G.astype(np.float64))
+    assert O.grad_errors(gp, gref).max() <= BWD_TOL
+
+
 def test_one_point_paths_give_zero():
     import torch
     ws, W = build_both("truncated", 3, depth=3)

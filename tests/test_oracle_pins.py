@@ -497,3 +497,28 @@ def test_leadlag_area_is_quadratic_variation():
         for j in range(d):
             a = Sg[:, W.index((d + i, j))] - Sg[:, W.index((i, d + j))]
             np.testing.assert_allclose(a, (dX[:, :, i] * dX[:, :, j]).sum(axis=1), rtol=1e-10, atol=1e-12)
+
+
+def test_windows_by_chen_and_finite_differences():
+    """Signatures over windows (Section 5): S_{0,r} = S_{0,l} (x) S_{l,r} (Chen) ties every window to two expanding
+    ones; the windowed gradient is checked against central differences of the windowed forward."""
+    d, N, B, L = 2, 4, 2, 9
+    W = O.truncated_words(d, N)
+    X = _grid_path(95, B, L, d)
+    windows = [(0, 9), (2, 7), (4, 5), (3, 3), (0, 4), (4, 9)]
+    Sw = O.forward_windows(X.astype(np.float32), W, windows)
+    assert Sw.shape == (B, len(windows), len(W))
+    assert np.all(Sw[:, 3] == 0.0)                                     # a single point: the identity
+    for k, (l, r) in enumerate(windows):
+        if l == 0 or l == r:
+            continue
+        for b in range(B):
+            head = np.concatenate([[1.0], O.forward_dense(X[b:b + 1, :l + 1].astype(np.float32), N)[0]])
+            mid = np.concatenate([[1.0], Sw[b, k]])
+            whole = O.forward_dense(X[b:b + 1, :r + 1].astype(np.float32), N)[0]
+            np.testing.assert_allclose(O.tensor_product(d, N, head, mid)[1:], whole, rtol=1e-12, atol=1e-14)
+    G = np.random.default_rng(3).standard_normal(Sw.shape)
+    ana = O.backward_windows(X.astype(np.float32), W, windows, G)
+    fun = lambda Y: float((O.forward_windows(Y.astype(np.float32), W, windows) * G).sum())
+    num = fd_grad(fun, X, 2.0 ** -12)
+    np.testing.assert_allclose(ana, num, rtol=2e-6, atol=2e-6)
