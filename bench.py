@@ -39,6 +39,11 @@ def flops_backward(ws, B, L):
     return 2.0 * (3.0 * nw + 4.5 * (fmin - nw)) * B * L
 
 
+def WORKLOADS_REF_get():
+    from sig_workloads import WORKLOADS
+    return WORKLOADS
+
+
 def setup(name, S, torch):
     from sig_workloads import WORKLOADS, make_grad_coeffs, workload_path, workload_word_list
     wl = WORKLOADS[name]
@@ -272,6 +277,36 @@ def main():
                               "note": "host clock, includes the per-call workspace allocation of the Python wrapper"}
         except Exception as e:                       # an optional extra must not take the benchmark line down
             out["windows"] = {"error": str(e)[:200]}
+
+        # log-signature (Section 3.3) on the headline shape: signature on the reduced word set (every word shorter than
+        # the depth + the Lyndon words of full length), tensor logarithm word by word, and back
+        try:
+            from sig_workloads import workload_path as workload_path_ref
+            wlh = WORKLOADS_REF_get()[HEADLINE]
+            wsl = S.sig_wordset_build_logsig(wlh.d, wlh.depth)
+            wsl.upload("cuda:0")
+            Xl = torch.from_numpy(workload_path_ref(wlh)).cuda()
+            cl = S.sig_forward(wsl, Xl)
+            lg = S.sig_logsig_forward(wsl, cl)
+            gl = torch.randn_like(lg)
+            S.sig_backward(wsl, Xl, cl, S.sig_logsig_backward(wsl, cl, gl))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                cl = S.sig_forward(wsl, Xl)
+                lg = S.sig_logsig_forward(wsl, cl)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(10):
+                S.sig_backward(wsl, Xl, cl, S.sig_logsig_backward(wsl, cl, gl))
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            out["log_signature"] = {"workload": f"{wlh.name} shape, depth {wlh.depth}: {wsl.size} signature words for {lg.shape[1]} "
+                                                f"log-signature coordinates (full truncation: {st['ws'].size if args.workload == HEADLINE else '-'})",
+                                    "fwd_ms": round((t1 - t0) * 100, 4), "bwd_ms": round((t2 - t1) * 100, 4),
+                                    "note": "host clock; first call compiles the specialised kernels for the word set"}
+        except Exception as e:
+            out["log_signature"] = {"error": str(e)[:200]}
 
         # the other word-set builders (host only): graph-induced set and the sparse lead-lag set of a 5-dimensional path
         t0 = time.perf_counter()

@@ -172,6 +172,21 @@ int    sig_backward(const sig_wordset* ws, const float* path, const float* coeff
                     int64_t B, int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes,
                     void* stream);
 
+/* ---- log-signature (Section 3.3) -----------------------------------------------------------------------------
+ * Coordinates: for every Lyndon word w of length <= depth, the coefficient of w in the tensor logarithm of the
+ * signature (the Lyndon-word coordinates the paper takes from its reference on efficient Lie bases).  Only the
+ * coefficients of the factors of Lyndon words are needed: sig_wordset_build_logsig builds the set "every word shorter
+ * than depth + the Lyndon words of length depth"; user_index lists the columns of the Lyndon words (by length, then
+ * lexicographic), sig_wordset_n_lyndon their number.  Pipeline: sig_forward on that set, then sig_logsig_forward
+ * (coeffs [B, |W|] -> logsig [B, n_lyndon]); backward: sig_logsig_backward (grad_logsig -> grad_coeffs [B, |W|],
+ * overwritten), then sig_backward.  All pointers device, float32; the word set must be uploaded. */
+int     sig_wordset_build_logsig(int d, int depth, sig_wordset** out);
+int64_t sig_wordset_n_lyndon(const sig_wordset* ws);
+int     sig_logsig_forward(const sig_wordset* ws, const float* coeffs, int64_t B, float* logsig, void* stream);
+size_t  sig_logsig_backward_workspace_bytes(const sig_wordset* ws, int64_t B);
+int     sig_logsig_backward(const sig_wordset* ws, const float* coeffs, const float* grad_logsig, int64_t B, float* grad_coeffs,
+                            void* workspace /*device*/, size_t workspace_bytes, void* stream);
+
 /* ---- signatures over windows (Section 5) -------------------------------------------------------------------
  * windows: device int64 [K][2], point indices (l_k, r_k) with 0 <= l_k <= r_k < n_points; window k is the path
  *          restricted to the points l_k .. r_k (segments l_k .. r_k - 1; l_k == r_k gives the zero signature).

@@ -102,6 +102,54 @@ def anisotropic_words(d: int, weights: Sequence[float], cutoff: float) -> List[W
     return sort_canonical(out)
 
 
+def lyndon_words(d: int, depth: int) -> List[Word]:
+    """Lyndon words of length 1..depth over {0..d-1}: words strictly smaller than every proper rotation of themselves
+    (tested word by word), by length then lexicographic."""
+    import itertools
+    out: List[Word] = []
+    for n in range(1, depth + 1):
+        for w in itertools.product(range(d), repeat=n):
+            if all(w < w[k:] + w[:k] for k in range(1, n)):
+                out.append(w)
+    return out
+
+
+def logsig_word_set(d: int, depth: int) -> List[Word]:
+    """Every word shorter than depth plus the Lyndon words of length depth, canonical order."""
+    return sort_canonical(truncated_words(d, depth - 1) + [w for w in lyndon_words(d, depth) if len(w) == depth]) \
+        if depth > 1 else [(i,) for i in range(d)]
+
+
+def tensor_log(d: int, depth: int, S: np.ndarray) -> np.ndarray:
+    """Tensor logarithm of a dense element 1 + x laid out [1 | level 1 | .. | level depth] (Section 3.3):
+    log(1 + x) = sum_{k=1..depth} (-1)^{k+1} x^k / k with truncated tensor products; the result has level 0 = 0."""
+    x = np.array(S, dtype=np.float64)
+    x[0] = 0.0
+    one_plus = np.zeros_like(x)
+    out = np.zeros_like(x)
+    power = np.zeros_like(x)
+    power[0] = 1.0                                   # x^0
+    for k in range(1, depth + 1):
+        power = tensor_product(d, depth, power, x)   # x^k (its levels below k vanish)
+        out += ((-1.0) ** (k + 1) / k) * power
+    return out
+
+
+def logsig_from_path(X: np.ndarray, depth: int) -> np.ndarray:
+    """Log-signature in Lyndon-word coordinates: the coefficients of the Lyndon words in the tensor logarithm of the
+    full truncated signature; [B, number of Lyndon words]."""
+    B, _, d = X.shape
+    words = truncated_words(d, depth)
+    index = {w: k for k, w in enumerate(words)}
+    cols = [index[w] for w in lyndon_words(d, depth)]
+    S = forward_dense(X, depth)
+    out = np.zeros((B, len(cols)))
+    for b in range(B):
+        L = tensor_log(d, depth, np.concatenate([[1.0], S[b]]))[1:]
+        out[b] = L[cols]
+    return out
+
+
 def forward_windows(X: np.ndarray, W: Sequence[Word], windows: Sequence[Tuple[int, int]]) -> np.ndarray:
     """Signatures over windows (Section 5): window (l, r) is the path restricted to its points l..r.  One plain forward
     evaluation per window on the sliced path; [B, K, |W|]."""

@@ -55,6 +55,11 @@ def load_library():
     sig("sig_backward_windows_workspace_bytes", c_sz, [c_p, c_i64, c_i64, c_i64, c_i64])
     sig("sig_forward_windows", c_int, [c_p, c_p, c_i64, c_i64, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
     sig("sig_backward_windows", c_int, [c_p, c_p, c_p, c_p, c_i64, c_i64, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
+    sig("sig_wordset_build_logsig", c_int, [c_int, c_int, PP])
+    sig("sig_wordset_n_lyndon", c_i64, [c_p])
+    sig("sig_logsig_forward", c_int, [c_p, c_p, c_i64, c_p, c_p])
+    sig("sig_logsig_backward_workspace_bytes", c_sz, [c_p, c_i64])
+    sig("sig_logsig_backward", c_int, [c_p, c_p, c_p, c_i64, c_p, c_p, c_sz, c_p])
     sig("sig_wordset_build_graph", c_int, [c_int, c_p, c_i64, c_int, PP])
     sig("sig_wordset_build_leadlag_sparse", c_int, [c_int, c_int, PP])
     sig("sig_leadlag_transform", c_int, [c_p, c_i64, c_i64, c_int, c_p, c_p])
@@ -303,6 +308,48 @@ def sig_leadlag_backward(grad_out, out=None):
         stream = torch.cuda.current_stream().cuda_stream
         _check(load_library().sig_leadlag_backward(ctypes.c_void_p(grad_out.data_ptr()), B, P, d, ctypes.c_void_p(out.data_ptr()),
                                                    ctypes.c_void_p(stream)), "sig_leadlag_backward")
+    return out
+
+
+def sig_wordset_build_logsig(d: int, depth: int) -> WordSet:
+    """Word set for log-signatures of the given depth (every word shorter than depth + the Lyndon words of length depth);
+    user_index holds the columns of the Lyndon words."""
+    h = ctypes.c_void_p()
+    _check(load_library().sig_wordset_build_logsig(d, depth, ctypes.byref(h)), "sig_wordset_build_logsig")
+    return WordSet(h.value)
+
+
+def sig_logsig_forward(ws: WordSet, coeffs):
+    """coeffs float32 CUDA [B, |W|] (from sig_forward on a log-signature word set) -> logsig [B, n_lyndon]."""
+    import torch
+    coeffs = coeffs.contiguous()
+    B = coeffs.shape[0]
+    lib = load_library()
+    n = int(lib.sig_wordset_n_lyndon(ws._h))
+    out = torch.empty((B, n), dtype=torch.float32, device=coeffs.device)
+    with torch.cuda.device(coeffs.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(lib.sig_logsig_forward(ws._h, ctypes.c_void_p(coeffs.data_ptr()), B, ctypes.c_void_p(out.data_ptr()),
+                                      ctypes.c_void_p(stream)), "sig_logsig_forward")
+    return out
+
+
+def sig_logsig_backward(ws: WordSet, coeffs, grad_logsig):
+    """grad_logsig [B, n_lyndon] -> gradient with respect to the signature coefficients [B, |W|]."""
+    import torch
+    coeffs, grad_logsig = coeffs.contiguous(), grad_logsig.contiguous()
+    B = coeffs.shape[0]
+    lib = load_library()
+    out = torch.empty_like(coeffs)
+    nbytes = int(lib.sig_logsig_backward_workspace_bytes(ws._h, B))
+    keep, wptr = _aligned_workspace(nbytes, coeffs.device)
+    with torch.cuda.device(coeffs.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(lib.sig_logsig_backward(ws._h, ctypes.c_void_p(coeffs.data_ptr()), ctypes.c_void_p(grad_logsig.data_ptr()), B,
+                                       ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(wptr), nbytes, ctypes.c_void_p(stream)),
+               "sig_logsig_backward")
+    if keep is not None:
+        keep.record_stream(torch.cuda.current_stream(coeffs.device))
     return out
 
 

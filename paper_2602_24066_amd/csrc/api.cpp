@@ -301,6 +301,56 @@ int sig_wordset_build_leadlag_sparse(int d, int depth, sig_wordset** out)
     return rc;
 }
 
+int sig_wordset_build_logsig(int d, int depth, sig_wordset** out)
+{
+    if (!out) return SIG_EINVAL;
+    sig::WordSet* w = nullptr;
+    int rc = sig::build_logsig(d, depth, &w);
+    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
+    return rc;
+}
+
+int64_t sig_wordset_n_lyndon(const sig_wordset* ws) { return ws ? W(ws)->n_lyndon : -1; }
+
+int sig_logsig_forward(const sig_wordset* ws, const float* coeffs, int64_t B, float* logsig, void* stream)
+{
+    if (!ws || B < 0) return SIG_EINVAL;
+    const sig::WordSet& w = *W(ws);
+    if (w.n_lyndon <= 0) return SIG_EUNSUPPORTED;
+    if (!w.dev) return SIG_ENOTUPLOADED;
+    if (B == 0) return SIG_OK;
+    if (!coeffs || !logsig) return SIG_EINVAL;
+    const unsigned char* base = (const unsigned char*)w.dev;
+    hipError_t e = sig::logsig_forward(coeffs, B, w.size(), (const int32_t*)(base + w.lyn_len_off),
+                                       (const int32_t*)(base + w.lyn_sub_off), w.n_lyndon, w.lyn_stride, w.depth, logsig,
+                                       (hipStream_t)stream);
+    return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
+size_t sig_logsig_backward_workspace_bytes(const sig_wordset* ws, int64_t B)
+{
+    if (!ws || B <= 0 || W(ws)->n_lyndon <= 0) return 0;
+    return ((size_t)B * (size_t)W(ws)->n_lyndon * (size_t)W(ws)->lyn_pairs * sizeof(float) + 255) & ~(size_t)255;
+}
+
+int sig_logsig_backward(const sig_wordset* ws, const float* coeffs, const float* grad_logsig, int64_t B, float* grad_coeffs,
+                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!ws || B < 0) return SIG_EINVAL;
+    const sig::WordSet& w = *W(ws);
+    if (w.n_lyndon <= 0) return SIG_EUNSUPPORTED;
+    if (!w.dev) return SIG_ENOTUPLOADED;
+    if (B == 0) return SIG_OK;
+    if (!coeffs || !grad_logsig || !grad_coeffs) return SIG_EINVAL;
+    if (!workspace || workspace_bytes < sig_logsig_backward_workspace_bytes(ws, B)) return SIG_EWORKSPACE;
+    const unsigned char* base = (const unsigned char*)w.dev;
+    hipError_t e = sig::logsig_backward(coeffs, grad_logsig, B, w.size(), (const int32_t*)(base + w.lyn_len_off),
+                                        (const int32_t*)(base + w.lyn_sub_off), w.n_lyndon, w.lyn_stride, w.depth, w.lyn_pairs,
+                                        (const int32_t*)(base + w.lyn_inv_off_off), (const int32_t*)(base + w.lyn_inv_ent_off),
+                                        (float*)workspace, grad_coeffs, (hipStream_t)stream);
+    return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
 int sig_leadlag_transform(const float* path, int64_t B, int64_t n_points, int d, float* out, void* stream)
 {
     if (B < 0 || n_points < 1 || d < 1) return SIG_EINVAL;

@@ -37,6 +37,12 @@ hipError_t window_gather(const float* path, int64_t B, int64_t P, int d, const i
                          hipStream_t stream);
 hipError_t window_scatter(const float* gsub, int64_t B, int64_t P, int d, const int64_t* win, int64_t K, int64_t n_sub,
                           float* gpath, hipStream_t stream);
+// log-signature coordinates from signature coefficients, and the adjoint (gcoeffs overwritten)
+hipError_t logsig_forward(const float* coeffs, int64_t B, int64_t nW, const int32_t* lyn_len, const int32_t* lyn_sub, int64_t n_lyn,
+                          int stride, int depth, float* out, hipStream_t stream);
+hipError_t logsig_backward(const float* coeffs, const float* glog, int64_t B, int64_t nW, const int32_t* lyn_len,
+                           const int32_t* lyn_sub, int64_t n_lyn, int stride, int depth, int n_pairs, const int32_t* inv_off,
+                           const int32_t* inv, float* part /*[B, n_lyn, n_pairs]*/, float* gcoeffs, hipStream_t stream);
 hipError_t fma_probe(float* out, int blocks, int iters, hipStream_t stream);   // out: blocks * 256 floats
 hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* grad_path, hipStream_t stream);
 

@@ -454,6 +454,169 @@ hipError_t window_scatter(const float* gsub, int64_t B, int64_t P, int d, const 
     return hipGetLastError();
 }
 
+// ---- log-signature in Lyndon-word coordinates (Section 3.3): the coefficient of the Lyndon word w in the tensor
+// logarithm log(1 + x) = sum_k (-1)^{k+1} x^k / k of the signature, where (x^k)(w) sums, over the ways of cutting w
+// into k non-empty pieces, the product of the pieces' signature coefficients.  With Q_k[j] = sum over cuts of w[0:j]
+// into k pieces:  Q_1[j] = S(w[0:j]),  Q_k[j] = sum_m Q_{k-1}[m] S(w[m:j]),  logsig(w) = sum_k (-1)^{k+1} Q_k[n] / k.
+constexpr int kMaxLogDepth = 12;
+
+// DEPTH > 0: compile-time bound on the word length, all loops unrolled so that the small tables stay in registers;
+// DEPTH == 0: any length up to kMaxLogDepth (tables in scratch memory).
+template <int DEPTH>
+__global__ void logsig_forward_kernel(const float* __restrict__ coeffs, int64_t B, int64_t nW, const int32_t* __restrict__ lyn_len,
+                                      const int32_t* __restrict__ lyn_sub, int64_t n_lyn, int stride, int depth,
+                                      float* __restrict__ out)
+{
+    constexpr int MD = DEPTH ? DEPTH : kMaxLogDepth;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * n_lyn) return;
+    const int64_t b = idx / n_lyn, k = idx - b * n_lyn;
+    const int n = lyn_len[k];
+    const int32_t* sub = lyn_sub + k * stride;
+    const float* S = coeffs + b * nW;
+    // sw[i][j] = S(w[i:j]) for 0 <= i < j <= n
+    float sw[MD][MD + 1];
+#pragma unroll
+    for (int i = 0; i < MD; ++i)
+#pragma unroll
+        for (int j = 0; j <= MD; ++j) sw[i][j] = (i < j && j <= n) ? S[sub[i * (depth + 1) + j]] : 0.0f;
+    float Q[MD + 1], Qn[MD + 1];
+#pragma unroll
+    for (int j = 0; j <= MD; ++j) Q[j] = j == 0 ? 0.0f : sw[0][j];                  // one piece: w[0:j]
+    float acc = 0.0f;
+#pragma unroll
+    for (int j = 1; j <= MD; ++j) acc = j == n ? Q[j] : acc;
+#pragma unroll
+    for (int kk = 2; kk <= MD; ++kk) {
+#pragma unroll
+        for (int j = 0; j <= MD; ++j) {
+            float v = 0.0f;
+#pragma unroll
+            for (int m = 1; m < MD; ++m)
+                if (m >= kk - 1 && m < j) v = fmaf(Q[m], sw[m][j], v);
+            Qn[j] = v;
+        }
+        float qn = 0.0f;
+#pragma unroll
+        for (int j = 0; j <= MD; ++j) { Q[j] = Qn[j]; qn = j == n ? Qn[j] : qn; }
+        if (kk <= n) acc += ((kk & 1) ? 1.0f : -1.0f) / (float)kk * qn;
+    }
+    out[idx] = acc;
+}
+
+// d logsig(w) / d S(w[i:j]) = sum_{a, c >= 0} (-1)^{a+c} / (a + c + 1) * Pre_a[i] * Suf_c[j], with Pre_a[i] the sum over
+// cuts of w[0:i] into a pieces (Pre_0[0] = 1) and Suf_c[j] the same for w[j:n] (Suf_0[n] = 1).  Sub-words are shared
+// between Lyndon words (a single letter by thousands of them), so the contributions are not added with atomics:
+// this kernel writes them to part[(b n_lyn + k) n_pairs + pair(i, j)] and logsig_gather_kernel sums, per sub-word,
+// the entries an inverse table lists.
+template <int DEPTH>
+__global__ void logsig_backward_kernel(const float* __restrict__ coeffs, const float* __restrict__ glog, int64_t B, int64_t nW,
+                                       const int32_t* __restrict__ lyn_len, const int32_t* __restrict__ lyn_sub, int64_t n_lyn,
+                                       int stride, int depth, int n_pairs, float* __restrict__ part)
+{
+    constexpr int MD = DEPTH ? DEPTH : kMaxLogDepth;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * n_lyn) return;
+    const int64_t b = idx / n_lyn, k = idx - b * n_lyn;
+    const int n = lyn_len[k];
+    const int32_t* sub = lyn_sub + k * stride;
+    const float* S = coeffs + b * nW;
+    const float g = glog[idx];
+    float sw[MD][MD + 1];
+#pragma unroll
+    for (int i = 0; i < MD; ++i)
+#pragma unroll
+        for (int j = 0; j <= MD; ++j) sw[i][j] = (i < j && j <= n) ? S[sub[i * (depth + 1) + j]] : 0.0f;
+    // pre[a][i], suf[c][j] for a, c = 0..n-1 (pieces that reach beyond n are zero through sw)
+    float pre[MD][MD + 1], suf[MD][MD + 1];
+#pragma unroll
+    for (int i = 0; i <= MD; ++i) { pre[0][i] = i == 0 ? 1.0f : 0.0f; suf[0][i] = i == n ? 1.0f : 0.0f; }
+#pragma unroll
+    for (int a = 1; a < MD; ++a)
+#pragma unroll
+        for (int i = 0; i <= MD; ++i) {
+            float v = 0.0f, u = 0.0f;
+#pragma unroll
+            for (int m = 0; m < MD; ++m)
+                if (m < i) v = fmaf(pre[a - 1][m], sw[m][i], v);
+#pragma unroll
+            for (int m = 1; m <= MD; ++m)
+                if (m > i && i < MD) u = fmaf(sw[i < MD ? i : 0][m], suf[a - 1][m], u);
+            pre[a][i] = v;
+            suf[a][i] = u;
+        }
+    float* dst = part + idx * n_pairs;
+#pragma unroll
+    for (int i = 0; i < MD; ++i)
+#pragma unroll
+        for (int j = i + 1; j <= MD; ++j) {
+            if (j > n) continue;
+            const int pair = i * depth - i * (i - 1) / 2 + (j - i - 1);      // pairs i < j <= depth in row-major order
+            float t = 0.0f;
+#pragma unroll
+            for (int a = 0; a < MD; ++a)
+#pragma unroll
+                for (int c = 0; c < MD; ++c)
+                    if (a + c < MD) t = fmaf((((a + c) & 1) ? -1.0f : 1.0f) / (float)(a + c + 1), pre[a][i] * suf[c][j], t);
+            dst[pair] = g * t;
+        }
+}
+
+// one wavefront per (path, sub-word): the lists of short sub-words are thousands of entries long
+__global__ __launch_bounds__(256) void logsig_gather_kernel(const float* __restrict__ part, int64_t B, int64_t nW, int64_t n_lyn,
+                                                            int n_pairs, const int32_t* __restrict__ inv_off,
+                                                            const int32_t* __restrict__ inv, float* __restrict__ gcoeffs)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t idx = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (idx >= B * nW) return;
+    const int64_t b = idx / nW, u = idx - b * nW;
+    const float* src = part + b * n_lyn * n_pairs;
+    float acc = 0.0f;
+    for (int32_t e = inv_off[u] + lane; e < inv_off[u + 1]; e += 64) acc += src[inv[e]];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    if (lane == 0) gcoeffs[idx] = acc;
+}
+
+hipError_t logsig_forward(const float* coeffs, int64_t B, int64_t nW, const int32_t* lyn_len, const int32_t* lyn_sub, int64_t n_lyn,
+                          int stride, int depth, float* out, hipStream_t stream)
+{
+    const int64_t n = B * n_lyn;
+    if (n <= 0) return hipSuccess;
+    if (depth > kMaxLogDepth) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((n + 127) / 128);
+#define SIG_LOGSIG_FWD(DEPTH) logsig_forward_kernel<DEPTH><<<grid, 128, 0, stream>>>(coeffs, B, nW, lyn_len, lyn_sub, n_lyn, stride, depth, out)
+    if (depth <= 4) SIG_LOGSIG_FWD(4);
+    else if (depth <= 6) SIG_LOGSIG_FWD(6);
+    else if (depth <= 8) SIG_LOGSIG_FWD(8);
+    else SIG_LOGSIG_FWD(0);
+#undef SIG_LOGSIG_FWD
+    return hipGetLastError();
+}
+hipError_t logsig_backward(const float* coeffs, const float* glog, int64_t B, int64_t nW, const int32_t* lyn_len,
+                           const int32_t* lyn_sub, int64_t n_lyn, int stride, int depth, int n_pairs, const int32_t* inv_off,
+                           const int32_t* inv, float* part, float* gcoeffs, hipStream_t stream)
+{
+    const int64_t n = B * n_lyn;
+    if (n <= 0) return hipSuccess;
+    if (depth > kMaxLogDepth) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((n + 127) / 128);
+#define SIG_LOGSIG_BWD(DEPTH) \
+    logsig_backward_kernel<DEPTH><<<grid, 128, 0, stream>>>(coeffs, glog, B, nW, lyn_len, lyn_sub, n_lyn, stride, depth, n_pairs, part)
+    if (depth <= 4) SIG_LOGSIG_BWD(4);
+    else if (depth <= 6) SIG_LOGSIG_BWD(6);
+    else if (depth <= 8) SIG_LOGSIG_BWD(8);
+    else SIG_LOGSIG_BWD(0);
+#undef SIG_LOGSIG_BWD
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t m = (B * nW + 3) / 4;                  // four wavefronts per workgroup
+    if (m > 0x7fffffff) return hipErrorInvalidValue;
+    logsig_gather_kernel<<<(unsigned)m, 256, 0, stream>>>(part, B, nW, n_lyn, n_pairs, inv_off, inv, gcoeffs);
+    return hipGetLastError();
+}
+
 // Register-only multiply-add loop for the benchmark: every thread runs `iters` rounds of 16 independent fmaf chains
 // (no memory traffic inside the loop) and stores one value so that nothing is optimised away.
 __global__ __launch_bounds__(256) void fma_probe_kernel(float* out, int iters, float a, float b)

@@ -564,4 +564,111 @@ int build_leadlag_sparse(int d, int depth, WordSet** out)
     } catch (const std::bad_alloc&) { return SIG_ENOMEM; }
 }
 
+// Lyndon words of length exactly n over {0..d-1} in lexicographic order (Duval's generation algorithm).
+static void lyndon_words_of_length(int d, int n, std::vector<int32_t>& letters, std::vector<int64_t>& offsets)
+{
+    std::vector<int32_t> w(1, -1);
+    while (!w.empty()) {
+        w.back() += 1;
+        if ((int)w.size() == n) {
+            letters.insert(letters.end(), w.begin(), w.end());
+            offsets.push_back((int64_t)letters.size());
+        }
+        const size_t m = w.size();
+        while ((int)w.size() < n) w.push_back(w[w.size() - m]);
+        while (!w.empty() && w.back() == d - 1) w.pop_back();
+    }
+}
+
+int build_logsig(int d, int depth, WordSet** out)
+{
+    if (!out || check_d(d) != SIG_OK || depth < 1) return SIG_EINVAL;
+    if (depth > SIG_MAX_KERNEL_LEN) return SIG_ETOOLARGE;
+    try {
+        // user list: the Lyndon words of length 1..depth, then every word of length depth - 1 (whose prefixes
+        // complete the lower levels)
+        std::vector<int32_t> letters;
+        std::vector<int64_t> offsets(1, 0);
+        for (int n = 1; n <= depth; ++n) lyndon_words_of_length(d, n, letters, offsets);
+        const int64_t n_lyn = (int64_t)offsets.size() - 1;
+        if (depth >= 2) {
+            double cnt = 1.0;
+            for (int k = 0; k < depth - 1; ++k) cnt *= d;
+            if (cnt > (double)kMaxWords) return SIG_ETOOLARGE;
+            std::vector<int32_t> w((size_t)depth - 1, 0);
+            while (true) {
+                letters.insert(letters.end(), w.begin(), w.end());
+                offsets.push_back((int64_t)letters.size());
+                int k = depth - 2;
+                while (k >= 0 && w[(size_t)k] == d - 1) { w[(size_t)k] = 0; --k; }
+                if (k < 0) break;
+                w[(size_t)k] += 1;
+            }
+        }
+        WordSet* ws = nullptr;
+        int rc = build_list(d, letters.data(), offsets.data(), (int64_t)offsets.size() - 1, &ws);
+        if (rc != SIG_OK) return rc;
+        ws->user_index.resize((size_t)n_lyn);            // only the Lyndon words are "requested"
+        // sub-word table: walk the trie by the parent/letter tables through a (parent, letter) -> child map
+        std::unordered_map<uint64_t, int32_t> child;
+        child.reserve((size_t)ws->size() * 2);
+        for (int64_t v = 0; v < ws->size(); ++v)
+            child.emplace(((uint64_t)(uint32_t)(ws->parent[(size_t)v] + 1) << 32) | (uint32_t)ws->letter[(size_t)v], (int32_t)v);
+        ws->n_lyndon = n_lyn;
+        ws->lyn_stride = (depth + 1) * (depth + 1);
+        ws->lyn_len.assign((size_t)n_lyn, 0);
+        ws->lyn_sub.assign((size_t)n_lyn * (size_t)ws->lyn_stride, -1);
+        for (int64_t k = 0; k < n_lyn; ++k) {
+            const int n = (int)(offsets[(size_t)k + 1] - offsets[(size_t)k]);
+            const int32_t* w = letters.data() + offsets[(size_t)k];
+            ws->lyn_len[(size_t)k] = n;
+            for (int i = 0; i < n; ++i) {
+                int32_t cur = -1;
+                for (int j = i + 1; j <= n; ++j) {
+                    auto it = child.find(((uint64_t)(uint32_t)(cur + 1) << 32) | (uint32_t)w[j - 1]);
+                    if (it == child.end()) { delete ws; return SIG_EINVAL; }       // cannot happen: the set holds all factors
+                    cur = it->second;
+                    ws->lyn_sub[(size_t)k * (size_t)ws->lyn_stride + (size_t)i * (size_t)(depth + 1) + (size_t)j] = cur;
+                }
+            }
+        }
+        // inverse table (counting sort by sub-word)
+        ws->lyn_pairs = depth * (depth + 1) / 2;
+        ws->lyn_inv_off.assign((size_t)ws->size() + 1, 0);
+        for (int64_t k = 0; k < n_lyn; ++k)
+            for (int i = 0; i < ws->lyn_len[(size_t)k]; ++i)
+                for (int j = i + 1; j <= ws->lyn_len[(size_t)k]; ++j)
+                    ws->lyn_inv_off[(size_t)ws->lyn_sub[(size_t)k * (size_t)ws->lyn_stride + (size_t)i * (size_t)(depth + 1) + (size_t)j] + 1]++;
+        for (int64_t u = 0; u < ws->size(); ++u) ws->lyn_inv_off[(size_t)u + 1] += ws->lyn_inv_off[(size_t)u];
+        ws->lyn_inv.assign((size_t)ws->lyn_inv_off[(size_t)ws->size()], 0);
+        {
+            std::vector<int32_t> fill(ws->lyn_inv_off.begin(), ws->lyn_inv_off.end() - 1);
+            for (int64_t k = 0; k < n_lyn; ++k) {
+                int pair = 0;
+                for (int i = 0; i < depth; ++i)
+                    for (int j = i + 1; j <= depth; ++j, ++pair) {
+                        if (j > ws->lyn_len[(size_t)k]) continue;
+                        const int32_t u = ws->lyn_sub[(size_t)k * (size_t)ws->lyn_stride + (size_t)i * (size_t)(depth + 1) + (size_t)j];
+                        ws->lyn_inv[(size_t)fill[(size_t)u]++] = (int32_t)(k * ws->lyn_pairs + pair);
+                    }
+            }
+        }
+        if ((int64_t)n_lyn * ws->lyn_pairs > 0x7fffffff) { delete ws; return SIG_ETOOLARGE; }
+        // append the tables to the device image
+        auto append = [&](const void* src, size_t bytes) {
+            const size_t off = (ws->image.size() + 255) & ~(size_t)255;
+            ws->image.resize(off + ((bytes + 255) & ~(size_t)255), 0);
+            std::memcpy(&ws->image[off], src, bytes);
+            return off;
+        };
+        ws->lyn_len_off = append(ws->lyn_len.data(), ws->lyn_len.size() * sizeof(int32_t));
+        ws->lyn_sub_off = append(ws->lyn_sub.data(), ws->lyn_sub.size() * sizeof(int32_t));
+        ws->lyn_inv_off_off = append(ws->lyn_inv_off.data(), ws->lyn_inv_off.size() * sizeof(int32_t));
+        ws->lyn_inv_ent_off = append(ws->lyn_inv.data(), std::max<size_t>(ws->lyn_inv.size(), 1) * sizeof(int32_t));
+        ws->depth = depth;
+        *out = ws;
+        return SIG_OK;
+    } catch (const std::bad_alloc&) { return SIG_ENOMEM; }
+}
+
 }  // namespace sig

@@ -65,6 +65,17 @@ struct WordSet {
     struct PlanOffsets { size_t units, ops, slots; };
     std::vector<PlanOffsets> offsets[2];
     std::vector<unsigned char> image;
+    // log-signature (sets built by build_logsig only): for every Lyndon word of length <= depth, its length and the
+    // canonical indices of all its contiguous sub-words w[i:j], 0 <= i < j <= n, at lyn_sub[k * lyn_stride + i * (depth + 1) + j]
+    int64_t n_lyndon = 0;
+    int lyn_stride = 0;
+    std::vector<int32_t> lyn_len, lyn_sub;
+    // inverse of lyn_sub for the backward pass: word u is the factor w_k[i:j] for the entries
+    // lyn_inv[lyn_inv_off[u] .. lyn_inv_off[u + 1]), each k * lyn_pairs + pair(i, j), pair(i, j) counting the pairs
+    // i < j <= depth in the order i = 0.., j = i + 1..
+    int lyn_pairs = 0;
+    std::vector<int32_t> lyn_inv_off, lyn_inv;
+    size_t lyn_len_off = 0, lyn_sub_off = 0, lyn_inv_off_off = 0, lyn_inv_ent_off = 0;    // offsets in the device image
     void* dev = nullptr;
     bool kernels_supported = true;     // false when max_len exceeds what the kernels handle
     // run-time specialised kernels with the balanced plan each was generated from, per direction, keyed by the
@@ -88,6 +99,9 @@ int build_anisotropic(int d, const double* weights, double cutoff, WordSet** out
 int build_list(int d, const int32_t* letters, const int64_t* offsets, int64_t n_words, WordSet** out);
 int build_graph(int d, const int32_t* edges, int64_t n_edges, int depth, WordSet** out);
 int build_leadlag_sparse(int d, int depth, WordSet** out);
+// Word set for the log-signature of depth `depth` in the Lyndon-word coordinates: every word shorter than depth and
+// the Lyndon words of length depth; user_index lists the Lyndon words of all lengths (by length, then lexicographic).
+int build_logsig(int d, int depth, WordSet** out);
 
 // Splits the word tree into work units of at most max_slots words and about target_cost multiply-adds.
 void build_plan(const WordSet& ws, int max_slots, int64_t target_cost, bool with_leave, Plan& plan);

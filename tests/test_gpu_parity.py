@@ -210,6 +210,50 @@ def test_windows(case):
     assert O.grad_errors(gp, gref).max() <= BWD_TOL
 
 
+@pytest.mark.parametrize("d,depth,B,L", [(2, 6, 7, 20), (3, 4, 66, 15), (4, 5, 3, 9), (5, 1, 2, 4)])
+def test_log_signature(d, depth, B, L):
+    """Log-signature in Lyndon-word coordinates: signature on the reduced word set, then the tensor logarithm word by
+    word, against the oracle's dense tensor logarithm of the full truncated signature."""
+    import torch
+    ws = S.sig_wordset_build_logsig(d, depth)
+    ws.upload("cuda:0")
+    X = make_path("iid", 500 + d, B, L, d)
+    xp = torch.from_numpy(X).cuda()
+    coeffs = S.sig_forward(ws, xp)
+    lg = S.sig_logsig_forward(ws, coeffs).cpu().numpy()
+    ref = O.logsig_from_path(X, depth)
+    lyn = O.lyndon_words(d, depth)
+    assert lg.shape == ref.shape == (B, len(lyn))
+    lengths = np.array([len(w) for w in lyn])
+    for n, e in O.level_errors(lg, ref, lengths).items():
+        assert e <= FWD_TOL, f"log-signature level {n}: {e:.3e}"
+
+
+def test_log_signature_gradient():
+    """d <G, logsig(X)> / dX through sig_logsig_backward and sig_backward against central differences of the oracle."""
+    import torch
+    d, depth, B, L = 3, 4, 2, 5
+    ws = S.sig_wordset_build_logsig(d, depth)
+    ws.upload("cuda:0")
+    # points on a grid of 2^-6, so that X +- h is exact in fp32 (the oracle consumes fp32 paths)
+    X = (np.round(make_path("iid", 510, B, L, d) * 64.0) / 64.0).astype(np.float32)
+    G = np.random.default_rng(511).standard_normal((B, int(S.load_library().sig_wordset_n_lyndon(ws._h)))).astype(np.float32)
+    xp = torch.from_numpy(X).cuda()
+    coeffs = S.sig_forward(ws, xp)
+    gc = S.sig_logsig_backward(ws, coeffs, torch.from_numpy(G).cuda())
+    gp = S.sig_backward(ws, xp, coeffs, gc).cpu().numpy()
+    Xd = X.astype(np.float64)
+    fun = lambda Y: float((O.logsig_from_path(Y, depth) * G).sum())
+    num = np.zeros_like(Xd)
+    h = 2.0 ** -10
+    for idx in np.ndindex(*Xd.shape):
+        Yp, Ym = Xd.copy(), Xd.copy()
+        Yp[idx] += h
+        Ym[idx] -= h
+        num[idx] = (fun(Yp) - fun(Ym)) / (2 * h)
+    assert O.grad_errors(gp, num).max() <= BWD_TOL
+
+
 def test_one_point_paths_give_zero():
     import torch
     ws, W = build_both("truncated", 3, depth=3)

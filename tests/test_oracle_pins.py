@@ -522,3 +522,55 @@ def test_windows_by_chen_and_finite_differences():
     fun = lambda Y: float((O.forward_windows(Y.astype(np.float32), W, windows) * G).sum())
     num = fd_grad(fun, X, 2.0 ** -12)
     np.testing.assert_allclose(ana, num, rtol=2e-6, atol=2e-6)
+
+
+def test_lyndon_words_and_tensor_log():
+    """Log-signature coordinates (Section 3.3).  Counts by Witt's formula; a single segment has a log-signature of
+    level 1 only; two segments give the Baker-Campbell-Hausdorff area term 1/2 (a_i b_j - a_j b_i) at the Lyndon word
+    (i, j); exponentiating the logarithm returns the signature."""
+    def mobius(n):
+        r, p, m = 1, 2, n
+        while p * p <= m:
+            if m % p == 0:
+                m //= p
+                if m % p == 0:
+                    return 0
+                r = -r
+            p += 1
+        return -r if m > 1 else r
+    for d, N in [(2, 6), (3, 4), (4, 3)]:
+        lyn = O.lyndon_words(d, N)
+        for n in range(1, N + 1):
+            witt = sum(mobius(k) * d ** (n // k) for k in range(1, n + 1) if n % k == 0) // n
+            assert sum(1 for w in lyn if len(w) == n) == witt
+    d, N = 3, 4
+    lyn = O.lyndon_words(d, N)
+    a = np.array([0.3, -0.7, 0.2])
+    b = np.array([-0.4, 0.1, 0.9])
+    one = np.stack([np.zeros(d), a])[None].astype(np.float32)
+    L1 = O.logsig_from_path(one, N)[0]
+    for k, w in enumerate(lyn):
+        ref = float(np.float32(a[w[0]])) if len(w) == 1 else 0.0
+        assert abs(L1[k] - ref) <= 1e-12
+    two = np.stack([np.zeros(d), a, a + b])[None].astype(np.float32)
+    af, bf = two[0, 1].astype(np.float64), (two[0, 2].astype(np.float64) - two[0, 1].astype(np.float64))
+    L2 = O.logsig_from_path(two, N)[0]
+    for k, w in enumerate(lyn):
+        if len(w) == 1:
+            assert abs(L2[k] - (af[w[0]] + bf[w[0]])) <= 1e-12
+        if len(w) == 2:
+            i, j = w
+            assert abs(L2[k] - 0.5 * (af[i] * bf[j] - af[j] * bf[i])) <= 1e-12
+    # exp(log S) = S on a longer path
+    X = make_path("iid", 99, 1, 7, d)
+    Sd = np.concatenate([[1.0], O.forward_dense(X, N)[0]])
+    Lg = O.tensor_log(d, N, Sd)
+    assert Lg[0] == 0.0
+    ex = np.zeros_like(Sd)
+    term = np.zeros_like(Sd)
+    term[0] = 1.0
+    ex += term
+    for k in range(1, N + 1):
+        term = O.tensor_product(d, N, term, Lg) / k
+        ex += term
+    np.testing.assert_allclose(ex, Sd, rtol=1e-12, atol=1e-14)

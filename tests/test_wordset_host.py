@@ -356,3 +356,17 @@ def test_leadlag_sparse_tables_bit_exact(d, depth):
     assert [W[i] for i in np.unique(ws.user_index)] == words                   # exactly the generated words
     if (d, depth) == (5, 4):
         assert len(words) == 1685 and len(W) == 1860
+
+
+@pytest.mark.parametrize("d,depth", [(2, 1), (2, 6), (3, 4), (4, 5), (5, 2)])
+def test_logsig_word_set_bit_exact(d, depth):
+    ws = S.sig_wordset_build_logsig(d, depth)
+    W = O.logsig_word_set(d, depth)
+    t = O.word_tables(W)
+    assert ws.size == len(W) and ws.max_len == depth
+    assert np.array_equal(ws.parent, t["parent"]) and np.array_equal(ws.letter, t["letter"])
+    assert np.array_equal(ws.level_start, t["level_start"])
+    lyn = O.lyndon_words(d, depth)
+    assert int(S.load_library().sig_wordset_n_lyndon(ws._h)) == len(lyn)
+    assert [W[i] for i in ws.user_index] == lyn
+    assert int(S.load_library().sig_wordset_n_lyndon(S.sig_wordset_build_truncated(2, 3)._h)) == 0
