@@ -139,7 +139,7 @@ std::mutex g_jit_mutex;
 // chip) over the path groups, a whole number of workgroups, and not so many that units shrink to a handful of words
 // (every unit recomputes the ancestors of its first word).
 constexpr int kJitWaves = 4;           // wavefronts (units) per workgroup
-int64_t jit_units(const sig::WordSet& w, int dir, int64_t B)
+int64_t jit_units(const sig::WordSet& w, int /*dir*/, int64_t B)
 {
     int64_t want = 2048;               // two wavefronts per SIMD
     if (const char* e = std::getenv("SIG_JIT_WAVES")) want = std::max(1, std::atoi(e));   // tuning knob

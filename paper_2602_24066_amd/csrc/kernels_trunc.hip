@@ -576,11 +576,6 @@ __device__ __forceinline__ void chain_tile_reduce(const float* Vsrc, float* gt, 
     }
 }
 
-__device__ __forceinline__ void lds_add(float* p, float v)
-{
-    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-
 // LDS of one wavefront of the backward kernel, in floats.  GEMM: the leaf level (adjoints constant in time) is
 // handled by time-batched matrix products over a tile of 16 segments, which need the slice-level values of the
 // tile in LDS (HA).
@@ -621,7 +616,6 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     constexpr int NL16 = WIDE ? NSV : 1;              // leaf 16-vectors
     constexpr int EPL = (T * D + kWave - 1) / kWave;
     constexpr int NSRC0 = 1 + (WIDE ? WQ : Q);        // sources before the earlier chain letters
-    constexpr int NSRC = NSRC0 + (K - 1);
     constexpr int LB = ilog2(D);
     using LY = BwdLds<D, N, WQ, T>;
     static_assert(!LY::GEMM || T == 16, "the time-batched leaf products take 16 segments per matrix instruction");
