@@ -96,7 +96,7 @@ Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points)
 // paths take its fused form (2 or 4 chunks of a path in one workgroup, everything between the chunks in LDS); larger
 // ones run it unchunked.  SIG_BWD_TAILS=0 switches it off, =1 takes the unfused form with chunk arrays in HBM
 // (SIG_CHUNKS chunks), =2 / =4 force the fused form with that many chunks.
-struct BwdShape { bool tails, fused; int64_t C, Lc; };
+struct BwdShape { bool tails, fused; int64_t C, Lc; bool split = false; };
 BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points)
 {
     const int64_t L = n_points - 1;
@@ -115,7 +115,10 @@ BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points
     }
     const int64_t Lc = (L + C - 1) / C;
     if ((C - 1) * Lc >= L) return s;
-    return BwdShape{true, true, C, Lc};
+    // two wavefronts per chunk with half of the tails each, when the path's gradient fits their LDS buffer
+    const char* sp = std::getenv("SIG_BWD_SPLIT");
+    const bool split = L <= sig::trunc_backward_tails_split_max_segments(w.d, w.depth, C) && !(sp && sp[0] == '0');
+    return BwdShape{true, true, C, Lc, split};
 }
 size_t chunk_array_bytes(const sig::WordSet& w, int64_t B, int64_t C)
 {
@@ -632,7 +635,7 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
         }
         hipEvent_t* pe = g_prof.next(1);
         if (pe) (void)hipEventRecord(pe[0], st);
-        if (ch.fused) e = sig::trunc_backward_tails_fused(w.d, w.depth, path, coeffs, grad_coeffs, B, n_points, ch.C, ch.Lc, gdx, st);
+        if (ch.fused) e = sig::trunc_backward_tails_fused(w.d, w.depth, path, coeffs, grad_coeffs, B, n_points, ch.C, ch.Lc, ch.split, gdx, st);
         else if (ch.tails) e = sig::trunc_backward_tails(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
         else e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
         if (pe) (void)hipEventRecord(pe[1], st);

@@ -1024,29 +1024,48 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
 // of a workgroup is an independent row.  CW = 2 or 4 ("fused"): a workgroup is one path and its CW wavefronts are
 // the CW chunks of it; the chunk signatures, their products and the adjoints at the chunk boundaries are formed inside
 // the kernel and exchanged through LDS, so that nothing but path, terminal signature and gradient is read from HBM.
-template <int D, int N, int T, int CW>
+// TW < D (fused only): a row is shared by D / TW wavefronts that hold TW of the D tails each, which halves the
+// registers of a wavefront so that two of them fit on a SIMD and hide each other's latencies.  Everything below the
+// tails splits cleanly; the chain above them is recomputed by every wavefront of the row, and since the adjoint
+// pushes are linear, each wavefront pushes the part that comes from its own tails (the adjoints the row starts
+// from go to the first of them).  The gradient of the whole path is summed in LDS and stored at the end.
+template <int D, int N, int T, int CW, int TW>
 struct TailsLds {
+    static_assert(D % TW == 0 && (CW > 0 || TW == D), "split rows exist in the fused form only");
     static constexpr int KL = N - 3;
     static constexpr int NC = (N + 3) / 4 * 4;
-    static constexpr int NWV = CW ? CW : kWavesPerBlock;                     // wavefronts per workgroup
-    static constexpr int NSRC = D + 1 + KL;             // tails, slice/leaf letters, per-lane chain letters
+    static constexpr int H = D / TW;                                         // wavefronts per row
+    static constexpr int NWV = CW ? CW * H : kWavesPerBlock;                 // wavefronts per workgroup
+    // sources of gradient values: the tails; letter lane % 4 (slice words, leaves and the last chain letter); the
+    // earlier chain letters
+    static constexpr int NSRC = TW + 1 + (KL - 1);
     static constexpr int W = level_start(D, N) + ipow(D, N);
+    // the chunk signatures and their products are kept up to length N - 1: the backward walk never reads the
+    // coefficients of the longest words, and their adjoints are the gradient itself
+    static constexpr int W1 = level_start(D, N);
     static constexpr int TILE = T * 2 * D + T * D * NC;                      // E, Ec of one wavefront
     static constexpr int RED = T * D + NSRC * T * kWave;                     // gt, Vb of one wavefront
-    // fused: area A holds first the CW + 2 signature buffers, later the reduction regions; the tiles come after it
-    static constexpr int AREA_A = CW ? ((CW + 2) * W > CW * RED ? (CW + 2) * W : CW * RED) : 0;
-    static constexpr int OFF_G = AREA_A + CW * TILE;                          // fused: the gradient row of the path
-    static constexpr int TOTAL = CW ? OFF_G + W : NWV * (TILE + RED);
-    static_assert(TILE % 4 == 0 && RED % 4 == 0 && AREA_A % 4 == 0 && W % 4 == 0, "16-byte alignment");
+    // fused: area A holds first the CW + 2 signature buffers and a copy of the gradient row of the path, later the
+    // reduction regions and, for split rows, the increment gradients of the whole path (four chunks: up to 3,000
+    // segments; two chunks: 1,000, which lets two workgroups share a compute unit)
+    static constexpr int GX_FLOATS = H > 1 ? (CW == 4 ? 3000 : 1000) * D : 0;
+    static constexpr int BUFS = (CW + 2) * W1 + W;
+    static constexpr int AREA_A = CW ? (BUFS > NWV * RED + GX_FLOATS ? BUFS : NWV * RED + GX_FLOATS) : 0;
+    // fused: the tiles come first (their addresses then fit the offset field of the LDS instructions), area A next
+    static constexpr int OFF_A = CW ? NWV * TILE : 0;
+    static constexpr int OFF_G = OFF_A + (CW + 2) * W1;                       // fused: the gradient row of the path
+    static constexpr int OFF_GX = OFF_A + NWV * RED;
+    static constexpr int TOTAL = CW ? OFF_A + AREA_A : NWV * (TILE + RED);
+    static_assert(TILE % 4 == 0 && RED % 4 == 0 && AREA_A % 4 == 0 && W % 4 == 0 && W1 % 4 == 0, "16-byte alignment");
     static constexpr size_t BYTES = (size_t)TOTAL * sizeof(float);
-    __device__ static float* tile(float* base, int wib) { return base + (CW ? AREA_A + wib * TILE : wib * (TILE + RED)); }
-    __device__ static float* red(float* base, int wib) { return base + (CW ? wib * RED : wib * (TILE + RED) + TILE); }
+    __device__ static float* tile(float* base, int wib) { return base + (CW ? wib * TILE : wib * (TILE + RED)); }
+    __device__ static float* red(float* base, int wib) { return base + (CW ? OFF_A + wib * RED : wib * (TILE + RED) + TILE); }
 };
 
 // V[NS][T][64]: source s holds, for every segment, one value per lane, and all 64 lanes contribute to letter s.
-// Lane s T + tt sums the row (s, tt) and adds it to gt[tt][s].
+// Lane s T + tt sums the row (s, tt) and adds it to gt[tt][first_letter + s].
 template <int NS, int T>
-__device__ __forceinline__ void tile_reduce_uniform(const float* V, float* gt, int D, int lane)
+__device__ __forceinline__ void tile_reduce_uniform(const float* V, float* gt, int D, int lane, int first_letter)
 {
     static_assert(NS * T <= kWave, "one lane per (source, segment)");
     if (lane < NS * T) {
@@ -1054,16 +1073,17 @@ __device__ __forceinline__ void tile_reduce_uniform(const float* V, float* gt, i
         v4f acc = row[0];
 #pragma unroll
         for (int i = 1; i < kWave / 4; ++i) acc += row[i];
-        gt[(lane % T) * D + lane / T] += (acc[0] + acc[1]) + (acc[2] + acc[3]);
+        gt[(lane % T) * D + first_letter + lane / T] += (acc[0] + acc[1]) + (acc[2] + acc[3]);
     }
 }
 
-template <int D, int KL, int T, int KI>
+// sources KI .. KE - 1: the chain letters before the last one
+template <int D, int KL, int T, int KI, int KE>
 __device__ __forceinline__ void lane_chain_tile_reduce(const float* Vsrc, float* gt, int lane, const int (&letter)[KL])
 {
-    if constexpr (KI < KL) {
+    if constexpr (KI < KE) {
         tile_reduce<chain_keep_mask(ilog2(D), KL, KI), T>(Vsrc + KI * T * kWave, gt, D, lane, letter[KI]);
-        lane_chain_tile_reduce<D, KL, T, KI + 1>(Vsrc, gt, lane, letter);
+        lane_chain_tile_reduce<D, KL, T, KI + 1, KE>(Vsrc, gt, lane, letter);
     }
 }
 
@@ -1105,25 +1125,32 @@ __device__ __forceinline__ float word_product(const float* a, const float* b, in
 }
 // adjoint of the word u (length n, index i) at a chunk boundary: g(u) + sum_{m >= 1} sum_{|v| = m} g(u v) q(v).
 // `share` lanes (a power of two, consecutive, all holding the same u) split the sums; `sub` is the lane's rank.
+// rot (a multiple of four, the same in the lanes of one u) rotates the order in which a lane walks its v, so that
+// lanes whose words lie a power of two apart do not meet in one LDS bank.
 template <int D, int N>
-__device__ __forceinline__ float word_contract(const float* g, const float* q, int n, int i, int sub, int share)
+__device__ __forceinline__ float word_contract(const float* g, const float* q, int n, int i, int sub, int share, int rot)
 {
+    static_assert(D % 4 == 0, "the words u v of one u are read four at a time");
     constexpr int LB = ilog2(D);
-    float acc = 0.0f;
+    v4f acc4 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int m = 1; m < N; ++m)
         if (m <= N - n) {
             const int cnt = 1 << (LB * m);
             const float* src = g + level_start(D, n + m) + (i << (LB * m));
             const float* qv = q + level_start(D, m);
-            for (int v = sub; v < cnt; v += share) acc = fmaf(src[v], qv[v], acc);
+            for (int v = 4 * sub; v < cnt; v += 4 * share) {
+                const int vr = (v + rot) & (cnt - 1);
+                acc4 += *(const v4f*)(src + vr) * *(const v4f*)(qv + vr);
+            }
         }
+    float acc = (acc4[0] + acc4[1]) + (acc4[2] + acc4[3]);
     for (int off = share >> 1; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
     return g[level_start(D, n) + i] + acc;
 }
 
-template <int D, int N, int T, int CW>
-__global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tails_bwd_kernel(
+template <int D, int N, int T, int CW, int TW>
+__global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void trunc_tails_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
     int64_t P, int64_t C, int64_t Lc, float* __restrict__ gdx)
 {
@@ -1133,12 +1160,16 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
     static_assert(ipow(D, KL) == kWave, "64 words of length N - 3, one per lane");
     constexpr int NC = (N + 3) / 4 * 4;
     constexpr int EPL = (T * D + kWave - 1) / kWave;
-    using LY = TailsLds<D, N, T, CW>;
+    using LY = TailsLds<D, N, T, CW, TW>;
+    constexpr int H = LY::H;
     extern __shared__ v4f bwd_smem[];
 
     const int lane = threadIdx.x % kWave;
     const int wib = threadIdx.x / kWave;
-    const int64_t row = CW ? (int64_t)blockIdx.x * C + wib : (int64_t)blockIdx.x * kWavesPerBlock + wib;
+    const int cib = wib / H;                          // fused: chunk of the workgroup's path
+    const int i0 = (wib % H) * TW;                    // first tail of this wavefront
+    const bool first = wib % H == 0;                  // the wavefront of the row that owns the chain above the tails
+    const int64_t row = CW ? (int64_t)blockIdx.x * C + cib : (int64_t)blockIdx.x * kWavesPerBlock + wib;
     if constexpr (CW == 0) {
         if (row >= B * C) return;                     // no workgroup barriers in this mode
     }
@@ -1164,10 +1195,11 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
 
     // ---- state
     float Sc[KL], Ac[KL];                  // per-lane chain: signature and adjoint (adjoint only in the owning lane)
-    float St[D], At[D];                    // tails
-    v4f S1[D], A1[D];                      // slice level: children of the tails (child layout)
-    v4f S2[D][4], Ac4[D][4];               // leaves (child layout); their adjoints are constant
-    float An[D][4][D];                     // leaf adjoints, node layout (lane = slice word)
+    float St[TW], At[TW];                  // tails i0 .. i0 + TW - 1
+    v4f S1[TW], A1[TW];                    // slice level: children of the tails (child layout)
+    v4f Ac4[TW][4];                        // adjoints of the leaves (child layout), constant; their coefficients
+                                           // are never needed
+    float An[TW][4][D];                    // leaf adjoints, node layout (lane = slice word)
 
     float dxn[EPL];
     auto fetch = [&](int64_t j0) {
@@ -1211,17 +1243,14 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
             Sc[k - 1] = sig(k, phi);
         }
 #pragma unroll
-        for (int i = 0; i < D; ++i) {
-            St[i] = sig(K, lane * D + i);
+        for (int ii = 0; ii < TW; ++ii) {
+            const int i = i0 + ii;
+            St[ii] = sig(K, lane * D + i);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 // slice word of register r in this lane: child (letter lane % 4) of tail i of lane 4 blk + r
                 const int ph = (((lane & ~3) + r) * D + i) * D + (lane & 3);
-                S1[i][r] = sig(N - 1, ph);
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr)
-                    // leaf of register (r, rr): child (letter lane % 4) of the slice word (r, lane 4 blk + rr)
-                    S2[i][r][rr] = sig(N, ((((lane & ~3) + r) * D + i) * D + rr) * D + (lane & 3));
+                S1[ii][r] = sig(N - 1, ph);
             }
         }
     };
@@ -1232,37 +1261,39 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
             phi = phi * D + letter[k - 1];
             const int share = ipow(D, KL - k);                    // lanes holding this word
             const float v = adj(k, phi, lane % share, share);
-            Ac[k - 1] = lane % share == 0 ? v : 0.0f;             // the adjoint lives in the owning lane only
+            Ac[k - 1] = first && lane % share == 0 ? v : 0.0f;    // the adjoint lives in the owning lane only
         }
 #pragma unroll
-        for (int i = 0; i < D; ++i) {
-            At[i] = adj(K, lane * D + i, 0, 1);
+        for (int ii = 0; ii < TW; ++ii) {
+            const int i = i0 + ii;
+            At[ii] = adj(K, lane * D + i, 0, 1);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) A1[i][r] = adj(N - 1, (((lane & ~3) + r) * D + i) * D + (lane & 3), 0, 1);
+            for (int r = 0; r < 4; ++r) A1[ii][r] = adj(N - 1, (((lane & ~3) + r) * D + i) * D + (lane & 3), 0, 1);
         }
     };
     // leaf adjoints are the gradient itself at every chunk boundary
 #pragma unroll
-    for (int i = 0; i < D; ++i)
+    for (int ii = 0; ii < TW; ++ii)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
+            const int i = i0 + ii;
             const int ph = (((lane & ~3) + r) * D + i) * D + (lane & 3);
 #pragma unroll
-            for (int j = 0; j < D; ++j) An[i][r][j] = gr[level_start(D, N) + ph * D + j];
+            for (int j = 0; j < D; ++j) An[ii][r][j] = gr[level_start(D, N) + ph * D + j];
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr)
-                Ac4[i][r][rr] = gr[level_start(D, N) + ((((lane & ~3) + r) * D + i) * D + rr) * D + (lane & 3)];
+                Ac4[ii][r][rr] = gr[level_start(D, N) + ((((lane & ~3) + r) * D + i) * D + rr) * D + (lane & 3)];
         }
 
     if constexpr (CW == 0) {
         load_signature([&](int n, int i) { return cf[level_start(D, n) + i]; });
         load_adjoint([&](int n, int i, int, int) { return gr[level_start(D, n) + i]; });
     } else {
-        constexpr int W = LY::W;
-        float* const SB = smem;                        // SB[c] = signature of chunk c, later partly reused
-        float* const TB = smem + CW * W;               // two more buffers
+        constexpr int W = LY::W1;                      // words of length < N
+        float* const SB = smem + LY::OFF_A;            // SB[c] = signature of chunk c, later partly reused
+        float* const TB = SB + CW * W;                 // two more buffers
         float* const GB = smem + LY::OFF_G;            // the gradient row, read many times by the boundary adjoints
-        for (int o = 4 * (int)threadIdx.x; o < W; o += 4 * CW * kWave) *(v4f*)(GB + o) = *(const v4f*)(gr + o);
+        for (int o = 4 * (int)threadIdx.x; o < LY::W; o += 4 * LY::NWV * kWave) *(v4f*)(GB + o) = *(const v4f*)(gr + o);
         // phase 1: signature of the own chunk, S <- S (x) exp(dX) segment by segment from the identity
         load_signature([&](int, int) { return 0.0f; });
         {
@@ -1273,7 +1304,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
                 stage();
                 wave_lds_fence();
                 fetch((n + 1) * T);                    // beyond the chunk: zeros
-#pragma unroll 1
+#pragma unroll 2
                 for (int tt = 0; tt < T; ++tt) {
                     const float* Et = &E[tt][0][0];
                     const float bs = Et[offB];
@@ -1288,63 +1319,68 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
                         Sc[k - 1] = fmaf(src[0], a[k - 1][1], Sc[k - 1]);
                     }
 #pragma unroll
-                    for (int i = 0; i < D; ++i) {
-                        const float a1 = fmaf(Ec[tt][i][1], a[KL][2], St[i]);
-                        const float a2 = fmaf(Ec[tt][i][2], a[KL][3], St[i]);
-                        St[i] = fmaf(Ec[tt][i][0], a[KL][1], St[i]);
-                        const v4f Gq = mfma4(a2, bs, S1[i], 1);
-                        S1[i] = mfma4(a1, bs, S1[i], 0);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) S2[i][r] = mfma4(Gq[r], bs, S2[i][r], 0);
+                    for (int ii = 0; ii < TW; ++ii) {
+                        const float* et = &Ec[tt][i0 + ii][0];
+                        const float a1 = fmaf(et[1], a[KL][2], St[ii]);
+                        St[ii] = fmaf(et[0], a[KL][1], St[ii]);
+                        S1[ii] = mfma4(a1, bs, S1[ii], 0);
                     }
                 }
             }
         }
         {   // publish it in canonical order
-            float* out = SB + wib * W;
+            float* out = SB + cib * W;
             int phi = 0;
 #pragma unroll
             for (int k = 1; k <= KL; ++k) {
                 phi = phi * D + letter[k - 1];
-                if (lane % ipow(D, KL - k) == 0) out[level_start(D, k) + phi] = Sc[k - 1];
+                if (first && lane % ipow(D, KL - k) == 0) out[level_start(D, k) + phi] = Sc[k - 1];
             }
 #pragma unroll
-            for (int i = 0; i < D; ++i) {
-                out[level_start(D, K) + lane * D + i] = St[i];
+            for (int ii = 0; ii < TW; ++ii) {
+                const int i = i0 + ii;
+                out[level_start(D, K) + lane * D + i] = St[ii];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    out[level_start(D, N - 1) + (((lane & ~3) + r) * D + i) * D + (lane & 3)] = S1[i][r];
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr)
-                        out[level_start(D, N) + ((((lane & ~3) + r) * D + i) * D + rr) * D + (lane & 3)] = S2[i][r][rr];
-                }
+                for (int r = 0; r < 4; ++r)
+                    out[level_start(D, N - 1) + (((lane & ~3) + r) * D + i) * D + (lane & 3)] = S1[ii][r];
             }
         }
         __syncthreads();
         // phase 2: what every chunk starts from.  P_c = S_1 (x) .. (x) S_c, Q_c = S_{c+1} (x) .. (x) S_CW.
         const float* qbuf = nullptr;                   // Q of the own chunk (not for the last one)
         if constexpr (CW == 4) {
-            lds_tensor_product<D, N>(SB, SB + W, TB, threadIdx.x, CW * kWave);                      // P_2
-            lds_tensor_product<D, N>(SB + 2 * W, SB + 3 * W, TB + W, threadIdx.x, CW * kWave);      // Q_2
+            constexpr int NT = LY::NWV * kWave;
+            lds_tensor_product<D, N - 1>(SB, SB + W, TB, threadIdx.x, NT);                              // P_2
+            lds_tensor_product<D, N - 1>(SB + 2 * W, SB + 3 * W, TB + W, threadIdx.x, NT);              // Q_2
             __syncthreads();
-            lds_tensor_product<D, N>(SB + W, TB + W, SB, threadIdx.x, CW * kWave);                  // Q_1 over S_1: chunk 0
+            lds_tensor_product<D, N - 1>(SB + W, TB + W, SB, threadIdx.x, NT);                          // Q_1 over S_1: chunk 0
             __syncthreads();                                                                        // keeps S_1 in registers
-            if (wib == 1) load_signature([&](int n, int i) { return TB[level_start(D, n) + i]; });
-            if (wib == 2) load_signature([&](int n, int i) { return word_product<D, N>(TB, SB + 2 * W, n, i); });
-            qbuf = wib == 0 ? SB : (wib == 1 ? TB + W : SB + 3 * W);
+            if (cib == 1) load_signature([&](int n, int i) { return TB[level_start(D, n) + i]; });
+            if (cib == 2) load_signature([&](int n, int i) { return word_product<D, N - 1>(TB, SB + 2 * W, n, i); });
+            qbuf = cib == 0 ? SB : (cib == 1 ? TB + W : SB + 3 * W);
         } else {
             static_assert(CW == 2, "two or four chunks per workgroup");
             qbuf = SB + W;                                                                          // Q_1 = S_2
         }
-        if (wib == CW - 1) {
+        if (cib == CW - 1) {
             load_signature([&](int n, int i) { return cf[level_start(D, n) + i]; });                // terminal signature
             load_adjoint([&](int n, int i, int, int) { return gr[level_start(D, n) + i]; });
         } else {
-            load_adjoint([&](int n, int i, int sub, int share) { return word_contract<D, N>(GB, qbuf, n, i, sub, share); });
+            load_adjoint([&](int n, int i, int sub, int share) {
+                return word_contract<D, N>(GB, qbuf, n, i, sub, share, 4 * (lane / share));
+            });
         }
         __syncthreads();                               // the buffers are dead: their space takes gt / Vb from here on
+        if constexpr (H > 1) {
+            float* const GX = smem + LY::OFF_GX;
+            for (int o = threadIdx.x; o < (int)(P - 1) * D; o += LY::NWV * kWave) GX[o] = 0.0f;
+            __syncthreads();
+        }
     }
 
+    float unit[4];                                     // unit[r] = 1 in the lanes 4 blk + r
+#pragma unroll
+    for (int r = 0; r < 4; ++r) unit[r] = (lane & 3) == r ? 1.0f : 0.0f;
     auto step = [&](int row_t) {
         const float* Et = &E[row_t][0][0];
         float ec[KL][NC];
@@ -1354,13 +1390,14 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
 #pragma unroll
             for (int t = 0; t <= N - (k + 1); ++t) ec[k][t] = src[t];
         }
-        float e4[D][3];                               // dX^{(i)} / (t + 1), the same in every lane
+        float e0[D], et[TW][3];                       // dX^{(j)}, and dX^{(i)} / (t + 1) of the own tails: lane-uniform
 #pragma unroll
-        for (int i = 0; i < D; ++i)
+        for (int j = 0; j < D; ++j) e0[j] = Ec[row_t][j][0];
 #pragma unroll
-            for (int t = 0; t < 3; ++t) e4[i][t] = Ec[row_t][i][t];
+        for (int ii = 0; ii < TW; ++ii)
+#pragma unroll
+            for (int t = 0; t < 3; ++t) et[ii][t] = Ec[row_t][i0 + ii][t];
         const float bs = Et[offB], nbs = -bs;
-        const float b0v = Et[lane & 3], b1v = 0.5f * b0v;
 
         // 1. reconstruction with -dX, 2. accumulators with +dX (per-lane chain)
         float am[KL + 1][N + 2], ap[KL + 1][N + 2];
@@ -1378,53 +1415,57 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
         float ysum = 0.0f;                            // gradient of letter lane % 4 from slice words and leaves
         float* vb = Vb + row_t * kWave + lane;
 #pragma unroll
-        for (int i = 0; i < D; ++i) {
+        for (int i = 0; i < TW; ++i) {      // tail i0 + i
             // tail i: reconstruction
-            const float am1 = fmaf(-e4[i][1], am[KL][2], St[i]);
-            const float am2 = fmaf(-e4[i][2], am[KL][3], St[i]);
-            St[i] = fmaf(-e4[i][0], am[KL][1], St[i]);
-            const v4f Gm = mfma4(am2, nbs, S1[i], 1);
+            const float am1 = fmaf(-et[i][1], am[KL][2], St[i]);
+            St[i] = fmaf(-et[i][0], am[KL][1], St[i]);
             S1[i] = mfma4(am1, nbs, S1[i], 0);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) S2[i][r] = mfma4(Gm[r], nbs, S2[i][r], 0);
             // accumulators
-            const float ap1 = fmaf(e4[i][1], ap[KL][2], St[i]);
-            const float ap2 = fmaf(e4[i][2], ap[KL][3], St[i]);
+            const float ap1 = fmaf(et[i][1], ap[KL][2], St[i]);
+            const float ap2 = fmaf(et[i][2], ap[KL][3], St[i]);
             const v4f Gp = mfma4(ap2, bs, S1[i], 1);                          // A+[1] of the slice words
             const v4f Pb1 = __builtin_amdgcn_mfma_f32_4x4x1f32(ap1, one, zero4, 0, 0, 0);          // parent values in
             const v4f Pb2 = __builtin_amdgcn_mfma_f32_4x4x1f32(0.5f * ap2, one, zero4, 0, 0, 0);   // the child layout
             // 3a. leaves, 3b. slice words
-            float gc = 0.0f, M1[4], M2[4];
+            // Register r of a lane holds a child of the tail of lane 4 blk + r: what the children push up to their
+            // tails is brought to the tail's lane by four accumulated products with unit columns (register j of
+            // T1 / T2 becomes the value of child j of the own tail), then weighted with dX per child letter.
+            float gc = 0.0f;
+            v4f T1 = zero4, T2 = zero4;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 float h = 0.0f;
 #pragma unroll
-                for (int j = 0; j < D; ++j) h = fmaf(e4[j][0], An[i][r][j], h);    // gbar[1] of the slice word
+                for (int j = 0; j < D; ++j) h = fmaf(e0[j], An[i][r][j], h);    // gbar[1] of the slice word
                 const v4f Pb = __builtin_amdgcn_mfma_f32_4x4x1f32(Gp[r], one, zero4, 0, 0, 0);
 #pragma unroll
                 for (int rr = 0; rr < 4; ++rr) gc = fmaf(Ac4[i][r][rr], Pb[rr], gc);
                 const float q0 = A1[i][r];
                 gc = fmaf(q0, Pb1[r], gc);
                 gc = fmaf(h, Pb2[r], gc);
-                M1[r] = b0v * q0;
-                M2[r] = b1v * h;
+                T1 = __builtin_amdgcn_mfma_f32_4x4x1f32(q0, unit[r], T1, 0, 0, 0);
+                T2 = __builtin_amdgcn_mfma_f32_4x4x1f32(h, unit[r], T2, 0, 0, 0);
                 A1[i][r] = q0 + h;
             }
             ysum += gc;
             // 3c. the tail word itself: gbar[0] = its adjoint, gbar[1], gbar[2] pushed up from its children
             const float g0 = At[i];
-            const float g1 = quad_transpose_reduce(M1, lane);
-            const float g2 = quad_transpose_reduce(M2, lane);
+            float g1 = e0[0] * T1[0], g2 = e0[0] * T2[0];
+#pragma unroll
+            for (int j = 1; j < D; ++j) {
+                g1 = fmaf(e0[j], T1[j], g1);
+                g2 = fmaf(e0[j], T2[j], g2);
+            }
+            g2 *= 0.5f;
             At[i] = g0 + g1 + g2;
             float gct = g0 * ap[KL][1];
             gct = fmaf(g1 * inv1(1), ap[KL][2], gct);
             gct = fmaf(g2 * inv1(2), ap[KL][3], gct);
             vb[i * T * kWave] = gct;                                          // letter i, every lane
-            gbL[1] = fmaf(e4[i][0], g0, gbL[1]);
-            gbL[2] = fmaf(e4[i][1], g1, gbL[2]);
-            gbL[3] = fmaf(e4[i][2], g2, gbL[3]);
+            gbL[1] = fmaf(et[i][0], g0, gbL[1]);
+            gbL[2] = fmaf(et[i][1], g1, gbL[2]);
+            gbL[3] = fmaf(et[i][2], g2, gbL[3]);
         }
-        vb[D * T * kWave] = ysum;                                             // letter lane % 4
         // 3d. per-lane chain
         float gb[KL + 1][N + 2];
 #pragma unroll
@@ -1445,8 +1486,10 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
                 gb[k - 1][t + 1] = fmaf(ec[k - 1][t], q, gb[k - 1][t + 1]);
             }
             Ac[k - 1] = asum;
-            vb[(D + 1 + (k - 1)) * T * kWave] = gc;                            // letter[k - 1]
+            if (k == KL) ysum += gc;                                          // letter[KL - 1] = lane % 4
+            else vb[(TW + 1 + (k - 1)) * T * kWave] = gc;                     // letter[k - 1]
         }
+        vb[TW * T * kWave] = ysum;                                            // letter lane % 4
     };
 
     const int64_t ntiles = (L + T - 1) / T;
@@ -1460,39 +1503,51 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
 #pragma unroll 1
         for (int tt = T - 1; tt >= 0; --tt) step(tt);
         wave_lds_fence();
-        tile_reduce_uniform<D, T>(Vb, gt, D, lane);        // the only writer of gt so far: plain read-modify-write
+        tile_reduce_uniform<TW, T>(Vb, gt, D, lane, i0);   // the only writer of gt so far: plain read-modify-write
         wave_lds_fence();
-        tile_reduce<3, T>(Vb + D * T * kWave, gt, D, lane, lane & 3);
-        lane_chain_tile_reduce<D, KL, T, 0>(Vb + (D + 1) * T * kWave, gt, lane, letter);
+        tile_reduce<3, T>(Vb + TW * T * kWave, gt, D, lane, lane & 3);
+        lane_chain_tile_reduce<D, KL, T, 0, KL - 1>(Vb + (TW + 1) * T * kWave, gt, lane, letter);
         wave_lds_fence();
         for (int e = lane; e < T * D; e += kWave) {
             const int64_t sgm = n * T + e / D;
-            if (sgm < L) gdx[(b * (P - 1) + seg0 + n * T) * D + e] = gt[e];
+            if constexpr (H == 1) {
+                if (sgm < L) gdx[(b * (P - 1) + seg0 + n * T) * D + e] = gt[e];
+            } else {
+                if (sgm < L)
+                    __hip_atomic_fetch_add(smem + LY::OFF_GX + (seg0 + n * T) * D + e, gt[e], __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
             gt[e] = 0.0f;
         }
     }
+    if constexpr (H > 1) {
+        __syncthreads();
+        const float* GX = smem + LY::OFF_GX;
+        for (int o = threadIdx.x; o < (int)(P - 1) * D; o += LY::NWV * kWave) gdx[b * (P - 1) * D + o] = GX[o];
+    }
 }
 
-template <int D, int N, int CW>
+template <int D, int N, int CW, int TW = D>
 hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
                                   int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
 {
     constexpr int T = 8;
-    using LY = TailsLds<D, N, T, CW>;
+    using LY = TailsLds<D, N, T, CW, TW>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
     if (CW && C != CW) return hipErrorInvalidValue;
+    if (LY::H > 1 && (P - 1) * D > LY::GX_FLOATS) return hipErrorInvalidValue;   // the path's gradient has to fit in LDS
     const int64_t blocks = CW ? B : (B * C + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
         static bool attr_set = false;
         if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T, CW>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T, CW, TW>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
             if (e != hipSuccess) return e;
             attr_set = true;
         }
     }
-    trunc_tails_bwd_kernel<D, N, T, CW><<<(unsigned)blocks, kWave * LY::NWV, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C, Lc,
+    trunc_tails_bwd_kernel<D, N, T, CW, TW><<<(unsigned)blocks, kWave * LY::NWV, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C, Lc,
                                                                                                 gdx);
     return hipGetLastError();
 }
@@ -1584,12 +1639,24 @@ hipError_t trunc_backward_tails(int d, int depth, const float* path, const float
 
 // Fused form: the C (2 or 4) chunks of a path are the wavefronts of one workgroup; coeffs / grad_coeffs are the
 // terminal signature and its gradient [B, |W|], nothing else is needed.  Every chunk must hold at least one segment.
+// split: two wavefronts per chunk with two tails each (paths of at most trunc_backward_tails_split_max_segments
+// segments).
+int64_t trunc_backward_tails_split_max_segments(int d, int depth, int64_t C)
+{
+    if (d == 4 && depth == 6 && C == 4) return TailsLds<4, 6, 8, 4, 2>::GX_FLOATS / 4;
+    if (d == 4 && depth == 6 && C == 2) return TailsLds<4, 6, 8, 2, 2>::GX_FLOATS / 4;
+    return 0;
+}
+
 hipError_t trunc_backward_tails_fused(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs,
-                                      int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
+                                      int64_t B, int64_t P, int64_t C, int64_t Lc, bool split, float* gdx, hipStream_t stream)
 {
     if ((C - 1) * Lc >= P - 1) return hipErrorInvalidValue;
-    if (d == 4 && depth == 6 && C == 4) return launch_trunc_tails_bwd<4, 6, 4>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
-    if (d == 4 && depth == 6 && C == 2) return launch_trunc_tails_bwd<4, 6, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (!(d == 4 && depth == 6)) return hipErrorInvalidValue;
+    if (C == 4 && split) return launch_trunc_tails_bwd<4, 6, 4, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (C == 2 && split) return launch_trunc_tails_bwd<4, 6, 2, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (C == 4) return launch_trunc_tails_bwd<4, 6, 4>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (C == 2) return launch_trunc_tails_bwd<4, 6, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
     return hipErrorInvalidValue;
 }
 
