@@ -91,6 +91,33 @@ Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points)
     const int64_t Lc = (L + C - 1) / C;
     return Chunks{(L + Lc - 1) / Lc, Lc};
 }
+// Forward for d = 4 in the layout with 64 words of length 3 per wavefront (two wavefronts per chunk of a path, 2 or 4
+// chunks per path in one workgroup, chunk signatures multiplied in LDS).  Returns the number of chunks, 0 = the
+// kernel with four wavefronts per path instead (with its chunk arrays in HBM for long paths): measured faster only
+// for fewer than 192 paths of more than 512 segments.  Four chunks need a compute unit per path, so larger batches
+// take two.  SIG_FWD_TAILS=0 (or a SIG_CHUNKS setting) switches it off, =2 / =4 force that many chunks.
+int64_t trunc_forward_fused_chunks(const sig::WordSet& w, int64_t B, int64_t n_points, const float* coeffs)
+{
+    if (!sig::trunc_forward_tails_available(w.d, w.depth) || ((uintptr_t)coeffs & 15) != 0) return 0;
+    const int64_t L = n_points - 1;
+    const char* force = std::getenv("SIG_FWD_TAILS");
+    const int f = (force && force[0]) ? std::atoi(force) : -1;
+    if (f == 0) return 0;
+    const char* hbm = std::getenv("SIG_CHUNKS");             // asks for the form with chunk arrays in HBM
+    if (f == -1 && hbm && hbm[0]) return 0;
+    int64_t C;
+    if (f == 2 || f == 4) {
+        C = f;
+    } else {
+        if (B < 192 && L > 512) return 0;
+        C = B <= 256 ? 4 : 2;
+    }
+    while (C > 1 && L < 8 * C) C /= 2;                       // chunks of at least 8 segments
+    if (C < 2) return 0;
+    const int64_t Lc = (L + C - 1) / C;
+    return (C - 1) * Lc >= L ? 0 : C;
+}
+
 // Backward launch shape for a full truncation.  d = 4 has a second kernel with one wavefront per (path, chunk) row
 // that does half the vector work per path; it needs about a thousand rows to fill the chip.  Batches of up to 768
 // paths take its fused form (2 or 4 chunks of a path in one workgroup, everything between the chunks in LDS); larger
@@ -534,6 +561,14 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
     }
     CallTimer whole(0, st);
     if (use_trunc_forward(w, B)) {
+        if (const int64_t C = trunc_forward_fused_chunks(w, B, n_points, coeffs)) {
+            const int64_t Lc = (n_points - 1 + C - 1) / C;
+            hipEvent_t* pe = g_prof.next(0);
+            if (pe) (void)hipEventRecord(pe[0], st);
+            hipError_t e = sig::trunc_forward_tails_fused(w.d, w.depth, path, B, n_points, C, Lc, coeffs, st);
+            if (pe) (void)hipEventRecord(pe[1], st);
+            return e == hipSuccess ? SIG_OK : hip_fail(e);
+        }
         const Chunks ch = trunc_chunks(w, 0, B, n_points);
         float* Sc = coeffs;
         float* Pfx = nullptr;
@@ -821,7 +856,8 @@ const char* sig_kernel_name(const sig_wordset* ws, int backward, int64_t B, int6
     if (!ws || !W(ws)->kernels_supported) return "unsupported";
     const sig::WordSet& w = *W(ws);
     if (B < 1 || n_points < 2) return sig_wordset_kernel_name(ws, backward);
-    if (!backward && use_trunc_forward(w, B)) return "trunc_mfma_fwd_kernel";
+    if (!backward && use_trunc_forward(w, B))
+        return trunc_forward_fused_chunks(w, B, n_points, nullptr) ? "trunc_tails_fwd_kernel" : "trunc_mfma_fwd_kernel";
     if (backward && use_trunc_backward(w, B)) {
         const BwdShape sh = trunc_backward_shape(w, B, n_points);
         return sh.tails ? "trunc_tails_bwd_kernel" : "trunc_mfma_bwd_kernel";

@@ -67,6 +67,11 @@ hipError_t trunc_backward_tails(int d, int depth, const float* path, const float
 // adjoints stay in LDS; coeffs / grad_coeffs are [B, |W|].  split (at most ..._split_max_segments segments per
 // path): two wavefronts per chunk, each with half of the tails.
 int64_t trunc_backward_tails_split_max_segments(int d, int depth, int64_t C);
+// forward with the C = 2 or 4 chunks of a path in one workgroup: chunk signatures multiplied in LDS; coeffs [B, |W|],
+// 16-byte aligned
+bool trunc_forward_tails_available(int d, int depth);
+hipError_t trunc_forward_tails_fused(int d, int depth, const float* path, int64_t B, int64_t P, int64_t C, int64_t Lc,
+                                     float* coeffs, hipStream_t stream);
 hipError_t trunc_backward_tails_fused(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs,
                                       int64_t B, int64_t P, int64_t C, int64_t Lc, bool split, float* gdx, hipStream_t stream);
 

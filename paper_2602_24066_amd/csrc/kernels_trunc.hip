@@ -1527,6 +1527,200 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Forward in the same register layout, for batches too short to fill the chip with one wavefront per path: a
+// workgroup is one path, cut into CW time chunks; a chunk is shared by D / TW wavefronts that hold TW of the D tails
+// (and everything below them) each and all recompute the chain above the tails.  Every wavefront runs the
+// recursion over its chunk from the identity and publishes its part of the chunk signature to LDS; the workgroup
+// then multiplies the chunk signatures (Chen's relation; CW = 4: (S_1 S_2)(S_3 S_4)) and writes the last product
+// to coeffs.  Nothing but the path is read and nothing but the signature is written.  (Two chunks stay the faster
+// form for large batches too: measured against a single chunk per path up to 8,192 paths.)
+template <int D, int N, int T, int CW, int TW>
+struct TailsFwdLds {
+    static constexpr int NC = (N + 3) / 4 * 4;
+    static constexpr int H = D / TW;
+    static constexpr int NWV = CW * H;
+    static constexpr int W = level_start(D, N) + ipow(D, N);
+    static constexpr int TILE = T * 2 * D + T * D * NC;                      // E, Ec of one wavefront
+    static constexpr int NBUF = CW == 2 ? 2 : CW + 2;                        // chunk signatures and first-round products
+    static constexpr int OFF_S = NWV * TILE;
+    static constexpr int TOTAL = OFF_S + NBUF * W;
+    static_assert(CW == 2 || CW == 4, "two or four chunks per workgroup");
+    static_assert(TILE % 4 == 0 && W % 4 == 0, "16-byte alignment");
+    static constexpr size_t BYTES = (size_t)TOTAL * sizeof(float);
+};
+
+template <int D, int N, int T, int CW, int TW>
+__global__ __launch_bounds__(kWave * CW * (D / TW)) void trunc_tails_fwd_kernel(const float* __restrict__ path, int64_t B,
+                                                                               int64_t P, int64_t Lc,
+                                                                               float* __restrict__ coeffs)
+{
+    static_assert(D == 4, "one group of four letters");
+    constexpr int K = N - 2;                          // length of the tail words
+    constexpr int KL = K - 1;                         // letters held per lane
+    static_assert(ipow(D, KL) == kWave, "64 words of length N - 3, one per lane");
+    constexpr int NC = (N + 3) / 4 * 4;
+    constexpr int EPL = (T * D + kWave - 1) / kWave;
+    using LY = TailsFwdLds<D, N, T, CW, TW>;
+    constexpr int H = LY::H;
+    constexpr int W = LY::W;
+    extern __shared__ v4f fwd_smem[];
+
+    const int lane = threadIdx.x % kWave;
+    const int wib = threadIdx.x / kWave;
+    const int cib = wib / H;                          // chunk of the workgroup's path
+    const int i0 = (wib % H) * TW;                    // first tail of this wavefront
+    const bool first = wib % H == 0;
+    const int64_t b = blockIdx.x;
+    float* const smem = (float*)fwd_smem;
+    float (*E)[2][D] = (float (*)[2][D])(smem + wib * LY::TILE);            // wave-private
+    float (*Ec)[D][NC] = (float (*)[D][NC])(smem + wib * LY::TILE + T * 2 * D);
+    float* const SB = smem + LY::OFF_S;
+    const int64_t seg0 = cib * Lc;
+    int letter[KL];
+    {
+        int q = lane;
+#pragma unroll
+        for (int k = KL - 1; k >= 0; --k) { letter[k] = q % D; q /= D; }
+    }
+    const float* X = path + (b * P + seg0) * D;
+    const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
+
+    float Sc[KL];                          // per-lane chain
+    float St[TW];                          // tails i0 .. i0 + TW - 1
+    v4f S1[TW];                            // slice level: children of the tails (child layout)
+    v4f S2[TW][4];                         // leaves (child layout)
+#pragma unroll
+    for (int k = 0; k < KL; ++k) Sc[k] = 0.0f;
+    const v4f zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int ii = 0; ii < TW; ++ii) {
+        St[ii] = 0.0f;
+        S1[ii] = zero4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) S2[ii][r] = zero4;
+    }
+
+    float dxn[EPL];
+    auto fetch = [&](int64_t j0) {
+#pragma unroll
+        for (int q = 0; q < EPL; ++q) {
+            const int e = (lane + q * kWave) < T * D ? lane + q * kWave : T * D - 1;
+            int64_t jj = j0 + e / D;
+            const bool ok = jj < L;
+            jj = jj < L ? jj : L - 1;
+            const int i = e % D;
+            const float x1 = X[(jj + 1) * D + i], x0 = X[jj * D + i];
+            dxn[q] = ok ? x1 - x0 : 0.0f;
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int q = 0; q < EPL; ++q) {
+            const int e = lane + q * kWave;
+            if (e < T * D) {
+#pragma unroll
+                for (int t = 0; t < N; ++t) {
+                    const float v = dxn[q] * inv1(t);
+                    if (t < 2) E[e / D][t][e % D] = v;
+                    Ec[e / D][e % D][t] = v;
+                }
+            }
+        }
+    };
+    // matrix-core B operand: lanes 0..15 carry dX^{(lane % 4)}, lanes 16..31 dX^{(lane % 4)} / 2
+    const int offB = lane < 32 ? (lane / 16) * D + (lane & 3) : 0;
+
+    const int64_t nt = (L + T - 1) / T;
+    fetch(0);
+    for (int64_t n = 0; n < nt; ++n) {
+        wave_lds_fence();
+        stage();
+        wave_lds_fence();
+        fetch((n + 1) * T);                            // beyond the chunk: zeros
+#pragma unroll 2
+        for (int tt = 0; tt < T; ++tt) {
+            const float bs = E[tt][0][offB];
+            float a[KL + 1][N + 2];
+#pragma unroll
+            for (int t = 0; t < N + 2; ++t) a[0][t] = 1.0f;
+#pragma unroll
+            for (int k = 1; k <= KL; ++k) {
+                const float* src = &Ec[tt][letter[k - 1]][0];
+#pragma unroll
+                for (int t = 1; t <= N - k; ++t) a[k][t] = fmaf(src[t], a[k - 1][t + 1], Sc[k - 1]);
+                Sc[k - 1] = fmaf(src[0], a[k - 1][1], Sc[k - 1]);
+            }
+#pragma unroll
+            for (int ii = 0; ii < TW; ++ii) {
+                const float* et = &Ec[tt][i0 + ii][0];
+                const float a1 = fmaf(et[1], a[KL][2], St[ii]);
+                const float a2 = fmaf(et[2], a[KL][3], St[ii]);
+                St[ii] = fmaf(et[0], a[KL][1], St[ii]);
+                const v4f Gq = mfma4(a2, bs, S1[ii], 1);
+                S1[ii] = mfma4(a1, bs, S1[ii], 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) S2[ii][r] = mfma4(Gq[r], bs, S2[ii][r], 0);
+            }
+        }
+    }
+    {   // publish the chunk signature in canonical order
+        float* out = SB + cib * W;
+        int phi = 0;
+#pragma unroll
+        for (int k = 1; k <= KL; ++k) {
+            phi = phi * D + letter[k - 1];
+            if (first && lane % ipow(D, KL - k) == 0) out[level_start(D, k) + phi] = Sc[k - 1];
+        }
+#pragma unroll
+        for (int ii = 0; ii < TW; ++ii) {
+            const int i = i0 + ii;
+            out[level_start(D, K) + lane * D + i] = St[ii];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                // register r: child (letter lane % 4) of tail i of lane 4 blk + r; (r, rr): child (letter lane % 4) of
+                // the slice word (r, lane 4 blk + rr)
+                out[level_start(D, N - 1) + (((lane & ~3) + r) * D + i) * D + (lane & 3)] = S1[ii][r];
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr)
+                    out[level_start(D, N) + ((((lane & ~3) + r) * D + i) * D + rr) * D + (lane & 3)] = S2[ii][r][rr];
+            }
+        }
+    }
+    __syncthreads();
+    constexpr int NT = LY::NWV * kWave;
+    float* const dst = coeffs + b * W;
+    if constexpr (CW == 4) {
+        float* const TB = SB + CW * W;
+        lds_tensor_product<D, N>(SB, SB + W, TB, threadIdx.x, NT);
+        lds_tensor_product<D, N>(SB + 2 * W, SB + 3 * W, TB + W, threadIdx.x, NT);
+        __syncthreads();
+        lds_tensor_product<D, N>(TB, TB + W, dst, threadIdx.x, NT);
+    } else {
+        lds_tensor_product<D, N>(SB, SB + W, dst, threadIdx.x, NT);
+    }
+}
+
+template <int D, int N, int CW, int TW>
+hipError_t launch_trunc_tails_fwd(const float* path, int64_t B, int64_t P, int64_t Lc, float* coeffs, hipStream_t stream)
+{
+    constexpr int T = 8;
+    using LY = TailsFwdLds<D, N, T, CW, TW>;
+    static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
+    if ((CW - 1) * Lc >= P - 1 || B > 0x7fffffff) return hipErrorInvalidValue;   // every chunk holds a segment
+    if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_fwd_kernel<D, N, T, CW, TW>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+    }
+    trunc_tails_fwd_kernel<D, N, T, CW, TW><<<(unsigned)B, kWave * LY::NWV, LY::BYTES, stream>>>(path, B, P, Lc, coeffs);
+    return hipGetLastError();
+}
+
 template <int D, int N, int CW, int TW = D>
 hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
                                   int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
@@ -1657,6 +1851,18 @@ hipError_t trunc_backward_tails_fused(int d, int depth, const float* path, const
     if (C == 2 && split) return launch_trunc_tails_bwd<4, 6, 2, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
     if (C == 4) return launch_trunc_tails_bwd<4, 6, 4>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
     if (C == 2) return launch_trunc_tails_bwd<4, 6, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    return hipErrorInvalidValue;
+}
+
+// Forward with the C = 2 or 4 chunks of a path in one workgroup (d = 4, depth 6); coeffs 16-byte aligned
+bool trunc_forward_tails_available(int d, int depth) { return d == 4 && depth == 6; }
+
+hipError_t trunc_forward_tails_fused(int d, int depth, const float* path, int64_t B, int64_t P, int64_t C, int64_t Lc,
+                                     float* coeffs, hipStream_t stream)
+{
+    if (!(d == 4 && depth == 6)) return hipErrorInvalidValue;
+    if (C == 4) return launch_trunc_tails_fwd<4, 6, 4, 2>(path, B, P, Lc, coeffs, stream);
+    if (C == 2) return launch_trunc_tails_fwd<4, 6, 2, 2>(path, B, P, Lc, coeffs, stream);
     return hipErrorInvalidValue;
 }
 

@@ -103,6 +103,37 @@ def test_backward_chunks_in_one_workgroup(monkeypatch, B, L, chunks, split):
     check_parity(ws, W, "truncated", 6, X, G, what=f"fused tails B={B} L={L} C={chunks} split={split}")
 
 
+# forward with the 2 or 4 chunks of a path in one workgroup (d = 4, depth 6), forced for any batch size; the last
+# two cases take it by themselves (batch sizes in its range)
+@pytest.mark.parametrize("B,L,chunks", [(3, 97, 4), (1, 32, 4), (5, 64, 4), (2, 35, 4), (1, 300, 4), (3, 17, 2),
+                                        (70, 40, 2), (2, 16, 2), (2, 1001, 2), (130, 50, 0), (400, 33, 0)])
+def test_forward_chunks_in_one_workgroup(monkeypatch, B, L, chunks):
+    if chunks:
+        monkeypatch.setenv("SIG_FWD_TAILS", str(chunks))
+    else:
+        monkeypatch.delenv("SIG_FWD_TAILS", raising=False)
+    monkeypatch.delenv("SIG_CHUNKS", raising=False)
+    ws, W = build_both("truncated", 4, depth=6)
+    assert ws.kernel_name(False, B, L + 1) == "trunc_tails_fwd_kernel"
+    X = make_path("time0", 1300 + L, B, L, 4)
+    G = make_grad_coeffs(1350 + L, B, ws.size)
+    check_parity(ws, W, "truncated", 6, X, G, what=f"fused forward B={B} L={L} C={chunks}")
+
+
+def test_forward_fused_and_four_wavefront_kernels_agree(monkeypatch):
+    ws, W = build_both("truncated", 4, depth=6)
+    X = make_path("time0", 21, 200, 255, 4)
+    G = make_grad_coeffs(22, 200, ws.size)
+    monkeypatch.setenv("SIG_FWD_TAILS", "0")
+    assert ws.kernel_name(False, 200, 256) == "trunc_mfma_fwd_kernel"
+    c0, _ = gpu_forward_backward(ws, X, G)
+    monkeypatch.delenv("SIG_FWD_TAILS")
+    c4, _ = gpu_forward_backward(ws, X, G)
+    lengths = np.array([len(w) for w in W])
+    for n, e in O.level_errors(c4, c0.astype(np.float64), lengths).items():
+        assert e <= 1e-5, (n, e)
+
+
 def test_chunked_and_unchunked_agree(monkeypatch):
     ws, W = build_both("truncated", 4, depth=6)
     X = make_path("time0", 11, 4, 128, 4)
