@@ -119,11 +119,12 @@ int64_t trunc_forward_fused_chunks(const sig::WordSet& w, int64_t B, int64_t n_p
 }
 
 // Backward launch shape for a full truncation.  d = 4 has a second kernel with one wavefront per (path, chunk) row
-// that does half the vector work per path; it needs about a thousand rows to fill the chip.  Batches of up to 768
-// paths take its fused form (2 or 4 chunks of a path in one workgroup, everything between the chunks in LDS); larger
-// ones run it unchunked.  SIG_BWD_TAILS=0 switches it off, =1 takes the unfused form with chunk arrays in HBM
-// (SIG_CHUNKS chunks), =2 / =4 force the fused form with that many chunks.
-struct BwdShape { bool tails, fused; int64_t C, Lc; bool split = false; };
+// that does half the vector work per path and fits two wavefronts on a SIMD, so it wants about two thousand rows.
+// Smaller batches take its fused form (2, 4 or 8 chunks of a path in one workgroup, everything between the chunks
+// in LDS), larger ones run it unchunked; the thresholds come from a scan over 64..2,048 paths of 64..1,024 segments.
+// SIG_BWD_TAILS=0 switches it off, =1 takes the unfused form with chunk arrays in HBM (SIG_CHUNKS chunks),
+// =2 / =4 / =8 force the fused form with that many chunks.
+struct BwdShape { bool tails, fused; int64_t C, Lc; };
 BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points)
 {
     const int64_t L = n_points - 1;
@@ -134,18 +135,12 @@ BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points
     const int f = (force && force[0]) ? std::atoi(force) : -1;
     if (f == 0) return s;
     if (f == 1) return BwdShape{true, false, ch.C, ch.Lc};
-    int64_t C = f == 2 || f == 4 ? f : (B <= 384 ? 4 : (B < 768 ? 2 : 1));
+    int64_t C = f == 2 || f == 4 || f == 8 ? f : (B <= 256 ? 8 : (B <= 896 ? 4 : (B <= 1536 ? 2 : 1)));
     while (C > 1 && L < 8 * C) C /= 2;                       // chunks of at least 8 segments
-    if (C == 1) {
-        if (f == -1 && B < 768 && ch.C == 1) return s;       // too few rows for one wavefront per path
-        return BwdShape{true, false, f == -1 ? 1 : ch.C, f == -1 ? L : ch.Lc};
-    }
+    if (C == 1) return BwdShape{true, false, f == -1 ? 1 : ch.C, f == -1 ? L : ch.Lc};
     const int64_t Lc = (L + C - 1) / C;
     if ((C - 1) * Lc >= L) return s;
-    // two wavefronts per chunk with half of the tails each, when the path's gradient fits their LDS buffer
-    const char* sp = std::getenv("SIG_BWD_SPLIT");
-    const bool split = L <= sig::trunc_backward_tails_split_max_segments(w.d, w.depth, C) && !(sp && sp[0] == '0');
-    return BwdShape{true, true, C, Lc, split};
+    return BwdShape{true, true, C, Lc};
 }
 size_t chunk_array_bytes(const sig::WordSet& w, int64_t B, int64_t C)
 {
@@ -670,7 +665,7 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
         }
         hipEvent_t* pe = g_prof.next(1);
         if (pe) (void)hipEventRecord(pe[0], st);
-        if (ch.fused) e = sig::trunc_backward_tails_fused(w.d, w.depth, path, coeffs, grad_coeffs, B, n_points, ch.C, ch.Lc, ch.split, gdx, st);
+        if (ch.fused) e = sig::trunc_backward_tails_fused(w.d, w.depth, path, coeffs, grad_coeffs, B, n_points, ch.C, ch.Lc, gdx, st);
         else if (ch.tails) e = sig::trunc_backward_tails(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
         else e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
         if (pe) (void)hipEventRecord(pe[1], st);

@@ -63,10 +63,10 @@ hipError_t trunc_backward(int d, int depth, const float* path, const float* coef
 bool trunc_backward_tails_available(int d, int depth);
 hipError_t trunc_backward_tails(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
                                 int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream);
-// the same with the C = 2 or 4 chunks of a path in one workgroup: chunk signatures, their products and the boundary
-// adjoints stay in LDS; coeffs / grad_coeffs are [B, |W|].  split (at most ..._split_max_segments segments per
-// path): two wavefronts per chunk, each with half of the tails.
-int64_t trunc_backward_tails_split_max_segments(int d, int depth, int64_t C);
+// the same with the C = 2, 4 or 8 chunks of a path in one workgroup: chunk signatures, their products and the
+// boundary adjoints stay in LDS; coeffs / grad_coeffs are [B, |W|]
+hipError_t trunc_backward_tails_fused(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs,
+                                      int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream);
 // forward with the C = 2 or 4 chunks of a path in one workgroup: chunk signatures multiplied in LDS; coeffs [B, |W|],
 // 16-byte aligned
 bool trunc_forward_tails_available(int d, int depth);

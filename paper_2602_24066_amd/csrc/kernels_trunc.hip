@@ -1024,37 +1024,28 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
 // of a workgroup is an independent row.  CW = 2 or 4 ("fused"): a workgroup is one path and its CW wavefronts are
 // the CW chunks of it; the chunk signatures, their products and the adjoints at the chunk boundaries are formed inside
 // the kernel and exchanged through LDS, so that nothing but path, terminal signature and gradient is read from HBM.
-// TW < D (fused only): a row is shared by D / TW wavefronts that hold TW of the D tails each, which halves the
-// registers of a wavefront so that two of them fit on a SIMD and hide each other's latencies.  Everything below the
-// tails splits cleanly; the chain above them is recomputed by every wavefront of the row, and since the adjoint
-// pushes are linear, each wavefront pushes the part that comes from its own tails (the adjoints the row starts
-// from go to the first of them).  The gradient of the whole path is summed in LDS and stored at the end.
-template <int D, int N, int T, int CW, int TW>
+template <int D, int N, int T, int CW>
 struct TailsLds {
-    static_assert(D % TW == 0 && (CW > 0 || TW == D), "split rows exist in the fused form only");
     static constexpr int KL = N - 3;
     static constexpr int NC = (N + 3) / 4 * 4;
-    static constexpr int H = D / TW;                                         // wavefronts per row
-    static constexpr int NWV = CW ? CW * H : kWavesPerBlock;                 // wavefronts per workgroup
-    // sources of gradient values: the tails; letter lane % 4 (slice words, leaves and the last chain letter); the
-    // earlier chain letters
-    static constexpr int NSRC = TW + 1 + (KL - 1);
+    static constexpr int NWV = CW ? CW : kWavesPerBlock;                     // wavefronts per workgroup
+    // sources of gradient values: one per letter for tails, slice words and leaves (the same letter in every lane),
+    // one per chain letter
+    static constexpr int NSRC = D + KL;
     static constexpr int W = level_start(D, N) + ipow(D, N);
     // the chunk signatures and their products are kept up to length N - 1: the backward walk never reads the
     // coefficients of the longest words, and their adjoints are the gradient itself
     static constexpr int W1 = level_start(D, N);
     static constexpr int TILE = T * 2 * D + T * D * NC;                      // E, Ec of one wavefront
     static constexpr int RED = T * D + NSRC * T * kWave;                     // gt, Vb of one wavefront
-    // fused: area A holds first the CW + 2 signature buffers and a copy of the gradient row of the path, later the
-    // reduction regions and, for split rows, the increment gradients of the whole path (four chunks: up to 3,000
-    // segments; two chunks: 1,000, which lets two workgroups share a compute unit)
-    static constexpr int GX_FLOATS = H > 1 ? (CW == 4 ? 3000 : 1000) * D : 0;
-    static constexpr int BUFS = (CW + 2) * W1 + W;
-    static constexpr int AREA_A = CW ? (BUFS > NWV * RED + GX_FLOATS ? BUFS : NWV * RED + GX_FLOATS) : 0;
+    // fused: area A holds first the signature buffers and a copy of the gradient row of the path, later the
+    // reduction regions
+    static constexpr int NBUF = CW > 2 ? 3 * CW - 4 : CW;                   // chunk signatures and running products
+    static constexpr int BUFS = NBUF * W1 + W;
+    static constexpr int AREA_A = CW ? (BUFS > NWV * RED ? BUFS : NWV * RED) : 0;
     // fused: the tiles come first (their addresses then fit the offset field of the LDS instructions), area A next
     static constexpr int OFF_A = CW ? NWV * TILE : 0;
-    static constexpr int OFF_G = OFF_A + (CW + 2) * W1;                       // fused: the gradient row of the path
-    static constexpr int OFF_GX = OFF_A + NWV * RED;
+    static constexpr int OFF_G = OFF_A + NBUF * W1;                           // fused: the gradient row of the path
     static constexpr int TOTAL = CW ? OFF_A + AREA_A : NWV * (TILE + RED);
     static_assert(TILE % 4 == 0 && RED % 4 == 0 && AREA_A % 4 == 0 && W % 4 == 0 && W1 % 4 == 0, "16-byte alignment");
     static constexpr size_t BYTES = (size_t)TOTAL * sizeof(float);
@@ -1149,8 +1140,8 @@ __device__ __forceinline__ float word_contract(const float* g, const float* q, i
     return g[level_start(D, n) + i] + acc;
 }
 
-template <int D, int N, int T, int CW, int TW>
-__global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void trunc_tails_bwd_kernel(
+template <int D, int N, int T, int CW>
+__global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tails_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
     int64_t P, int64_t C, int64_t Lc, float* __restrict__ gdx)
 {
@@ -1160,15 +1151,13 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
     static_assert(ipow(D, KL) == kWave, "64 words of length N - 3, one per lane");
     constexpr int NC = (N + 3) / 4 * 4;
     constexpr int EPL = (T * D + kWave - 1) / kWave;
-    using LY = TailsLds<D, N, T, CW, TW>;
-    constexpr int H = LY::H;
+    using LY = TailsLds<D, N, T, CW>;
+    constexpr int TW = D;                             // tails per lane
     extern __shared__ v4f bwd_smem[];
 
     const int lane = threadIdx.x % kWave;
     const int wib = threadIdx.x / kWave;
-    const int cib = wib / H;                          // fused: chunk of the workgroup's path
-    const int i0 = (wib % H) * TW;                    // first tail of this wavefront
-    const bool first = wib % H == 0;                  // the wavefront of the row that owns the chain above the tails
+    const int cib = wib;                              // fused: chunk of the workgroup's path
     const int64_t row = CW ? (int64_t)blockIdx.x * C + cib : (int64_t)blockIdx.x * kWavesPerBlock + wib;
     if constexpr (CW == 0) {
         if (row >= B * C) return;                     // no workgroup barriers in this mode
@@ -1195,11 +1184,10 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
 
     // ---- state
     float Sc[KL], Ac[KL];                  // per-lane chain: signature and adjoint (adjoint only in the owning lane)
-    float St[TW], At[TW];                  // tails i0 .. i0 + TW - 1
+    float St[TW], At[TW];                  // tails
     v4f S1[TW], A1[TW];                    // slice level: children of the tails (child layout)
-    v4f Ac4[TW][4];                        // adjoints of the leaves (child layout), constant; their coefficients
-                                           // are never needed
-    float An[TW][4][D];                    // leaf adjoints, node layout (lane = slice word)
+    float An[TW][4][D];                    // leaf adjoints, node layout (lane = slice word), constant: the gradient;
+                                           // the coefficients of the leaves are never needed
 
     float dxn[EPL];
     auto fetch = [&](int64_t j0) {
@@ -1229,7 +1217,6 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
         }
     };
     const v4f zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-    const float one = 1.0f;
     // matrix-core B operand: lanes 0..15 carry dX^{(lane % 4)}, lanes 16..31 dX^{(lane % 4)} / 2
     const int offB = lane < 32 ? (lane / 16) * D + (lane & 3) : 0;
 
@@ -1244,7 +1231,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
         }
 #pragma unroll
         for (int ii = 0; ii < TW; ++ii) {
-            const int i = i0 + ii;
+            const int i = ii;
             St[ii] = sig(K, lane * D + i);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -1261,11 +1248,11 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
             phi = phi * D + letter[k - 1];
             const int share = ipow(D, KL - k);                    // lanes holding this word
             const float v = adj(k, phi, lane % share, share);
-            Ac[k - 1] = first && lane % share == 0 ? v : 0.0f;    // the adjoint lives in the owning lane only
+            Ac[k - 1] = lane % share == 0 ? v : 0.0f;             // the adjoint lives in the owning lane only
         }
 #pragma unroll
         for (int ii = 0; ii < TW; ++ii) {
-            const int i = i0 + ii;
+            const int i = ii;
             At[ii] = adj(K, lane * D + i, 0, 1);
 #pragma unroll
             for (int r = 0; r < 4; ++r) A1[ii][r] = adj(N - 1, (((lane & ~3) + r) * D + i) * D + (lane & 3), 0, 1);
@@ -1276,13 +1263,10 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
     for (int ii = 0; ii < TW; ++ii)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int i = i0 + ii;
+            const int i = ii;
             const int ph = (((lane & ~3) + r) * D + i) * D + (lane & 3);
 #pragma unroll
             for (int j = 0; j < D; ++j) An[ii][r][j] = gr[level_start(D, N) + ph * D + j];
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr)
-                Ac4[ii][r][rr] = gr[level_start(D, N) + ((((lane & ~3) + r) * D + i) * D + rr) * D + (lane & 3)];
         }
 
     if constexpr (CW == 0) {
@@ -1290,8 +1274,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
         load_adjoint([&](int n, int i, int, int) { return gr[level_start(D, n) + i]; });
     } else {
         constexpr int W = LY::W1;                      // words of length < N
-        float* const SB = smem + LY::OFF_A;            // SB[c] = signature of chunk c, later partly reused
-        float* const TB = SB + CW * W;                 // two more buffers
+        float* const SB = smem + LY::OFF_A;            // SB[c] = signature of chunk c
         float* const GB = smem + LY::OFF_G;            // the gradient row, read many times by the boundary adjoints
         for (int o = 4 * (int)threadIdx.x; o < LY::W; o += 4 * LY::NWV * kWave) *(v4f*)(GB + o) = *(const v4f*)(gr + o);
         // phase 1: signature of the own chunk, S <- S (x) exp(dX) segment by segment from the identity
@@ -1320,7 +1303,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
                     }
 #pragma unroll
                     for (int ii = 0; ii < TW; ++ii) {
-                        const float* et = &Ec[tt][i0 + ii][0];
+                        const float* et = &Ec[tt][ii][0];
                         const float a1 = fmaf(et[1], a[KL][2], St[ii]);
                         St[ii] = fmaf(et[0], a[KL][1], St[ii]);
                         S1[ii] = mfma4(a1, bs, S1[ii], 0);
@@ -1334,11 +1317,11 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
 #pragma unroll
             for (int k = 1; k <= KL; ++k) {
                 phi = phi * D + letter[k - 1];
-                if (first && lane % ipow(D, KL - k) == 0) out[level_start(D, k) + phi] = Sc[k - 1];
+                if (lane % ipow(D, KL - k) == 0) out[level_start(D, k) + phi] = Sc[k - 1];
             }
 #pragma unroll
             for (int ii = 0; ii < TW; ++ii) {
-                const int i = i0 + ii;
+                const int i = ii;
                 out[level_start(D, K) + lane * D + i] = St[ii];
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
@@ -1346,22 +1329,31 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
             }
         }
         __syncthreads();
-        // phase 2: what every chunk starts from.  P_c = S_1 (x) .. (x) S_c, Q_c = S_{c+1} (x) .. (x) S_CW.
-        const float* qbuf = nullptr;                   // Q of the own chunk (not for the last one)
-        if constexpr (CW == 4) {
-            constexpr int NT = LY::NWV * kWave;
-            lds_tensor_product<D, N - 1>(SB, SB + W, TB, threadIdx.x, NT);                              // P_2
-            lds_tensor_product<D, N - 1>(SB + 2 * W, SB + 3 * W, TB + W, threadIdx.x, NT);              // Q_2
-            __syncthreads();
-            lds_tensor_product<D, N - 1>(SB + W, TB + W, SB, threadIdx.x, NT);                          // Q_1 over S_1: chunk 0
-            __syncthreads();                                                                        // keeps S_1 in registers
-            if (cib == 1) load_signature([&](int n, int i) { return TB[level_start(D, n) + i]; });
-            if (cib == 2) load_signature([&](int n, int i) { return word_product<D, N - 1>(TB, SB + 2 * W, n, i); });
-            qbuf = cib == 0 ? SB : (cib == 1 ? TB + W : SB + 3 * W);
-        } else {
-            static_assert(CW == 2, "two or four chunks per workgroup");
-            qbuf = SB + W;                                                                          // Q_1 = S_2
+        // phase 2: what every chunk starts from.  With the chunks numbered from 0: E_k = S_0 (x) .. (x) S_k, the
+        // signature at the end of chunk k, and Q_k = S_{k+1} (x) .. (x) S_{CW-1}, what follows it.  Both are running
+        // products, CW - 2 rounds of two products each (one per half of the workgroup); E_0 = S_0 is in the
+        // registers of chunk 0, E_{CW-1} is the terminal signature, Q_{CW-2} = S_{CW-1}.
+        float* const EB = SB + CW * W;                 // EB[k - 1] = E_k, k = 1 .. CW - 2
+        float* const QB = EB + (CW - 2) * W;           // QB[k] = Q_k, k = 0 .. CW - 3
+        if constexpr (CW > 2) {
+            constexpr int NT = LY::NWV * kWave / 2;
+            const bool upper = (int)threadIdx.x >= NT;
+            const int tid = (int)threadIdx.x - (upper ? NT : 0);
+#pragma unroll 1
+            for (int j = 1; j <= CW - 2; ++j) {
+                if (!upper)
+                    lds_tensor_product<D, N - 1>(j == 1 ? SB : EB + (j - 2) * W, SB + j * W, EB + (j - 1) * W, tid, NT);
+                else
+                    lds_tensor_product<D, N - 1>(SB + (CW - 1 - j) * W, j == 1 ? SB + (CW - 1) * W : QB + (CW - 1 - j) * W,
+                                                 QB + (CW - 2 - j) * W, tid, NT);
+                __syncthreads();
+            }
+            if (cib >= 1 && cib <= CW - 2) {
+                const float* e = EB + (cib - 1) * W;
+                load_signature([&](int n, int i) { return e[level_start(D, n) + i]; });
+            }
         }
+        const float* qbuf = cib == CW - 2 ? SB + (CW - 1) * W : QB + cib * W;   // Q of the own chunk (not for the last)
         if (cib == CW - 1) {
             load_signature([&](int n, int i) { return cf[level_start(D, n) + i]; });                // terminal signature
             load_adjoint([&](int n, int i, int, int) { return gr[level_start(D, n) + i]; });
@@ -1371,11 +1363,6 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
             });
         }
         __syncthreads();                               // the buffers are dead: their space takes gt / Vb from here on
-        if constexpr (H > 1) {
-            float* const GX = smem + LY::OFF_GX;
-            for (int o = threadIdx.x; o < (int)(P - 1) * D; o += LY::NWV * kWave) GX[o] = 0.0f;
-            __syncthreads();
-        }
     }
 
     float unit[4];                                     // unit[r] = 1 in the lanes 4 blk + r
@@ -1396,7 +1383,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
 #pragma unroll
         for (int ii = 0; ii < TW; ++ii)
 #pragma unroll
-            for (int t = 0; t < 3; ++t) et[ii][t] = Ec[row_t][i0 + ii][t];
+            for (int t = 0; t < 3; ++t) et[ii][t] = Ec[row_t][ii][t];
         const float bs = Et[offB], nbs = -bs;
 
         // 1. reconstruction with -dX, 2. accumulators with +dX (per-lane chain)
@@ -1412,10 +1399,12 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
             for (int t = 1; t <= N - k; ++t) ap[k][t] = fmaf(ec[k - 1][t], ap[k - 1][t + 1], Sc[k - 1]);
         }
         float gbL[4] = {0.0f, 0.0f, 0.0f, 0.0f};      // gbar of the lane's word from its tails, t = 1..3
-        float ysum = 0.0f;                            // gradient of letter lane % 4 from slice words and leaves
+        float y[D];                                   // gradient of letter j from tails, slice words and leaves
+#pragma unroll
+        for (int j = 0; j < D; ++j) y[j] = 0.0f;
         float* vb = Vb + row_t * kWave + lane;
 #pragma unroll
-        for (int i = 0; i < TW; ++i) {      // tail i0 + i
+        for (int i = 0; i < TW; ++i) {
             // tail i: reconstruction
             const float am1 = fmaf(-et[i][1], am[KL][2], St[i]);
             St[i] = fmaf(-et[i][0], am[KL][1], St[i]);
@@ -1424,44 +1413,44 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
             const float ap1 = fmaf(et[i][1], ap[KL][2], St[i]);
             const float ap2 = fmaf(et[i][2], ap[KL][3], St[i]);
             const v4f Gp = mfma4(ap2, bs, S1[i], 1);                          // A+[1] of the slice words
-            const v4f Pb1 = __builtin_amdgcn_mfma_f32_4x4x1f32(ap1, one, zero4, 0, 0, 0);          // parent values in
-            const v4f Pb2 = __builtin_amdgcn_mfma_f32_4x4x1f32(0.5f * ap2, one, zero4, 0, 0, 0);   // the child layout
-            // 3a. leaves, 3b. slice words
-            // Register r of a lane holds a child of the tail of lane 4 blk + r: what the children push up to their
-            // tails is brought to the tail's lane by four accumulated products with unit columns (register j of
-            // T1 / T2 becomes the value of child j of the own tail), then weighted with dX per child letter.
-            float gc = 0.0f;
+            // 3a. leaves: the leaf (slice word) j has the gradient as its adjoint; its letter is j in every lane.
+            // 3b. slice words.  Register r of a lane holds a child of the tail of lane 4 blk + r: their adjoints and
+            // what they push up are brought to the tail's lane by four accumulated products with unit columns
+            // (register j of T1 / T2 becomes the value of child j of the own tail), where the tail's accumulators
+            // and dX per child letter are at hand.
             v4f T1 = zero4, T2 = zero4;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 float h = 0.0f;
 #pragma unroll
-                for (int j = 0; j < D; ++j) h = fmaf(e0[j], An[i][r][j], h);    // gbar[1] of the slice word
-                const v4f Pb = __builtin_amdgcn_mfma_f32_4x4x1f32(Gp[r], one, zero4, 0, 0, 0);
-#pragma unroll
-                for (int rr = 0; rr < 4; ++rr) gc = fmaf(Ac4[i][r][rr], Pb[rr], gc);
+                for (int j = 0; j < D; ++j) {
+                    h = fmaf(e0[j], An[i][r][j], h);                           // gbar[1] of the slice word
+                    y[j] = fmaf(An[i][r][j], Gp[r], y[j]);
+                }
                 const float q0 = A1[i][r];
-                gc = fmaf(q0, Pb1[r], gc);
-                gc = fmaf(h, Pb2[r], gc);
                 T1 = __builtin_amdgcn_mfma_f32_4x4x1f32(q0, unit[r], T1, 0, 0, 0);
                 T2 = __builtin_amdgcn_mfma_f32_4x4x1f32(h, unit[r], T2, 0, 0, 0);
                 A1[i][r] = q0 + h;
             }
-            ysum += gc;
             // 3c. the tail word itself: gbar[0] = its adjoint, gbar[1], gbar[2] pushed up from its children
             const float g0 = At[i];
+            const float hp2 = 0.5f * ap2;
             float g1 = e0[0] * T1[0], g2 = e0[0] * T2[0];
+            y[0] = fmaf(T1[0], ap1, y[0]);
+            y[0] = fmaf(T2[0], hp2, y[0]);
 #pragma unroll
             for (int j = 1; j < D; ++j) {
                 g1 = fmaf(e0[j], T1[j], g1);
                 g2 = fmaf(e0[j], T2[j], g2);
+                y[j] = fmaf(T1[j], ap1, y[j]);
+                y[j] = fmaf(T2[j], hp2, y[j]);
             }
             g2 *= 0.5f;
             At[i] = g0 + g1 + g2;
             float gct = g0 * ap[KL][1];
             gct = fmaf(g1 * inv1(1), ap[KL][2], gct);
             gct = fmaf(g2 * inv1(2), ap[KL][3], gct);
-            vb[i * T * kWave] = gct;                                          // letter i, every lane
+            y[i] += gct;
             gbL[1] = fmaf(et[i][0], g0, gbL[1]);
             gbL[2] = fmaf(et[i][1], g1, gbL[2]);
             gbL[3] = fmaf(et[i][2], g2, gbL[3]);
@@ -1486,10 +1475,10 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
                 gb[k - 1][t + 1] = fmaf(ec[k - 1][t], q, gb[k - 1][t + 1]);
             }
             Ac[k - 1] = asum;
-            if (k == KL) ysum += gc;                                          // letter[KL - 1] = lane % 4
-            else vb[(TW + 1 + (k - 1)) * T * kWave] = gc;                     // letter[k - 1]
+            vb[(D + (k - 1)) * T * kWave] = gc;                               // letter[k - 1]
         }
-        vb[TW * T * kWave] = ysum;                                            // letter lane % 4
+#pragma unroll
+        for (int j = 0; j < D; ++j) vb[j * T * kWave] = y[j];                 // letter j, every lane
     };
 
     const int64_t ntiles = (L + T - 1) / T;
@@ -1503,27 +1492,15 @@ __global__ __launch_bounds__(kWave * (CW ? CW * (D / TW) : kWavesPerBlock)) void
 #pragma unroll 1
         for (int tt = T - 1; tt >= 0; --tt) step(tt);
         wave_lds_fence();
-        tile_reduce_uniform<TW, T>(Vb, gt, D, lane, i0);   // the only writer of gt so far: plain read-modify-write
+        tile_reduce_uniform<D, T>(Vb, gt, D, lane, 0);     // the only writer of gt so far: plain read-modify-write
         wave_lds_fence();
-        tile_reduce<3, T>(Vb + TW * T * kWave, gt, D, lane, lane & 3);
-        lane_chain_tile_reduce<D, KL, T, 0, KL - 1>(Vb + (TW + 1) * T * kWave, gt, lane, letter);
+        lane_chain_tile_reduce<D, KL, T, 0, KL>(Vb + D * T * kWave, gt, lane, letter);
         wave_lds_fence();
         for (int e = lane; e < T * D; e += kWave) {
             const int64_t sgm = n * T + e / D;
-            if constexpr (H == 1) {
-                if (sgm < L) gdx[(b * (P - 1) + seg0 + n * T) * D + e] = gt[e];
-            } else {
-                if (sgm < L)
-                    __hip_atomic_fetch_add(smem + LY::OFF_GX + (seg0 + n * T) * D + e, gt[e], __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
+            if (sgm < L) gdx[(b * (P - 1) + seg0 + n * T) * D + e] = gt[e];
             gt[e] = 0.0f;
         }
-    }
-    if constexpr (H > 1) {
-        __syncthreads();
-        const float* GX = smem + LY::OFF_GX;
-        for (int o = threadIdx.x; o < (int)(P - 1) * D; o += LY::NWV * kWave) gdx[b * (P - 1) * D + o] = GX[o];
     }
 }
 
@@ -1721,27 +1698,26 @@ hipError_t launch_trunc_tails_fwd(const float* path, int64_t B, int64_t P, int64
     return hipGetLastError();
 }
 
-template <int D, int N, int CW, int TW = D>
+template <int D, int N, int CW>
 hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
                                   int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
 {
     constexpr int T = 8;
-    using LY = TailsLds<D, N, T, CW, TW>;
+    using LY = TailsLds<D, N, T, CW>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
     if (CW && C != CW) return hipErrorInvalidValue;
-    if (LY::H > 1 && (P - 1) * D > LY::GX_FLOATS) return hipErrorInvalidValue;   // the path's gradient has to fit in LDS
     const int64_t blocks = CW ? B : (B * C + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
         static bool attr_set = false;
         if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T, CW, TW>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T, CW>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
             if (e != hipSuccess) return e;
             attr_set = true;
         }
     }
-    trunc_tails_bwd_kernel<D, N, T, CW, TW><<<(unsigned)blocks, kWave * LY::NWV, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C, Lc,
+    trunc_tails_bwd_kernel<D, N, T, CW><<<(unsigned)blocks, kWave * LY::NWV, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C, Lc,
                                                                                                 gdx);
     return hipGetLastError();
 }
@@ -1831,24 +1807,14 @@ hipError_t trunc_backward_tails(int d, int depth, const float* path, const float
     return hipErrorInvalidValue;
 }
 
-// Fused form: the C (2 or 4) chunks of a path are the wavefronts of one workgroup; coeffs / grad_coeffs are the
+// Fused form: the C (2, 4 or 8) chunks of a path are the wavefronts of one workgroup; coeffs / grad_coeffs are the
 // terminal signature and its gradient [B, |W|], nothing else is needed.  Every chunk must hold at least one segment.
-// split: two wavefronts per chunk with two tails each (paths of at most trunc_backward_tails_split_max_segments
-// segments).
-int64_t trunc_backward_tails_split_max_segments(int d, int depth, int64_t C)
-{
-    if (d == 4 && depth == 6 && C == 4) return TailsLds<4, 6, 8, 4, 2>::GX_FLOATS / 4;
-    if (d == 4 && depth == 6 && C == 2) return TailsLds<4, 6, 8, 2, 2>::GX_FLOATS / 4;
-    return 0;
-}
-
 hipError_t trunc_backward_tails_fused(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs,
-                                      int64_t B, int64_t P, int64_t C, int64_t Lc, bool split, float* gdx, hipStream_t stream)
+                                      int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
 {
     if ((C - 1) * Lc >= P - 1) return hipErrorInvalidValue;
     if (!(d == 4 && depth == 6)) return hipErrorInvalidValue;
-    if (C == 4 && split) return launch_trunc_tails_bwd<4, 6, 4, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
-    if (C == 2 && split) return launch_trunc_tails_bwd<4, 6, 2, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (C == 8) return launch_trunc_tails_bwd<4, 6, 8>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
     if (C == 4) return launch_trunc_tails_bwd<4, 6, 4>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
     if (C == 2) return launch_trunc_tails_bwd<4, 6, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
     return hipErrorInvalidValue;

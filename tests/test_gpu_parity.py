@@ -81,18 +81,17 @@ def test_backward_one_wavefront_per_row(monkeypatch, B, L, chunks):
     check_parity(ws, W, "truncated", 6, X, G, what=f"tails B={B} L={L} C={chunks}")
 
 
-# ... and its fused form: the 2 or 4 chunks of a path in one workgroup, chunk signatures and boundary adjoints in LDS.
-# split: two wavefronts per chunk that hold half of the tails each (paths of up to 3,000 segments with four chunks,
-# 1,000 with two; a longer path takes one wavefront per chunk)
-@pytest.mark.parametrize("B,L,chunks,split", [(3, 97, 4, 1), (1, 33, 4, 1), (5, 64, 4, 1), (2, 35, 4, 1), (1, 300, 4, 1),
-                                              (2, 3000, 4, 1), (1, 3001, 4, 1), (300, 255, 4, 1),
-                                              (3, 97, 4, 0), (1, 33, 4, 0), (5, 64, 4, 0), (2, 35, 4, 0), (1, 300, 4, 0),
-                                              (3, 17, 2, 0), (70, 40, 2, 0), (2, 16, 2, 0),
-                                              (3, 17, 2, 1), (70, 40, 2, 1), (2, 16, 2, 1), (2, 1000, 2, 1), (1, 1001, 2, 1),
-                                              (520, 100, 2, 1)])
-def test_backward_chunks_in_one_workgroup(monkeypatch, B, L, chunks, split):
-    monkeypatch.setenv("SIG_BWD_TAILS", str(chunks))
-    monkeypatch.setenv("SIG_BWD_SPLIT", str(split))
+# ... and its fused form: the 2, 4 or 8 chunks of a path in one workgroup, chunk signatures and boundary adjoints in
+# LDS; the last three cases take it by themselves (8, 4 and 2 chunks)
+@pytest.mark.parametrize("B,L,chunks", [(3, 97, 4), (1, 33, 4), (5, 64, 4), (2, 35, 4), (1, 300, 4), (2, 2000, 4),
+                                        (3, 17, 2), (70, 40, 2), (2, 16, 2), (2, 801, 2),
+                                        (3, 97, 8), (1, 64, 8), (2, 67, 8), (5, 255, 8), (1, 1500, 8),
+                                        (200, 100, 0), (300, 64, 0), (1000, 24, 0)])
+def test_backward_chunks_in_one_workgroup(monkeypatch, B, L, chunks):
+    if chunks:
+        monkeypatch.setenv("SIG_BWD_TAILS", str(chunks))
+    else:
+        monkeypatch.delenv("SIG_BWD_TAILS", raising=False)
     monkeypatch.delenv("SIG_CHUNKS", raising=False)
     ws, W = build_both("truncated", 4, depth=6)
     X = make_path("time0", 900 + L, B, L, 4)
@@ -100,7 +99,7 @@ def test_backward_chunks_in_one_workgroup(monkeypatch, B, L, chunks, split):
     lib = S.load_library()
     gdx = (4 * B * L * 4 + 255) // 256 * 256
     assert lib.sig_backward_workspace_bytes(ws._h, B, L + 1) == gdx       # no chunk arrays in device memory
-    check_parity(ws, W, "truncated", 6, X, G, what=f"fused tails B={B} L={L} C={chunks} split={split}")
+    check_parity(ws, W, "truncated", 6, X, G, what=f"fused tails B={B} L={L} C={chunks}")
 
 
 # forward with the 2 or 4 chunks of a path in one workgroup (d = 4, depth 6), forced for any batch size; the last
