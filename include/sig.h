@@ -218,8 +218,11 @@ int sig_leadlag_backward(const float* grad_out, int64_t B, int64_t n_points, int
  * the small fill / transpose / chunk-product / chain-rule kernels).  sig_profile_read synchronises with the
  * recorded events and returns the number of calls recorded since sig_profile_enable(1) and the sum of the
  * durations in milliseconds for `which` = 0 forward main kernel, 1 backward main kernel, 2 whole forward call,
- * 3 whole backward call.  At most SIG_PROFILE_MAX_LAUNCHES calls per direction are kept; later ones are not
- * recorded.  Not thread-safe; events are created on first use (no device memory is allocated). */
+ * 3 whole backward call.  sig_profile_enable(0) switches recording off, (1) switches all four channels on, and
+ * (2 << which, or several of these or-ed) only the named ones: every recorded event costs a few microseconds on
+ * the stream, so a timed region that needs one kernel's duration enables that channel alone.  At most
+ * SIG_PROFILE_MAX_LAUNCHES calls per channel are kept; later ones are not recorded.  Not thread-safe; events are
+ * created on first use (no device memory is allocated). */
 #define SIG_PROFILE_MAX_LAUNCHES 4096
 int sig_profile_enable(int on);
 int sig_profile_read(int which, int64_t* n_launches, double* total_ms);

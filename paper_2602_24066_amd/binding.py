@@ -495,8 +495,15 @@ def sig_probe_fma_tflops(blocks: int = 256 * 32, iters: int = 4096, repeats: int
     return 2.0 * 16 * iters * 256 * blocks / (best * 1e-3) / 1e12
 
 
-def sig_profile_enable(on: bool) -> None:
-    _check(load_library().sig_profile_enable(int(on)), "sig_profile_enable")
+def sig_profile_enable(on, channels=None) -> None:
+    """on: False / True (all four channels); channels: iterable of channel numbers 0..3 (forward main kernel,
+    backward main kernel, whole forward call, whole backward call) to record only those."""
+    arg = int(bool(on))
+    if on and channels is not None:
+        arg = 0
+        for c in channels:
+            arg |= 2 << int(c)
+    _check(load_library().sig_profile_enable(arg), "sig_profile_enable")
 
 
 def sig_profile_read(backward: bool, whole_call: bool = False) -> Tuple[int, float]:

@@ -41,12 +41,12 @@ int pick_variant(const sig::WordSet& ws, int dir, int64_t B, int64_t want = 2048
 
 // kernel timer (see sig_profile_enable); channels 0/1: main kernel of forward/backward, 2/3: whole call
 struct Profiler {
-    bool on = false;
+    unsigned mask = 0;                // bit `which` set: that channel records
     std::vector<hipEvent_t> ev[4];    // start/stop interleaved
     size_t used[4] = {0, 0, 0, 0};
     hipEvent_t* next(int dir)
     {
-        if (!on || used[dir] >= SIG_PROFILE_MAX_LAUNCHES) return nullptr;
+        if (!((mask >> dir) & 1u) || used[dir] >= SIG_PROFILE_MAX_LAUNCHES) return nullptr;
         if (ev[dir].size() < 2 * (used[dir] + 1)) {
             hipEvent_t a, b;
             if (hipEventCreate(&a) != hipSuccess) return nullptr;
@@ -785,7 +785,7 @@ int sig_backward_windows(const sig_wordset* ws, const float* path, const float* 
 
 int sig_profile_enable(int on)
 {
-    g_prof.on = on != 0;
+    g_prof.mask = on == 1 ? 0xFu : ((unsigned)on >> 1) & 0xFu;
     for (size_t& u : g_prof.used) u = 0;
     return SIG_OK;
 }
