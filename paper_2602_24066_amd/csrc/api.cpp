@@ -665,12 +665,17 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
         }
         hipEvent_t* pe = g_prof.next(1);
         if (pe) (void)hipEventRecord(pe[0], st);
-        if (ch.fused) e = sig::trunc_backward_tails_fused(w.d, w.depth, path, coeffs, grad_coeffs, B, n_points, ch.C, ch.Lc, gdx, st);
-        else if (ch.tails) e = sig::trunc_backward_tails(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
+        // the one-wavefront-per-row kernel applies the chain rule itself when its rows are whole paths or all
+        // chunks of a path share a workgroup
+        const bool points = ch.fused || (ch.tails && ch.C == 1);
+        if (ch.fused) e = sig::trunc_backward_tails_fused(w.d, w.depth, path, coeffs, grad_coeffs, B, n_points, ch.C, ch.Lc, grad_path, st);
+        else if (ch.tails)
+            e = sig::trunc_backward_tails(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx,
+                                          points ? grad_path : nullptr, st);
         else e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
-        e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
+        if (!points) e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
     const sig::Plan* jp = nullptr;

@@ -62,11 +62,12 @@ hipError_t trunc_backward(int d, int depth, const float* path, const float* coef
 // the gradient of the increments instead of accumulating, so the rows must tile every path exactly
 bool trunc_backward_tails_available(int d, int depth);
 hipError_t trunc_backward_tails(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
-                                int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream);
+                                int64_t P, int64_t C, int64_t Lc, float* gdx, float* grad_path /*C = 1: chain rule in the kernel*/,
+                                hipStream_t stream);
 // the same with the C = 2, 4 or 8 chunks of a path in one workgroup: chunk signatures, their products and the
-// boundary adjoints stay in LDS; coeffs / grad_coeffs are [B, |W|]
+// boundary adjoints stay in LDS; coeffs / grad_coeffs are [B, |W|]; writes the gradient with respect to the points
 hipError_t trunc_backward_tails_fused(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs,
-                                      int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream);
+                                      int64_t B, int64_t P, int64_t C, int64_t Lc, float* grad_path, hipStream_t stream);
 // forward with the C = 2 or 4 chunks of a path in one workgroup: chunk signatures multiplied in LDS; coeffs [B, |W|],
 // 16-byte aligned
 bool trunc_forward_tails_available(int d, int depth);

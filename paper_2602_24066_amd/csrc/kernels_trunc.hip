@@ -1036,7 +1036,10 @@ struct TailsLds {
     // the chunk signatures and their products are kept up to length N - 1: the backward walk never reads the
     // coefficients of the longest words, and their adjoints are the gradient itself
     static constexpr int W1 = level_start(D, N);
-    static constexpr int TILE = T * 2 * D + T * D * NC;                      // E, Ec of one wavefront
+    // E, Ec of one wavefront, and 2 D floats for the chain rule: the increment gradient of the first segment of the
+    // tile walked before, and of the last segment of the row
+    static constexpr int TILE = T * 2 * D + T * D * NC + 2 * D;
+    static constexpr int OFF_CG = T * 2 * D + T * D * NC;
     static constexpr int RED = T * D + NSRC * T * kWave;                     // gt, Vb of one wavefront
     // fused: area A holds first the signature buffers and a copy of the gradient row of the path, later the
     // reduction regions
@@ -1046,7 +1049,8 @@ struct TailsLds {
     // fused: the tiles come first (their addresses then fit the offset field of the LDS instructions), area A next
     static constexpr int OFF_A = CW ? NWV * TILE : 0;
     static constexpr int OFF_G = OFF_A + NBUF * W1;                           // fused: the gradient row of the path
-    static constexpr int TOTAL = CW ? OFF_A + AREA_A : NWV * (TILE + RED);
+    static constexpr int OFF_XY = OFF_A + AREA_A;     // fused: first / last segment gradients of the CW chunks
+    static constexpr int TOTAL = CW ? OFF_XY + CW * 2 * D : NWV * (TILE + RED);
     static_assert(TILE % 4 == 0 && RED % 4 == 0 && AREA_A % 4 == 0 && W % 4 == 0 && W1 % 4 == 0, "16-byte alignment");
     static constexpr size_t BYTES = (size_t)TOTAL * sizeof(float);
     __device__ static float* tile(float* base, int wib) { return base + (CW ? wib * TILE : wib * (TILE + RED)); }
@@ -1143,8 +1147,10 @@ __device__ __forceinline__ float word_contract(const float* g, const float* q, i
 template <int D, int N, int T, int CW>
 __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tails_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
-    int64_t P, int64_t C, int64_t Lc, float* __restrict__ gdx)
+    int64_t P, int64_t C, int64_t Lc, float* __restrict__ gdx, float* __restrict__ grad_path)
 {
+    // grad_path != nullptr (fused, or rows that are whole paths): the chain rule dX_j = X_{j+1} - X_j is applied here
+    // and the gradient with respect to the points is stored; otherwise gdx receives the increment gradients.
     static_assert(D == 4, "one group of four letters");
     constexpr int K = N - 2;                          // length of the tail words
     constexpr int KL = K - 1;                         // letters held per lane
@@ -1165,6 +1171,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
     float* const smem = (float*)bwd_smem;
     float (*E)[2][D] = (float (*)[2][D])(LY::tile(smem, wib));            // wave-private
     float (*Ec)[D][NC] = (float (*)[D][NC])(LY::tile(smem, wib) + T * 2 * D);
+    float* const cg = LY::tile(smem, wib) + LY::OFF_CG;                   // chain-rule carry, see the flush below
     float* gt = LY::red(smem, wib);                                       // fused: valid after the signature buffers
     float* Vb = gt + T * D;                                               // are dead
     const int64_t b = row / C;
@@ -1496,10 +1503,53 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
         wave_lds_fence();
         lane_chain_tile_reduce<D, KL, T, 0, KL>(Vb + D * T * kWave, gt, lane, letter);
         wave_lds_fence();
-        for (int e = lane; e < T * D; e += kWave) {
-            const int64_t sgm = n * T + e / D;
-            if (sgm < L) gdx[(b * (P - 1) + seg0 + n * T) * D + e] = gt[e];
-            gt[e] = 0.0f;
+        if (grad_path) {
+            // point j + 1 of the row: gradient of segment j minus that of segment j + 1 (next entry of the tile, or
+            // the first one of the tile walked before); the point after the last segment is left to the end
+            for (int e = lane; e < T * D; e += kWave) {
+                const int tt = e / D, i = e % D;
+                const int64_t sgm = n * T + tt;
+                if (sgm < L) {
+                    const float g = gt[e];
+                    if (sgm + 1 < L) {
+                        const float next = tt + 1 < T ? gt[e + D] : cg[i];
+                        grad_path[(b * P + seg0 + sgm + 1) * D + i] = g - next;
+                    } else {
+                        cg[D + i] = g;
+                    }
+                }
+            }
+            wave_lds_fence();
+            if (lane < D) cg[lane] = gt[lane];
+            wave_lds_fence();
+            for (int e = lane; e < T * D; e += kWave) gt[e] = 0.0f;
+        } else {
+            for (int e = lane; e < T * D; e += kWave) {
+                const int64_t sgm = n * T + e / D;
+                if (sgm < L) gdx[(b * (P - 1) + seg0 + n * T) * D + e] = gt[e];
+                gt[e] = 0.0f;
+            }
+        }
+    }
+    if (grad_path) {
+        // cg: gradient of the first segment of the row, cg + D: of its last one
+        if constexpr (CW == 0) {                       // the row is a whole path
+            if (lane < D) {
+                grad_path[(b * P) * D + lane] = -cg[lane];
+                grad_path[(b * P + L) * D + lane] = cg[D + lane];
+            }
+        } else {
+            float* const XY = smem + LY::OFF_XY;
+            if (lane < 2 * D) XY[cib * 2 * D + lane] = cg[lane];
+            __syncthreads();
+            // point where chunk k begins (k = CW: the end of the path): last segment of chunk k - 1 minus first of k
+            if ((int)threadIdx.x < (CW + 1) * D) {
+                const int k = threadIdx.x / D, i = threadIdx.x % D;
+                const float before = k >= 1 ? XY[(k - 1) * 2 * D + D + i] : 0.0f;
+                const float after = k < CW ? XY[k * 2 * D + i] : 0.0f;
+                const int64_t pt = k < CW ? k * Lc : P - 1;
+                grad_path[(b * P + pt) * D + i] = before - after;
+            }
         }
     }
 }
@@ -1700,7 +1750,7 @@ hipError_t launch_trunc_tails_fwd(const float* path, int64_t B, int64_t P, int64
 
 template <int D, int N, int CW>
 hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
-                                  int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
+                                  int64_t C, int64_t Lc, float* gdx, float* grad_path, hipStream_t stream)
 {
     constexpr int T = 8;
     using LY = TailsLds<D, N, T, CW>;
@@ -1717,8 +1767,9 @@ hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const 
             attr_set = true;
         }
     }
+    if (grad_path && CW == 0 && C != 1) return hipErrorInvalidValue;   // rows that are parts of paths cannot apply the chain rule
     trunc_tails_bwd_kernel<D, N, T, CW><<<(unsigned)blocks, kWave * LY::NWV, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C, Lc,
-                                                                                                gdx);
+                                                                                                gdx, grad_path);
     return hipGetLastError();
 }
 
@@ -1800,23 +1851,26 @@ bool trunc_backward_available(int d, int depth)
 // stores, it does not accumulate).
 bool trunc_backward_tails_available(int d, int depth) { return d == 4 && depth == 6; }
 
+// grad_path given (C = 1 only): the chain rule is applied in the kernel and gdx is not used
 hipError_t trunc_backward_tails(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
-                                int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
+                                int64_t P, int64_t C, int64_t Lc, float* gdx, float* grad_path, hipStream_t stream)
 {
-    if (d == 4 && depth == 6) return launch_trunc_tails_bwd<4, 6, 0>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (d == 4 && depth == 6)
+        return launch_trunc_tails_bwd<4, 6, 0>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, grad_path, stream);
     return hipErrorInvalidValue;
 }
 
 // Fused form: the C (2, 4 or 8) chunks of a path are the wavefronts of one workgroup; coeffs / grad_coeffs are the
-// terminal signature and its gradient [B, |W|], nothing else is needed.  Every chunk must hold at least one segment.
+// terminal signature and its gradient [B, |W|], nothing else is needed, and the gradient with respect to the points
+// [B, P, d] is written directly.  Every chunk must hold at least one segment.
 hipError_t trunc_backward_tails_fused(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs,
-                                      int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
+                                      int64_t B, int64_t P, int64_t C, int64_t Lc, float* grad_path, hipStream_t stream)
 {
-    if ((C - 1) * Lc >= P - 1) return hipErrorInvalidValue;
+    if ((C - 1) * Lc >= P - 1 || !grad_path) return hipErrorInvalidValue;
     if (!(d == 4 && depth == 6)) return hipErrorInvalidValue;
-    if (C == 8) return launch_trunc_tails_bwd<4, 6, 8>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
-    if (C == 4) return launch_trunc_tails_bwd<4, 6, 4>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
-    if (C == 2) return launch_trunc_tails_bwd<4, 6, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (C == 8) return launch_trunc_tails_bwd<4, 6, 8>(path, coeffs, grad_coeffs, B, P, C, Lc, nullptr, grad_path, stream);
+    if (C == 4) return launch_trunc_tails_bwd<4, 6, 4>(path, coeffs, grad_coeffs, B, P, C, Lc, nullptr, grad_path, stream);
+    if (C == 2) return launch_trunc_tails_bwd<4, 6, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, nullptr, grad_path, stream);
     return hipErrorInvalidValue;
 }
 
