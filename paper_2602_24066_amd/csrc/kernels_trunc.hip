@@ -256,7 +256,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_fwd_kernel(
     __shared__ __attribute__((aligned(16))) float Ec_all[kWavesPerBlock][2 * T][D][NC];   // scale index fastest (chain reads)
 
     const int lane = threadIdx.x % kWave;
-    const int wib = threadIdx.x / kWave;
+    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // the same in every lane: scalar registers
     const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
     if (wave >= B * C * G::WAVES) return;                 // no barriers below: a whole wavefront may leave
     float (*E)[N][D] = E_all[wib];
@@ -622,7 +622,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     extern __shared__ v4f bwd_smem[];
 
     const int lane = threadIdx.x % kWave;
-    const int wib = threadIdx.x / kWave;
+    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // the same in every lane: scalar registers
     const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
     if (wave >= B * C * G::WAVES) return;
     float* const lds = (float*)bwd_smem + wib * LY::PER_WAVE;            // wave-private
@@ -1036,9 +1036,9 @@ struct TailsLds {
     // the chunk signatures and their products are kept up to length N - 1: the backward walk never reads the
     // coefficients of the longest words, and their adjoints are the gradient itself
     static constexpr int W1 = level_start(D, N);
-    // E, Ec of one wavefront, and 2 D floats for the chain rule: the increment gradient of the first segment of the
-    // tile walked before, and of the last segment of the row
-    static constexpr int TILE = T * 2 * D + T * D * NC + 2 * D;
+    // E, Ec of one wavefront, and for the chain rule the increment gradients of the first and of the last segment of
+    // the row (2 D floats) and of the tile walked before (T D floats)
+    static constexpr int TILE = T * 2 * D + T * D * NC + 2 * D + T * D;
     static constexpr int OFF_CG = T * 2 * D + T * D * NC;
     static constexpr int RED = T * D + NSRC * T * kWave;                     // gt, Vb of one wavefront
     // fused: area A holds first the signature buffers and a copy of the gradient row of the path, later the
@@ -1144,13 +1144,16 @@ __device__ __forceinline__ float word_contract(const float* g, const float* q, i
     return g[level_start(D, n) + i] + acc;
 }
 
-template <int D, int N, int T, int CW>
+template <int D, int N, int T, int CW, bool POINTS>
 __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tails_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
-    int64_t P, int64_t C, int64_t Lc, float* __restrict__ gdx, float* __restrict__ grad_path)
+    int64_t P, int64_t C, int64_t Lc, float* __restrict__ out)
 {
-    // grad_path != nullptr (fused, or rows that are whole paths): the chain rule dX_j = X_{j+1} - X_j is applied here
-    // and the gradient with respect to the points is stored; otherwise gdx receives the increment gradients.
+    // POINTS (fused, or rows that are whole paths): the chain rule dX_j = X_{j+1} - X_j is applied here and out
+    // receives the gradient with respect to the points [B, P, d]; otherwise the increment gradients [B, P - 1, d].
+    static_assert(POINTS || CW == 0, "the fused form writes the gradient with respect to the points");
+    float* const grad_path = out;
+    float* const gdx = out;
     static_assert(D == 4, "one group of four letters");
     constexpr int K = N - 2;                          // length of the tail words
     constexpr int KL = K - 1;                         // letters held per lane
@@ -1162,7 +1165,9 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
     extern __shared__ v4f bwd_smem[];
 
     const int lane = threadIdx.x % kWave;
-    const int wib = threadIdx.x / kWave;
+    // the same in every lane: said so, the row number and what follows from it (path, first segment, length, base
+    // addresses) stay in scalar registers
+    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int cib = wib;                              // fused: chunk of the workgroup's path
     const int64_t row = CW ? (int64_t)blockIdx.x * C + cib : (int64_t)blockIdx.x * kWavesPerBlock + wib;
     if constexpr (CW == 0) {
@@ -1171,7 +1176,8 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
     float* const smem = (float*)bwd_smem;
     float (*E)[2][D] = (float (*)[2][D])(LY::tile(smem, wib));            // wave-private
     float (*Ec)[D][NC] = (float (*)[D][NC])(LY::tile(smem, wib) + T * 2 * D);
-    float* const cg = LY::tile(smem, wib) + LY::OFF_CG;                   // chain-rule carry, see the flush below
+    float* const cg = LY::tile(smem, wib) + LY::OFF_CG;                   // chain rule, see the flush below
+    float* const pg = cg + 2 * D;
     float* gt = LY::red(smem, wib);                                       // fused: valid after the signature buffers
     float* Vb = gt + T * D;                                               // are dead
     const int64_t b = row / C;
@@ -1462,7 +1468,9 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
             gbL[2] = fmaf(et[i][1], g1, gbL[2]);
             gbL[3] = fmaf(et[i][2], g2, gbL[3]);
         }
-        // 3d. per-lane chain
+        // 3d. per-lane chain.  The scaled increments of the chain letters are read from LDS a second time (through
+        // an opaque copy of the letter, so that the two reads are not merged): keeping them in registers across the
+        // tails would cost the registers that let two wavefronts share a SIMD.
         float gb[KL + 1][N + 2];
 #pragma unroll
         for (int k = 0; k <= KL; ++k)
@@ -1472,6 +1480,9 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
         for (int t = 1; t <= 3; ++t) gb[KL][t] = gbL[t];
 #pragma unroll
         for (int k = KL; k >= 1; --k) {
+            int letter_again = letter[k - 1];
+            asm volatile("" : "+v"(letter_again));
+            const float* ec2 = &Ec[row_t][letter_again][0];
             gb[k][0] = Ac[k - 1];
             float gc = 0.0f, asum = 0.0f;
 #pragma unroll
@@ -1479,7 +1490,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
                 const float q = gb[k][t];
                 asum += q;
                 gc = fmaf(q * inv1(t), ap[k - 1][t + 1], gc);
-                gb[k - 1][t + 1] = fmaf(ec[k - 1][t], q, gb[k - 1][t + 1]);
+                if (k > 1) gb[k - 1][t + 1] = fmaf(ec2[t], q, gb[k - 1][t + 1]);
             }
             Ac[k - 1] = asum;
             vb[(D + (k - 1)) * T * kWave] = gc;                               // letter[k - 1]
@@ -1503,26 +1514,26 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
         wave_lds_fence();
         lane_chain_tile_reduce<D, KL, T, 0, KL>(Vb + D * T * kWave, gt, lane, letter);
         wave_lds_fence();
-        if (grad_path) {
-            // point j + 1 of the row: gradient of segment j minus that of segment j + 1 (next entry of the tile, or
-            // the first one of the tile walked before); the point after the last segment is left to the end
-            for (int e = lane; e < T * D; e += kWave) {
+        if constexpr (POINTS) {
+            // Point j of the row gets the gradient of segment j - 1 minus that of segment j.  The points at which the
+            // segments of the tile walked before (pg, later in time) begin are complete now and are stored as one
+            // aligned row; the first point of the row and the one after its last segment are left to the end.
+            float* const row_points = grad_path + (b * P + seg0 + (n + 1) * T) * D;   // the same in every lane
+            // (the lane number is taken through an opaque copy: addresses derived from it would otherwise be kept
+            // in registers across the segment loop, which has none to spare)
+            int lane_here = lane;
+            asm volatile("" : "+v"(lane_here));
+            for (int e = lane_here; e < T * D; e += kWave) {
                 const int tt = e / D, i = e % D;
-                const int64_t sgm = n * T + tt;
-                if (sgm < L) {
-                    const float g = gt[e];
-                    if (sgm + 1 < L) {
-                        const float next = tt + 1 < T ? gt[e + D] : cg[i];
-                        grad_path[(b * P + seg0 + sgm + 1) * D + i] = g - next;
-                    } else {
-                        cg[D + i] = g;
-                    }
-                }
+                if ((n + 1) * T + tt < L) row_points[e] = (tt >= 1 ? pg[e - D] : gt[(T - 1) * D + i]) - pg[e];
+                if (n * T + tt == L - 1) cg[D + i] = gt[e];                  // last segment of the row
             }
             wave_lds_fence();
-            if (lane < D) cg[lane] = gt[lane];
+            for (int e = lane_here; e < T * D; e += kWave) {
+                pg[e] = gt[e];
+                gt[e] = 0.0f;
+            }
             wave_lds_fence();
-            for (int e = lane; e < T * D; e += kWave) gt[e] = 0.0f;
         } else {
             for (int e = lane; e < T * D; e += kWave) {
                 const int64_t sgm = n * T + e / D;
@@ -1531,8 +1542,15 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
             }
         }
     }
-    if (grad_path) {
-        // cg: gradient of the first segment of the row, cg + D: of its last one
+    if constexpr (POINTS) {
+        // the points inside the first tile; then cg: gradient of the first segment of the row, cg + D: of its last one
+        float* const row_points = grad_path + (b * P + seg0) * D;
+        for (int e = lane; e < T * D; e += kWave) {
+            const int tt = e / D;
+            if (tt >= 1 && tt < L) row_points[e] = pg[e - D] - pg[e];
+        }
+        if (lane < D) cg[lane] = pg[lane];
+        wave_lds_fence();
         if constexpr (CW == 0) {                       // the row is a whole path
             if (lane < D) {
                 grad_path[(b * P) * D + lane] = -cg[lane];
@@ -1594,7 +1612,7 @@ __global__ __launch_bounds__(kWave * CW * (D / TW)) void trunc_tails_fwd_kernel(
     extern __shared__ v4f fwd_smem[];
 
     const int lane = threadIdx.x % kWave;
-    const int wib = threadIdx.x / kWave;
+    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // the same in every lane: scalar registers
     const int cib = wib / H;                          // chunk of the workgroup's path
     const int i0 = (wib % H) * TW;                    // first tail of this wavefront
     const bool first = wib % H == 0;
@@ -1748,9 +1766,9 @@ hipError_t launch_trunc_tails_fwd(const float* path, int64_t B, int64_t P, int64
     return hipGetLastError();
 }
 
-template <int D, int N, int CW>
+template <int D, int N, int CW, bool POINTS>
 hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
-                                  int64_t C, int64_t Lc, float* gdx, float* grad_path, hipStream_t stream)
+                                  int64_t C, int64_t Lc, float* out, hipStream_t stream)
 {
     constexpr int T = 8;
     using LY = TailsLds<D, N, T, CW>;
@@ -1761,15 +1779,15 @@ hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const 
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
         static bool attr_set = false;
         if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T, CW>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T, CW, POINTS>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
             if (e != hipSuccess) return e;
             attr_set = true;
         }
     }
-    if (grad_path && CW == 0 && C != 1) return hipErrorInvalidValue;   // rows that are parts of paths cannot apply the chain rule
-    trunc_tails_bwd_kernel<D, N, T, CW><<<(unsigned)blocks, kWave * LY::NWV, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C, Lc,
-                                                                                                gdx, grad_path);
+    if (POINTS && CW == 0 && C != 1) return hipErrorInvalidValue;   // rows that are parts of paths cannot apply the chain rule
+    trunc_tails_bwd_kernel<D, N, T, CW, POINTS><<<(unsigned)blocks, kWave * LY::NWV, LY::BYTES, stream>>>(path, coeffs, grad, B, P,
+                                                                                                        C, Lc, out);
     return hipGetLastError();
 }
 
@@ -1855,9 +1873,9 @@ bool trunc_backward_tails_available(int d, int depth) { return d == 4 && depth =
 hipError_t trunc_backward_tails(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
                                 int64_t P, int64_t C, int64_t Lc, float* gdx, float* grad_path, hipStream_t stream)
 {
-    if (d == 4 && depth == 6)
-        return launch_trunc_tails_bwd<4, 6, 0>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, grad_path, stream);
-    return hipErrorInvalidValue;
+    if (!(d == 4 && depth == 6)) return hipErrorInvalidValue;
+    if (grad_path) return launch_trunc_tails_bwd<4, 6, 0, true>(path, coeffs, grad_coeffs, B, P, C, Lc, grad_path, stream);
+    return launch_trunc_tails_bwd<4, 6, 0, false>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
 }
 
 // Fused form: the C (2, 4 or 8) chunks of a path are the wavefronts of one workgroup; coeffs / grad_coeffs are the
@@ -1868,9 +1886,9 @@ hipError_t trunc_backward_tails_fused(int d, int depth, const float* path, const
 {
     if ((C - 1) * Lc >= P - 1 || !grad_path) return hipErrorInvalidValue;
     if (!(d == 4 && depth == 6)) return hipErrorInvalidValue;
-    if (C == 8) return launch_trunc_tails_bwd<4, 6, 8>(path, coeffs, grad_coeffs, B, P, C, Lc, nullptr, grad_path, stream);
-    if (C == 4) return launch_trunc_tails_bwd<4, 6, 4>(path, coeffs, grad_coeffs, B, P, C, Lc, nullptr, grad_path, stream);
-    if (C == 2) return launch_trunc_tails_bwd<4, 6, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, nullptr, grad_path, stream);
+    if (C == 8) return launch_trunc_tails_bwd<4, 6, 8, true>(path, coeffs, grad_coeffs, B, P, C, Lc, grad_path, stream);
+    if (C == 4) return launch_trunc_tails_bwd<4, 6, 4, true>(path, coeffs, grad_coeffs, B, P, C, Lc, grad_path, stream);
+    if (C == 2) return launch_trunc_tails_bwd<4, 6, 2, true>(path, coeffs, grad_coeffs, B, P, C, Lc, grad_path, stream);
     return hipErrorInvalidValue;
 }
 
