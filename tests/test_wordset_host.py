@@ -370,3 +370,32 @@ def test_logsig_word_set_bit_exact(d, depth):
     assert int(S.load_library().sig_wordset_n_lyndon(ws._h)) == len(lyn)
     assert [W[i] for i in ws.user_index] == lyn
     assert int(S.load_library().sig_wordset_n_lyndon(S.sig_wordset_build_truncated(2, 3)._h)) == 0
+
+
+# ---- which kernel a batch would launch (host logic only: no device call is made) ---------------------------
+def test_kernel_selection_for_full_truncations(monkeypatch):
+    for k in ("SIG_FWD_TAILS", "SIG_BWD_TAILS", "SIG_CHUNKS", "SIG_NO_JIT"):
+        monkeypatch.delenv(k, raising=False)
+    ws46 = S.sig_wordset_build_truncated(4, 6)
+    # d = 4: the one-wavefront-per-row layout for every batch size of the forward except few, long paths
+    assert ws46.kernel_name(False, 256, 256) == "trunc_tails_fwd_kernel"
+    assert ws46.kernel_name(False, 5000, 64) == "trunc_tails_fwd_kernel"
+    assert ws46.kernel_name(False, 64, 2049) == "trunc_mfma_fwd_kernel"
+    assert ws46.kernel_name(False, 64, 9) == "trunc_mfma_fwd_kernel"          # too short for two chunks of 8 segments
+    assert ws46.kernel_name(True, 256, 256) == "trunc_tails_bwd_kernel"
+    assert ws46.kernel_name(True, 4000, 40) == "trunc_tails_bwd_kernel"
+    monkeypatch.setenv("SIG_FWD_TAILS", "0")
+    monkeypatch.setenv("SIG_BWD_TAILS", "0")
+    assert ws46.kernel_name(False, 256, 256) == "trunc_mfma_fwd_kernel"
+    assert ws46.kernel_name(True, 256, 256) == "trunc_mfma_bwd_kernel"
+    monkeypatch.delenv("SIG_FWD_TAILS")
+    monkeypatch.delenv("SIG_BWD_TAILS")
+    monkeypatch.setenv("SIG_CHUNKS", "4")                                       # asks for chunk arrays in HBM
+    assert ws46.kernel_name(False, 256, 256) == "trunc_mfma_fwd_kernel"
+    monkeypatch.delenv("SIG_CHUNKS")
+    # the other instantiated shapes, and a truncation without one
+    assert S.sig_wordset_build_truncated(8, 5).kernel_name(True, 128, 1025) == "trunc_mfma_bwd_kernel"
+    assert S.sig_wordset_build_truncated(16, 4).kernel_name(False, 64, 4097) == "trunc_mfma_fwd_kernel"
+    assert S.sig_wordset_build_truncated(3, 4).kernel_name(False, 64, 65) == "sig_fwd_jit"
+    # batches beyond the row limit of the truncated kernels take the specialised ones
+    assert ws46.kernel_name(False, 70000, 17) == "sig_fwd_jit"
