@@ -22,6 +22,8 @@
 
 #include "kernels.hpp"
 
+#include <cstdlib>
+
 namespace sig {
 
 namespace {
@@ -509,19 +511,11 @@ __global__ void logsig_forward_kernel(const float* __restrict__ coeffs, int64_t 
 // between Lyndon words (a single letter by thousands of them), so the contributions are not added with atomics:
 // this kernel writes them to part[(b n_lyn + k) n_pairs + pair(i, j)] and logsig_gather_kernel sums, per sub-word,
 // the entries an inverse table lists.
-template <int DEPTH>
-__global__ void logsig_backward_kernel(const float* __restrict__ coeffs, const float* __restrict__ glog, int64_t B, int64_t nW,
-                                       const int32_t* __restrict__ lyn_len, const int32_t* __restrict__ lyn_sub, int64_t n_lyn,
-                                       int stride, int depth, int n_pairs, float* __restrict__ part)
+// emit(i, j, value) receives g * d logsig(w) / d S(w[i:j]) for every 0 <= i < j <= n
+template <int MD, class Emit>
+__device__ __forceinline__ void logsig_word_adjoint(const float* __restrict__ S, const int32_t* __restrict__ sub, int n, int depth,
+                                                    float g, Emit&& emit)
 {
-    constexpr int MD = DEPTH ? DEPTH : kMaxLogDepth;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= B * n_lyn) return;
-    const int64_t b = idx / n_lyn, k = idx - b * n_lyn;
-    const int n = lyn_len[k];
-    const int32_t* sub = lyn_sub + k * stride;
-    const float* S = coeffs + b * nW;
-    const float g = glog[idx];
     float sw[MD][MD + 1];
 #pragma unroll
     for (int i = 0; i < MD; ++i)
@@ -545,21 +539,60 @@ __global__ void logsig_backward_kernel(const float* __restrict__ coeffs, const f
             pre[a][i] = v;
             suf[a][i] = u;
         }
-    float* dst = part + idx * n_pairs;
 #pragma unroll
     for (int i = 0; i < MD; ++i)
 #pragma unroll
         for (int j = i + 1; j <= MD; ++j) {
             if (j > n) continue;
-            const int pair = i * depth - i * (i - 1) / 2 + (j - i - 1);      // pairs i < j <= depth in row-major order
             float t = 0.0f;
 #pragma unroll
             for (int a = 0; a < MD; ++a)
 #pragma unroll
                 for (int c = 0; c < MD; ++c)
                     if (a + c < MD) t = fmaf((((a + c) & 1) ? -1.0f : 1.0f) / (float)(a + c + 1), pre[a][i] * suf[c][j], t);
-            dst[pair] = g * t;
+            emit(i, j, g * t);
         }
+}
+
+template <int DEPTH>
+__global__ void logsig_backward_kernel(const float* __restrict__ coeffs, const float* __restrict__ glog, int64_t B, int64_t nW,
+                                       const int32_t* __restrict__ lyn_len, const int32_t* __restrict__ lyn_sub, int64_t n_lyn,
+                                       int stride, int depth, int n_pairs, float* __restrict__ part)
+{
+    constexpr int MD = DEPTH ? DEPTH : kMaxLogDepth;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= B * n_lyn) return;
+    const int64_t b = idx / n_lyn, k = idx - b * n_lyn;
+    float* dst = part + idx * n_pairs;
+    logsig_word_adjoint<MD>(coeffs + b * nW, lyn_sub + k * stride, lyn_len[k], depth, glog[idx], [&](int i, int j, float v) {
+        dst[i * depth - i * (i - 1) / 2 + (j - i - 1)] = v;                     // pairs i < j <= depth in row-major order
+    });
+}
+
+// One workgroup per path, for word sets whose gradient row fits in LDS: the contributions are added there with LDS
+// atomics (sub-words shared by many Lyndon words meet in one address, but only within a workgroup) and the row is
+// stored once.  Neither the array of contributions nor the inverse table is needed.
+template <int DEPTH>
+__global__ __launch_bounds__(512) void logsig_backward_lds_kernel(const float* __restrict__ coeffs, const float* __restrict__ glog,
+                                                                  int64_t nW, const int32_t* __restrict__ lyn_len,
+                                                                  const int32_t* __restrict__ lyn_sub, int64_t n_lyn, int stride,
+                                                                  int depth, float* __restrict__ gcoeffs)
+{
+    constexpr int MD = DEPTH ? DEPTH : kMaxLogDepth;
+    extern __shared__ float4 logsig_smem[];
+    float* const acc = (float*)logsig_smem;
+    const int64_t b = blockIdx.x;
+    for (int64_t u = threadIdx.x; u < nW; u += blockDim.x) acc[u] = 0.0f;
+    __syncthreads();
+    const float* S = coeffs + b * nW;
+    for (int64_t k = threadIdx.x; k < n_lyn; k += blockDim.x) {
+        const int32_t* sub = lyn_sub + k * stride;
+        logsig_word_adjoint<MD>(S, sub, lyn_len[k], depth, glog[b * n_lyn + k], [&](int i, int j, float v) {
+            __hip_atomic_fetch_add(acc + sub[i * (depth + 1) + j], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        });
+    }
+    __syncthreads();
+    for (int64_t u = threadIdx.x; u < nW; u += blockDim.x) gcoeffs[b * nW + u] = acc[u];
 }
 
 // one wavefront per (path, sub-word): the lists of short sub-words are thousands of entries long
@@ -594,13 +627,49 @@ hipError_t logsig_forward(const float* coeffs, int64_t B, int64_t nW, const int3
 #undef SIG_LOGSIG_FWD
     return hipGetLastError();
 }
+// bytes of LDS the one-kernel form of the backward needs for a gradient row; 0 = the row does not fit
+static size_t logsig_row_lds_bytes(int64_t nW)
+{
+    const char* two = std::getenv("SIG_LOGSIG_GATHER");          // the tests force the two-kernel form with it
+    if (two && two[0] && two[0] != '0') return 0;
+    const size_t n = ((size_t)nW * sizeof(float) + 15) & ~(size_t)15;
+    return n <= 128 * 1024 ? n : 0;
+}
+
 hipError_t logsig_backward(const float* coeffs, const float* glog, int64_t B, int64_t nW, const int32_t* lyn_len,
                            const int32_t* lyn_sub, int64_t n_lyn, int stride, int depth, int n_pairs, const int32_t* inv_off,
                            const int32_t* inv, float* part, float* gcoeffs, hipStream_t stream)
 {
     const int64_t n = B * n_lyn;
-    if (n <= 0) return hipSuccess;
+    if (B <= 0) return hipSuccess;
     if (depth > kMaxLogDepth) return hipErrorInvalidValue;
+    if (const size_t lds = logsig_row_lds_bytes(nW)) {
+        if (B > 0x7fffffff) return hipErrorInvalidValue;
+#define SIG_LOGSIG_BWD_LDS(DEPTH)                                                                                              \
+    do {                                                                                                                       \
+        if (lds > 64 * 1024) {                                                                                                 \
+            static bool attr_set = false;                                                                                      \
+            if (!attr_set) {                                                                                                   \
+                hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&logsig_backward_lds_kernel<DEPTH>),         \
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);                   \
+                if (ea != hipSuccess) return ea;                                                                               \
+                attr_set = true;                                                                                               \
+            }                                                                                                                  \
+        }                                                                                                                      \
+        logsig_backward_lds_kernel<DEPTH><<<(unsigned)B, 512, lds, stream>>>(coeffs, glog, nW, lyn_len, lyn_sub, n_lyn, stride, \
+                                                                            depth, gcoeffs);                                   \
+    } while (0)
+        if (depth <= 4) SIG_LOGSIG_BWD_LDS(4);
+        else if (depth <= 6) SIG_LOGSIG_BWD_LDS(6);
+        else if (depth <= 8) SIG_LOGSIG_BWD_LDS(8);
+        else SIG_LOGSIG_BWD_LDS(0);
+#undef SIG_LOGSIG_BWD_LDS
+        return hipGetLastError();
+    }
+    if (n <= 0) {                                          // no Lyndon words: the gradient is zero
+        return fill_zero(gcoeffs, B * nW, stream);
+    }
+    if (!part) return hipErrorInvalidValue;
     const unsigned grid = (unsigned)((n + 127) / 128);
 #define SIG_LOGSIG_BWD(DEPTH) \
     logsig_backward_kernel<DEPTH><<<grid, 128, 0, stream>>>(coeffs, glog, B, nW, lyn_len, lyn_sub, n_lyn, stride, depth, n_pairs, part)

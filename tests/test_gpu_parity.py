@@ -266,9 +266,16 @@ def test_log_signature(d, depth, B, L):
         assert e <= FWD_TOL, f"log-signature level {n}: {e:.3e}"
 
 
-def test_log_signature_gradient():
-    """d <G, logsig(X)> / dX through sig_logsig_backward and sig_backward against central differences of the oracle."""
+@pytest.mark.parametrize("two_kernels", [False, True])
+def test_log_signature_gradient(monkeypatch, two_kernels):
+    """d <G, logsig(X)> / dX through sig_logsig_backward and sig_backward against central differences of the oracle;
+    sig_logsig_backward in its one-kernel form (gradient row summed in LDS) and in the form for rows that do not fit
+    there (contributions written out, then gathered per word)."""
     import torch
+    if two_kernels:
+        monkeypatch.setenv("SIG_LOGSIG_GATHER", "1")
+    else:
+        monkeypatch.delenv("SIG_LOGSIG_GATHER", raising=False)
     d, depth, B, L = 3, 4, 2, 5
     ws = S.sig_wordset_build_logsig(d, depth)
     ws.upload("cuda:0")
