@@ -14,7 +14,9 @@
  *     (Appendix A, word integer encoding), i.e. levels 1..N concatenated,
  *     each row-major.
  *   - A path is float32 [B, n_points, d], row-major, n_points = L + 1 >= 1.
- *   - coeffs / grad_coeffs are float32 [B, |W|] in canonical order, 16-byte aligned.
+ *   - coeffs / grad_coeffs are float32 [B, |W|] in canonical order; 16-byte aligned buffers get the fastest
+ *     kernels (others fall back to kernels that read word by word; the long-path form with time chunks in the
+ *     workspace returns SIG_EINVAL for them).
  *   - Every function returns 0 on success and a negative SIG_E* code on
  *     failure; nothing is printed, no exception or abort crosses the ABI.
  *   - "host" / "device" on a pointer says where the memory lives.  The library

@@ -635,7 +635,10 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     CallTimer whole(1, st);
     hipError_t e = hipSuccess;
     const bool trunc = use_trunc_backward(w, B);
-    const BwdShape ch = trunc ? trunc_backward_shape(w, B, n_points) : BwdShape{false, false, 1, n_points - 1};
+    BwdShape ch = trunc ? trunc_backward_shape(w, B, n_points) : BwdShape{false, false, 1, n_points - 1};
+    // the fused form copies the gradient row with 16-byte loads; rows that are not aligned so take the kernel with
+    // four wavefronts per path, which reads word by word
+    if (ch.fused && (((uintptr_t)coeffs | (uintptr_t)grad_coeffs) & 15) != 0) ch = BwdShape{false, false, 1, n_points - 1};
     if (!ch.tails) {                     // the one-wavefront-per-row kernel stores every entry itself
         e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
         if (e != hipSuccess) return hip_fail(e);

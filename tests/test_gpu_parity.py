@@ -133,6 +133,34 @@ def test_forward_fused_and_four_wavefront_kernels_agree(monkeypatch):
         assert e <= 1e-5, (n, e)
 
 
+def test_rows_that_are_not_16_byte_aligned():
+    """coeffs / grad_coeffs four bytes off a 16-byte boundary: the d = 4 kernels that use vector loads and stores step
+    aside for the ones that do not, with the same results."""
+    import torch
+    ws, W = build_both("truncated", 4, depth=6)
+    B, L = 130, 70
+    X = make_path("time0", 31, B, L, 4)
+    G = make_grad_coeffs(32, B, ws.size)
+    xp = torch.from_numpy(X).cuda()
+    buf_c = torch.empty(B * ws.size + 1, dtype=torch.float32, device="cuda")
+    buf_g = torch.empty(B * ws.size + 1, dtype=torch.float32, device="cuda")
+    c_off = buf_c[1:].view(B, ws.size)
+    g_off = buf_g[1:].view(B, ws.size)
+    assert c_off.data_ptr() % 16 == 4 and c_off.is_contiguous()
+    g_off.copy_(torch.from_numpy(G))
+    S.sig_forward(ws, xp, out=c_off)
+    gp_off = S.sig_backward(ws, xp, c_off, g_off)
+    c = S.sig_forward(ws, xp)
+    gp = S.sig_backward(ws, xp, c, torch.from_numpy(G).cuda())
+    lengths = np.array([len(w) for w in W])
+    for n, e in O.level_errors(c_off.cpu().numpy(), c.cpu().numpy().astype(np.float64), lengths).items():
+        assert e <= 1e-5, (n, e)
+    assert O.grad_errors(gp_off.cpu().numpy(), gp.cpu().numpy().astype(np.float64)).max() <= 1e-4
+    for n, e in O.level_errors(c_off.cpu().numpy(), O.forward_words(X, W), lengths).items():
+        assert e <= FWD_TOL, (n, e)
+    assert O.grad_errors(gp_off.cpu().numpy(), O.backward_words(X, W, G.astype(np.float64))).max() <= BWD_TOL
+
+
 def test_chunked_and_unchunked_agree(monkeypatch):
     ws, W = build_both("truncated", 4, depth=6)
     X = make_path("time0", 11, 4, 128, 4)
