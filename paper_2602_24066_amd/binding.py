@@ -438,7 +438,7 @@ def sig_forward(ws: WordSet, path, out=None, workspace=None):
     if workspace is None:
         keep, wptr = _aligned_workspace(nbytes, path.device)
     else:
-        keep, wptr, nbytes = workspace, workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        keep, wptr, nbytes = None, workspace.data_ptr(), workspace.numel() * workspace.element_size()   # the caller's to keep alive
     with torch.cuda.device(path.device):
         stream = torch.cuda.current_stream().cuda_stream
         _check(lib.sig_forward(ws._h, ctypes.c_void_p(path.data_ptr()), B, P, ctypes.c_void_p(out.data_ptr()),
@@ -465,7 +465,7 @@ def sig_backward(ws: WordSet, path, coeffs, grad_coeffs, out=None, workspace=Non
     if workspace is None:
         keep, wptr = _aligned_workspace(nbytes, path.device)
     else:
-        keep, wptr, nbytes = workspace, workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        keep, wptr, nbytes = None, workspace.data_ptr(), workspace.numel() * workspace.element_size()   # the caller's to keep alive
     with torch.cuda.device(path.device):
         stream = torch.cuda.current_stream().cuda_stream
         _check(lib.sig_backward(ws._h, ctypes.c_void_p(path.data_ptr()), ctypes.c_void_p(coeffs.data_ptr()),

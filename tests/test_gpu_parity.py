@@ -326,6 +326,56 @@ def test_log_signature_gradient(monkeypatch, two_kernels):
     assert O.grad_errors(gp, num).max() <= BWD_TOL
 
 
+@pytest.mark.parametrize("kind,d,depth,B,L", [("truncated", 4, 6, 9, 70), ("truncated", 8, 5, 2, 24), ("words", 5, 4, 70, 19)])
+def test_step_captured_in_a_graph(kind, d, depth, B, L):
+    """Forward + backward recorded into a HIP graph (the library enqueues kernels only: no allocation, no memset) and
+    replayed on new inputs, with eager calls and synchronisations between the replays; every replay must reproduce
+    the eager results, and the first one the oracle's."""
+    import torch
+    from sig_workloads import random_prefix_closed_words
+    words = random_prefix_closed_words(1699, d, 200, depth) if kind == "words" else None
+    ws, W = build_both(kind, d, depth=depth, words=words)
+    lib = S.load_library()
+    X0 = make_path("iid", 1700, B, L, d)
+    G0 = make_grad_coeffs(1701, B, ws.size)
+    xp = torch.from_numpy(X0).cuda()
+    grad = torch.from_numpy(G0).cuda()
+    coeffs = torch.empty((B, ws.size), dtype=torch.float32, device="cuda")
+    gpath = torch.empty((B, L + 1, d), dtype=torch.float32, device="cuda")
+    wf = torch.empty(max(int(lib.sig_forward_workspace_bytes(ws._h, B, L + 1)), 256), dtype=torch.uint8, device="cuda")
+    wb = torch.empty(max(int(lib.sig_backward_workspace_bytes(ws._h, B, L + 1)), 256), dtype=torch.uint8, device="cuda")
+
+    def step():
+        S.sig_forward(ws, xp, out=coeffs, workspace=wf)
+        S.sig_backward(ws, xp, coeffs, grad, out=gpath, workspace=wb)
+
+    step()                                   # compiles / sets kernel attributes outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    lengths = np.array([len(w) for w in W])
+    for rep in range(3):
+        X = make_path("iid", 1710 + rep, B, L, d)
+        G = make_grad_coeffs(1720 + rep, B, ws.size)
+        xp.copy_(torch.from_numpy(X).cuda())
+        grad.copy_(torch.from_numpy(G).cuda())
+        coeffs.zero_()
+        gpath.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        c_graph, g_graph = coeffs.cpu().numpy(), gpath.cpu().numpy()
+        c_eager = S.sig_forward(ws, xp)
+        g_eager = S.sig_backward(ws, xp, c_eager, grad)
+        torch.cuda.synchronize()
+        assert np.array_equal(c_graph, c_eager.cpu().numpy()), f"replay {rep}: forward differs from the eager call"
+        assert O.grad_errors(g_graph, g_eager.cpu().numpy().astype(np.float64)).max() <= 1e-5, f"replay {rep}"
+        if rep == 0:
+            for n, e in O.level_errors(c_graph, O.forward_words(X, W), lengths).items():
+                assert e <= FWD_TOL, (n, e)
+            assert O.grad_errors(g_graph, O.backward_words(X, W, G.astype(np.float64))).max() <= BWD_TOL
+
+
 def test_one_point_paths_give_zero():
     import torch
     ws, W = build_both("truncated", 3, depth=3)
