@@ -320,9 +320,10 @@ def main():
             torch.cuda.synchronize()
             t2 = time.perf_counter()
             out["log_signature"] = {"workload": f"{wlh.name} shape, depth {wlh.depth}: {wsl.size} signature words for {lg.shape[1]} "
-                                                f"log-signature coordinates (full truncation: {st['ws'].size if args.workload == HEADLINE else '-'})",
+                                                f"log-signature coordinates",
+                                    "kernels": [wsl.kernel_name(False, wlh.B, wlh.L + 1), wsl.kernel_name(True, wlh.B, wlh.L + 1)],
                                     "fwd_ms": round((t1 - t0) * 100, 4), "bwd_ms": round((t2 - t1) * 100, 4),
-                                    "note": "host clock; first call compiles the specialised kernels for the word set"}
+                                    "note": "host clock, signature + tensor logarithm (forward) and their adjoints (backward)"}
         except Exception as e:
             out["log_signature"] = {"error": str(e)[:200]}
 

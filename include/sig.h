@@ -178,7 +178,8 @@ int    sig_backward(const sig_wordset* ws, const float* path, const float* coeff
  * Coordinates: for every Lyndon word w of length <= depth, the coefficient of w in the tensor logarithm of the
  * signature (the Lyndon-word coordinates the paper takes from its reference on efficient Lie bases).  Only the
  * coefficients of the factors of Lyndon words are needed: sig_wordset_build_logsig builds the set "every word shorter
- * than depth + the Lyndon words of length depth"; user_index lists the columns of the Lyndon words (by length, then
+ * than depth + the Lyndon words of length depth" (the full truncation instead for the (d, depth) pairs that have
+ * a kernel of their own for it: faster, and a superset); user_index lists the columns of the Lyndon words (by length, then
  * lexicographic), sig_wordset_n_lyndon their number.  Pipeline: sig_forward on that set, then sig_logsig_forward
  * (coeffs [B, |W|] -> logsig [B, n_lyndon]); backward: sig_logsig_backward (grad_logsig -> grad_coeffs [B, |W|],
  * overwritten), then sig_backward.  All pointers device, float32; the word set must be uploaded. */

@@ -580,6 +580,9 @@ static void lyndon_words_of_length(int d, int n, std::vector<int32_t>& letters, 
     }
 }
 
+bool trunc_forward_available(int d, int depth);      // kernels_trunc.hip
+bool trunc_backward_available(int d, int depth);
+
 int build_logsig(int d, int depth, WordSet** out)
 {
     if (!out || check_d(d) != SIG_OK || depth < 1) return SIG_EINVAL;
@@ -605,10 +608,14 @@ int build_logsig(int d, int depth, WordSet** out)
                 w[(size_t)k] += 1;
             }
         }
+        // Shapes with a kernel for the full truncation take that set instead (it holds every factor too, and its
+        // kernels are several times faster than the specialised ones on the reduced set).
         WordSet* ws = nullptr;
-        int rc = build_list(d, letters.data(), offsets.data(), (int64_t)offsets.size() - 1, &ws);
+        const bool full = trunc_forward_available(d, depth) && trunc_backward_available(d, depth);
+        int rc = full ? build_truncated(d, depth, &ws)
+                      : build_list(d, letters.data(), offsets.data(), (int64_t)offsets.size() - 1, &ws);
         if (rc != SIG_OK) return rc;
-        ws->user_index.resize((size_t)n_lyn);            // only the Lyndon words are "requested"
+        ws->user_index.assign((size_t)n_lyn, 0);         // only the Lyndon words are "requested"; filled below
         // sub-word table: walk the trie by the parent/letter tables through a (parent, letter) -> child map
         std::unordered_map<uint64_t, int32_t> child;
         child.reserve((size_t)ws->size() * 2);
@@ -631,6 +638,7 @@ int build_logsig(int d, int depth, WordSet** out)
                     ws->lyn_sub[(size_t)k * (size_t)ws->lyn_stride + (size_t)i * (size_t)(depth + 1) + (size_t)j] = cur;
                 }
             }
+            ws->user_index[(size_t)k] = ws->lyn_sub[(size_t)k * (size_t)ws->lyn_stride + (size_t)n];   // the word itself
         }
         // inverse table (counting sort by sub-word)
         ws->lyn_pairs = depth * (depth + 1) / 2;

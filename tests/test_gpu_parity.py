@@ -275,7 +275,7 @@ def test_windows(case):
     assert O.grad_errors(gp, gref).max() <= BWD_TOL
 
 
-@pytest.mark.parametrize("d,depth,B,L", [(2, 6, 7, 20), (3, 4, 66, 15), (4, 5, 3, 9), (5, 1, 2, 4)])
+@pytest.mark.parametrize("d,depth,B,L", [(2, 6, 7, 20), (3, 4, 66, 15), (4, 5, 3, 9), (5, 1, 2, 4), (4, 6, 5, 33)])
 def test_log_signature(d, depth, B, L):
     """Log-signature in Lyndon-word coordinates: signature on the reduced word set, then the tensor logarithm word by
     word, against the oracle's dense tensor logarithm of the full truncated signature."""

@@ -372,6 +372,18 @@ def test_logsig_word_set_bit_exact(d, depth):
     assert int(S.load_library().sig_wordset_n_lyndon(S.sig_wordset_build_truncated(2, 3)._h)) == 0
 
 
+def test_logsig_word_set_on_a_shape_with_a_truncated_kernel():
+    """(4, 6) has kernels for the full truncation: the log-signature set is that truncation, the Lyndon words are
+    located in it."""
+    ws = S.sig_wordset_build_logsig(4, 6)
+    W = O.truncated_words(4, 6)
+    assert ws.size == len(W) == 5460
+    lyn = O.lyndon_words(4, 6)
+    assert int(S.load_library().sig_wordset_n_lyndon(ws._h)) == len(lyn) == 964
+    assert [W[i] for i in ws.user_index] == lyn
+    assert ws.kernel_name(False, 256, 256) == "trunc_tails_fwd_kernel"
+
+
 # ---- which kernel a batch would launch (host logic only: no device call is made) ---------------------------
 def test_kernel_selection_for_full_truncations(monkeypatch):
     for k in ("SIG_FWD_TAILS", "SIG_BWD_TAILS", "SIG_CHUNKS", "SIG_NO_JIT"):
