@@ -1014,14 +1014,17 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
 
 // ---------------------------------------------------------------------------------------------------------
 // Backward with one wavefront per row for d = 4: a lane holds a word of length N - 3 (64 of them) and, in
-// registers, its D children of length N - 2 ("tails", letter = register index, the same in every lane); the two
-// levels below every tail run on the matrix cores as in trunc_mfma_bwd_kernel.  Compared with four wavefronts per
-// row that each hold one tail per lane, the chain above the tails is computed once instead of four times and
-// the four tails are independent instruction streams for the lone wavefront; rows are (path, time chunk) pairs,
-// so the launcher cuts short batches into chunks to fill the chip.  No other wavefront writes the gradient of
-// this row's segments: the tile is flushed with plain stores.
+// registers, its D children of length N - 2 ("tails", letter = register index, the same in every lane) with the
+// D children of each ("slice words") and the gradients of the D leaves below each of those.  Everything below a
+// tail is in the tail's lane and every letter there is the same in all lanes, so the two lower levels are plain
+// multiply-adds with lane-uniform increments: the backward walk never reconstructs the leaf coefficients, and with
+// D values per tail the slice level gains nothing from the matrix cores (an earlier form that kept it in the
+// lane layout of trunc_mfma_bwd_kernel paid for transposes between the two layouts and ran 15 % slower).  Compared
+// with four wavefronts per row that each hold one tail per lane, the chain above the tails is computed once
+// instead of four times; rows are (path, time chunk) pairs, so the launcher cuts short batches into chunks to fill
+// the chip.  No other wavefront writes the gradient of this row's segments: the tile is flushed with plain stores.
 // CW = 0: rows are (path, chunk) pairs whose start signature and adjoint come from global arrays; every wavefront
-// of a workgroup is an independent row.  CW = 2 or 4 ("fused"): a workgroup is one path and its CW wavefronts are
+// of a workgroup is an independent row.  CW = 2, 4 or 8 ("fused"): a workgroup is one path and its CW wavefronts are
 // the CW chunks of it; the chunk signatures, their products and the adjoints at the chunk boundaries are formed inside
 // the kernel and exchanged through LDS, so that nothing but path, terminal signature and gradient is read from HBM.
 template <int D, int N, int T, int CW>
@@ -1036,10 +1039,10 @@ struct TailsLds {
     // the chunk signatures and their products are kept up to length N - 1: the backward walk never reads the
     // coefficients of the longest words, and their adjoints are the gradient itself
     static constexpr int W1 = level_start(D, N);
-    // E, Ec of one wavefront, and for the chain rule the increment gradients of the first and of the last segment of
-    // the row (2 D floats) and of the tile walked before (T D floats)
-    static constexpr int TILE = T * 2 * D + T * D * NC + 2 * D + T * D;
-    static constexpr int OFF_CG = T * 2 * D + T * D * NC;
+    // scaled increments Ec of one wavefront, and for the chain rule the increment gradients of the first and of the
+    // last segment of the row (2 D floats) and of the tile walked before (T D floats)
+    static constexpr int TILE = T * D * NC + 2 * D + T * D;
+    static constexpr int OFF_CG = T * D * NC;
     static constexpr int RED = T * D + NSRC * T * kWave;                     // gt, Vb of one wavefront
     // fused: area A holds first the signature buffers and a copy of the gradient row of the path, later the
     // reduction regions
@@ -1174,8 +1177,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
         if (row >= B * C) return;                     // no workgroup barriers in this mode
     }
     float* const smem = (float*)bwd_smem;
-    float (*E)[2][D] = (float (*)[2][D])(LY::tile(smem, wib));            // wave-private
-    float (*Ec)[D][NC] = (float (*)[D][NC])(LY::tile(smem, wib) + T * 2 * D);
+    float (*Ec)[D][NC] = (float (*)[D][NC])(LY::tile(smem, wib));         // wave-private
     float* const cg = LY::tile(smem, wib) + LY::OFF_CG;                   // chain rule, see the flush below
     float* const pg = cg + 2 * D;
     float* gt = LY::red(smem, wib);                                       // fused: valid after the signature buffers
@@ -1198,8 +1200,8 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
     // ---- state
     float Sc[KL], Ac[KL];                  // per-lane chain: signature and adjoint (adjoint only in the owning lane)
     float St[TW], At[TW];                  // tails
-    v4f S1[TW], A1[TW];                    // slice level: children of the tails (child layout)
-    float An[TW][4][D];                    // leaf adjoints, node layout (lane = slice word), constant: the gradient;
+    v4f S1[TW], A1[TW];                    // slice level: the D children of every tail
+    float An[TW][D][D];                    // adjoints of the D leaves below every slice word, constant: the gradient;
                                            // the coefficients of the leaves are never needed
 
     float dxn[EPL];
@@ -1223,15 +1225,11 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
 #pragma unroll
                 for (int t = 0; t < N; ++t) {
                     const float v = dxn[q] * inv1(t);
-                    if (t < 2) E[e / D][t][e % D] = v;
                     Ec[e / D][e % D][t] = v;
                 }
             }
         }
     };
-    const v4f zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-    // matrix-core B operand: lanes 0..15 carry dX^{(lane % 4)}, lanes 16..31 dX^{(lane % 4)} / 2
-    const int offB = lane < 32 ? (lane / 16) * D + (lane & 3) : 0;
 
     // ---- initial state.  sig(n, i): coefficient of the word (length n, index i) the row starts from;
     // adj(n, i, sub, share): its adjoint (length < N), where `share` consecutive lanes hold the same word.
@@ -1247,11 +1245,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
             const int i = ii;
             St[ii] = sig(K, lane * D + i);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                // slice word of register r in this lane: child (letter lane % 4) of tail i of lane 4 blk + r
-                const int ph = (((lane & ~3) + r) * D + i) * D + (lane & 3);
-                S1[ii][r] = sig(N - 1, ph);
-            }
+            for (int j = 0; j < D; ++j) S1[ii][j] = sig(N - 1, (lane * D + i) * D + j);
         }
     };
     auto load_adjoint = [&](auto&& adj) {
@@ -1268,19 +1262,16 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
             const int i = ii;
             At[ii] = adj(K, lane * D + i, 0, 1);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) A1[ii][r] = adj(N - 1, (((lane & ~3) + r) * D + i) * D + (lane & 3), 0, 1);
+            for (int j = 0; j < D; ++j) A1[ii][j] = adj(N - 1, (lane * D + i) * D + j, 0, 1);
         }
     };
     // leaf adjoints are the gradient itself at every chunk boundary
 #pragma unroll
     for (int ii = 0; ii < TW; ++ii)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int i = ii;
-            const int ph = (((lane & ~3) + r) * D + i) * D + (lane & 3);
+        for (int j = 0; j < D; ++j)
 #pragma unroll
-            for (int j = 0; j < D; ++j) An[ii][r][j] = gr[level_start(D, N) + ph * D + j];
-        }
+            for (int jj = 0; jj < D; ++jj) An[ii][j][jj] = gr[level_start(D, N) + ((lane * D + ii) * D + j) * D + jj];
 
     if constexpr (CW == 0) {
         load_signature([&](int n, int i) { return cf[level_start(D, n) + i]; });
@@ -1302,8 +1293,6 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
                 fetch((n + 1) * T);                    // beyond the chunk: zeros
 #pragma unroll 2
                 for (int tt = 0; tt < T; ++tt) {
-                    const float* Et = &E[tt][0][0];
-                    const float bs = Et[offB];
                     float a[KL + 1][N + 2];
 #pragma unroll
                     for (int t = 0; t < N + 2; ++t) a[0][t] = 1.0f;
@@ -1319,7 +1308,8 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
                         const float* et = &Ec[tt][ii][0];
                         const float a1 = fmaf(et[1], a[KL][2], St[ii]);
                         St[ii] = fmaf(et[0], a[KL][1], St[ii]);
-                        S1[ii] = mfma4(a1, bs, S1[ii], 0);
+#pragma unroll
+                        for (int j = 0; j < D; ++j) S1[ii][j] = fmaf(Ec[tt][j][0], a1, S1[ii][j]);
                     }
                 }
             }
@@ -1336,9 +1326,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
             for (int ii = 0; ii < TW; ++ii) {
                 const int i = ii;
                 out[level_start(D, K) + lane * D + i] = St[ii];
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    out[level_start(D, N - 1) + (((lane & ~3) + r) * D + i) * D + (lane & 3)] = S1[ii][r];
+                *(v4f*)(out + level_start(D, N - 1) + (lane * D + i) * D) = S1[ii];
             }
         }
         __syncthreads();
@@ -1378,11 +1366,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
         __syncthreads();                               // the buffers are dead: their space takes gt / Vb from here on
     }
 
-    float unit[4];                                     // unit[r] = 1 in the lanes 4 blk + r
-#pragma unroll
-    for (int r = 0; r < 4; ++r) unit[r] = (lane & 3) == r ? 1.0f : 0.0f;
     auto step = [&](int row_t) {
-        const float* Et = &E[row_t][0][0];
         float ec[KL][NC];
 #pragma unroll
         for (int k = 0; k < KL; ++k) {
@@ -1390,14 +1374,11 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
 #pragma unroll
             for (int t = 0; t <= N - (k + 1); ++t) ec[k][t] = src[t];
         }
-        float e0[D], et[TW][3];                       // dX^{(j)}, and dX^{(i)} / (t + 1) of the own tails: lane-uniform
+        float eu[D][3];                               // dX^{(j)} / (t + 1), t = 0..2: the same in every lane
 #pragma unroll
-        for (int j = 0; j < D; ++j) e0[j] = Ec[row_t][j][0];
+        for (int j = 0; j < D; ++j)
 #pragma unroll
-        for (int ii = 0; ii < TW; ++ii)
-#pragma unroll
-            for (int t = 0; t < 3; ++t) et[ii][t] = Ec[row_t][ii][t];
-        const float bs = Et[offB], nbs = -bs;
+            for (int t = 0; t < 3; ++t) eu[j][t] = Ec[row_t][j][t];
 
         // 1. reconstruction with -dX, 2. accumulators with +dX (per-lane chain)
         float am[KL + 1][N + 2], ap[KL + 1][N + 2];
@@ -1416,57 +1397,45 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
 #pragma unroll
         for (int j = 0; j < D; ++j) y[j] = 0.0f;
         float* vb = Vb + row_t * kWave + lane;
+        // Everything below a tail lives in the tail's lane and every letter is the same in all lanes, so the two
+        // levels are plain multiply-adds with lane-uniform increments (the matrix cores bring nothing here: the
+        // leaf coefficients are not reconstructed, and the slice level is D values per tail).
 #pragma unroll
         for (int i = 0; i < TW; ++i) {
-            // tail i: reconstruction
-            const float am1 = fmaf(-et[i][1], am[KL][2], St[i]);
-            St[i] = fmaf(-et[i][0], am[KL][1], St[i]);
-            S1[i] = mfma4(am1, nbs, S1[i], 0);
-            // accumulators
-            const float ap1 = fmaf(et[i][1], ap[KL][2], St[i]);
-            const float ap2 = fmaf(et[i][2], ap[KL][3], St[i]);
-            const v4f Gp = mfma4(ap2, bs, S1[i], 1);                          // A+[1] of the slice words
-            // 3a. leaves: the leaf (slice word) j has the gradient as its adjoint; its letter is j in every lane.
-            // 3b. slice words.  Register r of a lane holds a child of the tail of lane 4 blk + r: their adjoints and
-            // what they push up are brought to the tail's lane by four accumulated products with unit columns
-            // (register j of T1 / T2 becomes the value of child j of the own tail), where the tail's accumulators
-            // and dX per child letter are at hand.
-            v4f T1 = zero4, T2 = zero4;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                float h = 0.0f;
-#pragma unroll
-                for (int j = 0; j < D; ++j) {
-                    h = fmaf(e0[j], An[i][r][j], h);                           // gbar[1] of the slice word
-                    y[j] = fmaf(An[i][r][j], Gp[r], y[j]);
-                }
-                const float q0 = A1[i][r];
-                T1 = __builtin_amdgcn_mfma_f32_4x4x1f32(q0, unit[r], T1, 0, 0, 0);
-                T2 = __builtin_amdgcn_mfma_f32_4x4x1f32(h, unit[r], T2, 0, 0, 0);
-                A1[i][r] = q0 + h;
-            }
-            // 3c. the tail word itself: gbar[0] = its adjoint, gbar[1], gbar[2] pushed up from its children
-            const float g0 = At[i];
+            // tail i and its children: reconstruction, then the accumulators
+            const float am1 = fmaf(-eu[i][1], am[KL][2], St[i]);
+            St[i] = fmaf(-eu[i][0], am[KL][1], St[i]);
+            const float ap1 = fmaf(eu[i][1], ap[KL][2], St[i]);
+            const float ap2 = fmaf(eu[i][2], ap[KL][3], St[i]);
             const float hp2 = 0.5f * ap2;
-            float g1 = e0[0] * T1[0], g2 = e0[0] * T2[0];
-            y[0] = fmaf(T1[0], ap1, y[0]);
-            y[0] = fmaf(T2[0], hp2, y[0]);
+            const float g0 = At[i];
+            float g1 = 0.0f, g2 = 0.0f;
 #pragma unroll
-            for (int j = 1; j < D; ++j) {
-                g1 = fmaf(e0[j], T1[j], g1);
-                g2 = fmaf(e0[j], T2[j], g2);
-                y[j] = fmaf(T1[j], ap1, y[j]);
-                y[j] = fmaf(T2[j], hp2, y[j]);
+            for (int j = 0; j < D; ++j) {
+                S1[i][j] = fmaf(-eu[j][0], am1, S1[i][j]);
+                const float Gp = fmaf(eu[j][1], ap2, S1[i][j]);               // A+[1] of the slice word
+                float h = 0.0f;                                                // its gbar[1], from the leaves
+#pragma unroll
+                for (int jj = 0; jj < D; ++jj) {
+                    h = fmaf(eu[jj][0], An[i][j][jj], h);
+                    y[jj] = fmaf(An[i][j][jj], Gp, y[jj]);                     // leaf letter jj
+                }
+                const float q0 = A1[i][j];
+                A1[i][j] = q0 + h;
+                y[j] = fmaf(q0, ap1, y[j]);                                    // slice letter j
+                y[j] = fmaf(h, hp2, y[j]);
+                g1 = fmaf(eu[j][0], q0, g1);                                   // what the slice word pushes up
+                g2 = fmaf(eu[j][1], h, g2);
             }
-            g2 *= 0.5f;
+            // the tail word itself: gbar[0] = its adjoint, gbar[1], gbar[2] pushed up from its children
             At[i] = g0 + g1 + g2;
             float gct = g0 * ap[KL][1];
             gct = fmaf(g1 * inv1(1), ap[KL][2], gct);
             gct = fmaf(g2 * inv1(2), ap[KL][3], gct);
             y[i] += gct;
-            gbL[1] = fmaf(et[i][0], g0, gbL[1]);
-            gbL[2] = fmaf(et[i][1], g1, gbL[2]);
-            gbL[3] = fmaf(et[i][2], g2, gbL[3]);
+            gbL[1] = fmaf(eu[i][0], g0, gbL[1]);
+            gbL[2] = fmaf(eu[i][1], g1, gbL[2]);
+            gbL[3] = fmaf(eu[i][2], g2, gbL[3]);
         }
         // 3d. per-lane chain.  The scaled increments of the chain letters are read from LDS a second time (through
         // an opaque copy of the letter, so that the two reads are not merged): keeping them in registers across the
