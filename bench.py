@@ -123,9 +123,10 @@ def time_steps(S, torch, st, steps, warmup):
 def roofline_entry(flops, ms, kernel=""):
     """Algorithmic flops per launch over the measured kernel duration.  The cascade kernels for full truncations issue
     most of their multiply-adds as fp32 matrix-core instructions (dense fp32 MFMA peak = FP32 vector peak = 157.3
-    TFLOP/s); the d = 4 backward kernel, the run-time specialised and the table-driven kernels use the vector ALU only."""
+    TFLOP/s); the d = 4 and d = 8 backward kernels, the run-time specialised and the table-driven kernels use the vector
+    ALU only."""
     ach = flops / (ms * 1e-3) / 1e12
-    on_matrix_cores = kernel.startswith("trunc_") and not kernel.startswith("trunc_tails_bwd")
+    on_matrix_cores = kernel.startswith("trunc_") and not kernel.startswith(("trunc_tails_bwd", "trunc_node_bwd"))
     return {"bound": "mfma" if on_matrix_cores else "alu", "achieved": round(ach, 3),
             "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_FP32_VECTOR_TFLOPS, 4),
             "traffic": None}

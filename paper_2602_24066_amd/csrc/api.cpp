@@ -841,7 +841,7 @@ const char* sig_wordset_kernel_name(const sig_wordset* ws, int backward)
 {
     if (!ws || !W(ws)->kernels_supported) return "unsupported";
     if (!backward && use_trunc_forward(*W(ws), 1)) return "trunc_mfma_fwd_kernel";
-    if (backward && use_trunc_backward(*W(ws), 1)) return "trunc_mfma_bwd_kernel";
+    if (backward && use_trunc_backward(*W(ws), 1)) return sig::trunc_backward_kernel_name(W(ws)->d, W(ws)->depth);
     if (jit_enabled(*W(ws))) return backward ? "sig_bwd_jit" : "sig_fwd_jit";
     return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";
 }
@@ -863,7 +863,7 @@ const char* sig_kernel_name(const sig_wordset* ws, int backward, int64_t B, int6
         return trunc_forward_fused_chunks(w, B, n_points, nullptr) ? "trunc_tails_fwd_kernel" : "trunc_mfma_fwd_kernel";
     if (backward && use_trunc_backward(w, B)) {
         const BwdShape sh = trunc_backward_shape(w, B, n_points);
-        return sh.tails ? "trunc_tails_bwd_kernel" : "trunc_mfma_bwd_kernel";
+        return sh.tails ? "trunc_tails_bwd_kernel" : sig::trunc_backward_kernel_name(w.d, w.depth);
     }
     if (jit_enabled(w)) return backward ? "sig_bwd_jit" : "sig_fwd_jit";
     return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";

@@ -57,6 +57,7 @@ hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t
                          hipStream_t stream);
 hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
                           int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream);
+const char* trunc_backward_kernel_name(int d, int depth);   // of the kernel trunc_backward launches
 
 // d = 4: backward with one wavefront per row (a lane holds a word of length N - 3 and its four children); stores
 // the gradient of the increments instead of accumulating, so the rows must tile every path exactly

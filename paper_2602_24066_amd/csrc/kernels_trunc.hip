@@ -1067,10 +1067,12 @@ __device__ __forceinline__ void tile_reduce_uniform(const float* V, float* gt, i
 {
     static_assert(NS * T <= kWave, "one lane per (source, segment)");
     if (lane < NS * T) {
+        // the rows lie 256 bytes apart: every lane starts at another 16-byte piece of its row, or all of them would
+        // meet in the same four banks
         const v4f* row = (const v4f*)(V + lane * kWave);
-        v4f acc = row[0];
+        v4f acc = row[lane & 15];
 #pragma unroll
-        for (int i = 1; i < kWave / 4; ++i) acc += row[i];
+        for (int i = 1; i < kWave / 4; ++i) acc += row[(i + lane) & 15];
         gt[(lane % T) * D + first_letter + lane / T] += (acc[0] + acc[1]) + (acc[2] + acc[3]);
     }
 }
@@ -1542,6 +1544,236 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// Backward on the vector ALU alone, for truncations whose words of length N - 2 fill whole wavefronts with room in
+// the registers for two more levels: a lane holds a word u of length K = N - 2 (its chain of K letters per lane),
+// the coefficients and adjoints of its D children and the gradients of the D^2 leaves below them.  The letters
+// below u are the same in every lane, so the two lower levels are multiply-adds with lane-uniform increments and
+// their gradient contributions are D per-letter sums (the matrix-core form of these levels, trunc_mfma_bwd_kernel,
+// keeps the children in another lane layout and pays for the transposes: measured 20 % slower for d = 8).
+// D^K / 64 wavefronts share a (path, chunk) row: the increment gradients are accumulated into gdx (zeroed by the
+// caller) with floating-point atomics.
+template <int D, int N, int T>
+struct NodeLds {
+    static constexpr int K = N - 2;
+    static constexpr int NC = (N + 3) / 4 * 4;
+    static constexpr int NSRC = D + K;                 // one source of gradient values per letter, one per chain letter
+    static constexpr int OFF_GT = T * D * NC;
+    static constexpr int OFF_VB = OFF_GT + T * D;
+    static constexpr int PER_WAVE = OFF_VB + NSRC * T * kWave;
+    static_assert(OFF_GT % 4 == 0 && OFF_VB % 4 == 0 && PER_WAVE % 4 == 0, "16-byte alignment of the LDS regions");
+    static constexpr size_t BYTES = (size_t)kWavesPerBlock * PER_WAVE * sizeof(float);
+};
+
+template <int D, int N, int T>
+__global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
+    const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
+    int64_t P, int64_t C, int64_t Lc, float* gdx)
+{
+    static_assert((D & (D - 1)) == 0, "the gradient reduction takes letters as bit fields of the lane number");
+    constexpr int K = N - 2;
+    constexpr int WAVES = ipow(D, K) / kWave;          // wavefronts per row
+    static_assert(WAVES * kWave == ipow(D, K) && D * T <= kWave, "whole wavefronts; one lane per (letter, segment)");
+    constexpr int NC = (N + 3) / 4 * 4;
+    constexpr int EPL = (T * D + kWave - 1) / kWave;
+    constexpr int LB = ilog2(D);
+    using LY = NodeLds<D, N, T>;
+    extern __shared__ v4f bwd_smem[];
+
+    const int lane = threadIdx.x % kWave;
+    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // the same in every lane: scalar registers
+    const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
+    if (wave >= B * C * WAVES) return;
+    float* const lds = (float*)bwd_smem + wib * LY::PER_WAVE;            // wave-private
+    float (*Ec)[D][NC] = (float (*)[D][NC])lds;
+    float* gt = lds + LY::OFF_GT;
+    float* Vb = lds + LY::OFF_VB;
+    const int64_t row = wave / WAVES;
+    const int64_t b = row / C;
+    const int64_t seg0 = (row - b * C) * Lc;
+    const int p = (int)(wave % WAVES) * kWave + lane;  // the lane's word of length K
+    int letter[K];
+    {
+        int q = p;
+#pragma unroll
+        for (int k = K - 1; k >= 0; --k) { letter[k] = q % D; q /= D; }
+    }
+    const float* X = path + (b * P + seg0) * D;
+    const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
+    const int64_t nW = level_start(D, N) + ipow(D, N);
+    const float* cf = coeffs + row * nW;
+    const float* gr = grad + row * nW;
+
+    // ---- state: signature and adjoints at the end of the row
+    float Sc[K], Ac[K];                    // chain (a word shared by several lanes has its adjoint in the first of them)
+    float S1[D], A1[D];                    // children of u
+    float An[D][D];                        // gradients of the leaves: constant adjoints
+    {
+        int phi = 0;
+#pragma unroll
+        for (int k = 1; k <= K; ++k) {
+            phi = phi * D + letter[k - 1];
+            Sc[k - 1] = cf[level_start(D, k) + phi];
+            Ac[k - 1] = p % ipow(D, K - k) == 0 ? gr[level_start(D, k) + phi] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            S1[j] = cf[level_start(D, N - 1) + p * D + j];
+            A1[j] = gr[level_start(D, N - 1) + p * D + j];
+#pragma unroll
+            for (int jj = 0; jj < D; ++jj) An[j][jj] = gr[level_start(D, N) + (p * D + j) * D + jj];
+        }
+    }
+
+    float dxn[EPL];
+    auto fetch = [&](int64_t j0) {
+#pragma unroll
+        for (int q = 0; q < EPL; ++q) {
+            const int e = (lane + q * kWave) < T * D ? lane + q * kWave : T * D - 1;
+            int64_t jj = j0 + e / D;
+            const bool ok = jj >= 0 && jj < L;
+            jj = jj < 0 ? 0 : (jj < L ? jj : L - 1);
+            const int i = e % D;
+            const float x1 = X[(jj + 1) * D + i], x0 = X[jj * D + i];
+            dxn[q] = ok ? x1 - x0 : 0.0f;
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int q = 0; q < EPL; ++q) {
+            const int e = lane + q * kWave;
+            if (e < T * D) {
+#pragma unroll
+                for (int t = 0; t < N; ++t) Ec[e / D][e % D][t] = dxn[q] * inv1(t);
+            }
+        }
+    };
+
+    auto step = [&](int row_t) {
+        float ec[K][NC];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const float* src = &Ec[row_t][letter[k]][0];
+#pragma unroll
+            for (int t = 0; t <= N - (k + 1); ++t) ec[k][t] = src[t];
+        }
+        float eu[D][2];                               // dX^{(j)}, dX^{(j)} / 2: the same in every lane
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            eu[j][0] = Ec[row_t][j][0];
+            eu[j][1] = Ec[row_t][j][1];
+        }
+        // 1. reconstruction with -dX, 2. accumulators with +dX from the reconstructed signature
+        float am[K + 1][N + 2], ap[K + 1][N + 2];
+#pragma unroll
+        for (int t = 0; t < N + 2; ++t) am[0][t] = ap[0][t] = 1.0f;
+#pragma unroll
+        for (int k = 1; k <= K; ++k) {
+#pragma unroll
+            for (int t = 1; t <= N - k; ++t) am[k][t] = fmaf(-ec[k - 1][t], am[k - 1][t + 1], Sc[k - 1]);
+            Sc[k - 1] = fmaf(-ec[k - 1][0], am[k - 1][1], Sc[k - 1]);
+#pragma unroll
+            for (int t = 1; t <= N - k; ++t) ap[k][t] = fmaf(ec[k - 1][t], ap[k - 1][t + 1], Sc[k - 1]);
+        }
+        // 3. children and leaves: adjoint pushes and the gradient per letter
+        float y[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) y[j] = 0.0f;
+        const float hp2 = 0.5f * ap[K][2];
+        float g1 = 0.0f, g2 = 0.0f;
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            S1[j] = fmaf(-eu[j][0], am[K][1], S1[j]);
+            const float Gp = fmaf(eu[j][1], ap[K][2], S1[j]);                 // A+[1] of the child
+            float h = 0.0f;                                                    // its gbar[1], from the leaves
+#pragma unroll
+            for (int jj = 0; jj < D; ++jj) {
+                h = fmaf(eu[jj][0], An[j][jj], h);
+                y[jj] = fmaf(An[j][jj], Gp, y[jj]);                            // leaf letter jj
+            }
+            const float q0 = A1[j];
+            A1[j] = q0 + h;
+            y[j] = fmaf(q0, ap[K][1], y[j]);                                   // child letter j
+            y[j] = fmaf(h, hp2, y[j]);
+            g1 = fmaf(eu[j][0], q0, g1);                                       // what the child pushes up to u
+            g2 = fmaf(eu[j][1], h, g2);
+        }
+        // 4. chain
+        float gb[K + 1][N + 2];
+#pragma unroll
+        for (int k = 0; k <= K; ++k)
+#pragma unroll
+            for (int t = 0; t < N + 2; ++t) gb[k][t] = 0.0f;
+        gb[K][1] = g1;
+        gb[K][2] = g2;
+        float* vb = Vb + row_t * kWave + lane;
+#pragma unroll
+        for (int k = K; k >= 1; --k) {
+            gb[k][0] = Ac[k - 1];
+            float gc = 0.0f, asum = 0.0f;
+#pragma unroll
+            for (int t = 0; t <= N - k; ++t) {
+                const float q = gb[k][t];
+                asum += q;
+                gc = fmaf(q * inv1(t), ap[k - 1][t + 1], gc);
+                gb[k - 1][t + 1] = fmaf(ec[k - 1][t], q, gb[k - 1][t + 1]);
+            }
+            Ac[k - 1] = asum;
+            vb[(D + k - 1) * T * kWave] = gc;                                  // letter[k - 1]
+        }
+#pragma unroll
+        for (int j = 0; j < D; ++j) vb[j * T * kWave] = y[j];                  // letter j, every lane
+    };
+
+    const int64_t ntiles = (L + T - 1) / T;
+    for (int e = lane; e < T * D; e += kWave) gt[e] = 0.0f;
+    fetch((ntiles - 1) * T);
+    for (int64_t n = ntiles - 1; n >= 0; --n) {
+        wave_lds_fence();
+        stage();
+        wave_lds_fence();
+        fetch((n - 1) * T);                            // n = 0: out of range, zeros
+#pragma unroll 1
+        for (int tt = T - 1; tt >= 0; --tt) step(tt);
+        wave_lds_fence();
+        tile_reduce_uniform<D, T>(Vb, gt, D, lane, 0);     // the only writer of gt so far: plain read-modify-write
+        wave_lds_fence();
+        tile_reduce<(1 << LB) - 1, T>(Vb + (D + K - 1) * T * kWave, gt, D, lane, letter[K - 1]);
+        chain_tile_reduce<D, K, T, 0>(Vb + D * T * kWave, gt, lane, letter);
+        wave_lds_fence();
+        // flush: (segment, letter) is contiguous in gdx
+        for (int e = lane; e < T * D; e += kWave) {
+            const int64_t sg = n * T + e / D;
+            if (sg < L) unsafeAtomicAdd(gdx + (b * (P - 1) + seg0 + n * T) * D + e, gt[e]);
+            gt[e] = 0.0f;
+        }
+    }
+}
+
+template <int D, int N>
+hipError_t launch_trunc_node_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P, int64_t C,
+                                 int64_t Lc, float* gdx, hipStream_t stream)
+{
+    constexpr int T = 8;
+    using LY = NodeLds<D, N, T>;
+    static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
+    const int64_t waves = B * C * (ipow(D, N - 2) / kWave);
+    const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_node_bwd_kernel<D, N, T>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+    }
+    trunc_node_bwd_kernel<D, N, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C, Lc,
+                                                                                                  gdx);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // Forward in the same register layout, for batches too short to fill the chip with one wavefront per path: a
 // workgroup is one path, cut into CW time chunks; a chunk is shared by D / TW wavefronts that hold TW of the D tails
 // (and everything below them) each and all recompute the chain above the tails.  Every wavefront runs the
@@ -1873,12 +2105,17 @@ hipError_t trunc_forward_tails_fused(int d, int depth, const float* path, int64_
     return hipErrorInvalidValue;
 }
 
+const char* trunc_backward_kernel_name(int d, int depth)
+{
+    return (d == 16 && depth == 4) ? "trunc_mfma_bwd_kernel" : "trunc_node_bwd_kernel";
+}
+
 // gdx: [B, L, d] accumulation buffer, zeroed by the caller
 hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
                           int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
 {
-    if (d == 4 && depth == 6) return launch_trunc_mfma_bwd<4, 6, 1>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
-    if (d == 8 && depth == 5) return launch_trunc_mfma_bwd<8, 5, 2>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (d == 4 && depth == 6) return launch_trunc_node_bwd<4, 6>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (d == 8 && depth == 5) return launch_trunc_node_bwd<8, 5>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
     if (d == 16 && depth == 4) return launch_trunc_mfma_bwd<16, 4, 1>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
     return hipErrorInvalidValue;
 }

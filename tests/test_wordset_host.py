@@ -399,14 +399,15 @@ def test_kernel_selection_for_full_truncations(monkeypatch):
     monkeypatch.setenv("SIG_FWD_TAILS", "0")
     monkeypatch.setenv("SIG_BWD_TAILS", "0")
     assert ws46.kernel_name(False, 256, 256) == "trunc_mfma_fwd_kernel"
-    assert ws46.kernel_name(True, 256, 256) == "trunc_mfma_bwd_kernel"
+    assert ws46.kernel_name(True, 256, 256) == "trunc_node_bwd_kernel"
     monkeypatch.delenv("SIG_FWD_TAILS")
     monkeypatch.delenv("SIG_BWD_TAILS")
     monkeypatch.setenv("SIG_CHUNKS", "4")                                       # asks for chunk arrays in HBM
     assert ws46.kernel_name(False, 256, 256) == "trunc_mfma_fwd_kernel"
     monkeypatch.delenv("SIG_CHUNKS")
     # the other instantiated shapes, and a truncation without one
-    assert S.sig_wordset_build_truncated(8, 5).kernel_name(True, 128, 1025) == "trunc_mfma_bwd_kernel"
+    assert S.sig_wordset_build_truncated(8, 5).kernel_name(True, 128, 1025) == "trunc_node_bwd_kernel"
+    assert S.sig_wordset_build_truncated(16, 4).kernel_name(True, 64, 4097) == "trunc_mfma_bwd_kernel"
     assert S.sig_wordset_build_truncated(16, 4).kernel_name(False, 64, 4097) == "trunc_mfma_fwd_kernel"
     assert S.sig_wordset_build_truncated(3, 4).kernel_name(False, 64, 65) == "sig_fwd_jit"
     # batches beyond the row limit of the truncated kernels take the specialised ones
