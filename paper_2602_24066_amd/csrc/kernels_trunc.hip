@@ -1732,7 +1732,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
         stage();
         wave_lds_fence();
         fetch((n - 1) * T);                            // n = 0: out of range, zeros
-#pragma unroll 1
+#pragma unroll 2
         for (int tt = T - 1; tt >= 0; --tt) step(tt);
         wave_lds_fence();
         tile_reduce_uniform<D, T>(Vb, gt, D, lane, 0);     // the only writer of gt so far: plain read-modify-write
