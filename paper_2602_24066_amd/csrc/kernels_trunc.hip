@@ -576,23 +576,23 @@ __device__ __forceinline__ void chain_tile_reduce(const float* Vsrc, float* gt, 
     }
 }
 
-// LDS of one wavefront of the backward kernel, in floats.  GEMM: the leaf level (adjoints constant in time) is
+// LDS of one wavefront of the backward kernel for d = 16, in floats.  The leaf level (adjoints constant in time) is
 // handled by time-batched matrix products over a tile of 16 segments, which need the slice-level values of the
 // tile in LDS (HA).
 template <int D, int N, int WQ, int T>
 struct BwdLds {
     using G = MGeo<D, N, N - 2, WQ>;
-    static constexpr bool GEMM = G::WIDE;
+    static_assert(G::WIDE, "sixteen letters: the leaves of a slice word fill a 16x16 matrix instruction");
     static constexpr int NC = (N + 3) / 4 * 4;
     static constexpr int NSV = WQ * 4;
-    static constexpr int NSRC = 1 + (G::WIDE ? WQ : G::Q) + (N - 2 - 1);
+    static constexpr int NSRC = 1 + WQ + (N - 2 - 1);
     static constexpr int SP = 68;                       // row stride of HA: 64 parents + 4 (keeps 16-byte alignment)
     static constexpr int OFF_E = 0;
     static constexpr int OFF_EC = OFF_E + T * 2 * D;
     static constexpr int OFF_GT = OFF_EC + T * D * NC;
     static constexpr int OFF_VB = OFF_GT + T * D;
     static constexpr int OFF_HA = OFF_VB + NSRC * T * kWave;
-    static constexpr int PER_WAVE = OFF_HA + (GEMM ? NSV * T * SP : 0);
+    static constexpr int PER_WAVE = OFF_HA + NSV * T * SP;
     static_assert(OFF_EC % 4 == 0 && OFF_GT % 4 == 0 && OFF_VB % 4 == 0 && OFF_HA % 4 == 0 && PER_WAVE % 4 == 0,
                   "16-byte alignment of the LDS regions");
     static constexpr size_t BYTES = (size_t)kWavesPerBlock * PER_WAVE * sizeof(float);
@@ -606,19 +606,15 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     static_assert((D & (D - 1)) == 0, "the gradient reduction takes letters as bit fields of the lane number");
     constexpr int K = N - 2;
     using G = MGeo<D, N, K, WQ>;
-    constexpr int Q = G::Q;
-    constexpr bool WIDE = G::WIDE;
+    static_assert(G::WIDE, "sixteen letters; narrower alphabets take trunc_node_bwd_kernel");
     constexpr int NBS = G::NBS;                       // slice combinations: index t * WQ + g, t in {0, 1}
-    constexpr int NBU = G::NBU;                       // leaf combinations: WIDE 1, else Q
     constexpr int NC = (N + 3) / 4 * 4;
     constexpr int NSV = WQ * 4;                       // slice word vectors
-    constexpr int NL4 = WIDE ? 1 : NSV * Q;           // leaf 4-vectors
-    constexpr int NL16 = WIDE ? NSV : 1;              // leaf 16-vectors
     constexpr int EPL = (T * D + kWave - 1) / kWave;
-    constexpr int NSRC0 = 1 + (WIDE ? WQ : Q);        // sources before the earlier chain letters
+    constexpr int NSRC0 = 1 + WQ;                     // sources before the earlier chain letters
     constexpr int LB = ilog2(D);
     using LY = BwdLds<D, N, WQ, T>;
-    static_assert(!LY::GEMM || T == 16, "the time-batched leaf products take 16 segments per matrix instruction");
+    static_assert(T == 16, "the time-batched leaf products take 16 segments per matrix instruction");
     extern __shared__ v4f bwd_smem[];
 
     const int lane = threadIdx.x % kWave;
@@ -630,8 +626,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     float (*Ec)[D][NC] = (float (*)[D][NC])(lds + LY::OFF_EC);
     float* gt = lds + LY::OFF_GT;
     float* Vb = lds + LY::OFF_VB;
-    float* HA = lds + LY::OFF_HA;                                       // [NSV][T][SP], GEMM only
-    constexpr bool GEMM = LY::GEMM;
+    float* HA = lds + LY::OFF_HA;                                       // [NSV][T][SP]
     constexpr int SP = LY::SP;
     constexpr int KS = D / 4;
     // row = (path, chunk): walks the segments [c Lc, min((c + 1) Lc, P - 1)) of path b backwards, starting from
@@ -655,30 +650,22 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     const float* cf = coeffs + row * nW;
     const float* gr = grad + row * nW;
 
-    int offS[NBS], offU[NBU];
+    int offS[NBS];
 #pragma unroll
     for (int r = 0; r < NBS; ++r) {
         const int c = 4 * r + lane / 16;
         offS[r] = c < 2 * WQ ? (c / WQ) * D + 4 * (g0 + c % WQ) + (lane & 3) : 0;
     }
-#pragma unroll
-    for (int r = 0; r < NBU; ++r) {
-        const int c = 4 * r + lane / 16;
-        if constexpr (WIDE) offU[r] = c < 1 ? (lane & 15) : 0;
-        else offU[r] = c < Q ? 4 * c + (lane & 3) : 0;
-    }
 
     // ---- state: terminal signature and adjoints
     float Sc[K], Ac[K];
     v4f S1[WQ], A1[WQ];
-    v4f S2[NL4], Ac4[NL4];            // leaves, child layout (4x4x1)
-    v16f S2w[NL16], Ac16[NL16];       // leaves, child layout (16x16x1)
-    float An[GEMM ? 1 : NSV][D];      // leaf adjoints, node layout
-    // GEMM: leaf adjoints G[v][parent][letter] as A operands of the 16x16x4 matrix instruction (lane l supplies
-    // row l % 16, k = l / 16).  Ga: rows = parents 16 mb + l % 16, k = letters 4 ks + l / 16 (contraction over letters);
+    // The coefficients of the leaves are never needed (their adjoints are the gradient itself).  Leaf adjoints
+    // G[v][parent][letter] as A operands of the 16x16x4 matrix instruction (lane l supplies row l % 16, k = l / 16).
+    // Ga: rows = parents 16 mb + l % 16, k = letters 4 ks + l / 16 (contraction over letters);
     // Gt: rows = letters l % 16, k = parents 4 ks + l / 16 (contraction over parents).
-    float Ga[GEMM ? NSV : 1][4][KS];
-    float Gt[GEMM ? NSV : 1][16];
+    float Ga[NSV][4][KS];
+    float Gt[NSV][16];
     int phi = 0;
 #pragma unroll
     for (int k = 1; k <= K; ++k) {
@@ -695,38 +682,15 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             S1[g][r] = cf[level_start(D, N - 1) + ph];
             A1[g][r] = gr[level_start(D, N - 1) + ph];
             const int v = g * 4 + r;
-            if constexpr (GEMM) {
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
+            for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks)
-                        Ga[v][mb][ks] = gr[level_start(D, N) + __shfl(ph, 16 * mb + (lane & 15)) * D + 4 * ks + lane / 16];
+                for (int ks = 0; ks < KS; ++ks)
+                    Ga[v][mb][ks] = gr[level_start(D, N) + __shfl(ph, 16 * mb + (lane & 15)) * D + 4 * ks + lane / 16];
 #pragma unroll
-                for (int ks = 0; ks < 16; ++ks) {
-                    const int pw = __shfl(ph, 4 * ks + lane / 16);
-                    Gt[v][ks] = (lane & 15) < D ? gr[level_start(D, N) + pw * D + (lane & 15)] : 0.0f;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < D; ++j) An[v][j] = gr[level_start(D, N) + ph * D + j];
-            }
-            if constexpr (WIDE) {
-#pragma unroll
-                for (int rr = 0; rr < 16; ++rr) {
-                    const int src = 16 * (rr / 4) + 4 * (lane / 16) + (rr % 4);
-                    const int pl = __shfl(ph, src) * D + (lane & 15);
-                    S2w[v][rr] = cf[level_start(D, N) + pl];
-                    if constexpr (!GEMM) Ac16[v][rr] = gr[level_start(D, N) + pl];
-                }
-            } else {
-#pragma unroll
-                for (int q = 0; q < Q; ++q)
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) {
-                        const int pl = __shfl(ph, (lane & ~3) + rr) * D + 4 * q + (lane & 3);
-                        S2[v * Q + q][rr] = cf[level_start(D, N) + pl];
-                        Ac4[v * Q + q][rr] = gr[level_start(D, N) + pl];
-                    }
+            for (int ks = 0; ks < 16; ++ks) {
+                const int pw = __shfl(ph, 4 * ks + lane / 16);
+                Gt[v][ks] = (lane & 15) < D ? gr[level_start(D, N) + pw * D + (lane & 15)] : 0.0f;
             }
         }
 
@@ -758,9 +722,6 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         }
     };
     const v4f zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-    v16f zero16;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) zero16[q] = 0.0f;
     const float one = 1.0f;
 
     // A segment is processed in two phases.  recon: steps 1 and 2 of the list above (they only depend on the
@@ -772,7 +733,6 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         v4f Gp[WQ];
         v4f Pb1, Pb2;
         float b0v[WQ];
-        float dxu[GEMM ? 1 : D];
     };
     auto recon = [&](int row, Saved& sv) {
         const float* Et = &E[row][0][0];
@@ -782,17 +742,11 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
 #pragma unroll
             for (int t = 0; t <= N - (k + 1); ++t) sv.ec[k][t] = src[t];
         }
-        float bs[NBS], nbs[NBS], bu[NBU], nbu[NBU];
+        float bs[NBS], nbs[NBS];
 #pragma unroll
         for (int r = 0; r < NBS; ++r) { bs[r] = Et[offS[r]]; nbs[r] = -bs[r]; }
 #pragma unroll
-        for (int r = 0; r < NBU; ++r) { bu[r] = Et[offU[r]]; nbu[r] = -bu[r]; }
-#pragma unroll
         for (int g = 0; g < WQ; ++g) sv.b0v[g] = Et[4 * (g0 + g) + (lane & 3)];
-        if constexpr (!GEMM) {
-#pragma unroll
-            for (int j = 0; j < D; ++j) sv.dxu[j] = Et[j];
-        }
 
         // 1. reconstruction with -dX
         float am[K + 1][N + 2];
@@ -804,21 +758,8 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             for (int t = 1; t <= N - k; ++t) am[k][t] = fmaf(-sv.ec[k - 1][t], am[k - 1][t + 1], Sc[k - 1]);
             Sc[k - 1] = fmaf(-sv.ec[k - 1][0], am[k - 1][1], Sc[k - 1]);
         }
-        v4f Gm[WQ];
 #pragma unroll
-        for (int g = 0; g < WQ; ++g) {
-            Gm[g] = mfma4(am[K][2], nbs[(WQ + g) / 4], S1[g], (WQ + g) % 4);
-            S1[g] = mfma4(am[K][1], nbs[g / 4], S1[g], g % 4);
-        }
-#pragma unroll
-        for (int v = 0; v < NSV; ++v) {
-            if constexpr (WIDE) {
-                S2w[v] = mfma16(Gm[v / 4][v % 4], nbu[0], S2w[v], 0);
-            } else {
-#pragma unroll
-                for (int q = 0; q < Q; ++q) S2[v * Q + q] = mfma4(Gm[v / 4][v % 4], nbu[q / 4], S2[v * Q + q], q % 4);
-            }
-        }
+        for (int g = 0; g < WQ; ++g) S1[g] = mfma4(am[K][1], nbs[g / 4], S1[g], g % 4);
         // 2. accumulators with +dX from the reconstructed signature
 #pragma unroll
         for (int t = 0; t < N + 2; ++t) sv.ap[0][t] = 1.0f;
@@ -834,37 +775,14 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     };
 
     auto adjoint = [&](int row, const Saved& sv) {
-        // 3a. leaves
-        float gcl[WIDE ? 1 : Q];
-#pragma unroll
-        for (int q = 0; q < (WIDE ? 1 : Q); ++q) gcl[q] = 0.0f;
+        // 3a. leaves: gbar[1] of the slice word was computed for the whole tile before the segment loop; its slot
+        // takes A+_{N-1}[1] of the slice word for the product over parents after the loop
         v4f g1[WQ];
 #pragma unroll
         for (int v = 0; v < NSV; ++v) {
-            const float a = sv.Gp[v / 4][v % 4];         // A+_{N-1}[1] of the slice word in this lane
-            if constexpr (GEMM) {
-                // gbar[1] of the slice word was computed for the whole tile before the segment loop; its slot
-                // takes A+ for the product over parents after the loop
-                float* slot = HA + (v * T + row) * SP + lane;
-                g1[v / 4][v % 4] = *slot;
-                *slot = a;
-                continue;
-            }
-            float h = 0.0f;
-#pragma unroll
-            for (int j = 0; j < D; ++j) h = fmaf(sv.dxu[j], An[v][j], h);
-            g1[v / 4][v % 4] = h;                        // gbar[1] of the slice word
-            if constexpr (WIDE) {
-                const v16f Pb = __builtin_amdgcn_mfma_f32_16x16x1f32(a, one, zero16, 0, 0, 0);
-#pragma unroll
-                for (int rr = 0; rr < 16; ++rr) gcl[0] = fmaf(Ac16[v][rr], Pb[rr], gcl[0]);
-            } else {
-                const v4f Pb = __builtin_amdgcn_mfma_f32_4x4x1f32(a, one, zero4, 0, 0, 0);
-#pragma unroll
-                for (int q = 0; q < Q; ++q)
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) gcl[q] = fmaf(Ac4[v * Q + q][rr], Pb[rr], gcl[q]);
-            }
+            float* slot = HA + (v * T + row) * SP + lane;
+            g1[v / 4][v % 4] = *slot;
+            *slot = sv.Gp[v / 4][v % 4];
         }
         // 3b. slice words
         float gcs[WQ], M1[4], M2[4];
@@ -911,23 +829,9 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         //    Vb[source][segment][lane]; they are summed over lanes once per tile (tile_reduce), which keeps
         //    dependent cross-lane chains out of the segment loop.
         float* vb = Vb + row * kWave + lane;
-        {
-            float x = gck[K - 1];
-            if constexpr (WIDE) x += gcl[0];
-            vb[0] = x;                                            // source 0: letters = lane bits [0, LB)
-        }
-        if constexpr (!WIDE) {
+        vb[0] = gck[K - 1];                                       // source 0: letters = lane bits [0, LB)
 #pragma unroll
-            for (int q = 0; q < Q; ++q) {                         // sources 1..Q: letters 4 q + lane % 4
-                float y = gcl[q];
-#pragma unroll
-                for (int g = 0; g < WQ; ++g) y += (g0 + g == q) ? gcs[g] : 0.0f;
-                vb[(1 + q) * T * kWave] = y;
-            }
-        } else {
-#pragma unroll
-            for (int g = 0; g < WQ; ++g) vb[(1 + g) * T * kWave] = gcs[g];   // sources 1..WQ: letters 4 (g0 + g) + lane % 4
-        }
+        for (int g = 0; g < WQ; ++g) vb[(1 + g) * T * kWave] = gcs[g];   // sources 1..WQ: letters 4 (g0 + g) + lane % 4
 #pragma unroll
         for (int k = 0; k < K - 1; ++k) vb[(NSRC0 + k) * T * kWave] = gck[k];   // earlier chain letters
     };
@@ -940,7 +844,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         stage();
         wave_lds_fence();
         fetch((n - 1) * T);                            // n = 0: out of range, zeros
-        if constexpr (GEMM) {
+        {
             // gbar[1](slice word p, segment s) = sum_j dX_s^{(j)} G[p][j] for the 16 segments of the tile:
             // [64 parents x D letters] . [D letters x 16 segments] per slice vector; the result (row = parent
             // 4 (l / 16) + r of block mb, column = segment l % 16) goes to HA[v][segment][parent]
@@ -975,7 +879,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             adjoint(0, SB);
         }
         wave_lds_fence();
-        if constexpr (GEMM) {
+        {
             // dLoss/d dX_s^{(j)} += sum_p G[p][j] A+(p, s): [D letters x 64 parents] . [64 parents x 16 segments] per
             // slice vector; row = letter 4 (l / 16) + r, column = segment l % 16
             v4f acc[4] = {zero4, zero4, zero4, zero4};
@@ -994,13 +898,8 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             wave_lds_fence();
         }
         tile_reduce<(1 << LB) - 1, T>(Vb, gt, D, lane, letter[K - 1]);
-        if constexpr (!WIDE) {
 #pragma unroll
-            for (int q = 0; q < Q; ++q) tile_reduce<3, T>(Vb + (1 + q) * T * kWave, gt, D, lane, 4 * q + (lane & 3));
-        } else {
-#pragma unroll
-            for (int g = 0; g < WQ; ++g) tile_reduce<3, T>(Vb + (1 + g) * T * kWave, gt, D, lane, 4 * (g0 + g) + (lane & 3));
-        }
+        for (int g = 0; g < WQ; ++g) tile_reduce<3, T>(Vb + (1 + g) * T * kWave, gt, D, lane, 4 * (g0 + g) + (lane & 3));
         chain_tile_reduce<D, K, T, 0>(Vb + NSRC0 * T * kWave, gt, lane, letter);
         wave_lds_fence();
         // flush: (segment, letter) is contiguous in gdx
@@ -1997,7 +1896,7 @@ hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const f
                                  int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
 {
     using G = MGeo<D, N, N - 2, WQ>;
-    constexpr int T = G::WIDE ? 16 : 8;
+    constexpr int T = 16;
     using LY = BwdLds<D, N, WQ, T>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
     const int64_t waves = B * C * G::WAVES;
