@@ -18,6 +18,8 @@ SMALL = [
     ("truncated", dict(d=4, depth=6), 5, 17, "time0"),
     ("truncated", dict(d=8, depth=3), 129, 9, "iid"),
     ("truncated", dict(d=16, depth=3), 3, 40, "ar1"),
+    ("truncated", dict(d=8, depth=5), 3, 21, "scaled"),
+    ("truncated", dict(d=16, depth=4), 2, 19, "ar1"),
     # d = 1: a level is a single number (X_L - X_0)^n / n!; a path that returns towards its start cancels
     # it in fp32, so the one-letter case uses the monotone time channel (level n = 1/n!)
     ("truncated", dict(d=1, depth=6), 2, 12, "time0"),
