@@ -190,6 +190,43 @@ __global__ __launch_bounds__(256) void chunk_product_kernel(const float* __restr
     *(f4*)(out + b * out_stride + o) = quad_product(a + b * a_stride, bfac + b * b_stride, g, n, o - g.ls[n]);
 }
 
+// coefficient of one word (length n, index i inside the level) of a (x) b
+__device__ __forceinline__ float word_product(const float* a, const float* b, const Levels& g, int n, int i)
+{
+    float acc = a[g.ls[n] + i] + b[g.ls[n] + i];
+    for (int k = 1; k < n; ++k) {
+        const int sh = g.lb * (n - k);
+        acc = fmaf(a[g.ls[k] + (i >> sh)], b[g.ls[n - k] + (i & ((1 << sh) - 1))], acc);
+    }
+    return acc;
+}
+
+// out[b] = a[b] (x) bfac[b] (x) c[b] in one pass (three time chunks, the usual count for long paths): a quad of
+// (a (x) b) (x) c is the quad of a (x) b plus, for every cut, the coefficient of a (x) b at the shared prefix times
+// the suffix quad of c.  The prefix coefficients are recomputed per quad (a few multiply-adds on cached operands),
+// which saves the intermediate array and one launch.
+__global__ __launch_bounds__(256) void chunk_product3_kernel(const float* __restrict__ a, const float* __restrict__ bfac,
+                                                             const float* __restrict__ c, int64_t in_stride,
+                                                             float* __restrict__ out, int64_t out_stride, Levels g)
+{
+    const int64_t b = blockIdx.y;
+    const int o = 4 * (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (o >= g.W) return;
+    int n = 1;
+    while (o >= g.ls[n + 1]) ++n;
+    const int i = o - g.ls[n];
+    const float* pa = a + b * in_stride;
+    const float* pb = bfac + b * in_stride;
+    const float* pc = c + b * in_stride;
+    f4 acc = quad_product(pa, pb, g, n, i) + *(const f4*)(pc + g.ls[n] + i);
+    for (int l = 1; l < n; ++l) {
+        const int sh = g.lb * (n - l);
+        const float ab = word_product(pa, pb, g, l, i >> sh);
+        acc += ab * *(const f4*)(pc + g.ls[n - l] + (i & ((1 << sh) - 1)));
+    }
+    *(f4*)(out + b * out_stride + o) = acc;
+}
+
 // One workgroup per (path, chunk): Abar[b][c](u) = grad[b](u) + sum_{m >= 1} sum_{|v| = m} grad[b](u v) Q[b][c](v);
 // the last chunk's adjoint is grad itself.  The words of one length k are spread over the whole workgroup, with
 // blockDim / d^k threads (at most 64, at least 1) sharing the inner sums of a word; for a fixed m the terms of a
@@ -274,6 +311,10 @@ hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, c
         // forward with large signatures: one grid-wide product per chunk boundary
         const int64_t W = g.W;
         const dim3 grid((unsigned)((W / 4 + 255) / 256), (unsigned)B);
+        if (C == 3) {
+            chunk_product3_kernel<<<grid, 256, 0, stream>>>(Sc, Sc + W, Sc + 2 * (int64_t)W, (int64_t)C * W, coeffs_out, W, g);
+            return hipGetLastError();
+        }
         const float* acc = Sc;                       // S_1 of every path, row stride C W
         int64_t acc_stride = (int64_t)C * W;
         for (int s = 1; s < C; ++s) {
