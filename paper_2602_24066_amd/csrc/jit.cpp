@@ -210,10 +210,19 @@ void emit_backward_unit(std::ostringstream& o, const Plan& plan, int uidx, int D
     o << "__device__ __forceinline__ void bwd_unit_" << uidx
       << "(const float* __restrict__ dxg, long ntiles, long L, float* tile, float* gt_all, float* gdx, long b0, long B, int lane,\n"
          "     int wib, const float* __restrict__ cf, const float* __restrict__ gr)\n{\n";
+    // slots of words with children carry a coefficient; the others only an adjoint
+    std::vector<char> has_children((size_t)ud.n_slots, 0);
+    for (int q = 0, slot = 0; q < ud.n_ops; ++q) {
+        const Op op = decode(plan.ops[(size_t)(ud.op_off + q)]);
+        if (op.kind == OP_ENTER) has_children[(size_t)slot++] = 1;
+        else if (op.kind == OP_LEAF) ++slot;
+    }
     for (int r = 0; r < ud.n_slots; ++r) {
         const int32_t w = plan.slot_word[(size_t)(ud.slot_off + r)];
         const int32_t wi = w >= 0 ? w : ~w;
-        o << "    float s" << r << " = cf[" << wi << "], ab" << r << " = ";
+        o << "    float ";
+        if (has_children[(size_t)r]) o << "s" << r << " = cf[" << wi << "], ";
+        o << "ab" << r << " = ";
         if (w >= 0) o << "gr[" << wi << "];\n";
         else o << "0.0f;\n";
     }
@@ -255,11 +264,10 @@ void emit_backward_unit(std::ostringstream& o, const Plan& plan, int uidx, int D
             ++slot;
         } else if (op.kind == OP_LEAF) {
             const std::string s = "s" + std::to_string(slot), b = "ab" + std::to_string(slot);
+            // the coefficient of a word without children is not reconstructed: nothing reads it
             if (k == 1) {
-                o << "            " << s << " -= dx" << i << ";\n";
                 o << "            g" << i << " += " << b << ";\n";
             } else {
-                o << "            " << s << " = __builtin_fmaf(-dx" << i << ", m" << k - 1 << "_1, " << s << ");\n";
                 o << "            g" << i << " = __builtin_fmaf(" << b << ", p" << k - 1 << "_1, g" << i << ");\n";
                 o << "            q" << k - 1 << "_1 = __builtin_fmaf(dx" << i << ", " << b << ", q" << k - 1 << "_1);\n";
             }

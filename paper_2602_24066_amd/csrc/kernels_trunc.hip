@@ -1696,9 +1696,8 @@ struct TailsFwdLds {
 };
 
 template <int D, int N, int T, int CW, int TW>
-__global__ __launch_bounds__(kWave * CW * (D / TW)) void trunc_tails_fwd_kernel(const float* __restrict__ path, int64_t B,
-                                                                               int64_t P, int64_t Lc,
-                                                                               float* __restrict__ coeffs)
+__global__ __launch_bounds__(kWave * CW * (D / TW)) void trunc_tails_fwd_kernel(const float* __restrict__ path, int64_t P,
+                                                                               int64_t Lc, float* __restrict__ coeffs)
 {
     static_assert(D == 4, "one group of four letters");
     constexpr int K = N - 2;                          // length of the tail words
@@ -1862,7 +1861,7 @@ hipError_t launch_trunc_tails_fwd(const float* path, int64_t B, int64_t P, int64
             attr_set = true;
         }
     }
-    trunc_tails_fwd_kernel<D, N, T, CW, TW><<<(unsigned)B, kWave * LY::NWV, LY::BYTES, stream>>>(path, B, P, Lc, coeffs);
+    trunc_tails_fwd_kernel<D, N, T, CW, TW><<<(unsigned)B, kWave * LY::NWV, LY::BYTES, stream>>>(path, P, Lc, coeffs);
     return hipGetLastError();
 }
 
