@@ -202,6 +202,37 @@ def test_many_short_paths():
     check_parity(ws, W, "truncated", 6, X, G, sample=sample, what="B=66000")
 
 
+@pytest.mark.parametrize("d,depth,B", [(8, 5, 60000), (4, 6, 400000)])
+def test_more_than_2_to_the_31_coefficients(d, depth, B):
+    """Row offsets in 64 bits: 60,000 paths of the (8, 5) truncation are 2.25e9 coefficients (9 GB per array), and so
+    are 400,000 paths of the (4, 6) truncation, which the run-time specialised kernels serve (lanes = paths).
+    Sampled paths against the oracle, among them the row in which the element index passes 2^31 and the last one.
+    The cotangent is drawn on the device (a seeded input; 2e9 normals would take the host half a minute)."""
+    import torch
+    ws, W = build_both("truncated", d, depth=depth)
+    L = 2
+    assert B * ws.size > 2**31
+    X = make_path("iid", 43, B, L, d)
+    xp = torch.from_numpy(X).cuda()
+    gen = torch.Generator(device="cuda").manual_seed(44)
+    G = torch.randn((B, ws.size), device="cuda", dtype=torch.float32, generator=gen)
+    coeffs = S.sig_forward(ws, xp)
+    gp = S.sig_backward(ws, xp, coeffs, G)
+    torch.cuda.synchronize()
+    edge = 2**31 // ws.size
+    idx = np.array([0, 1, 4095, edge - 1, edge, edge + 1, B - 2, B - 1])
+    sel = torch.from_numpy(idx).cuda()
+    c, g, gg = coeffs[sel].cpu().numpy(), gp[sel].cpu().numpy(), G[sel].cpu().numpy()
+    del coeffs, G
+    Xs = np.ascontiguousarray(X[idx])
+    lengths = np.array([len(w) for w in W])
+    for n, e in O.level_errors(c, O.forward_dense(Xs, depth), lengths).items():
+        assert e <= FWD_TOL, (n, e)
+    gerr = O.grad_errors(g, O.backward_dense(Xs, depth, gg.astype(np.float64)))
+    assert gerr.max() <= BWD_TOL, gerr
+    assert torch.isfinite(gp).all()
+
+
 def test_graph_induced_word_set():
     edges = [(0, 1), (0, 2), (1, 3), (2, 3), (3, 4), (3, 5), (1, 5), (4, 5), (2, 4)]
     ws = S.sig_wordset_build_graph(6, edges, 5)
