@@ -277,6 +277,60 @@ hipError_t launch_jit_backward(sig::JitKernel& k, const sig::Plan& p, const floa
 }
 
 int bwd_tile_steps(int d) { return std::max(1, std::min(16, 32 / std::max(d, 1))); }
+
+// ---- full truncations without a register-resident kernel of their own: lanes = words -----------------------
+// Lanes = paths needs 64 paths per wavefront and a compilation that grows with the word set (minutes beyond a few
+// ten thousand words); lanes = words fills the wavefronts from a single path on and compiles in about a second per
+// shape.  Taken whenever the words of a path fill at least half a wavefront; SIG_LANES=0 switches it off, =1 takes
+// it for every shape it is defined for.
+bool use_lanes(const sig::WordSet& w, int64_t B)
+{
+    if (w.kind != 0 || !jit_enabled(w)) return false;
+    const char* e = std::getenv("SIG_LANES");
+    const int f = (e && e[0]) ? std::atoi(e) : -1;
+    if (f == 0) return false;
+    const sig::LanesShape s = sig::lanes_shape(w.d, w.depth);
+    if (!s.ok || B * s.waves > (int64_t)0x7fffffff) return false;
+    return f == 1 || s.lanes >= 32;
+}
+
+sig::JitKernel* ensure_lanes(const sig::WordSet& cw, int dir, bool load)
+{
+    sig::WordSet& w = const_cast<sig::WordSet&>(cw);     // the cache is logically mutable
+    std::lock_guard<std::mutex> lock(g_jit_mutex);
+    if (!w.lanes[dir]) w.lanes[dir] = new (std::nothrow) sig::JitKernel;
+    sig::JitKernel* k = w.lanes[dir];
+    if (!k) return nullptr;
+    if (!k->tried) {
+        k->tried = true;
+        try {
+            const sig::LanesShape s = sig::lanes_shape(w.d, w.depth);
+            k->nw = s.nwb;
+            k->tile = s.T;
+            (void)sig::jit_compile(sig::lanes_source(w.d, w.depth, s, dir != 0), dir ? "sig_bwd_lanes" : "sig_fwd_lanes", *k);
+        } catch (const std::bad_alloc&) { k->ok = false; }
+    }
+    if (!k->ok) return nullptr;
+    if (load && !k->fn && sig::jit_load(*k) != hipSuccess) {
+        k->ok = false;
+        return nullptr;
+    }
+    return k;
+}
+
+hipError_t launch_lanes(sig::JitKernel& k, const sig::WordSet& w, const float* path, const float* coeffs_in, const float* grad,
+                        int64_t B, int64_t n_points, float* out, hipStream_t st)
+{
+    const sig::LanesShape s = sig::lanes_shape(w.d, w.depth);
+    long lB = (long)B, lP = (long)n_points;
+    const int64_t blocks = (B * s.waves + k.nw - 1) / k.nw;
+    if (grad) {
+        void* args[] = {(void*)&path, (void*)&coeffs_in, (void*)&grad, (void*)&lB, (void*)&lP, (void*)&out};
+        return hipModuleLaunchKernel(k.fn, (unsigned)blocks, 1, 1, (unsigned)k.nw * 64, 1, 1, 0, st, args, nullptr);
+    }
+    void* args[] = {(void*)&path, (void*)&lB, (void*)&lP, (void*)&out};
+    return hipModuleLaunchKernel(k.fn, (unsigned)blocks, 1, 1, (unsigned)k.nw * 64, 1, 1, 0, st, args, nullptr);
+}
 }  // namespace
 
 extern "C" {
@@ -469,6 +523,7 @@ int sig_wordset_jit_prepare(sig_wordset* ws, int backward, int64_t B)
     const int dir = backward ? 1 : 0;
     if (!jit_enabled(w)) return SIG_EUNSUPPORTED;
     if (dir == 0 ? use_trunc_forward(w, B) : use_trunc_backward(w, B)) return SIG_EUNSUPPORTED;
+    if (use_lanes(w, B)) return ensure_lanes(w, dir, false) ? SIG_OK : SIG_EJIT;
     return ensure_jit(w, dir, B, false) ? SIG_OK : SIG_EJIT;
 }
 
@@ -478,10 +533,15 @@ size_t sig_wordset_jit_source(sig_wordset* ws, int backward, int64_t B, char* bu
     const sig::WordSet& w = *W(ws);
     const int dir = backward ? 1 : 0;
     if (!jit_enabled(w)) return 0;
-    sig::WordSet::JitEntry* e = jit_entry(w, dir, B);
-    if (!e) return 0;
-    int nw = 0, tile = 0;
-    const std::string src = jit_source(w, dir, e->plan, nw, tile);
+    std::string src;
+    if (use_lanes(w, B)) {
+        src = sig::lanes_source(w.d, w.depth, sig::lanes_shape(w.d, w.depth), dir != 0);
+    } else {
+        sig::WordSet::JitEntry* e = jit_entry(w, dir, B);
+        if (!e) return 0;
+        int nw = 0, tile = 0;
+        src = jit_source(w, dir, e->plan, nw, tile);
+    }
     if (buf && n > 0) {
         const size_t c = std::min(n - 1, src.size());
         std::memcpy(buf, src.data(), c);
@@ -582,6 +642,14 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
             e = sig::chunk_scan(w.d, w.depth, Sc, Pfx, nullptr, nullptr, coeffs, nullptr, nullptr, B, (int)ch.C, nullptr, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
+    if (use_lanes(w, B))
+        if (sig::JitKernel* lk = ensure_lanes(w, 0, true)) {
+            hipEvent_t* pe = g_prof.next(0);
+            if (pe) (void)hipEventRecord(pe[0], st);
+            hipError_t e = launch_lanes(*lk, w, path, nullptr, nullptr, B, n_points, coeffs, st);
+            if (pe) (void)hipEventRecord(pe[1], st);
+            return e == hipSuccess ? SIG_OK : hip_fail(e);
+        }
     const sig::Plan* jp = nullptr;
     if (sig::JitKernel* jk = ensure_jit(w, 0, B, true, &jp)) {
         if (!workspace || workspace_bytes < jit_dxt_bytes(w, B, n_points, 0)) return SIG_EWORKSPACE;
@@ -681,6 +749,16 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
         if (!points) e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
+    if (use_lanes(w, B))
+        if (sig::JitKernel* lk = ensure_lanes(w, 1, true)) {
+            hipEvent_t* pe = g_prof.next(1);
+            if (pe) (void)hipEventRecord(pe[0], st);
+            e = launch_lanes(*lk, w, path, coeffs, grad_coeffs, B, n_points, gdx, st);
+            if (pe) (void)hipEventRecord(pe[1], st);
+            if (e != hipSuccess) return hip_fail(e);
+            e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
+            return e == hipSuccess ? SIG_OK : hip_fail(e);
+        }
     const sig::Plan* jp = nullptr;
     if (sig::JitKernel* jk = ensure_jit(w, 1, B, true, &jp)) {
         const size_t gdx_bytes = ((size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;
@@ -842,6 +920,7 @@ const char* sig_wordset_kernel_name(const sig_wordset* ws, int backward)
     if (!ws || !W(ws)->kernels_supported) return "unsupported";
     if (!backward && use_trunc_forward(*W(ws), 1)) return "trunc_mfma_fwd_kernel";
     if (backward && use_trunc_backward(*W(ws), 1)) return sig::trunc_backward_kernel_name(W(ws)->d, W(ws)->depth);
+    if (use_lanes(*W(ws), 1)) return backward ? "sig_bwd_lanes" : "sig_fwd_lanes";
     if (jit_enabled(*W(ws))) return backward ? "sig_bwd_jit" : "sig_fwd_jit";
     return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";
 }
@@ -865,6 +944,7 @@ const char* sig_kernel_name(const sig_wordset* ws, int backward, int64_t B, int6
         const BwdShape sh = trunc_backward_shape(w, B, n_points);
         return sh.tails ? "trunc_tails_bwd_kernel" : sig::trunc_backward_kernel_name(w.d, w.depth);
     }
+    if (use_lanes(w, B)) return backward ? "sig_bwd_lanes" : "sig_fwd_lanes";
     if (jit_enabled(w)) return backward ? "sig_bwd_jit" : "sig_fwd_jit";
     return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";
 }

@@ -351,7 +351,7 @@ int jit_compile(const std::string& src, const char* kernel_name, JitKernel& out)
         out.log = "hiprtcCreateProgram failed";
         return -1;
     }
-    const char* opts[] = {"--offload-arch=gfx950", "-O3", "-munsafe-fp-atomics", "-Xclang", "-target-feature", "-Xclang",
+    const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-munsafe-fp-atomics", "-Xclang", "-target-feature", "-Xclang",
                           "-packed-fp32-ops"};
     const hiprtcResult rc = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
     size_t logsz = 0;
@@ -394,6 +394,11 @@ WordSet::~WordSet()
                 delete e->kernel;
             }
             delete e;
+        }
+    for (int dir = 0; dir < 2; ++dir)
+        if (lanes[dir]) {
+            jit_release(*lanes[dir]);
+            delete lanes[dir];
         }
 }
 

@@ -29,4 +29,15 @@ int jit_compile(const std::string& src, const char* kernel_name, JitKernel& out)
 hipError_t jit_load(JitKernel& k);
 void jit_release(JitKernel& k);
 
+// Full truncations with lanes = words (jit_lanes.cpp): a lane holds a word of length depth - R and the R levels below
+// it, `lanes` = d^(depth - R) of them per path in `waves` wavefronts, nwb wavefronts per workgroup, T segments per tile.
+struct LanesShape {
+    bool ok;
+    int R, T, nwb;
+    int64_t lanes, waves;
+};
+LanesShape lanes_shape(int d, int depth);
+// source of sig_fwd_lanes (backward = false) or sig_bwd_lanes for that shape
+std::string lanes_source(int d, int depth, const LanesShape& s, bool backward);
+
 }  // namespace sig

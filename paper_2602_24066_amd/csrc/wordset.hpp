@@ -86,6 +86,8 @@ struct WordSet {
         JitKernel* kernel = nullptr;
     };
     std::vector<JitEntry*> jit[2];
+    // full truncations: kernels with lanes = words, per direction (jit_lanes.cpp); built on first use
+    JitKernel* lanes[2] = {nullptr, nullptr};
     WordSet() = default;
     WordSet(const WordSet&) = delete;
     WordSet& operator=(const WordSet&) = delete;

@@ -233,6 +233,48 @@ def test_more_than_2_to_the_31_coefficients(d, depth, B):
     assert torch.isfinite(gp).all()
 
 
+@pytest.mark.parametrize("d,depth,B,L", [
+    (6, 5, 3, 21),      # two levels per lane, 216 words of length 3: three full wavefronts and a ragged one
+    (3, 6, 5, 33),      # 81 lanes per path
+    (2, 7, 4, 9),       # half a wavefront per path
+    (7, 4, 2, 17),      # 49 lanes
+    (5, 3, 6, 8),       # 5 lanes per path (forced: the launcher would take lanes = paths)
+    (10, 4, 2, 19),     # one level per lane: 1,000 words of length 3, tiles of 6 segments
+    (9, 4, 3, 1),       # a single segment
+    (12, 3, 2, 11),     # 144 lanes, tiles of 5 segments
+    (40, 3, 1, 5),      # tiles of one segment, 65,640 coefficients from a single path
+])
+def test_truncations_with_lanes_as_words(d, depth, B, L, monkeypatch):
+    """Full truncations that have no register-resident kernel of their own: the run-time compiled kernels with a
+    word per lane, every coefficient and the whole gradient against the oracle."""
+    monkeypatch.setenv("SIG_LANES", "1")
+    ws, W = build_both("truncated", d, depth=depth)
+    assert ws.kernel_name(False, B, L + 1) == "sig_fwd_lanes" and ws.kernel_name(True, B, L + 1) == "sig_bwd_lanes"
+    X = make_path("iid", 71 + d, B, L, d)
+    G = make_grad_coeffs(72 + d, B, ws.size)
+    check_parity(ws, W, "truncated", depth, X, G, what=f"lanes = words, d={d} N={depth}")
+
+
+def test_lanes_as_words_and_lanes_as_paths_agree(monkeypatch):
+    """The two run-time compiled forms of one truncation on the same inputs (each is compared with the oracle
+    elsewhere; this pins the switch between them)."""
+    import torch
+    d, depth, B, L = 6, 4, 70, 40
+    X = torch.from_numpy(make_path("iid", 81, B, L, d)).cuda()
+    out = {}
+    for form in ("0", "1"):
+        monkeypatch.setenv("SIG_LANES", form)
+        ws = S.sig_wordset_build_truncated(d, depth)
+        ws.upload("cuda:0")
+        assert ws.kernel_name(False, B, L + 1) == ("sig_fwd_lanes" if form == "1" else "sig_fwd_jit")
+        G = torch.from_numpy(make_grad_coeffs(82, B, ws.size)).cuda()
+        c = S.sig_forward(ws, X)
+        g = S.sig_backward(ws, X, c, G)
+        out[form] = (c.cpu().numpy(), g.cpu().numpy())
+    np.testing.assert_allclose(out["0"][0], out["1"][0], rtol=2e-4, atol=1e-6)
+    np.testing.assert_allclose(out["0"][1], out["1"][1], rtol=1e-3, atol=1e-4)
+
+
 def test_graph_induced_word_set():
     edges = [(0, 1), (0, 2), (1, 3), (2, 3), (3, 4), (3, 5), (1, 5), (4, 5), (2, 4)]
     ws = S.sig_wordset_build_graph(6, edges, 5)

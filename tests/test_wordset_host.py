@@ -288,6 +288,14 @@ def test_runtime_compilation_without_a_device():
         assert ws.jit_prepare(backward, 128) == 0
     full = S.sig_wordset_build_truncated(4, 6)                  # served by a precompiled kernel instead
     assert full.jit_prepare(False, 128) == -9
+    # truncations of other shapes: one fixed source with the shape as macros, a word per lane
+    for d, depth, levels in [(6, 5, 2), (10, 4, 1), (40, 3, 1)]:
+        ws = S.sig_wordset_build_truncated(d, depth)
+        for backward in (False, True):
+            src = ws.jit_source(backward, 32)
+            assert f"#define D {d}\n#define N {depth}\n#define R {levels}\n" in src
+            assert ("sig_bwd_lanes" if backward else "sig_fwd_lanes") in src
+            assert ws.jit_prepare(backward, 32) == 0
 
 
 def test_time_chunk_workspace():
@@ -386,7 +394,7 @@ def test_logsig_word_set_on_a_shape_with_a_truncated_kernel():
 
 # ---- which kernel a batch would launch (host logic only: no device call is made) ---------------------------
 def test_kernel_selection_for_full_truncations(monkeypatch):
-    for k in ("SIG_FWD_TAILS", "SIG_BWD_TAILS", "SIG_CHUNKS", "SIG_NO_JIT"):
+    for k in ("SIG_FWD_TAILS", "SIG_BWD_TAILS", "SIG_CHUNKS", "SIG_NO_JIT", "SIG_LANES"):
         monkeypatch.delenv(k, raising=False)
     ws46 = S.sig_wordset_build_truncated(4, 6)
     # d = 4: the one-wavefront-per-row layout for every batch size of the forward except few, long paths
@@ -409,6 +417,13 @@ def test_kernel_selection_for_full_truncations(monkeypatch):
     assert S.sig_wordset_build_truncated(8, 5).kernel_name(True, 128, 1025) == "trunc_node_bwd_kernel"
     assert S.sig_wordset_build_truncated(16, 4).kernel_name(True, 64, 4097) == "trunc_mfma_bwd_kernel"
     assert S.sig_wordset_build_truncated(16, 4).kernel_name(False, 64, 4097) == "trunc_mfma_fwd_kernel"
+    # other truncations: a word per lane when the words of length N - 2 (N - 1 beyond 8 letters) fill half a
+    # wavefront, else a path per lane
     assert S.sig_wordset_build_truncated(3, 4).kernel_name(False, 64, 65) == "sig_fwd_jit"
-    # batches beyond the row limit of the truncated kernels take the specialised ones
-    assert ws46.kernel_name(False, 70000, 17) == "sig_fwd_jit"
+    assert S.sig_wordset_build_truncated(6, 5).kernel_name(False, 32, 100) == "sig_fwd_lanes"
+    assert S.sig_wordset_build_truncated(10, 4).kernel_name(True, 1, 200) == "sig_bwd_lanes"
+    monkeypatch.setenv("SIG_LANES", "0")
+    assert S.sig_wordset_build_truncated(6, 5).kernel_name(False, 32, 100) == "sig_fwd_jit"
+    monkeypatch.delenv("SIG_LANES")
+    # batches beyond the row limit of the register-resident kernels take the run-time compiled ones
+    assert ws46.kernel_name(False, 70000, 17) == "sig_fwd_lanes"
