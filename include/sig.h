@@ -127,7 +127,12 @@ int sig_wordset_plan_get(const sig_wordset* ws, int backward, int variant, const
  * for a word set therefore takes seconds.  sig_wordset_jit_prepare does that compilation ahead of time for the
  * plan variant a batch of B paths would use (host only, no device needed); it returns SIG_OK, SIG_EUNSUPPORTED if
  * this word set is not run through specialised kernels, or SIG_EJIT if hiprtc failed (sig_forward / sig_backward
- * then fall back to the table-driven kernels).  Setting the environment variable SIG_NO_JIT=1 disables it. */
+ * then fall back to the table-driven kernels).  Setting the environment variable SIG_NO_JIT=1 disables it.
+ * Full truncations (any d <= 64) without a precompiled kernel are the exception to "grows with the word set": they
+ * run one fixed kernel source with a word per lane, compiled for the shape (d, depth) in under a second per
+ * direction (Section 3.1, eq. (3), with the prefixes shared between words); SIG_LANES=0 sends them through the
+ * straight-line form as well, SIG_LANES=1 takes the word-per-lane form even where a path has only a few words of
+ * length depth - 2.  sig_wordset_jit_prepare and sig_wordset_jit_source cover whichever form the batch would use. */
 #define SIG_EJIT (-10)
 int sig_wordset_jit_prepare(sig_wordset* ws, int backward, int64_t B);
 /* The plan the specialised kernel for a batch of B paths is generated from, in the format of sig_wordset_plan_get.

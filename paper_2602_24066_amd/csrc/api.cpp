@@ -289,9 +289,9 @@ bool use_lanes(const sig::WordSet& w, int64_t B)
     const char* e = std::getenv("SIG_LANES");
     const int f = (e && e[0]) ? std::atoi(e) : -1;
     if (f == 0) return false;
-    const sig::LanesShape s = sig::lanes_shape(w.d, w.depth);
-    if (!s.ok || B * s.waves > (int64_t)0x7fffffff) return false;
-    return f == 1 || s.lanes >= 32;
+    const sig::LanesShape s = sig::lanes_shape(w.d, w.depth, false), sb = sig::lanes_shape(w.d, w.depth, true);
+    if (!s.ok || !sb.ok || B * std::max(s.waves, sb.waves) > (int64_t)0x7fffffff) return false;
+    return f == 1 || std::min(s.lanes, sb.lanes) >= 32;
 }
 
 sig::JitKernel* ensure_lanes(const sig::WordSet& cw, int dir, bool load)
@@ -304,7 +304,7 @@ sig::JitKernel* ensure_lanes(const sig::WordSet& cw, int dir, bool load)
     if (!k->tried) {
         k->tried = true;
         try {
-            const sig::LanesShape s = sig::lanes_shape(w.d, w.depth);
+            const sig::LanesShape s = sig::lanes_shape(w.d, w.depth, dir != 0);
             k->nw = s.nwb;
             k->tile = s.T;
             (void)sig::jit_compile(sig::lanes_source(w.d, w.depth, s, dir != 0), dir ? "sig_bwd_lanes" : "sig_fwd_lanes", *k);
@@ -321,7 +321,7 @@ sig::JitKernel* ensure_lanes(const sig::WordSet& cw, int dir, bool load)
 hipError_t launch_lanes(sig::JitKernel& k, const sig::WordSet& w, const float* path, const float* coeffs_in, const float* grad,
                         int64_t B, int64_t n_points, float* out, hipStream_t st)
 {
-    const sig::LanesShape s = sig::lanes_shape(w.d, w.depth);
+    const sig::LanesShape s = sig::lanes_shape(w.d, w.depth, grad != nullptr);
     long lB = (long)B, lP = (long)n_points;
     const int64_t blocks = (B * s.waves + k.nw - 1) / k.nw;
     if (grad) {
@@ -535,7 +535,7 @@ size_t sig_wordset_jit_source(sig_wordset* ws, int backward, int64_t B, char* bu
     if (!jit_enabled(w)) return 0;
     std::string src;
     if (use_lanes(w, B)) {
-        src = sig::lanes_source(w.d, w.depth, sig::lanes_shape(w.d, w.depth), dir != 0);
+        src = sig::lanes_source(w.d, w.depth, sig::lanes_shape(w.d, w.depth, dir != 0), dir != 0);
     } else {
         sig::WordSet::JitEntry* e = jit_entry(w, dir, B);
         if (!e) return 0;

@@ -36,7 +36,7 @@ struct LanesShape {
     int R, T, nwb;
     int64_t lanes, waves;
 };
-LanesShape lanes_shape(int d, int depth);
+LanesShape lanes_shape(int d, int depth, bool backward);
 // source of sig_fwd_lanes (backward = false) or sig_bwd_lanes for that shape
 std::string lanes_source(int d, int depth, const LanesShape& s, bool backward);
 

@@ -20,6 +20,7 @@ namespace {
 const char* const kLanesSource = R"SRC(
 #define K (N - R)
 #define NC ((N + 3) / 4 * 4)
+#define DP ((D + 3) / 4 * 4)
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int ipow(int b, int e)
@@ -36,10 +37,18 @@ constexpr long level_start(int n)
     return r;
 }
 constexpr float inv1(int t) { return 1.0f / (float)(t + 1); }
+// chain positions k = 1 .. NU whose letter changes at most once inside a wavefront (runs of D^(K-k) >= 64 lanes)
+constexpr int count_wide()
+{
+    int n = 0;
+    for (int k = 1; k <= K; ++k) n += ipow(D, K - k) >= 64 ? 1 : 0;
+    return n;
+}
 
 #define NL ipow(D, K)                       /* words of length K = lanes per path */
 #define WAVES ((NL + 63) / 64)
 #define NWORDS (level_start(N) + ipow(D, N))
+#define NU count_wide()
 
 static_assert(K >= 1 && (R == 1 || R == 2), "a lane holds a word of length N - R and one or two levels below it");
 static_assert(T * D <= 64, "one lane per (letter, segment) of a tile");
@@ -61,12 +70,26 @@ __device__ __forceinline__ float fetch_increment(const float* __restrict__ X, lo
     const float x1 = X[(jj + 1) * D + i], x0 = X[jj * D + i];
     return ok ? x1 - x0 : 0.0f;
 }
-// Ec[segment][letter][t] = dX / (t + 1)
+// LDS of a tile: Ec[segment][letter][t] = dX / (t + 1) for the chain (a lane reads the row of its own letter), and
+// E0[segment][letter] = dX, E1 = dX / 2 as contiguous rows for the levels below u (every lane reads all letters)
+#define TILE_F (T * D * NC + 2 * T * DP)
 __device__ __forceinline__ void stage_increment(float* Ec, float dx, int lane)
 {
     if (lane < T * D) {
 #pragma unroll
         for (int t = 0; t < N; ++t) Ec[lane * NC + t] = dx * inv1(t);
+        float* E0 = Ec + T * D * NC;
+        E0[(lane / D) * DP + lane % D] = dx;
+        E0[T * DP + (lane / D) * DP + lane % D] = dx * 0.5f;
+    }
+}
+// the D increments of a segment from one of the contiguous rows
+__device__ __forceinline__ void load_row(const float* row, float (&e)[DP])
+{
+#pragma unroll
+    for (int q = 0; q < DP / 4; ++q) {
+        const f4 v = ((const f4*)row)[q];
+        e[4 * q] = v[0]; e[4 * q + 1] = v[1]; e[4 * q + 2] = v[2]; e[4 * q + 3] = v[3];
     }
 }
 
@@ -74,12 +97,13 @@ __device__ __forceinline__ void stage_increment(float* Ec, float dx, int lane)
 extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float* __restrict__ path, long B, long P,
                                                                       float* __restrict__ coeffs)
 {
-    __shared__ __attribute__((aligned(16))) float smem[NWB * T * D * NC];
+    __shared__ __attribute__((aligned(16))) float smem[NWB * TILE_F];
     const int lane = threadIdx.x & 63;
     const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long wave = (long)blockIdx.x * NWB + wib;
     if (wave >= B * WAVES) return;                       // wavefronts share nothing: no barrier is skipped
-    float* Ec = smem + wib * (T * D * NC);
+    float* Ec = smem + wib * TILE_F;
+    const float* E0 = Ec + T * D * NC;
     const long b = wave / WAVES;
     const int p0 = __builtin_amdgcn_readfirstlane((int)(wave - b * WAVES) * 64);
     const bool valid = p0 + lane < NL;
@@ -116,6 +140,8 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float
 #pragma unroll 2
         for (int tt = 0; tt < T; ++tt) {
             const float* Et = Ec + tt * D * NC;
+            float e0[DP];
+            load_row(E0 + tt * DP, e0);
             float ap[K + 1][N + 2];
 #pragma unroll
             for (int t = 0; t < N + 2; ++t) ap[0][t] = 1.0f;
@@ -126,15 +152,18 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float
                 for (int t = 1; t <= N - k; ++t) ap[k][t] = __builtin_fmaf(src[t], ap[k - 1][t + 1], Sc[k - 1]);
                 Sc[k - 1] = __builtin_fmaf(src[0], ap[k - 1][1], Sc[k - 1]);
             }
+#if R == 2
+            float e1[DP];
+            load_row(E0 + T * DP + tt * DP, e1);
+#endif
 #pragma unroll
             for (int j = 0; j < D; ++j) {
-                const float e0 = Et[j * NC];
 #if R == 2
-                const float Gp = __builtin_fmaf(Et[j * NC + 1], ap[K][2], S1[j]);
+                const float Gp = __builtin_fmaf(e1[j], ap[K][2], S1[j]);
 #pragma unroll
-                for (int jj = 0; jj < D; ++jj) S2[j][jj] = __builtin_fmaf(Et[jj * NC], Gp, S2[j][jj]);
+                for (int jj = 0; jj < D; ++jj) S2[j][jj] = __builtin_fmaf(e0[jj], Gp, S2[j][jj]);
 #endif
-                S1[j] = __builtin_fmaf(e0, ap[K][1], S1[j]);
+                S1[j] = __builtin_fmaf(e0[j], ap[K][1], S1[j]);
             }
         }
     }
@@ -153,15 +182,30 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float
 #endif
     }
 }
-
 #else
 // Backward (Section 4: reconstruction with -dX, Proposition 4.6; gradient of Proposition 4.1 in its adjoint form).
 // Per segment a lane produces one gradient contribution per letter below u (all lanes to the same letter) and one
-// per chain letter (to the lane's own letter at that position); they go to LDS per segment of a tile and lane
-// j T + t then sums, for letter j and segment t, the rows of the first kind and the members of the second kind,
-// and adds the total to gdx (zeroed by the caller) with one floating-point atomic.
-#define NSRC (D + K)
-#define BW_PER_WAVE (T * D * NC + NSRC * T * 64)
+// per chain position (to the lane's own letter at that position).  They go to LDS rows [source][segment][lane] for
+// the segments of a tile and are summed per tile:
+//   - rows of the letters below u: lane j T + t adds up row (j, t);
+//   - chain positions whose letter runs over fewer than 64 lanes: the same lane adds the members of its letter;
+//   - chain positions with longer runs (at most two letters in a wavefront, the change at lane `split`): the lanes
+//     write to one of two rows, which are summed like the rows of the first kind by a second group of lanes;
+// every total goes to gdx (zeroed by the caller) with one floating-point atomic.
+#define NSRC (D + K + NU)
+#define BW_PER_WAVE (TILE_F + NSRC * T * 64)
+// row of chain position k (1-based): two rows for each of the first NU positions, one for the others
+constexpr int chain_row(int k) { return k <= NU ? D + 2 * (k - 1) : D + 2 * NU + (k - NU - 1); }
+
+__device__ __forceinline__ float row_sum(const float* row, int lane)
+{
+    // rows lie 256 bytes apart: every lane starts at another 16-byte piece of its row
+    const f4* r = (const f4*)row;
+    f4 acc = r[lane & 15];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) acc += r[(i + lane) & 15];
+    return (acc[0] + acc[1]) + (acc[2] + acc[3]);
+}
 
 extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float* __restrict__ path,
         const float* __restrict__ coeffs, const float* __restrict__ grad, long B, long P, float* gdx)
@@ -172,7 +216,8 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
     const long wave = (long)blockIdx.x * NWB + wib;
     if (wave >= B * WAVES) return;
     float* Ec = smem + wib * BW_PER_WAVE;
-    float* Vb = Ec + T * D * NC;
+    const float* E0 = Ec + T * D * NC;
+    float* Vb = Ec + TILE_F;
     const long b = wave / WAVES;
     const int p0 = __builtin_amdgcn_readfirstlane((int)(wave - b * WAVES) * 64);
     const bool valid = p0 + lane < NL;
@@ -207,6 +252,14 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
         for (int jj = 0; jj < D; ++jj) An[j][jj] = valid ? gr[level_start(K + 2) + ((long)p * D + j) * D + jj] : 0.0f;
     }
 #endif
+    // chain positions with long runs: first lane of the second letter (64 and beyond: one letter in this wavefront)
+    int split[NU + 1], first_letter[NU + 1];
+#pragma unroll
+    for (int k = 1; k <= NU; ++k) {
+        const int s = ipow(D, K - k);
+        split[k] = (p0 / s + 1) * s - p0;
+        first_letter[k] = (p0 / s) % D;
+    }
 
     const long ntiles = (L + T - 1) / T;
     float dxn = fetch_increment(X, (ntiles - 1) * T, L, lane);
@@ -218,6 +271,8 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
 #pragma unroll 2
         for (int tt = T - 1; tt >= 0; --tt) {
             const float* Et = Ec + tt * D * NC;
+            float e0[DP];
+            load_row(E0 + tt * DP, e0);
             float ec[K][NC];
 #pragma unroll
             for (int k = 0; k < K; ++k) {
@@ -249,9 +304,11 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
 #pragma unroll
             for (int j = 0; j < D; ++j) {
                 vb[j * T * 64] = A1[j] * ap[K][1];
-                g1 = __builtin_fmaf(Et[j * NC], A1[j], g1);
+                g1 = __builtin_fmaf(e0[j], A1[j], g1);
             }
 #else
+            float e1[DP];
+            load_row(E0 + T * DP + tt * DP, e1);
             float y[D];
 #pragma unroll
             for (int j = 0; j < D; ++j) y[j] = 0.0f;
@@ -259,20 +316,20 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
             float g2 = 0.0f;
 #pragma unroll
             for (int j = 0; j < D; ++j) {
-                S1[j] = __builtin_fmaf(-Et[j * NC], am[K][1], S1[j]);
-                const float Gp = __builtin_fmaf(Et[j * NC + 1], ap[K][2], S1[j]);
+                S1[j] = __builtin_fmaf(-e0[j], am[K][1], S1[j]);
+                const float Gp = __builtin_fmaf(e1[j], ap[K][2], S1[j]);
                 float h = 0.0f;
 #pragma unroll
                 for (int jj = 0; jj < D; ++jj) {
-                    h = __builtin_fmaf(Et[jj * NC], An[j][jj], h);
+                    h = __builtin_fmaf(e0[jj], An[j][jj], h);
                     y[jj] = __builtin_fmaf(An[j][jj], Gp, y[jj]);
                 }
                 const float q0 = A1[j];
                 A1[j] = q0 + h;
                 y[j] = __builtin_fmaf(q0, ap[K][1], y[j]);
                 y[j] = __builtin_fmaf(h, hp2, y[j]);
-                g1 = __builtin_fmaf(Et[j * NC], q0, g1);
-                g2 = __builtin_fmaf(Et[j * NC + 1], h, g2);
+                g1 = __builtin_fmaf(e0[j], q0, g1);
+                g2 = __builtin_fmaf(e1[j], h, g2);
             }
             gb[K][2] = g2;
 #pragma unroll
@@ -292,32 +349,54 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
                     gb[k - 1][t + 1] = __builtin_fmaf(ec[k - 1][t], q, gb[k - 1][t + 1]);
                 }
                 Ac[k - 1] = asum;
-                vb[(D + k - 1) * T * 64] = gc;
+                if (k <= NU) {
+                    const bool second = lane >= split[k <= NU ? k : 0];
+                    vb[chain_row(k) * T * 64] = second ? 0.0f : gc;
+                    vb[(chain_row(k) + 1) * T * 64] = second ? gc : 0.0f;
+                } else {
+                    vb[chain_row(k) * T * 64] = gc;
+                }
             }
         }
         wave_lds_fence();
         if (lane < T * D) {
             const int j = lane / T, t = lane % T;
-            // rows of the letters below u: all 64 lanes.  The rows lie 256 bytes apart, so every lane starts at
-            // another 16-byte piece of its row.
-            const f4* row = (const f4*)(Vb + lane * 64);
-            f4 acc4 = row[lane & 15];
+            float acc = row_sum(Vb + lane * 64, lane);
+            // chain position k with runs of s < 64 lanes: the lanes whose k-th letter is j, s of them every s D
 #pragma unroll
-            for (int i = 1; i < 16; ++i) acc4 += row[(i + lane) & 15];
-            float acc = (acc4[0] + acc4[1]) + (acc4[2] + acc4[3]);
-            // chain position k: the lanes whose k-th letter is j, runs of D^(K-k) words every D^(K-k+1)
-#pragma unroll
-            for (int k = 1; k <= K; ++k) {
+            for (int k = NU + 1; k <= K; ++k) {
                 const int s = ipow(D, K - k), period = s * D;
-                const float* V = Vb + ((D + k - 1) * T + t) * 64;
-                for (int rs = (p0 / period) * period + j * s; rs < p0 + 64; rs += period) {
-                    const int lo = rs > p0 ? rs : p0;
-                    const int hi = rs + s < p0 + 64 ? rs + s : p0 + 64;
-                    for (int q = lo; q < hi; ++q) acc += V[q - p0];
-                }
+                const float* V = Vb + (chain_row(k) * T + t) * 64;
+                const int rs0 = (p0 / period) * period + j * s - p0;     // first run that can reach this wavefront
+#pragma unroll
+                for (int r = 0; r < (64 + period - 1) / period + 1; ++r)
+#pragma unroll
+                    for (int u = 0; u < s; ++u) {
+                        const int q = rs0 + r * period + u;
+                        const bool in = q >= 0 && q < 64;
+                        const float v = V[in ? q : 0];
+                        acc += in ? v : 0.0f;
+                    }
             }
             const long sg = n * T + t;
             if (sg < L) __hip_atomic_fetch_add(gdx + (b * L + sg) * D + j, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+        for (int base = 0; base < 2 * NU * T; base += 64) {
+            const int o = base + lane;
+            if (o < 2 * NU * T) {
+                const int r = o / T, t = o % T;                           // row D + r: position r / 2 + 1, half r % 2
+                int sp = 64, fl = 0;
+#pragma unroll
+                for (int k = 1; k <= NU; ++k)
+                    if (r / 2 + 1 == k) { sp = split[k]; fl = first_letter[k]; }
+                const long sg = n * T + t;
+                if (sg < L && ((r & 1) == 0 || sp < 64)) {
+                    const float acc = row_sum(Vb + ((D + r) * T + t) * 64, lane);
+                    const int j = (r & 1) ? (fl + 1 == D ? 0 : fl + 1) : fl;
+                    __hip_atomic_fetch_add(gdx + (b * L + sg) * D + j, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
         }
     }
 }
@@ -326,23 +405,51 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
 
 }  // namespace
 
-LanesShape lanes_shape(int d, int depth)
+LanesShape lanes_shape(int d, int depth, bool backward)
 {
-    LanesShape s{};
-    if (d < 2 || d > 64 || depth < 2 || depth > 12) return s;
-    // two levels per lane while their state fits the registers (forward d + d^2 values, backward about twice that)
-    s.R = (d <= 8 && depth >= 3) ? 2 : 1;
-    s.T = 64 / d < 8 ? 64 / d : 8;
-    double lanes = 1.0;
-    for (int k = 0; k < depth - s.R; ++k) lanes *= d;
-    if (lanes > 1.0e9) return LanesShape{};
-    s.lanes = (int64_t)lanes;
-    s.waves = (s.lanes + 63) / 64;
-    const int NC = (depth + 3) / 4 * 4;
-    const size_t per_wave = ((size_t)s.T * d * NC + (size_t)(d + depth - s.R) * s.T * 64) * sizeof(float);
-    s.nwb = (int)(per_wave * 4 <= 64 * 1024 ? 4 : (per_wave * 2 <= 64 * 1024 ? 2 : (per_wave <= 64 * 1024 ? 1 : 0)));
-    s.ok = s.nwb > 0;
-    return s;
+    LanesShape best{};
+    if (d < 2 || d > 64 || depth < 2 || depth > 12) return best;
+    const int NC = (depth + 3) / 4 * 4, DP = (d + 3) / 4 * 4;
+    double best_cost = 0.0;
+    // two levels per lane while their state fits the registers (forward d + d^2 values, backward twice that and the
+    // per-letter sums); between the admissible forms, the one with fewer instructions per path and segment
+    for (int R = 1; R <= 2; ++R) {
+        if (depth - R < 1) continue;
+        if (R == 2 && d > (backward ? 10 : 12)) continue;
+        LanesShape s{};
+        s.R = R;
+        s.T = 64 / d < 8 ? 64 / d : 8;
+        const int K = depth - R;
+        double lanes = 1.0;
+        for (int k = 0; k < K; ++k) lanes *= d;
+        if (lanes > 1.0e9) continue;
+        s.lanes = (int64_t)lanes;
+        s.waves = (s.lanes + 63) / 64;
+        int chain = 0, wide = 0;
+        double run = lanes;
+        for (int k = 1; k <= K; ++k) {
+            chain += depth - k + 1;
+            run /= d;                                      // d^(K - k)
+            wide += run >= 64.0 ? 1 : 0;
+        }
+        const double per_lane = 2.0 * chain + (R == 2 ? (double)d * d + 3.0 * d : 2.0 * d);
+        const double cost = (double)s.waves * per_lane;
+        // LDS of a wavefront: the increments of a tile and, backward, the gradient rows of its segments; eight
+        // wavefronts of 20 KB fit a compute unit, so longer tiles are cut down to that
+        auto lds_bytes = [&](int T) {
+            const size_t tile = (size_t)T * d * NC + 2 * (size_t)T * DP;
+            return (tile + (backward ? (size_t)(d + K + wide) * T * 64 : 0)) * sizeof(float);
+        };
+        while (s.T > 1 && lds_bytes(s.T) > 20 * 1024) --s.T;
+        const size_t per_wave = lds_bytes(s.T);
+        s.nwb = (int)(per_wave * 4 <= 64 * 1024 ? 4 : (per_wave * 2 <= 64 * 1024 ? 2 : (per_wave <= 64 * 1024 ? 1 : 0)));
+        s.ok = s.nwb > 0;
+        if (s.ok && (!best.ok || cost < best_cost)) {
+            best = s;
+            best_cost = cost;
+        }
+    }
+    return best;
 }
 
 std::string lanes_source(int d, int depth, const LanesShape& s, bool backward)

@@ -239,9 +239,12 @@ def test_more_than_2_to_the_31_coefficients(d, depth, B):
     (2, 7, 4, 9),       # half a wavefront per path
     (7, 4, 2, 17),      # 49 lanes
     (5, 3, 6, 8),       # 5 lanes per path (forced: the launcher would take lanes = paths)
-    (10, 4, 2, 19),     # one level per lane: 1,000 words of length 3, tiles of 6 segments
+    (10, 4, 2, 19),     # 100 lanes with 110 coefficients each, tiles of 6 segments
     (9, 4, 3, 1),       # a single segment
-    (12, 3, 2, 11),     # 144 lanes, tiles of 5 segments
+    (12, 3, 2, 11),     # one level per lane: 144 lanes, tiles of 5 segments
+    (12, 4, 1, 7),      # one level per lane; the first chain letter changes inside some wavefronts (runs of 144 lanes)
+    (6, 6, 1, 6),       # runs of 216, 36, 6 and 1 lanes
+    (3, 8, 2, 10),      # six chain letters, two of them with runs of 64 lanes or more
     (40, 3, 1, 5),      # tiles of one segment, 65,640 coefficients from a single path
 ])
 def test_truncations_with_lanes_as_words(d, depth, B, L, monkeypatch):

@@ -289,7 +289,7 @@ def test_runtime_compilation_without_a_device():
     full = S.sig_wordset_build_truncated(4, 6)                  # served by a precompiled kernel instead
     assert full.jit_prepare(False, 128) == -9
     # truncations of other shapes: one fixed source with the shape as macros, a word per lane
-    for d, depth, levels in [(6, 5, 2), (10, 4, 1), (40, 3, 1)]:
+    for d, depth, levels in [(6, 5, 2), (10, 4, 2), (12, 3, 1), (40, 3, 1)]:
         ws = S.sig_wordset_build_truncated(d, depth)
         for backward in (False, True):
             src = ws.jit_source(backward, 32)
