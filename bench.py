@@ -329,6 +329,38 @@ def main():
         except Exception as e:
             out["log_signature"] = {"error": str(e)[:200]}
 
+        # shapes of the paper's own timing table (Section 5, Table 1: training step = forward + backward, float32,
+        # one H200): synthetic random walks of the same shape; the paper's figure is context, another machine's
+        try:
+            from sig_workloads import make_path as make_path_ref
+            table = {}
+            for (Bp, Mp, dp, Np, paper_us) in [(32, 100, 6, 4, 207.52), (32, 100, 6, 5, 555.63), (32, 100, 6, 6, 3360.0),
+                                               (64, 1000, 4, 6, 6450.0), (1, 200, 10, 4, 320.35),
+                                               (256, 200, 10, 4, 9830.0)]:
+                wsp = S.sig_wordset_build_truncated(dp, Np)
+                wsp.upload("cuda:0")
+                Xp = torch.from_numpy(make_path_ref("iid", 7, Bp, Mp - 1, dp)).cuda()
+                cp = S.sig_forward(wsp, Xp)
+                gp = torch.randn_like(cp)
+                S.sig_backward(wsp, Xp, cp, gp)
+                torch.cuda.synchronize()
+                S.sig_profile_enable(True)
+                for _ in range(5):
+                    S.sig_forward(wsp, Xp, out=cp)
+                    S.sig_backward(wsp, Xp, cp, gp)
+                torch.cuda.synchronize()
+                nf, mf = S.sig_profile_read(False, True)
+                nb, mb = S.sig_profile_read(True, True)
+                S.sig_profile_enable(False)
+                us = (mf / max(nf, 1) + mb / max(nb, 1)) * 1e3
+                table[f"B={Bp} points={Mp} d={dp} N={Np}"] = {
+                    "coeffs": wsp.size, "step_us": round(us, 1), "paper_h200_step_us": paper_us,
+                    "fwd_bwd_coeff_steps_per_s": round(Bp * (Mp - 1) * wsp.size / (us * 1e-6), 1),
+                    "kernels": [wsp.kernel_name(False, Bp, Mp), wsp.kernel_name(True, Bp, Mp)]}
+            out["paper_table_shapes"] = table
+        except Exception as e:
+            out["paper_table_shapes"] = {"error": str(e)[:200]}
+
         # the other word-set builders (host only): graph-induced set and the sparse lead-lag set of a 5-dimensional path
         t0 = time.perf_counter()
         g = S.sig_wordset_build_graph(10, [(a, b) for a in range(10) for b in range(10) if 0 < b - a <= 3], 6)

@@ -283,28 +283,42 @@ int bwd_tile_steps(int d) { return std::max(1, std::min(16, 32 / std::max(d, 1))
 // ten thousand words); lanes = words fills the wavefronts from a single path on and compiles in about a second per
 // shape.  Taken whenever the words of a path fill at least half a wavefront; SIG_LANES=0 switches it off, =1 takes
 // it for every shape it is defined for.
+int lanes_levels_asked()
+{
+    const char* e = std::getenv("SIG_LANES_LEVELS");       // testing knob: 1 or 2 levels below the lane's word
+    const int v = (e && e[0]) ? std::atoi(e) : 0;
+    return v == 1 || v == 2 ? v : 0;
+}
+sig::LanesShape lanes_shape_for(const sig::WordSet& w, int dir, int64_t B)
+{
+    sig::LanesShape s = sig::lanes_shape(w.d, w.depth, dir != 0, B, lanes_levels_asked());
+    if (!s.ok) s = sig::lanes_shape(w.d, w.depth, dir != 0, B, 0);
+    return s;
+}
+
 bool use_lanes(const sig::WordSet& w, int64_t B)
 {
     if (w.kind != 0 || !jit_enabled(w)) return false;
     const char* e = std::getenv("SIG_LANES");
     const int f = (e && e[0]) ? std::atoi(e) : -1;
     if (f == 0) return false;
-    const sig::LanesShape s = sig::lanes_shape(w.d, w.depth, false), sb = sig::lanes_shape(w.d, w.depth, true);
+    const sig::LanesShape s = lanes_shape_for(w, 0, B), sb = lanes_shape_for(w, 1, B);
     if (!s.ok || !sb.ok || B * std::max(s.waves, sb.waves) > (int64_t)0x7fffffff) return false;
     return f == 1 || std::min(s.lanes, sb.lanes) >= 32;
 }
 
-sig::JitKernel* ensure_lanes(const sig::WordSet& cw, int dir, bool load)
+sig::JitKernel* ensure_lanes(const sig::WordSet& cw, int dir, const sig::LanesShape& s, bool load)
 {
     sig::WordSet& w = const_cast<sig::WordSet&>(cw);     // the cache is logically mutable
     std::lock_guard<std::mutex> lock(g_jit_mutex);
-    if (!w.lanes[dir]) w.lanes[dir] = new (std::nothrow) sig::JitKernel;
-    sig::JitKernel* k = w.lanes[dir];
+    sig::JitKernel*& slot = w.lanes[dir][s.R - 1];
+    if (!slot) slot = new (std::nothrow) sig::JitKernel;
+    sig::JitKernel* k = slot;
     if (!k) return nullptr;
     if (!k->tried) {
         k->tried = true;
         try {
-            const sig::LanesShape s = sig::lanes_shape(w.d, w.depth, dir != 0);
+            // everything but the levels per lane follows from (d, depth, direction): one kernel per slot
             k->nw = s.nwb;
             k->tile = s.T;
             (void)sig::jit_compile(sig::lanes_source(w.d, w.depth, s, dir != 0), dir ? "sig_bwd_lanes" : "sig_fwd_lanes", *k);
@@ -318,10 +332,9 @@ sig::JitKernel* ensure_lanes(const sig::WordSet& cw, int dir, bool load)
     return k;
 }
 
-hipError_t launch_lanes(sig::JitKernel& k, const sig::WordSet& w, const float* path, const float* coeffs_in, const float* grad,
+hipError_t launch_lanes(sig::JitKernel& k, const sig::LanesShape& s, const float* path, const float* coeffs_in, const float* grad,
                         int64_t B, int64_t n_points, float* out, hipStream_t st)
 {
-    const sig::LanesShape s = sig::lanes_shape(w.d, w.depth, grad != nullptr);
     long lB = (long)B, lP = (long)n_points;
     const int64_t blocks = (B * s.waves + k.nw - 1) / k.nw;
     if (grad) {
@@ -523,7 +536,7 @@ int sig_wordset_jit_prepare(sig_wordset* ws, int backward, int64_t B)
     const int dir = backward ? 1 : 0;
     if (!jit_enabled(w)) return SIG_EUNSUPPORTED;
     if (dir == 0 ? use_trunc_forward(w, B) : use_trunc_backward(w, B)) return SIG_EUNSUPPORTED;
-    if (use_lanes(w, B)) return ensure_lanes(w, dir, false) ? SIG_OK : SIG_EJIT;
+    if (use_lanes(w, B)) return ensure_lanes(w, dir, lanes_shape_for(w, dir, B), false) ? SIG_OK : SIG_EJIT;
     return ensure_jit(w, dir, B, false) ? SIG_OK : SIG_EJIT;
 }
 
@@ -535,7 +548,7 @@ size_t sig_wordset_jit_source(sig_wordset* ws, int backward, int64_t B, char* bu
     if (!jit_enabled(w)) return 0;
     std::string src;
     if (use_lanes(w, B)) {
-        src = sig::lanes_source(w.d, w.depth, sig::lanes_shape(w.d, w.depth, dir != 0), dir != 0);
+        src = sig::lanes_source(w.d, w.depth, lanes_shape_for(w, dir, B), dir != 0);
     } else {
         sig::WordSet::JitEntry* e = jit_entry(w, dir, B);
         if (!e) return 0;
@@ -642,14 +655,16 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
             e = sig::chunk_scan(w.d, w.depth, Sc, Pfx, nullptr, nullptr, coeffs, nullptr, nullptr, B, (int)ch.C, nullptr, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
-    if (use_lanes(w, B))
-        if (sig::JitKernel* lk = ensure_lanes(w, 0, true)) {
+    if (use_lanes(w, B)) {
+        const sig::LanesShape ls = lanes_shape_for(w, 0, B);
+        if (sig::JitKernel* lk = ensure_lanes(w, 0, ls, true)) {
             hipEvent_t* pe = g_prof.next(0);
             if (pe) (void)hipEventRecord(pe[0], st);
-            hipError_t e = launch_lanes(*lk, w, path, nullptr, nullptr, B, n_points, coeffs, st);
+            hipError_t e = launch_lanes(*lk, ls, path, nullptr, nullptr, B, n_points, coeffs, st);
             if (pe) (void)hipEventRecord(pe[1], st);
             return e == hipSuccess ? SIG_OK : hip_fail(e);
         }
+    }
     const sig::Plan* jp = nullptr;
     if (sig::JitKernel* jk = ensure_jit(w, 0, B, true, &jp)) {
         if (!workspace || workspace_bytes < jit_dxt_bytes(w, B, n_points, 0)) return SIG_EWORKSPACE;
@@ -749,16 +764,18 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
         if (!points) e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
-    if (use_lanes(w, B))
-        if (sig::JitKernel* lk = ensure_lanes(w, 1, true)) {
+    if (use_lanes(w, B)) {
+        const sig::LanesShape ls = lanes_shape_for(w, 1, B);
+        if (sig::JitKernel* lk = ensure_lanes(w, 1, ls, true)) {
             hipEvent_t* pe = g_prof.next(1);
             if (pe) (void)hipEventRecord(pe[0], st);
-            e = launch_lanes(*lk, w, path, coeffs, grad_coeffs, B, n_points, gdx, st);
+            e = launch_lanes(*lk, ls, path, coeffs, grad_coeffs, B, n_points, gdx, st);
             if (pe) (void)hipEventRecord(pe[1], st);
             if (e != hipSuccess) return hip_fail(e);
             e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
             return e == hipSuccess ? SIG_OK : hip_fail(e);
         }
+    }
     const sig::Plan* jp = nullptr;
     if (sig::JitKernel* jk = ensure_jit(w, 1, B, true, &jp)) {
         const size_t gdx_bytes = ((size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;

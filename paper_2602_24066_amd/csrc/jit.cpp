@@ -396,10 +396,11 @@ WordSet::~WordSet()
             delete e;
         }
     for (int dir = 0; dir < 2; ++dir)
-        if (lanes[dir]) {
-            jit_release(*lanes[dir]);
-            delete lanes[dir];
-        }
+        for (int r = 0; r < 2; ++r)
+            if (lanes[dir][r]) {
+                jit_release(*lanes[dir][r]);
+                delete lanes[dir][r];
+            }
 }
 
 void jit_release(JitKernel& k)

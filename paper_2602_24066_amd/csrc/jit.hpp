@@ -30,13 +30,15 @@ hipError_t jit_load(JitKernel& k);
 void jit_release(JitKernel& k);
 
 // Full truncations with lanes = words (jit_lanes.cpp): a lane holds a word of length depth - R and the R levels below
-// it, `lanes` = d^(depth - R) of them per path in `waves` wavefronts, nwb wavefronts per workgroup, T segments per tile.
+// it, `lanes` = d^(depth - R) of them per path in `waves` wavefronts, nwb wavefronts per workgroup, T segments per
+// gradient tile, TS segments of increments staged at a time.
 struct LanesShape {
     bool ok;
-    int R, T, nwb;
+    int R, T, TS, nwb;
     int64_t lanes, waves;
 };
-LanesShape lanes_shape(int d, int depth, bool backward);
+// the form for a batch of B paths; levels = 1 or 2 asks for that R (0: the cheaper one)
+LanesShape lanes_shape(int d, int depth, bool backward, int64_t B, int levels);
 // source of sig_fwd_lanes (backward = false) or sig_bwd_lanes for that shape
 std::string lanes_source(int d, int depth, const LanesShape& s, bool backward);
 

@@ -9,6 +9,7 @@
 // wavefronts serve a path; lanes past d^K carry a copy of the last word with zero adjoints and store nothing.
 // Against lanes = paths this fills the wavefronts for any batch size and needs one short compilation per shape
 // instead of one that grows with the word set.
+#include <algorithm>
 #include <sstream>
 #include <string>
 
@@ -51,7 +52,7 @@ constexpr int count_wide()
 #define NU count_wide()
 
 static_assert(K >= 1 && (R == 1 || R == 2), "a lane holds a word of length N - R and one or two levels below it");
-static_assert(T * D <= 64, "one lane per (letter, segment) of a tile");
+static_assert(T * D <= 64 && TS % T == 0, "one lane per (letter, segment) of a tile; whole tiles per staging tile");
 
 __device__ __forceinline__ void wave_lds_fence()
 {
@@ -59,28 +60,39 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_wave_barrier();
 }
 
-// increment (segment j0 + lane / D, letter lane % D) of the tile that starts at segment j0; zero outside [0, L)
-__device__ __forceinline__ float fetch_increment(const float* __restrict__ X, long j0, long L, int lane)
+// Increments are staged TS segments at a time (a multiple of T; the global loads of the next staging tile are in
+// flight while this one is worked on, and a longer tile hides their latency when a SIMD has a single wavefront).
+// Element e = lane + 64 q of a staging tile is (segment j0 + e / D, letter e % D); zero outside [0, L).
+#define EPL ((TS * D + 63) / 64)
+__device__ __forceinline__ void fetch_increments(const float* __restrict__ X, long j0, long L, int lane, float (&dx)[EPL])
 {
-    const int e = lane < T * D ? lane : T * D - 1;
-    long jj = j0 + e / D;
-    const bool ok = jj >= 0 && jj < L;
-    jj = jj < 0 ? 0 : (jj < L ? jj : L - 1);
-    const int i = e % D;
-    const float x1 = X[(jj + 1) * D + i], x0 = X[jj * D + i];
-    return ok ? x1 - x0 : 0.0f;
-}
-// LDS of a tile: Ec[segment][letter][t] = dX / (t + 1) for the chain (a lane reads the row of its own letter), and
-// E0[segment][letter] = dX, E1 = dX / 2 as contiguous rows for the levels below u (every lane reads all letters)
-#define TILE_F (T * D * NC + 2 * T * DP)
-__device__ __forceinline__ void stage_increment(float* Ec, float dx, int lane)
-{
-    if (lane < T * D) {
+    // points are rows of D floats, so element e of the tile is X[j0 D + e + D] - X[j0 D + e]
+    const long base = j0 * D, lim = L * D;
 #pragma unroll
-        for (int t = 0; t < N; ++t) Ec[lane * NC + t] = dx * inv1(t);
-        float* E0 = Ec + T * D * NC;
-        E0[(lane / D) * DP + lane % D] = dx;
-        E0[T * DP + (lane / D) * DP + lane % D] = dx * 0.5f;
+    for (int q = 0; q < EPL; ++q) {
+        long idx = base + lane + 64 * q;
+        const bool ok = idx >= 0 && idx < lim;
+        idx = idx < 0 ? 0 : (idx < lim ? idx : lim - 1);
+        const float x1 = X[idx + D], x0 = X[idx];
+        dx[q] = ok ? x1 - x0 : 0.0f;
+    }
+}
+// LDS of a staging tile: Ec[segment][letter][t] = dX / (t + 1) for the chain (a lane reads the row of its own
+// letter), and E0[segment][letter] = dX, E1 = dX / 2 as contiguous rows for the levels below u (every lane reads all
+// letters)
+#define TILE_F (TS * D * NC + 2 * TS * DP)
+__device__ __forceinline__ void stage_increments(float* Ec, const float (&dx)[EPL], int lane)
+{
+#pragma unroll
+    for (int q = 0; q < EPL; ++q) {
+        const int e = lane + 64 * q;
+        if (e < TS * D) {
+#pragma unroll
+            for (int t = 0; t < N; ++t) Ec[e * NC + t] = dx[q] * inv1(t);
+            float* E0 = Ec + TS * D * NC;
+            E0[(e / D) * DP + e % D] = dx[q];
+            E0[TS * DP + (e / D) * DP + e % D] = dx[q] * 0.5f;
+        }
     }
 }
 // the D increments of a segment from one of the contiguous rows
@@ -103,7 +115,7 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float
     const long wave = (long)blockIdx.x * NWB + wib;
     if (wave >= B * WAVES) return;                       // wavefronts share nothing: no barrier is skipped
     float* Ec = smem + wib * TILE_F;
-    const float* E0 = Ec + T * D * NC;
+    const float* E0 = Ec + TS * D * NC;
     const long b = wave / WAVES;
     const int p0 = __builtin_amdgcn_readfirstlane((int)(wave - b * WAVES) * 64);
     const bool valid = p0 + lane < NL;
@@ -130,15 +142,16 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float
         for (int jj = 0; jj < D; ++jj) S2[j][jj] = 0.0f;
 #endif
 
-    const long ntiles = (L + T - 1) / T;
-    float dxn = fetch_increment(X, 0, L, lane);
+    const long ntiles = (L + TS - 1) / TS;
+    float dxn[EPL];
+    fetch_increments(X, 0, L, lane, dxn);
     for (long n = 0; n < ntiles; ++n) {
         wave_lds_fence();
-        stage_increment(Ec, dxn, lane);
+        stage_increments(Ec, dxn, lane);
         wave_lds_fence();
-        dxn = fetch_increment(X, (n + 1) * T, L, lane);  // past the end: zeros, and a zero increment changes nothing
+        fetch_increments(X, (n + 1) * TS, L, lane, dxn); // past the end: zeros, and a zero increment changes nothing
 #pragma unroll 2
-        for (int tt = 0; tt < T; ++tt) {
+        for (int tt = 0; tt < TS; ++tt) {
             const float* Et = Ec + tt * D * NC;
             float e0[DP];
             load_row(E0 + tt * DP, e0);
@@ -154,7 +167,7 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float
             }
 #if R == 2
             float e1[DP];
-            load_row(E0 + T * DP + tt * DP, e1);
+            load_row(E0 + TS * DP + tt * DP, e1);
 #endif
 #pragma unroll
             for (int j = 0; j < D; ++j) {
@@ -216,7 +229,7 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
     const long wave = (long)blockIdx.x * NWB + wib;
     if (wave >= B * WAVES) return;
     float* Ec = smem + wib * BW_PER_WAVE;
-    const float* E0 = Ec + T * D * NC;
+    const float* E0 = Ec + TS * D * NC;
     float* Vb = Ec + TILE_F;
     const long b = wave / WAVES;
     const int p0 = __builtin_amdgcn_readfirstlane((int)(wave - b * WAVES) * 64);
@@ -261,18 +274,21 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
         first_letter[k] = (p0 / s) % D;
     }
 
-    const long ntiles = (L + T - 1) / T;
-    float dxn = fetch_increment(X, (ntiles - 1) * T, L, lane);
-    for (long n = ntiles - 1; n >= 0; --n) {
+    const long nstage = (L + TS - 1) / TS;
+    float dxn[EPL];
+    fetch_increments(X, (nstage - 1) * TS, L, lane, dxn);
+    for (long ns = nstage - 1; ns >= 0; --ns) {
         wave_lds_fence();
-        stage_increment(Ec, dxn, lane);
+        stage_increments(Ec, dxn, lane);
         wave_lds_fence();
-        dxn = fetch_increment(X, (n - 1) * T, L, lane);
+        fetch_increments(X, (ns - 1) * TS, L, lane, dxn);
+      for (int sub = TS / T - 1; sub >= 0; --sub) {          // tiles of T segments: the unit of the gradient sums
+        const long n = ns * (TS / T) + sub;
 #pragma unroll 2
         for (int tt = T - 1; tt >= 0; --tt) {
-            const float* Et = Ec + tt * D * NC;
+            const float* Et = Ec + (sub * T + tt) * D * NC;
             float e0[DP];
-            load_row(E0 + tt * DP, e0);
+            load_row(E0 + (sub * T + tt) * DP, e0);
             float ec[K][NC];
 #pragma unroll
             for (int k = 0; k < K; ++k) {
@@ -308,7 +324,7 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
             }
 #else
             float e1[DP];
-            load_row(E0 + T * DP + tt * DP, e1);
+            load_row(E0 + TS * DP + (sub * T + tt) * DP, e1);
             float y[D];
 #pragma unroll
             for (int j = 0; j < D; ++j) y[j] = 0.0f;
@@ -398,6 +414,8 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
                 }
             }
         }
+        wave_lds_fence();                                      // the rows are rewritten by the next tile
+      }
     }
 }
 #endif
@@ -405,15 +423,18 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
 
 }  // namespace
 
-LanesShape lanes_shape(int d, int depth, bool backward)
+LanesShape lanes_shape(int d, int depth, bool backward, int64_t B, int levels)
 {
     LanesShape best{};
     if (d < 2 || d > 64 || depth < 2 || depth > 12) return best;
     const int NC = (depth + 3) / 4 * 4, DP = (d + 3) / 4 * 4;
     double best_cost = 0.0;
-    // two levels per lane while their state fits the registers (forward d + d^2 values, backward twice that and the
-    // per-letter sums); between the admissible forms, the one with fewer instructions per path and segment
+    // Two levels per lane while their state fits the registers (forward d + d^2 values, backward twice that and the
+    // per-letter sums).  Between the admissible forms: the time of a segment is the instructions of a lane times the
+    // wavefronts a SIMD has to run one after the other (1,024 SIMDs); two levels per lane share more work between
+    // words but leave few wavefronts for small batches, where one level per lane then has the shorter segment.
     for (int R = 1; R <= 2; ++R) {
+        if (levels != 0 && R != levels) continue;
         if (depth - R < 1) continue;
         if (R == 2 && d > (backward ? 10 : 12)) continue;
         LanesShape s{};
@@ -433,15 +454,30 @@ LanesShape lanes_shape(int d, int depth, bool backward)
             wide += run >= 64.0 ? 1 : 0;
         }
         const double per_lane = 2.0 * chain + (R == 2 ? (double)d * d + 3.0 * d : 2.0 * d);
-        const double cost = (double)s.waves * per_lane;
-        // LDS of a wavefront: the increments of a tile and, backward, the gradient rows of its segments; eight
-        // wavefronts of 20 KB fit a compute unit, so longer tiles are cut down to that
-        auto lds_bytes = [&](int T) {
-            const size_t tile = (size_t)T * d * NC + 2 * (size_t)T * DP;
+        const double rounds = (double)std::max<int64_t>(B, 1) * (double)s.waves / 1024.0;
+        const double cost = per_lane * (rounds < 1.0 ? 1.0 : rounds);
+        // LDS of a wavefront: the increments of a staging tile and, backward, the gradient rows of the segments of a
+        // tile; eight wavefronts of 20 KB fit a compute unit, so longer tiles are cut down to that.  The staging
+        // tile is as many tiles as fit (up to 32 segments and three increments per lane): its global loads are issued
+        // one staging tile ahead.
+        auto lds_bytes = [&](int T, int TS) {
+            const size_t tile = (size_t)TS * ((size_t)d * NC + 2 * (size_t)DP);
             return (tile + (backward ? (size_t)(d + K + wide) * T * 64 : 0)) * sizeof(float);
         };
-        while (s.T > 1 && lds_bytes(s.T) > 20 * 1024) --s.T;
-        const size_t per_wave = lds_bytes(s.T);
+        // (a lane carries its share of the next staging tile in registers: one increment where the state of two
+        // levels already fills them)
+        const int staged = (R == 2 && d * d + d > 48) ? 64 : 192;
+        if (backward) {
+            while (s.T > 1 && lds_bytes(s.T, s.T) > 20 * 1024) --s.T;
+            s.TS = s.T;
+            while (s.TS + s.T <= 32 && (s.TS + s.T) * d <= staged && lds_bytes(s.T, s.TS + s.T) <= 20 * 1024) s.TS += s.T;
+        } else {
+            s.T = 1;                                       // no gradient tiles: only the staging tile matters
+            s.TS = 32;
+            while (s.TS > 2 && (s.TS * d > staged || s.TS % 2 != 0 || lds_bytes(1, s.TS) > 8 * 1024)) --s.TS;
+            if (s.TS * d > 64 && s.TS * d > staged) s.TS = 1;
+        }
+        const size_t per_wave = lds_bytes(s.T, s.TS);
         s.nwb = (int)(per_wave * 4 <= 64 * 1024 ? 4 : (per_wave * 2 <= 64 * 1024 ? 2 : (per_wave <= 64 * 1024 ? 1 : 0)));
         s.ok = s.nwb > 0;
         if (s.ok && (!best.ok || cost < best_cost)) {
@@ -455,7 +491,7 @@ LanesShape lanes_shape(int d, int depth, bool backward)
 std::string lanes_source(int d, int depth, const LanesShape& s, bool backward)
 {
     std::ostringstream o;
-    o << "#define D " << d << "\n#define N " << depth << "\n#define R " << s.R << "\n#define T " << s.T << "\n#define NWB "
+    o << "#define D " << d << "\n#define N " << depth << "\n#define R " << s.R << "\n#define T " << s.T << "\n#define TS " << s.TS << "\n#define NWB "
       << s.nwb << "\n#define BACKWARD " << (backward ? 1 : 0) << "\n"
       << kLanesSource;
     return o.str();

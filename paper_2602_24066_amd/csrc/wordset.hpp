@@ -86,8 +86,9 @@ struct WordSet {
         JitKernel* kernel = nullptr;
     };
     std::vector<JitEntry*> jit[2];
-    // full truncations: kernels with lanes = words, per direction (jit_lanes.cpp); built on first use
-    JitKernel* lanes[2] = {nullptr, nullptr};
+    // full truncations: kernels with lanes = words, per direction and levels per lane (jit_lanes.cpp); built on
+    // first use
+    JitKernel* lanes[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};
     WordSet() = default;
     WordSet(const WordSet&) = delete;
     WordSet& operator=(const WordSet&) = delete;

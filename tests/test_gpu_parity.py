@@ -233,29 +233,36 @@ def test_more_than_2_to_the_31_coefficients(d, depth, B):
     assert torch.isfinite(gp).all()
 
 
-@pytest.mark.parametrize("d,depth,B,L", [
-    (6, 5, 3, 21),      # two levels per lane, 216 words of length 3: three full wavefronts and a ragged one
-    (3, 6, 5, 33),      # 81 lanes per path
-    (2, 7, 4, 9),       # half a wavefront per path
-    (7, 4, 2, 17),      # 49 lanes
-    (5, 3, 6, 8),       # 5 lanes per path (forced: the launcher would take lanes = paths)
-    (10, 4, 2, 19),     # 100 lanes with 110 coefficients each, tiles of 6 segments
-    (9, 4, 3, 1),       # a single segment
-    (12, 3, 2, 11),     # one level per lane: 144 lanes, tiles of 5 segments
-    (12, 4, 1, 7),      # one level per lane; the first chain letter changes inside some wavefronts (runs of 144 lanes)
-    (6, 6, 1, 6),       # runs of 216, 36, 6 and 1 lanes
-    (3, 8, 2, 10),      # six chain letters, two of them with runs of 64 lanes or more
-    (40, 3, 1, 5),      # tiles of one segment, 65,640 coefficients from a single path
+@pytest.mark.parametrize("d,depth,B,L,levels", [
+    (6, 5, 3, 21, 2),     # two levels per lane, 216 words of length 3: three full wavefronts and a ragged one
+    (6, 5, 2, 13, 1),     # one level per lane: 1,296 lanes; the first chain letter runs over 216 of them
+    (3, 6, 5, 33, 2),     # 81 lanes per path
+    (3, 6, 2, 20, 1),     # 243 lanes
+    (2, 7, 4, 9, 2),      # half a wavefront per path
+    (7, 4, 2, 17, 2),     # 49 lanes
+    (7, 4, 2, 17, 1),     # 343 lanes
+    (5, 3, 6, 8, 2),      # 5 lanes per path (forced: the launcher would take lanes = paths)
+    (10, 4, 2, 19, 2),    # 100 lanes with 110 coefficients each, tiles of 6 segments
+    (10, 4, 1, 25, 1),    # 1,000 lanes
+    (9, 4, 3, 1, 1),      # a single segment
+    (12, 3, 2, 11, 1),    # 144 lanes, tiles of 5 segments
+    (12, 4, 1, 7, 1),     # the first chain letter changes inside some wavefronts (runs of 144 lanes)
+    (6, 6, 1, 6, 2),      # runs of 216, 36, 6 and 1 lanes
+    (3, 8, 2, 10, 2),     # six chain letters, two of them with runs of 64 lanes or more
+    (40, 3, 1, 5, 1),     # tiles of one segment, 65,640 coefficients from a single path
 ])
-def test_truncations_with_lanes_as_words(d, depth, B, L, monkeypatch):
+def test_truncations_with_lanes_as_words(d, depth, B, L, levels, monkeypatch):
     """Full truncations that have no register-resident kernel of their own: the run-time compiled kernels with a
-    word per lane, every coefficient and the whole gradient against the oracle."""
+    word per lane, in both of their forms (the d leaves, or the d children and d^2 leaves, below the lane's word),
+    every coefficient and the whole gradient against the oracle."""
     monkeypatch.setenv("SIG_LANES", "1")
+    monkeypatch.setenv("SIG_LANES_LEVELS", str(levels))
     ws, W = build_both("truncated", d, depth=depth)
     assert ws.kernel_name(False, B, L + 1) == "sig_fwd_lanes" and ws.kernel_name(True, B, L + 1) == "sig_bwd_lanes"
+    assert f"#define R {levels}\n" in ws.jit_source(False, B) and f"#define R {levels}\n" in ws.jit_source(True, B)
     X = make_path("iid", 71 + d, B, L, d)
     G = make_grad_coeffs(72 + d, B, ws.size)
-    check_parity(ws, W, "truncated", depth, X, G, what=f"lanes = words, d={d} N={depth}")
+    check_parity(ws, W, "truncated", depth, X, G, what=f"lanes = words, d={d} N={depth}, {levels} levels per lane")
 
 
 def test_lanes_as_words_and_lanes_as_paths_agree(monkeypatch):

@@ -288,14 +288,16 @@ def test_runtime_compilation_without_a_device():
         assert ws.jit_prepare(backward, 128) == 0
     full = S.sig_wordset_build_truncated(4, 6)                  # served by a precompiled kernel instead
     assert full.jit_prepare(False, 128) == -9
-    # truncations of other shapes: one fixed source with the shape as macros, a word per lane
-    for d, depth, levels in [(6, 5, 2), (10, 4, 2), (12, 3, 1), (40, 3, 1)]:
+    # truncations of other shapes: one fixed source with the shape as macros, a word per lane; two levels below the
+    # lane's word for large batches, one for small ones (more, shorter wavefronts) and for large alphabets
+    for d, depth, B, levels in [(6, 5, 4096, 2), (6, 5, 32, 1), (10, 4, 4096, 2), (10, 4, 1, 1), (12, 3, 4096, 1),
+                                (40, 3, 64, 1)]:
         ws = S.sig_wordset_build_truncated(d, depth)
         for backward in (False, True):
-            src = ws.jit_source(backward, 32)
+            src = ws.jit_source(backward, B)
             assert f"#define D {d}\n#define N {depth}\n#define R {levels}\n" in src
             assert ("sig_bwd_lanes" if backward else "sig_fwd_lanes") in src
-            assert ws.jit_prepare(backward, 32) == 0
+            assert ws.jit_prepare(backward, B) == 0
 
 
 def test_time_chunk_workspace():
@@ -394,7 +396,7 @@ def test_logsig_word_set_on_a_shape_with_a_truncated_kernel():
 
 # ---- which kernel a batch would launch (host logic only: no device call is made) ---------------------------
 def test_kernel_selection_for_full_truncations(monkeypatch):
-    for k in ("SIG_FWD_TAILS", "SIG_BWD_TAILS", "SIG_CHUNKS", "SIG_NO_JIT", "SIG_LANES"):
+    for k in ("SIG_FWD_TAILS", "SIG_BWD_TAILS", "SIG_CHUNKS", "SIG_NO_JIT", "SIG_LANES", "SIG_LANES_LEVELS"):
         monkeypatch.delenv(k, raising=False)
     ws46 = S.sig_wordset_build_truncated(4, 6)
     # d = 4: the one-wavefront-per-row layout for every batch size of the forward except few, long paths
