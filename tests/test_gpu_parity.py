@@ -265,6 +265,26 @@ def test_truncations_with_lanes_as_words(d, depth, B, L, levels, monkeypatch):
     check_parity(ws, W, "truncated", depth, X, G, what=f"lanes = words, d={d} N={depth}, {levels} levels per lane")
 
 
+def test_lanes_as_words_on_random_shapes(monkeypatch):
+    """Sixteen seeded random shapes (2..20 letters, depth 2..6, up to 30,000 words, 1..5 paths of 1..40 segments),
+    alternating between the two forms of the word-per-lane kernels where both exist."""
+    rng = np.random.default_rng(2024)
+    monkeypatch.setenv("SIG_LANES", "1")
+    done = 0
+    while done < 16:
+        d, depth = int(rng.integers(2, 21)), int(rng.integers(2, 7))
+        if sum(d ** n for n in range(1, depth + 1)) > 30000 or (d, depth) in ((4, 6), (8, 5), (16, 4)):
+            continue
+        B, L = int(rng.integers(1, 6)), int(rng.integers(1, 41))
+        monkeypatch.setenv("SIG_LANES_LEVELS", str(1 + done % 2))
+        ws, W = build_both("truncated", d, depth=depth)
+        assert ws.kernel_name(True, B, L + 1) == "sig_bwd_lanes"
+        X = make_path("iid", 300 + done, B, L, d)
+        G = make_grad_coeffs(400 + done, B, ws.size)
+        check_parity(ws, W, "truncated", depth, X, G, what=f"random shape {done}: d={d} N={depth} B={B} L={L}")
+        done += 1
+
+
 def test_lanes_as_words_and_lanes_as_paths_agree(monkeypatch):
     """The two run-time compiled forms of one truncation on the same inputs (each is compared with the oracle
     elsewhere; this pins the switch between them)."""
