@@ -344,6 +344,7 @@ def test_leadlag_transform_and_sparse_word_set():
 WINDOW_SETS = [
     ("truncated", dict(d=3, depth=4)),
     ("truncated", dict(d=4, depth=6)),
+    ("truncated", dict(d=5, depth=4)),
     ("anisotropic", dict(d=4, weights=(1.0, 1.0, 2.0, 3.0), cutoff=5.0)),
     ("words", dict(d=6, n_words=500, max_len=5)),
 ]
@@ -431,7 +432,8 @@ def test_log_signature_gradient(monkeypatch, two_kernels):
     assert O.grad_errors(gp, num).max() <= BWD_TOL
 
 
-@pytest.mark.parametrize("kind,d,depth,B,L", [("truncated", 4, 6, 9, 70), ("truncated", 8, 5, 2, 24), ("words", 5, 4, 70, 19)])
+@pytest.mark.parametrize("kind,d,depth,B,L", [("truncated", 4, 6, 9, 70), ("truncated", 8, 5, 2, 24), ("words", 5, 4, 70, 19),
+                                              ("truncated", 6, 4, 5, 31)])
 def test_step_captured_in_a_graph(kind, d, depth, B, L):
     """Forward + backward recorded into a HIP graph (the library enqueues kernels only: no allocation, no memset) and
     replayed on new inputs, with eager calls and synchronisations between the replays; every replay must reproduce
