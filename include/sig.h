@@ -132,7 +132,9 @@ int sig_wordset_plan_get(const sig_wordset* ws, int backward, int variant, const
  * run one fixed kernel source with a word per lane, compiled for the shape (d, depth) in under a second per
  * direction (Section 3.1, eq. (3), with the prefixes shared between words); SIG_LANES=0 sends them through the
  * straight-line form as well, SIG_LANES=1 takes the word-per-lane form even where a path has only a few words of
- * length depth - 2.  sig_wordset_jit_prepare and sig_wordset_jit_source cover whichever form the batch would use. */
+ * length depth - 2.  sig_wordset_jit_prepare and sig_wordset_jit_source cover whichever form the batch would use.
+ * With SIG_JIT_CACHE set to an existing directory, compiled code objects are kept there (named by a hash of their
+ * source and the compiler version) and later processes load them instead of compiling. */
 #define SIG_EJIT (-10)
 int sig_wordset_jit_prepare(sig_wordset* ws, int backward, int64_t B);
 /* The plan the specialised kernel for a batch of B paths is generated from, in the format of sig_wordset_plan_get.

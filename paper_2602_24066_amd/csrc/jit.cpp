@@ -13,8 +13,11 @@
 #include "jit.hpp"
 
 #include <hip/hiprtc.h>
+#include <unistd.h>
 
+#include <cstdint>
 #include <cstdio>
+#include <cstdlib>
 #include <set>
 #include <sstream>
 #include <utility>
@@ -343,9 +346,66 @@ std::string jit_backward_source(const WordSet& ws, const Plan& plan, int NW, int
     return o.str();
 }
 
+namespace {
+// Optional cache of compiled code objects on disk: with SIG_JIT_CACHE set to a directory, a code object is stored
+// there under a 64-bit hash of its source (which carries every specialisation) and of the compiler version, and later
+// processes load it instead of compiling.  Files are written under a temporary name and renamed, so concurrent
+// writers cannot leave a torn file; a file that fails to load is simply recompiled over.
+std::string cache_file(const std::string& src)
+{
+    const char* dir = std::getenv("SIG_JIT_CACHE");
+    if (!dir || !dir[0]) return std::string();
+    uint64_t h = 1469598103934665603ull;                  // FNV-1a
+    auto mix = [&](const char* p, size_t n) {
+        for (size_t i = 0; i < n; ++i) { h ^= (unsigned char)p[i]; h *= 1099511628211ull; }
+    };
+    int major = 0, minor = 0;
+    (void)hiprtcVersion(&major, &minor);
+    mix((const char*)&major, sizeof major);
+    mix((const char*)&minor, sizeof minor);
+    mix(src.data(), src.size());
+    char name[64];
+    std::snprintf(name, sizeof name, "/sig_gfx950_%016llx.hsaco", (unsigned long long)h);
+    return std::string(dir) + name;
+}
+bool cache_load(const std::string& file, std::vector<char>& code)
+{
+    if (file.empty()) return false;
+    std::FILE* f = std::fopen(file.c_str(), "rb");
+    if (!f) return false;
+    bool ok = false;
+    if (std::fseek(f, 0, SEEK_END) == 0) {
+        const long n = std::ftell(f);
+        if (n > 0 && std::fseek(f, 0, SEEK_SET) == 0) {
+            code.resize((size_t)n);
+            ok = std::fread(code.data(), 1, (size_t)n, f) == (size_t)n;
+        }
+    }
+    std::fclose(f);
+    if (!ok) code.clear();
+    return ok;
+}
+void cache_store(const std::string& file, const std::vector<char>& code)
+{
+    if (file.empty() || code.empty()) return;
+    const std::string tmp = file + ".tmp" + std::to_string((long long)getpid());
+    std::FILE* f = std::fopen(tmp.c_str(), "wb");
+    if (!f) return;                                       // a cache that cannot be written is not an error
+    const bool ok = std::fwrite(code.data(), 1, code.size(), f) == code.size();
+    if (std::fclose(f) != 0 || !ok || std::rename(tmp.c_str(), file.c_str()) != 0) (void)std::remove(tmp.c_str());
+}
+}  // namespace
+
 int jit_compile(const std::string& src, const char* kernel_name, JitKernel& out)
 {
     out.ok = false;
+    const std::string cached = cache_file(src);
+    if (cache_load(cached, out.code)) {
+        out.name = kernel_name;
+        out.log = "loaded from " + cached;
+        out.ok = true;
+        return 0;
+    }
     hiprtcProgram prog = nullptr;
     if (hiprtcCreateProgram(&prog, src.c_str(), "sig_jit.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS) {
         out.log = "hiprtcCreateProgram failed";
@@ -372,6 +432,7 @@ int jit_compile(const std::string& src, const char* kernel_name, JitKernel& out)
     const hiprtcResult rc2 = hiprtcGetCode(prog, &out.code[0]);
     (void)hiprtcDestroyProgram(&prog);
     if (rc2 != HIPRTC_SUCCESS) return -4;
+    cache_store(cached, out.code);
     out.name = kernel_name;
     out.ok = true;
     return 0;

@@ -483,6 +483,28 @@ def test_step_captured_in_a_graph(kind, d, depth, B, L):
             assert O.grad_errors(g_graph, O.backward_words(X, W, G.astype(np.float64))).max() <= BWD_TOL
 
 
+def test_code_object_from_the_disk_cache_runs(tmp_path, monkeypatch):
+    """A kernel loaded from SIG_JIT_CACHE instead of compiled gives the results of the compiled one, bit for bit."""
+    import torch
+    monkeypatch.setenv("SIG_JIT_CACHE", str(tmp_path))
+    words = random_prefix_closed_words(77, 5, 150, 4)
+    X = torch.from_numpy(make_path("iid", 78, 9, 23, 5)).cuda()
+    res = []
+    for _ in range(2):
+        ws = S.sig_wordset_build(5, words)
+        ws.upload("cuda:0")
+        G = torch.from_numpy(make_grad_coeffs(79, 9, ws.size)).cuda()
+        c = S.sig_forward(ws, X)
+        g = S.sig_backward(ws, X, c, G)
+        res.append((c.cpu().numpy(), g.cpu().numpy()))
+    import os
+    assert len(os.listdir(tmp_path)) == 2                         # forward and backward kernel, written once
+    assert np.array_equal(res[0][0], res[1][0])
+    np.testing.assert_allclose(res[0][1], res[1][1], rtol=1e-5, atol=1e-6)      # atomics: order of additions
+    ws2, W = build_both("words", 5, words=words)
+    check_parity(ws2, W, "words", None, make_path("iid", 78, 9, 23, 5), make_grad_coeffs(79, 9, ws2.size), what="cached kernels")
+
+
 def test_one_point_paths_give_zero():
     import torch
     ws, W = build_both("truncated", 3, depth=3)

@@ -300,6 +300,36 @@ def test_runtime_compilation_without_a_device():
             assert ws.jit_prepare(backward, B) == 0
 
 
+def test_code_object_cache_on_disk(tmp_path, monkeypatch):
+    """SIG_JIT_CACHE: the first compilation stores the code object, a fresh word-set object of the same set loads it
+    (no compiler run: the log says where it came from); another word set gets another file."""
+    import time
+    monkeypatch.setenv("SIG_JIT_CACHE", str(tmp_path))
+    lib = S.load_library()
+    words = random_prefix_closed_words(31, 4, 120, 5)
+    a = S.sig_wordset_build(4, words)
+    assert a.jit_prepare(False, 64) == 0
+    files = sorted(os.listdir(tmp_path))
+    assert len(files) == 1 and files[0].startswith("sig_gfx950_") and files[0].endswith(".hsaco")
+    stamp = os.path.getmtime(os.path.join(tmp_path, files[0]))
+    b = S.sig_wordset_build(4, words)
+    t0 = time.perf_counter()
+    assert b.jit_prepare(False, 64) == 0
+    assert time.perf_counter() - t0 < 0.2
+    assert sorted(os.listdir(tmp_path)) == files and os.path.getmtime(os.path.join(tmp_path, files[0])) == stamp
+    assert a.jit_prepare(True, 64) == 0                           # the backward kernel: a second file
+    assert len(os.listdir(tmp_path)) == 2
+    c = S.sig_wordset_build_truncated(6, 4)                       # word-per-lane source of another shape: a third
+    assert c.jit_prepare(False, 8) == 0
+    assert len(os.listdir(tmp_path)) == 3
+    # a directory that does not exist: compilation still succeeds, nothing is written
+    monkeypatch.setenv("SIG_JIT_CACHE", str(tmp_path / "missing"))
+    d = S.sig_wordset_build(4, words)
+    assert d.jit_prepare(False, 64) == 0
+    assert not os.path.exists(tmp_path / "missing")
+    del lib
+
+
 def test_time_chunk_workspace():
     """Few long paths of a full truncation are cut into time chunks: the forward workspace holds the chunk
     signatures and the partial products; many paths, or short ones, need none."""
