@@ -235,7 +235,8 @@ void emit_backward_unit(std::ostringstream& o, const Plan& plan, int uidx, int D
     o << "    for (long n = ntiles - 1; n >= 0; --n) {\n";
     o << "        __syncthreads();\n        tile_stage(tile, tid, r);\n        __syncthreads();\n";
     o << "        tile_fetch(dxg, n - 1, tid, r);\n";
-    o << "#pragma unroll 2\n        for (int tt = T - 1; tt >= 0; --tt) {\n";
+    // not unrolled: measured as fast as unrolled by two, and the compilation is a quarter shorter
+    o << "#pragma unroll 1\n        for (int tt = T - 1; tt >= 0; --tt) {\n";
     o << "            const float* dxp = tile + tt * D * 64 + lane;\n";
     emit_step_loads(o, uses, "            ");
     for (int i : uses.letters) o << "            float g" << i << " = 0.0f;\n";
