@@ -38,11 +38,11 @@ constexpr long level_start(int n)
     return r;
 }
 constexpr float inv1(int t) { return 1.0f / (float)(t + 1); }
-// chain positions k = 1 .. NU whose letter changes at most once inside a wavefront (runs of D^(K-k) >= 64 lanes)
+// chain positions k = 1 .. NU whose letter takes at most three values inside a wavefront (runs of D^(K-k) >= 32 lanes)
 constexpr int count_wide()
 {
     int n = 0;
-    for (int k = 1; k <= K; ++k) n += ipow(D, K - k) >= 64 ? 1 : 0;
+    for (int k = 1; k <= K; ++k) n += ipow(D, K - k) >= 32 ? 1 : 0;
     return n;
 }
 
@@ -201,14 +201,14 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float
 // per chain position (to the lane's own letter at that position).  They go to LDS rows [source][segment][lane] for
 // the segments of a tile and are summed per tile:
 //   - rows of the letters below u: lane j T + t adds up row (j, t);
-//   - chain positions whose letter runs over fewer than 64 lanes: the same lane adds the members of its letter;
-//   - chain positions with longer runs (at most two letters in a wavefront, the change at lane `split`): the lanes
-//     write to one of two rows, which are summed like the rows of the first kind by a second group of lanes;
+//   - chain positions whose letter runs over fewer than 32 lanes: the same lane adds the members of its letter;
+//   - chain positions with longer runs (at most three of them reach into a wavefront): a lane writes to the row of
+//     its run, and these rows are summed like the rows of the first kind by a second group of lanes;
 // every total goes to gdx (zeroed by the caller) with one floating-point atomic.
-#define NSRC (D + K + NU)
+#define NSRC (D + K + 2 * NU)
 #define BW_PER_WAVE (TILE_F + NSRC * T * 64)
-// row of chain position k (1-based): two rows for each of the first NU positions, one for the others
-constexpr int chain_row(int k) { return k <= NU ? D + 2 * (k - 1) : D + 2 * NU + (k - NU - 1); }
+// row of chain position k (1-based): three rows for each of the first NU positions, one for the others
+constexpr int chain_row(int k) { return k <= NU ? D + 3 * (k - 1) : D + 3 * NU + (k - NU - 1); }
 
 __device__ __forceinline__ float row_sum(const float* row, int lane)
 {
@@ -265,12 +265,14 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
         for (int jj = 0; jj < D; ++jj) An[j][jj] = valid ? gr[level_start(K + 2) + ((long)p * D + j) * D + jj] : 0.0f;
     }
 #endif
-    // chain positions with long runs: first lane of the second letter (64 and beyond: one letter in this wavefront)
-    int split[NU + 1], first_letter[NU + 1];
+    // chain positions with long runs: the run of this lane among those that reach into the wavefront (0, 1 or 2),
+    // how many do, and the letter of the first
+    int my_run[NU + 1], runs[NU + 1], first_letter[NU + 1];
 #pragma unroll
     for (int k = 1; k <= NU; ++k) {
         const int s = ipow(D, K - k);
-        split[k] = (p0 / s + 1) * s - p0;
+        my_run[k] = (p0 + lane) / s - p0 / s;
+        runs[k] = (p0 + 63) / s - p0 / s + 1;
         first_letter[k] = (p0 / s) % D;
     }
 
@@ -366,9 +368,10 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
                 }
                 Ac[k - 1] = asum;
                 if (k <= NU) {
-                    const bool second = lane >= split[k <= NU ? k : 0];
-                    vb[chain_row(k) * T * 64] = second ? 0.0f : gc;
-                    vb[(chain_row(k) + 1) * T * 64] = second ? gc : 0.0f;
+                    const int kk = k <= NU ? k : 0;
+                    vb[chain_row(k) * T * 64] = my_run[kk] == 0 ? gc : 0.0f;
+                    if (runs[kk] > 1) vb[(chain_row(k) + 1) * T * 64] = my_run[kk] == 1 ? gc : 0.0f;
+                    if (runs[kk] > 2) vb[(chain_row(k) + 2) * T * 64] = my_run[kk] == 2 ? gc : 0.0f;
                 } else {
                     vb[chain_row(k) * T * 64] = gc;
                 }
@@ -378,7 +381,7 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
         if (lane < T * D) {
             const int j = lane / T, t = lane % T;
             float acc = row_sum(Vb + lane * 64, lane);
-            // chain position k with runs of s < 64 lanes: the lanes whose k-th letter is j, s of them every s D
+            // chain position k with runs of s < 32 lanes: the lanes whose k-th letter is j, s of them every s D
 #pragma unroll
             for (int k = NU + 1; k <= K; ++k) {
                 const int s = ipow(D, K - k), period = s * D;
@@ -398,18 +401,18 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
             if (sg < L) __hip_atomic_fetch_add(gdx + (b * L + sg) * D + j, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
 #pragma unroll
-        for (int base = 0; base < 2 * NU * T; base += 64) {
+        for (int base = 0; base < 3 * NU * T; base += 64) {
             const int o = base + lane;
-            if (o < 2 * NU * T) {
-                const int r = o / T, t = o % T;                           // row D + r: position r / 2 + 1, half r % 2
-                int sp = 64, fl = 0;
+            if (o < 3 * NU * T) {
+                const int r = o / T, t = o % T;                           // row D + r: position r / 3 + 1, run r % 3
+                int nr = 0, fl = 0;
 #pragma unroll
                 for (int k = 1; k <= NU; ++k)
-                    if (r / 2 + 1 == k) { sp = split[k]; fl = first_letter[k]; }
+                    if (r / 3 + 1 == k) { nr = runs[k]; fl = first_letter[k]; }
                 const long sg = n * T + t;
-                if (sg < L && ((r & 1) == 0 || sp < 64)) {
+                if (sg < L && r % 3 < nr) {
                     const float acc = row_sum(Vb + ((D + r) * T + t) * 64, lane);
-                    const int j = (r & 1) ? (fl + 1 == D ? 0 : fl + 1) : fl;
+                    const int j = (fl + r % 3) % D;
                     __hip_atomic_fetch_add(gdx + (b * L + sg) * D + j, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
@@ -451,7 +454,7 @@ LanesShape lanes_shape(int d, int depth, bool backward, int64_t B, int levels)
         for (int k = 1; k <= K; ++k) {
             chain += depth - k + 1;
             run /= d;                                      // d^(K - k)
-            wide += run >= 64.0 ? 1 : 0;
+            wide += run >= 32.0 ? 1 : 0;
         }
         const double per_lane = 2.0 * chain + (R == 2 ? (double)d * d + 3.0 * d : 2.0 * d);
         const double rounds = (double)std::max<int64_t>(B, 1) * (double)s.waves / 1024.0;
@@ -462,7 +465,7 @@ LanesShape lanes_shape(int d, int depth, bool backward, int64_t B, int levels)
         // one staging tile ahead.
         auto lds_bytes = [&](int T, int TS) {
             const size_t tile = (size_t)TS * ((size_t)d * NC + 2 * (size_t)DP);
-            return (tile + (backward ? (size_t)(d + K + wide) * T * 64 : 0)) * sizeof(float);
+            return (tile + (backward ? (size_t)(d + K + 2 * wide) * T * 64 : 0)) * sizeof(float);
         };
         // (a lane carries its share of the next staging tile in registers: one increment where the state of two
         // levels already fills them)
