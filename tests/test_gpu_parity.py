@@ -265,6 +265,17 @@ def test_truncations_with_lanes_as_words(d, depth, B, L, levels, monkeypatch):
     check_parity(ws, W, "truncated", depth, X, G, what=f"lanes = words, d={d} N={depth}, {levels} levels per lane")
 
 
+def test_lanes_as_words_on_a_long_path():
+    """5,000 segments through the word-per-lane kernels: many staging tiles, and the reconstruction of the
+    backward pass over a long walk (within the gradient tolerance, as for the 4,096 segments of c5)."""
+    ws, W = build_both("truncated", 6, depth=4)
+    B, L = 2, 5000
+    assert ws.kernel_name(True, B, L + 1) == "sig_bwd_lanes"
+    X = make_path("iid", 91, B, L, 6)
+    G = make_grad_coeffs(92, B, ws.size)
+    check_parity(ws, W, "truncated", 4, X, G, what="lanes = words, 5,000 segments")
+
+
 def test_lanes_as_words_on_random_shapes(monkeypatch):
     """Sixteen seeded random shapes (2..20 letters, depth 2..6, up to 30,000 words, 1..5 paths of 1..40 segments),
     alternating between the two forms of the word-per-lane kernels where both exist."""
