@@ -84,7 +84,7 @@ def time_steps(S, torch, st, steps, warmup):
     """Returns (seconds per step by the host clock, forward main-kernel ms, backward main-kernel ms, GPU ms of the
     whole forward call, of the whole backward call), averaged over `steps` steps.  Every recorded event costs a few
     microseconds on the stream, so the timed region records one pair per step only, around the dominant kernel (found
-    in the warm-up, which records everything); the other durations come from an untimed pass of the same steps
+    in the warm-up, which records everything); the other durations come from untimed passes of the same steps
     afterwards."""
     S.sig_profile_enable(True)
     for _ in range(max(warmup, 1)):
@@ -102,16 +102,22 @@ def time_steps(S, torch, st, steps, warmup):
     t1 = time.perf_counter()
     nd, msd = S.sig_profile_read(bool(dominant))
     assert nd == steps
-    S.sig_profile_enable(True)
+    # two untimed passes: event pairs around the main kernels, then around whole calls (nested pairs would add their
+    # own recording time to the outer one)
+    S.sig_profile_enable(True, channels=[0, 1])
     for _ in range(steps):
         step(S, st)
     torch.cuda.synchronize()
     nf, msf = S.sig_profile_read(False)
     nb, msb = S.sig_profile_read(True)
-    _, cf = S.sig_profile_read(False, whole_call=True)
-    _, cb = S.sig_profile_read(True, whole_call=True)
+    S.sig_profile_enable(True, channels=[2, 3])
+    for _ in range(steps):
+        step(S, st)
+    torch.cuda.synchronize()
+    ncf, cf = S.sig_profile_read(False, whole_call=True)
+    ncb, cb = S.sig_profile_read(True, whole_call=True)
     S.sig_profile_enable(False)
-    assert nf == steps and nb == steps
+    assert nf == steps and nb == steps and ncf == steps and ncb == steps
     kf, kb = msf / nf, msb / nb
     if dominant:
         kb = msd / nd                 # the dominant kernel's duration is the one measured inside the timed region
@@ -176,8 +182,10 @@ def cpu_baseline(st, sample_paths, budget_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    # the clock of an idle MI355X takes some tens of milliseconds of load to settle (c2: 0.105 ms per step over 50 steps,
+    # 0.094 ms from about 1,000 steps on), so the defaults time a tenth of a second after a fifth of that as warm-up
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--no-others", action="store_true", help="skip the per-workload table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
@@ -247,8 +255,16 @@ def main():
             torch.cuda.reset_peak_memory_stats()
             base = torch.cuda.memory_allocated()
             s2 = st if name == args.workload else setup(name, S, torch)
-            n = 10 if name != "c5" else 5
-            sec2, kf2, kb2, f2, b2 = time_steps(S, torch, s2, n, 2)
+            # about 0.15 s of work per measuring pass (the clock settles first): 20 to --steps steps
+            step(S, s2)                                  # first call: run-time compilation, kernel attributes
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                step(S, s2)
+            torch.cuda.synchronize()
+            n = int(min(max(args.steps, 20), max(20, 0.15 / max((time.perf_counter() - t0) / 3, 1e-6))))
+            sec2, kf2, kb2, f2, b2 = time_steps(S, torch, s2, n, max(n // 5, 2))
+            per_steps = n
             w2, wl2 = s2["ws"], s2["wl"]
             wk = wl2.B * wl2.L * w2.size
             per[name] = {
@@ -259,7 +275,7 @@ def main():
                 "fwd_roofline_frac": roofline_entry(flops_forward(w2, wl2.B, wl2.L), f2)["frac"],
                 "bwd_roofline_frac": roofline_entry(flops_backward(w2, wl2.B, wl2.L), b2)["frac"],
                 "kernels": [w2.kernel_name(False, wl2.B, wl2.L + 1), w2.kernel_name(True, wl2.B, wl2.L + 1)],
-                "wordset_build_ms": round(s2["build_ms"], 3),
+                "wordset_build_ms": round(s2["build_ms"], 3), "steps": per_steps,
             }
             if name == "c5":
                 per[name]["peak_device_bytes"] = int(torch.cuda.max_memory_allocated() - base)
@@ -282,18 +298,18 @@ def main():
             S.sig_backward_windows(wsw, Xw, wins, cw, gw)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(10):
+            for _ in range(200):
                 cw = S.sig_forward_windows(wsw, Xw, wins)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
-            for _ in range(10):
+            for _ in range(200):
                 S.sig_backward_windows(wsw, Xw, wins, cw, gw)
             torch.cuda.synchronize()
             t2 = time.perf_counter()
             wk = Bw * Kw * lenw * wsw.size
             out["windows"] = {"workload": f"B={Bw} L={Lw} d={wsw.dim} |W|={wsw.size}, {Kw} sliding windows of {lenw} segments",
-                              "fwd_ms": round((t1 - t0) * 100, 4), "bwd_ms": round((t2 - t1) * 100, 4),
-                              "fwd_bwd_coeff_steps_per_s": round(wk / ((t2 - t0) / 10), 1),
+                              "fwd_ms": round((t1 - t0) * 5, 4), "bwd_ms": round((t2 - t1) * 5, 4),
+                              "fwd_bwd_coeff_steps_per_s": round(wk / ((t2 - t0) / 200), 1),
                               "note": "host clock, includes the per-call workspace allocation of the Python wrapper"}
         except Exception as e:                       # an optional extra must not take the benchmark line down
             out["windows"] = {"error": str(e)[:200]}
@@ -312,19 +328,19 @@ def main():
             S.sig_backward(wsl, Xl, cl, S.sig_logsig_backward(wsl, cl, gl))
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(10):
+            for _ in range(200):
                 cl = S.sig_forward(wsl, Xl)
                 lg = S.sig_logsig_forward(wsl, cl)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
-            for _ in range(10):
+            for _ in range(200):
                 S.sig_backward(wsl, Xl, cl, S.sig_logsig_backward(wsl, cl, gl))
             torch.cuda.synchronize()
             t2 = time.perf_counter()
             out["log_signature"] = {"workload": f"{wlh.name} shape, depth {wlh.depth}: {wsl.size} signature words for {lg.shape[1]} "
                                                 f"log-signature coordinates",
                                     "kernels": [wsl.kernel_name(False, wlh.B, wlh.L + 1), wsl.kernel_name(True, wlh.B, wlh.L + 1)],
-                                    "fwd_ms": round((t1 - t0) * 100, 4), "bwd_ms": round((t2 - t1) * 100, 4),
+                                    "fwd_ms": round((t1 - t0) * 5, 4), "bwd_ms": round((t2 - t1) * 5, 4),
                                     "note": "host clock, signature + tensor logarithm (forward) and their adjoints (backward)"}
         except Exception as e:
             out["log_signature"] = {"error": str(e)[:200]}
@@ -344,8 +360,8 @@ def main():
                 gp = torch.randn_like(cp)
                 S.sig_backward(wsp, Xp, cp, gp)
                 torch.cuda.synchronize()
-                S.sig_profile_enable(True)
-                for _ in range(5):
+                S.sig_profile_enable(True, channels=[2, 3])       # whole calls only
+                for _ in range(300):
                     S.sig_forward(wsp, Xp, out=cp)
                     S.sig_backward(wsp, Xp, cp, gp)
                 torch.cuda.synchronize()

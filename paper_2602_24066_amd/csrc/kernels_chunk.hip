@@ -201,28 +201,58 @@ __device__ __forceinline__ float word_product(const float* a, const float* b, co
     return acc;
 }
 
-// out[b] = a[b] (x) bfac[b] (x) c[b] in one pass (three time chunks, the usual count for long paths): a quad of
-// (a (x) b) (x) c is the quad of a (x) b plus, for every cut, the coefficient of a (x) b at the shared prefix times
-// the suffix quad of c.  The prefix coefficients are recomputed per quad (a few multiply-adds on cached operands),
-// which saves the intermediate array and one launch.
+// out[b] = a[b] (x) bfac[b] (x) c[b] in one pass (three time chunks, the usual count for long paths), without the
+// intermediate array and its launch:
+//     (a b c)(w) = c(w) + (a b)(w) + sum_{0 < l < n} (a b)(w_1..w_l) c(w_{l+1}..w_n),
+//     (a b)(w)   = a(w) + b(w)     + sum_{0 < k < n} a(w_1..w_k) b(w_{k+1}..w_n).
+// A workgroup takes 1,024 consecutive words of one length n (blockIdx.x runs over the lengths, each padded to whole
+// workgroups).  Their prefixes of length l are the 1,024 / d^(n-l) (at least one) consecutive words of that length,
+// so a(prefix) and (a b)(prefix) are computed once per workgroup into LDS; what a thread then reads per quad is
+// the three quads of w and, per cut, one suffix quad of b and one of c.
+constexpr int kProduct3Prefixes = 384;             // 256 + 64 + 16 + 4 + 1 + ... for d = 4; fewer for larger d
+
+__host__ __device__ inline int product3_blocks(const Levels& g, int n) { return ((g.ls[n + 1] - g.ls[n]) / 4 + 255) / 256; }
+
 __global__ __launch_bounds__(256) void chunk_product3_kernel(const float* __restrict__ a, const float* __restrict__ bfac,
                                                              const float* __restrict__ c, int64_t in_stride,
                                                              float* __restrict__ out, int64_t out_stride, Levels g)
 {
+    __shared__ float sA[kProduct3Prefixes], sAB[kProduct3Prefixes];
     const int64_t b = blockIdx.y;
-    const int o = 4 * (int)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (o >= g.W) return;
-    int n = 1;
-    while (o >= g.ls[n + 1]) ++n;
-    const int i = o - g.ls[n];
+    int blk = (int)blockIdx.x, n = 1;
+    while (n < g.N && blk >= product3_blocks(g, n)) { blk -= product3_blocks(g, n); ++n; }
+    const int words = g.ls[n + 1] - g.ls[n];
+    const int i0 = blk * 1024;                         // first word of the workgroup inside its length
     const float* pa = a + b * in_stride;
     const float* pb = bfac + b * in_stride;
     const float* pc = c + b * in_stride;
-    f4 acc = quad_product(pa, pb, g, n, i) + *(const f4*)(pc + g.ls[n] + i);
+    // prefixes of length l = 1 .. n - 1 of the words i0 .. i0 + 1023: cnt_l consecutive words from p0_l on
+    int off = 0;
     for (int l = 1; l < n; ++l) {
         const int sh = g.lb * (n - l);
-        const float ab = word_product(pa, pb, g, l, i >> sh);
-        acc += ab * *(const f4*)(pc + g.ls[n - l] + (i & ((1 << sh) - 1)));
+        const int p0 = i0 >> sh;
+        const int cnt = (1024 >> sh) > 0 ? (1024 >> sh) : 1;
+        const int have = g.ls[l + 1] - g.ls[l];
+        for (int t = threadIdx.x; t < cnt; t += blockDim.x)
+            if (p0 + t < have) {
+                sA[off + t] = pa[g.ls[l] + p0 + t];
+                sAB[off + t] = word_product(pa, pb, g, l, p0 + t);
+            }
+        off += cnt;
+    }
+    __syncthreads();
+    const int i = i0 + 4 * (int)threadIdx.x;
+    if (i >= words) return;
+    const int o = g.ls[n] + i;
+    f4 acc = (*(const f4*)(pa + o) + *(const f4*)(pb + o)) + *(const f4*)(pc + o);
+    off = 0;
+    for (int l = 1; l < n; ++l) {
+        const int sh = g.lb * (n - l);
+        const int pi = off + (i >> sh) - (i0 >> sh);
+        const int suffix = g.ls[n - l] + (i & ((1 << sh) - 1));
+        acc += sA[pi] * *(const f4*)(pb + suffix);
+        acc += sAB[pi] * *(const f4*)(pc + suffix);
+        off += (1024 >> sh) > 0 ? (1024 >> sh) : 1;
     }
     *(f4*)(out + b * out_stride + o) = acc;
 }
@@ -312,7 +342,10 @@ hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, c
         const int64_t W = g.W;
         const dim3 grid((unsigned)((W / 4 + 255) / 256), (unsigned)B);
         if (C == 3) {
-            chunk_product3_kernel<<<grid, 256, 0, stream>>>(Sc, Sc + W, Sc + 2 * (int64_t)W, (int64_t)C * W, coeffs_out, W, g);
+            unsigned blocks = 0;
+            for (int n = 1; n <= g.N; ++n) blocks += (unsigned)product3_blocks(g, n);
+            chunk_product3_kernel<<<dim3(blocks, (unsigned)B), 256, 0, stream>>>(Sc, Sc + W, Sc + 2 * (int64_t)W, (int64_t)C * W,
+                                                                               coeffs_out, W, g);
             return hipGetLastError();
         }
         const float* acc = Sc;                       // S_1 of every path, row stride C W
