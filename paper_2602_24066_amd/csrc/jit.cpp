@@ -349,9 +349,12 @@ std::string jit_backward_source(const WordSet& ws, const Plan& plan, int NW, int
 
 namespace {
 // Optional cache of compiled code objects on disk: with SIG_JIT_CACHE set to a directory, a code object is stored
-// there under a 64-bit hash of its source (which carries every specialisation) and of the compiler version, and later
+// there under a 64-bit hash of its source (which carries every specialisation), the compiler version and the compile
+// options, and later
 // processes load it instead of compiling.  Files are written under a temporary name and renamed, so concurrent
 // writers cannot leave a torn file; a file that fails to load is simply recompiled over.
+// stands for the option list of jit_compile in the file name hash: to be changed with it
+constexpr char kCompileOptionsTag[] = "gfx950 -O3 c++17 unsafe-fp-atomics no-packed-fp32 v1";
 std::string cache_file(const std::string& src)
 {
     const char* dir = std::getenv("SIG_JIT_CACHE");
@@ -364,6 +367,7 @@ std::string cache_file(const std::string& src)
     (void)hiprtcVersion(&major, &minor);
     mix((const char*)&major, sizeof major);
     mix((const char*)&minor, sizeof minor);
+    mix(kCompileOptionsTag, sizeof kCompileOptionsTag);
     mix(src.data(), src.size());
     char name[64];
     std::snprintf(name, sizeof name, "/sig_gfx950_%016llx.hsaco", (unsigned long long)h);
