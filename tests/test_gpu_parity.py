@@ -49,6 +49,14 @@ def test_small_cases_elementwise(case):
     check_parity(ws, W, kind, kw.get("depth"), X, G, what=f"small[{case}]")
 
 
+def d4_inputs(seed, B, L):
+    """Inputs for the register-resident d = 4 kernels: the monotone time channel of c2, and paths whose increments
+    change sign in every channel (iid; per-channel scales for longer paths), so that chunk-boundary adjoints and the
+    products in LDS see both signs everywhere."""
+    dists = ["time0", "iid"] + (["scaled"] if L >= 64 else [])
+    return [(dist, make_path(dist, seed + 7 * k, B, L, 4)) for k, dist in enumerate(dists)]
+
+
 # Time chunks (Chen's relation between chunk signatures): forced chunk counts, including chunk lengths that do not
 # divide L and a last chunk of a single segment; the automatic choice is exercised by the small batches below.
 @pytest.mark.parametrize("d,depth,B,L,chunks", [(4, 6, 3, 97, 3), (4, 6, 2, 65, 2), (4, 6, 1, 160, 5), (8, 5, 2, 100, 3),
@@ -59,14 +67,15 @@ def test_time_chunks(monkeypatch, d, depth, B, L, chunks):
     else:
         monkeypatch.delenv("SIG_CHUNKS", raising=False)
     ws, W = build_both("truncated", d, depth=depth)
-    X = make_path("time0" if d == 4 else "iid", 500 + L, B, L, d)
     G = make_grad_coeffs(600 + L, B, ws.size)
     lib = S.load_library()
     if chunks:
         assert lib.sig_forward_workspace_bytes(ws._h, B, L + 1) >= 2 * 4 * B * chunks * ws.size
     else:
         assert lib.sig_forward_workspace_bytes(ws._h, B, L + 1) > 0      # few paths: chunking is chosen by itself
-    check_parity(ws, W, "truncated", depth, X, G, what=f"chunks d={d} N={depth} L={L} C={chunks}")
+    inputs = d4_inputs(500 + L, B, L) if d == 4 else [("iid", make_path("iid", 500 + L, B, L, d))]
+    for dist, X in inputs:
+        check_parity(ws, W, "truncated", depth, X, G, what=f"chunks d={d} N={depth} L={L} C={chunks} {dist}")
 
 
 # d = 4 backward with one wavefront per (path, chunk) row, forced for batches that would not select it
@@ -78,9 +87,9 @@ def test_backward_one_wavefront_per_row(monkeypatch, B, L, chunks):
     else:
         monkeypatch.delenv("SIG_CHUNKS", raising=False)
     ws, W = build_both("truncated", 4, depth=6)
-    X = make_path("time0", 700 + L, B, L, 4)
     G = make_grad_coeffs(800 + L, B, ws.size)
-    check_parity(ws, W, "truncated", 6, X, G, what=f"tails B={B} L={L} C={chunks}")
+    for dist, X in d4_inputs(700 + L, B, L):
+        check_parity(ws, W, "truncated", 6, X, G, what=f"tails B={B} L={L} C={chunks} {dist}")
 
 
 # ... and its fused form: the 2, 4 or 8 chunks of a path in one workgroup, chunk signatures and boundary adjoints in
@@ -96,12 +105,12 @@ def test_backward_chunks_in_one_workgroup(monkeypatch, B, L, chunks):
         monkeypatch.delenv("SIG_BWD_TAILS", raising=False)
     monkeypatch.delenv("SIG_CHUNKS", raising=False)
     ws, W = build_both("truncated", 4, depth=6)
-    X = make_path("time0", 900 + L, B, L, 4)
     G = make_grad_coeffs(950 + L, B, ws.size)
     lib = S.load_library()
     gdx = (4 * B * L * 4 + 255) // 256 * 256
     assert lib.sig_backward_workspace_bytes(ws._h, B, L + 1) == gdx       # no chunk arrays in device memory
-    check_parity(ws, W, "truncated", 6, X, G, what=f"fused tails B={B} L={L} C={chunks}")
+    for dist, X in d4_inputs(900 + L, B, L):
+        check_parity(ws, W, "truncated", 6, X, G, what=f"fused tails B={B} L={L} C={chunks} {dist}")
 
 
 # forward with the 2 or 4 chunks of a path in one workgroup (d = 4, depth 6), forced for any batch size; the last
@@ -116,9 +125,9 @@ def test_forward_chunks_in_one_workgroup(monkeypatch, B, L, chunks):
     monkeypatch.delenv("SIG_CHUNKS", raising=False)
     ws, W = build_both("truncated", 4, depth=6)
     assert ws.kernel_name(False, B, L + 1) == "trunc_tails_fwd_kernel"
-    X = make_path("time0", 1300 + L, B, L, 4)
     G = make_grad_coeffs(1350 + L, B, ws.size)
-    check_parity(ws, W, "truncated", 6, X, G, what=f"fused forward B={B} L={L} C={chunks}")
+    for dist, X in d4_inputs(1300 + L, B, L):
+        check_parity(ws, W, "truncated", 6, X, G, what=f"fused forward B={B} L={L} C={chunks} {dist}")
 
 
 def test_forward_fused_and_four_wavefront_kernels_agree(monkeypatch):
@@ -371,7 +380,7 @@ def test_windows(case):
     words = random_prefix_closed_words(400 + case, d, kw["n_words"], kw["max_len"]) if kind == "words" else None
     ws, W = build_both(kind, d, depth=kw.get("depth"), weights=kw.get("weights"), cutoff=kw.get("cutoff"), words=words)
     B, L = 5, 40
-    X = make_path("time0" if kind == "truncated" and d == 4 else "iid", 410 + case, B, L, d)
+    X = make_path("iid", 410 + case, B, L, d)
     windows = [(0, L), (0, 1), (0, 7), (0, 23), (5, 15), (10, 20), (15, 25), (39, 40), (17, 17), (3, 38), (5, 15)]
     K = len(windows)
     G = make_grad_coeffs(420 + case, B * K, ws.size).reshape(B, K, ws.size)

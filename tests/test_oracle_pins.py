@@ -398,6 +398,49 @@ def test_backward_words_matches_finite_differences_and_dense():
     np.testing.assert_allclose(O.backward_dense(X.astype(np.float32), N, Gd), ana, rtol=1e-10, atol=1e-12)
 
 
+def _fd_coordinates_and_directions(fun, ana, X, n_coord, n_dir, seed, h=2.0 ** -12):
+    """Central differences of `fun` at `n_coord` random coordinates and along `n_dir` random directions of X against
+    the analytic gradient `ana`; X lies on a grid on which the +-h steps are exact in fp32."""
+    rng = np.random.default_rng(seed)
+    flat = rng.choice(X.size, size=n_coord, replace=False)
+    scale = np.abs(ana).max()
+    for f in flat:
+        idx = np.unravel_index(f, X.shape)
+        Xp = X.copy(); Xp[idx] += h
+        Xm = X.copy(); Xm[idx] -= h
+        num = (fun(Xp) - fun(Xm)) / (2 * h)
+        assert abs(num - ana[idx]) <= 2e-6 * max(scale, abs(num)), (idx, num, ana[idx])
+    for _ in range(n_dir):
+        V = rng.integers(-1, 2, size=X.shape).astype(np.float64)     # +-h V stays on the grid
+        num = (fun(X + h * V) - fun(X - h * V)) / (2 * h)
+        dot = float((ana * V).sum())
+        assert abs(num - dot) <= 2e-6 * max(scale * np.sqrt(V.size), abs(num)), (num, dot)
+
+
+def test_backward_finite_differences_on_c2_shaped_case():
+    """The c2 word set (d = 4, depth 6, 5,460 words, time channel) on a small batch: 64 random coordinates and 8 random
+    directions of the path against central differences of the dense forward oracle (Proposition 4.1)."""
+    d, N, B, L = 4, 6, 2, 24
+    X = np.round(make_path("time0", 96, B, L, d).astype(np.float64) * 128) / 128
+    G = np.random.default_rng(6).standard_normal((B, sum(d ** n for n in range(1, N + 1))))
+    ana = O.backward_dense(X.astype(np.float32), N, G)
+    fun = lambda Y: float((O.forward_dense(Y.astype(np.float32), N) * G).sum())
+    _fd_coordinates_and_directions(fun, ana, X, 64, 8, seed=7)
+
+
+def test_backward_finite_differences_on_c4a_shaped_case():
+    """The c4a word set (d = 6, weights (1,1,2,2,3,3), degree <= 8: 5,754 words up to length 8) on a small batch, per-word
+    route: 64 random coordinates and 8 random directions against central differences of the per-word forward oracle."""
+    d, B, L = 6, 2, 12
+    C = O.anisotropic_words(d, (1.0, 1.0, 2.0, 2.0, 3.0, 3.0), 8.0)
+    assert len(C) == 5754
+    X = _grid_path(97, B, L, d)
+    G = np.random.default_rng(8).standard_normal((B, len(C)))
+    ana = O.backward_words(X.astype(np.float32), C, G)
+    fun = lambda Y: float((O.forward_words(Y.astype(np.float32), C) * G).sum())
+    _fd_coordinates_and_directions(fun, ana, X, 64, 8, seed=9)
+
+
 def test_backward_level1_closed_form():
     # L = sum_i c_i S(i) = c . (X_L - X_0): gradient is -c at the first point, +c at the last, 0 between
     d, N, L = 3, 3, 6
@@ -543,6 +586,9 @@ def test_lyndon_words_and_tensor_log():
         for n in range(1, N + 1):
             witt = sum(mobius(k) * d ** (n // k) for k in range(1, n + 1) if n % k == 0) // n
             assert sum(1 for w in lyn if len(w) == n) == witt
+    # the orientation of the definition (a word strictly smaller than all of its proper rotations), as a literal list
+    assert O.lyndon_words(2, 4) == [(0,), (1,), (0, 1), (0, 0, 1), (0, 1, 1), (0, 0, 0, 1), (0, 0, 1, 1), (0, 1, 1, 1)]
+    assert O.lyndon_words(3, 2) == [(0,), (1,), (2,), (0, 1), (0, 2), (1, 2)]
     d, N = 3, 4
     lyn = O.lyndon_words(d, N)
     a = np.array([0.3, -0.7, 0.2])
@@ -560,7 +606,9 @@ def test_lyndon_words_and_tensor_log():
             assert abs(L2[k] - (af[w[0]] + bf[w[0]])) <= 1e-12
         if len(w) == 2:
             i, j = w
+            assert i < j                                   # a Lyndon word of length 2 is increasing
             assert abs(L2[k] - 0.5 * (af[i] * bf[j] - af[j] * bf[i])) <= 1e-12
+    assert sorted(w for w in lyn if len(w) == 2) == [(i, j) for i in range(d) for j in range(i + 1, d)]
     # exp(log S) = S on a longer path
     X = make_path("iid", 99, 1, 7, d)
     Sd = np.concatenate([[1.0], O.forward_dense(X, N)[0]])
