@@ -1,16 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the signature hot path on one MI355X.
 
-A step = sig_forward + sig_backward over one batch of the headline workload (c2: B=256, L=256, d=4,
-depth 6, 5460 coefficients; synthetic random-walk paths with a time channel).  All buffers live in HBM
-before the timed region; nothing is allocated inside it.
+A step = sig_forward + sig_backward over one batch of the headline workload, the largest configuration: c5
+(B=64, L=4096, d=16, depth 4, 69,904 coefficients; synthetic AR(1) paths).  All buffers live in HBM before the
+timed region; nothing is allocated inside it.
 
 Prints ONE JSON line:
   value        coefficient-steps/s for forward + backward = B * L * |W| / (time of one step)
-  roofline     the dominant kernel (backward main kernel) against the FP32 vector peak: algorithmic
-               flops per launch / average kernel duration measured with HIP events in the timed region
+  roofline     the dominant kernel (backward main kernel) against the FP32 peak: algorithmic flops per launch /
+               average kernel duration measured with HIP events in the timed region
   cpu_baseline the fp64 oracle timed on the host cores on a bounded sample of the same workload
-  per_workload forward / backward GPU times (whole call) and roofline fractions of all six workloads
+  errors       forward error per word length and gradient error of this run's GPU results against the oracle on
+               the same sample (the measures the parity tests use)
+  per_workload the same for all six workloads: GPU times (whole call and main kernel), roofline fractions,
+               errors against the oracle, oracle timing
 """
 import argparse
 import json
@@ -22,8 +25,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_FP32_VECTOR_TFLOPS = 157.3     # 256 CU x 4 SIMD x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
-HEADLINE = "c2"
+PEAK_FP32_TFLOPS = 157.3            # 256 CU x 4 SIMD x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz = dense fp32 MFMA peak
+HBM_PEAK_GBS = 8000.0
+HEADLINE = "c5"
+ALL = ("c1", "c2", "c3", "c4a", "c4b", "c5")
+# paths handed to the oracle per workload (the first n of the batch): about 15 s of host work for c5, 1-3 s for the others
+CPU_SAMPLE = {"c1": 32, "c2": 256, "c3": 16, "c4a": 16, "c4b": 16, "c5": 16}
 
 
 def flops_forward(ws, B, L):
@@ -39,9 +46,13 @@ def flops_backward(ws, B, L):
     return 2.0 * (3.0 * nw + 4.5 * (fmin - nw)) * B * L
 
 
-def WORKLOADS_REF_get():
-    from sig_workloads import WORKLOADS
-    return WORKLOADS
+def bytes_backward(ws, B, L, d):
+    """Algorithmic HBM bytes of one backward call: path and both coefficient arrays read, the gradient written."""
+    return 4.0 * B * (L + 1) * d + 8.0 * B * ws.size + 4.0 * B * (L + 1) * d
+
+
+def bytes_forward(ws, B, L, d):
+    return 4.0 * B * (L + 1) * d + 4.0 * B * ws.size
 
 
 def setup(name, S, torch):
@@ -61,7 +72,7 @@ def setup(name, S, torch):
     G = make_grad_coeffs(wl.seed, wl.B, ws.size)
     lib = S.load_library()
     st = {
-        "wl": wl, "ws": ws, "X": X, "G": G, "build_ms": build_ms,
+        "wl": wl, "ws": ws, "X": X, "G": G, "build_ms": build_ms, "words": words,
         "path": torch.from_numpy(X).cuda(),
         "grad": torch.from_numpy(G).cuda(),
         "coeffs": torch.empty((wl.B, ws.size), dtype=torch.float32, device="cuda"),
@@ -69,6 +80,7 @@ def setup(name, S, torch):
     }
     nf = int(lib.sig_forward_workspace_bytes(ws._h, wl.B, wl.L + 1))
     nb = int(lib.sig_backward_workspace_bytes(ws._h, wl.B, wl.L + 1))
+    st["workspace_bytes"] = [nf, nb]
     st["wf"] = torch.empty(max(nf, 256), dtype=torch.uint8, device="cuda")
     st["wb"] = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
     assert st["wf"].data_ptr() % 256 == 0 and st["wb"].data_ptr() % 256 == 0
@@ -127,69 +139,116 @@ def time_steps(S, torch, st, steps, warmup):
 
 
 def roofline_entry(flops, ms, kernel=""):
-    """Algorithmic flops per launch over the measured kernel duration.  The cascade kernels for full truncations issue
-    most of their multiply-adds as fp32 matrix-core instructions (dense fp32 MFMA peak = FP32 vector peak = 157.3
-    TFLOP/s); the d = 4 and d = 8 backward kernels, the run-time specialised and the table-driven kernels use the vector
-    ALU only."""
+    """Algorithmic flops per launch over the measured kernel duration.  The kernels for full truncations issue their
+    leaf-level multiply-adds as fp32 matrix-core instructions (dense fp32 MFMA peak = FP32 vector peak = 157.3
+    TFLOP/s); the run-time specialised and the table-driven kernels use the vector ALU only."""
     ach = flops / (ms * 1e-3) / 1e12
-    on_matrix_cores = kernel.startswith("trunc_") and not kernel.startswith(("trunc_tails_bwd", "trunc_node_bwd"))
+    on_matrix_cores = kernel.startswith("trunc_")
     return {"bound": "mfma" if on_matrix_cores else "alu", "achieved": round(ach, 3),
-            "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_FP32_VECTOR_TFLOPS, 4),
+            "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_FP32_TFLOPS, 4),
             "traffic": None}
 
 
-def measured_traffic(kernel, workload):
-    """HBM bytes per launch of `kernel` on `workload` from the committed rocprofv3 counter runs (FETCH_SIZE and
-    WRITE_SIZE, scaled by a copy kernel of known size); None when that pair has not been measured."""
-    path = os.path.join(ROOT, "paper_2602_24066_amd", "measured_traffic.json")
-    try:
-        with open(path) as f:
-            table = json.load(f)
-    except OSError:
+def counter_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` on `workload` from the rocprofv3 counter runs summarised under profiles/
+    (FETCH_SIZE and WRITE_SIZE of a run of this program, scaled by a copy kernel of known size); None when that
+    pair has no entry.  Counters cannot be collected from inside the timed run."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
         return None
+    with open(path) as f:
+        table = json.load(f)
     for row in table.get("kernels", []):
         if row["workload"] == workload and kernel.startswith(row["kernel_prefix"]):
             return row["hbm_bytes_per_launch"]
     return None
 
 
-def cpu_baseline(st, sample_paths, budget_s=12.0):
-    """The oracle as it stands (fp64 dense tensor algebra, one path per OpenMP thread) on the first `sample_paths`
-    paths, repeated until about `budget_s` seconds of wall-clock have been spent (at least once)."""
+def oracle_words(st):
+    from oracle import sig_oracle as O
+    wl = st["wl"]
+    if wl.kind == "truncated":
+        return O.truncated_words(wl.d, wl.depth)
+    if wl.kind == "anisotropic":
+        return O.anisotropic_words(wl.d, wl.weights, wl.cutoff)
+    return O.prefix_closure(st["words"])
+
+
+def oracle_check(st, n_paths):
+    """The oracle as it stands (fp64; dense tensor algebra for truncations, word by word for the other sets; one path
+    per OpenMP thread) on the first `n_paths` paths of the batch, timed once after a one-path warm-up; and the errors
+    of the GPU results in st["coeffs"] / st["gpath"] against it.  Returns (cpu_baseline dict, errors dict)."""
     import numpy as np
     from oracle import sig_oracle as O
     wl, ws = st["wl"], st["ws"]
-    X = np.ascontiguousarray(st["X"][:sample_paths])
-    G = st["G"][:sample_paths].astype(np.float64)
-    O.forward_dense(X[:1], wl.depth)                       # load + warm
-    tf = tb = 0.0
-    reps = 0
-    while reps == 0 or (tf + tb < budget_s and reps < 200):
-        t0 = time.perf_counter()
-        O.forward_dense(X, wl.depth)
-        t1 = time.perf_counter()
-        O.backward_dense(X, wl.depth, G)
-        t2 = time.perf_counter()
-        tf, tb, reps = tf + (t1 - t0), tb + (t2 - t1), reps + 1
-    work = reps * sample_paths * wl.L * ws.size
-    return {"value": round(work / (tf + tb), 1), "unit": "coefficient-steps/s (forward + backward)", "cores": O.threads(),
-            "kind": "oracle",
-            "sample": f"{sample_paths} of {wl.B} paths of {wl.name}, full length L={wl.L}, {reps} repetitions; fp64 dense "
-                      f"tensor-algebra forward {tf:.2f} s + reverse-mode backward {tb:.2f} s in total",
-            "forward_value": round(work / tf, 1)}
+    n = min(n_paths, wl.B)
+    X = np.ascontiguousarray(st["X"][:n])
+    G = st["G"][:n].astype(np.float64)
+    W = oracle_words(st)
+    dense = wl.kind == "truncated"
+    fwd = (lambda x: O.forward_dense(x, wl.depth)) if dense else (lambda x: O.forward_words(x, W))
+    bwd = (lambda x, g: O.backward_dense(x, wl.depth, g)) if dense else (lambda x, g: O.backward_words(x, W, g))
+    fwd(X[:1, :min(wl.L, 16) + 1])                       # load the library, start the thread pool
+    t0 = time.perf_counter()
+    ref = fwd(X)
+    t1 = time.perf_counter()
+    gref = bwd(X, G)
+    t2 = time.perf_counter()
+    work = n * wl.L * ws.size
+    cpu = {"value": round(work / (t2 - t0), 1), "unit": "coefficient-steps/s (forward + backward)",
+           "cores": min(O.threads(), n), "kind": "oracle",
+           "sample": f"first {n} of {wl.B} paths of {wl.name}, full length L={wl.L}, one run; fp64 "
+                     + ("dense tensor algebra" if dense else "word-by-word evaluation")
+                     + f": forward {t1 - t0:.2f} s + reverse-mode backward {t2 - t1:.2f} s",
+           "forward_value": round(work / (t1 - t0), 1)}
+    lengths = np.array([len(w) for w in W])
+    c = st["coeffs"][:n].cpu().numpy()
+    g = st["gpath"][:n].cpu().numpy()
+    ferr = O.level_errors(c, ref, lengths)
+    gerr = O.grad_errors(g, gref)
+    errors = {"paths_checked": n,
+              "forward_error_per_level": {str(k): float(f"{v:.3e}") for k, v in ferr.items()},
+              "forward_tolerance": 1e-4,
+              "gradient_error_max": float(f"{float(gerr.max()):.3e}"), "gradient_tolerance": 1e-3,
+              "within_tolerance": bool(max(ferr.values()) <= 1e-4 and gerr.max() <= 1e-3)}
+    return cpu, errors
+
+
+def workload_row(S, torch, st, sec, kf, kb, cf, cb, steps):
+    wl, ws = st["wl"], st["ws"]
+    wk = wl.B * wl.L * ws.size
+    kn_f, kn_b = ws.kernel_name(False, wl.B, wl.L + 1), ws.kernel_name(True, wl.B, wl.L + 1)
+    ff, fb = flops_forward(ws, wl.B, wl.L), flops_backward(ws, wl.B, wl.L)
+    bb = bytes_backward(ws, wl.B, wl.L, wl.d)
+    return {
+        "coeffs": ws.size, "fwd_ms": round(cf, 4), "bwd_ms": round(cb, 4),
+        "fwd_main_kernel_ms": round(kf, 4), "bwd_main_kernel_ms": round(kb, 4),
+        "fwd_coeff_steps_per_s": round(wk / (cf * 1e-3), 1),
+        "fwd_bwd_coeff_steps_per_s": round(wk / ((cf + cb) * 1e-3), 1),
+        "fwd_roofline_frac": roofline_entry(ff, cf)["frac"],
+        "bwd_roofline_frac": roofline_entry(fb, cb)["frac"],
+        "fwd_main_kernel_roofline_frac": roofline_entry(ff, kf)["frac"],
+        "bwd_main_kernel_roofline_frac": roofline_entry(fb, kb)["frac"],
+        # algorithmic bytes of the backward call over its GPU time, against the 8 TB/s of HBM3E
+        "bwd_algorithmic_bytes": int(bb), "bwd_hbm_gbs_algorithmic": round(bb / (cb * 1e-3) / 1e9, 1),
+        "bwd_hbm_bytes_counters": counter_traffic(kn_b, wl.name),
+        "kernels": [kn_f, kn_b], "workspace_bytes": st["workspace_bytes"],
+        "wordset_build_ms": round(st["build_ms"], 3), "steps": steps,
+    }
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # the clock of an idle MI355X takes some tens of milliseconds of load to settle (c2: 0.105 ms per step over 50 steps,
-    # 0.094 ms from about 1,000 steps on), so the defaults time a tenth of a second after a fifth of that as warm-up
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=200)
+    # the clock of an idle MI355X takes some tens of milliseconds of load to settle; a c5 step takes 2-3 ms, so the
+    # default times about a second of work after a fifth of that as warm-up
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=80)
     ap.add_argument("--workload", default=HEADLINE)
-    ap.add_argument("--no-others", action="store_true", help="skip the per-workload table")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
-    ap.add_argument("--cpu-sample", type=int, default=0, help="paths given to the oracle (0 = the whole batch)")
+    ap.add_argument("--only", default="", help="comma-separated workloads for the per-workload table (default: all six)")
+    ap.add_argument("--no-others", action="store_true", help="skip the per-workload table and the extras")
+    ap.add_argument("--no-extras", action="store_true", help="skip windows, log-signature and the paper's table shapes")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (timing and errors)")
     ap.add_argument("--calibrate", action="store_true",
                     help="after the timed region launch a plain 256 MiB copy kernel three times (reference for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -209,20 +268,23 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    torch.cuda.reset_peak_memory_stats()
+    base_mem = torch.cuda.memory_allocated()
     st = setup(args.workload, S, torch)
     wl, ws = st["wl"], st["ws"]
     sec, ms_f, ms_b, call_f, call_b = time_steps(S, torch, st, args.steps, args.warmup)
+    peak_mem = int(torch.cuda.max_memory_allocated() - base_mem)
     work = wl.B * wl.L * ws.size
     ff, fb = flops_forward(ws, wl.B, wl.L), flops_backward(ws, wl.B, wl.L)
     kn_f, kn_b = ws.kernel_name(False, wl.B, wl.L + 1), ws.kernel_name(True, wl.B, wl.L + 1)
     rf, rb = roofline_entry(ff, ms_f, kn_f), roofline_entry(fb, ms_b, kn_b)
-    dominant = rb if ms_b >= ms_f else rf
-    dominant = dict(dominant)
+    dominant = dict(rb if ms_b >= ms_f else rf)
     dominant["kernel"] = kn_b if ms_b >= ms_f else kn_f
     dominant["kernel_ms"] = round(max(ms_b, ms_f), 4)
     dominant["algorithmic_flops_per_launch"] = fb if ms_b >= ms_f else ff
-    dominant["traffic"] = measured_traffic(dominant["kernel"], wl.name)
-
+    dominant["traffic"] = counter_traffic(dominant["kernel"], wl.name)
+    dominant["traffic_source"] = ("profiles/hbm_traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this program"
+                                  if dominant["traffic"] is not None else None)
     # plain v_fma_f32 rate of this chip, measured in the same run (register-only kernel, 32 wavefronts per compute unit):
     # the roof for vector code that does not use packed FP32
     dominant["measured_unpacked_fma_tflops"] = round(S.sig_probe_fma_tflops(), 1)
@@ -245,16 +307,31 @@ def main():
                     "roofline_frac": roofline_entry(ff, call_f)["frac"], "main_kernel_roofline_frac": rf["frac"]},
         "backward": {"kernel": kn_b, "kernel_ms": round(ms_b, 4), "call_ms": round(call_b, 4),
                      "coeff_steps_per_s": round(work / (call_b * 1e-3), 1),
-                     "roofline_frac": roofline_entry(fb, call_b)["frac"], "main_kernel_roofline_frac": rb["frac"]},
+                     "roofline_frac": roofline_entry(fb, call_b)["frac"], "main_kernel_roofline_frac": rb["frac"],
+                     "algorithmic_bytes": int(bytes_backward(ws, wl.B, wl.L, wl.d)),
+                     "hbm_gbs_algorithmic": round(bytes_backward(ws, wl.B, wl.L, wl.d) / (call_b * 1e-3) / 1e9, 1),
+                     "hbm_peak_gbs": HBM_PEAK_GBS},
         "roofline": dominant,
+        "memory": {"peak_device_bytes": peak_mem, "mem_out_bytes": 4 * wl.B * ws.size,
+                   "note": "inputs, outputs and workspaces of forward + backward held at once"},
     }
+    head_row = workload_row(S, torch, st, sec, ms_f, ms_b, call_f, call_b, args.steps)
+    if not args.no_cpu:
+        cpu, errs = oracle_check(st, CPU_SAMPLE[wl.name])
+        out["cpu_baseline"] = cpu
+        out["errors"] = errs
+        head_row["cpu_baseline"], head_row["errors"] = cpu, errs
 
     if not args.no_others:
         per = {}
-        for name in ("c1", "c2", "c3", "c4a", "c4b", "c5"):
+        names = [n for n in (args.only.split(",") if args.only else ALL) if n]
+        for name in names:
+            if name == wl.name:
+                per[name] = head_row
+                continue
             torch.cuda.reset_peak_memory_stats()
             base = torch.cuda.memory_allocated()
-            s2 = st if name == args.workload else setup(name, S, torch)
+            s2 = setup(name, S, torch)
             # about 0.15 s of work per measuring pass (the clock settles first): 20 to --steps steps
             step(S, s2)                                  # first call: run-time compilation, kernel attributes
             torch.cuda.synchronize()
@@ -264,118 +341,102 @@ def main():
             torch.cuda.synchronize()
             n = int(min(max(args.steps, 20), max(20, 0.15 / max((time.perf_counter() - t0) / 3, 1e-6))))
             sec2, kf2, kb2, f2, b2 = time_steps(S, torch, s2, n, max(n // 5, 2))
-            per_steps = n
-            w2, wl2 = s2["ws"], s2["wl"]
-            wk = wl2.B * wl2.L * w2.size
-            per[name] = {
-                "coeffs": w2.size, "fwd_ms": round(f2, 4), "bwd_ms": round(b2, 4),
-                "fwd_main_kernel_ms": round(kf2, 4), "bwd_main_kernel_ms": round(kb2, 4),
-                "fwd_coeff_steps_per_s": round(wk / (f2 * 1e-3), 1),
-                "fwd_bwd_coeff_steps_per_s": round(wk / ((f2 + b2) * 1e-3), 1),
-                "fwd_roofline_frac": roofline_entry(flops_forward(w2, wl2.B, wl2.L), f2)["frac"],
-                "bwd_roofline_frac": roofline_entry(flops_backward(w2, wl2.B, wl2.L), b2)["frac"],
-                "kernels": [w2.kernel_name(False, wl2.B, wl2.L + 1), w2.kernel_name(True, wl2.B, wl2.L + 1)],
-                "wordset_build_ms": round(s2["build_ms"], 3), "steps": per_steps,
-            }
-            if name == "c5":
-                per[name]["peak_device_bytes"] = int(torch.cuda.max_memory_allocated() - base)
-                per[name]["mem_out_bytes"] = 4 * wl2.B * w2.size
-            if s2 is not st:
-                del s2
-                torch.cuda.empty_cache()
+            per[name] = workload_row(S, torch, s2, sec2, kf2, kb2, f2, b2, n)
+            per[name]["peak_device_bytes"] = int(torch.cuda.max_memory_allocated() - base)
+            per[name]["mem_out_bytes"] = 4 * s2["wl"].B * s2["ws"].size
+            if not args.no_cpu:
+                per[name]["cpu_baseline"], per[name]["errors"] = oracle_check(s2, CPU_SAMPLE[name])
+            del s2
+            torch.cuda.empty_cache()
         out["per_workload"] = per
 
-        # signatures over windows (Section 5 of the paper): 32 paths of 1,024 segments, 64 sliding windows of 128
-        # segments each, the headline word set; all 2,048 (path, window) pairs advance in one launch
-        try:
-            from sig_workloads import make_path
-            wsw = st["ws"] if args.workload == HEADLINE else setup(HEADLINE, S, torch)["ws"]
-            Bw, Lw, Kw, lenw = 32, 1024, 64, 128
-            Xw = torch.from_numpy(make_path("time0", 77, Bw, Lw, wsw.dim)).cuda()
-            wins = [(k * (Lw - lenw) // (Kw - 1), k * (Lw - lenw) // (Kw - 1) + lenw) for k in range(Kw)]
-            cw = S.sig_forward_windows(wsw, Xw, wins)
-            gw = torch.randn_like(cw)
-            S.sig_backward_windows(wsw, Xw, wins, cw, gw)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(200):
-                cw = S.sig_forward_windows(wsw, Xw, wins)
-            torch.cuda.synchronize()
-            t1 = time.perf_counter()
-            for _ in range(200):
-                S.sig_backward_windows(wsw, Xw, wins, cw, gw)
-            torch.cuda.synchronize()
-            t2 = time.perf_counter()
-            wk = Bw * Kw * lenw * wsw.size
-            out["windows"] = {"workload": f"B={Bw} L={Lw} d={wsw.dim} |W|={wsw.size}, {Kw} sliding windows of {lenw} segments",
-                              "fwd_ms": round((t1 - t0) * 5, 4), "bwd_ms": round((t2 - t1) * 5, 4),
-                              "fwd_bwd_coeff_steps_per_s": round(wk / ((t2 - t0) / 200), 1),
-                              "note": "host clock, includes the per-call workspace allocation of the Python wrapper"}
-        except Exception as e:                       # an optional extra must not take the benchmark line down
-            out["windows"] = {"error": str(e)[:200]}
+    if not args.no_others and not args.no_extras:
+        from sig_workloads import WORKLOADS, make_path, workload_path
+        lib = S.load_library()
+        c2 = WORKLOADS["c2"]
 
-        # log-signature (Section 3.3) on the headline shape: signature on the reduced word set (every word shorter than
-        # the depth + the Lyndon words of full length), tensor logarithm word by word, and back
-        try:
-            from sig_workloads import workload_path as workload_path_ref
-            wlh = WORKLOADS_REF_get()[HEADLINE]
-            wsl = S.sig_wordset_build_logsig(wlh.d, wlh.depth)
-            wsl.upload("cuda:0")
-            Xl = torch.from_numpy(workload_path_ref(wlh)).cuda()
-            cl = S.sig_forward(wsl, Xl)
-            lg = S.sig_logsig_forward(wsl, cl)
-            gl = torch.randn_like(lg)
-            S.sig_backward(wsl, Xl, cl, S.sig_logsig_backward(wsl, cl, gl))
+        def gpu_ms(fn, reps=200):
+            """Average GPU time of fn() over `reps` back-to-back calls, by events on the current stream."""
+            fn()
             torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(200):
-                cl = S.sig_forward(wsl, Xl)
-                lg = S.sig_logsig_forward(wsl, cl)
-            torch.cuda.synchronize()
-            t1 = time.perf_counter()
-            for _ in range(200):
-                S.sig_backward(wsl, Xl, cl, S.sig_logsig_backward(wsl, cl, gl))
-            torch.cuda.synchronize()
-            t2 = time.perf_counter()
-            out["log_signature"] = {"workload": f"{wlh.name} shape, depth {wlh.depth}: {wsl.size} signature words for {lg.shape[1]} "
-                                                f"log-signature coordinates",
-                                    "kernels": [wsl.kernel_name(False, wlh.B, wlh.L + 1), wsl.kernel_name(True, wlh.B, wlh.L + 1)],
-                                    "fwd_ms": round((t1 - t0) * 5, 4), "bwd_ms": round((t2 - t1) * 5, 4),
-                                    "note": "host clock, signature + tensor logarithm (forward) and their adjoints (backward)"}
-        except Exception as e:
-            out["log_signature"] = {"error": str(e)[:200]}
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            e1.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        # signatures over windows (Section 5 of the paper): 32 paths of 1,024 segments, the c2 word set; 64 sliding
+        # windows of 128 segments, and 64 expanding windows (0, 16 k); all (path, window) pairs advance in one launch
+        wsw = S.sig_wordset_build_truncated(c2.d, c2.depth)
+        wsw.upload("cuda:0")
+        Bw, Lw, Kw, lenw = 32, 1024, 64, 128
+        Xw = torch.from_numpy(make_path("iid", 77, Bw, Lw, wsw.dim)).cuda()
+        shapes = {"sliding": [(k * (Lw - lenw) // (Kw - 1), k * (Lw - lenw) // (Kw - 1) + lenw) for k in range(Kw)],
+                  "expanding": [(0, (k + 1) * (Lw // Kw)) for k in range(Kw)]}
+        out["windows"] = {"workload": f"B={Bw} L={Lw} d={wsw.dim} |W|={wsw.size}, {Kw} windows"}
+        for kind, wins in shapes.items():
+            plan = S.WindowPlan(wsw, Xw, wins)
+            gw = torch.randn((Bw, Kw, wsw.size), device="cuda")
+            tf = gpu_ms(lambda: plan.forward())
+            tb = gpu_ms(lambda: plan.backward(gw))
+            seg = sum(r - l for l, r in wins)
+            out["windows"][kind] = {"fwd_ms": round(tf, 4), "bwd_ms": round(tb, 4),
+                                    "fwd_bwd_coeff_steps_per_s": round(Bw * seg * wsw.size / ((tf + tb) * 1e-3), 1)}
+
+        # log-signature (Section 3.3) on the c2 shape: signature on the word set of the Lyndon words' factors, tensor
+        # logarithm word by word, and back
+        wsl = S.sig_wordset_build_logsig(c2.d, c2.depth)
+        wsl.upload("cuda:0")
+        Xl = torch.from_numpy(workload_path(c2)).cuda()
+        cl = S.sig_forward(wsl, Xl)
+        lg = S.sig_logsig_forward(wsl, cl)
+        gl = torch.randn_like(lg)
+        wfl = torch.empty(max(int(lib.sig_forward_workspace_bytes(wsl._h, c2.B, c2.L + 1)), 256), dtype=torch.uint8, device="cuda")
+        wbl = torch.empty(max(int(lib.sig_backward_workspace_bytes(wsl._h, c2.B, c2.L + 1)), 256), dtype=torch.uint8, device="cuda")
+        gpl = torch.empty_like(Xl)
+
+        def logsig_fwd():
+            S.sig_forward(wsl, Xl, out=cl, workspace=wfl)
+            return S.sig_logsig_forward(wsl, cl)
+
+        def logsig_bwd():
+            S.sig_backward(wsl, Xl, cl, S.sig_logsig_backward(wsl, cl, gl), out=gpl, workspace=wbl)
+
+        out["log_signature"] = {"workload": f"c2 shape, depth {c2.depth}: {wsl.size} signature words for {lg.shape[1]} "
+                                            f"log-signature coordinates",
+                                "kernels": [wsl.kernel_name(False, c2.B, c2.L + 1), wsl.kernel_name(True, c2.B, c2.L + 1)],
+                                "fwd_ms": round(gpu_ms(logsig_fwd), 4), "bwd_ms": round(gpu_ms(logsig_bwd), 4),
+                                "note": "GPU time, signature + tensor logarithm (forward) and their adjoints (backward)"}
 
         # shapes of the paper's own timing table (Section 5, Table 1: training step = forward + backward, float32,
         # one H200): synthetic random walks of the same shape; the paper's figure is context, another machine's
-        try:
-            from sig_workloads import make_path as make_path_ref
-            table = {}
-            for (Bp, Mp, dp, Np, paper_us) in [(32, 100, 6, 4, 207.52), (32, 100, 6, 5, 555.63), (32, 100, 6, 6, 3360.0),
-                                               (64, 1000, 4, 6, 6450.0), (1, 200, 10, 4, 320.35),
-                                               (256, 200, 10, 4, 9830.0)]:
-                wsp = S.sig_wordset_build_truncated(dp, Np)
-                wsp.upload("cuda:0")
-                Xp = torch.from_numpy(make_path_ref("iid", 7, Bp, Mp - 1, dp)).cuda()
-                cp = S.sig_forward(wsp, Xp)
-                gp = torch.randn_like(cp)
+        table = {}
+        for (Bp, Mp, dp, Np, paper_us) in [(32, 100, 6, 4, 207.52), (32, 100, 6, 5, 555.63), (32, 100, 6, 6, 3360.0),
+                                           (64, 1000, 4, 6, 6450.0), (1, 200, 10, 4, 320.35),
+                                           (256, 200, 10, 4, 9830.0)]:
+            wsp = S.sig_wordset_build_truncated(dp, Np)
+            wsp.upload("cuda:0")
+            Xp = torch.from_numpy(make_path("iid", 7, Bp, Mp - 1, dp)).cuda()
+            cp = S.sig_forward(wsp, Xp)
+            gp = torch.randn_like(cp)
+            S.sig_backward(wsp, Xp, cp, gp)
+            torch.cuda.synchronize()
+            S.sig_profile_enable(True, channels=[2, 3])       # whole calls only
+            for _ in range(300):
+                S.sig_forward(wsp, Xp, out=cp)
                 S.sig_backward(wsp, Xp, cp, gp)
-                torch.cuda.synchronize()
-                S.sig_profile_enable(True, channels=[2, 3])       # whole calls only
-                for _ in range(300):
-                    S.sig_forward(wsp, Xp, out=cp)
-                    S.sig_backward(wsp, Xp, cp, gp)
-                torch.cuda.synchronize()
-                nf, mf = S.sig_profile_read(False, True)
-                nb, mb = S.sig_profile_read(True, True)
-                S.sig_profile_enable(False)
-                us = (mf / max(nf, 1) + mb / max(nb, 1)) * 1e3
-                table[f"B={Bp} points={Mp} d={dp} N={Np}"] = {
-                    "coeffs": wsp.size, "step_us": round(us, 1), "paper_h200_step_us": paper_us,
-                    "fwd_bwd_coeff_steps_per_s": round(Bp * (Mp - 1) * wsp.size / (us * 1e-6), 1),
-                    "kernels": [wsp.kernel_name(False, Bp, Mp), wsp.kernel_name(True, Bp, Mp)]}
-            out["paper_table_shapes"] = table
-        except Exception as e:
-            out["paper_table_shapes"] = {"error": str(e)[:200]}
+            torch.cuda.synchronize()
+            nf, mf = S.sig_profile_read(False, True)
+            nb, mb = S.sig_profile_read(True, True)
+            S.sig_profile_enable(False)
+            us = (mf / max(nf, 1) + mb / max(nb, 1)) * 1e3
+            table[f"B={Bp} points={Mp} d={dp} N={Np}"] = {
+                "coeffs": wsp.size, "step_us": round(us, 1), "paper_h200_step_us": paper_us,
+                "fwd_bwd_coeff_steps_per_s": round(Bp * (Mp - 1) * wsp.size / (us * 1e-6), 1),
+                "kernels": [wsp.kernel_name(False, Bp, Mp), wsp.kernel_name(True, Bp, Mp)]}
+        out["paper_table_shapes"] = table
 
         # the other word-set builders (host only): graph-induced set and the sparse lead-lag set of a 5-dimensional path
         t0 = time.perf_counter()
@@ -385,9 +446,6 @@ def main():
         t2 = time.perf_counter()
         out["other_word_sets"] = {"graph(d=10, edges i->i+1..i+3, depth 6)": {"words": g.size, "build_ms": round((t1 - t0) * 1e3, 3)},
                                   "leadlag_sparse(d=5, depth 4)": {"words": ll.size, "build_ms": round((t2 - t1) * 1e3, 3)}}
-
-    if not args.no_cpu and wl.kind == "truncated":
-        out["cpu_baseline"] = cpu_baseline(st, min(args.cpu_sample, wl.B) if args.cpu_sample > 0 else wl.B)
 
     if args.calibrate:
         n = 64 * 1024 * 1024

@@ -101,6 +101,23 @@ const int32_t* sig_wordset_letter(const sig_wordset* ws);       /* host [|W|] */
 const int32_t* sig_wordset_level_start(const sig_wordset* ws);  /* host [max_len + 2] */
 const int64_t* sig_wordset_user_index(const sig_wordset* ws);   /* host [n_user] or NULL */
 
+/* Launch-shape knobs of a word set.  They are filled once, when the set is built, from the environment variables in
+ * brackets, and changed afterwards only through sig_wordset_set_option; sig_forward / sig_backward never read the
+ * environment.  The launcher's own choice is the default; the knobs exist for tests and tuning scans.
+ *   "no_jit"        [SIG_NO_JIT]         1: table-driven kernels instead of run-time specialised ones
+ *   "jit_waves"     [SIG_JIT_WAVES]      wavefronts the balanced plan of the specialised kernels aims at (0: 2,048)
+ *   "chunks"        [SIG_CHUNKS]         time chunks with the chunk arrays in the workspace (0: launcher decides)
+ *   "fwd_tails"     [SIG_FWD_TAILS]      d = 4 forward with the chunks of a path in one workgroup: -1 auto, 0 off, 2, 4
+ *   "bwd_tails"     [SIG_BWD_TAILS]      d = 4 backward: -1 auto, 0 off, 1 one wavefront per row, 2 / 4 / 8 fused chunks
+ *   "lanes"         [SIG_LANES]          word-per-lane kernels for full truncations: -1 auto, 0 off, 1 wherever defined
+ *   "lanes_levels"  [SIG_LANES_LEVELS]   levels below the lane's word: 0 auto, 1, 2
+ *   "logsig_gather" [SIG_LOGSIG_GATHER]  1: two-kernel form of sig_logsig_backward
+ *   "jit_wg_waves"  [SIG_JIT_WG_WAVES]   wavefronts per workgroup of the specialised kernels, 1..4 (default 4)
+ * Workspace sizes depend on the knobs: query them again after a change.  Returns SIG_EINVAL for an unknown name.
+ * Not to be called while another thread runs sig_forward / sig_backward on the same word set. */
+int sig_wordset_set_option(sig_wordset* ws, const char* name, int value);
+int sig_wordset_get_option(const sig_wordset* ws, const char* name, int* value);
+
 /* Multiply-adds one path needs per segment when Horner intermediates are shared between words with a
  * common prefix: sum over words u of (1 + height of the sub-tree under u).  This is the work unit the
  * benchmark prices against the FP32 vector peak (Algorithm 1 evaluated once per (prefix, target length)). */
@@ -127,14 +144,18 @@ int sig_wordset_plan_get(const sig_wordset* ws, int backward, int variant, const
  * for a word set therefore takes seconds.  sig_wordset_jit_prepare does that compilation ahead of time for the
  * plan variant a batch of B paths would use (host only, no device needed); it returns SIG_OK, SIG_EUNSUPPORTED if
  * this word set is not run through specialised kernels, or SIG_EJIT if hiprtc failed (sig_forward / sig_backward
- * then fall back to the table-driven kernels).  Setting the environment variable SIG_NO_JIT=1 disables it.
+ * then fall back to the table-driven kernels).  The option "no_jit" disables it.
  * Full truncations (any d <= 64) without a precompiled kernel are the exception to "grows with the word set": they
  * run one fixed kernel source with a word per lane, compiled for the shape (d, depth) in under a second per
- * direction (Section 3.1, eq. (3), with the prefixes shared between words); SIG_LANES=0 sends them through the
- * straight-line form as well, SIG_LANES=1 takes the word-per-lane form even where a path has only a few words of
+ * direction (Section 3.1, eq. (3), with the prefixes shared between words); the option "lanes" = 0 sends them through
+ * the straight-line form as well, = 1 takes the word-per-lane form even where a path has only a few words of
  * length depth - 2.  sig_wordset_jit_prepare and sig_wordset_jit_source cover whichever form the batch would use.
- * With SIG_JIT_CACHE set to an existing directory, compiled code objects are kept there (named by a hash of their
- * source and the compiler version) and later processes load them instead of compiling. */
+ * With the environment variable SIG_JIT_CACHE naming an existing directory (read when a kernel is compiled), code
+ * objects are kept there (named by a hash of their source, the compiler version and the compile options; each file
+ * carries its length and a checksum) and later processes load them instead of compiling; a file that fails its
+ * checks or does not load is removed and replaced.
+ * Threads: calls on different word-set objects may run concurrently; a compilation holds only its own kernel's lock.
+ * A word-set object serves the device it was uploaded on. */
 #define SIG_EJIT (-10)
 int sig_wordset_jit_prepare(sig_wordset* ws, int backward, int64_t B);
 /* The plan the specialised kernel for a batch of B paths is generated from, in the format of sig_wordset_plan_get.

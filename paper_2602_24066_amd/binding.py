@@ -88,6 +88,8 @@ def load_library():
     sig("sig_backward_workspace_bytes", c_sz, [c_p, c_i64, c_i64])
     sig("sig_forward", c_int, [c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
     sig("sig_backward", c_int, [c_p, c_p, c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
+    sig("sig_wordset_set_option", c_int, [c_p, ctypes.c_char_p, c_int])
+    sig("sig_wordset_get_option", c_int, [c_p, ctypes.c_char_p, ctypes.POINTER(c_int)])
     sig("sig_profile_enable", c_int, [c_int])
     sig("sig_profile_read", c_int, [c_int, ctypes.POINTER(c_i64), ctypes.POINTER(c_dbl)])
     sig("sig_strerror", ctypes.c_char_p, [c_int])
@@ -178,6 +180,15 @@ class WordSet:
         if B > 0 and n_points > 1:
             return self._lib.sig_kernel_name(self._h, int(backward), B, n_points).decode()
         return self._lib.sig_wordset_kernel_name(self._h, int(backward)).decode()
+
+    def set_option(self, name: str, value: int) -> None:
+        """Launch-shape knob of this word set (see sig_wordset_set_option in include/sig.h)."""
+        _check(self._lib.sig_wordset_set_option(self._h, name.encode(), int(value)), "sig_wordset_set_option")
+
+    def get_option(self, name: str) -> int:
+        v = ctypes.c_int()
+        _check(self._lib.sig_wordset_get_option(self._h, name.encode(), ctypes.byref(v)), "sig_wordset_get_option")
+        return int(v.value)
 
     def plan_count(self, backward: bool = False) -> int:
         return int(self._lib.sig_wordset_plan_count(self._h, int(backward)))
@@ -393,9 +404,16 @@ def sig_forward_windows(ws: WordSet, path, windows):
 def sig_backward_windows(ws: WordSet, path, windows, coeffs, grad_coeffs):
     """Gradient with respect to the path of a loss on the windowed signatures: grad_coeffs [B, K, |W|] -> [B, n, d]."""
     import torch
+    for name, t in (("path", path), ("coeffs", coeffs), ("grad_coeffs", grad_coeffs)):
+        if not t.is_cuda or t.dtype != torch.float32:
+            raise ValueError(f"{name} must be a float32 CUDA tensor")
+    if path.dim() != 3 or path.shape[2] != ws.dim:
+        raise ValueError(f"path must be [B, n, {ws.dim}]")
     path, coeffs, grad_coeffs = path.contiguous(), coeffs.contiguous(), grad_coeffs.contiguous()
     B, P, d = path.shape
     wt, K, max_len = _windows_tensor(windows, path.device)
+    if K and int(np.asarray(windows).reshape(-1, 2)[:, 1].max()) >= P:
+        raise ValueError("window end beyond the path")
     if tuple(coeffs.shape) != (B, K, ws.size) or tuple(grad_coeffs.shape) != (B, K, ws.size):
         raise ValueError("shape mismatch")
     lib = load_library()
@@ -412,6 +430,55 @@ def sig_backward_windows(ws: WordSet, path, windows, coeffs, grad_coeffs):
         if t is not None:
             t.record_stream(torch.cuda.current_stream(path.device))
     return out
+
+
+class WindowPlan:
+    """Windowed signatures with every buffer allocated once: the device copy of the window list, the outputs and
+    the workspaces of sig_forward_windows / sig_backward_windows.  forward() and backward() only enqueue (for
+    timing loops and HIP-graph capture); each call overwrites the buffers of the one before."""
+
+    def __init__(self, ws: WordSet, path, windows):
+        import torch
+        if not path.is_cuda or path.dtype != torch.float32 or path.dim() != 3 or path.shape[2] != ws.dim:
+            raise ValueError("path must be a float32 CUDA tensor [B, n, d] with the word set's d")
+        self.ws, self.path = ws, path.contiguous()
+        B, P, d = self.path.shape
+        self.wt, self.K, self.max_len = _windows_tensor(windows, path.device)
+        if self.K and int(np.asarray(windows).reshape(-1, 2)[:, 1].max()) >= P:
+            raise ValueError("window end beyond the path")
+        lib = load_library()
+        self.coeffs = torch.empty((B, self.K, ws.size), dtype=torch.float32, device=path.device)
+        self.grad_path = torch.empty((B, P, d), dtype=torch.float32, device=path.device)
+        self.nf = int(lib.sig_forward_windows_workspace_bytes(ws._h, B, P, self.K, self.max_len))
+        self.nb = int(lib.sig_backward_windows_workspace_bytes(ws._h, B, P, self.K, self.max_len))
+        self._wf, self.wf = _aligned_workspace(self.nf, path.device)
+        self._wb, self.wb = _aligned_workspace(self.nb, path.device)
+
+    def forward(self):
+        import torch
+        B, P, _ = self.path.shape
+        with torch.cuda.device(self.path.device):
+            stream = torch.cuda.current_stream().cuda_stream
+            _check(load_library().sig_forward_windows(
+                self.ws._h, ctypes.c_void_p(self.path.data_ptr()), B, P, ctypes.c_void_p(self.wt.data_ptr()), self.K,
+                self.max_len, ctypes.c_void_p(self.coeffs.data_ptr()), ctypes.c_void_p(self.wf), self.nf,
+                ctypes.c_void_p(stream)), "sig_forward_windows")
+        return self.coeffs
+
+    def backward(self, grad_coeffs):
+        import torch
+        B, P, _ = self.path.shape
+        if tuple(grad_coeffs.shape) != tuple(self.coeffs.shape) or grad_coeffs.dtype != torch.float32 or not grad_coeffs.is_cuda:
+            raise ValueError("grad_coeffs must be a float32 CUDA tensor [B, K, |W|]")
+        grad_coeffs = grad_coeffs.contiguous()
+        with torch.cuda.device(self.path.device):
+            stream = torch.cuda.current_stream().cuda_stream
+            _check(load_library().sig_backward_windows(
+                self.ws._h, ctypes.c_void_p(self.path.data_ptr()), ctypes.c_void_p(self.coeffs.data_ptr()),
+                ctypes.c_void_p(grad_coeffs.data_ptr()), B, P, ctypes.c_void_p(self.wt.data_ptr()), self.K, self.max_len,
+                ctypes.c_void_p(self.grad_path.data_ptr()), ctypes.c_void_p(self.wb), self.nb, ctypes.c_void_p(stream)),
+                "sig_backward_windows")
+        return self.grad_path
 
 
 def _aligned_workspace(nbytes: int, device):

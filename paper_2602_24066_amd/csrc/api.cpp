@@ -28,6 +28,35 @@ int hip_fail(hipError_t e)
 
 const sig::WordSet* W(const sig_wordset* ws) { return ws; }
 
+// Launch-shape knobs: one table for the environment variables read when a set is built and for
+// sig_wordset_set_option / sig_wordset_get_option.
+struct OptionName { const char* name; const char* env; int sig::WordSet::Options::*field; };
+const OptionName kOptions[] = {
+    {"no_jit", "SIG_NO_JIT", &sig::WordSet::Options::no_jit},
+    {"jit_waves", "SIG_JIT_WAVES", &sig::WordSet::Options::jit_waves},
+    {"chunks", "SIG_CHUNKS", &sig::WordSet::Options::chunks},
+    {"fwd_tails", "SIG_FWD_TAILS", &sig::WordSet::Options::fwd_tails},
+    {"bwd_tails", "SIG_BWD_TAILS", &sig::WordSet::Options::bwd_tails},
+    {"lanes", "SIG_LANES", &sig::WordSet::Options::lanes},
+    {"lanes_levels", "SIG_LANES_LEVELS", &sig::WordSet::Options::lanes_levels},
+    {"logsig_gather", "SIG_LOGSIG_GATHER", &sig::WordSet::Options::logsig_gather},
+    {"jit_wg_waves", "SIG_JIT_WG_WAVES", &sig::WordSet::Options::jit_wg_waves},
+};
+void options_from_environment(sig::WordSet& w)
+{
+    for (const OptionName& o : kOptions) {
+        const char* e = std::getenv(o.env);
+        if (e && e[0]) w.opt.*(o.field) = std::atoi(e);
+    }
+}
+int finish_build(int rc, sig::WordSet* w, sig_wordset** out)
+{
+    if (rc != SIG_OK) return rc;
+    options_from_environment(*w);
+    *out = static_cast<sig_wordset*>(w);
+    return SIG_OK;
+}
+
 // Picks the plan variant: the coarsest one (least recomputation of shared ancestors) that still
 // yields enough wavefronts to occupy the 256 compute units, else the finest.
 int pick_variant(const sig::WordSet& ws, int dir, int64_t B, int64_t want = 2048 /* two wavefronts per SIMD */)
@@ -79,9 +108,8 @@ Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points)
     const int64_t L = n_points - 1;
     int64_t C = 1;
     if (L >= 64 && sig::chunking_available(w.d, w.depth)) {
-        const char* e = std::getenv("SIG_CHUNKS");                                        // tuning knob
-        if (e && e[0]) {
-            C = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(std::atoi(e), 64), L / 32));
+        if (w.opt.chunks > 0) {                                                           // tuning knob
+            C = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(w.opt.chunks, 64), L / 32));
         } else if (dir == 0) {
             const int64_t slots = (int64_t)1024 * sig::trunc_occupancy(w.d, w.depth, dir);
             C = slots / sig::trunc_waves_per_row(w.d, w.depth, dir) / std::max<int64_t>(B, 1);
@@ -100,11 +128,9 @@ int64_t trunc_forward_fused_chunks(const sig::WordSet& w, int64_t B, int64_t n_p
 {
     if (!sig::trunc_forward_tails_available(w.d, w.depth) || ((uintptr_t)coeffs & 15) != 0) return 0;
     const int64_t L = n_points - 1;
-    const char* force = std::getenv("SIG_FWD_TAILS");
-    const int f = (force && force[0]) ? std::atoi(force) : -1;
+    const int f = w.opt.fwd_tails;
     if (f == 0) return 0;
-    const char* hbm = std::getenv("SIG_CHUNKS");             // asks for the form with chunk arrays in HBM
-    if (f == -1 && hbm && hbm[0]) return 0;
+    if (f == -1 && w.opt.chunks > 0) return 0;               // asks for the form with chunk arrays in HBM
     int64_t C;
     if (f == 2 || f == 4) {
         C = f;
@@ -131,8 +157,7 @@ BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points
     const Chunks ch = trunc_chunks(w, 1, B, n_points);
     BwdShape s{false, false, ch.C, ch.Lc};
     if (!sig::trunc_backward_tails_available(w.d, w.depth)) return s;
-    const char* force = std::getenv("SIG_BWD_TAILS");
-    const int f = (force && force[0]) ? std::atoi(force) : -1;
+    const int f = w.opt.bwd_tails;
     if (f == 0) return s;
     if (f == 1) return BwdShape{true, false, ch.C, ch.Lc};
     int64_t C = f == 2 || f == 4 || f == 8 ? f : (B <= 256 ? 8 : (B <= 896 ? 4 : (B <= 1536 ? 2 : 1)));
@@ -163,24 +188,29 @@ std::mutex g_jit_mutex;
 // Work units asked of the balanced planner for a batch of B paths: one or two wavefronts per SIMD (1,024 on the
 // chip) over the path groups, a whole number of workgroups, and not so many that units shrink to a handful of words
 // (every unit recomputes the ancestors of its first word).
-constexpr int kJitWaves = 4;           // wavefronts (units) per workgroup
+int jit_wg_waves(const sig::WordSet& w)   // wavefronts (units) per workgroup
+{
+    return w.opt.jit_wg_waves == 8 ? 8 : std::max(1, std::min(4, w.opt.jit_wg_waves));
+}
 int64_t jit_units(const sig::WordSet& w, int /*dir*/, int64_t B)
 {
+    const int kJitWaves = jit_wg_waves(w);
     int64_t want = 2048;               // two wavefronts per SIMD
-    if (const char* e = std::getenv("SIG_JIT_WAVES")) want = std::max(1, std::atoi(e));   // tuning knob
+    if (w.opt.jit_waves > 0) want = w.opt.jit_waves;                                       // tuning knob
     const int64_t groups = (B + 63) / 64;
     int64_t n = std::max<int64_t>(1, want / groups);
     n = std::min(n, std::max<int64_t>(1, w.size() / 8));
     return (n + kJitWaves - 1) / kJitWaves * kJitWaves;
 }
 
-// segments per LDS tile; backward also keeps four gradient tiles [T][d][65] in the 64 KB of static LDS
-int jit_tile_steps(int d, int dir) { return std::min(8, (dir ? 48 : 240) / std::max(d, 1)); }
+// segments per LDS tile; backward also keeps one gradient tile [T][d][65] per wavefront of the workgroup (four as a
+// rule) in the 64 KB of static LDS
+int jit_tile_steps(int d, int dir, int nw = 4) { return std::min(8, (dir ? 192 / std::max(nw, 4) : 240) / std::max(d, 1)); }
+int jit_tile_for(const sig::WordSet& w, int dir) { return std::max(1, jit_tile_steps(w.d, dir, jit_wg_waves(w))); }
 
 bool jit_enabled(const sig::WordSet& w)
 {
-    const char* off = std::getenv("SIG_NO_JIT");
-    if (off && off[0] && off[0] != '0') return false;
+    if (w.opt.no_jit) return false;
     return w.kernels_supported && w.size() > 0 && jit_tile_steps(w.d, 1) >= 1;
 }
 
@@ -190,15 +220,18 @@ sig::WordSet::JitEntry* jit_entry(const sig::WordSet& cw, int dir, int64_t B)
 {
     sig::WordSet& w = const_cast<sig::WordSet&>(cw);     // the cache is logically mutable
     const int64_t n_units = jit_units(w, dir, B);
+    const int wgw = jit_wg_waves(w);
     std::lock_guard<std::mutex> lock(g_jit_mutex);
     for (auto* e : w.jit[dir])
-        if (e->n_units == n_units) return e;
+        if (e->n_units == n_units && e->wg_waves == wgw) return e;
     auto* e = new (std::nothrow) sig::WordSet::JitEntry;
     if (!e) return nullptr;
     try {
         e->n_units = n_units;
+        e->wg_waves = wgw;
         if (dir == 0) sig::build_plan_balanced(w, n_units, 320, false, 1, 1, e->plan);
         else sig::build_plan_balanced(w, n_units, 160, true, 6, 9, e->plan);
+        e->kernel = new sig::JitKernel;
         w.jit[dir].push_back(e);
     } catch (const std::bad_alloc&) {
         delete e;
@@ -210,44 +243,71 @@ sig::WordSet::JitEntry* jit_entry(const sig::WordSet& cw, int dir, int64_t B)
 // Source of the specialised kernel of an entry; fills nw / tile.
 std::string jit_source(const sig::WordSet& w, int dir, const sig::Plan& p, int& nw, int& tile)
 {
-    // Four wavefronts per workgroup = one per SIMD, so a workgroup's registers fit whatever a unit needs.  (A
-    // 512-thread workgroup of a 248-VGPR kernel was refused at dispatch on gfx950.)
-    nw = (int)std::min<size_t>((size_t)kJitWaves, std::max<size_t>(1, p.units.size()));
-    tile = jit_tile_steps(w.d, dir);
+    // Four wavefronts per workgroup = one per SIMD, so a workgroup's registers fit whatever a unit needs.
+    nw = (int)std::min<size_t>((size_t)jit_wg_waves(w), std::max<size_t>(1, p.units.size()));
+    tile = jit_tile_for(w, dir);
     return dir ? sig::jit_backward_source(w, p, nw, tile) : sig::jit_forward_source(w, p, nw, tile);
 }
 
-// Compiled (and, if load is set, loaded) kernel for (direction, batch size), or nullptr if specialisation is off or
-// failed.  Compilation happens once per entry; the outcome is remembered.  *plan receives the entry's plan.
-sig::JitKernel* ensure_jit(const sig::WordSet& cw, int dir, int64_t B, bool load, const sig::Plan** plan = nullptr)
+// What a call may do to get its kernel: compile and load it (ordinary entry points), or only use one that is already
+// loaded (the entry point that allocates nothing: loading a code object allocates device memory).
+enum class Build { compile_only, compile_and_load, loaded_only };
+// Set by ensure_* when a Build::loaded_only call found a kernel that exists but is not compiled or loaded yet.
+thread_local bool g_not_ready = false;
+
+// Brings one kernel to the asked state under the kernel's own lock (a compilation of seconds does not hold up calls
+// on other word sets or kernels); `source` is called at most once per kernel.
+template <class MakeSource>
+sig::JitKernel* bring_up(sig::JitKernel* k, Build how, const char* name, MakeSource source)
+{
+    std::lock_guard<std::mutex> lock(k->m);
+    if (how == Build::loaded_only) {
+        if (k->tried && !k->ok) return nullptr;          // specialisation failed earlier: the fallback kernels run
+        if (!k->fn) { g_not_ready = true; return nullptr; }
+        return k;
+    }
+    std::string src;
+    if (!k->tried) {
+        k->tried = true;
+        try {
+            src = source(*k);
+            (void)sig::jit_compile(src, name, *k);
+        } catch (const std::bad_alloc&) { k->ok = false; }
+    }
+    if (!k->ok) return nullptr;
+    if (how == Build::compile_and_load && !k->fn && sig::jit_load(*k) != hipSuccess) {
+        // a code object from the disk cache that does not load is removed and compiled afresh, once
+        bool again = false;
+        if (!k->cache_file.empty()) {
+            try {
+                if (src.empty()) src = source(*k);
+                again = sig::jit_compile(src, name, *k, false) == 0 && sig::jit_load(*k) == hipSuccess;
+            } catch (const std::bad_alloc&) { again = false; }
+        }
+        if (!again) {
+            k->ok = false;
+            return nullptr;
+        }
+    }
+    return k;
+}
+
+// Kernel for (direction, batch size) in the asked state, or nullptr if specialisation is off or failed.
+// Compilation happens once per entry; the outcome is remembered.  *plan receives the entry's plan.
+sig::JitKernel* ensure_jit(const sig::WordSet& cw, int dir, int64_t B, Build how, const sig::Plan** plan = nullptr)
 {
     if (!jit_enabled(cw)) return nullptr;
     sig::WordSet::JitEntry* e = jit_entry(cw, dir, B);
     if (!e) return nullptr;
     if (plan) *plan = &e->plan;
-    std::lock_guard<std::mutex> lock(g_jit_mutex);
-    if (!e->kernel) e->kernel = new (std::nothrow) sig::JitKernel;
-    sig::JitKernel* k = e->kernel;
-    if (!k) return nullptr;
-    if (!k->tried) {
-        k->tried = true;
-        try {
-            const std::string src = jit_source(cw, dir, e->plan, k->nw, k->tile);
-            (void)sig::jit_compile(src, dir ? "sig_bwd_jit" : "sig_fwd_jit", *k);
-        } catch (const std::bad_alloc&) { k->ok = false; }
-    }
-    if (!k->ok) return nullptr;
-    if (load && !k->fn && sig::jit_load(*k) != hipSuccess) {
-        k->ok = false;
-        return nullptr;
-    }
-    return k;
+    return bring_up(e->kernel, how, dir ? "sig_bwd_jit" : "sig_fwd_jit",
+                    [&](sig::JitKernel& k) { return jit_source(cw, dir, e->plan, k.nw, k.tile); });
 }
 
 // bytes of the transposed increments the specialised kernels read: [groups][Lpad][d][64] floats
 int64_t jit_lpad(const sig::WordSet& w, int64_t n_points, int dir)
 {
-    const int64_t T = jit_tile_steps(w.d, dir), L = n_points - 1;
+    const int64_t T = jit_tile_for(w, dir), L = n_points - 1;
     return (L + T - 1) / T * T;
 }
 size_t jit_dxt_bytes(const sig::WordSet& w, int64_t B, int64_t n_points, int dir)
@@ -283,15 +343,13 @@ int bwd_tile_steps(int d) { return std::max(1, std::min(16, 32 / std::max(d, 1))
 // ten thousand words); lanes = words fills the wavefronts from a single path on and compiles in about a second per
 // shape.  Taken whenever the words of a path fill at least half a wavefront; SIG_LANES=0 switches it off, =1 takes
 // it for every shape it is defined for.
-int lanes_levels_asked()
+int lanes_levels_asked(const sig::WordSet& w)             // testing knob: 1 or 2 levels below the lane's word
 {
-    const char* e = std::getenv("SIG_LANES_LEVELS");       // testing knob: 1 or 2 levels below the lane's word
-    const int v = (e && e[0]) ? std::atoi(e) : 0;
-    return v == 1 || v == 2 ? v : 0;
+    return w.opt.lanes_levels == 1 || w.opt.lanes_levels == 2 ? w.opt.lanes_levels : 0;
 }
 sig::LanesShape lanes_shape_for(const sig::WordSet& w, int dir, int64_t B)
 {
-    sig::LanesShape s = sig::lanes_shape(w.d, w.depth, dir != 0, B, lanes_levels_asked());
+    sig::LanesShape s = sig::lanes_shape(w.d, w.depth, dir != 0, B, lanes_levels_asked(w));
     if (!s.ok) s = sig::lanes_shape(w.d, w.depth, dir != 0, B, 0);
     return s;
 }
@@ -299,37 +357,30 @@ sig::LanesShape lanes_shape_for(const sig::WordSet& w, int dir, int64_t B)
 bool use_lanes(const sig::WordSet& w, int64_t B)
 {
     if (w.kind != 0 || !jit_enabled(w)) return false;
-    const char* e = std::getenv("SIG_LANES");
-    const int f = (e && e[0]) ? std::atoi(e) : -1;
+    const int f = w.opt.lanes;
     if (f == 0) return false;
     const sig::LanesShape s = lanes_shape_for(w, 0, B), sb = lanes_shape_for(w, 1, B);
     if (!s.ok || !sb.ok || B * std::max(s.waves, sb.waves) > (int64_t)0x7fffffff) return false;
     return f == 1 || std::min(s.lanes, sb.lanes) >= 32;
 }
 
-sig::JitKernel* ensure_lanes(const sig::WordSet& cw, int dir, const sig::LanesShape& s, bool load)
+sig::JitKernel* ensure_lanes(const sig::WordSet& cw, int dir, const sig::LanesShape& s, Build how)
 {
     sig::WordSet& w = const_cast<sig::WordSet&>(cw);     // the cache is logically mutable
-    std::lock_guard<std::mutex> lock(g_jit_mutex);
-    sig::JitKernel*& slot = w.lanes[dir][s.R - 1];
-    if (!slot) slot = new (std::nothrow) sig::JitKernel;
-    sig::JitKernel* k = slot;
+    sig::JitKernel* k = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_jit_mutex);
+        sig::JitKernel*& slot = w.lanes[dir][s.R - 1];
+        if (!slot) slot = new (std::nothrow) sig::JitKernel;
+        k = slot;
+    }
     if (!k) return nullptr;
-    if (!k->tried) {
-        k->tried = true;
-        try {
-            // everything but the levels per lane follows from (d, depth, direction): one kernel per slot
-            k->nw = s.nwb;
-            k->tile = s.T;
-            (void)sig::jit_compile(sig::lanes_source(w.d, w.depth, s, dir != 0), dir ? "sig_bwd_lanes" : "sig_fwd_lanes", *k);
-        } catch (const std::bad_alloc&) { k->ok = false; }
-    }
-    if (!k->ok) return nullptr;
-    if (load && !k->fn && sig::jit_load(*k) != hipSuccess) {
-        k->ok = false;
-        return nullptr;
-    }
-    return k;
+    // everything but the levels per lane follows from (d, depth, direction): one kernel per slot
+    return bring_up(k, how, dir ? "sig_bwd_lanes" : "sig_fwd_lanes", [&](sig::JitKernel& kk) {
+        kk.nw = s.nwb;
+        kk.tile = s.T;
+        return sig::lanes_source(w.d, w.depth, s, dir != 0);
+    });
 }
 
 hipError_t launch_lanes(sig::JitKernel& k, const sig::LanesShape& s, const float* path, const float* coeffs_in, const float* grad,
@@ -352,54 +403,64 @@ int sig_wordset_build_truncated(int d, int depth, sig_wordset** out)
 {
     if (!out) return SIG_EINVAL;
     sig::WordSet* w = nullptr;
-    int rc = sig::build_truncated(d, depth, &w);
-    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
-    return rc;
+    return finish_build(sig::build_truncated(d, depth, &w), w, out);
 }
 
 int sig_wordset_build_anisotropic(int d, const double* weights, double cutoff, sig_wordset** out)
 {
     if (!out) return SIG_EINVAL;
     sig::WordSet* w = nullptr;
-    int rc = sig::build_anisotropic(d, weights, cutoff, &w);
-    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
-    return rc;
+    return finish_build(sig::build_anisotropic(d, weights, cutoff, &w), w, out);
 }
 
 int sig_wordset_build(int d, const int32_t* letters, const int64_t* offsets, int64_t n_words, sig_wordset** out)
 {
     if (!out) return SIG_EINVAL;
     sig::WordSet* w = nullptr;
-    int rc = sig::build_list(d, letters, offsets, n_words, &w);
-    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
-    return rc;
+    return finish_build(sig::build_list(d, letters, offsets, n_words, &w), w, out);
 }
 
 int sig_wordset_build_graph(int d, const int32_t* edges, int64_t n_edges, int depth, sig_wordset** out)
 {
     if (!out) return SIG_EINVAL;
     sig::WordSet* w = nullptr;
-    int rc = sig::build_graph(d, edges, n_edges, depth, &w);
-    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
-    return rc;
+    return finish_build(sig::build_graph(d, edges, n_edges, depth, &w), w, out);
 }
 
 int sig_wordset_build_leadlag_sparse(int d, int depth, sig_wordset** out)
 {
     if (!out) return SIG_EINVAL;
     sig::WordSet* w = nullptr;
-    int rc = sig::build_leadlag_sparse(d, depth, &w);
-    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
-    return rc;
+    return finish_build(sig::build_leadlag_sparse(d, depth, &w), w, out);
 }
 
 int sig_wordset_build_logsig(int d, int depth, sig_wordset** out)
 {
     if (!out) return SIG_EINVAL;
     sig::WordSet* w = nullptr;
-    int rc = sig::build_logsig(d, depth, &w);
-    if (rc == SIG_OK) *out = static_cast<sig_wordset*>(w);
-    return rc;
+    return finish_build(sig::build_logsig(d, depth, &w), w, out);
+}
+
+int sig_wordset_set_option(sig_wordset* ws, const char* name, int value)
+{
+    if (!ws || !name) return SIG_EINVAL;
+    for (const OptionName& o : kOptions)
+        if (std::strcmp(o.name, name) == 0) {
+            ws->opt.*(o.field) = value;
+            return SIG_OK;
+        }
+    return SIG_EINVAL;
+}
+
+int sig_wordset_get_option(const sig_wordset* ws, const char* name, int* value)
+{
+    if (!ws || !name || !value) return SIG_EINVAL;
+    for (const OptionName& o : kOptions)
+        if (std::strcmp(o.name, name) == 0) {
+            *value = W(ws)->opt.*(o.field);
+            return SIG_OK;
+        }
+    return SIG_EINVAL;
 }
 
 int64_t sig_wordset_n_lyndon(const sig_wordset* ws) { return ws ? W(ws)->n_lyndon : -1; }
@@ -439,7 +500,7 @@ int sig_logsig_backward(const sig_wordset* ws, const float* coeffs, const float*
     hipError_t e = sig::logsig_backward(coeffs, grad_logsig, B, w.size(), (const int32_t*)(base + w.lyn_len_off),
                                         (const int32_t*)(base + w.lyn_sub_off), w.n_lyndon, w.lyn_stride, w.depth, w.lyn_pairs,
                                         (const int32_t*)(base + w.lyn_inv_off_off), (const int32_t*)(base + w.lyn_inv_ent_off),
-                                        (float*)workspace, grad_coeffs, (hipStream_t)stream);
+                                        (float*)workspace, grad_coeffs, w.opt.logsig_gather != 0, (hipStream_t)stream);
     return e == hipSuccess ? SIG_OK : hip_fail(e);
 }
 
@@ -536,8 +597,8 @@ int sig_wordset_jit_prepare(sig_wordset* ws, int backward, int64_t B)
     const int dir = backward ? 1 : 0;
     if (!jit_enabled(w)) return SIG_EUNSUPPORTED;
     if (dir == 0 ? use_trunc_forward(w, B) : use_trunc_backward(w, B)) return SIG_EUNSUPPORTED;
-    if (use_lanes(w, B)) return ensure_lanes(w, dir, lanes_shape_for(w, dir, B), false) ? SIG_OK : SIG_EJIT;
-    return ensure_jit(w, dir, B, false) ? SIG_OK : SIG_EJIT;
+    if (use_lanes(w, B)) return ensure_lanes(w, dir, lanes_shape_for(w, dir, B), Build::compile_only) ? SIG_OK : SIG_EJIT;
+    return ensure_jit(w, dir, B, Build::compile_only) ? SIG_OK : SIG_EJIT;
 }
 
 size_t sig_wordset_jit_source(sig_wordset* ws, int backward, int64_t B, char* buf, size_t n)
@@ -573,6 +634,7 @@ int sig_wordset_upload(sig_wordset* ws, void* dev_buf, size_t dev_bytes, void* s
     hipError_t e = hipMemcpyAsync(dev_buf, ws->image.data(), ws->image.size(), hipMemcpyHostToDevice, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
     ws->dev = dev_buf;
+    (void)hipGetDevice(&ws->dev_id);
     return SIG_OK;
 }
 
@@ -657,7 +719,7 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
     }
     if (use_lanes(w, B)) {
         const sig::LanesShape ls = lanes_shape_for(w, 0, B);
-        if (sig::JitKernel* lk = ensure_lanes(w, 0, ls, true)) {
+        if (sig::JitKernel* lk = ensure_lanes(w, 0, ls, Build::compile_and_load)) {
             hipEvent_t* pe = g_prof.next(0);
             if (pe) (void)hipEventRecord(pe[0], st);
             hipError_t e = launch_lanes(*lk, ls, path, nullptr, nullptr, B, n_points, coeffs, st);
@@ -666,7 +728,7 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
         }
     }
     const sig::Plan* jp = nullptr;
-    if (sig::JitKernel* jk = ensure_jit(w, 0, B, true, &jp)) {
+    if (sig::JitKernel* jk = ensure_jit(w, 0, B, Build::compile_and_load, &jp)) {
         if (!workspace || workspace_bytes < jit_dxt_bytes(w, B, n_points, 0)) return SIG_EWORKSPACE;
         if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
         float* dxT = (float*)workspace;
@@ -698,8 +760,9 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
     return e == hipSuccess ? SIG_OK : hip_fail(e);
 }
 
-int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
-                 int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes, void* stream)
+// `how` says whether a run-time specialised kernel may be compiled and loaded by this call.
+static int backward_impl(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                         int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes, void* stream, Build how)
 {
     int rc = check_common(ws, path, B, n_points);
     if (rc != SIG_OK) return rc;
@@ -766,7 +829,10 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     }
     if (use_lanes(w, B)) {
         const sig::LanesShape ls = lanes_shape_for(w, 1, B);
-        if (sig::JitKernel* lk = ensure_lanes(w, 1, ls, true)) {
+        g_not_ready = false;
+        sig::JitKernel* lk = ensure_lanes(w, 1, ls, how);
+        if (!lk && g_not_ready) return SIG_EJIT;
+        if (lk) {
             hipEvent_t* pe = g_prof.next(1);
             if (pe) (void)hipEventRecord(pe[0], st);
             e = launch_lanes(*lk, ls, path, coeffs, grad_coeffs, B, n_points, gdx, st);
@@ -777,7 +843,10 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
         }
     }
     const sig::Plan* jp = nullptr;
-    if (sig::JitKernel* jk = ensure_jit(w, 1, B, true, &jp)) {
+    g_not_ready = false;
+    sig::JitKernel* jk = ensure_jit(w, 1, B, how, &jp);
+    if (!jk && g_not_ready) return SIG_EJIT;
+    if (jk) {
         const size_t gdx_bytes = ((size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;
         float* dxT = (float*)((unsigned char*)workspace + gdx_bytes);
         const int64_t Lpad = jit_lpad(w, n_points, 1);
@@ -812,6 +881,13 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
     if (e != hipSuccess) return hip_fail(e);
     e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
     return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
+int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                 int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return backward_impl(ws, path, coeffs, grad_coeffs, B, n_points, grad_path, workspace, workspace_bytes, stream,
+                         Build::compile_and_load);
 }
 
 // ---- windows: every (path, window) pair is gathered into a path of its own (padded with its last point), the

@@ -18,6 +18,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <set>
 #include <sstream>
 #include <utility>
@@ -350,41 +351,49 @@ std::string jit_backward_source(const WordSet& ws, const Plan& plan, int NW, int
 namespace {
 // Optional cache of compiled code objects on disk: with SIG_JIT_CACHE set to a directory, a code object is stored
 // there under a 64-bit hash of its source (which carries every specialisation), the compiler version and the compile
-// options, and later
-// processes load it instead of compiling.  Files are written under a temporary name and renamed, so concurrent
-// writers cannot leave a torn file; a file that fails to load is simply recompiled over.
-// stands for the option list of jit_compile in the file name hash: to be changed with it
-constexpr char kCompileOptionsTag[] = "gfx950 -O3 c++17 unsafe-fp-atomics no-packed-fp32 v1";
+// options, and later processes load it instead of compiling.  Files are written under a temporary name and renamed, so
+// concurrent writers cannot leave a torn file; a file that fails its checks or does not load is removed and the
+// kernel compiled afresh.
+// the option list of every compilation; it enters the file name hash of the disk cache
+const char* const kCompileOptions[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-munsafe-fp-atomics", "-Xclang", "-target-feature",
+                                       "-Xclang", "-packed-fp32-ops"};
+constexpr int kNumCompileOptions = (int)(sizeof kCompileOptions / sizeof kCompileOptions[0]);
+
+uint64_t fnv1a(const char* p, size_t n, uint64_t h = 1469598103934665603ull)
+{
+    for (size_t i = 0; i < n; ++i) { h ^= (unsigned char)p[i]; h *= 1099511628211ull; }
+    return h;
+}
 std::string cache_file(const std::string& src)
 {
-    const char* dir = std::getenv("SIG_JIT_CACHE");
+    const char* dir = std::getenv("SIG_JIT_CACHE");       // read when a kernel is compiled, never on the launch path
     if (!dir || !dir[0]) return std::string();
-    uint64_t h = 1469598103934665603ull;                  // FNV-1a
-    auto mix = [&](const char* p, size_t n) {
-        for (size_t i = 0; i < n; ++i) { h ^= (unsigned char)p[i]; h *= 1099511628211ull; }
-    };
     int major = 0, minor = 0;
     (void)hiprtcVersion(&major, &minor);
-    mix((const char*)&major, sizeof major);
-    mix((const char*)&minor, sizeof minor);
-    mix(kCompileOptionsTag, sizeof kCompileOptionsTag);
-    mix(src.data(), src.size());
+    uint64_t h = fnv1a((const char*)&major, sizeof major);
+    h = fnv1a((const char*)&minor, sizeof minor, h);
+    for (const char* o : kCompileOptions) h = fnv1a(o, std::strlen(o) + 1, h);
+    h = fnv1a(src.data(), src.size(), h);
     char name[64];
     std::snprintf(name, sizeof name, "/sig_gfx950_%016llx.hsaco", (unsigned long long)h);
     return std::string(dir) + name;
 }
+// File layout: 8 bytes magic, 8 bytes length of the code object, 8 bytes FNV-1a hash of it, then the code object.  A file
+// that is short, foreign or damaged is not used.
+constexpr char kCacheMagic[8] = {'S', 'I', 'G', 'J', 'I', 'T', '0', '2'};
 bool cache_load(const std::string& file, std::vector<char>& code)
 {
     if (file.empty()) return false;
     std::FILE* f = std::fopen(file.c_str(), "rb");
     if (!f) return false;
     bool ok = false;
-    if (std::fseek(f, 0, SEEK_END) == 0) {
-        const long n = std::ftell(f);
-        if (n > 0 && std::fseek(f, 0, SEEK_SET) == 0) {
-            code.resize((size_t)n);
-            ok = std::fread(code.data(), 1, (size_t)n, f) == (size_t)n;
-        }
+    char magic[8];
+    uint64_t len = 0, hash = 0;
+    if (std::fread(magic, 1, 8, f) == 8 && std::memcmp(magic, kCacheMagic, 8) == 0 && std::fread(&len, 8, 1, f) == 1 &&
+        std::fread(&hash, 8, 1, f) == 1 && len > 0 && len < (1ull << 31)) {
+        code.resize((size_t)len);
+        ok = std::fread(code.data(), 1, (size_t)len, f) == (size_t)len && std::fgetc(f) == EOF &&
+             fnv1a(code.data(), code.size()) == hash;
     }
     std::fclose(f);
     if (!ok) code.clear();
@@ -396,29 +405,32 @@ void cache_store(const std::string& file, const std::vector<char>& code)
     const std::string tmp = file + ".tmp" + std::to_string((long long)getpid());
     std::FILE* f = std::fopen(tmp.c_str(), "wb");
     if (!f) return;                                       // a cache that cannot be written is not an error
-    const bool ok = std::fwrite(code.data(), 1, code.size(), f) == code.size();
+    const uint64_t len = code.size(), hash = fnv1a(code.data(), code.size());
+    const bool ok = std::fwrite(kCacheMagic, 1, 8, f) == 8 && std::fwrite(&len, 8, 1, f) == 1 && std::fwrite(&hash, 8, 1, f) == 1 &&
+                    std::fwrite(code.data(), 1, code.size(), f) == code.size();
     if (std::fclose(f) != 0 || !ok || std::rename(tmp.c_str(), file.c_str()) != 0) (void)std::remove(tmp.c_str());
 }
 }  // namespace
 
-int jit_compile(const std::string& src, const char* kernel_name, JitKernel& out)
+int jit_compile(const std::string& src, const char* kernel_name, JitKernel& out, bool use_cache)
 {
     out.ok = false;
+    out.cache_file.clear();
     const std::string cached = cache_file(src);
-    if (cache_load(cached, out.code)) {
+    if (use_cache && cache_load(cached, out.code)) {
         out.name = kernel_name;
         out.log = "loaded from " + cached;
+        out.cache_file = cached;
         out.ok = true;
         return 0;
     }
+    if (!use_cache && !cached.empty()) (void)std::remove(cached.c_str());      // a cached object that did not load: replaced below
     hiprtcProgram prog = nullptr;
     if (hiprtcCreateProgram(&prog, src.c_str(), "sig_jit.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS) {
         out.log = "hiprtcCreateProgram failed";
         return -1;
     }
-    const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-munsafe-fp-atomics", "-Xclang", "-target-feature", "-Xclang",
-                          "-packed-fp32-ops"};
-    const hiprtcResult rc = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
+    const hiprtcResult rc = hiprtcCompileProgram(prog, kNumCompileOptions, const_cast<const char**>(kCompileOptions));
     size_t logsz = 0;
     if (hiprtcGetProgramLogSize(prog, &logsz) == HIPRTC_SUCCESS && logsz > 1) {
         out.log.resize(logsz);
@@ -443,12 +455,42 @@ int jit_compile(const std::string& src, const char* kernel_name, JitKernel& out)
     return 0;
 }
 
+bool jit_launch_shape_fits(int nw, int max_threads_per_block, int static_lds_bytes, int num_regs)
+{
+    if (nw < 1 || nw * 64 > max_threads_per_block) return false;
+    if (static_lds_bytes > 64 * 1024) return false;
+    // a SIMD holds 512 vector registers per lane; the nw wavefronts of a workgroup are spread over the four SIMDs of
+    // a compute unit, so (nw + 3) / 4 of them share one
+    const int per_simd = (nw + 3) / 4;
+    return num_regs * per_simd <= 512;
+}
+
 hipError_t jit_load(JitKernel& k)
 {
-    if (k.fn) return hipSuccess;
-    hipError_t e = hipModuleLoadData(&k.mod, k.code.data());
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    return hipModuleGetFunction(&k.fn, k.mod, k.name.c_str());
+    if (k.fn) return k.dev == dev ? hipSuccess : hipErrorInvalidDevice;   // a word set (and its kernels) serves one device
+    e = hipModuleLoadData(&k.mod, k.code.data());
+    if (e != hipSuccess) return e;
+    hipFunction_t fn = nullptr;
+    e = hipModuleGetFunction(&fn, k.mod, k.name.c_str());
+    if (e != hipSuccess) return e;
+    int max_threads = 0, lds = 0, regs = 0;
+    if ((e = hipFuncGetAttribute(&max_threads, HIP_FUNC_ATTRIBUTE_MAX_THREADS_PER_BLOCK, fn)) != hipSuccess) return e;
+    if ((e = hipFuncGetAttribute(&lds, HIP_FUNC_ATTRIBUTE_SHARED_SIZE_BYTES, fn)) != hipSuccess) return e;
+    if ((e = hipFuncGetAttribute(&regs, HIP_FUNC_ATTRIBUTE_NUM_REGS, fn)) != hipSuccess) return e;
+    if (!jit_launch_shape_fits(k.nw, max_threads, lds, regs)) {
+        k.log += "\nrefused: the code object does not fit the launch shape (" + std::to_string(k.nw * 64) + " threads; declares max " +
+                 std::to_string(max_threads) + " threads, " + std::to_string(lds) + " bytes of LDS, " + std::to_string(regs) +
+                 " registers)";
+        (void)hipModuleUnload(k.mod);
+        k.mod = nullptr;
+        return hipErrorLaunchOutOfResources;
+    }
+    k.fn = fn;
+    k.dev = dev;
+    return hipSuccess;
 }
 
 WordSet::~WordSet()

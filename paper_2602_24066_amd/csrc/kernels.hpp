@@ -3,10 +3,28 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <mutex>
+#include <set>
+#include <utility>
 
 #include "wordset.hpp"
 
 namespace sig {
+
+// Raises a kernel's dynamic-LDS limit (needed above 64 KB) once per (device, kernel).  Safe for concurrent callers.
+inline hipError_t ensure_dynamic_lds(const void* kernel, int bytes)
+{
+    static std::mutex m;
+    static std::set<std::pair<int, const void*>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(m);
+    if (done.count({dev, kernel})) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.insert({dev, kernel});
+    return e;
+}
 
 struct GenericArgs {
     const UnitDesc* units = nullptr;      // device
@@ -42,7 +60,9 @@ hipError_t logsig_forward(const float* coeffs, int64_t B, int64_t nW, const int3
                           int stride, int depth, float* out, hipStream_t stream);
 hipError_t logsig_backward(const float* coeffs, const float* glog, int64_t B, int64_t nW, const int32_t* lyn_len,
                            const int32_t* lyn_sub, int64_t n_lyn, int stride, int depth, int n_pairs, const int32_t* inv_off,
-                           const int32_t* inv, float* part /*[B, n_lyn, n_pairs]*/, float* gcoeffs, hipStream_t stream);
+                           const int32_t* inv, float* part /*[B, n_lyn, n_pairs]*/, float* gcoeffs, bool two_kernels,
+                           hipStream_t stream);
+
 hipError_t fma_probe(float* out, int blocks, int iters, hipStream_t stream);   // out: blocks * 256 floats
 hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* grad_path, hipStream_t stream);
 

@@ -327,13 +327,8 @@ hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, c
     const bool fuse = Q != nullptr && grad != nullptr && Abar != nullptr;
     const size_t lds = 3 * (size_t)g.W * sizeof(float);
     if (lds <= kMaxChunkLds) {
-        static bool attr_set = false;            // raising the dynamic LDS limit is needed once per process
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunk_scan_kernel<true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxChunkLds);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&chunk_scan_kernel<true>), (int)kMaxChunkLds);
+        if (e != hipSuccess) return e;
         chunk_scan_kernel<true><<<dim3((unsigned)B, fuse ? 2 : 1), 1024, lds, stream>>>(
             Sc, Pfx, Q, terminal, coeffs_out, fuse ? grad : nullptr, fuse ? Abar : nullptr, C, g);
         if (fuse && adjoints_done) *adjoints_done = true;

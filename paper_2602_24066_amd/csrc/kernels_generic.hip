@@ -628,33 +628,27 @@ hipError_t logsig_forward(const float* coeffs, int64_t B, int64_t nW, const int3
     return hipGetLastError();
 }
 // bytes of LDS the one-kernel form of the backward needs for a gradient row; 0 = the row does not fit
-static size_t logsig_row_lds_bytes(int64_t nW)
+static size_t logsig_row_lds_bytes(int64_t nW, bool two_kernels)
 {
-    const char* two = std::getenv("SIG_LOGSIG_GATHER");          // the tests force the two-kernel form with it
-    if (two && two[0] && two[0] != '0') return 0;
+    if (two_kernels) return 0;                                   // the tests force the two-kernel form
     const size_t n = ((size_t)nW * sizeof(float) + 15) & ~(size_t)15;
     return n <= 128 * 1024 ? n : 0;
 }
 
 hipError_t logsig_backward(const float* coeffs, const float* glog, int64_t B, int64_t nW, const int32_t* lyn_len,
                            const int32_t* lyn_sub, int64_t n_lyn, int stride, int depth, int n_pairs, const int32_t* inv_off,
-                           const int32_t* inv, float* part, float* gcoeffs, hipStream_t stream)
+                           const int32_t* inv, float* part, float* gcoeffs, bool two_kernels, hipStream_t stream)
 {
     const int64_t n = B * n_lyn;
     if (B <= 0) return hipSuccess;
     if (depth > kMaxLogDepth) return hipErrorInvalidValue;
-    if (const size_t lds = logsig_row_lds_bytes(nW)) {
+    if (const size_t lds = logsig_row_lds_bytes(nW, two_kernels)) {
         if (B > 0x7fffffff) return hipErrorInvalidValue;
 #define SIG_LOGSIG_BWD_LDS(DEPTH)                                                                                              \
     do {                                                                                                                       \
         if (lds > 64 * 1024) {                                                                                                 \
-            static bool attr_set = false;                                                                                      \
-            if (!attr_set) {                                                                                                   \
-                hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&logsig_backward_lds_kernel<DEPTH>),         \
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);                   \
-                if (ea != hipSuccess) return ea;                                                                               \
-                attr_set = true;                                                                                               \
-            }                                                                                                                  \
+            hipError_t ea = ensure_dynamic_lds(reinterpret_cast<const void*>(&logsig_backward_lds_kernel<DEPTH>), 128 * 1024); \
+            if (ea != hipSuccess) return ea;                                                                                   \
         }                                                                                                                      \
         logsig_backward_lds_kernel<DEPTH><<<(unsigned)B, 512, lds, stream>>>(coeffs, glog, nW, lyn_len, lyn_sub, n_lyn, stride, \
                                                                             depth, gcoeffs);                                   \

@@ -1659,13 +1659,8 @@ hipError_t launch_trunc_node_bwd(const float* path, const float* coeffs, const f
     const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_node_bwd_kernel<D, N, T>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&trunc_node_bwd_kernel<D, N, T>), (int)LY::BYTES);
+        if (e != hipSuccess) return e;
     }
     trunc_node_bwd_kernel<D, N, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C, Lc,
                                                                                                   gdx);
@@ -1853,13 +1848,8 @@ hipError_t launch_trunc_tails_fwd(const float* path, int64_t B, int64_t P, int64
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
     if ((CW - 1) * Lc >= P - 1 || B > 0x7fffffff) return hipErrorInvalidValue;   // every chunk holds a segment
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_fwd_kernel<D, N, T, CW, TW>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&trunc_tails_fwd_kernel<D, N, T, CW, TW>), (int)LY::BYTES);
+        if (e != hipSuccess) return e;
     }
     trunc_tails_fwd_kernel<D, N, T, CW, TW><<<(unsigned)B, kWave * LY::NWV, LY::BYTES, stream>>>(path, P, Lc, coeffs);
     return hipGetLastError();
@@ -1876,13 +1866,8 @@ hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const 
     const int64_t blocks = CW ? B : (B * C + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T, CW, POINTS>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T, CW, POINTS>), (int)LY::BYTES);
+        if (e != hipSuccess) return e;
     }
     if (POINTS && CW == 0 && C != 1) return hipErrorInvalidValue;   // rows that are parts of paths cannot apply the chain rule
     trunc_tails_bwd_kernel<D, N, T, CW, POINTS><<<(unsigned)blocks, kWave * LY::NWV, LY::BYTES, stream>>>(path, coeffs, grad, B, P,
@@ -1902,13 +1887,8 @@ hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const f
     const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&trunc_mfma_bwd_kernel<D, N, WQ, T>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LY::BYTES);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&trunc_mfma_bwd_kernel<D, N, WQ, T>), (int)LY::BYTES);
+        if (e != hipSuccess) return e;
     }
     trunc_mfma_bwd_kernel<D, N, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(path, coeffs, grad, B,
                                                                                                       P, C, Lc, gdx);

@@ -77,11 +77,28 @@ struct WordSet {
     std::vector<int32_t> lyn_inv_off, lyn_inv;
     size_t lyn_len_off = 0, lyn_sub_off = 0, lyn_inv_off_off = 0, lyn_inv_ent_off = 0;    // offsets in the device image
     void* dev = nullptr;
+    int dev_id = -1;                   // device the image was uploaded to (a word-set object serves one device)
+    // Launch-shape knobs.  Filled once when the set is built (from the SIG_* environment variables of that moment) and
+    // changed afterwards only through sig_wordset_set_option; no entry point reads the environment per call.
+    struct Options {
+        int no_jit = 0;                // 1: table-driven kernels instead of run-time specialised ones
+        int jit_waves = 0;             // wavefronts the balanced plan aims at (0: two per SIMD)
+        int chunks = 0;                // time chunks with the chunk arrays in the workspace (0: the launcher decides)
+        int fwd_tails = -1;            // d = 4 forward, chunks of a path in one workgroup: -1 auto, 0 off, 2 / 4 forced
+        int bwd_tails = -1;            // d = 4 backward: -1 auto, 0 off, 1 one wavefront per row, 2 / 4 / 8 fused chunks
+        int lanes = -1;                // word-per-lane kernels for full truncations: -1 auto, 0 off, 1 whenever defined
+        int lanes_levels = 0;          // levels below the lane's word: 0 auto, 1, 2
+        int logsig_gather = 0;         // 1: two-kernel form of the log-signature adjoint
+        int jit_wg_waves = 4;          // wavefronts (work units) per workgroup of the run-time specialised kernels, 1..4;
+                                       // 8 is accepted for inspecting the generated code on the host only: jit_load
+                                       // refuses code objects whose registers do not fit two wavefronts per SIMD
+    } opt;
     bool kernels_supported = true;     // false when max_len exceeds what the kernels handle
     // run-time specialised kernels with the balanced plan each was generated from, per direction, keyed by the
     // number of work units asked for; built on first use
     struct JitEntry {
         int64_t n_units = 0;
+        int wg_waves = 0;              // wavefronts per workgroup the kernel is generated for
         Plan plan;
         JitKernel* kernel = nullptr;
     };

@@ -130,14 +130,15 @@ def test_forward_chunks_in_one_workgroup(monkeypatch, B, L, chunks):
         check_parity(ws, W, "truncated", 6, X, G, what=f"fused forward B={B} L={L} C={chunks} {dist}")
 
 
-def test_forward_fused_and_four_wavefront_kernels_agree(monkeypatch):
+def test_forward_fused_and_four_wavefront_kernels_agree():
     ws, W = build_both("truncated", 4, depth=6)
     X = make_path("time0", 21, 200, 255, 4)
     G = make_grad_coeffs(22, 200, ws.size)
-    monkeypatch.setenv("SIG_FWD_TAILS", "0")
+    ws.set_option("fwd_tails", 0)
     assert ws.kernel_name(False, 200, 256) == "trunc_mfma_fwd_kernel"
     c0, _ = gpu_forward_backward(ws, X, G)
-    monkeypatch.delenv("SIG_FWD_TAILS")
+    ws.set_option("fwd_tails", -1)
+    assert ws.kernel_name(False, 200, 256) == "trunc_tails_fwd_kernel"
     c4, _ = gpu_forward_backward(ws, X, G)
     lengths = np.array([len(w) for w in W])
     for n, e in O.level_errors(c4, c0.astype(np.float64), lengths).items():
@@ -172,13 +173,13 @@ def test_rows_that_are_not_16_byte_aligned():
     assert O.grad_errors(gp_off.cpu().numpy(), O.backward_words(X, W, G.astype(np.float64))).max() <= BWD_TOL
 
 
-def test_chunked_and_unchunked_agree(monkeypatch):
+def test_chunked_and_unchunked_agree():
     ws, W = build_both("truncated", 4, depth=6)
-    X = make_path("time0", 11, 4, 128, 4)
+    X = make_path("iid", 11, 4, 128, 4)
     G = make_grad_coeffs(12, 4, ws.size)
-    monkeypatch.setenv("SIG_CHUNKS", "1")
+    ws.set_option("chunks", 1)
     c1, g1 = gpu_forward_backward(ws, X, G)
-    monkeypatch.setenv("SIG_CHUNKS", "4")
+    ws.set_option("chunks", 4)
     c4, g4 = gpu_forward_backward(ws, X, G)
     lengths = np.array([len(w) for w in W])
     for n, e in O.level_errors(c4, c1.astype(np.float64), lengths).items():

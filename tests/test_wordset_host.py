@@ -165,12 +165,13 @@ def test_error_codes():
     deep = S.sig_wordset_build_truncated(2, 14)
     assert lib.sig_forward(deep._h, ctypes.c_void_p(256), 1, 2, ctypes.c_void_p(256), None, 0, None) == -9
     gdx = 4 * 10 * 2 * 4 + (-(4 * 10 * 2 * 4)) % 256          # dLoss/d dX: B * L * d floats, rounded up to 256 bytes
-    os.environ["SIG_NO_JIT"] = "1"
-    try:
-        assert lib.sig_backward_workspace_bytes(ws._h, 4, 11) == gdx
-        assert lib.sig_forward_workspace_bytes(ws._h, 4, 11) == 0
-    finally:
-        del os.environ["SIG_NO_JIT"]
+    ws.set_option("no_jit", 1)
+    assert ws.get_option("no_jit") == 1
+    assert lib.sig_backward_workspace_bytes(ws._h, 4, 11) == gdx
+    assert lib.sig_forward_workspace_bytes(ws._h, 4, 11) == 0
+    ws.set_option("no_jit", 0)
+    assert lib.sig_wordset_set_option(ws._h, b"no_such_knob", 1) == -1
+    assert lib.sig_wordset_set_option(None, b"no_jit", 1) == -1
     # with run-time specialisation: the transposed increments in addition (padded to whole tiles of segments)
     nb = lib.sig_backward_workspace_bytes(ws._h, 4, 11)
     nf = lib.sig_forward_workspace_bytes(ws._h, 4, 11)
@@ -436,15 +437,20 @@ def test_kernel_selection_for_full_truncations(monkeypatch):
     assert ws46.kernel_name(False, 64, 9) == "trunc_mfma_fwd_kernel"          # too short for two chunks of 8 segments
     assert ws46.kernel_name(True, 256, 256) == "trunc_tails_bwd_kernel"
     assert ws46.kernel_name(True, 4000, 40) == "trunc_tails_bwd_kernel"
-    monkeypatch.setenv("SIG_FWD_TAILS", "0")
-    monkeypatch.setenv("SIG_BWD_TAILS", "0")
+    ws46.set_option("fwd_tails", 0)
+    ws46.set_option("bwd_tails", 0)
     assert ws46.kernel_name(False, 256, 256) == "trunc_mfma_fwd_kernel"
     assert ws46.kernel_name(True, 256, 256) == "trunc_node_bwd_kernel"
-    monkeypatch.delenv("SIG_FWD_TAILS")
-    monkeypatch.delenv("SIG_BWD_TAILS")
-    monkeypatch.setenv("SIG_CHUNKS", "4")                                       # asks for chunk arrays in HBM
+    ws46.set_option("fwd_tails", -1)
+    ws46.set_option("bwd_tails", -1)
+    ws46.set_option("chunks", 4)                                                # asks for chunk arrays in HBM
     assert ws46.kernel_name(False, 256, 256) == "trunc_mfma_fwd_kernel"
-    monkeypatch.delenv("SIG_CHUNKS")
+    ws46.set_option("chunks", 0)
+    # the knobs are read from the environment once, when a set is built; a set built earlier does not see a change
+    monkeypatch.setenv("SIG_FWD_TAILS", "0")
+    assert ws46.kernel_name(False, 256, 256) == "trunc_tails_fwd_kernel"
+    assert S.sig_wordset_build_truncated(4, 6).kernel_name(False, 256, 256) == "trunc_mfma_fwd_kernel"
+    monkeypatch.delenv("SIG_FWD_TAILS")
     # the other instantiated shapes, and a truncation without one
     assert S.sig_wordset_build_truncated(8, 5).kernel_name(True, 128, 1025) == "trunc_node_bwd_kernel"
     assert S.sig_wordset_build_truncated(16, 4).kernel_name(True, 64, 4097) == "trunc_mfma_bwd_kernel"
