@@ -47,6 +47,7 @@ extern "C" {
 #define SIG_ETOOLARGE    (-7)  /* word set exceeds a format limit (see SIG_MAX_*)                        */
 #define SIG_ENOTUPLOADED (-8)  /* sig_forward/sig_backward called before sig_wordset_upload              */
 #define SIG_EUNSUPPORTED (-9)  /* word length above what the kernels handle (SIG_MAX_KERNEL_LEN)         */
+#define SIG_ENOTREADY    (-11) /* sig_backward_static: the kernel for this set and batch is not loaded yet */
 
 #define SIG_MAX_WORD_LEN    32          /* table format limit on |w|                                     */
 #define SIG_MAX_KERNEL_LEN  12          /* longest word the GPU kernels handle                           */
@@ -201,6 +202,20 @@ size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_
 int    sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs,
                     int64_t B, int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes,
                     void* stream);
+
+/* The same computation for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): no workspace argument; the buffers sig_backward takes from its workspace
+ * (gradient with respect to the increments, transposed increments, chunk arrays) live in a static device array of
+ * SIG_STATIC_SCRATCH_BYTES that each GPU the library runs on holds until the process ends.  The call allocates nothing
+ * and frees nothing; it only enqueues kernels on `stream` (what must start at zero is cleared by a kernel first).
+ * Errors beyond those of sig_backward: SIG_ETOOLARGE when sig_backward_workspace_bytes(ws, B, n_points) exceeds
+ * SIG_STATIC_SCRATCH_BYTES; SIG_ENOTREADY when the word set runs through a run-time compiled kernel that this process
+ * has not loaded yet (loading a code object allocates): one sig_backward call of the same batch size loads it.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on the same device (different streams or
+ * host threads) race; calls on one stream are ordered and safe. */
+#define SIG_STATIC_SCRATCH_BYTES (32u << 20)
+int    sig_backward_static(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs,
+                           int64_t B, int64_t n_points, float* grad_path, void* stream);
 
 /* ---- log-signature (Section 3.3) -----------------------------------------------------------------------------
  * Coordinates: for every Lyndon word w of length <= depth, the coefficient of w in the tensor logarithm of the

@@ -88,6 +88,7 @@ def load_library():
     sig("sig_backward_workspace_bytes", c_sz, [c_p, c_i64, c_i64])
     sig("sig_forward", c_int, [c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
     sig("sig_backward", c_int, [c_p, c_p, c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
+    sig("sig_backward_static", c_int, [c_p, c_p, c_p, c_p, c_i64, c_i64, c_p, c_p])
     sig("sig_wordset_set_option", c_int, [c_p, ctypes.c_char_p, c_int])
     sig("sig_wordset_get_option", c_int, [c_p, ctypes.c_char_p, ctypes.POINTER(c_int)])
     sig("sig_profile_enable", c_int, [c_int])
@@ -540,6 +541,27 @@ def sig_backward(ws: WordSet, path, coeffs, grad_coeffs, out=None, workspace=Non
                                 ctypes.c_void_p(wptr), nbytes, ctypes.c_void_p(stream)), "sig_backward")
     if keep is not None:
         keep.record_stream(torch.cuda.current_stream(path.device))
+    return out
+
+
+SIG_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def sig_backward_static(ws: WordSet, path, coeffs, grad_coeffs, out):
+    """sig_backward without a workspace argument and without any allocation: the library's static device scratch
+    serves as workspace.  `out` [B, L+1, d] is the caller's.  Enqueues on torch's current stream."""
+    import torch
+    for name, t in (("path", path), ("coeffs", coeffs), ("grad_coeffs", grad_coeffs), ("out", out)):
+        if not t.is_cuda or t.dtype != torch.float32 or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous float32 CUDA tensor")
+    B, P, d = path.shape
+    if d != ws.dim or tuple(coeffs.shape) != (B, ws.size) or tuple(grad_coeffs.shape) != (B, ws.size) or tuple(out.shape) != (B, P, d):
+        raise ValueError("shape mismatch")
+    with torch.cuda.device(path.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(load_library().sig_backward_static(ws._h, ctypes.c_void_p(path.data_ptr()), ctypes.c_void_p(coeffs.data_ptr()),
+                                                  ctypes.c_void_p(grad_coeffs.data_ptr()), B, P, ctypes.c_void_p(out.data_ptr()),
+                                                  ctypes.c_void_p(stream)), "sig_backward_static")
     return out
 
 

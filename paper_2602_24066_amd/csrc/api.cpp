@@ -760,6 +760,7 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
     return e == hipSuccess ? SIG_OK : hip_fail(e);
 }
 
+// sig_backward and sig_backward_static: the same kernels on the caller's workspace or on the static scratch array;
 // `how` says whether a run-time specialised kernel may be compiled and loaded by this call.
 static int backward_impl(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
                          int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes, void* stream, Build how)
@@ -831,7 +832,7 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
         const sig::LanesShape ls = lanes_shape_for(w, 1, B);
         g_not_ready = false;
         sig::JitKernel* lk = ensure_lanes(w, 1, ls, how);
-        if (!lk && g_not_ready) return SIG_EJIT;
+        if (!lk && g_not_ready) return SIG_ENOTREADY;
         if (lk) {
             hipEvent_t* pe = g_prof.next(1);
             if (pe) (void)hipEventRecord(pe[0], st);
@@ -845,7 +846,7 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
     const sig::Plan* jp = nullptr;
     g_not_ready = false;
     sig::JitKernel* jk = ensure_jit(w, 1, B, how, &jp);
-    if (!jk && g_not_ready) return SIG_EJIT;
+    if (!jk && g_not_ready) return SIG_ENOTREADY;
     if (jk) {
         const size_t gdx_bytes = ((size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;
         float* dxT = (float*)((unsigned char*)workspace + gdx_bytes);
@@ -888,6 +889,19 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
 {
     return backward_impl(ws, path, coeffs, grad_coeffs, B, n_points, grad_path, workspace, workspace_bytes, stream,
                          Build::compile_and_load);
+}
+
+int sig_backward_static(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                        int64_t n_points, float* grad_path, void* stream)
+{
+    int rc = check_common(ws, path, B, n_points);
+    if (rc != SIG_OK) return rc;
+    if (sig_backward_workspace_bytes(ws, B, n_points) > (size_t)SIG_STATIC_SCRATCH_BYTES) return SIG_ETOOLARGE;
+    void* scratch_ptr = nullptr;                         // this device's copy of the static array
+    hipError_t e = sig::static_scratch(&scratch_ptr);
+    if (e != hipSuccess) return hip_fail(e);
+    return backward_impl(ws, path, coeffs, grad_coeffs, B, n_points, grad_path, scratch_ptr, (size_t)SIG_STATIC_SCRATCH_BYTES, stream,
+                         Build::loaded_only);
 }
 
 // ---- windows: every (path, window) pair is gathered into a path of its own (padded with its last point), the
@@ -1001,6 +1015,7 @@ const char* sig_strerror(int code)
         case SIG_ENOTUPLOADED: return "word set tables not uploaded";
         case SIG_EUNSUPPORTED: return "not supported for this word set";
         case SIG_EJIT: return "run-time compilation failed";
+        case SIG_ENOTREADY: return "the kernel for this word set and batch is not loaded yet (call sig_backward once first)";
         default: return "unknown error";
     }
 }

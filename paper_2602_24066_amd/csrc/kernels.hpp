@@ -62,7 +62,9 @@ hipError_t logsig_backward(const float* coeffs, const float* glog, int64_t B, in
                            const int32_t* lyn_sub, int64_t n_lyn, int stride, int depth, int n_pairs, const int32_t* inv_off,
                            const int32_t* inv, float* part /*[B, n_lyn, n_pairs]*/, float* gcoeffs, bool two_kernels,
                            hipStream_t stream);
-
+// Device memory of the entry point that allocates nothing: address of this device's copy of the library's static
+// scratch array (SIG_STATIC_SCRATCH_BYTES bytes, 256-byte aligned), looked up once per device.
+hipError_t static_scratch(void** ptr);
 hipError_t fma_probe(float* out, int blocks, int iters, hipStream_t stream);   // out: blocks * 256 floats
 hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* grad_path, hipStream_t stream);
 

@@ -20,9 +20,15 @@
 
 #include <cstdint>
 
+#include "../../include/sig.h"
 #include "kernels.hpp"
 
 #include <cstdlib>
+
+// Workspace of sig_backward_static, the entry point for callers that cannot allocate: one copy per device, held until
+// the process ends.  In host code this name is only a handle for hipGetSymbolAddress (static_scratch below); kernels
+// and fills receive the address that call returns, never the name.
+static __device__ __align__(256) unsigned char scratch[SIG_STATIC_SCRATCH_BYTES];
 
 namespace sig {
 
@@ -719,6 +725,27 @@ hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* gra
     const int threads = 256;
     grad_points_kernel<<<(unsigned)((n + threads - 1) / threads), threads, 0, stream>>>(gdx, B, P, d, grad_path);
     return hipGetLastError();
+}
+
+hipError_t static_scratch(void** ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex m;
+    static void* per_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(m);
+    if (!per_device[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));      // this device's copy of the array
+        if (e != hipSuccess) return e;
+        if (!p || ((uintptr_t)p & 255) != 0) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    return hipSuccess;
 }
 
 }  // namespace sig

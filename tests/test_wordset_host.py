@@ -172,6 +172,10 @@ def test_error_codes():
     ws.set_option("no_jit", 0)
     assert lib.sig_wordset_set_option(ws._h, b"no_such_knob", 1) == -1
     assert lib.sig_wordset_set_option(None, b"no_jit", 1) == -1
+    # the entry point that allocates nothing: same argument checks, before anything touches a device
+    assert lib.sig_backward_static(None, None, None, None, 1, 2, None, None) == -1
+    assert lib.sig_backward_static(ws._h, ctypes.c_void_p(256), ctypes.c_void_p(256), ctypes.c_void_p(256), 1, 2,
+                                   ctypes.c_void_p(256), None) == -8                                        # not uploaded
     # with run-time specialisation: the transposed increments in addition (padded to whole tiles of segments)
     nb = lib.sig_backward_workspace_bytes(ws._h, 4, 11)
     nf = lib.sig_forward_workspace_bytes(ws._h, 4, 11)
