@@ -114,6 +114,7 @@ const int64_t* sig_wordset_user_index(const sig_wordset* ws);   /* host [n_user]
  *   "lanes_levels"  [SIG_LANES_LEVELS]   levels below the lane's word: 0 auto, 1, 2
  *   "logsig_gather" [SIG_LOGSIG_GATHER]  1: two-kernel form of sig_logsig_backward
  *   "jit_wg_waves"  [SIG_JIT_WG_WAVES]   wavefronts per workgroup of the specialised kernels, 1..4 (default 4)
+ *   "bwd_tile"      [SIG_BWD_TILE]       segments per LDS tile of the d = 16 backward kernel: 0 default, 8, 16
  * Workspace sizes depend on the knobs: query them again after a change.  Returns SIG_EINVAL for an unknown name.
  * Not to be called while another thread runs sig_forward / sig_backward on the same word set. */
 int sig_wordset_set_option(sig_wordset* ws, const char* name, int value);

@@ -41,6 +41,7 @@ const OptionName kOptions[] = {
     {"lanes_levels", "SIG_LANES_LEVELS", &sig::WordSet::Options::lanes_levels},
     {"logsig_gather", "SIG_LOGSIG_GATHER", &sig::WordSet::Options::logsig_gather},
     {"jit_wg_waves", "SIG_JIT_WG_WAVES", &sig::WordSet::Options::jit_wg_waves},
+    {"bwd_tile", "SIG_BWD_TILE", &sig::WordSet::Options::bwd_tile},
 };
 void options_from_environment(sig::WordSet& w)
 {
@@ -822,7 +823,7 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
         else if (ch.tails)
             e = sig::trunc_backward_tails(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx,
                                           points ? grad_path : nullptr, st);
-        else e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, st);
+        else e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, w.opt.bwd_tile, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
         if (!points) e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);

@@ -77,8 +77,9 @@ int trunc_waves_per_row(int d, int depth, int backward);    // wavefronts per (p
 // own in coeffs / grad_coeffs ([B * C, |W|]).  C = 1, Lc = P - 1 treats whole paths.
 hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t P, int64_t C, int64_t Lc, float* coeffs,
                          hipStream_t stream);
+// tile: segments per LDS tile where a kernel offers a choice (d = 16: 8 or 16; 0 = the default)
 hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
-                          int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream);
+                          int64_t P, int64_t C, int64_t Lc, float* gdx, int tile, hipStream_t stream);
 const char* trunc_backward_kernel_name(int d, int depth);   // of the kernel trunc_backward launches
 
 // d = 4: backward with one wavefront per row (a lane holds a word of length N - 3 and its four children); stores

@@ -614,7 +614,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     constexpr int NSRC0 = 1 + WQ;                     // sources before the earlier chain letters
     constexpr int LB = ilog2(D);
     using LY = BwdLds<D, N, WQ, T>;
-    static_assert(T == 16, "the time-batched leaf products take 16 segments per matrix instruction");
+    static_assert(T == 16 || T == 8, "the time-batched leaf products take up to 16 segments per matrix instruction");
     extern __shared__ v4f bwd_smem[];
 
     const int lane = threadIdx.x % kWave;
@@ -848,9 +848,12 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             // gbar[1](slice word p, segment s) = sum_j dX_s^{(j)} G[p][j] for the 16 segments of the tile:
             // [64 parents x D letters] . [D letters x 16 segments] per slice vector; the result (row = parent
             // 4 (l / 16) + r of block mb, column = segment l % 16) goes to HA[v][segment][parent]
+            // (a tile of 8 segments fills half of the 16 columns; the other lanes compute on a copy and store nothing)
+            const int col = (lane & 15) % T;
+            const bool col_ok = (lane & 15) < T;
             float Bx[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) Bx[ks] = E[lane & 15][0][4 * ks + lane / 16];
+            for (int ks = 0; ks < KS; ++ks) Bx[ks] = E[col][0][4 * ks + lane / 16];
 #pragma unroll
             for (int v = 0; v < NSV; ++v)
 #pragma unroll
@@ -859,7 +862,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks)
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Ga[v][mb][ks], Bx[ks], acc, 0, 0, 0);
-                    *(v4f*)(HA + (v * T + (lane & 15)) * SP + 16 * mb + 4 * (lane / 16)) = acc;
+                    if (T == 16 || col_ok) *(v4f*)(HA + (v * T + col) * SP + 16 * mb + 4 * (lane / 16)) = acc;
                 }
             wave_lds_fence();
         }
@@ -882,17 +885,18 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         {
             // dLoss/d dX_s^{(j)} += sum_p G[p][j] A+(p, s): [D letters x 64 parents] . [64 parents x 16 segments] per
             // slice vector; row = letter 4 (l / 16) + r, column = segment l % 16
+            const int col = (lane & 15) % T;
             v4f acc[4] = {zero4, zero4, zero4, zero4};
 #pragma unroll
             for (int v = 0; v < NSV; ++v)
 #pragma unroll
                 for (int ks = 0; ks < 16; ++ks) {
-                    const float bv = HA[(v * T + (lane & 15)) * SP + 4 * ks + lane / 16];
+                    const float bv = HA[(v * T + col) * SP + 4 * ks + lane / 16];
                     acc[ks % 4] = __builtin_amdgcn_mfma_f32_16x16x4f32(Gt[v][ks], bv, acc[ks % 4], 0, 0, 0);
                 }
             const v4f sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-            if (4 * (lane / 16) < D) {
-                v4f* dst = (v4f*)(gt + (lane & 15) * D + 4 * (lane / 16));
+            if (4 * (lane / 16) < D && (T == 16 || (lane & 15) < T)) {
+                v4f* dst = (v4f*)(gt + col * D + 4 * (lane / 16));
                 *dst = *dst + sum;
             }
             wave_lds_fence();
@@ -1547,20 +1551,28 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
         }
     };
 
-    auto step = [&](int row_t) {
-        float ec[K][NC];
+    // The scaled increments of a segment are read from LDS one segment ahead of their use (a lone wavefront per SIMD has
+    // nobody to hide the LDS latency behind): `In` is what a step reads, filled by load_in while the step before runs.
+    struct In {
+        float ec[K][NC];                              // dX^{(letter[k])} / (t + 1) for the chain
+        float eu[D][2];                               // dX^{(j)}, dX^{(j)} / 2: the same in every lane
+    };
+    auto load_in = [&](int row_t, In& in) {
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const float* src = &Ec[row_t][letter[k]][0];
 #pragma unroll
-            for (int t = 0; t <= N - (k + 1); ++t) ec[k][t] = src[t];
+            for (int t = 0; t <= N - (k + 1); ++t) in.ec[k][t] = src[t];
         }
-        float eu[D][2];                               // dX^{(j)}, dX^{(j)} / 2: the same in every lane
 #pragma unroll
         for (int j = 0; j < D; ++j) {
-            eu[j][0] = Ec[row_t][j][0];
-            eu[j][1] = Ec[row_t][j][1];
+            in.eu[j][0] = Ec[row_t][j][0];
+            in.eu[j][1] = Ec[row_t][j][1];
         }
+    };
+    auto step = [&](int row_t, const In& in) {
+        const float (&ec)[K][NC] = in.ec;
+        const float (&eu)[D][2] = in.eu;
         // 1. reconstruction with -dX, 2. accumulators with +dX from the reconstructed signature
         float am[K + 1][N + 2], ap[K + 1][N + 2];
 #pragma unroll
@@ -1631,8 +1643,21 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
         stage();
         wave_lds_fence();
         fetch((n - 1) * T);                            // n = 0: out of range, zeros
-#pragma unroll 2
-        for (int tt = T - 1; tt >= 0; --tt) step(tt);
+        {
+            static_assert(T % 2 == 0 && T >= 4, "the segment loop is unrolled by two");
+            In ia, ib;
+            load_in(T - 1, ia);
+#pragma unroll 1
+            for (int tt = T - 1; tt >= 3; tt -= 2) {
+                load_in(tt - 1, ib);
+                step(tt, ia);
+                load_in(tt - 2, ia);
+                step(tt - 1, ib);
+            }
+            load_in(0, ib);
+            step(1, ia);
+            step(0, ib);
+        }
         wave_lds_fence();
         tile_reduce_uniform<D, T>(Vb, gt, D, lane, 0);     // the only writer of gt so far: plain read-modify-write
         wave_lds_fence();
@@ -1648,11 +1673,10 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
     }
 }
 
-template <int D, int N>
+template <int D, int N, int T = 8>
 hipError_t launch_trunc_node_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P, int64_t C,
                                  int64_t Lc, float* gdx, hipStream_t stream)
 {
-    constexpr int T = 8;
     using LY = NodeLds<D, N, T>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
     const int64_t waves = B * C * (ipow(D, N - 2) / kWave);
@@ -1875,12 +1899,11 @@ hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const 
     return hipGetLastError();
 }
 
-template <int D, int N, int WQ>
+template <int D, int N, int WQ, int T>
 hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
                                  int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
 {
     using G = MGeo<D, N, N - 2, WQ>;
-    constexpr int T = 16;
     using LY = BwdLds<D, N, WQ, T>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
     const int64_t waves = B * C * G::WAVES;
@@ -1990,11 +2013,16 @@ const char* trunc_backward_kernel_name(int d, int depth)
 
 // gdx: [B, L, d] accumulation buffer, zeroed by the caller
 hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
-                          int64_t P, int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
+                          int64_t P, int64_t C, int64_t Lc, float* gdx, int tile, hipStream_t stream)
 {
     if (d == 4 && depth == 6) return launch_trunc_node_bwd<4, 6>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
-    if (d == 8 && depth == 5) return launch_trunc_node_bwd<8, 5>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
-    if (d == 16 && depth == 4) return launch_trunc_mfma_bwd<16, 4, 1>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    if (d == 8 && depth == 5)
+        return tile == 4 ? launch_trunc_node_bwd<8, 5, 4>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream)
+                         : launch_trunc_node_bwd<8, 5, 8>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+    // d = 16: tiles of 8 segments keep a workgroup's LDS under half a compute unit's, so two wavefronts share a SIMD
+    if (d == 16 && depth == 4)
+        return tile == 8 ? launch_trunc_mfma_bwd<16, 4, 1, 8>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream)
+                         : launch_trunc_mfma_bwd<16, 4, 1, 16>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
     return hipErrorInvalidValue;
 }
 
