@@ -55,7 +55,7 @@ def bytes_forward(ws, B, L, d):
     return 4.0 * B * (L + 1) * d + 4.0 * B * ws.size
 
 
-def setup(name, S, torch):
+def setup(name, S, torch, plain=False):
     from sig_workloads import WORKLOADS, make_grad_coeffs, workload_path, workload_word_list
     wl = WORKLOADS[name]
     words = workload_word_list(wl) if wl.kind == "words" else None
@@ -78,9 +78,18 @@ def setup(name, S, torch):
         "coeffs": torch.empty((wl.B, ws.size), dtype=torch.float32, device="cuda"),
         "gpath": torch.empty((wl.B, wl.L + 1, wl.d), dtype=torch.float32, device="cuda"),
     }
-    nf = int(lib.sig_forward_workspace_bytes(ws._h, wl.B, wl.L + 1))
-    nb = int(lib.sig_backward_workspace_bytes(ws._h, wl.B, wl.L + 1))
+    # where the library offers it for the shape, a step keeps the time-chunk signatures of the forward pass for the
+    # backward pass (sig_forward_checkpointed / sig_backward_checkpointed); plain=True times sig_forward / sig_backward
+    nck = 0 if plain else int(lib.sig_checkpoint_bytes(ws._h, wl.B, wl.L + 1))
+    st["ck"] = torch.empty(nck, dtype=torch.uint8, device="cuda") if nck else None
+    if nck:
+        nf = int(lib.sig_forward_checkpointed_workspace_bytes(ws._h, wl.B, wl.L + 1))
+        nb = int(lib.sig_backward_checkpointed_workspace_bytes(ws._h, wl.B, wl.L + 1))
+    else:
+        nf = int(lib.sig_forward_workspace_bytes(ws._h, wl.B, wl.L + 1))
+        nb = int(lib.sig_backward_workspace_bytes(ws._h, wl.B, wl.L + 1))
     st["workspace_bytes"] = [nf, nb]
+    st["checkpoint_bytes"] = nck
     st["wf"] = torch.empty(max(nf, 256), dtype=torch.uint8, device="cuda")
     st["wb"] = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
     assert st["wf"].data_ptr() % 256 == 0 and st["wb"].data_ptr() % 256 == 0
@@ -88,6 +97,10 @@ def setup(name, S, torch):
 
 
 def step(S, st):
+    if st["ck"] is not None:
+        S.sig_forward_checkpointed(st["ws"], st["path"], out=st["coeffs"], checkpoint=st["ck"], workspace=st["wf"])
+        S.sig_backward_checkpointed(st["ws"], st["path"], st["coeffs"], st["grad"], st["ck"], out=st["gpath"], workspace=st["wb"])
+        return
     S.sig_forward(st["ws"], st["path"], out=st["coeffs"], workspace=st["wf"])
     S.sig_backward(st["ws"], st["path"], st["coeffs"], st["grad"], out=st["gpath"], workspace=st["wb"])
 
@@ -232,7 +245,8 @@ def workload_row(S, torch, st, sec, kf, kb, cf, cb, steps):
         # algorithmic bytes of the backward call over its GPU time, against the 8 TB/s of HBM3E
         "bwd_algorithmic_bytes": int(bb), "bwd_hbm_gbs_algorithmic": round(bb / (cb * 1e-3) / 1e9, 1),
         "bwd_hbm_bytes_counters": counter_traffic(kn_b, wl.name),
-        "kernels": [kn_f, kn_b], "workspace_bytes": st["workspace_bytes"],
+        "kernels": [kn_f, kn_b], "workspace_bytes": st["workspace_bytes"], "checkpoint_bytes": st["checkpoint_bytes"],
+        "calls": "sig_forward_checkpointed + sig_backward_checkpointed" if st["ck"] is not None else "sig_forward + sig_backward",
         "wordset_build_ms": round(st["build_ms"], 3), "steps": steps,
     }
 
@@ -346,6 +360,19 @@ def main():
             per[name]["mem_out_bytes"] = 4 * s2["wl"].B * s2["ws"].size
             if not args.no_cpu:
                 per[name]["cpu_baseline"], per[name]["errors"] = oracle_check(s2, CPU_SAMPLE[name])
+            if s2["ck"] is not None:
+                # the same workload through sig_forward / sig_backward, which keep the terminal signature alone
+                s3 = setup(name, S, torch, plain=True)
+                step(S, s3)
+                torch.cuda.synchronize()
+                _, kf3, kb3, f3, b3 = time_steps(S, torch, s3, n, max(n // 5, 2))
+                w3, wl3 = s3["ws"], s3["wl"]
+                per[name]["without_checkpoint"] = {
+                    "fwd_ms": round(f3, 4), "bwd_ms": round(b3, 4),
+                    "fwd_roofline_frac": roofline_entry(flops_forward(w3, wl3.B, wl3.L), f3)["frac"],
+                    "bwd_roofline_frac": roofline_entry(flops_backward(w3, wl3.B, wl3.L), b3)["frac"],
+                    "kernels": [w3.kernel_name(False, wl3.B, wl3.L + 1), w3.kernel_name(True, wl3.B, wl3.L + 1)]}
+                del s3
             del s2
             torch.cuda.empty_cache()
         out["per_workload"] = per

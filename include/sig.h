@@ -114,7 +114,8 @@ const int64_t* sig_wordset_user_index(const sig_wordset* ws);   /* host [n_user]
  *   "lanes_levels"  [SIG_LANES_LEVELS]   levels below the lane's word: 0 auto, 1, 2
  *   "logsig_gather" [SIG_LOGSIG_GATHER]  1: two-kernel form of sig_logsig_backward
  *   "jit_wg_waves"  [SIG_JIT_WG_WAVES]   wavefronts per workgroup of the specialised kernels, 1..4 (default 4)
- *   "bwd_tile"      [SIG_BWD_TILE]       segments per LDS tile of the d = 16 backward kernel: 0 default, 8, 16
+ *   "bwd_tile"      [SIG_BWD_TILE]       segments per LDS tile of the d = 16 (8, 16) and d = 8 (4, 8) backward kernels
+ *   "ckpt_chunks"   [SIG_CKPT_CHUNKS]    time chunks of the checkpointed calls: 0 launcher's rule, 1 off, 2..4 forced
  * Workspace sizes depend on the knobs: query them again after a change.  Returns SIG_EINVAL for an unknown name.
  * Not to be called while another thread runs sig_forward / sig_backward on the same word set. */
 int sig_wordset_set_option(sig_wordset* ws, const char* name, int value);
@@ -203,6 +204,29 @@ size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_
 int    sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs,
                     int64_t B, int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes,
                     void* stream);
+
+/* ---- forward and backward with time chunks kept between the two calls --------------------------------------------
+ * Chen's relation (eq. 2) lets a path be cut into C consecutive chunks whose signatures multiply to the signature of
+ * the path.  sig_forward_checkpointed computes the chunk signatures side by side, leaves them in `checkpoint` (device,
+ * [B, C, |W|] float32, 256-byte aligned, sig_checkpoint_bytes bytes, the caller's to keep until the backward call)
+ * and writes their product to coeffs.  sig_backward_checkpointed then walks the C chunks of every path side by side:
+ * the signature at the end of chunk c is the product of the first c chunk signatures, the adjoint there is
+ * Abar_c(u) = sum_v grad_coeffs(u v) Q_c(v) with Q_c the product of the chunk signatures after c (Proposition 4.1
+ * with the right factor taken at a chunk boundary), and inside a chunk the recursion is that of sig_backward
+ * (Proposition 4.6).  Nothing is recomputed; the price is C times the memory of coeffs between the two calls, where
+ * sig_forward / sig_backward keep the terminal signature alone (Section 4.2).  The library picks C for the batch
+ * (2 .. 4, for full truncations whose backward kernel would otherwise leave SIMDs with a single wavefront: few
+ * paths with many segments); where it sees no gain sig_checkpoint_bytes is 0, `checkpoint` is not touched and the
+ * two calls are sig_forward / sig_backward.  Results agree with sig_forward / sig_backward to rounding. */
+size_t sig_checkpoint_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
+size_t sig_forward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
+size_t sig_backward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
+int    sig_forward_checkpointed(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs,
+                                void* checkpoint, size_t checkpoint_bytes, void* workspace, size_t workspace_bytes,
+                                void* stream);
+int    sig_backward_checkpointed(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs,
+                                 const void* checkpoint, size_t checkpoint_bytes, int64_t B, int64_t n_points,
+                                 float* grad_path, void* workspace, size_t workspace_bytes, void* stream);
 
 /* The same computation for callers that cannot allocate device memory (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc): no workspace argument; the buffers sig_backward takes from its workspace

@@ -88,6 +88,11 @@ def load_library():
     sig("sig_backward_workspace_bytes", c_sz, [c_p, c_i64, c_i64])
     sig("sig_forward", c_int, [c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
     sig("sig_backward", c_int, [c_p, c_p, c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p])
+    sig("sig_checkpoint_bytes", c_sz, [c_p, c_i64, c_i64])
+    sig("sig_forward_checkpointed_workspace_bytes", c_sz, [c_p, c_i64, c_i64])
+    sig("sig_backward_checkpointed_workspace_bytes", c_sz, [c_p, c_i64, c_i64])
+    sig("sig_forward_checkpointed", c_int, [c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p, c_sz, c_p])
+    sig("sig_backward_checkpointed", c_int, [c_p, c_p, c_p, c_p, c_p, c_sz, c_i64, c_i64, c_p, c_p, c_sz, c_p])
     sig("sig_backward_static", c_int, [c_p, c_p, c_p, c_p, c_i64, c_i64, c_p, c_p])
     sig("sig_wordset_set_option", c_int, [c_p, ctypes.c_char_p, c_int])
     sig("sig_wordset_get_option", c_int, [c_p, ctypes.c_char_p, ctypes.POINTER(c_int)])
@@ -539,6 +544,67 @@ def sig_backward(ws: WordSet, path, coeffs, grad_coeffs, out=None, workspace=Non
         _check(lib.sig_backward(ws._h, ctypes.c_void_p(path.data_ptr()), ctypes.c_void_p(coeffs.data_ptr()),
                                 ctypes.c_void_p(grad_coeffs.data_ptr()), B, P, ctypes.c_void_p(out.data_ptr()),
                                 ctypes.c_void_p(wptr), nbytes, ctypes.c_void_p(stream)), "sig_backward")
+    if keep is not None:
+        keep.record_stream(torch.cuda.current_stream(path.device))
+    return out
+
+
+def sig_forward_checkpointed(ws: WordSet, path, out=None, checkpoint=None, workspace=None):
+    """sig_forward that also leaves the time-chunk signatures in `checkpoint` for sig_backward_checkpointed.
+    Returns (coeffs, checkpoint); checkpoint is a uint8 CUDA tensor (empty where the library takes no chunks)."""
+    import torch
+    if not path.is_cuda or path.dtype != torch.float32 or path.dim() != 3 or path.shape[2] != ws.dim:
+        raise ValueError("path must be a float32 CUDA tensor [B, L+1, d] with the word set's d")
+    path = path.contiguous()
+    B, P, _ = path.shape
+    lib = load_library()
+    if out is None:
+        out = torch.empty((B, ws.size), dtype=torch.float32, device=path.device)
+    nck = int(lib.sig_checkpoint_bytes(ws._h, B, P))
+    if checkpoint is None:
+        checkpoint = torch.empty(nck, dtype=torch.uint8, device=path.device)
+    nbytes = int(lib.sig_forward_checkpointed_workspace_bytes(ws._h, B, P))
+    if workspace is None:
+        keep, wptr = _aligned_workspace(nbytes, path.device)
+    else:
+        keep, wptr, nbytes = None, workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    with torch.cuda.device(path.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(lib.sig_forward_checkpointed(ws._h, ctypes.c_void_p(path.data_ptr()), B, P, ctypes.c_void_p(out.data_ptr()),
+                                            ctypes.c_void_p(checkpoint.data_ptr() if checkpoint.numel() else 0),
+                                            checkpoint.numel() * checkpoint.element_size(), ctypes.c_void_p(wptr), nbytes,
+                                            ctypes.c_void_p(stream)), "sig_forward_checkpointed")
+    if keep is not None:
+        keep.record_stream(torch.cuda.current_stream(path.device))
+    return out, checkpoint
+
+
+def sig_backward_checkpointed(ws: WordSet, path, coeffs, grad_coeffs, checkpoint, out=None, workspace=None):
+    """sig_backward over the time chunks sig_forward_checkpointed left in `checkpoint`."""
+    import torch
+    for name, t in (("path", path), ("coeffs", coeffs), ("grad_coeffs", grad_coeffs)):
+        if not t.is_cuda or t.dtype != torch.float32:
+            raise ValueError(f"{name} must be a float32 CUDA tensor")
+    path, coeffs, grad_coeffs = path.contiguous(), coeffs.contiguous(), grad_coeffs.contiguous()
+    B, P, d = path.shape
+    if d != ws.dim or tuple(coeffs.shape) != (B, ws.size) or tuple(grad_coeffs.shape) != (B, ws.size):
+        raise ValueError("shape mismatch")
+    lib = load_library()
+    if out is None:
+        out = torch.empty((B, P, d), dtype=torch.float32, device=path.device)
+    nbytes = int(lib.sig_backward_checkpointed_workspace_bytes(ws._h, B, P))
+    if workspace is None:
+        keep, wptr = _aligned_workspace(nbytes, path.device)
+    else:
+        keep, wptr, nbytes = None, workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    with torch.cuda.device(path.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(lib.sig_backward_checkpointed(ws._h, ctypes.c_void_p(path.data_ptr()), ctypes.c_void_p(coeffs.data_ptr()),
+                                             ctypes.c_void_p(grad_coeffs.data_ptr()),
+                                             ctypes.c_void_p(checkpoint.data_ptr() if checkpoint.numel() else 0),
+                                             checkpoint.numel() * checkpoint.element_size(), B, P,
+                                             ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(wptr), nbytes,
+                                             ctypes.c_void_p(stream)), "sig_backward_checkpointed")
     if keep is not None:
         keep.record_stream(torch.cuda.current_stream(path.device))
     return out

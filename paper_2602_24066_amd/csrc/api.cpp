@@ -42,6 +42,7 @@ const OptionName kOptions[] = {
     {"logsig_gather", "SIG_LOGSIG_GATHER", &sig::WordSet::Options::logsig_gather},
     {"jit_wg_waves", "SIG_JIT_WG_WAVES", &sig::WordSet::Options::jit_wg_waves},
     {"bwd_tile", "SIG_BWD_TILE", &sig::WordSet::Options::bwd_tile},
+    {"ckpt_chunks", "SIG_CKPT_CHUNKS", &sig::WordSet::Options::ckpt_chunks},
 };
 void options_from_environment(sig::WordSet& w)
 {
@@ -167,6 +168,29 @@ BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points
     const int64_t Lc = (L + C - 1) / C;
     if ((C - 1) * Lc >= L) return s;
     return BwdShape{true, true, C, Lc};
+}
+// Checkpointed form (sig_forward_checkpointed / sig_backward_checkpointed): the forward pass leaves the signatures of C
+// time chunks of every path in a buffer the caller keeps, and the backward pass walks the C chunks side by side
+// without recomputing them.  Taken where the backward kernel of a full truncation has too few rows to put two
+// wavefronts on every SIMD (the d = 8 kernel: eight wavefronts per row); C = 2 .. 4, chunks of at least 64 segments.
+// "ckpt_chunks" forces a count (0: this rule, 1: off).
+Chunks checkpoint_chunks(const sig::WordSet& w, int64_t B, int64_t n_points)
+{
+    const int64_t L = n_points - 1;
+    int64_t C = 1;
+    if (w.kind == 0 && B >= 1 && B <= 65535 && sig::trunc_backward_available(w.d, w.depth) && sig::chunking_available(w.d, w.depth) &&
+        !sig::trunc_backward_tails_available(w.d, w.depth)) {
+        if (w.opt.ckpt_chunks > 0) {
+            C = std::min<int64_t>(w.opt.ckpt_chunks, 4);
+        } else if (w.d == 8) {
+            const int64_t rows_wanted = 2048 / sig::trunc_waves_per_row(w.d, w.depth, 1);
+            C = std::min<int64_t>(4, (rows_wanted + B - 1) / B);
+        }
+        C = std::max<int64_t>(1, std::min<int64_t>(C, L / 64));
+    }
+    if (C < 2) return Chunks{1, L};
+    const int64_t Lc = (L + C - 1) / C;
+    return Chunks{(L + Lc - 1) / Lc, Lc};
 }
 size_t chunk_array_bytes(const sig::WordSet& w, int64_t B, int64_t C)
 {
@@ -763,6 +787,48 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
 
 // sig_backward and sig_backward_static: the same kernels on the caller's workspace or on the static scratch array;
 // `how` says whether a run-time specialised kernel may be compiled and loaded by this call.
+static size_t gdx_bytes_of(const sig::WordSet& w, int64_t B, int64_t n_points)
+{
+    return ((size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;
+}
+
+// Backward over the C time chunks whose signatures the forward pass left in ckpt [B][C][|W|]: signature and adjoint at
+// the end of every chunk from products of the chunk signatures, then all (path, chunk) rows in one launch.
+static int backward_checkpointed(const sig::WordSet& w, const float* path, const float* coeffs, const float* grad_coeffs,
+                                 const float* ckpt, const Chunks& ch, int64_t B, int64_t n_points, float* grad_path,
+                                 void* workspace, hipStream_t st)
+{
+    if ((((uintptr_t)coeffs | (uintptr_t)grad_coeffs | (uintptr_t)ckpt) & 15) != 0) return SIG_EINVAL;
+    const int64_t nW = w.size();
+    const size_t gb = gdx_bytes_of(w, B, n_points), nb = chunk_array_bytes(w, B, ch.C);
+    float* gdx = (float*)workspace;
+    float* Abar = (float*)((unsigned char*)workspace + gb);
+    CallTimer whole(1, st);
+    hipError_t e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
+    const float* row_coeffs = ckpt;
+    if (ch.C == 2) {
+        // two chunks: the signature at the end of the first is the first chunk's own, what follows it the second's
+        if (e == hipSuccess) e = sig::chunk_adjoint(w.d, w.depth, grad_coeffs, ckpt + nW, Abar, B, 2, true, st);
+    } else {
+        float* Pfx = (float*)((unsigned char*)workspace + gb + nb);
+        float* Q = (float*)((unsigned char*)workspace + gb + 2 * nb);
+        bool adjoints_done = false;
+        if (e == hipSuccess)
+            e = sig::chunk_scan(w.d, w.depth, ckpt, Pfx, Q, coeffs, nullptr, grad_coeffs, Abar, B, (int)ch.C, &adjoints_done, st);
+        if (e == hipSuccess && !adjoints_done) e = sig::chunk_adjoint(w.d, w.depth, grad_coeffs, Q, Abar, B, (int)ch.C, true, st);
+        row_coeffs = Pfx;
+    }
+    if (e != hipSuccess) return hip_fail(e);
+    hipEvent_t* pe = g_prof.next(1);
+    if (pe) (void)hipEventRecord(pe[0], st);
+    // the rows of the last chunk are the caller's terminal signature and gradient themselves
+    e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, Abar, coeffs, grad_coeffs, B, n_points, ch.C, ch.Lc, gdx, w.opt.bwd_tile, st);
+    if (pe) (void)hipEventRecord(pe[1], st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
+    return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
 static int backward_impl(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
                          int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes, void* stream, Build how)
 {
@@ -809,7 +875,7 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
             bool adjoints_done = false;
             if (e == hipSuccess)
                 e = sig::chunk_scan(w.d, w.depth, Sc, Pfx, Q, coeffs, nullptr, grad_coeffs, Abar, B, (int)ch.C, &adjoints_done, st);
-            if (e == hipSuccess && !adjoints_done) e = sig::chunk_adjoint(w.d, w.depth, grad_coeffs, Q, Abar, B, (int)ch.C, st);
+            if (e == hipSuccess && !adjoints_done) e = sig::chunk_adjoint(w.d, w.depth, grad_coeffs, Q, Abar, B, (int)ch.C, false, st);
             if (e != hipSuccess) return hip_fail(e);
             row_coeffs = Pfx;
             row_grad = Abar;
@@ -823,7 +889,7 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
         else if (ch.tails)
             e = sig::trunc_backward_tails(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx,
                                           points ? grad_path : nullptr, st);
-        else e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx, w.opt.bwd_tile, st);
+        else e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, nullptr, nullptr, B, n_points, ch.C, ch.Lc, gdx, w.opt.bwd_tile, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
         if (!points) e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
@@ -890,6 +956,77 @@ int sig_backward(const sig_wordset* ws, const float* path, const float* coeffs, 
 {
     return backward_impl(ws, path, coeffs, grad_coeffs, B, n_points, grad_path, workspace, workspace_bytes, stream,
                          Build::compile_and_load);
+}
+
+size_t sig_checkpoint_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
+{
+    if (!ws || B <= 0 || n_points <= 1) return 0;
+    const Chunks ch = checkpoint_chunks(*W(ws), B, n_points);
+    return ch.C >= 2 ? chunk_array_bytes(*W(ws), B, ch.C) : 0;
+}
+
+size_t sig_forward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
+{
+    if (!ws || B <= 0 || n_points <= 1) return 0;
+    const Chunks ch = checkpoint_chunks(*W(ws), B, n_points);
+    if (ch.C < 2) return sig_forward_workspace_bytes(ws, B, n_points);
+    return ch.C > 3 ? chunk_array_bytes(*W(ws), B, ch.C) : 0;            // partial products of four chunks
+}
+
+size_t sig_backward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
+{
+    if (!ws || B <= 0 || n_points <= 1) return 0;
+    const sig::WordSet& w = *W(ws);
+    const Chunks ch = checkpoint_chunks(w, B, n_points);
+    if (ch.C < 2) return sig_backward_workspace_bytes(ws, B, n_points);
+    // gradient of the increments, boundary adjoints; beyond two chunks also the products before and after every chunk
+    return gdx_bytes_of(w, B, n_points) + (ch.C == 2 ? 1 : 3) * chunk_array_bytes(w, B, ch.C);
+}
+
+int sig_forward_checkpointed(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs,
+                             void* checkpoint, size_t checkpoint_bytes, void* workspace, size_t workspace_bytes, void* stream)
+{
+    int rc = check_common(ws, path, B, n_points);
+    if (rc != SIG_OK) return rc;
+    const sig::WordSet& w = *W(ws);
+    const Chunks ch = (B > 0 && n_points > 1) ? checkpoint_chunks(w, B, n_points) : Chunks{1, 0};
+    if (ch.C < 2) return sig_forward(ws, path, B, n_points, coeffs, workspace, workspace_bytes, stream);
+    if (!coeffs) return SIG_EINVAL;
+    const size_t nb = chunk_array_bytes(w, B, ch.C);
+    if (!checkpoint || checkpoint_bytes < nb) return SIG_EWORKSPACE;
+    if (((uintptr_t)checkpoint & 255) != 0 || ((uintptr_t)coeffs & 15) != 0) return SIG_EINVAL;
+    float* Pfx = nullptr;
+    if (ch.C > 3) {
+        if (!workspace || workspace_bytes < nb) return SIG_EWORKSPACE;
+        if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
+        Pfx = (float*)workspace;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    CallTimer whole(0, st);
+    float* Sc = (float*)checkpoint;
+    hipEvent_t* pe = g_prof.next(0);
+    if (pe) (void)hipEventRecord(pe[0], st);
+    hipError_t e = sig::trunc_forward(w.d, w.depth, path, B, n_points, ch.C, ch.Lc, Sc, st);
+    if (pe) (void)hipEventRecord(pe[1], st);
+    if (e == hipSuccess) e = sig::chunk_scan(w.d, w.depth, Sc, Pfx, nullptr, nullptr, coeffs, nullptr, nullptr, B, (int)ch.C, nullptr, st);
+    return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
+int sig_backward_checkpointed(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs,
+                              const void* checkpoint, size_t checkpoint_bytes, int64_t B, int64_t n_points, float* grad_path,
+                              void* workspace, size_t workspace_bytes, void* stream)
+{
+    int rc = check_common(ws, path, B, n_points);
+    if (rc != SIG_OK) return rc;
+    const sig::WordSet& w = *W(ws);
+    const Chunks ch = (B > 0 && n_points > 1) ? checkpoint_chunks(w, B, n_points) : Chunks{1, 0};
+    if (ch.C < 2) return sig_backward(ws, path, coeffs, grad_coeffs, B, n_points, grad_path, workspace, workspace_bytes, stream);
+    if (!coeffs || !grad_coeffs || !grad_path) return SIG_EINVAL;
+    if (!checkpoint || checkpoint_bytes < chunk_array_bytes(w, B, ch.C)) return SIG_EWORKSPACE;
+    if (!workspace || workspace_bytes < sig_backward_checkpointed_workspace_bytes(ws, B, n_points)) return SIG_EWORKSPACE;
+    if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)checkpoint & 255) != 0) return SIG_EINVAL;
+    return backward_checkpointed(w, path, coeffs, grad_coeffs, (const float*)checkpoint, ch, B, n_points, grad_path, workspace,
+                                 (hipStream_t)stream);
 }
 
 int sig_backward_static(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,

@@ -78,8 +78,12 @@ int trunc_waves_per_row(int d, int depth, int backward);    // wavefronts per (p
 hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t P, int64_t C, int64_t Lc, float* coeffs,
                          hipStream_t stream);
 // tile: segments per LDS tile where a kernel offers a choice (d = 16: 8 or 16; 0 = the default)
-hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
-                          int64_t P, int64_t C, int64_t Lc, float* gdx, int tile, hipStream_t stream);
+// coeffs_last / grad_last (both or neither): [B][|W|] arrays that hold the rows of the last chunk of every path, while
+// coeffs / grad_coeffs hold the other chunks' rows in [B][C][|W|] (the last slot of a path unused); nullptr: all rows
+// are in coeffs / grad_coeffs
+hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs,
+                          const float* coeffs_last, const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
+                          float* gdx, int tile, hipStream_t stream);
 const char* trunc_backward_kernel_name(int d, int depth);   // of the kernel trunc_backward launches
 
 // d = 4: backward with one wavefront per row (a lane holds a word of length N - 3 and its four children); stores
@@ -110,7 +114,8 @@ hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, c
 // (backward, small signatures: when grad [B, |W|] and Abar [B, C, |W|] are given the kernel also forms the boundary
 // adjoints and *adjoints_done is set; otherwise call chunk_adjoint afterwards)
 // Abar [B, C, |W|]: adjoint of the signature at the end of every chunk, from grad [B, |W|] and Q
-hipError_t chunk_adjoint(int d, int depth, const float* grad, const float* Q, float* Abar, int64_t B, int C,
+// (skip_last: the last chunk's row of Abar, a copy of grad, is not written)
+hipError_t chunk_adjoint(int d, int depth, const float* grad, const float* Q, float* Abar, int64_t B, int C, bool skip_last,
                          hipStream_t stream);
 
 }  // namespace sig

@@ -68,11 +68,15 @@ __device__ __forceinline__ void copy_row(const float* src, float* dst, float* ds
 // out(u) = gr(u) + sum_{m >= 1} sum_{|v| = m} gr(u v) q(v) for every word u, by the whole workgroup.  The words of
 // one length k are spread over the workgroup, with blockDim / d^k threads (at most 64, at least 1) sharing the
 // inner sums of a word; for a fixed m the terms of a word are contiguous in gr and in q.
-__device__ __forceinline__ void adjoint_contract(const float* gr, const float* q, float* __restrict__ out, const Levels& g)
+// (k_only > 0: the words of that length alone, and with k_only == 1 also the copy of the longest words, so that a
+// grid of N - 1 workgroups per row shares the work)
+__device__ __forceinline__ void adjoint_contract(const float* gr, const float* q, float* __restrict__ out, const Levels& g,
+                                                 int k_only = 0)
 {
     const int N = g.N;
-    copy_row(gr + g.ls[N], out + g.ls[N], nullptr, g.W - g.ls[N]);       // words of length N
+    if (k_only <= 1) copy_row(gr + g.ls[N], out + g.ls[N], nullptr, g.W - g.ls[N]);       // words of length N
     for (int k = 1; k < N; ++k) {
+        if (k_only > 0 && k != k_only) continue;
         const int nk = g.ls[k + 1] - g.ls[k];                           // words of length k
         int tpw = (int)blockDim.x / nk;                                 // threads per word (power of two)
         tpw = tpw > 64 ? 64 : (tpw < 1 ? 1 : tpw);
@@ -263,7 +267,7 @@ __global__ __launch_bounds__(256) void chunk_product3_kernel(const float* __rest
 // word are contiguous in grad and in Q.
 template <bool LDS>
 __global__ __launch_bounds__(512) void chunk_adjoint_kernel(const float* __restrict__ grad, const float* __restrict__ Q,
-                                                            float* __restrict__ Abar, int C, Levels g)
+                                                            float* __restrict__ Abar, int C, bool skip_last, Levels g)
 {
     extern __shared__ f4 smem4[];
     float* sm = (float*)smem4;
@@ -274,7 +278,7 @@ __global__ __launch_bounds__(512) void chunk_adjoint_kernel(const float* __restr
     const float* gr = grad + b * W;
     float* out = Abar + row * W;
     if (c == C - 1) {
-        copy_row(gr, out, nullptr, W);
+        if (!skip_last && blockIdx.y == 0) copy_row(gr, out, nullptr, W);
         return;
     }
     const float* q = Q + row * W;
@@ -285,7 +289,81 @@ __global__ __launch_bounds__(512) void chunk_adjoint_kernel(const float* __restr
         gr = sm;
         q = sm + W;
     }
-    adjoint_contract(gr, q, out, g);
+    // large signatures: one workgroup per (row, word length), their sums read global memory and are bound by latency
+    adjoint_contract(gr, q, out, g, gridDim.y > 1 ? (int)blockIdx.y + 1 : 0);
+}
+
+// The same sums for large signatures, one workgroup per (path, chunk, first letter a): every word u that begins with a
+// gets Abar(u) = grad(u) + sum_v grad(u v) Q(v).  The words u v all begin with a too, so workgroups share no output,
+// and what a workgroup reads - the gradients of the words a v and Q(v) for |v| < N, 2 (d + .. + d^(N-1)) floats - is
+// staged in LDS once: sg[ls[m] + v] = grad(a v), sq[ls[m] + v] = Q(v) for |v| = m.  All 512 threads work on one word
+// length at a time and split the sums of a word between 512 / (words of that length) of them (whole wavefronts add
+// up through LDS), so that short words, whose sums run over thousands of terms, take as few rounds as long ones.
+__global__ __launch_bounds__(512) void chunk_adjoint_subtree_kernel(const float* __restrict__ grad, const float* __restrict__ Q,
+                                                                    float* __restrict__ Abar, int C, Levels g)
+{
+    extern __shared__ f4 smem4[];
+    __shared__ float red[8];
+    const int64_t row = blockIdx.x;
+    const int64_t b = row / C;
+    if ((int)(row - b * C) == C - 1) return;             // the last chunk's adjoint is the gradient itself
+    const int a = (int)blockIdx.y;
+    const int N = g.N, W = g.W, lb = g.lb;
+    const int below = g.ls[N];                           // words shorter than N
+    float* sq = (float*)smem4;
+    float* sg = sq + below;
+    const float* gr = grad + b * W;
+    const float* q = Q + row * W;
+    float* out = Abar + row * W;
+    const int tid = (int)threadIdx.x, nthr = (int)blockDim.x;
+    for (int m = 1; m < N; ++m) {
+        const int cnt = 1 << (lb * m);
+        const float* src = gr + g.ls[m + 1] + (int64_t)a * cnt;      // the words a v, |v| = m
+        for (int v = tid; v < cnt; v += nthr) {
+            sq[g.ls[m] + v] = q[g.ls[m] + v];
+            sg[g.ls[m] + v] = src[v];
+        }
+    }
+    {
+        const int cnt = 1 << (lb * (N - 1));             // words of length N that begin with a: copied
+        const float* src = sg + g.ls[N - 1];
+        float* dst = out + g.ls[N] + a * cnt;
+        __syncthreads();
+        for (int o = 4 * tid; o < cnt; o += 4 * nthr) *(f4*)(dst + o) = *(const f4*)(src + o);
+    }
+    for (int k = 1; k < N; ++k) {
+        const int nk = 1 << (lb * (k - 1));              // words of length k that begin with a: u = a u', |u'| = k - 1
+        int tpw = nthr / nk;                             // threads per word (a power of two)
+        tpw = tpw < 1 ? 1 : tpw;
+        const int wpp = nthr / tpw;                      // words per pass
+        const int t = tid % tpw;
+        for (int i0 = 0; i0 < nk; i0 += wpp) {
+            const int iw = i0 + tid / tpw;               // u' inside its length
+            float acc = 0.0f;
+            if (iw < nk)
+                for (int m = 1; m <= N - k; ++m) {
+                    const int cnt = 1 << (lb * m);
+                    const float* src = sg + g.ls[k - 1 + m] + (iw << (lb * m));   // the words a u' v
+                    const float* qv = sq + g.ls[m];
+                    for (int v = t; v < cnt; v += tpw) acc = fmaf(src[v], qv[v], acc);
+                }
+            const int within = tpw < 64 ? tpw : 64;
+            for (int off = within >> 1; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+            if (tpw > 64) {                              // a word's threads span tpw / 64 consecutive wavefronts
+                __syncthreads();
+                if ((tid & 63) == 0) red[tid >> 6] = acc;
+                __syncthreads();
+                if (t == 0) {
+                    acc = 0.0f;
+                    for (int wv = 0; wv < tpw / 64; ++wv) acc += red[(tid >> 6) + wv];
+                }
+            }
+            if (iw < nk && t == 0) {
+                const float own = k == 1 ? gr[g.ls[1] + a] : sg[g.ls[k - 1] + iw];
+                out[g.ls[k] + a * nk + iw] = own + acc;
+            }
+        }
+    }
 }
 
 constexpr size_t kMaxChunkLds = 96 * 1024;       // three signatures of up to 8,192 coefficients
@@ -359,14 +437,17 @@ hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, c
     return hipGetLastError();
 }
 
-hipError_t chunk_adjoint(int d, int depth, const float* grad, const float* Q, float* Abar, int64_t B, int C,
+hipError_t chunk_adjoint(int d, int depth, const float* grad, const float* Q, float* Abar, int64_t B, int C, bool skip_last,
                          hipStream_t stream)
 {
     Levels g;
     if (!make_levels(d, depth, g) || C < 2 || B < 1 || B * C > 0x7fffffff) return hipErrorInvalidValue;
     const size_t lds = 2 * (size_t)g.W * sizeof(float);
-    if (lds <= 64 * 1024) chunk_adjoint_kernel<true><<<(unsigned)(B * C), 512, lds, stream>>>(grad, Q, Abar, C, g);
-    else chunk_adjoint_kernel<false><<<(unsigned)(B * C), 512, 0, stream>>>(grad, Q, Abar, C, g);
+    if (lds <= 64 * 1024) chunk_adjoint_kernel<true><<<(unsigned)(B * C), 512, lds, stream>>>(grad, Q, Abar, C, skip_last, g);
+    else if (skip_last && g.lb * (g.N - 1) >= 2 && 2 * (size_t)g.ls[g.N] * sizeof(float) <= 64 * 1024)
+        chunk_adjoint_subtree_kernel<<<dim3((unsigned)(B * C), 1u << g.lb), 512, 2 * (size_t)g.ls[g.N] * sizeof(float), stream>>>(
+            grad, Q, Abar, C, g);
+    else chunk_adjoint_kernel<false><<<dim3((unsigned)(B * C), (unsigned)(g.N - 1)), 512, 0, stream>>>(grad, Q, Abar, C, skip_last, g);
     return hipGetLastError();
 }
 

@@ -600,8 +600,9 @@ struct BwdLds {
 
 template <int D, int N, int WQ, int T>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
-    const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
-    int64_t P, int64_t C, int64_t Lc, float* gdx)
+    const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad,
+    const float* __restrict__ coeffs_last, const float* __restrict__ grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
+    float* gdx)
 {
     static_assert((D & (D - 1)) == 0, "the gradient reduction takes letters as bit fields of the lane number");
     constexpr int K = N - 2;
@@ -647,8 +648,11 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     const float* X = path + (b * P + seg0) * D;
     const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
     const int64_t nW = level_start(D, N) + ipow(D, N);
-    const float* cf = coeffs + row * nW;
-    const float* gr = grad + row * nW;
+    // rows of the last chunk of a path may live in arrays of their own ([B][|W|]: the caller's terminal signature
+    // and gradient), the others in [B][C][|W|] arrays
+    const bool in_last = coeffs_last != nullptr && row - b * C == C - 1;
+    const float* cf = in_last ? coeffs_last + b * nW : coeffs + row * nW;
+    const float* gr = in_last ? grad_last + b * nW : grad + row * nW;
 
     int offS[NBS];
 #pragma unroll
@@ -1469,8 +1473,9 @@ struct NodeLds {
 
 template <int D, int N, int T>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
-    const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
-    int64_t P, int64_t C, int64_t Lc, float* gdx)
+    const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad,
+    const float* __restrict__ coeffs_last, const float* __restrict__ grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
+    float* gdx)
 {
     static_assert((D & (D - 1)) == 0, "the gradient reduction takes letters as bit fields of the lane number");
     constexpr int K = N - 2;
@@ -1503,8 +1508,10 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
     const float* X = path + (b * P + seg0) * D;
     const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
     const int64_t nW = level_start(D, N) + ipow(D, N);
-    const float* cf = coeffs + row * nW;
-    const float* gr = grad + row * nW;
+    // rows of the last chunk of a path may live in arrays of their own ([B][|W|]), the others in [B][C][|W|] arrays
+    const bool in_last = coeffs_last != nullptr && row - b * C == C - 1;
+    const float* cf = in_last ? coeffs_last + b * nW : coeffs + row * nW;
+    const float* gr = in_last ? grad_last + b * nW : grad + row * nW;
 
     // ---- state: signature and adjoints at the end of the row
     float Sc[K], Ac[K];                    // chain (a word shared by several lanes has its adjoint in the first of them)
@@ -1674,8 +1681,9 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
 }
 
 template <int D, int N, int T = 8>
-hipError_t launch_trunc_node_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P, int64_t C,
-                                 int64_t Lc, float* gdx, hipStream_t stream)
+hipError_t launch_trunc_node_bwd(const float* path, const float* coeffs, const float* grad, const float* coeffs_last,
+                                 const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx,
+                                 hipStream_t stream)
 {
     using LY = NodeLds<D, N, T>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
@@ -1686,8 +1694,8 @@ hipError_t launch_trunc_node_bwd(const float* path, const float* coeffs, const f
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&trunc_node_bwd_kernel<D, N, T>), (int)LY::BYTES);
         if (e != hipSuccess) return e;
     }
-    trunc_node_bwd_kernel<D, N, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(path, coeffs, grad, B, P, C, Lc,
-                                                                                                  gdx);
+    trunc_node_bwd_kernel<D, N, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(
+        path, coeffs, grad, coeffs_last, grad_last, B, P, C, Lc, gdx);
     return hipGetLastError();
 }
 
@@ -1900,8 +1908,9 @@ hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const 
 }
 
 template <int D, int N, int WQ, int T>
-hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
-                                 int64_t C, int64_t Lc, float* gdx, hipStream_t stream)
+hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const float* grad, const float* coeffs_last,
+                                 const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx,
+                                 hipStream_t stream)
 {
     using G = MGeo<D, N, N - 2, WQ>;
     using LY = BwdLds<D, N, WQ, T>;
@@ -1913,8 +1922,8 @@ hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const f
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&trunc_mfma_bwd_kernel<D, N, WQ, T>), (int)LY::BYTES);
         if (e != hipSuccess) return e;
     }
-    trunc_mfma_bwd_kernel<D, N, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(path, coeffs, grad, B,
-                                                                                                      P, C, Lc, gdx);
+    trunc_mfma_bwd_kernel<D, N, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(
+        path, coeffs, grad, coeffs_last, grad_last, B, P, C, Lc, gdx);
     return hipGetLastError();
 }
 
@@ -2012,17 +2021,25 @@ const char* trunc_backward_kernel_name(int d, int depth)
 }
 
 // gdx: [B, L, d] accumulation buffer, zeroed by the caller
-hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
-                          int64_t P, int64_t C, int64_t Lc, float* gdx, int tile, hipStream_t stream)
+hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs,
+                          const float* coeffs_last, const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
+                          float* gdx, int tile, hipStream_t stream)
 {
-    if (d == 4 && depth == 6) return launch_trunc_node_bwd<4, 6>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
-    if (d == 8 && depth == 5)
-        return tile == 4 ? launch_trunc_node_bwd<8, 5, 4>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream)
-                         : launch_trunc_node_bwd<8, 5, 8>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
-    // d = 16: tiles of 8 segments keep a workgroup's LDS under half a compute unit's, so two wavefronts share a SIMD
+    if ((coeffs_last == nullptr) != (grad_last == nullptr)) return hipErrorInvalidValue;
+    if (d == 4 && depth == 6)
+        return launch_trunc_node_bwd<4, 6>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, stream);
+    // d = 8: tiles of 4 segments keep a workgroup's LDS at 50 KB, so that two (or three) workgroups share a compute unit:
+    // taken when the launch has the wavefronts for it
+    if (d == 8 && depth == 5) {
+        const bool small = tile == 4 || (tile == 0 && B * C * 8 >= 2048);
+        return small ? launch_trunc_node_bwd<8, 5, 4>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, stream)
+                     : launch_trunc_node_bwd<8, 5, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, stream);
+    }
+    // d = 16: tiles of 8 segments halve the LDS of a workgroup but fill only half of the columns of the time-batched
+    // matrix products; measured slower or equal at every batch size, kept selectable
     if (d == 16 && depth == 4)
-        return tile == 8 ? launch_trunc_mfma_bwd<16, 4, 1, 8>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream)
-                         : launch_trunc_mfma_bwd<16, 4, 1, 16>(path, coeffs, grad_coeffs, B, P, C, Lc, gdx, stream);
+        return tile == 8 ? launch_trunc_mfma_bwd<16, 4, 1, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, stream)
+                         : launch_trunc_mfma_bwd<16, 4, 1, 16>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, stream);
     return hipErrorInvalidValue;
 }
 

@@ -89,6 +89,7 @@ struct WordSet {
         int lanes = -1;                // word-per-lane kernels for full truncations: -1 auto, 0 off, 1 whenever defined
         int lanes_levels = 0;          // levels below the lane's word: 0 auto, 1, 2
         int logsig_gather = 0;         // 1: two-kernel form of the log-signature adjoint
+        int ckpt_chunks = 0;           // time chunks of the checkpointed forward / backward: 0 launcher's rule, 1 off, 2..4
         int bwd_tile = 0;              // segments per LDS tile of the d = 16 backward kernel: 0 default, 8, 16
         int jit_wg_waves = 4;          // wavefronts (work units) per workgroup of the run-time specialised kernels, 1..4;
                                        // 8 is accepted for inspecting the generated code on the host only: jit_load

@@ -130,6 +130,35 @@ def test_forward_chunks_in_one_workgroup(monkeypatch, B, L, chunks):
         check_parity(ws, W, "truncated", 6, X, G, what=f"fused forward B={B} L={L} C={chunks} {dist}")
 
 
+# Forward and backward with the time-chunk signatures kept between the two calls (checkpointed form): every chunk
+# count, chunk lengths that do not divide L, the launcher's own choice, and shapes where it takes no chunks at all
+@pytest.mark.parametrize("d,depth,B,L,chunks", [(8, 5, 2, 200, 0), (8, 5, 3, 131, 2), (8, 5, 2, 197, 3), (8, 5, 1, 260, 4),
+                                                (16, 4, 2, 150, 2), (16, 4, 1, 200, 3), (8, 5, 2, 40, 0), (4, 6, 3, 300, 0),
+                                                (3, 4, 5, 100, 0)])
+def test_checkpointed_forward_and_backward(d, depth, B, L, chunks):
+    import torch
+    ws, W = build_both("truncated", d, depth=depth)
+    if chunks:
+        ws.set_option("ckpt_chunks", chunks)
+    lib = S.load_library()
+    nck = int(lib.sig_checkpoint_bytes(ws._h, B, L + 1))
+    expect_chunks = chunks if chunks else (min(4, L // 64) if d == 8 and L >= 128 else 0)
+    assert nck == (4 * B * expect_chunks * ws.size + 255) // 256 * 256
+    X = make_path("iid", 2500 + L, B, L, d)
+    G = make_grad_coeffs(2600 + L, B, ws.size)
+    xp, grad = torch.from_numpy(X).cuda(), torch.from_numpy(G).cuda()
+    coeffs, ck = S.sig_forward_checkpointed(ws, xp)
+    assert ck.numel() == nck
+    gp = S.sig_backward_checkpointed(ws, xp, coeffs, grad, ck)
+    torch.cuda.synchronize()
+    coeffs, gp = coeffs.cpu().numpy(), gp.cpu().numpy()
+    lengths = np.array([len(w) for w in W])
+    for n, e in O.level_errors(coeffs, O.forward_dense(X, depth), lengths).items():
+        assert e <= FWD_TOL, f"checkpointed forward, level {n}: {e:.3e}"
+    gerr = O.grad_errors(gp, O.backward_dense(X, depth, G.astype(np.float64)))
+    assert gerr.max() <= BWD_TOL, f"checkpointed backward: {gerr.max():.3e}"
+
+
 def test_forward_fused_and_four_wavefront_kernels_agree():
     ws, W = build_both("truncated", 4, depth=6)
     X = make_path("time0", 21, 200, 255, 4)
