@@ -329,6 +329,12 @@ def main():
         "memory": {"peak_device_bytes": peak_mem, "mem_out_bytes": 4 * wl.B * ws.size,
                    "note": "inputs, outputs and workspaces of forward + backward held at once"},
     }
+    if wl.kind == "truncated" and ws.kernel_name(True).startswith("trunc_"):
+        # reconstruction drift: the terminal signature stepped back through all L segments should end at zero
+        _, resid = S.sig_backward_residual(ws, st["path"], st["coeffs"], st["grad"])
+        out["reconstruction"] = {"segments": wl.L, "residual_max_abs": float(f"{float(resid.max()):.3e}"),
+                                 "largest_coefficient": float(f"{float(st['coeffs'].abs().max()):.3e}"),
+                                 "note": "largest |S(w)| left after multiplying by exp(-dX_j) for j = L..1, over all paths"}
     head_row = workload_row(S, torch, st, sec, ms_f, ms_b, call_f, call_b, args.steps)
     if not args.no_cpu:
         cpu, errs = oracle_check(st, CPU_SAMPLE[wl.name])

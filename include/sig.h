@@ -205,6 +205,16 @@ int    sig_backward(const sig_wordset* ws, const float* path, const float* coeff
                     int64_t B, int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes,
                     void* stream);
 
+/* sig_backward with a check of the reconstruction it rests on (Lemma 4.5, Proposition 4.6): stepping the terminal
+ * signature back through all segments must end at the signature of the empty path, whose coefficients of non-empty
+ * words are zero.  residual: device float32 [B], receives per path the largest absolute value left in the
+ * reconstructed coefficients (words shorter than the depth: the longest words are never reconstructed).  Offered for
+ * the full truncations with a precompiled kernel (SIG_EUNSUPPORTED otherwise); runs the kernel that walks whole paths,
+ * so it measures the drift over all L segments.  Workspace as for sig_backward. */
+int    sig_backward_residual(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs,
+                             int64_t B, int64_t n_points, float* grad_path, float* residual /*device [B]*/,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- forward and backward with time chunks kept between the two calls --------------------------------------------
  * Chen's relation (eq. 2) lets a path be cut into C consecutive chunks whose signatures multiply to the signature of
  * the path.  sig_forward_checkpointed computes the chunk signatures side by side, leaves them in `checkpoint` (device,

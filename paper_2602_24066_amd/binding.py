@@ -93,6 +93,7 @@ def load_library():
     sig("sig_backward_checkpointed_workspace_bytes", c_sz, [c_p, c_i64, c_i64])
     sig("sig_forward_checkpointed", c_int, [c_p, c_p, c_i64, c_i64, c_p, c_p, c_sz, c_p, c_sz, c_p])
     sig("sig_backward_checkpointed", c_int, [c_p, c_p, c_p, c_p, c_p, c_sz, c_i64, c_i64, c_p, c_p, c_sz, c_p])
+    sig("sig_backward_residual", c_int, [c_p, c_p, c_p, c_p, c_i64, c_i64, c_p, c_p, c_p, c_sz, c_p])
     sig("sig_backward_static", c_int, [c_p, c_p, c_p, c_p, c_i64, c_i64, c_p, c_p])
     sig("sig_wordset_set_option", c_int, [c_p, ctypes.c_char_p, c_int])
     sig("sig_wordset_get_option", c_int, [c_p, ctypes.c_char_p, ctypes.POINTER(c_int)])
@@ -547,6 +548,33 @@ def sig_backward(ws: WordSet, path, coeffs, grad_coeffs, out=None, workspace=Non
     if keep is not None:
         keep.record_stream(torch.cuda.current_stream(path.device))
     return out
+
+
+def sig_backward_residual(ws: WordSet, path, coeffs, grad_coeffs):
+    """(grad_path, residual [B]): sig_backward plus, per path, the largest absolute coefficient left when the terminal
+    signature has been stepped back through all segments (zero in exact arithmetic)."""
+    import torch
+    path, coeffs, grad_coeffs = path.contiguous(), coeffs.contiguous(), grad_coeffs.contiguous()
+    B, P, d = path.shape
+    if d != ws.dim or tuple(coeffs.shape) != (B, ws.size) or tuple(grad_coeffs.shape) != (B, ws.size):
+        raise ValueError("shape mismatch")
+    lib = load_library()
+    out = torch.empty((B, P, d), dtype=torch.float32, device=path.device)
+    resid = torch.empty((B,), dtype=torch.float32, device=path.device)
+    bt = ws.get_option("bwd_tails")
+    ws.set_option("bwd_tails", 0)                 # workspace of the kernel that walks whole paths
+    nbytes = int(lib.sig_backward_workspace_bytes(ws._h, B, P))
+    ws.set_option("bwd_tails", bt)
+    keep, wptr = _aligned_workspace(nbytes, path.device)
+    with torch.cuda.device(path.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        _check(lib.sig_backward_residual(ws._h, ctypes.c_void_p(path.data_ptr()), ctypes.c_void_p(coeffs.data_ptr()),
+                                         ctypes.c_void_p(grad_coeffs.data_ptr()), B, P, ctypes.c_void_p(out.data_ptr()),
+                                         ctypes.c_void_p(resid.data_ptr()), ctypes.c_void_p(wptr), nbytes,
+                                         ctypes.c_void_p(stream)), "sig_backward_residual")
+    if keep is not None:
+        keep.record_stream(torch.cuda.current_stream(path.device))
+    return out, resid
 
 
 def sig_forward_checkpointed(ws: WordSet, path, out=None, checkpoint=None, workspace=None):

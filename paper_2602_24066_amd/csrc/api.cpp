@@ -197,6 +197,11 @@ size_t chunk_array_bytes(const sig::WordSet& w, int64_t B, int64_t C)
     return ((size_t)B * (size_t)C * (size_t)w.size() * sizeof(float) + 255) & ~(size_t)255;
 }
 
+// arrays [B][C][|W|] a chunked forward pass takes from its workspace: the chunk signatures, and the partial products
+// when four or more large signatures are multiplied pair by pair (two or three, and signatures that fit LDS, are
+// multiplied in one kernel)
+size_t forward_chunk_arrays(const sig::WordSet& w, int64_t C) { return (C >= 4 && w.size() > 8192) ? 2 : 1; }
+
 bool use_trunc_forward(const sig::WordSet& w, int64_t B)
 {
     return w.kind == 0 && B <= 65535 && sig::trunc_forward_available(w.d, w.depth);
@@ -669,7 +674,7 @@ size_t sig_forward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_p
     const sig::WordSet& w = *W(ws);
     if (use_trunc_forward(w, B)) {
         const Chunks ch = trunc_chunks(w, 0, B, n_points);
-        return ch.C > 1 ? 2 * chunk_array_bytes(w, B, ch.C) : 0;      // chunk signatures + partial products
+        return ch.C > 1 ? forward_chunk_arrays(w, ch.C) * chunk_array_bytes(w, B, ch.C) : 0;
     }
     if (!jit_enabled(w)) return 0;
     return jit_dxt_bytes(w, B, n_points, 0);
@@ -729,10 +734,10 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
         float* Pfx = nullptr;
         if (ch.C > 1) {
             const size_t nb = chunk_array_bytes(w, B, ch.C);
-            if (!workspace || workspace_bytes < 2 * nb) return SIG_EWORKSPACE;
+            if (!workspace || workspace_bytes < forward_chunk_arrays(w, ch.C) * nb) return SIG_EWORKSPACE;
             if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)coeffs & 15) != 0) return SIG_EINVAL;
             Sc = (float*)workspace;
-            Pfx = (float*)((unsigned char*)workspace + nb);
+            if (forward_chunk_arrays(w, ch.C) > 1) Pfx = (float*)((unsigned char*)workspace + nb);
         }
         hipEvent_t* pe = g_prof.next(0);
         if (pe) (void)hipEventRecord(pe[0], st);
@@ -822,7 +827,8 @@ static int backward_checkpointed(const sig::WordSet& w, const float* path, const
     hipEvent_t* pe = g_prof.next(1);
     if (pe) (void)hipEventRecord(pe[0], st);
     // the rows of the last chunk are the caller's terminal signature and gradient themselves
-    e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, Abar, coeffs, grad_coeffs, B, n_points, ch.C, ch.Lc, gdx, w.opt.bwd_tile, st);
+    e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, Abar, coeffs, grad_coeffs, B, n_points, ch.C, ch.Lc, gdx, nullptr,
+                            w.opt.bwd_tile, st);
     if (pe) (void)hipEventRecord(pe[1], st);
     if (e != hipSuccess) return hip_fail(e);
     e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
@@ -830,7 +836,8 @@ static int backward_checkpointed(const sig::WordSet& w, const float* path, const
 }
 
 static int backward_impl(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
-                         int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes, void* stream, Build how)
+                         int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes, void* stream, Build how,
+                         float* residual = nullptr)
 {
     int rc = check_common(ws, path, B, n_points);
     if (rc != SIG_OK) return rc;
@@ -850,6 +857,12 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
     hipError_t e = hipSuccess;
     const bool trunc = use_trunc_backward(w, B);
     BwdShape ch = trunc ? trunc_backward_shape(w, B, n_points) : BwdShape{false, false, 1, n_points - 1};
+    if (residual) {                      // reported by the kernels that walk whole paths with several wavefronts per row
+        if (!trunc) return SIG_EUNSUPPORTED;
+        ch = BwdShape{false, false, 1, n_points - 1};
+        e = sig::fill_zero(residual, B, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
     // the fused form copies the gradient row with 16-byte loads; rows that are not aligned so take the kernel with
     // four wavefronts per path, which reads word by word
     if (ch.fused && (((uintptr_t)coeffs | (uintptr_t)grad_coeffs) & 15) != 0) ch = BwdShape{false, false, 1, n_points - 1};
@@ -889,7 +902,8 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
         else if (ch.tails)
             e = sig::trunc_backward_tails(w.d, w.depth, path, row_coeffs, row_grad, B, n_points, ch.C, ch.Lc, gdx,
                                           points ? grad_path : nullptr, st);
-        else e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, nullptr, nullptr, B, n_points, ch.C, ch.Lc, gdx, w.opt.bwd_tile, st);
+        else e = sig::trunc_backward(w.d, w.depth, path, row_coeffs, row_grad, nullptr, nullptr, B, n_points, ch.C, ch.Lc, gdx, residual,
+                                     w.opt.bwd_tile, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
         if (!points) e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
@@ -970,7 +984,7 @@ size_t sig_forward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B
     if (!ws || B <= 0 || n_points <= 1) return 0;
     const Chunks ch = checkpoint_chunks(*W(ws), B, n_points);
     if (ch.C < 2) return sig_forward_workspace_bytes(ws, B, n_points);
-    return ch.C > 3 ? chunk_array_bytes(*W(ws), B, ch.C) : 0;            // partial products of four chunks
+    return forward_chunk_arrays(*W(ws), ch.C) > 1 ? chunk_array_bytes(*W(ws), B, ch.C) : 0;   // partial products of four chunks
 }
 
 size_t sig_backward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
@@ -996,7 +1010,7 @@ int sig_forward_checkpointed(const sig_wordset* ws, const float* path, int64_t B
     if (!checkpoint || checkpoint_bytes < nb) return SIG_EWORKSPACE;
     if (((uintptr_t)checkpoint & 255) != 0 || ((uintptr_t)coeffs & 15) != 0) return SIG_EINVAL;
     float* Pfx = nullptr;
-    if (ch.C > 3) {
+    if (forward_chunk_arrays(w, ch.C) > 1) {
         if (!workspace || workspace_bytes < nb) return SIG_EWORKSPACE;
         if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
         Pfx = (float*)workspace;
@@ -1027,6 +1041,19 @@ int sig_backward_checkpointed(const sig_wordset* ws, const float* path, const fl
     if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)checkpoint & 255) != 0) return SIG_EINVAL;
     return backward_checkpointed(w, path, coeffs, grad_coeffs, (const float*)checkpoint, ch, B, n_points, grad_path, workspace,
                                  (hipStream_t)stream);
+}
+
+int sig_backward_residual(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                          int64_t n_points, float* grad_path, float* residual, void* workspace, size_t workspace_bytes,
+                          void* stream)
+{
+    if (!residual) return SIG_EINVAL;
+    if (ws && B > 0 && n_points == 1) {
+        hipError_t e = sig::fill_zero(residual, B, (hipStream_t)stream);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return backward_impl(ws, path, coeffs, grad_coeffs, B, n_points, grad_path, workspace, workspace_bytes, stream,
+                         Build::compile_and_load, residual);
 }
 
 int sig_backward_static(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,

@@ -80,10 +80,11 @@ hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t
 // tile: segments per LDS tile where a kernel offers a choice (d = 16: 8 or 16; 0 = the default)
 // coeffs_last / grad_last (both or neither): [B][|W|] arrays that hold the rows of the last chunk of every path, while
 // coeffs / grad_coeffs hold the other chunks' rows in [B][C][|W|] (the last slot of a path unused); nullptr: all rows
-// are in coeffs / grad_coeffs
+// are in coeffs / grad_coeffs.  resid: largest |coefficient| left in the signature reconstructed back to the start of
+// every path (rows that begin at segment 0 report)
 hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs,
                           const float* coeffs_last, const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
-                          float* gdx, int tile, hipStream_t stream);
+                          float* gdx, float* resid /*[B], zeroed by the caller, or nullptr*/, int tile, hipStream_t stream);
 const char* trunc_backward_kernel_name(int d, int depth);   // of the kernel trunc_backward launches
 
 // d = 4: backward with one wavefront per row (a lane holds a word of length N - 3 and its four children); stores

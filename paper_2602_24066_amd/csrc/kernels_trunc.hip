@@ -576,6 +576,16 @@ __device__ __forceinline__ void chain_tile_reduce(const float* Vsrc, float* gt, 
     }
 }
 
+// Reconstruction check: after the walk back over a whole path the reconstructed signature is that of the empty path,
+// whose coefficients of non-empty words are zero (Lemma 4.5, Proposition 4.6).  resid[b] receives the largest
+// absolute value a wavefront still holds (non-negative floats order like their bit patterns).
+__device__ __forceinline__ void report_residual(float m, float* resid, int64_t b)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if ((threadIdx.x & 63) == 0) atomicMax((int*)resid + b, __float_as_int(m));
+}
+
 // LDS of one wavefront of the backward kernel for d = 16, in floats.  The leaf level (adjoints constant in time) is
 // handled by time-batched matrix products over a tile of 16 segments, which need the slice-level values of the
 // tile in LDS (HA).
@@ -602,7 +612,7 @@ template <int D, int N, int WQ, int T>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad,
     const float* __restrict__ coeffs_last, const float* __restrict__ grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
-    float* gdx)
+    float* gdx, float* resid)
 {
     static_assert((D & (D - 1)) == 0, "the gradient reduction takes letters as bit fields of the lane number");
     constexpr int K = N - 2;
@@ -916,6 +926,16 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             if (s < L) unsafeAtomicAdd(gdx + (b * (P - 1) + seg0 + n * T) * D + e, gt[e]);
             gt[e] = 0.0f;
         }
+    }
+    if (resid != nullptr && seg0 == 0) {
+        float m = 0.0f;
+#pragma unroll
+        for (int k = 0; k < K; ++k) m = fmaxf(m, fabsf(Sc[k]));
+#pragma unroll
+        for (int g = 0; g < WQ; ++g)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) m = fmaxf(m, fabsf(S1[g][r]));
+        report_residual(m, resid, b);
     }
 }
 
@@ -1475,7 +1495,7 @@ template <int D, int N, int T>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad,
     const float* __restrict__ coeffs_last, const float* __restrict__ grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
-    float* gdx)
+    float* gdx, float* resid)
 {
     static_assert((D & (D - 1)) == 0, "the gradient reduction takes letters as bit fields of the lane number");
     constexpr int K = N - 2;
@@ -1678,11 +1698,19 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
             gt[e] = 0.0f;
         }
     }
+    if (resid != nullptr && seg0 == 0) {
+        float m = 0.0f;
+#pragma unroll
+        for (int k = 0; k < K; ++k) m = fmaxf(m, fabsf(Sc[k]));
+#pragma unroll
+        for (int j = 0; j < D; ++j) m = fmaxf(m, fabsf(S1[j]));
+        report_residual(m, resid, b);
+    }
 }
 
 template <int D, int N, int T = 8>
 hipError_t launch_trunc_node_bwd(const float* path, const float* coeffs, const float* grad, const float* coeffs_last,
-                                 const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx,
+                                 const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx, float* resid,
                                  hipStream_t stream)
 {
     using LY = NodeLds<D, N, T>;
@@ -1695,7 +1723,7 @@ hipError_t launch_trunc_node_bwd(const float* path, const float* coeffs, const f
         if (e != hipSuccess) return e;
     }
     trunc_node_bwd_kernel<D, N, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(
-        path, coeffs, grad, coeffs_last, grad_last, B, P, C, Lc, gdx);
+        path, coeffs, grad, coeffs_last, grad_last, B, P, C, Lc, gdx, resid);
     return hipGetLastError();
 }
 
@@ -1909,7 +1937,7 @@ hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const 
 
 template <int D, int N, int WQ, int T>
 hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const float* grad, const float* coeffs_last,
-                                 const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx,
+                                 const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx, float* resid,
                                  hipStream_t stream)
 {
     using G = MGeo<D, N, N - 2, WQ>;
@@ -1923,7 +1951,7 @@ hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const f
         if (e != hipSuccess) return e;
     }
     trunc_mfma_bwd_kernel<D, N, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(
-        path, coeffs, grad, coeffs_last, grad_last, B, P, C, Lc, gdx);
+        path, coeffs, grad, coeffs_last, grad_last, B, P, C, Lc, gdx, resid);
     return hipGetLastError();
 }
 
@@ -2023,23 +2051,23 @@ const char* trunc_backward_kernel_name(int d, int depth)
 // gdx: [B, L, d] accumulation buffer, zeroed by the caller
 hipError_t trunc_backward(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs,
                           const float* coeffs_last, const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
-                          float* gdx, int tile, hipStream_t stream)
+                          float* gdx, float* resid, int tile, hipStream_t stream)
 {
     if ((coeffs_last == nullptr) != (grad_last == nullptr)) return hipErrorInvalidValue;
     if (d == 4 && depth == 6)
-        return launch_trunc_node_bwd<4, 6>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, stream);
+        return launch_trunc_node_bwd<4, 6>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
     // d = 8: tiles of 4 segments keep a workgroup's LDS at 50 KB, so that two (or three) workgroups share a compute unit:
     // taken when the launch has the wavefronts for it
     if (d == 8 && depth == 5) {
         const bool small = tile == 4 || (tile == 0 && B * C * 8 >= 2048);
-        return small ? launch_trunc_node_bwd<8, 5, 4>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, stream)
-                     : launch_trunc_node_bwd<8, 5, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, stream);
+        return small ? launch_trunc_node_bwd<8, 5, 4>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream)
+                     : launch_trunc_node_bwd<8, 5, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
     }
     // d = 16: tiles of 8 segments halve the LDS of a workgroup but fill only half of the columns of the time-batched
     // matrix products; measured slower or equal at every batch size, kept selectable
     if (d == 16 && depth == 4)
-        return tile == 8 ? launch_trunc_mfma_bwd<16, 4, 1, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, stream)
-                         : launch_trunc_mfma_bwd<16, 4, 1, 16>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, stream);
+        return tile == 8 ? launch_trunc_mfma_bwd<16, 4, 1, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream)
+                         : launch_trunc_mfma_bwd<16, 4, 1, 16>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
     return hipErrorInvalidValue;
 }
 

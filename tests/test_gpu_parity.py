@@ -70,7 +70,7 @@ def test_time_chunks(monkeypatch, d, depth, B, L, chunks):
     G = make_grad_coeffs(600 + L, B, ws.size)
     lib = S.load_library()
     if chunks:
-        assert lib.sig_forward_workspace_bytes(ws._h, B, L + 1) >= 2 * 4 * B * chunks * ws.size
+        assert lib.sig_forward_workspace_bytes(ws._h, B, L + 1) >= 4 * B * chunks * ws.size
     else:
         assert lib.sig_forward_workspace_bytes(ws._h, B, L + 1) > 0      # few paths: chunking is chosen by itself
     inputs = d4_inputs(500 + L, B, L) if d == 4 else [("iid", make_path("iid", 500 + L, B, L, d))]
@@ -157,6 +157,31 @@ def test_checkpointed_forward_and_backward(d, depth, B, L, chunks):
         assert e <= FWD_TOL, f"checkpointed forward, level {n}: {e:.3e}"
     gerr = O.grad_errors(gp, O.backward_dense(X, depth, G.astype(np.float64)))
     assert gerr.max() <= BWD_TOL, f"checkpointed backward: {gerr.max():.3e}"
+
+
+@pytest.mark.parametrize("d,depth,B,L", [(8, 5, 2, 300), (16, 4, 2, 400), (4, 6, 3, 257)])
+def test_reconstruction_returns_to_the_empty_signature(d, depth, B, L):
+    """Stepping the terminal signature back through all segments (Proposition 4.6) must end at the signature of the
+    empty path (Lemma 4.5): the kernels report the largest coefficient they are left with, and the gradient of the
+    same call is the ordinary one."""
+    import torch
+    ws, W = build_both("truncated", d, depth=depth)
+    X = make_path("iid", 2700 + L, B, L, d)
+    G = make_grad_coeffs(2800 + L, B, ws.size)
+    xp, grad = torch.from_numpy(X).cuda(), torch.from_numpy(G).cuda()
+    coeffs = S.sig_forward(ws, xp)
+    gp, resid = S.sig_backward_residual(ws, xp, coeffs, grad)
+    torch.cuda.synchronize()
+    resid = resid.cpu().numpy()
+    scale = float(coeffs.abs().max())
+    assert resid.shape == (B,) and np.all(resid >= 0.0) and resid.max() <= 1e-4 * max(scale, 1.0), (resid, scale)
+    gerr = O.grad_errors(gp.cpu().numpy(), O.backward_dense(X, depth, G.astype(np.float64)))
+    assert gerr.max() <= BWD_TOL
+    # a terminal signature that is not the path's own does not come back to zero: the check discriminates
+    wrong = coeffs.clone()
+    wrong[:, 0] += 0.5
+    _, resid2 = S.sig_backward_residual(ws, xp, wrong, grad)
+    assert float(resid2.min()) > 0.1
 
 
 def test_forward_fused_and_four_wavefront_kernels_agree():

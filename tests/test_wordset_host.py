@@ -337,12 +337,22 @@ def test_code_object_cache_on_disk(tmp_path, monkeypatch):
 
 def test_time_chunk_workspace():
     """Few long paths of a full truncation are cut into time chunks: the forward workspace holds the chunk
-    signatures and the partial products; many paths, or short ones, need none."""
+    signatures (and the partial products when four or more signatures too large for LDS are multiplied pair by pair);
+    many paths, or short ones, need none."""
     lib = S.load_library()
     ws = S.sig_wordset_build_truncated(4, 6)
     rows = 2 * 4                                               # B = 2 paths, L = 1024 -> 4 chunks of 256 segments
     per_array = (4 * rows * ws.size + 255) // 256 * 256
-    assert lib.sig_forward_workspace_bytes(ws._h, 2, 1025) == 2 * per_array
+    assert lib.sig_forward_workspace_bytes(ws._h, 2, 1025) == per_array
+    ws85 = S.sig_wordset_build_truncated(8, 5)
+    per85 = (4 * 2 * 4 * ws85.size + 255) // 256 * 256        # 2 paths, 4 chunks of 256 segments
+    assert lib.sig_forward_workspace_bytes(ws85._h, 2, 1025) == 2 * per85
+    assert lib.sig_forward_workspace_bytes(ws85._h, 128, 1025) == (4 * 128 * 3 * ws85.size + 255) // 256 * 256   # three chunks
+    # checkpointed form: offered where the backward kernel of the shape would leave SIMDs with a single wavefront
+    assert lib.sig_checkpoint_bytes(ws85._h, 128, 1025) == (4 * 128 * 2 * ws85.size + 255) // 256 * 256
+    assert lib.sig_checkpoint_bytes(ws85._h, 1024, 1025) == 0 and lib.sig_checkpoint_bytes(ws85._h, 128, 100) == 0
+    assert lib.sig_checkpoint_bytes(ws._h, 2, 1025) == 0
+    assert lib.sig_backward_checkpointed_workspace_bytes(ws._h, 2, 1025) == lib.sig_backward_workspace_bytes(ws._h, 2, 1025)
     assert lib.sig_forward_workspace_bytes(ws._h, 2, 300) == 0
     assert lib.sig_forward_workspace_bytes(ws._h, 4096, 1025) == 0
     gdx = (4 * 2 * 1024 * 4 + 255) // 256 * 256
