@@ -1076,9 +1076,17 @@ static size_t win_sub_bytes(const sig::WordSet& w, int64_t B, int64_t K, int64_t
     return ((size_t)B * (size_t)K * (size_t)n_sub * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;
 }
 
+// Full truncations with register-resident kernels read every window straight from the path (no copy of the path per
+// window, short windows end early); other word sets take the gather into padded sub-paths.
+static bool windows_direct(const sig::WordSet& w, int64_t B, int64_t K, int backward)
+{
+    return B * K <= 65535 && (backward ? use_trunc_backward(w, B * K) : use_trunc_forward(w, B * K));
+}
+
 size_t sig_forward_windows_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points, int64_t K, int64_t max_window_len)
 {
     if (!ws || B <= 0 || K <= 0 || n_points < 1 || max_window_len < 0) return 0;
+    if (windows_direct(*W(ws), B, K, 0)) return 0;
     const int64_t n_sub = max_window_len + 1;
     return win_sub_bytes(*W(ws), B, K, n_sub) + sig_forward_workspace_bytes(ws, B * K, n_sub);
 }
@@ -1086,6 +1094,7 @@ size_t sig_forward_windows_workspace_bytes(const sig_wordset* ws, int64_t B, int
 size_t sig_backward_windows_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points, int64_t K, int64_t max_window_len)
 {
     if (!ws || B <= 0 || K <= 0 || n_points < 1 || max_window_len < 0) return 0;
+    if (windows_direct(*W(ws), B, K, 1)) return n_points > 1 ? gdx_bytes_of(*W(ws), B, n_points) : 0;
     const int64_t n_sub = max_window_len + 1;
     return 2 * win_sub_bytes(*W(ws), B, K, n_sub) + sig_backward_workspace_bytes(ws, B * K, n_sub);
 }
@@ -1100,6 +1109,21 @@ int sig_forward_windows(const sig_wordset* ws, const float* path, int64_t B, int
     if (!windows || !coeffs) return SIG_EINVAL;
     if (B * K > (int64_t)65535 * 64) return SIG_ETOOLARGE;
     const sig::WordSet& w = *W(ws);
+    if (windows_direct(w, B, K, 0)) {
+        hipStream_t st = (hipStream_t)stream;
+        if (n_points == 1 || max_window_len == 0) {
+            hipError_t e0 = sig::fill_zero(coeffs, B * K * w.size(), st);
+            return e0 == hipSuccess ? SIG_OK : hip_fail(e0);
+        }
+        CallTimer whole(0, st);
+        sig::WindowList wl;
+        wl.win = windows; wl.K = K; wl.max_len = max_window_len;
+        hipEvent_t* pe = g_prof.next(0);
+        if (pe) (void)hipEventRecord(pe[0], st);
+        hipError_t e1 = sig::trunc_forward_windows(w.d, w.depth, path, B, n_points, wl, coeffs, st);
+        if (pe) (void)hipEventRecord(pe[1], st);
+        return e1 == hipSuccess ? SIG_OK : hip_fail(e1);
+    }
     const int64_t n_sub = max_window_len + 1;
     const size_t sb = win_sub_bytes(w, B, K, n_sub);
     if (!workspace || workspace_bytes < sig_forward_windows_workspace_bytes(ws, B, n_points, K, max_window_len)) return SIG_EWORKSPACE;
@@ -1126,6 +1150,24 @@ int sig_backward_windows(const sig_wordset* ws, const float* path, const float* 
     if (K == 0) return SIG_OK;
     if (!windows || !coeffs || !grad_coeffs) return SIG_EINVAL;
     if (B * K > (int64_t)65535 * 64) return SIG_ETOOLARGE;
+    if (windows_direct(w, B, K, 1)) {
+        if (n_points == 1 || max_window_len == 0) return SIG_OK;            // grad_path is zero already
+        if (!workspace || workspace_bytes < gdx_bytes_of(w, B, n_points)) return SIG_EWORKSPACE;
+        if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
+        CallTimer whole(1, st);
+        float* gdx = (float*)workspace;
+        e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
+        if (e != hipSuccess) return hip_fail(e);
+        sig::WindowList wl;
+        wl.win = windows; wl.K = K; wl.max_len = max_window_len;
+        hipEvent_t* pe = g_prof.next(1);
+        if (pe) (void)hipEventRecord(pe[0], st);
+        e = sig::trunc_backward_windows(w.d, w.depth, path, coeffs, grad_coeffs, B, n_points, wl, gdx, st);
+        if (pe) (void)hipEventRecord(pe[1], st);
+        if (e != hipSuccess) return hip_fail(e);
+        e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
+        return e == hipSuccess ? SIG_OK : hip_fail(e);
+    }
     const int64_t n_sub = max_window_len + 1;
     const size_t sb = win_sub_bytes(w, B, K, n_sub);
     if (!workspace || workspace_bytes < sig_backward_windows_workspace_bytes(ws, B, n_points, K, max_window_len)) return SIG_EWORKSPACE;

@@ -68,6 +68,14 @@ hipError_t static_scratch(void** ptr);
 hipError_t fma_probe(float* out, int blocks, int iters, hipStream_t stream);   // out: blocks * 256 floats
 hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* grad_path, hipStream_t stream);
 
+// Window list of a launch (signatures over windows): K windows per path, window k between the points win[2 k] and
+// win[2 k + 1] (device array, clamped to the path by the kernels), at most max_len segments; win == nullptr: no windows.
+struct WindowList {
+    const int64_t* win = nullptr;
+    int64_t K = 0;
+    int64_t max_len = 0;
+};
+
 // Register-resident kernels for full truncations (kernels_trunc.hip)
 bool trunc_forward_available(int d, int depth);
 bool trunc_backward_available(int d, int depth);
@@ -77,6 +85,12 @@ int trunc_waves_per_row(int d, int depth, int backward);    // wavefronts per (p
 // own in coeffs / grad_coeffs ([B * C, |W|]).  C = 1, Lc = P - 1 treats whole paths.
 hipError_t trunc_forward(int d, int depth, const float* path, int64_t B, int64_t P, int64_t C, int64_t Lc, float* coeffs,
                          hipStream_t stream);
+// Signatures over windows straight from the path: coeffs [B][K][|W|]; backward adds into gdx [B][P - 1][d] (zeroed by
+// the caller; windows overlap) from coeffs / grad_coeffs [B][K][|W|].  Offered where trunc_forward / trunc_backward are.
+hipError_t trunc_forward_windows(int d, int depth, const float* path, int64_t B, int64_t P, const WindowList& wl, float* coeffs,
+                                 hipStream_t stream);
+hipError_t trunc_backward_windows(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                                  int64_t P, const WindowList& wl, float* gdx, hipStream_t stream);
 // tile: segments per LDS tile where a kernel offers a choice (d = 16: 8 or 16; 0 = the default)
 // coeffs_last / grad_last (both or neither): [B][|W|] arrays that hold the rows of the last chunk of every path, while
 // coeffs / grad_coeffs hold the other chunks' rows in [B][C][|W|] (the last slot of a path unused); nullptr: all rows

@@ -236,10 +236,31 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_wave_barrier();
 }
 
+// Rows of a launch: (path, time chunk) pairs, or, with a window list (Section 5: signatures over windows), (path,
+// window) pairs: window k is the path between the points win[2 k] and win[2 k + 1] (clamped to the path), at most
+// max_len segments.  Every window of every path advances as a row of its own, read straight from the path.
+__device__ __forceinline__ void row_segments(const WindowList& wl, int64_t row, int64_t P, int64_t C, int64_t Lc,
+                                             int64_t& b, int64_t& seg0, int64_t& L)
+{
+    if (wl.win == nullptr) {
+        b = row / C;
+        seg0 = (row - b * C) * Lc;
+        L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
+    } else {
+        b = row / wl.K;
+        const int64_t k = row - b * wl.K;
+        int64_t l = wl.win[2 * k], r = wl.win[2 * k + 1];
+        l = l < 0 ? 0 : (l > P - 1 ? P - 1 : l);
+        r = r < l ? l : (r > P - 1 ? P - 1 : r);
+        seg0 = l;
+        L = r - l < wl.max_len ? r - l : wl.max_len;
+    }
+}
+
 template <int D, int N, int K, int WQ, int T>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_fwd_kernel(const float* __restrict__ path,
                                                                                 int64_t B, int64_t P, int64_t C, int64_t Lc,
-                                                                                float* __restrict__ coeffs)
+                                                                                WindowList wl, float* __restrict__ coeffs)
 {
     using G = MGeo<D, N, K, WQ>;
     constexpr int Q = G::Q;
@@ -258,14 +279,14 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_fwd_kernel(
     const int lane = threadIdx.x % kWave;
     const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // the same in every lane: scalar registers
     const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
-    if (wave >= B * C * G::WAVES) return;                 // no barriers below: a whole wavefront may leave
+    if (wave >= B * C * (wl.win ? wl.K : 1) * G::WAVES) return;   // no barriers below: a whole wavefront may leave
     float (*E)[N][D] = E_all[wib];
     float (*Ec)[D][NC] = Ec_all[wib];
     // row = (path, chunk): chunk c of a path covers its segments [c Lc, min((c + 1) Lc, P - 1)) and is treated as
-    // a path of its own whose signature goes to row `row` of coeffs (C = 1: the whole path)
+    // a path of its own whose signature goes to row `row` of coeffs (C = 1: the whole path); or (path, window)
     const int64_t row = wave / G::WAVES;
-    const int64_t b = row / C;
-    const int64_t seg0 = (row - b * C) * Lc;
+    int64_t b, seg0, L;
+    row_segments(wl, row, P, C, Lc, b, seg0, L);
     const int wip = (int)(wave % G::WAVES);               // wavefront inside the path
     const int slice = wip % G::NSL;
     const int p = (wip / G::NSL) * kWave + lane;          // this lane's prefix (base-D number of K letters)
@@ -277,7 +298,6 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_fwd_kernel(
     }
     const int g0 = slice * WQ;
     const float* X = path + (b * P + seg0) * D;
-    const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
 
     // per-lane offsets (in floats, inside one row of E) of the matrix-core B operands: register r serves the
     // combinations 4r..4r+3, one per group of 16 lanes
@@ -314,9 +334,9 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_fwd_kernel(
             // in flight together); out-of-range segments are zeroed afterwards
             const int e = (lane + q * kWave) < T * D ? lane + q * kWave : T * D - 1;
             const int64_t jj = j0 + e / D;
-            const int64_t jc = jj < L ? jj : L - 1;
+            const int64_t jc = jj < L ? jj : (L > 0 ? L - 1 : 0);
             const int i = e % D;
-            const float x1 = X[(jc + 1) * D + i], x0 = X[jc * D + i];
+            const float x1 = X[(jc + (L > 0 ? 1 : 0)) * D + i], x0 = X[jc * D + i];   // an empty window reads its own point
             dxn[q] = jj < L ? x1 - x0 : 0.0f;
         }
     };
@@ -455,14 +475,14 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_fwd_kernel(
 
 template <int D, int N, int K, int WQ>
 hipError_t launch_trunc_mfma_fwd(const float* path, int64_t B, int64_t P, int64_t C, int64_t Lc, float* coeffs,
-                                 hipStream_t stream)
+                                 hipStream_t stream, const WindowList& wl = WindowList())
 {
     using G = MGeo<D, N, K, WQ>;
     constexpr int T = G::WIDE ? 8 : 16;          // d = 16: 32 KB of LDS per workgroup, so that three fit on a compute unit
-    const int64_t waves = B * C * G::WAVES;
+    const int64_t waves = B * C * (wl.win ? wl.K : 1) * G::WAVES;
     const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    trunc_mfma_fwd_kernel<D, N, K, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, 0, stream>>>(path, B, P, C, Lc, coeffs);
+    trunc_mfma_fwd_kernel<D, N, K, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, 0, stream>>>(path, B, P, C, Lc, wl, coeffs);
     return hipGetLastError();
 }
 
@@ -612,7 +632,7 @@ template <int D, int N, int WQ, int T>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad,
     const float* __restrict__ coeffs_last, const float* __restrict__ grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
-    float* gdx, float* resid)
+    WindowList wl, float* gdx, float* resid)
 {
     static_assert((D & (D - 1)) == 0, "the gradient reduction takes letters as bit fields of the lane number");
     constexpr int K = N - 2;
@@ -631,7 +651,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     const int lane = threadIdx.x % kWave;
     const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // the same in every lane: scalar registers
     const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
-    if (wave >= B * C * G::WAVES) return;
+    if (wave >= B * C * (wl.win ? wl.K : 1) * G::WAVES) return;
     float* const lds = (float*)bwd_smem + wib * LY::PER_WAVE;            // wave-private
     float (*E)[2][D] = (float (*)[2][D])(lds + LY::OFF_E);
     float (*Ec)[D][NC] = (float (*)[D][NC])(lds + LY::OFF_EC);
@@ -643,8 +663,9 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     // row = (path, chunk): walks the segments [c Lc, min((c + 1) Lc, P - 1)) of path b backwards, starting from
     // row `row` of coeffs (signature up to the end of the chunk) and of grad (adjoint at the end of the chunk)
     const int64_t row = wave / G::WAVES;
-    const int64_t b = row / C;
-    const int64_t seg0 = (row - b * C) * Lc;
+    int64_t b, seg0, L;
+    row_segments(wl, row, P, C, Lc, b, seg0, L);
+    if (L <= 0) return;                                                  // an empty window: no gradient
     const int wip = (int)(wave % G::WAVES);
     const int slice = wip % G::NSL;
     const int p = (wip / G::NSL) * kWave + lane;
@@ -656,7 +677,6 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     }
     const int g0 = slice * WQ;
     const float* X = path + (b * P + seg0) * D;
-    const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
     const int64_t nW = level_start(D, N) + ipow(D, N);
     // rows of the last chunk of a path may live in arrays of their own ([B][|W|]: the caller's terminal signature
     // and gradient), the others in [B][C][|W|] arrays
@@ -1079,7 +1099,7 @@ __device__ __forceinline__ float word_contract(const float* g, const float* q, i
 template <int D, int N, int T, int CW, bool POINTS>
 __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tails_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad, int64_t B,
-    int64_t P, int64_t C, int64_t Lc, float* __restrict__ out)
+    int64_t P, int64_t C, int64_t Lc, WindowList wl, float* __restrict__ out)
 {
     // POINTS (fused, or rows that are whole paths): the chain rule dX_j = X_{j+1} - X_j is applied here and out
     // receives the gradient with respect to the points [B, P, d]; otherwise the increment gradients [B, P - 1, d].
@@ -1103,7 +1123,7 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
     const int cib = wib;                              // fused: chunk of the workgroup's path
     const int64_t row = CW ? (int64_t)blockIdx.x * C + cib : (int64_t)blockIdx.x * kWavesPerBlock + wib;
     if constexpr (CW == 0) {
-        if (row >= B * C) return;                     // no workgroup barriers in this mode
+        if (row >= B * C * (wl.win ? wl.K : 1)) return;   // no workgroup barriers in this mode
     }
     float* const smem = (float*)bwd_smem;
     float (*Ec)[D][NC] = (float (*)[D][NC])(LY::tile(smem, wib));         // wave-private
@@ -1111,8 +1131,11 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
     float* const pg = cg + 2 * D;
     float* gt = LY::red(smem, wib);                                       // fused: valid after the signature buffers
     float* Vb = gt + T * D;                                               // are dead
-    const int64_t b = row / C;
-    const int64_t seg0 = (row - b * C) * Lc;
+    int64_t b, seg0, L;
+    row_segments(wl, row, P, C, Lc, b, seg0, L);      // (a window list comes with CW = 0 and without POINTS only)
+    if constexpr (CW == 0) {
+        if (L <= 0) return;                           // an empty window: no gradient
+    }
     int letter[KL];
     {
         int q = lane;
@@ -1120,7 +1143,6 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
         for (int k = KL - 1; k >= 0; --k) { letter[k] = q % D; q /= D; }
     }
     const float* X = path + (b * P + seg0) * D;
-    const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
     const int64_t nW = level_start(D, N) + ipow(D, N);
     // CW = 0: row arrays; fused: the terminal signature and the gradient of the path
     const float* cf = coeffs + (CW ? b : row) * nW;
@@ -1435,7 +1457,11 @@ __global__ __launch_bounds__(kWave * (CW ? CW : kWavesPerBlock)) void trunc_tail
         } else {
             for (int e = lane; e < T * D; e += kWave) {
                 const int64_t sgm = n * T + e / D;
-                if (sgm < L) gdx[(b * (P - 1) + seg0 + n * T) * D + e] = gt[e];
+                if (sgm < L) {
+                    // windows of a path overlap: their gradients add up; rows that tile a path store
+                    if (wl.win) unsafeAtomicAdd(gdx + (b * (P - 1) + seg0 + n * T) * D + e, gt[e]);
+                    else gdx[(b * (P - 1) + seg0 + n * T) * D + e] = gt[e];
+                }
                 gt[e] = 0.0f;
             }
         }
@@ -1495,7 +1521,7 @@ template <int D, int N, int T>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad,
     const float* __restrict__ coeffs_last, const float* __restrict__ grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
-    float* gdx, float* resid)
+    WindowList wl, float* gdx, float* resid)
 {
     static_assert((D & (D - 1)) == 0, "the gradient reduction takes letters as bit fields of the lane number");
     constexpr int K = N - 2;
@@ -1510,14 +1536,15 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
     const int lane = threadIdx.x % kWave;
     const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // the same in every lane: scalar registers
     const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
-    if (wave >= B * C * WAVES) return;
+    if (wave >= B * C * (wl.win ? wl.K : 1) * WAVES) return;
     float* const lds = (float*)bwd_smem + wib * LY::PER_WAVE;            // wave-private
     float (*Ec)[D][NC] = (float (*)[D][NC])lds;
     float* gt = lds + LY::OFF_GT;
     float* Vb = lds + LY::OFF_VB;
     const int64_t row = wave / WAVES;
-    const int64_t b = row / C;
-    const int64_t seg0 = (row - b * C) * Lc;
+    int64_t b, seg0, L;
+    row_segments(wl, row, P, C, Lc, b, seg0, L);
+    if (L <= 0) return;                                // an empty window: no gradient
     const int p = (int)(wave % WAVES) * kWave + lane;  // the lane's word of length K
     int letter[K];
     {
@@ -1526,7 +1553,6 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
         for (int k = K - 1; k >= 0; --k) { letter[k] = q % D; q /= D; }
     }
     const float* X = path + (b * P + seg0) * D;
-    const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
     const int64_t nW = level_start(D, N) + ipow(D, N);
     // rows of the last chunk of a path may live in arrays of their own ([B][|W|]), the others in [B][C][|W|] arrays
     const bool in_last = coeffs_last != nullptr && row - b * C == C - 1;
@@ -1711,11 +1737,11 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
 template <int D, int N, int T = 8>
 hipError_t launch_trunc_node_bwd(const float* path, const float* coeffs, const float* grad, const float* coeffs_last,
                                  const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx, float* resid,
-                                 hipStream_t stream)
+                                 hipStream_t stream, const WindowList& wl = WindowList())
 {
     using LY = NodeLds<D, N, T>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
-    const int64_t waves = B * C * (ipow(D, N - 2) / kWave);
+    const int64_t waves = B * C * (wl.win ? wl.K : 1) * (ipow(D, N - 2) / kWave);
     const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
@@ -1723,7 +1749,7 @@ hipError_t launch_trunc_node_bwd(const float* path, const float* coeffs, const f
         if (e != hipSuccess) return e;
     }
     trunc_node_bwd_kernel<D, N, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(
-        path, coeffs, grad, coeffs_last, grad_last, B, P, C, Lc, gdx, resid);
+        path, coeffs, grad, coeffs_last, grad_last, B, P, C, Lc, wl, gdx, resid);
     return hipGetLastError();
 }
 
@@ -1752,7 +1778,8 @@ struct TailsFwdLds {
 
 template <int D, int N, int T, int CW, int TW>
 __global__ __launch_bounds__(kWave * CW * (D / TW)) void trunc_tails_fwd_kernel(const float* __restrict__ path, int64_t P,
-                                                                               int64_t Lc, float* __restrict__ coeffs)
+                                                                               int64_t Lc, WindowList wl,
+                                                                               float* __restrict__ coeffs)
 {
     static_assert(D == 4, "one group of four letters");
     constexpr int K = N - 2;                          // length of the tail words
@@ -1770,12 +1797,22 @@ __global__ __launch_bounds__(kWave * CW * (D / TW)) void trunc_tails_fwd_kernel(
     const int cib = wib / H;                          // chunk of the workgroup's path
     const int i0 = (wib % H) * TW;                    // first tail of this wavefront
     const bool first = wib % H == 0;
-    const int64_t b = blockIdx.x;
+    // the workgroup's row: a path, or with a window list a (path, window) pair whose segments are cut into CW chunks
+    // (an empty window or chunk leaves the identity, which the products carry along)
+    const int64_t orow = blockIdx.x;
+    int64_t b = orow, seg0 = cib * Lc, L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
+    if (wl.win != nullptr) {
+        int64_t l0, lrow;
+        row_segments(wl, orow, P, 1, 0, b, l0, lrow);
+        const int64_t lc = (lrow + CW - 1) / CW;
+        seg0 = l0 + cib * lc;
+        L = lrow - cib * lc < lc ? lrow - cib * lc : lc;
+        L = L < 0 ? 0 : L;
+    }
     float* const smem = (float*)fwd_smem;
     float (*E)[2][D] = (float (*)[2][D])(smem + wib * LY::TILE);            // wave-private
     float (*Ec)[D][NC] = (float (*)[D][NC])(smem + wib * LY::TILE + T * 2 * D);
     float* const SB = smem + LY::OFF_S;
-    const int64_t seg0 = cib * Lc;
     int letter[KL];
     {
         int q = lane;
@@ -1783,7 +1820,6 @@ __global__ __launch_bounds__(kWave * CW * (D / TW)) void trunc_tails_fwd_kernel(
         for (int k = KL - 1; k >= 0; --k) { letter[k] = q % D; q /= D; }
     }
     const float* X = path + (b * P + seg0) * D;
-    const int64_t L = (P - 1 - seg0) < Lc ? (P - 1 - seg0) : Lc;
 
     float Sc[KL];                          // per-lane chain
     float St[TW];                          // tails i0 .. i0 + TW - 1
@@ -1807,9 +1843,9 @@ __global__ __launch_bounds__(kWave * CW * (D / TW)) void trunc_tails_fwd_kernel(
             const int e = (lane + q * kWave) < T * D ? lane + q * kWave : T * D - 1;
             int64_t jj = j0 + e / D;
             const bool ok = jj < L;
-            jj = jj < L ? jj : L - 1;
+            jj = jj < L ? jj : (L > 0 ? L - 1 : 0);
             const int i = e % D;
-            const float x1 = X[(jj + 1) * D + i], x0 = X[jj * D + i];
+            const float x1 = X[(jj + (L > 0 ? 1 : 0)) * D + i], x0 = X[jj * D + i];   // an empty chunk reads its own point
             dxn[q] = ok ? x1 - x0 : 0.0f;
         }
     };
@@ -1888,7 +1924,7 @@ __global__ __launch_bounds__(kWave * CW * (D / TW)) void trunc_tails_fwd_kernel(
     }
     __syncthreads();
     constexpr int NT = LY::NWV * kWave;
-    float* const dst = coeffs + b * W;
+    float* const dst = coeffs + orow * W;
     if constexpr (CW == 4) {
         float* const TB = SB + CW * W;
         lds_tensor_product<D, N>(SB, SB + W, TB, threadIdx.x, NT);
@@ -1901,29 +1937,32 @@ __global__ __launch_bounds__(kWave * CW * (D / TW)) void trunc_tails_fwd_kernel(
 }
 
 template <int D, int N, int CW, int TW>
-hipError_t launch_trunc_tails_fwd(const float* path, int64_t B, int64_t P, int64_t Lc, float* coeffs, hipStream_t stream)
+hipError_t launch_trunc_tails_fwd(const float* path, int64_t B, int64_t P, int64_t Lc, float* coeffs, hipStream_t stream,
+                                  const WindowList& wl = WindowList())
 {
     constexpr int T = 8;
     using LY = TailsFwdLds<D, N, T, CW, TW>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
-    if ((CW - 1) * Lc >= P - 1 || B > 0x7fffffff) return hipErrorInvalidValue;   // every chunk holds a segment
+    const int64_t rows = B * (wl.win ? wl.K : 1);
+    if ((!wl.win && (CW - 1) * Lc >= P - 1) || rows > 0x7fffffff) return hipErrorInvalidValue;   // every chunk holds a segment
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&trunc_tails_fwd_kernel<D, N, T, CW, TW>), (int)LY::BYTES);
         if (e != hipSuccess) return e;
     }
-    trunc_tails_fwd_kernel<D, N, T, CW, TW><<<(unsigned)B, kWave * LY::NWV, LY::BYTES, stream>>>(path, P, Lc, coeffs);
+    trunc_tails_fwd_kernel<D, N, T, CW, TW><<<(unsigned)rows, kWave * LY::NWV, LY::BYTES, stream>>>(path, P, Lc, wl, coeffs);
     return hipGetLastError();
 }
 
 template <int D, int N, int CW, bool POINTS>
 hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const float* grad, int64_t B, int64_t P,
-                                  int64_t C, int64_t Lc, float* out, hipStream_t stream)
+                                  int64_t C, int64_t Lc, float* out, hipStream_t stream, const WindowList& wl = WindowList())
 {
     constexpr int T = 8;
     using LY = TailsLds<D, N, T, CW>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
     if (CW && C != CW) return hipErrorInvalidValue;
-    const int64_t blocks = CW ? B : (B * C + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (wl.win && (CW != 0 || POINTS || C != 1)) return hipErrorInvalidValue;   // windows: one row each, gradients added up
+    const int64_t blocks = CW ? B : (B * C * (wl.win ? wl.K : 1) + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&trunc_tails_bwd_kernel<D, N, T, CW, POINTS>), (int)LY::BYTES);
@@ -1931,19 +1970,19 @@ hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const 
     }
     if (POINTS && CW == 0 && C != 1) return hipErrorInvalidValue;   // rows that are parts of paths cannot apply the chain rule
     trunc_tails_bwd_kernel<D, N, T, CW, POINTS><<<(unsigned)blocks, kWave * LY::NWV, LY::BYTES, stream>>>(path, coeffs, grad, B, P,
-                                                                                                        C, Lc, out);
+                                                                                                        C, Lc, wl, out);
     return hipGetLastError();
 }
 
 template <int D, int N, int WQ, int T>
 hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const float* grad, const float* coeffs_last,
                                  const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx, float* resid,
-                                 hipStream_t stream)
+                                 hipStream_t stream, const WindowList& wl = WindowList())
 {
     using G = MGeo<D, N, N - 2, WQ>;
     using LY = BwdLds<D, N, WQ, T>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
-    const int64_t waves = B * C * G::WAVES;
+    const int64_t waves = B * C * (wl.win ? wl.K : 1) * G::WAVES;
     const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
@@ -1951,7 +1990,7 @@ hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const f
         if (e != hipSuccess) return e;
     }
     trunc_mfma_bwd_kernel<D, N, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(
-        path, coeffs, grad, coeffs_last, grad_last, B, P, C, Lc, gdx, resid);
+        path, coeffs, grad, coeffs_last, grad_last, B, P, C, Lc, wl, gdx, resid);
     return hipGetLastError();
 }
 
@@ -2068,6 +2107,36 @@ hipError_t trunc_backward(int d, int depth, const float* path, const float* coef
     if (d == 16 && depth == 4)
         return tile == 8 ? launch_trunc_mfma_bwd<16, 4, 1, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream)
                          : launch_trunc_mfma_bwd<16, 4, 1, 16>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
+    return hipErrorInvalidValue;
+}
+
+hipError_t trunc_forward_windows(int d, int depth, const float* path, int64_t B, int64_t P, const WindowList& wl, float* coeffs,
+                                 hipStream_t stream)
+{
+    if (!wl.win || wl.K < 1 || B * wl.K > 65535) return hipErrorInvalidValue;
+    // d = 4: the two halves of a window in one workgroup (16-byte aligned rows), as for whole paths
+    if (d == 4 && depth == 6) {
+        if (((uintptr_t)coeffs & 15) == 0) return launch_trunc_tails_fwd<4, 6, 2, 2>(path, B, P, 0, coeffs, stream, wl);
+        return launch_trunc_mfma_fwd<4, 6, kChainFwd46, 1>(path, B, P, 1, P - 1, coeffs, stream, wl);
+    }
+    if (d == 8 && depth == 5) return launch_trunc_mfma_fwd<8, 5, 3, 2>(path, B, P, 1, P - 1, coeffs, stream, wl);
+    if (d == 16 && depth == 4) return launch_trunc_mfma_fwd<16, 4, 2, 1>(path, B, P, 1, P - 1, coeffs, stream, wl);
+    return hipErrorInvalidValue;
+}
+
+hipError_t trunc_backward_windows(int d, int depth, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
+                                  int64_t P, const WindowList& wl, float* gdx, hipStream_t stream)
+{
+    if (!wl.win || wl.K < 1 || B * wl.K > 65535) return hipErrorInvalidValue;
+    if (d == 4 && depth == 6)
+        return launch_trunc_tails_bwd<4, 6, 0, false>(path, coeffs, grad_coeffs, B, P, 1, P - 1, gdx, stream, wl);
+    if (d == 8 && depth == 5) {
+        const bool small = B * wl.K * 8 >= 2048;           // see trunc_backward
+        return small ? launch_trunc_node_bwd<8, 5, 4>(path, coeffs, grad_coeffs, nullptr, nullptr, B, P, 1, P - 1, gdx, nullptr, stream, wl)
+                     : launch_trunc_node_bwd<8, 5, 8>(path, coeffs, grad_coeffs, nullptr, nullptr, B, P, 1, P - 1, gdx, nullptr, stream, wl);
+    }
+    if (d == 16 && depth == 4)
+        return launch_trunc_mfma_bwd<16, 4, 1, 16>(path, coeffs, grad_coeffs, nullptr, nullptr, B, P, 1, P - 1, gdx, nullptr, stream, wl);
     return hipErrorInvalidValue;
 }
 
