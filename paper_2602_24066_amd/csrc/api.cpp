@@ -172,7 +172,8 @@ BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points
 // Checkpointed form (sig_forward_checkpointed / sig_backward_checkpointed): the forward pass leaves the signatures of C
 // time chunks of every path in a buffer the caller keeps, and the backward pass walks the C chunks side by side
 // without recomputing them.  Taken where the backward kernel of a full truncation has too few rows to put two
-// wavefronts on every SIMD (the d = 8 kernel: eight wavefronts per row); C = 2 .. 4, chunks of at least 64 segments.
+// wavefronts on every SIMD (eight wavefronts per row for d = 8, sixteen for d = 16); C = 2 .. 4, chunks of at least 64
+// segments.
 // "ckpt_chunks" forces a count (0: this rule, 1: off).
 Chunks checkpoint_chunks(const sig::WordSet& w, int64_t B, int64_t n_points)
 {
@@ -182,7 +183,7 @@ Chunks checkpoint_chunks(const sig::WordSet& w, int64_t B, int64_t n_points)
         !sig::trunc_backward_tails_available(w.d, w.depth)) {
         if (w.opt.ckpt_chunks > 0) {
             C = std::min<int64_t>(w.opt.ckpt_chunks, 4);
-        } else if (w.d == 8) {
+        } else {
             const int64_t rows_wanted = 2048 / sig::trunc_waves_per_row(w.d, w.depth, 1);
             C = std::min<int64_t>(4, (rows_wanted + B - 1) / B);
         }

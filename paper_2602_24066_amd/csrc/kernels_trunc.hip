@@ -563,7 +563,11 @@ __device__ __forceinline__ int gather_bits(int keep, int lane)
 // V[T][64]: one value per (segment, lane).  Lanes that agree on the lane-number bits in KEEP contribute to the same
 // letter (my_letter, valid in every lane of the class).  Each class sums its values per segment and adds the
 // result to gt[segment][letter]; the lanes of a class split the segments between them.
-template <int KEEP, int T>
+// The classes of a call carry different letters and the lanes of a class take different segments, so no two lanes of a
+// call meet in one entry of gt, and the calls of a wavefront follow each other in order: a plain read-modify-write
+// does (LDS floating-point atomics were measured at some ninety clocks each and cost the d = 16 backward kernel a
+// sixth of its time).  ATOMIC = true is for a caller whose classes may share a letter.
+template <int KEEP, int T, bool ATOMIC = false>
 __device__ __forceinline__ void tile_reduce(const float* V, float* gt, int D, int lane, int my_letter)
 {
     constexpr int NL = 1 << (6 - popcount6(KEEP));     // lanes per class
@@ -575,7 +579,8 @@ __device__ __forceinline__ void tile_reduce(const float* V, float* gt, int D, in
             float acc = 0.0f;
 #pragma unroll
             for (int i = 0; i < NL; ++i) acc += V[tt * kWave + ((lane & KEEP) | spread_bits(KEEP, i))];
-            __hip_atomic_fetch_add(gt + tt * D + my_letter, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if constexpr (ATOMIC) __hip_atomic_fetch_add(gt + tt * D + my_letter, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            else gt[tt * D + my_letter] += acc;
         }
     }
 }
@@ -587,12 +592,12 @@ __host__ __device__ constexpr int chain_keep_mask(int LB, int K, int k)
     return lo >= 6 ? 0 : ((((1 << LB) - 1) << lo) & 63);
 }
 
-template <int D, int K, int T, int KI>
+template <int D, int K, int T, int KI, bool ATOMIC = false>
 __device__ __forceinline__ void chain_tile_reduce(const float* Vsrc, float* gt, int lane, const int (&letter)[K])
 {
     if constexpr (KI < K - 1) {
-        tile_reduce<chain_keep_mask(ilog2(D), K, KI), T>(Vsrc + KI * T * kWave, gt, D, lane, letter[KI]);
-        chain_tile_reduce<D, K, T, KI + 1>(Vsrc, gt, lane, letter);
+        tile_reduce<chain_keep_mask(ilog2(D), K, KI), T, ATOMIC>(Vsrc + KI * T * kWave, gt, D, lane, letter[KI]);
+        chain_tile_reduce<D, K, T, KI + 1, ATOMIC>(Vsrc, gt, lane, letter);
     }
 }
 
@@ -609,27 +614,29 @@ __device__ __forceinline__ void report_residual(float m, float* resid, int64_t b
 // LDS of one wavefront of the backward kernel for d = 16, in floats.  The leaf level (adjoints constant in time) is
 // handled by time-batched matrix products over a tile of 16 segments, which need the slice-level values of the
 // tile in LDS (HA).
-template <int D, int N, int WQ, int T>
+template <int D, int N, int WQ, int T, int VG>
 struct BwdLds {
     using G = MGeo<D, N, N - 2, WQ>;
     static_assert(G::WIDE, "sixteen letters: the leaves of a slice word fill a 16x16 matrix instruction");
+    static_assert(T % VG == 0 && VG % 2 == 0, "the gradient sources are summed every VG segments");
     static constexpr int NC = (N + 3) / 4 * 4;
     static constexpr int NSV = WQ * 4;
     static constexpr int NSRC = 1 + WQ + (N - 2 - 1);
-    static constexpr int SP = 68;                       // row stride of HA: 64 parents + 4 (keeps 16-byte alignment)
-    static constexpr int OFF_E = 0;
-    static constexpr int OFF_EC = OFF_E + T * 2 * D;
+    static constexpr int SP = 68;                       // row stride of HA: 64 parents + 4 (16-byte aligned rows whose
+                                                        // columns fall into different banks)
+    static constexpr int OFF_EC = 0;
     static constexpr int OFF_GT = OFF_EC + T * D * NC;
     static constexpr int OFF_VB = OFF_GT + T * D;
-    static constexpr int OFF_HA = OFF_VB + NSRC * T * kWave;
+    static constexpr int OFF_HA = OFF_VB + NSRC * VG * kWave;
     static constexpr int PER_WAVE = OFF_HA + NSV * T * SP;
-    static_assert(OFF_EC % 4 == 0 && OFF_GT % 4 == 0 && OFF_VB % 4 == 0 && OFF_HA % 4 == 0 && PER_WAVE % 4 == 0,
+    static_assert(OFF_GT % 4 == 0 && OFF_VB % 4 == 0 && OFF_HA % 4 == 0 && PER_WAVE % 4 == 0,
                   "16-byte alignment of the LDS regions");
     static constexpr size_t BYTES = (size_t)kWavesPerBlock * PER_WAVE * sizeof(float);
 };
 
-template <int D, int N, int WQ, int T>
-__global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
+// (tiles shorter than 16 segments exist to put two workgroups on a compute unit: their registers are held to half a SIMD's)
+template <int D, int N, int WQ, int T, int VG>
+__global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trunc_mfma_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad,
     const float* __restrict__ coeffs_last, const float* __restrict__ grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
     WindowList wl, float* gdx, float* resid)
@@ -644,8 +651,8 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     constexpr int EPL = (T * D + kWave - 1) / kWave;
     constexpr int NSRC0 = 1 + WQ;                     // sources before the earlier chain letters
     constexpr int LB = ilog2(D);
-    using LY = BwdLds<D, N, WQ, T>;
-    static_assert(T == 16 || T == 8, "the time-batched leaf products take up to 16 segments per matrix instruction");
+    using LY = BwdLds<D, N, WQ, T, VG>;
+    static_assert(T <= 16 && T % 2 == 0, "the time-batched leaf products take up to 16 segments per matrix instruction");
     extern __shared__ v4f bwd_smem[];
 
     const int lane = threadIdx.x % kWave;
@@ -653,8 +660,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
     const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
     if (wave >= B * C * (wl.win ? wl.K : 1) * G::WAVES) return;
     float* const lds = (float*)bwd_smem + wib * LY::PER_WAVE;            // wave-private
-    float (*E)[2][D] = (float (*)[2][D])(lds + LY::OFF_E);
-    float (*Ec)[D][NC] = (float (*)[D][NC])(lds + LY::OFF_EC);
+    float (*Ec)[D][NC] = (float (*)[D][NC])(lds + LY::OFF_EC);          // Ec[segment][letter][t] = dX^{(letter)} / (t + 1)
     float* gt = lds + LY::OFF_GT;
     float* Vb = lds + LY::OFF_VB;
     float* HA = lds + LY::OFF_HA;                                       // [NSV][T][SP]
@@ -688,7 +694,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
 #pragma unroll
     for (int r = 0; r < NBS; ++r) {
         const int c = 4 * r + lane / 16;
-        offS[r] = c < 2 * WQ ? (c / WQ) * D + 4 * (g0 + c % WQ) + (lane & 3) : 0;
+        offS[r] = c < 2 * WQ ? (4 * (g0 + c % WQ) + (lane & 3)) * NC + c / WQ : 0;
     }
 
     // ---- state: terminal signature and adjoints
@@ -747,11 +753,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             const int e = lane + q * kWave;
             if (e < T * D) {
 #pragma unroll
-                for (int t = 0; t < N; ++t) {
-                    const float v = dxn[q] * inv1(t);
-                    if (t < 2) E[e / D][t][e % D] = v;
-                    Ec[e / D][e % D][t] = v;
-                }
+                for (int t = 0; t < N; ++t) Ec[e / D][e % D][t] = dxn[q] * inv1(t);
             }
         }
     };
@@ -769,7 +771,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         float b0v[WQ];
     };
     auto recon = [&](int row, Saved& sv) {
-        const float* Et = &E[row][0][0];
+        const float* Et = &Ec[row][0][0];
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const float* src = &Ec[row][letter[k]][0];
@@ -780,7 +782,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
 #pragma unroll
         for (int r = 0; r < NBS; ++r) { bs[r] = Et[offS[r]]; nbs[r] = -bs[r]; }
 #pragma unroll
-        for (int g = 0; g < WQ; ++g) sv.b0v[g] = Et[4 * (g0 + g) + (lane & 3)];
+        for (int g = 0; g < WQ; ++g) sv.b0v[g] = Et[(4 * (g0 + g) + (lane & 3)) * NC];
 
         // 1. reconstruction with -dX
         float am[K + 1][N + 2];
@@ -862,12 +864,25 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         // 4. gradient contributions of this segment: every lane parks its values in private LDS slots
         //    Vb[source][segment][lane]; they are summed over lanes once per tile (tile_reduce), which keeps
         //    dependent cross-lane chains out of the segment loop.
-        float* vb = Vb + row * kWave + lane;
+        float* vb = Vb + (row % VG) * kWave + lane;
         vb[0] = gck[K - 1];                                       // source 0: letters = lane bits [0, LB)
 #pragma unroll
-        for (int g = 0; g < WQ; ++g) vb[(1 + g) * T * kWave] = gcs[g];   // sources 1..WQ: letters 4 (g0 + g) + lane % 4
+        for (int g = 0; g < WQ; ++g) vb[(1 + g) * VG * kWave] = gcs[g];   // sources 1..WQ: letters 4 (g0 + g) + lane % 4
 #pragma unroll
-        for (int k = 0; k < K - 1; ++k) vb[(NSRC0 + k) * T * kWave] = gck[k];   // earlier chain letters
+        for (int k = 0; k < K - 1; ++k) vb[(NSRC0 + k) * VG * kWave] = gck[k];   // earlier chain letters
+    };
+    // the sources of the VG segments from `first` on, summed over the lanes into the gradient tile
+    auto reduce_sources = [&](int first) {
+        wave_lds_fence();
+        float* gtv = gt + first * D;
+        // (the lanes of a class take different segments and the classes of a source different letters: no two lanes of
+        // a call meet in one entry, so plain read-modify-writes do; LDS atomics cost some ninety clocks each)
+        tile_reduce<(1 << LB) - 1, VG, false>(Vb, gtv, D, lane, letter[K - 1]);
+#pragma unroll
+        for (int g = 0; g < WQ; ++g)
+            tile_reduce<3, VG, false>(Vb + (1 + g) * VG * kWave, gtv, D, lane, 4 * (g0 + g) + (lane & 3));
+        chain_tile_reduce<D, K, VG, 0, false>(Vb + NSRC0 * VG * kWave, gtv, lane, letter);
+        wave_lds_fence();
     };
 
     const int64_t ntiles = (L + T - 1) / T;
@@ -887,7 +902,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             const bool col_ok = (lane & 15) < T;
             float Bx[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) Bx[ks] = E[col][0][4 * ks + lane / 16];
+            for (int ks = 0; ks < KS; ++ks) Bx[ks] = Ec[col][4 * ks + lane / 16][0];
 #pragma unroll
             for (int v = 0; v < NSV; ++v)
 #pragma unroll
@@ -902,18 +917,36 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
         }
         {
             static_assert(T % 2 == 0, "the segment loop is unrolled by two");
-            Saved SA, SB;
-            recon(T - 1, SA);
+            if constexpr (T == 16) {
+                // a lone wavefront per SIMD: recon runs one segment ahead of adjoint so that their chains overlap
+                Saved SA, SB;
+                recon(T - 1, SA);
 #pragma unroll 1
-            for (int tt = T - 1; tt >= 3; tt -= 2) {
-                recon(tt - 1, SB);
-                adjoint(tt, SA);
-                recon(tt - 2, SA);
-                adjoint(tt - 1, SB);
+                for (int tt = T - 1; tt >= 3; tt -= 2) {
+                    recon(tt - 1, SB);
+                    adjoint(tt, SA);
+                    recon(tt - 2, SA);
+                    adjoint(tt - 1, SB);
+                    if constexpr (VG < T) {
+                        if ((tt - 1) % VG == 0) reduce_sources(tt - 1);
+                    }
+                }
+                recon(0, SB);
+                adjoint(1, SA);
+                adjoint(0, SB);
+            } else {
+                // two wavefronts per SIMD hide each other's latencies; one set of saved values keeps the registers
+                // within half a SIMD's
+#pragma unroll 1
+                for (int tt = T - 1; tt >= 0; --tt) {
+                    Saved SA;
+                    recon(tt, SA);
+                    adjoint(tt, SA);
+                    if constexpr (VG < T) {
+                        if (tt % VG == 0 && tt > 0) reduce_sources(tt);
+                    }
+                }
             }
-            recon(0, SB);
-            adjoint(1, SA);
-            adjoint(0, SB);
         }
         wave_lds_fence();
         {
@@ -935,11 +968,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_mfma_bwd_kernel(
             }
             wave_lds_fence();
         }
-        tile_reduce<(1 << LB) - 1, T>(Vb, gt, D, lane, letter[K - 1]);
-#pragma unroll
-        for (int g = 0; g < WQ; ++g) tile_reduce<3, T>(Vb + (1 + g) * T * kWave, gt, D, lane, 4 * (g0 + g) + (lane & 3));
-        chain_tile_reduce<D, K, T, 0>(Vb + NSRC0 * T * kWave, gt, lane, letter);
-        wave_lds_fence();
+        reduce_sources(0);                             // the last VG segments walked (all of them where VG = T)
         // flush: (segment, letter) is contiguous in gdx
         for (int e = lane; e < T * D; e += kWave) {
             const int64_t s = n * T + e / D;
@@ -1974,22 +2003,22 @@ hipError_t launch_trunc_tails_bwd(const float* path, const float* coeffs, const 
     return hipGetLastError();
 }
 
-template <int D, int N, int WQ, int T>
+template <int D, int N, int WQ, int T, int VG = T>
 hipError_t launch_trunc_mfma_bwd(const float* path, const float* coeffs, const float* grad, const float* coeffs_last,
                                  const float* grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc, float* gdx, float* resid,
                                  hipStream_t stream, const WindowList& wl = WindowList())
 {
     using G = MGeo<D, N, N - 2, WQ>;
-    using LY = BwdLds<D, N, WQ, T>;
+    using LY = BwdLds<D, N, WQ, T, VG>;
     static_assert(LY::BYTES <= 160 * 1024, "LDS of one compute unit");
     const int64_t waves = B * C * (wl.win ? wl.K : 1) * G::WAVES;
     const int64_t blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if (LY::BYTES > 64 * 1024) {                 // above the default limit the kernel has to be told once
-        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&trunc_mfma_bwd_kernel<D, N, WQ, T>), (int)LY::BYTES);
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&trunc_mfma_bwd_kernel<D, N, WQ, T, VG>), (int)LY::BYTES);
         if (e != hipSuccess) return e;
     }
-    trunc_mfma_bwd_kernel<D, N, WQ, T><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(
+    trunc_mfma_bwd_kernel<D, N, WQ, T, VG><<<(unsigned)blocks, kWave * kWavesPerBlock, LY::BYTES, stream>>>(
         path, coeffs, grad, coeffs_last, grad_last, B, P, C, Lc, wl, gdx, resid);
     return hipGetLastError();
 }
@@ -2102,11 +2131,17 @@ hipError_t trunc_backward(int d, int depth, const float* path, const float* coef
         return small ? launch_trunc_node_bwd<8, 5, 4>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream)
                      : launch_trunc_node_bwd<8, 5, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
     }
-    // d = 16: tiles of 8 segments halve the LDS of a workgroup but fill only half of the columns of the time-batched
-    // matrix products; measured slower or equal at every batch size, kept selectable
-    if (d == 16 && depth == 4)
-        return tile == 8 ? launch_trunc_mfma_bwd<16, 4, 1, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream)
-                         : launch_trunc_mfma_bwd<16, 4, 1, 16>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
+    // d = 16: a tile of 16 segments fills the 16 columns of the time-batched matrix products but its 139 KB of LDS leave
+    // room for one workgroup per compute unit, and a lone wavefront issues vector instructions at half the rate of its
+    // SIMD.  Tiles of 12 segments (gradient sources summed every 4 segments: 77 KB) let two workgroups share a compute
+    // unit at three quarters of the columns: taken when the launch has two wavefronts per SIMD to offer.  (Tiles of 8
+    // segments, half the columns, were measured slower or equal at every batch size; kept selectable.)
+    if (d == 16 && depth == 4) {
+        const int t = tile == 8 || tile == 12 || tile == 16 ? tile : (B * C * 16 >= 2048 ? 12 : 16);
+        if (t == 8) return launch_trunc_mfma_bwd<16, 4, 1, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
+        if (t == 12) return launch_trunc_mfma_bwd<16, 4, 1, 12, 4>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
+        return launch_trunc_mfma_bwd<16, 4, 1, 16>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
+    }
     return hipErrorInvalidValue;
 }
 
