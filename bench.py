@@ -251,6 +251,20 @@ def workload_row(S, torch, st, sec, kf, kb, cf, cb, steps):
     }
 
 
+def plain_row(S, torch, name, n):
+    """The workload through sig_forward / sig_backward, which keep the terminal signature alone between the calls."""
+    s3 = setup(name, S, torch, plain=True)
+    step(S, s3)
+    torch.cuda.synchronize()
+    _, kf3, kb3, f3, b3 = time_steps(S, torch, s3, n, max(n // 5, 2))
+    w3, wl3 = s3["ws"], s3["wl"]
+    return {"fwd_ms": round(f3, 4), "bwd_ms": round(b3, 4),
+            "fwd_roofline_frac": roofline_entry(flops_forward(w3, wl3.B, wl3.L), f3)["frac"],
+            "bwd_roofline_frac": roofline_entry(flops_backward(w3, wl3.B, wl3.L), b3)["frac"],
+            "kernels": [w3.kernel_name(False, wl3.B, wl3.L + 1), w3.kernel_name(True, wl3.B, wl3.L + 1)],
+            "workspace_bytes": s3["workspace_bytes"]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -299,9 +313,11 @@ def main():
     dominant["traffic"] = counter_traffic(dominant["kernel"], wl.name)
     dominant["traffic_source"] = ("profiles/hbm_traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this program"
                                   if dominant["traffic"] is not None else None)
-    # plain v_fma_f32 rate of this chip, measured in the same run (register-only kernel, 32 wavefronts per compute unit):
-    # the roof for vector code that does not use packed FP32
+    # plain v_fma_f32 rate of this chip, measured in the same run with a register-only kernel: 8 wavefronts per SIMD (the
+    # roof for vector code that does not use packed FP32) and a single wavefront per SIMD (which issues at about half
+    # the rate of its SIMD: why the kernels want two wavefronts per SIMD)
     dominant["measured_unpacked_fma_tflops"] = round(S.sig_probe_fma_tflops(), 1)
+    dominant["measured_unpacked_fma_tflops_one_wavefront_per_simd"] = round(S.sig_probe_fma_tflops(blocks=256, iters=16384), 1)
 
     out = {
         "metric": "signature coeff-steps/sec (fwd, fwd+bwd) + % of FP32 vector roofline, 1 GPU",
@@ -336,6 +352,9 @@ def main():
                                  "largest_coefficient": float(f"{float(st['coeffs'].abs().max()):.3e}"),
                                  "note": "largest |S(w)| left after multiplying by exp(-dX_j) for j = L..1, over all paths"}
     head_row = workload_row(S, torch, st, sec, ms_f, ms_b, call_f, call_b, args.steps)
+    out["calls"] = head_row["calls"]
+    if st["ck"] is not None and not args.no_others:
+        head_row["without_checkpoint"] = plain_row(S, torch, wl.name, min(args.steps, 100))
     if not args.no_cpu:
         cpu, errs = oracle_check(st, CPU_SAMPLE[wl.name])
         out["cpu_baseline"] = cpu
@@ -367,18 +386,7 @@ def main():
             if not args.no_cpu:
                 per[name]["cpu_baseline"], per[name]["errors"] = oracle_check(s2, CPU_SAMPLE[name])
             if s2["ck"] is not None:
-                # the same workload through sig_forward / sig_backward, which keep the terminal signature alone
-                s3 = setup(name, S, torch, plain=True)
-                step(S, s3)
-                torch.cuda.synchronize()
-                _, kf3, kb3, f3, b3 = time_steps(S, torch, s3, n, max(n // 5, 2))
-                w3, wl3 = s3["ws"], s3["wl"]
-                per[name]["without_checkpoint"] = {
-                    "fwd_ms": round(f3, 4), "bwd_ms": round(b3, 4),
-                    "fwd_roofline_frac": roofline_entry(flops_forward(w3, wl3.B, wl3.L), f3)["frac"],
-                    "bwd_roofline_frac": roofline_entry(flops_backward(w3, wl3.B, wl3.L), b3)["frac"],
-                    "kernels": [w3.kernel_name(False, wl3.B, wl3.L + 1), w3.kernel_name(True, wl3.B, wl3.L + 1)]}
-                del s3
+                per[name]["without_checkpoint"] = plain_row(S, torch, name, n)
             del s2
             torch.cuda.empty_cache()
         out["per_workload"] = per

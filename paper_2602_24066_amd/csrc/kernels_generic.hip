@@ -687,10 +687,14 @@ hipError_t logsig_backward(const float* coeffs, const float* glog, int64_t B, in
 }
 
 // Register-only multiply-add loop for the benchmark: every thread runs `iters` rounds of 16 independent fmaf chains
-// (no memory traffic inside the loop) and stores one value so that nothing is optimised away.
+// (no memory traffic inside the loop) and stores one value so that nothing is optimised away.  The multiplier and the
+// addend differ from lane to lane, so all three operands of every instruction are vector registers, as in the
+// signature kernels (with a scalar-register operand the same loop was measured at two thirds of the rate).
 __global__ __launch_bounds__(256) void fma_probe_kernel(float* out, int iters, float a, float b)
 {
     float x[16];
+    a += (float)threadIdx.x * 1e-7f;
+    b += (float)threadIdx.x * 1e-8f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) x[i] = (float)(threadIdx.x + i);
     for (int it = 0; it < iters; ++it) {
