@@ -318,6 +318,13 @@ def main():
     # the rate of its SIMD: why the kernels want two wavefronts per SIMD)
     dominant["measured_unpacked_fma_tflops"] = round(S.sig_probe_fma_tflops(), 1)
     dominant["measured_unpacked_fma_tflops_one_wavefront_per_simd"] = round(S.sig_probe_fma_tflops(blocks=256, iters=16384), 1)
+    # what a SIMD issues per nanosecond, by instruction kind and wavefronts per SIMD (register-only probes): ns per
+    # wavefront-iteration of 64 multiply-adds (vector or scalar multiplier), of 8 16x16x4 matrix instructions, and of both
+    dominant["issue_probe_ns"] = {
+        f"{w}_per_simd": {"fma64_vector_operands": round(S.sig_probe_issue_ns(0, w), 1),
+                          "fma64_scalar_multiplier": round(S.sig_probe_issue_ns(1, w), 1),
+                          "mfma8_16x16x4": round(S.sig_probe_issue_ns(2, w), 1),
+                          "fma64_and_mfma8_interleaved": round(S.sig_probe_issue_ns(3, w), 1)} for w in (1, 2, 4)}
 
     out = {
         "metric": "signature coeff-steps/sec (fwd, fwd+bwd) + % of FP32 vector roofline, 1 GPU",

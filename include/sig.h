@@ -315,6 +315,13 @@ int sig_profile_read(int which, int64_t* n_launches, double* total_ms);
  * floating-point operations in all) and stores one float; out: device, blocks * 256 floats.  The caller times it. */
 int sig_probe_fma(void* out /*device*/, size_t out_bytes, int blocks, int iters, void* stream);
 
+/* Issue-rate probes for benchmarks: register-only loops of `blocks` workgroups of 256 threads (one wavefront per SIMD of
+ * a compute unit per workgroup); per iteration a wavefront issues, by `mode`,
+ *   0: 64 multiply-adds whose operands are all vector registers      1: 64 multiply-adds with a scalar-register multiplier
+ *   2: 8 matrix instructions 16x16x4 (fp32)                            3: the 64 multiply-adds of 0 interleaved with the 8 of 2
+ * out: device, blocks * 256 floats.  The caller times the launch; with 256 blocks a SIMD holds one wavefront, with 512 two. */
+int sig_probe_issue(void* out /*device*/, size_t out_bytes, int blocks, int iters, int mode, void* stream);
+
 /* ---- diagnostics ------------------------------------------------------------------------------------- */
 const char* sig_strerror(int code);
 int         sig_last_hip_error(void);          /* hipError_t of the last SIG_EHIP on this thread, else 0 */

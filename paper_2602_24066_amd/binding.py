@@ -105,6 +105,7 @@ def load_library():
     sig("sig_wordset_kernel_name", ctypes.c_char_p, [c_p, c_int])
     sig("sig_kernel_name", ctypes.c_char_p, [c_p, c_int, c_i64, c_i64])
     sig("sig_probe_fma", c_int, [c_p, c_sz, c_int, c_int, c_p])
+    sig("sig_probe_issue", c_int, [c_p, c_sz, c_int, c_int, c_int, c_p])
     _lib = lib
     return lib
 
@@ -676,6 +677,26 @@ def sig_probe_fma_tflops(blocks: int = 256 * 32, iters: int = 4096, repeats: int
         e1.synchronize()
         best = min(best, e0.elapsed_time(e1))
     return 2.0 * 16 * iters * 256 * blocks / (best * 1e-3) / 1e12
+
+
+def sig_probe_issue_ns(mode: int, waves_per_simd: int = 1, iters: int = 8192, repeats: int = 3) -> float:
+    """Nanoseconds a SIMD takes per probe iteration and wavefront (64 multiply-adds and / or 8 matrix instructions,
+    see sig_probe_issue in include/sig.h) with `waves_per_simd` wavefronts resident on every SIMD; best of `repeats`."""
+    import torch
+    lib = load_library()
+    blocks = 256 * waves_per_simd
+    out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    best = float("inf")
+    for _ in range(repeats + 1):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        _check(lib.sig_probe_issue(ctypes.c_void_p(out.data_ptr()), out.numel() * 4, blocks, iters, mode, ctypes.c_void_p(stream)),
+               "sig_probe_issue")
+        e1.record()
+        e1.synchronize()
+        best = min(best, e0.elapsed_time(e1))
+    return best * 1e6 / iters / waves_per_simd
 
 
 def sig_profile_enable(on, channels=None) -> None:

@@ -66,6 +66,7 @@ hipError_t logsig_backward(const float* coeffs, const float* glog, int64_t B, in
 // scratch array (SIG_STATIC_SCRATCH_BYTES bytes, 256-byte aligned), looked up once per device.
 hipError_t static_scratch(void** ptr);
 hipError_t fma_probe(float* out, int blocks, int iters, hipStream_t stream);   // out: blocks * 256 floats
+hipError_t issue_probe(float* out, int blocks, int iters, int mode, hipStream_t stream);   // out: blocks * 256 floats
 hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* grad_path, hipStream_t stream);
 
 // Window list of a launch (signatures over windows): K windows per path, window k between the points win[2 k] and

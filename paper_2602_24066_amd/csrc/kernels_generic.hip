@@ -707,6 +707,56 @@ __global__ __launch_bounds__(256) void fma_probe_kernel(float* out, int iters, f
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// Issue-rate probes (register-only loops; per iteration 64 vector multiply-adds and / or 8 matrix instructions):
+//   MODE 0  64 v_fma_f32 whose three operands are vector registers
+//   MODE 1  64 v_fma_f32 with the multiplier in a scalar register (lane-uniform kernel argument)
+//   MODE 2  8 v_mfma_f32_16x16x4_f32 (independent accumulators)
+//   MODE 3  the 64 multiply-adds of MODE 0 interleaved with the 8 matrix instructions of MODE 2
+// Timed with one and with several wavefronts per SIMD they show what a lone wavefront can issue, whether vector and
+// matrix instructions overlap, and what a scalar operand costs.
+typedef float probe_v4f __attribute__((ext_vector_type(4)));
+template <int MODE>
+__global__ __launch_bounds__(256) void issue_probe_kernel(float* out, int iters, float a0, float b0)
+{
+    constexpr bool kVec = MODE != 2, kMat = MODE >= 2;
+    float x[64];
+    probe_v4f acc[8];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) x[i] = (float)threadIdx.x * 1e-3f + (float)i;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = (probe_v4f){0.0f, 0.0f, 0.0f, 0.0f};
+    float a = a0, b = b0 + (float)threadIdx.x * 1e-8f;
+    if (MODE != 1) a += (float)threadIdx.x * 1e-7f;      // MODE 1 keeps the multiplier lane-uniform
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (kMat) acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[i], 0, 0, 0);
+            if (kVec) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) x[8 * i + j] = fmaf(x[8 * i + j], a, b);
+            }
+        }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) s += x[i];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+hipError_t issue_probe(float* out, int blocks, int iters, int mode, hipStream_t stream)
+{
+    if (blocks <= 0 || iters <= 0 || mode < 0 || mode > 3) return hipErrorInvalidValue;
+    switch (mode) {
+        case 0: issue_probe_kernel<0><<<(unsigned)blocks, 256, 0, stream>>>(out, iters, 0.999f, 0.001f); break;
+        case 1: issue_probe_kernel<1><<<(unsigned)blocks, 256, 0, stream>>>(out, iters, 0.999f, 0.001f); break;
+        case 2: issue_probe_kernel<2><<<(unsigned)blocks, 256, 0, stream>>>(out, iters, 0.999f, 0.001f); break;
+        default: issue_probe_kernel<3><<<(unsigned)blocks, 256, 0, stream>>>(out, iters, 0.999f, 0.001f); break;
+    }
+    return hipGetLastError();
+}
+
 hipError_t fma_probe(float* out, int blocks, int iters, hipStream_t stream)
 {
     if (blocks <= 0 || iters <= 0) return hipErrorInvalidValue;
