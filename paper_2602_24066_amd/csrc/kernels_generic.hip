@@ -263,20 +263,31 @@ __global__ __launch_bounds__(kWave) void bwd_generic_kernel(const UnitDesc* __re
 // Increments, differenced and transposed for the run-time specialised kernels (lane = path):
 //   dxT[((g * Lpad + j) * d + i) * 64 + lane] = X[b][j+1][i] - X[b][j][i],  b = 64 g + lane,
 // zero for padded segments j >= L and for b >= B.
-__global__ void increments_transposed_kernel(const float* __restrict__ path, int64_t B, int64_t P, int d, int64_t Lpad,
-                                             int64_t total, float* __restrict__ dxT)
+// One workgroup takes 64 paths x TS segments: every wavefront reads runs of consecutive floats of one path at a time
+// (coalesced), the differences go to an LDS tile [segment * d + letter][path] and leave it as rows of 64 paths.
+__global__ void increments_transposed_kernel(const float* __restrict__ path, int64_t B, int64_t P, int d, int64_t Lpad, int TS,
+                                             int64_t tiles, float* __restrict__ dxT)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const int lane = (int)(idx % kWave);
-    const int64_t r = idx / kWave;
-    const int i = (int)(r % d);
-    const int64_t j = (r / d) % Lpad;
-    const int64_t g = r / ((int64_t)d * Lpad);
-    const int64_t b = g * kWave + lane;
-    float v = 0.0f;
-    if (b < B && j < P - 1) v = path[(b * P + j + 1) * d + i] - path[(b * P + j) * d + i];
-    dxT[idx] = v;
+    extern __shared__ float tile[];                       // [TS * d][65]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int64_t g = blockIdx.x / tiles;
+    const int64_t j0 = (blockIdx.x % tiles) * TS;
+    const int R = TS * d;
+    const int64_t L = P - 1;
+    for (int p = wave; p < kWave; p += nwaves) {
+        const int64_t b = g * kWave + p;
+        const float* row = path + (b * P + j0) * d;
+        for (int e = lane; e < R; e += kWave) {
+            const int64_t j = j0 + e / d;
+            float v = 0.0f;
+            if (b < B && j < L) v = row[e + d] - row[e];
+            tile[e * 65 + p] = v;
+        }
+    }
+    __syncthreads();
+    float* out = dxT + ((g * Lpad + j0) * d) * kWave;
+    for (int e = wave; e < R; e += nwaves)
+        if (j0 + e / d < Lpad) out[(int64_t)e * kWave + lane] = tile[e * 65 + lane];
 }
 
 __global__ void fill_zero_kernel(float* p, int64_t n)
@@ -354,12 +365,13 @@ hipError_t generic_backward(const GenericArgs& a, int max_len, hipStream_t strea
 
 hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d, int64_t Lpad, float* dxT, hipStream_t stream)
 {
-    const int64_t total = ((B + kWave - 1) / kWave) * Lpad * d * kWave;
-    if (total <= 0) return hipSuccess;
-    const int threads = 256;
-    const int64_t blocks = (total + threads - 1) / threads;
-    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    increments_transposed_kernel<<<(unsigned)blocks, threads, 0, stream>>>(path, B, P, d, Lpad, total, dxT);
+    const int64_t groups = (B + kWave - 1) / kWave;
+    if (groups <= 0 || Lpad <= 0 || d <= 0) return hipSuccess;
+    const int TS = std::max(1, 128 / d);
+    const size_t lds = (size_t)TS * d * 65 * sizeof(float);
+    const int64_t tiles = (Lpad + TS - 1) / TS;
+    if (lds > 64 * 1024 || tiles > 0x7fffffff / groups) return hipErrorInvalidValue;
+    increments_transposed_kernel<<<(unsigned)(tiles * groups), 256, lds, stream>>>(path, B, P, d, Lpad, TS, tiles, dxT);
     return hipGetLastError();
 }
 
