@@ -116,6 +116,7 @@ const int64_t* sig_wordset_user_index(const sig_wordset* ws);   /* host [n_user]
  *   "jit_wg_waves"  [SIG_JIT_WG_WAVES]   wavefronts per workgroup of the specialised kernels, 1..4 (default 4)
  *   "bwd_tile"      [SIG_BWD_TILE]       segments per LDS tile of the d = 16 (8, 16) and d = 8 (4, 8) backward kernels
  *   "ckpt_chunks"   [SIG_CKPT_CHUNKS]    time chunks of the checkpointed calls: 0 launcher's rule, 1 off, 2..4 forced
+ *   "jit_fwd_tile"  [SIG_JIT_FWD_TILE]   segments per LDS tile of the specialised forward kernels: 0 default, 1..32
  * Workspace sizes depend on the knobs: query them again after a change.  Returns SIG_EINVAL for an unknown name.
  * Not to be called while another thread runs sig_forward / sig_backward on the same word set. */
 int sig_wordset_set_option(sig_wordset* ws, const char* name, int value);

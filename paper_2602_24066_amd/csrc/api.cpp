@@ -43,6 +43,7 @@ const OptionName kOptions[] = {
     {"jit_wg_waves", "SIG_JIT_WG_WAVES", &sig::WordSet::Options::jit_wg_waves},
     {"bwd_tile", "SIG_BWD_TILE", &sig::WordSet::Options::bwd_tile},
     {"ckpt_chunks", "SIG_CKPT_CHUNKS", &sig::WordSet::Options::ckpt_chunks},
+    {"jit_fwd_tile", "SIG_JIT_FWD_TILE", &sig::WordSet::Options::jit_fwd_tile},
 };
 void options_from_environment(sig::WordSet& w)
 {
@@ -237,7 +238,11 @@ int64_t jit_units(const sig::WordSet& w, int /*dir*/, int64_t B)
 // segments per LDS tile; backward also keeps one gradient tile [T][d][65] per wavefront of the workgroup (four as a
 // rule) in the 64 KB of static LDS
 int jit_tile_steps(int d, int dir, int nw = 4) { return std::min(8, (dir ? 192 / std::max(nw, 4) : 240) / std::max(d, 1)); }
-int jit_tile_for(const sig::WordSet& w, int dir) { return std::max(1, jit_tile_steps(w.d, dir, jit_wg_waves(w))); }
+int jit_tile_for(const sig::WordSet& w, int dir)
+{
+    if (dir == 0 && w.opt.jit_fwd_tile > 0) return std::max(1, std::min(std::min(w.opt.jit_fwd_tile, 32), 240 / std::max(w.d, 1)));
+    return std::max(1, jit_tile_steps(w.d, dir, jit_wg_waves(w)));
+}
 
 bool jit_enabled(const sig::WordSet& w)
 {
@@ -251,15 +256,16 @@ sig::WordSet::JitEntry* jit_entry(const sig::WordSet& cw, int dir, int64_t B)
 {
     sig::WordSet& w = const_cast<sig::WordSet&>(cw);     // the cache is logically mutable
     const int64_t n_units = jit_units(w, dir, B);
-    const int wgw = jit_wg_waves(w);
+    const int wgw = jit_wg_waves(w), tile = jit_tile_for(w, dir);
     std::lock_guard<std::mutex> lock(g_jit_mutex);
     for (auto* e : w.jit[dir])
-        if (e->n_units == n_units && e->wg_waves == wgw) return e;
+        if (e->n_units == n_units && e->wg_waves == wgw && e->tile == tile) return e;
     auto* e = new (std::nothrow) sig::WordSet::JitEntry;
     if (!e) return nullptr;
     try {
         e->n_units = n_units;
         e->wg_waves = wgw;
+        e->tile = tile;
         if (dir == 0) sig::build_plan_balanced(w, n_units, 320, false, 1, 1, e->plan);
         else sig::build_plan_balanced(w, n_units, 160, true, 6, 9, e->plan);
         e->kernel = new sig::JitKernel;

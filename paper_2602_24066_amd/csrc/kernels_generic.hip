@@ -263,25 +263,31 @@ __global__ __launch_bounds__(kWave) void bwd_generic_kernel(const UnitDesc* __re
 // Increments, differenced and transposed for the run-time specialised kernels (lane = path):
 //   dxT[((g * Lpad + j) * d + i) * 64 + lane] = X[b][j+1][i] - X[b][j][i],  b = 64 g + lane,
 // zero for padded segments j >= L and for b >= B.
-// One workgroup takes 64 paths x TS segments: every wavefront reads runs of consecutive floats of one path at a time
+// One workgroup takes 64 paths x TS segments: a wavefront reads runs of consecutive floats of its 16 paths
 // (coalesced), the differences go to an LDS tile [segment * d + letter][path] and leave it as rows of 64 paths.
 __global__ void increments_transposed_kernel(const float* __restrict__ path, int64_t B, int64_t P, int d, int64_t Lpad, int TS,
                                              int64_t tiles, float* __restrict__ dxT)
 {
     extern __shared__ float tile[];                       // [TS * d][65]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = 4;
     const int64_t g = blockIdx.x / tiles;
     const int64_t j0 = (blockIdx.x % tiles) * TS;
     const int R = TS * d;
     const int64_t L = P - 1;
-    for (int p = wave; p < kWave; p += nwaves) {
-        const int64_t b = g * kWave + p;
-        const float* row = path + (b * P + j0) * d;
-        for (int e = lane; e < R; e += kWave) {
-            const int64_t j = j0 + e / d;
-            float v = 0.0f;
-            if (b < B && j < L) v = row[e + d] - row[e];
-            tile[e * 65 + p] = v;
+    // 16 paths per wavefront (workgroups of 256 threads); the loads of all of them are issued before the first is used
+    for (int e0 = 0; e0 < R; e0 += kWave) {
+        const int e = e0 + lane;
+        const bool live = e < R && j0 + e / d < L;
+        float v[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int64_t b = g * kWave + wave * 16 + q;
+            const float* row = path + (b * P + j0) * d;
+            v[q] = (live && b < B) ? row[e + d] - row[e] : 0.0f;
+        }
+        if (e < R) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) tile[e * 65 + wave * 16 + q] = v[q];
         }
     }
     __syncthreads();
@@ -367,7 +373,7 @@ hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d,
 {
     const int64_t groups = (B + kWave - 1) / kWave;
     if (groups <= 0 || Lpad <= 0 || d <= 0) return hipSuccess;
-    const int TS = std::max(1, 128 / d);
+    const int TS = std::max(1, 64 / d);
     const size_t lds = (size_t)TS * d * 65 * sizeof(float);
     const int64_t tiles = (Lpad + TS - 1) / TS;
     if (lds > 64 * 1024 || tiles > 0x7fffffff / groups) return hipErrorInvalidValue;

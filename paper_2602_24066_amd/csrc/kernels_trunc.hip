@@ -585,6 +585,32 @@ __device__ __forceinline__ void tile_reduce(const float* V, float* gt, int D, in
     }
 }
 
+// Values of other lanes without LDS traffic: DPP forms inside a row of 16 lanes (CTRL: 0x128 lane + 8 mod 16, 0x140 lane
+// 15 - l, 0x141 lane 7 - l of the half row, 0xB1 / 0x4E lanes l ^ 1 / l ^ 2 of the quad), the swizzle network for an
+// exclusive-or of the lane number below 32.  Every lane must be active.
+template <int CTRL>
+__device__ __forceinline__ float dpp_lane(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+template <int XOR_MASK>
+__device__ __forceinline__ float swizzle_xor(float x)
+{
+    static_assert(XOR_MASK > 0 && XOR_MASK < 32, "the swizzle network works on groups of 32 lanes");
+    return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), (XOR_MASK << 10) | 0x1f));
+}
+// Four values per lane (v[s] belongs to segment s) summed over pairs of partner lanes, twice, each time keeping half of
+// the segments: the lane ends up with the sum over four lanes for segment 2 hi + lo.  X1 / X2 fetch the partner's value;
+// the partner of the first exchange differs in `hi`, the partner of the second agrees in `hi` and differs in `lo`.
+template <class X1, class X2>
+__device__ __forceinline__ float fold_four_segments(const float (&v)[4], bool hi, bool lo, X1 x1, X2 x2)
+{
+    const float k0 = hi ? v[2] : v[0], k1 = hi ? v[3] : v[1];
+    const float s0 = hi ? v[0] : v[2], s1 = hi ? v[1] : v[3];
+    const float a0 = k0 + x1(s0), a1 = k1 + x1(s1);
+    return (lo ? a1 : a0) + x2(lo ? a0 : a1);
+}
+
 // chain letter k (0-based) of K: bit field of the lane number, or empty when the letter is the same in the whole wavefront
 __host__ __device__ constexpr int chain_keep_mask(int LB, int K, int k)
 {
@@ -627,7 +653,10 @@ struct BwdLds {
     static constexpr int OFF_EC = 0;
     static constexpr int OFF_GT = OFF_EC + T * D * NC;
     static constexpr int OFF_VB = OFF_GT + T * D;
-    static constexpr int OFF_HA = OFF_VB + NSRC * VG * kWave;
+    // tiles for two workgroups per compute unit keep the gradient sources of VG = 4 segments in registers and sum them
+    // over lanes with cross-lane moves; the other shapes park them in LDS (VB)
+    static constexpr bool SOURCES_IN_REGISTERS = T < 16 && VG == 4 && D == 16 && N == 4 && WQ == 1;
+    static constexpr int OFF_HA = OFF_VB + (SOURCES_IN_REGISTERS ? 0 : NSRC * VG * kWave);
     static constexpr int PER_WAVE = OFF_HA + NSV * T * SP;
     static_assert(OFF_GT % 4 == 0 && OFF_VB % 4 == 0 && OFF_HA % 4 == 0 && PER_WAVE % 4 == 0,
                   "16-byte alignment of the LDS regions");
@@ -810,7 +839,8 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trun
         sv.Pb2 = __builtin_amdgcn_mfma_f32_4x4x1f32(0.5f * sv.ap[K][2], one, zero4, 0, 0, 0);
     };
 
-    auto adjoint = [&](int row, const Saved& sv) {
+    struct Sources { float last, slice, first; };     // gradient sources of a segment: letter[K - 1], slice letter, letter[0]
+    auto adjoint = [&](int row, const Saved& sv, Sources& src) {
         // 3a. leaves: gbar[1] of the slice word was computed for the whole tile before the segment loop; its slot
         // takes A+_{N-1}[1] of the slice word for the product over parents after the loop
         v4f g1[WQ];
@@ -864,12 +894,41 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trun
         // 4. gradient contributions of this segment: every lane parks its values in private LDS slots
         //    Vb[source][segment][lane]; they are summed over lanes once per tile (tile_reduce), which keeps
         //    dependent cross-lane chains out of the segment loop.
-        float* vb = Vb + (row % VG) * kWave + lane;
-        vb[0] = gck[K - 1];                                       // source 0: letters = lane bits [0, LB)
+        if constexpr (LY::SOURCES_IN_REGISTERS) {
+            src.last = gck[K - 1];
+            src.slice = gcs[0];
+            src.first = gck[0];
+        } else {
+            float* vb = Vb + (row % VG) * kWave + lane;
+            vb[0] = gck[K - 1];                                       // source 0: letters = lane bits [0, LB)
 #pragma unroll
-        for (int g = 0; g < WQ; ++g) vb[(1 + g) * VG * kWave] = gcs[g];   // sources 1..WQ: letters 4 (g0 + g) + lane % 4
+            for (int g = 0; g < WQ; ++g) vb[(1 + g) * VG * kWave] = gcs[g];   // sources 1..WQ: letters 4 (g0 + g) + lane % 4
 #pragma unroll
-        for (int k = 0; k < K - 1; ++k) vb[(NSRC0 + k) * VG * kWave] = gck[k];   // earlier chain letters
+            for (int k = 0; k < K - 1; ++k) vb[(NSRC0 + k) * VG * kWave] = gck[k];   // earlier chain letters
+        }
+    };
+    // The same sums with the sources of four segments in registers (d = 16, depth 4: letter[1] = lane bits 0..3, the
+    // slice letter = 4 g0 + lane bits 0..1, letter[0] = lane bits 4..5 of this wavefront's 64 parents).  Each source
+    // is folded over the lane bits its letter does not depend on; two of those bits select the segment a lane ends up
+    // with, so the four segments cost little more than one.
+    auto reduce_registers = [&](int first, const float (&last)[4], const float (&slice)[4], const float (&chain0)[4]) {
+        float* gtv = gt + first * D;
+        auto x32 = [](float x) { return __shfl_xor(x, 32); };
+        auto x16 = [](float x) { return swizzle_xor<16>(x); };
+        // letter[1]: classes of the four lanes that differ in bits 4, 5; every lane ends with one (segment, letter)
+        const float r0 = fold_four_segments(last, (lane & 32) != 0, (lane & 16) != 0, x32, x16);
+        gtv[(lane >> 4) * D + letter[K - 1]] += r0;
+        // slice letter: classes of sixteen lanes that differ in bits 2..5
+        float r1 = fold_four_segments(slice, (lane & 32) != 0, (lane & 16) != 0, x32, x16);
+        r1 += dpp_lane<0x128>(r1);
+        r1 += swizzle_xor<4>(r1);
+        if ((lane & 12) == 0) gtv[(lane >> 4) * D + 4 * g0 + (lane & 3)] += r1;
+        // letter[0]: classes of the sixteen lanes of a row
+        float r2 = fold_four_segments(chain0, (lane & 8) != 0, (lane & 4) != 0, [](float x) { return dpp_lane<0x140>(x); },
+                                      [](float x) { return dpp_lane<0x141>(x); });
+        r2 += dpp_lane<0xB1>(r2);
+        r2 += dpp_lane<0x4E>(r2);
+        if ((lane & 3) == 0) gtv[((lane >> 2) & 3) * D + letter[0]] += r2;
     };
     // the sources of the VG segments from `first` on, summed over the lanes into the gradient tile
     auto reduce_sources = [&](int first) {
@@ -920,28 +979,46 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trun
             if constexpr (T == 16) {
                 // a lone wavefront per SIMD: recon runs one segment ahead of adjoint so that their chains overlap
                 Saved SA, SB;
+                Sources unused;
                 recon(T - 1, SA);
 #pragma unroll 1
                 for (int tt = T - 1; tt >= 3; tt -= 2) {
                     recon(tt - 1, SB);
-                    adjoint(tt, SA);
+                    adjoint(tt, SA, unused);
                     recon(tt - 2, SA);
-                    adjoint(tt - 1, SB);
+                    adjoint(tt - 1, SB, unused);
                     if constexpr (VG < T) {
                         if ((tt - 1) % VG == 0) reduce_sources(tt - 1);
                     }
                 }
                 recon(0, SB);
-                adjoint(1, SA);
-                adjoint(0, SB);
+                adjoint(1, SA, unused);
+                adjoint(0, SB, unused);
+            } else if constexpr (LY::SOURCES_IN_REGISTERS) {
+#pragma unroll 1
+                for (int t0 = T - VG; t0 >= 0; t0 -= VG) {
+                    float last[VG], slice[VG], chain0[VG];
+#pragma unroll
+                    for (int i = VG - 1; i >= 0; --i) {
+                        Saved SA;
+                        Sources src;
+                        recon(t0 + i, SA);
+                        adjoint(t0 + i, SA, src);
+                        last[i] = src.last;
+                        slice[i] = src.slice;
+                        chain0[i] = src.first;
+                    }
+                    reduce_registers(t0, last, slice, chain0);
+                }
             } else {
                 // two wavefronts per SIMD hide each other's latencies; one set of saved values keeps the registers
                 // within half a SIMD's
 #pragma unroll 1
                 for (int tt = T - 1; tt >= 0; --tt) {
                     Saved SA;
+                    Sources unused;
                     recon(tt, SA);
-                    adjoint(tt, SA);
+                    adjoint(tt, SA, unused);
                     if constexpr (VG < T) {
                         if (tt % VG == 0 && tt > 0) reduce_sources(tt);
                     }
@@ -968,7 +1045,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trun
             }
             wave_lds_fence();
         }
-        reduce_sources(0);                             // the last VG segments walked (all of them where VG = T)
+        if constexpr (!LY::SOURCES_IN_REGISTERS) reduce_sources(0);   // the last VG segments walked (all of them where VG = T)
         // flush: (segment, letter) is contiguous in gdx
         for (int e = lane; e < T * D; e += kWave) {
             const int64_t s = n * T + e / D;

@@ -91,6 +91,7 @@ struct WordSet {
         int logsig_gather = 0;         // 1: two-kernel form of the log-signature adjoint
         int ckpt_chunks = 0;           // time chunks of the checkpointed forward / backward: 0 launcher's rule, 1 off, 2..4
         int bwd_tile = 0;              // segments per LDS tile of the d = 16 backward kernel: 0 default, 8, 16
+        int jit_fwd_tile = 0;          // segments per LDS tile of the specialised forward kernels: 0 default, 1..32
         int jit_wg_waves = 4;          // wavefronts (work units) per workgroup of the run-time specialised kernels, 1..4;
                                        // 8 is accepted for inspecting the generated code on the host only: jit_load
                                        // refuses code objects whose registers do not fit two wavefronts per SIMD
@@ -101,6 +102,7 @@ struct WordSet {
     struct JitEntry {
         int64_t n_units = 0;
         int wg_waves = 0;              // wavefronts per workgroup the kernel is generated for
+        int tile = 0;                  // segments per LDS tile the kernel is generated for
         Plan plan;
         JitKernel* kernel = nullptr;
     };
