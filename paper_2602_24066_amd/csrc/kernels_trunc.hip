@@ -650,22 +650,24 @@ struct BwdLds {
     static constexpr int NSRC = 1 + WQ + (N - 2 - 1);
     static constexpr int SP = 68;                       // row stride of HA: 64 parents + 4 (16-byte aligned rows whose
                                                         // columns fall into different banks)
-    static constexpr int OFF_EC = 0;
-    static constexpr int OFF_GT = OFF_EC + T * D * NC;
+    // the table of scaled increments of a tile is the same for the wavefronts of a workgroup (they walk the same
+    // row) and sits once at the start of LDS; the rest is private to a wavefront
+    static constexpr int EC_FLOATS = T * D * NC;
+    static constexpr int OFF_GT = 0;
     static constexpr int OFF_VB = OFF_GT + T * D;
-    // tiles for two workgroups per compute unit keep the gradient sources of VG = 4 segments in registers and sum them
-    // over lanes with cross-lane moves; the other shapes park them in LDS (VB)
-    static constexpr bool SOURCES_IN_REGISTERS = T < 16 && VG == 4 && D == 16 && N == 4 && WQ == 1;
+    // the shapes for two workgroups per compute unit keep the gradient sources of VG = 4 segments in registers and sum
+    // them over lanes with cross-lane moves; the other shapes park them in LDS (VB)
+    static constexpr bool SOURCES_IN_REGISTERS = VG == 4 && T > VG && D == 16 && N == 4 && WQ == 1;
     static constexpr int OFF_HA = OFF_VB + (SOURCES_IN_REGISTERS ? 0 : NSRC * VG * kWave);
     static constexpr int PER_WAVE = OFF_HA + NSV * T * SP;
-    static_assert(OFF_GT % 4 == 0 && OFF_VB % 4 == 0 && OFF_HA % 4 == 0 && PER_WAVE % 4 == 0,
+    static_assert(EC_FLOATS % 4 == 0 && OFF_VB % 4 == 0 && OFF_HA % 4 == 0 && PER_WAVE % 4 == 0,
                   "16-byte alignment of the LDS regions");
-    static constexpr size_t BYTES = (size_t)kWavesPerBlock * PER_WAVE * sizeof(float);
+    static constexpr bool TWO_WORKGROUPS = SOURCES_IN_REGISTERS;   // per compute unit: registers held to half a SIMD's
+    static constexpr size_t BYTES = ((size_t)EC_FLOATS + (size_t)kWavesPerBlock * PER_WAVE) * sizeof(float);
 };
 
-// (tiles shorter than 16 segments exist to put two workgroups on a compute unit: their registers are held to half a SIMD's)
 template <int D, int N, int WQ, int T, int VG>
-__global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trunc_mfma_bwd_kernel(
+__global__ __launch_bounds__(kWave * kWavesPerBlock, (BwdLds<D, N, WQ, T, VG>::TWO_WORKGROUPS ? 2 : 1)) void trunc_mfma_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad,
     const float* __restrict__ coeffs_last, const float* __restrict__ grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
     WindowList wl, float* gdx, float* resid)
@@ -677,19 +679,21 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trun
     constexpr int NBS = G::NBS;                       // slice combinations: index t * WQ + g, t in {0, 1}
     constexpr int NC = (N + 3) / 4 * 4;
     constexpr int NSV = WQ * 4;                       // slice word vectors
-    constexpr int EPL = (T * D + kWave - 1) / kWave;
     constexpr int NSRC0 = 1 + WQ;                     // sources before the earlier chain letters
     constexpr int LB = ilog2(D);
     using LY = BwdLds<D, N, WQ, T, VG>;
     static_assert(T <= 16 && T % 2 == 0, "the time-batched leaf products take up to 16 segments per matrix instruction");
+    static_assert(T * D <= kWave * kWavesPerBlock, "one element of the increment tile per thread");
+    static_assert(G::WAVES % kWavesPerBlock == 0, "the wavefronts of a workgroup walk the same row: they share the table of "
+                                                  "increments and meet at its barriers");
     extern __shared__ v4f bwd_smem[];
 
     const int lane = threadIdx.x % kWave;
     const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // the same in every lane: scalar registers
     const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + wib;
-    if (wave >= B * C * (wl.win ? wl.K : 1) * G::WAVES) return;
-    float* const lds = (float*)bwd_smem + wib * LY::PER_WAVE;            // wave-private
-    float (*Ec)[D][NC] = (float (*)[D][NC])(lds + LY::OFF_EC);          // Ec[segment][letter][t] = dX^{(letter)} / (t + 1)
+    if (wave >= B * C * (wl.win ? wl.K : 1) * G::WAVES) return;          // whole workgroups: the row count is a multiple
+    float* const lds = (float*)bwd_smem + LY::EC_FLOATS + wib * LY::PER_WAVE;   // wave-private
+    float (*Ec)[D][NC] = (float (*)[D][NC])bwd_smem;                    // Ec[segment][letter][t] = dX^{(letter)} / (t + 1), shared
     float* gt = lds + LY::OFF_GT;
     float* Vb = lds + LY::OFF_VB;
     float* HA = lds + LY::OFF_HA;                                       // [NSV][T][SP]
@@ -763,27 +767,21 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trun
             }
         }
 
-    float dxn[EPL];
+    // the workgroup loads a tile of increments together: thread e takes (segment e / D, letter e % D)
+    float dxn;
+    const int tile_e = (int)threadIdx.x < T * D ? (int)threadIdx.x : T * D - 1;
     auto fetch = [&](int64_t j0) {
-#pragma unroll
-        for (int q = 0; q < EPL; ++q) {
-            const int e = (lane + q * kWave) < T * D ? lane + q * kWave : T * D - 1;
-            int64_t jj = j0 + e / D;
-            const bool ok = jj >= 0 && jj < L;
-            jj = jj < 0 ? 0 : (jj < L ? jj : L - 1);
-            const int i = e % D;
-            const float x1 = X[(jj + 1) * D + i], x0 = X[jj * D + i];
-            dxn[q] = ok ? x1 - x0 : 0.0f;
-        }
+        int64_t jj = j0 + tile_e / D;
+        const bool ok = jj >= 0 && jj < L;
+        jj = jj < 0 ? 0 : (jj < L ? jj : L - 1);
+        const int i = tile_e % D;
+        const float x1 = X[(jj + 1) * D + i], x0 = X[jj * D + i];
+        dxn = ok ? x1 - x0 : 0.0f;
     };
     auto stage = [&]() {
+        if ((int)threadIdx.x < T * D) {
 #pragma unroll
-        for (int q = 0; q < EPL; ++q) {
-            const int e = lane + q * kWave;
-            if (e < T * D) {
-#pragma unroll
-                for (int t = 0; t < N; ++t) Ec[e / D][e % D][t] = dxn[q] * inv1(t);
-            }
+            for (int t = 0; t < N; ++t) Ec[tile_e / D][tile_e % D][t] = dxn * inv1(t);
         }
     };
     const v4f zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -840,15 +838,19 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trun
     };
 
     struct Sources { float last, slice, first; };     // gradient sources of a segment: letter[K - 1], slice letter, letter[0]
+    // A+ of parent p goes to slot (p % 4) * 16 + p / 4 of its row: the product over parents after the segment loop
+    // reads parents 4 ks + lane / 16, ks = 0..15, which are then 16 consecutive floats.  (All lanes read their
+    // gbar[1] from the row before any of them writes into it.)
+    const int aplus_slot = (lane & 3) * 16 + (lane >> 2);
     auto adjoint = [&](int row, const Saved& sv, Sources& src) {
         // 3a. leaves: gbar[1] of the slice word was computed for the whole tile before the segment loop; its slot
         // takes A+_{N-1}[1] of the slice word for the product over parents after the loop
         v4f g1[WQ];
 #pragma unroll
         for (int v = 0; v < NSV; ++v) {
-            float* slot = HA + (v * T + row) * SP + lane;
-            g1[v / 4][v % 4] = *slot;
-            *slot = sv.Gp[v / 4][v % 4];
+            float* slots = HA + (v * T + row) * SP;
+            g1[v / 4][v % 4] = slots[lane];
+            slots[aplus_slot] = sv.Gp[v / 4][v % 4];
         }
         // 3b. slice words
         float gcs[WQ], M1[4], M2[4];
@@ -948,9 +950,9 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trun
     for (int e = lane; e < T * D; e += kWave) gt[e] = 0.0f;
     fetch((ntiles - 1) * T);
     for (int64_t n = ntiles - 1; n >= 0; --n) {
-        wave_lds_fence();
+        __syncthreads();                               // every wavefront is done with the table of the tile before
         stage();
-        wave_lds_fence();
+        __syncthreads();
         fetch((n - 1) * T);                            // n = 0: out of range, zeros
         {
             // gbar[1](slice word p, segment s) = sum_j dX_s^{(j)} G[p][j] for the 16 segments of the tile:
@@ -976,7 +978,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trun
         }
         {
             static_assert(T % 2 == 0, "the segment loop is unrolled by two");
-            if constexpr (T == 16) {
+            if constexpr (T == 16 && !LY::TWO_WORKGROUPS) {
                 // a lone wavefront per SIMD: recon runs one segment ahead of adjoint so that their chains overlap
                 Saved SA, SB;
                 Sources unused;
@@ -1032,12 +1034,16 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (T < 16 ? 2 : 1)) void trun
             const int col = (lane & 15) % T;
             v4f acc[4] = {zero4, zero4, zero4, zero4};
 #pragma unroll
-            for (int v = 0; v < NSV; ++v)
+            for (int v = 0; v < NSV; ++v) {
+                const v4f* bv = (const v4f*)(HA + (v * T + col) * SP + 16 * (lane / 16));
 #pragma unroll
-                for (int ks = 0; ks < 16; ++ks) {
-                    const float bv = HA[(v * T + col) * SP + 4 * ks + lane / 16];
-                    acc[ks % 4] = __builtin_amdgcn_mfma_f32_16x16x4f32(Gt[v][ks], bv, acc[ks % 4], 0, 0, 0);
+                for (int kq = 0; kq < 4; ++kq) {
+                    const v4f b4 = bv[kq];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        acc[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(Gt[v][4 * kq + r], b4[r], acc[r], 0, 0, 0);
                 }
+            }
             const v4f sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
             if (4 * (lane / 16) < D && (T == 16 || (lane & 15) < T)) {
                 v4f* dst = (v4f*)(gt + col * D + 4 * (lane / 16));
@@ -2208,13 +2214,15 @@ hipError_t trunc_backward(int d, int depth, const float* path, const float* coef
         return small ? launch_trunc_node_bwd<8, 5, 4>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream)
                      : launch_trunc_node_bwd<8, 5, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
     }
-    // d = 16: a tile of 16 segments fills the 16 columns of the time-batched matrix products but its 139 KB of LDS leave
-    // room for one workgroup per compute unit, and a lone wavefront issues vector instructions at half the rate of its
-    // SIMD.  Tiles of 12 segments (gradient sources summed every 4 segments: 77 KB) let two workgroups share a compute
-    // unit at three quarters of the columns: taken when the launch has two wavefronts per SIMD to offer.  (Tiles of 8
-    // segments, half the columns, were measured slower or equal at every batch size; kept selectable.)
+    // d = 16: a tile of 16 segments fills the 16 columns of the time-batched matrix products.  With the gradient sources
+    // parked in LDS for the whole tile a workgroup takes 126 KB, one per compute unit, and a lone wavefront issues vector
+    // instructions at half the rate of its SIMD: that form (segments software-pipelined) is for launches that have no
+    // second wavefront per SIMD to offer anyway.  With the sources of 4 segments in registers, summed by cross-lane moves,
+    // the workgroup needs 78 KB and two share a compute unit: taken from 2,048 wavefronts on.  tile = 16 / 4 force the
+    // two forms; 12 and 8 are shorter tiles (three quarters, half of the columns), measured slower, kept selectable.
     if (d == 16 && depth == 4) {
-        const int t = tile == 8 || tile == 12 || tile == 16 ? tile : (B * C * 16 >= 2048 ? 12 : 16);
+        const int t = tile == 4 || tile == 8 || tile == 12 || tile == 16 ? tile : (B * C * 16 >= 2048 ? 4 : 16);
+        if (t == 4) return launch_trunc_mfma_bwd<16, 4, 1, 16, 4>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
         if (t == 8) return launch_trunc_mfma_bwd<16, 4, 1, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
         if (t == 12) return launch_trunc_mfma_bwd<16, 4, 1, 12, 4>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
         return launch_trunc_mfma_bwd<16, 4, 1, 16>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);

@@ -90,7 +90,7 @@ struct WordSet {
         int lanes_levels = 0;          // levels below the lane's word: 0 auto, 1, 2
         int logsig_gather = 0;         // 1: two-kernel form of the log-signature adjoint
         int ckpt_chunks = 0;           // time chunks of the checkpointed forward / backward: 0 launcher's rule, 1 off, 2..4
-        int bwd_tile = 0;              // segments per LDS tile of the d = 16 backward kernel: 0 default, 8, 16
+        int bwd_tile = 0;              // LDS tile shape of the d = 8 (4, 8) and d = 16 (4, 8, 12, 16) backward kernels; 0: launcher's rule
         int jit_fwd_tile = 0;          // segments per LDS tile of the specialised forward kernels: 0 default, 1..32
         int jit_wg_waves = 4;          // wavefronts (work units) per workgroup of the run-time specialised kernels, 1..4;
                                        // 8 is accepted for inspecting the generated code on the host only: jit_load

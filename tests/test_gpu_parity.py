@@ -160,6 +160,30 @@ def test_checkpointed_forward_and_backward(d, depth, B, L, chunks):
     assert gerr.max() <= BWD_TOL, f"checkpointed backward: {gerr.max():.3e}"
 
 
+# Every tile shape of the d = 16 and d = 8 backward kernels, forced on batches far too small to take them by themselves:
+# tiles that do not divide the number of segments, a single ragged tile, with and without time chunks
+@pytest.mark.parametrize("d,depth,tile", [(16, 4, 4), (16, 4, 8), (16, 4, 12), (16, 4, 16), (8, 5, 4), (8, 5, 8)])
+@pytest.mark.parametrize("B,L,chunks", [(2, 77, 0), (1, 9, 0), (3, 150, 2)])
+def test_backward_tile_shapes(d, depth, tile, B, L, chunks):
+    import torch
+    ws, W = build_both("truncated", d, depth=depth)
+    ws.set_option("bwd_tile", tile)
+    X = make_path("iid", 2900 + L + tile, B, L, d)
+    G = make_grad_coeffs(3000 + L + tile, B, ws.size)
+    gref = O.backward_dense(X, depth, G.astype(np.float64))
+    xp, grad = torch.from_numpy(X).cuda(), torch.from_numpy(G).cuda()
+    if chunks:
+        ws.set_option("ckpt_chunks", chunks)
+        coeffs, ck = S.sig_forward_checkpointed(ws, xp)
+        gp = S.sig_backward_checkpointed(ws, xp, coeffs, grad, ck)
+    else:
+        coeffs = S.sig_forward(ws, xp)
+        gp = S.sig_backward(ws, xp, coeffs, grad)
+    torch.cuda.synchronize()
+    gerr = O.grad_errors(gp.cpu().numpy(), gref)
+    assert gerr.max() <= BWD_TOL, f"d={d} tile={tile} B={B} L={L} chunks={chunks}: {gerr.max():.3e}"
+
+
 @pytest.mark.parametrize("d,depth,B,L", [(8, 5, 2, 300), (16, 4, 2, 400), (4, 6, 3, 257)])
 def test_reconstruction_returns_to_the_empty_signature(d, depth, B, L):
     """Stepping the terminal signature back through all segments (Proposition 4.6) must end at the signature of the
