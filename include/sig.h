@@ -114,7 +114,7 @@ const int64_t* sig_wordset_user_index(const sig_wordset* ws);   /* host [n_user]
  *   "lanes_levels"  [SIG_LANES_LEVELS]   levels below the lane's word: 0 auto, 1, 2
  *   "logsig_gather" [SIG_LOGSIG_GATHER]  1: two-kernel form of sig_logsig_backward
  *   "jit_wg_waves"  [SIG_JIT_WG_WAVES]   wavefronts per workgroup of the specialised kernels, 1..4 (default 4)
- *   "bwd_tile"      [SIG_BWD_TILE]       LDS tile of the backward kernels, 0 = launcher's rule.  d = 8: 4 or 8 segments;
+ *   "bwd_tile"      [SIG_BWD_TILE]       LDS tile of the backward kernels, 0 = launcher's rule.  d = 8: 4, 8 or 16 segments;
  *                                        d = 16: 8, 12 or 16 segments, or 4 = 16 segments with the gradient sources
  *                                        summed every 4 (the form that fits two workgroups on a compute unit)
  *   "ckpt_chunks"   [SIG_CKPT_CHUNKS]    time chunks of the checkpointed calls: 0 launcher's rule, 1 off, 2..4 forced

@@ -585,7 +585,7 @@ __device__ __forceinline__ void tile_reduce(const float* V, float* gt, int D, in
     }
 }
 
-// Values of other lanes without LDS traffic: DPP forms inside a row of 16 lanes (CTRL: 0x128 lane + 8 mod 16, 0x140 lane
+// Values of other lanes without LDS traffic: DPP forms inside a row of 16 lanes (CTRL: 0x120 + n lane + n mod 16, 0x140 lane
 // 15 - l, 0x141 lane 7 - l of the half row, 0xB1 / 0x4E lanes l ^ 1 / l ^ 2 of the quad), the swizzle network for an
 // exclusive-or of the lane number below 32.  Every lane must be active.
 template <int CTRL>
@@ -599,6 +599,21 @@ __device__ __forceinline__ float swizzle_xor(float x)
     static_assert(XOR_MASK > 0 && XOR_MASK < 32, "the swizzle network works on groups of 32 lanes");
     return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(x), (XOR_MASK << 10) | 0x1f));
 }
+// The same exchange across rows with the swap instructions of gfx950 (vector ALU, no LDS round trip, no selects):
+// v_permlane32_swap exchanges the upper 32 lanes of its first operand with the lower 32 of its second, v_permlane16_swap
+// the odd rows of 16 lanes of the first with the even rows of the second.  After the swap the two registers hold, in
+// every lane, this lane's and its partner's (lane ^ 32, lane ^ 16) value of the operand the lane keeps: `a` in the lower
+// half / the even rows, `b` in the upper half / the odd rows.
+__device__ __forceinline__ float fold_swap32(float a, float b)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float fold_swap16(float a, float b)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 // Four values per lane (v[s] belongs to segment s) summed over pairs of partner lanes, twice, each time keeping half of
 // the segments: the lane ends up with the sum over four lanes for segment 2 hi + lo.  X1 / X2 fetch the partner's value;
 // the partner of the first exchange differs in `hi`, the partner of the second agrees in `hi` and differs in `lo`.
@@ -609,6 +624,20 @@ __device__ __forceinline__ float fold_four_segments(const float (&v)[4], bool hi
     const float s0 = hi ? v[0] : v[2], s1 = hi ? v[1] : v[3];
     const float a0 = k0 + x1(s0), a1 = k1 + x1(s1);
     return (lo ? a1 : a0) + x2(lo ? a0 : a1);
+}
+
+// One round of the same exchange on an array: v[0 .. N/2) <- the half of v this lane keeps (the upper one where `upper`)
+// plus the other half of the partner lane, which keeps the opposite one.  Repeated with partners that agree in the bits
+// used so far, the N values of every lane end up spread over the lanes, each summed over the lanes visited.
+template <int N, class X>
+__device__ __forceinline__ void fold_halves(float* v, bool upper, X partner)
+{
+#pragma unroll
+    for (int i = 0; i < N / 2; ++i) {
+        const float keep = upper ? v[i + N / 2] : v[i];
+        const float send = upper ? v[i] : v[i + N / 2];
+        v[i] = keep + partner(send);
+    }
 }
 
 // chain letter k (0-based) of K: bit field of the lane number, or empty when the letter is the same in the whole wavefront
@@ -915,15 +944,13 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (BwdLds<D, N, WQ, T, VG>::T
     // with, so the four segments cost little more than one.
     auto reduce_registers = [&](int first, const float (&last)[4], const float (&slice)[4], const float (&chain0)[4]) {
         float* gtv = gt + first * D;
-        auto x32 = [](float x) { return __shfl_xor(x, 32); };
-        auto x16 = [](float x) { return swizzle_xor<16>(x); };
         // letter[1]: classes of the four lanes that differ in bits 4, 5; every lane ends with one (segment, letter)
-        const float r0 = fold_four_segments(last, (lane & 32) != 0, (lane & 16) != 0, x32, x16);
+        const float r0 = fold_swap16(fold_swap32(last[0], last[2]), fold_swap32(last[1], last[3]));
         gtv[(lane >> 4) * D + letter[K - 1]] += r0;
-        // slice letter: classes of sixteen lanes that differ in bits 2..5
-        float r1 = fold_four_segments(slice, (lane & 32) != 0, (lane & 16) != 0, x32, x16);
+        // slice letter: classes of sixteen lanes that differ in bits 2..5 (inside a row: lanes l, l + 4, l + 8, l + 12)
+        float r1 = fold_swap16(fold_swap32(slice[0], slice[2]), fold_swap32(slice[1], slice[3]));
         r1 += dpp_lane<0x128>(r1);
-        r1 += swizzle_xor<4>(r1);
+        r1 += dpp_lane<0x124>(r1);
         if ((lane & 12) == 0) gtv[(lane >> 4) * D + 4 * g0 + (lane & 3)] += r1;
         // letter[0]: classes of the sixteen lanes of a row
         float r2 = fold_four_segments(chain0, (lane & 8) != 0, (lane & 4) != 0, [](float x) { return dpp_lane<0x140>(x); },
@@ -932,6 +959,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (BwdLds<D, N, WQ, T, VG>::T
         r2 += dpp_lane<0x4E>(r2);
         if ((lane & 3) == 0) gtv[((lane >> 2) & 3) * D + letter[0]] += r2;
     };
+
     // the sources of the VG segments from `first` on, summed over the lanes into the gradient tile
     auto reduce_sources = [&](int first) {
         wave_lds_fence();
@@ -945,6 +973,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (BwdLds<D, N, WQ, T, VG>::T
         chain_tile_reduce<D, K, VG, 0, false>(Vb + NSRC0 * VG * kWave, gtv, lane, letter);
         wave_lds_fence();
     };
+
 
     const int64_t ntiles = (L + T - 1) / T;
     for (int e = lane; e < T * D; e += kWave) gt[e] = 0.0f;
@@ -1622,15 +1651,21 @@ struct NodeLds {
     static constexpr int K = N - 2;
     static constexpr int NC = (N + 3) / 4 * 4;
     static constexpr int NSRC = D + K;                 // one source of gradient values per letter, one per chain letter
+    // d = 8, depth 5: the sources of two segments stay in registers and are summed over lanes with cross-lane moves
+    // (the LDS slots and their row sums cost a fifth of the kernel); other shapes park them in LDS (VB)
+    static constexpr bool SOURCES_IN_REGISTERS = D == 8 && N == 5;
     static constexpr int OFF_GT = T * D * NC;
-    static constexpr int OFF_VB = OFF_GT + T * D;
-    static constexpr int PER_WAVE = OFF_VB + NSRC * T * kWave;
+    // gradient tile [T][D]; with the sources in registers three of them (one per kind of source, stored, not
+    // accumulated) and T values for the chain letter that is the same in the whole wavefront
+    static constexpr int OFF_VB = OFF_GT + (SOURCES_IN_REGISTERS ? 3 * T * D + (T + 3) / 4 * 4 : T * D);
+    static constexpr int PER_WAVE = OFF_VB + (SOURCES_IN_REGISTERS ? 0 : NSRC * T * kWave);
     static_assert(OFF_GT % 4 == 0 && OFF_VB % 4 == 0 && PER_WAVE % 4 == 0, "16-byte alignment of the LDS regions");
     static constexpr size_t BYTES = (size_t)kWavesPerBlock * PER_WAVE * sizeof(float);
 };
 
+// (the shortest tile is for launches with two wavefronts per SIMD: its registers are held to half a SIMD's)
 template <int D, int N, int T>
-__global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
+__global__ __launch_bounds__(kWave * kWavesPerBlock, (D == 8 ? 2 : 1)) void trunc_node_bwd_kernel(
     const float* __restrict__ path, const float* __restrict__ coeffs, const float* __restrict__ grad,
     const float* __restrict__ coeffs_last, const float* __restrict__ grad_last, int64_t B, int64_t P, int64_t C, int64_t Lc,
     WindowList wl, float* gdx, float* resid)
@@ -1638,11 +1673,12 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
     static_assert((D & (D - 1)) == 0, "the gradient reduction takes letters as bit fields of the lane number");
     constexpr int K = N - 2;
     constexpr int WAVES = ipow(D, K) / kWave;          // wavefronts per row
-    static_assert(WAVES * kWave == ipow(D, K) && D * T <= kWave, "whole wavefronts; one lane per (letter, segment)");
+    using LY = NodeLds<D, N, T>;
+    static_assert(WAVES * kWave == ipow(D, K) && (LY::SOURCES_IN_REGISTERS || D * T <= kWave),
+                  "whole wavefronts; one lane per (letter, segment) where the sources are summed from LDS");
     constexpr int NC = (N + 3) / 4 * 4;
     constexpr int EPL = (T * D + kWave - 1) / kWave;
     constexpr int LB = ilog2(D);
-    using LY = NodeLds<D, N, T>;
     extern __shared__ v4f bwd_smem[];
 
     const int lane = threadIdx.x % kWave;
@@ -1735,7 +1771,8 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
             in.eu[j][1] = Ec[row_t][j][1];
         }
     };
-    auto step = [&](int row_t, const In& in) {
+    // yo[D], co[K]: where the gradient sources of the segment go when they stay in registers
+    auto step = [&](int row_t, const In& in, float* yo, float* co) {
         const float (&ec)[K][NC] = in.ec;
         const float (&eu)[D][2] = in.eu;
         // 1. reconstruction with -dX, 2. accumulators with +dX from the reconstructed signature
@@ -1794,10 +1831,63 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
                 gb[k - 1][t + 1] = fmaf(ec[k - 1][t], q, gb[k - 1][t + 1]);
             }
             Ac[k - 1] = asum;
-            vb[(D + k - 1) * T * kWave] = gc;                                  // letter[k - 1]
+            if constexpr (LY::SOURCES_IN_REGISTERS) co[k - 1] = gc;
+            else vb[(D + k - 1) * T * kWave] = gc;                             // letter[k - 1]
         }
+        if constexpr (LY::SOURCES_IN_REGISTERS) {
 #pragma unroll
-        for (int j = 0; j < D; ++j) vb[j * T * kWave] = y[j];                  // letter j, every lane
+            for (int j = 0; j < D; ++j) yo[j] = y[j];
+        } else {
+#pragma unroll
+            for (int j = 0; j < D; ++j) vb[j * T * kWave] = y[j];              // letter j, every lane
+        }
+    };
+    // Sums over lanes for the two segments `first`, `first` + 1 (d = 8, depth 5: letter[2] = lane bits 0..2, letter[1] =
+    // bits 3..5, letter[0] the same in the whole wavefront).  yv[8 s + j]: contribution of the lane to letter j in
+    // segment s (every lane, every letter); cv[3 s + k]: contribution to letter[k].  Exchange rounds that halve the
+    // number of values come first (across the halves and rows of the wavefront: swap instructions), plain butterfly
+    // sums last; the partners used (lane ^ 32, ^ 16, ^ 8, ^ 7, ^ 3, ^ 1) generate every lane.  Results are stored, one
+    // tile per kind of source: every (segment, letter) entry of a tile has exactly one writer per tile.
+    float* const gy = gt;
+    float* const g1 = gt + T * D;
+    float* const g2 = gt + 2 * T * D;
+    float* const gc0 = gt + 3 * T * D;
+    auto reduce_pair = [&](int first, const float* yv, const float* cv) {
+        auto r8 = [](float x) { return dpp_lane<0x128>(x); };      // lane ^ 8
+        auto m7 = [](float x) { return dpp_lane<0x141>(x); };      // lane ^ 7
+        auto q3 = [](float x) { return dpp_lane<0x1B>(x); };       // lane ^ 3
+        auto q1 = [](float x) { return dpp_lane<0xB1>(x); };       // lane ^ 1
+        // letters below the lane's word: lane bit 5 ends with the segment, bits 4, 3, 2 with the letter
+        float a[D / 2];
+#pragma unroll
+        for (int i = 0; i < D / 2; ++i)
+            a[i] = fold_swap16(fold_swap32(yv[i], yv[D + i]), fold_swap32(yv[i + D / 2], yv[D + i + D / 2]));
+        fold_halves<4>(a, (lane & 8) != 0, r8);
+        fold_halves<2>(a, (lane & 4) != 0, m7);
+        float ry = a[0];
+        ry += q3(ry);
+        ry += q1(ry);
+        if ((lane & 3) == 0) gy[(first + (lane >> 5)) * D + ((lane >> 2) & 7)] = ry;
+        // letter[0]: all 64 lanes
+        float r0 = fold_swap32(cv[0], cv[K]);
+        r0 = fold_swap16(r0, r0);
+        r0 += r8(r0);
+        r0 += m7(r0);
+        r0 += q3(r0);
+        r0 += q1(r0);
+        if ((lane & 31) == 0) gc0[first + (lane >> 5)] = r0;
+        // letter[1]: the eight lanes that differ in bits 0..2
+        float c1[2] = {cv[1], cv[K + 1]};
+        fold_halves<2>(c1, (lane & 4) != 0, m7);
+        float r1 = c1[0];
+        r1 += q3(r1);
+        r1 += q1(r1);
+        if ((lane & 3) == 0) g1[(first + ((lane >> 2) & 1)) * D + letter[1]] = r1;
+        // letter[2]: the eight lanes that differ in bits 3..5
+        float r2 = fold_swap32(cv[2], cv[K + 2]);
+        r2 = fold_swap16(r2, r2);
+        r2 += r8(r2);
+        if ((lane & 0x18) == 0) g2[(first + (lane >> 5)) * D + letter[2]] = r2;
     };
 
     const int64_t ntiles = (L + T - 1) / T;
@@ -1808,32 +1898,56 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void trunc_node_bwd_kernel(
         stage();
         wave_lds_fence();
         fetch((n - 1) * T);                            // n = 0: out of range, zeros
-        {
+        if constexpr (LY::SOURCES_IN_REGISTERS) {
+            static_assert(K == 3 && T % 2 == 0 && T >= 4, "reduce_pair is written for three chain letters");
+            In ia, ib;
+            float yv[2 * D], cv[2 * K];
+            load_in(T - 1, ia);
+#pragma unroll 1
+            for (int tt = T - 1; tt >= 3; tt -= 2) {
+                load_in(tt - 1, ib);
+                step(tt, ia, yv + D, cv + K);
+                load_in(tt - 2, ia);
+                step(tt - 1, ib, yv, cv);
+                reduce_pair(tt - 1, yv, cv);
+            }
+            load_in(0, ib);
+            step(1, ia, yv + D, cv + K);
+            step(0, ib, yv, cv);
+            reduce_pair(0, yv, cv);
+            wave_lds_fence();
+        } else {
             static_assert(T % 2 == 0 && T >= 4, "the segment loop is unrolled by two");
             In ia, ib;
             load_in(T - 1, ia);
 #pragma unroll 1
             for (int tt = T - 1; tt >= 3; tt -= 2) {
                 load_in(tt - 1, ib);
-                step(tt, ia);
+                step(tt, ia, nullptr, nullptr);
                 load_in(tt - 2, ia);
-                step(tt - 1, ib);
+                step(tt - 1, ib, nullptr, nullptr);
             }
             load_in(0, ib);
-            step(1, ia);
-            step(0, ib);
+            step(1, ia, nullptr, nullptr);
+            step(0, ib, nullptr, nullptr);
+            wave_lds_fence();
+            tile_reduce_uniform<D, T>(Vb, gt, D, lane, 0);     // the only writer of gt so far: plain read-modify-write
+            wave_lds_fence();
+            tile_reduce<(1 << LB) - 1, T>(Vb + (D + K - 1) * T * kWave, gt, D, lane, letter[K - 1]);
+            chain_tile_reduce<D, K, T, 0>(Vb + D * T * kWave, gt, lane, letter);
+            wave_lds_fence();
         }
-        wave_lds_fence();
-        tile_reduce_uniform<D, T>(Vb, gt, D, lane, 0);     // the only writer of gt so far: plain read-modify-write
-        wave_lds_fence();
-        tile_reduce<(1 << LB) - 1, T>(Vb + (D + K - 1) * T * kWave, gt, D, lane, letter[K - 1]);
-        chain_tile_reduce<D, K, T, 0>(Vb + D * T * kWave, gt, lane, letter);
-        wave_lds_fence();
         // flush: (segment, letter) is contiguous in gdx
         for (int e = lane; e < T * D; e += kWave) {
             const int64_t sg = n * T + e / D;
-            if (sg < L) unsafeAtomicAdd(gdx + (b * (P - 1) + seg0 + n * T) * D + e, gt[e]);
-            gt[e] = 0.0f;
+            float v;
+            if constexpr (LY::SOURCES_IN_REGISTERS) {
+                v = (gy[e] + g1[e]) + (g2[e] + (e % D == letter[0] ? gc0[e / D] : 0.0f));
+            } else {
+                v = gt[e];
+                gt[e] = 0.0f;
+            }
+            if (sg < L) unsafeAtomicAdd(gdx + (b * (P - 1) + seg0 + n * T) * D + e, v);
         }
     }
     if (resid != nullptr && seg0 == 0) {
@@ -2207,12 +2321,12 @@ hipError_t trunc_backward(int d, int depth, const float* path, const float* coef
     if ((coeffs_last == nullptr) != (grad_last == nullptr)) return hipErrorInvalidValue;
     if (d == 4 && depth == 6)
         return launch_trunc_node_bwd<4, 6>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
-    // d = 8: tiles of 4 segments keep a workgroup's LDS at 50 KB, so that two (or three) workgroups share a compute unit:
-    // taken when the launch has the wavefronts for it
+    // d = 8: with the gradient sources in registers a wavefront needs a few KB of LDS whatever the tile; the tile length
+    // only sets how often increments are staged and gradients flushed
     if (d == 8 && depth == 5) {
-        const bool small = tile == 4 || (tile == 0 && B * C * 8 >= 2048);
-        return small ? launch_trunc_node_bwd<8, 5, 4>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream)
-                     : launch_trunc_node_bwd<8, 5, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
+        if (tile == 4) return launch_trunc_node_bwd<8, 5, 4>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
+        if (tile == 16) return launch_trunc_node_bwd<8, 5, 16>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
+        return launch_trunc_node_bwd<8, 5, 8>(path, coeffs, grad_coeffs, coeffs_last, grad_last, B, P, C, Lc, gdx, resid, stream);
     }
     // d = 16: a tile of 16 segments fills the 16 columns of the time-batched matrix products.  With the gradient sources
     // parked in LDS for the whole tile a workgroup takes 126 KB, one per compute unit, and a lone wavefront issues vector

@@ -162,7 +162,7 @@ def test_checkpointed_forward_and_backward(d, depth, B, L, chunks):
 
 # Every tile shape of the d = 16 and d = 8 backward kernels, forced on batches far too small to take them by themselves:
 # tiles that do not divide the number of segments, a single ragged tile, with and without time chunks
-@pytest.mark.parametrize("d,depth,tile", [(16, 4, 4), (16, 4, 8), (16, 4, 12), (16, 4, 16), (8, 5, 4), (8, 5, 8)])
+@pytest.mark.parametrize("d,depth,tile", [(16, 4, 4), (16, 4, 8), (16, 4, 12), (16, 4, 16), (8, 5, 4), (8, 5, 8), (8, 5, 16)])
 @pytest.mark.parametrize("B,L,chunks", [(2, 77, 0), (1, 9, 0), (3, 150, 2)])
 def test_backward_tile_shapes(d, depth, tile, B, L, chunks):
     import torch
