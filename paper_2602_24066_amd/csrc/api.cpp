@@ -696,8 +696,10 @@ size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_
     if (use_trunc_backward(w, B)) {
         const BwdShape ch = trunc_backward_shape(w, B, n_points);
         if (ch.C > 1 && !ch.fused) n += 4 * chunk_array_bytes(w, B, ch.C);   // chunk signatures, prefixes, suffixes, adjoints
-    } else if (jit_enabled(w)) {                                    // + transposed increments
-        n += jit_dxt_bytes(w, B, n_points, 1);
+    } else if (jit_enabled(w)) {
+        // the specialised kernels keep the increment gradients in the (padded) layout of their transposed increments
+        const size_t t = jit_dxt_bytes(w, B, n_points, 1);
+        n = std::max(n, t) + t;
     }
     return n;
 }
@@ -873,7 +875,9 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
     // the fused form copies the gradient row with 16-byte loads; rows that are not aligned so take the kernel with
     // four wavefronts per path, which reads word by word
     if (ch.fused && (((uintptr_t)coeffs | (uintptr_t)grad_coeffs) & 15) != 0) ch = BwdShape{false, false, 1, n_points - 1};
-    if (!ch.tails) {                     // the one-wavefront-per-row kernel stores every entry itself
+    // word sets that may run through the straight-line specialised kernels clear their (larger) array further down
+    const bool maybe_jit = !trunc && !use_lanes(w, B) && jit_enabled(w);
+    if (!ch.tails && !maybe_jit) {       // the one-wavefront-per-row kernel stores every entry itself
         e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
         if (e != hipSuccess) return hip_fail(e);
     }
@@ -936,9 +940,13 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
     sig::JitKernel* jk = ensure_jit(w, 1, B, how, &jp);
     if (!jk && g_not_ready) return SIG_ENOTREADY;
     if (jk) {
-        const size_t gdx_bytes = ((size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float) + 255) & ~(size_t)255;
+        // increment gradients and increments in the same layout [group][padded segment][letter][lane], one after the other
+        const size_t t_bytes = jit_dxt_bytes(w, B, n_points, 1);
+        const size_t gdx_bytes = std::max(gdx_bytes_of(w, B, n_points), t_bytes);
         float* dxT = (float*)((unsigned char*)workspace + gdx_bytes);
         const int64_t Lpad = jit_lpad(w, n_points, 1);
+        e = sig::fill_zero(gdx, (int64_t)(t_bytes / sizeof(float)), st);
+        if (e != hipSuccess) return hip_fail(e);
         e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, st);
         if (e != hipSuccess) return hip_fail(e);
         hipEvent_t* pe = g_prof.next(1);
@@ -947,8 +955,12 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
                                 gdx, st);
         if (pe) (void)hipEventRecord(pe[1], st);
         if (e != hipSuccess) return hip_fail(e);
-        e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
+        e = sig::grad_points_transposed(gdx, B, n_points, w.d, Lpad, grad_path, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
+    }
+    if (maybe_jit) {                     // no specialised kernel after all: the table-driven one takes gdx [B][L][d]
+        e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
+        if (e != hipSuccess) return hip_fail(e);
     }
     const int v = pick_variant(w, 1, B);
     const sig::Plan& p = w.plans[1][(size_t)v];

@@ -50,7 +50,6 @@ void emit_prelude(std::ostringstream& o, int D, int T, int NW, bool backward)
     o << "#define D " << D << "\n#define T " << T << "\n#define NW " << NW << "\n";
     o << "#define TILE_F4 (T * D * 16)\n";                         // float4 per tile (T * D rows of 64 floats)
     o << "#define EPT ((TILE_F4 + NW * 64 - 1) / (NW * 64))\n";    // float4 per thread
-    o << "#define LP 65\n";
     o << R"SRC(
 typedef float f4 __attribute__((ext_vector_type(4)));
 // The increments arrive differenced and transposed (increments_transposed_kernel): for the 64 paths of the
@@ -93,26 +92,20 @@ __device__ __attribute__((noinline)) void idle_unit(const float* __restrict__ dx
 )SRC";
     } else {
         o << R"SRC(
-// Gradient tiles: every wavefront (unit) has its own gt[(tt * D + i) * LP + lane] in LDS and overwrites all of it
+// Gradient tiles: every wavefront (unit) has its own gt[(tt * D + i) * 64 + lane] in LDS and overwrites all of it
 // in every tile with plain stores (LDS floating-point atomics turned out to be far slower than the arithmetic).
-// At the end of a tile the NW tiles are added up and added to gdx [B][L][D] (zeroed by the caller) with one path per
-// pass, so that a wavefront's floating-point atomics cover contiguous (segment, letter) runs; all workgroup columns
+// At the end of a tile the NW tiles are added up and added to the increment gradients, which the specialised kernels
+// keep in the layout of the increments themselves, gdx[group][segment][letter][lane] (zeroed by the caller): a row of
+// a tile is 64 consecutive floats, one floating-point atomic instruction of full cache lines; all workgroup columns
 // (blockIdx.x) add into the same array.
-#define GT_F (T * D * LP)
-__device__ __attribute__((noinline)) void grad_flush(const float* gt_all, float* gdx, long L, long j0, long b0, long B, int lane,
-                                                     int wib)
+#define GT_F (T * D * 64)
+__device__ __attribute__((noinline)) void grad_flush(const float* gt_all, float* gdx_tile, int lane, int wib)
 {
-    for (int bb = wib; bb < 64; bb += NW) {
-        if (b0 + bb < B) {
-            float* dst = gdx + ((b0 + bb) * L + j0) * D;
-            for (int e = lane; e < T * D; e += 64)
-                if (j0 + e / D < L) {
-                    float v = 0.0f;
+    for (int e = wib; e < T * D; e += NW) {
+        float v = 0.0f;
 #pragma unroll
-                    for (int w = 0; w < NW; ++w) v += gt_all[w * GT_F + e * LP + bb];
-                    __hip_atomic_fetch_add(dst + e, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-        }
+        for (int w = 0; w < NW; ++w) v += gt_all[w * GT_F + e * 64 + lane];
+        __hip_atomic_fetch_add(gdx_tile + e * 64 + lane, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 __device__ __attribute__((noinline)) void idle_unit(const float* __restrict__ dxg, long ntiles, long L, float* tile, float* gt_all,
@@ -129,7 +122,7 @@ __device__ __attribute__((noinline)) void idle_unit(const float* __restrict__ dx
         __syncthreads();
         tile_fetch(dxg, n - 1, tid, r);
         __syncthreads();
-        grad_flush(gt_all, gdx, L, n * T, b0, B, lane, wib);
+        grad_flush(gt_all, gdx + n * (long)(T * D * 64), lane, wib);
     }
 }
 )SRC";
@@ -298,13 +291,13 @@ void emit_backward_unit(std::ostringstream& o, const Plan& plan, int uidx, int D
             o << "            }\n";
         }
     }
-    o << "            float* gp = gt + tt * D * LP + lane;\n";
+    o << "            float* gp = gt + tt * D * 64 + lane;\n";
     for (int i = 0; i < D_of_plan; ++i) {
-        if (uses.letters.count(i)) o << "            gp[" << i << " * LP] = g" << i << ";\n";
-        else o << "            gp[" << i << " * LP] = 0.0f;\n";
+        if (uses.letters.count(i)) o << "            gp[" << i << " * 64] = g" << i << ";\n";
+        else o << "            gp[" << i << " * 64] = 0.0f;\n";
     }
     o << "        }\n";
-    o << "        __syncthreads();\n        grad_flush(gt_all, gdx, L, n * T, b0, B, lane, wib);\n    }\n}\n\n";
+    o << "        __syncthreads();\n        grad_flush(gt_all, gdx + n * (long)(T * D * 64), lane, wib);\n    }\n}\n\n";
 }
 
 }  // namespace
@@ -340,6 +333,7 @@ std::string jit_backward_source(const WordSet& ws, const Plan& plan, int NW, int
     o << "    const int lane = threadIdx.x & 63;\n    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);\n";
     o << "    const long b0 = (long)blockIdx.y * 64;\n    const long b = b0 + lane;\n    const long bc = b < B ? b : B - 1;\n";
     o << "    const float* dxg = dxT + (long)blockIdx.y * ntiles * (T * D * 64);\n";
+    o << "    gdx += (long)blockIdx.y * ntiles * (T * D * 64);\n";
     o << "    const float* cf = coeffs + bc * nW;\n    const float* gr = grad + bc * nW;\n";
     o << "    const int unit = blockIdx.x * NW + wib;\n    switch (unit) {\n";
     for (int u = 0; u < nu; ++u)

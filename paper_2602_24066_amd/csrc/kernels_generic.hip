@@ -381,6 +381,47 @@ hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d,
     return hipGetLastError();
 }
 
+// Chain rule for the specialised kernels, whose increment gradients lie in the layout of their increments,
+// g[((grp * Lpad + j) * d + i) * 64 + lane]:  dLoss/dX_j = dLoss/d dX_j - dLoss/d dX_{j+1}  (Section 4.1), written to
+// grad_path [B][P][d].  A workgroup takes 64 paths x TS points: rows of 64 paths in, through an LDS tile
+// [(TS + 1) * d][65], runs of consecutive floats of one path out.
+__global__ void grad_points_transposed_kernel(const float* __restrict__ g, int64_t B, int64_t P, int d, int64_t Lpad, int TS,
+                                              int64_t tiles, float* __restrict__ grad_path)
+{
+    extern __shared__ float tile[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = 4;
+    const int64_t grp = blockIdx.x / tiles;
+    const int64_t j0 = (blockIdx.x % tiles) * TS;            // points j0 .. j0 + TS - 1; tile row r: segment j0 - 1 + r / d
+    const int64_t L = P - 1;
+    const int rows = (TS + 1) * d;
+    for (int r = wave; r < rows; r += nwaves) {
+        const int64_t j = j0 - 1 + r / d;
+        tile[r * 65 + lane] = (j >= 0 && j < L) ? g[((grp * Lpad + j) * d + r % d) * kWave + lane] : 0.0f;
+    }
+    __syncthreads();
+    for (int q = 0; q < 16; ++q) {
+        const int p = wave * 16 + q;
+        const int64_t b = grp * kWave + p;
+        if (b >= B) break;
+        for (int e = lane; e < TS * d; e += kWave) {
+            const int64_t pt = j0 + e / d;
+            if (pt < P) grad_path[(b * P + j0) * d + e] = tile[e * 65 + p] - tile[(e + d) * 65 + p];
+        }
+    }
+}
+
+hipError_t grad_points_transposed(const float* g, int64_t B, int64_t P, int d, int64_t Lpad, float* grad_path, hipStream_t stream)
+{
+    const int64_t groups = (B + kWave - 1) / kWave;
+    if (groups <= 0 || P <= 0 || d <= 0) return hipSuccess;
+    const int TS = std::max(1, 64 / d);
+    const size_t lds = (size_t)(TS + 1) * d * 65 * sizeof(float);
+    const int64_t tiles = (P + TS - 1) / TS;
+    if (lds > 64 * 1024 || tiles > 0x7fffffff / groups) return hipErrorInvalidValue;
+    grad_points_transposed_kernel<<<(unsigned)(tiles * groups), 256, lds, stream>>>(g, B, P, d, Lpad, TS, tiles, grad_path);
+    return hipGetLastError();
+}
+
 // Lead-lag transform (Section 8): out[b][2k] = (X_k, X_k), out[b][2k+1] = (X_k, X_{k+1}); channels 0..d-1 lag,
 // d..2d-1 lead.  out: [B, 2P - 1, 2d].
 __global__ void leadlag_kernel(const float* __restrict__ path, int64_t B, int64_t P, int d, float* __restrict__ out)
