@@ -173,6 +173,13 @@ int sig_wordset_jit_plan_get(sig_wordset* ws, int backward, int64_t B, const int
                              int64_t* fma_per_step);
 /* Copies the generated source (NUL-terminated, truncated to n bytes) and returns its full length, 0 if none. */
 size_t sig_wordset_jit_source(sig_wordset* ws, int backward, int64_t B, char* buf, size_t n);
+/* The check every run-time compiled kernel passes before it may be launched, as a function of what the loaded code
+ * object declares (host only; 1 = may be launched).  A kernel of `waves` wavefronts per workgroup is refused when
+ * waves * 64 exceeds max_threads_per_block, when its static LDS exceeds the 64 KB a kernel may use without opting in
+ * (the shape of a dispatch that the runtime rejected: 8 wavefronts with 112 KB of static LDS), or when its registers
+ * do not fit the wavefronts of a workgroup that share a SIMD (512 per lane).  A refused kernel is never dispatched; the
+ * table-driven kernels run instead. */
+int sig_jit_launch_shape_ok(int waves, int max_threads_per_block, int static_lds_bytes, int registers);
 
 /* ---- device tables ------------------------------------------------------------------------------------
  * The kernels read the launch plan from device memory the caller provides.  Allocate

@@ -106,6 +106,7 @@ def load_library():
     sig("sig_kernel_name", ctypes.c_char_p, [c_p, c_int, c_i64, c_i64])
     sig("sig_probe_fma", c_int, [c_p, c_sz, c_int, c_int, c_p])
     sig("sig_probe_issue", c_int, [c_p, c_sz, c_int, c_int, c_int, c_p])
+    sig("sig_jit_launch_shape_ok", c_int, [c_int, c_int, c_int, c_int])
     _lib = lib
     return lib
 

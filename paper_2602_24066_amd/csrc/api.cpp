@@ -1259,6 +1259,11 @@ const char* sig_wordset_kernel_name(const sig_wordset* ws, int backward)
     return backward ? "bwd_generic_kernel" : "fwd_generic_kernel";
 }
 
+int sig_jit_launch_shape_ok(int waves, int max_threads_per_block, int static_lds_bytes, int registers)
+{
+    return sig::jit_launch_shape_fits(waves, max_threads_per_block, static_lds_bytes, registers) ? 1 : 0;
+}
+
 int sig_probe_fma(void* out, size_t out_bytes, int blocks, int iters, void* stream)
 {
     if (!out || blocks < 1 || iters < 1) return SIG_EINVAL;

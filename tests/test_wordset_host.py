@@ -35,6 +35,18 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), f"{n} declared in include/*.h but not exported"
 
 
+def test_compiled_kernels_are_checked_against_their_launch_shape():
+    """What a loaded code object declares decides whether it may be dispatched (the check of jit_load)."""
+    ok = S.load_library().sig_jit_launch_shape_ok
+    assert ok(4, 256, 62 * 1024, 153) == 1              # the shapes in use: four wavefronts, static LDS under 64 KB
+    assert ok(4, 256, 64 * 1024, 256) == 1
+    assert ok(8, 512, 112128, 146) == 0                 # eight wavefronts with 112 KB of static LDS: the rejected dispatch
+    assert ok(4, 256, 64 * 1024 + 4, 100) == 0
+    assert ok(8, 256, 32 * 1024, 100) == 0              # more threads than the kernel declares
+    assert ok(8, 1024, 32 * 1024, 256) == 1 and ok(8, 1024, 32 * 1024, 257) == 0   # two wavefronts share a SIMD's 512 registers
+    assert ok(0, 256, 0, 10) == 0
+
+
 def test_strerror_and_version():
     lib = S.load_library()
     assert lib.sig_strerror(0) == b"success"
