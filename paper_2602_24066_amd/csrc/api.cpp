@@ -814,7 +814,9 @@ static int backward_checkpointed(const sig::WordSet& w, const float* path, const
 {
     if ((((uintptr_t)coeffs | (uintptr_t)grad_coeffs | (uintptr_t)ckpt) & 15) != 0) return SIG_EINVAL;
     const int64_t nW = w.size();
-    const size_t gb = gdx_bytes_of(w, B, n_points), nb = chunk_array_bytes(w, B, ch.C);
+    // workspace: increment gradients | boundary adjoints [B][C - 1][|W|] | for more than two chunks: products from the
+    // left and from the right, [B][C][|W|] each
+    const size_t gb = gdx_bytes_of(w, B, n_points), nb = chunk_array_bytes(w, B, ch.C), ab = chunk_array_bytes(w, B, ch.C - 1);
     float* gdx = (float*)workspace;
     float* Abar = (float*)((unsigned char*)workspace + gb);
     CallTimer whole(1, st);
@@ -824,12 +826,11 @@ static int backward_checkpointed(const sig::WordSet& w, const float* path, const
         // two chunks: the signature at the end of the first is the first chunk's own, what follows it the second's
         if (e == hipSuccess) e = sig::chunk_adjoint(w.d, w.depth, grad_coeffs, ckpt + nW, Abar, B, 2, true, st);
     } else {
-        float* Pfx = (float*)((unsigned char*)workspace + gb + nb);
-        float* Q = (float*)((unsigned char*)workspace + gb + 2 * nb);
-        bool adjoints_done = false;
+        float* Pfx = (float*)((unsigned char*)workspace + gb + ab);
+        float* Q = (float*)((unsigned char*)workspace + gb + ab + nb);
         if (e == hipSuccess)
-            e = sig::chunk_scan(w.d, w.depth, ckpt, Pfx, Q, coeffs, nullptr, grad_coeffs, Abar, B, (int)ch.C, &adjoints_done, st);
-        if (e == hipSuccess && !adjoints_done) e = sig::chunk_adjoint(w.d, w.depth, grad_coeffs, Q, Abar, B, (int)ch.C, true, st);
+            e = sig::chunk_scan(w.d, w.depth, ckpt, Pfx, Q, coeffs, nullptr, nullptr, nullptr, B, (int)ch.C, nullptr, st);
+        if (e == hipSuccess) e = sig::chunk_adjoint(w.d, w.depth, grad_coeffs, Q, Abar, B, (int)ch.C, true, st);
         row_coeffs = Pfx;
     }
     if (e != hipSuccess) return hip_fail(e);
@@ -1013,7 +1014,7 @@ size_t sig_backward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t 
     const Chunks ch = checkpoint_chunks(w, B, n_points);
     if (ch.C < 2) return sig_backward_workspace_bytes(ws, B, n_points);
     // gradient of the increments, boundary adjoints; beyond two chunks also the products before and after every chunk
-    return gdx_bytes_of(w, B, n_points) + (ch.C == 2 ? 1 : 3) * chunk_array_bytes(w, B, ch.C);
+    return gdx_bytes_of(w, B, n_points) + chunk_array_bytes(w, B, ch.C - 1) + (ch.C == 2 ? 0 : 2) * chunk_array_bytes(w, B, ch.C);
 }
 
 int sig_forward_checkpointed(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs,

@@ -276,7 +276,8 @@ __global__ __launch_bounds__(512) void chunk_adjoint_kernel(const float* __restr
     const int c = (int)(row - b * C);
     const int W = g.W;
     const float* gr = grad + b * W;
-    float* out = Abar + row * W;
+    // without the rows of the last chunk the array is [B][C - 1][W]
+    float* out = Abar + (skip_last ? row - b : row) * W;
     if (c == C - 1) {
         if (!skip_last && blockIdx.y == 0) copy_row(gr, out, nullptr, W);
         return;
@@ -314,7 +315,7 @@ __global__ __launch_bounds__(512) void chunk_adjoint_subtree_kernel(const float*
     float* sg = sq + below;
     const float* gr = grad + b * W;
     const float* q = Q + row * W;
-    float* out = Abar + row * W;
+    float* out = Abar + (row - b) * W;                   // [B][C - 1][W]: the last chunk has no row
     const int tid = (int)threadIdx.x, nthr = (int)blockDim.x;
     for (int m = 1; m < N; ++m) {
         const int cnt = 1 << (lb * m);

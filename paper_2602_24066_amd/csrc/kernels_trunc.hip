@@ -747,10 +747,10 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (BwdLds<D, N, WQ, T, VG>::T
     const float* X = path + (b * P + seg0) * D;
     const int64_t nW = level_start(D, N) + ipow(D, N);
     // rows of the last chunk of a path may live in arrays of their own ([B][|W|]: the caller's terminal signature
-    // and gradient), the others in [B][C][|W|] arrays
+    // and gradient); the others in a [B][C][|W|] array of signatures and, then, a [B][C - 1][|W|] array of adjoints
     const bool in_last = coeffs_last != nullptr && row - b * C == C - 1;
     const float* cf = in_last ? coeffs_last + b * nW : coeffs + row * nW;
-    const float* gr = in_last ? grad_last + b * nW : grad + row * nW;
+    const float* gr = in_last ? grad_last + b * nW : grad + (coeffs_last != nullptr ? row - b : row) * nW;
 
     int offS[NBS];
 #pragma unroll
@@ -1702,10 +1702,11 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock, (D == 8 ? 2 : 1)) void trun
     }
     const float* X = path + (b * P + seg0) * D;
     const int64_t nW = level_start(D, N) + ipow(D, N);
-    // rows of the last chunk of a path may live in arrays of their own ([B][|W|]), the others in [B][C][|W|] arrays
+    // rows of the last chunk of a path may live in arrays of their own ([B][|W|]); the others in a [B][C][|W|] array of
+    // signatures and, then, a [B][C - 1][|W|] array of adjoints
     const bool in_last = coeffs_last != nullptr && row - b * C == C - 1;
     const float* cf = in_last ? coeffs_last + b * nW : coeffs + row * nW;
-    const float* gr = in_last ? grad_last + b * nW : grad + row * nW;
+    const float* gr = in_last ? grad_last + b * nW : grad + (coeffs_last != nullptr ? row - b : row) * nW;
 
     // ---- state: signature and adjoints at the end of the row
     float Sc[K], Ac[K];                    // chain (a word shared by several lanes has its adjoint in the first of them)

@@ -364,6 +364,9 @@ def test_time_chunk_workspace():
     assert lib.sig_checkpoint_bytes(ws85._h, 128, 1025) == (4 * 128 * 2 * ws85.size + 255) // 256 * 256
     assert lib.sig_checkpoint_bytes(ws85._h, 1024, 1025) == 0 and lib.sig_checkpoint_bytes(ws85._h, 128, 100) == 0
     assert lib.sig_checkpoint_bytes(ws._h, 2, 1025) == 0
+    # its backward workspace: increment gradients and one boundary adjoint per chunk but the last
+    gdx85 = (4 * 128 * 1024 * 8 + 255) // 256 * 256
+    assert lib.sig_backward_checkpointed_workspace_bytes(ws85._h, 128, 1025) == gdx85 + (4 * 128 * 1 * ws85.size + 255) // 256 * 256
     assert lib.sig_backward_checkpointed_workspace_bytes(ws._h, 2, 1025) == lib.sig_backward_workspace_bytes(ws._h, 2, 1025)
     assert lib.sig_forward_workspace_bytes(ws._h, 2, 300) == 0
     assert lib.sig_forward_workspace_bytes(ws._h, 4096, 1025) == 0
