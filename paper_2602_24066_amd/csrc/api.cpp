@@ -772,7 +772,7 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
         if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
         float* dxT = (float*)workspace;
         const int64_t Lpad = jit_lpad(w, n_points, 0);
-        hipError_t e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, st);
+        hipError_t e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, nullptr, st);
         if (e != hipSuccess) return hip_fail(e);
         hipEvent_t* pe = g_prof.next(0);
         if (pe) (void)hipEventRecord(pe[0], st);
@@ -946,9 +946,7 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
         const size_t gdx_bytes = std::max(gdx_bytes_of(w, B, n_points), t_bytes);
         float* dxT = (float*)((unsigned char*)workspace + gdx_bytes);
         const int64_t Lpad = jit_lpad(w, n_points, 1);
-        e = sig::fill_zero(gdx, (int64_t)(t_bytes / sizeof(float)), st);
-        if (e != hipSuccess) return hip_fail(e);
-        e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, st);
+        e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, gdx, st);   // clears the gradients as well
         if (e != hipSuccess) return hip_fail(e);
         hipEvent_t* pe = g_prof.next(1);
         if (pe) (void)hipEventRecord(pe[0], st);

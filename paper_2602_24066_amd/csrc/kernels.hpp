@@ -46,7 +46,9 @@ struct GenericArgs {
 size_t generic_bwd_lds_bytes(int d, int max_slots, int tile_steps);
 hipError_t generic_forward(const GenericArgs& a, int max_len, hipStream_t stream);
 hipError_t generic_backward(const GenericArgs& a, int max_len, hipStream_t stream);
-hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d, int64_t Lpad, float* dxT, hipStream_t stream);
+// zeroed: nullptr, or an array of the layout of dxT that the kernel clears on the way (the increment gradients)
+hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d, int64_t Lpad, float* dxT, float* zeroed,
+                                 hipStream_t stream);
 // chain rule from increment gradients in the layout of increments_transposed to grad_path [B][P][d]
 hipError_t grad_points_transposed(const float* g, int64_t B, int64_t P, int d, int64_t Lpad, float* grad_path, hipStream_t stream);
 hipError_t fill_zero(float* p, int64_t n, hipStream_t stream);

@@ -266,7 +266,7 @@ __global__ __launch_bounds__(kWave) void bwd_generic_kernel(const UnitDesc* __re
 // One workgroup takes 64 paths x TS segments: a wavefront reads runs of consecutive floats of its 16 paths
 // (coalesced), the differences go to an LDS tile [segment * d + letter][path] and leave it as rows of 64 paths.
 __global__ void increments_transposed_kernel(const float* __restrict__ path, int64_t B, int64_t P, int d, int64_t Lpad, int TS,
-                                             int64_t tiles, float* __restrict__ dxT)
+                                             int64_t tiles, float* __restrict__ dxT, float* __restrict__ zeroed)
 {
     extern __shared__ float tile[];                       // [TS * d][65]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = 4;
@@ -291,9 +291,12 @@ __global__ void increments_transposed_kernel(const float* __restrict__ path, int
         }
     }
     __syncthreads();
-    float* out = dxT + ((g * Lpad + j0) * d) * kWave;
+    const int64_t base = ((g * Lpad + j0) * d) * kWave;
     for (int e = wave; e < R; e += nwaves)
-        if (j0 + e / d < Lpad) out[(int64_t)e * kWave + lane] = tile[e * 65 + lane];
+        if (j0 + e / d < Lpad) {
+            dxT[base + (int64_t)e * kWave + lane] = tile[e * 65 + lane];
+            if (zeroed) zeroed[base + (int64_t)e * kWave + lane] = 0.0f;   // an array of the same layout, cleared on the way
+        }
 }
 
 __global__ void fill_zero_kernel(float* p, int64_t n)
@@ -369,7 +372,8 @@ hipError_t generic_backward(const GenericArgs& a, int max_len, hipStream_t strea
     return launch_bwd<12>(a, stream);
 }
 
-hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d, int64_t Lpad, float* dxT, hipStream_t stream)
+hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d, int64_t Lpad, float* dxT, float* zeroed,
+                                 hipStream_t stream)
 {
     const int64_t groups = (B + kWave - 1) / kWave;
     if (groups <= 0 || Lpad <= 0 || d <= 0) return hipSuccess;
@@ -377,7 +381,7 @@ hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d,
     const size_t lds = (size_t)TS * d * 65 * sizeof(float);
     const int64_t tiles = (Lpad + TS - 1) / TS;
     if (lds > 64 * 1024 || tiles > 0x7fffffff / groups) return hipErrorInvalidValue;
-    increments_transposed_kernel<<<(unsigned)(tiles * groups), 256, lds, stream>>>(path, B, P, d, Lpad, TS, tiles, dxT);
+    increments_transposed_kernel<<<(unsigned)(tiles * groups), 256, lds, stream>>>(path, B, P, d, Lpad, TS, tiles, dxT, zeroed);
     return hipGetLastError();
 }
 
