@@ -428,6 +428,18 @@ def test_backward_finite_differences_on_c2_shaped_case():
     _fd_coordinates_and_directions(fun, ana, X, 64, 8, seed=7)
 
 
+@pytest.mark.parametrize("d,N,L,dist,seed", [(8, 5, 10, "scaled", 10), (16, 4, 8, "ar1", 12)])
+def test_backward_finite_differences_on_c3_and_c5_shaped_cases(d, N, L, dist, seed):
+    """The c3 and c5 word sets (d = 8, depth 5: 37,448 words; d = 16, depth 4: 69,904 words) with their input
+    distributions on a small batch: 64 random coordinates and 8 random directions against central differences."""
+    B = 2
+    X = np.round(make_path(dist, 90 + seed, B, L, d).astype(np.float64) * 128) / 128
+    G = np.random.default_rng(seed).standard_normal((B, sum(d ** n for n in range(1, N + 1))))
+    ana = O.backward_dense(X.astype(np.float32), N, G)
+    fun = lambda Y: float((O.forward_dense(Y.astype(np.float32), N) * G).sum())
+    _fd_coordinates_and_directions(fun, ana, X, 64, 8, seed=seed + 1)
+
+
 def test_backward_finite_differences_on_c4a_shaped_case():
     """The c4a word set (d = 6, weights (1,1,2,2,3,3), degree <= 8: 5,754 words up to length 8) on a small batch, per-word
     route: 64 random coordinates and 8 random directions against central differences of the per-word forward oracle."""
