@@ -14,7 +14,10 @@ HIPCC_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang",
                "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument",
                # matrix-instruction results stay in ordinary vector registers: the vector ALU reads them without
                # v_accvgpr_read copies (a quarter of the instructions of the backward kernels otherwise)
-               "-mllvm", "-amdgpu-mfma-vgpr-form"]
+               "-mllvm", "-amdgpu-mfma-vgpr-form",
+               # instruction scheduling for latency hiding inside a wavefront rather than for occupancy, which launch
+               # bounds fix anyway (two wavefronts per SIMD at most in the main kernels): measured 3-7 % on them
+               "-mllvm", "-amdgpu-sched-strategy=max-ilp"]
 
 
 def hipcc() -> str:
