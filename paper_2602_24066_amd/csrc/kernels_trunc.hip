@@ -2240,8 +2240,8 @@ constexpr int kOccFwd46 = 4;
 int trunc_occupancy(int d, int depth, int backward)
 {
     if (d == 4 && depth == 6) return backward ? 3 : kOccFwd46;
-    if (d == 8 && depth == 5) return backward ? 1 : 3;
-    if (d == 16 && depth == 4) return backward ? 1 : 3;
+    if (d == 8 && depth == 5) return backward ? 1 : 2;     // forward: 216 and 204 registers under the scheduler that
+    if (d == 16 && depth == 4) return backward ? 1 : 2;    // maximises instruction-level parallelism
     return 1;
 }
 

@@ -359,7 +359,7 @@ def test_time_chunk_workspace():
     ws85 = S.sig_wordset_build_truncated(8, 5)
     per85 = (4 * 2 * 4 * ws85.size + 255) // 256 * 256        # 2 paths, 4 chunks of 256 segments
     assert lib.sig_forward_workspace_bytes(ws85._h, 2, 1025) == 2 * per85
-    assert lib.sig_forward_workspace_bytes(ws85._h, 128, 1025) == (4 * 128 * 3 * ws85.size + 255) // 256 * 256   # three chunks
+    assert lib.sig_forward_workspace_bytes(ws85._h, 128, 1025) == (4 * 128 * 2 * ws85.size + 255) // 256 * 256   # two chunks
     # checkpointed form: offered where the backward kernel of the shape would leave SIMDs with a single wavefront
     assert lib.sig_checkpoint_bytes(ws85._h, 128, 1025) == (4 * 128 * 2 * ws85.size + 255) // 256 * 256
     assert lib.sig_checkpoint_bytes(ws85._h, 1024, 1025) == 0 and lib.sig_checkpoint_bytes(ws85._h, 128, 100) == 0
