@@ -47,6 +47,23 @@ def test_compiled_kernels_are_checked_against_their_launch_shape():
     assert ok(0, 256, 0, 10) == 0
 
 
+def test_boundary_from_plain_c(tmp_path):
+    """include/sig.h is a C header: a C99 program compiled with gcc links against the library and calls it."""
+    import shutil, subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    here = os.path.dirname(os.path.abspath(__file__))
+    root = os.path.dirname(here)
+    lib = S.lib_path()
+    exe = str(tmp_path / "abi_smoke")
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"),
+                    os.path.join(here, "c_abi", "abi_smoke.c"), "-o", exe, lib, "-Wl,-rpath," + os.path.dirname(lib)], check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout.split("\n")
+    assert out[0].split() == ["120", "3", "4", str(S.sig_wordset_build_truncated(3, 4).min_fma_per_step)]
+    assert out[1].startswith("-1 ")
+
+
 def test_strerror_and_version():
     lib = S.load_library()
     assert lib.sig_strerror(0) == b"success"
