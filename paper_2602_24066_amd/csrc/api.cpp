@@ -104,7 +104,7 @@ struct CallTimer {
 // relation.  Measured on the three instantiated shapes this pays off for the forward kernels once a chunk is a
 // few hundred segments long (the chunk products and the second launch cost about as much as 100 segments); the
 // backward kernels already fill their register budget with one wavefront per SIMD and would in addition have to
-// recompute the chunk signatures, so they are chunked only on request (SIG_CHUNKS, used by the tests).
+// recompute the chunk signatures, so they are chunked only on request (option "chunks", used by the tests).
 struct Chunks { int64_t C, Lc; };
 Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points)
 {
@@ -126,7 +126,7 @@ Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points)
 // chunks per path in one workgroup, chunk signatures multiplied in LDS).  Returns the number of chunks, 0 = the
 // kernel with four wavefronts per path instead (with its chunk arrays in HBM for long paths): measured faster only
 // for fewer than 192 paths of more than 512 segments.  Four chunks need a compute unit per path, so larger batches
-// take two.  SIG_FWD_TAILS=0 (or a SIG_CHUNKS setting) switches it off, =2 / =4 force that many chunks.
+// take two.  The option "fwd_tails" = 0 (or a "chunks" setting) switches it off, = 2 / = 4 force that many chunks.
 int64_t trunc_forward_fused_chunks(const sig::WordSet& w, int64_t B, int64_t n_points, const float* coeffs)
 {
     if (!sig::trunc_forward_tails_available(w.d, w.depth) || ((uintptr_t)coeffs & 15) != 0) return 0;
@@ -151,7 +151,7 @@ int64_t trunc_forward_fused_chunks(const sig::WordSet& w, int64_t B, int64_t n_p
 // that does half the vector work per path and fits two wavefronts on a SIMD, so it wants about two thousand rows.
 // Smaller batches take its fused form (2, 4 or 8 chunks of a path in one workgroup, everything between the chunks
 // in LDS), larger ones run it unchunked; the thresholds come from a scan over 64..2,048 paths of 64..1,024 segments.
-// SIG_BWD_TAILS=0 switches it off, =1 takes the unfused form with chunk arrays in HBM (SIG_CHUNKS chunks),
+// The option "bwd_tails" = 0 switches it off, = 1 takes the unfused form with chunk arrays in HBM ("chunks" chunks),
 // =2 / =4 / =8 force the fused form with that many chunks.
 struct BwdShape { bool tails, fused; int64_t C, Lc; };
 BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points)
@@ -378,7 +378,7 @@ int bwd_tile_steps(int d) { return std::max(1, std::min(16, 32 / std::max(d, 1))
 // ---- full truncations without a register-resident kernel of their own: lanes = words -----------------------
 // Lanes = paths needs 64 paths per wavefront and a compilation that grows with the word set (minutes beyond a few
 // ten thousand words); lanes = words fills the wavefronts from a single path on and compiles in about a second per
-// shape.  Taken whenever the words of a path fill at least half a wavefront; SIG_LANES=0 switches it off, =1 takes
+// shape.  Taken whenever the words of a path fill at least half a wavefront; the option "lanes" = 0 switches it off, = 1 takes
 // it for every shape it is defined for.
 int lanes_levels_asked(const sig::WordSet& w)             // testing knob: 1 or 2 levels below the lane's word
 {
