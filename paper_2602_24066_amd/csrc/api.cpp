@@ -102,9 +102,10 @@ struct CallTimer {
 // Time chunks for full truncations: with few paths the sequential kernels leave wavefront slots empty, so the
 // segments of every path are cut into C chunks that run as independent rows and are combined afterwards with Chen's
 // relation.  Measured on the three instantiated shapes this pays off for the forward kernels once a chunk is a
-// few hundred segments long (the chunk products and the second launch cost about as much as 100 segments); the
-// backward kernels already fill their register budget with one wavefront per SIMD and would in addition have to
-// recompute the chunk signatures, so they are chunked only on request (option "chunks", used by the tests).
+// few hundred segments long (the chunk products and the second launch cost about as much as 100 segments); a
+// chunked backward pass that starts from the terminal signature alone has to recompute the chunk signatures, a forward
+// pass of its own, so sig_backward chunks only on request (option "chunks", used by the tests) and the checkpointed
+// calls, which keep the chunk signatures, are the way to more rows.
 struct Chunks { int64_t C, Lc; };
 Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points)
 {
