@@ -50,18 +50,23 @@ def oracle_backward(X, W, kind, depth, G):
     return O.backward_words(X, W, G)
 
 
-def gpu_forward_backward(ws, X, G):
+def gpu_forward_backward(ws, X, G, checkpointed=False):
+    """sig_forward + sig_backward, or the pair of calls that keeps the time-chunk signatures between them."""
     import torch
     xp = torch.from_numpy(X).cuda()
-    coeffs = S.sig_forward(ws, xp)
-    gp = S.sig_backward(ws, xp, coeffs, torch.from_numpy(G).cuda()) if G is not None else None
+    if checkpointed:
+        coeffs, ck = S.sig_forward_checkpointed(ws, xp)
+        gp = S.sig_backward_checkpointed(ws, xp, coeffs, torch.from_numpy(G).cuda(), ck) if G is not None else None
+    else:
+        coeffs = S.sig_forward(ws, xp)
+        gp = S.sig_backward(ws, xp, coeffs, torch.from_numpy(G).cuda()) if G is not None else None
     torch.cuda.synchronize()
     return coeffs.cpu().numpy(), (gp.cpu().numpy() if gp is not None else None)
 
 
-def check_parity(ws, W, kind, depth, X, G, sample=None, what=""):
+def check_parity(ws, W, kind, depth, X, G, sample=None, what="", checkpointed=False):
     """Runs the HIP path on the whole batch and the oracle on `sample` (indices) or on everything."""
-    coeffs, gp = gpu_forward_backward(ws, X, G)
+    coeffs, gp = gpu_forward_backward(ws, X, G, checkpointed)
     assert np.isfinite(coeffs).all(), what
     idx = np.arange(X.shape[0]) if sample is None else np.asarray(sample)
     Xs = np.ascontiguousarray(X[idx])

@@ -703,16 +703,20 @@ FULL = {
 }
 
 
-@pytest.mark.parametrize("name", list(FULL))
-def test_full_size_workloads(name):
+# (name, checkpointed): the benchmark times the checkpointed pair of calls where the library offers it (c3, c5) and
+# the plain pair beside it
+@pytest.mark.parametrize("name,checkpointed", [(n, False) for n in FULL] + [("c3", True), ("c5", True)])
+def test_full_size_workloads(name, checkpointed):
     wl = WORKLOADS[name]
     ws, W = build_for_workload(wl)
+    if checkpointed:
+        assert S.load_library().sig_checkpoint_bytes(ws._h, wl.B, wl.L + 1) > 0
     X = workload_path(wl)
     G = make_grad_coeffs(wl.seed, wl.B, ws.size)
     if name == "c5":
         O.set_threads(2)              # the oracle's backward keeps every intermediate signature: 2.3 GB per path
     try:
-        errs, gerr = check_parity(ws, W, wl.kind, wl.depth, X, G, sample=FULL[name], what=name)
+        errs, gerr = check_parity(ws, W, wl.kind, wl.depth, X, G, sample=FULL[name], what=name, checkpointed=checkpointed)
     finally:
         O.set_threads(16)
     print(f"{name}: forward level errors {errs}; gradient error max {gerr.max():.3e}")
