@@ -1101,6 +1101,13 @@ static bool windows_direct(const sig::WordSet& w, int64_t B, int64_t K, int back
 {
     return B * K <= 65535 && (backward ? use_trunc_backward(w, B * K) : use_trunc_forward(w, B * K));
 }
+// Word sets that run through the straight-line specialised kernels (lane = row): their rows can be windows as well,
+// the increments being transposed straight from the path.  (The workspace the window calls ask for covers both this
+// form and the gather into padded sub-paths, which the other kernels and a failed compilation take.)
+static bool windows_rows_jit(const sig::WordSet& w, int64_t rows)
+{
+    return !use_trunc_forward(w, rows) && !use_trunc_backward(w, rows) && !use_lanes(w, rows) && jit_enabled(w);
+}
 
 size_t sig_forward_windows_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points, int64_t K, int64_t max_window_len)
 {
@@ -1147,6 +1154,25 @@ int sig_forward_windows(const sig_wordset* ws, const float* path, int64_t B, int
     const size_t sb = win_sub_bytes(w, B, K, n_sub);
     if (!workspace || workspace_bytes < sig_forward_windows_workspace_bytes(ws, B, n_points, K, max_window_len)) return SIG_EWORKSPACE;
     if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
+    // straight-line specialised kernels: the rows' increments are transposed straight from the path, window by window
+    if (windows_rows_jit(w, B * K) && n_points > 1 && max_window_len > 0) {
+        const sig::Plan* jp = nullptr;
+        if (sig::JitKernel* jk = ensure_jit(w, 0, B * K, Build::compile_and_load, &jp)) {
+            hipStream_t st = (hipStream_t)stream;
+            CallTimer whole(0, st);
+            sig::WindowList wl;
+            wl.win = windows; wl.K = K; wl.max_len = max_window_len;
+            float* dxT = (float*)workspace;
+            const int64_t Lpad = jit_lpad(w, n_sub, 0);
+            hipError_t e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, nullptr, st, wl);
+            if (e != hipSuccess) return hip_fail(e);
+            hipEvent_t* pe = g_prof.next(0);
+            if (pe) (void)hipEventRecord(pe[0], st);
+            e = launch_jit_forward(*jk, *jp, dxT, B * K, Lpad / jk->tile, coeffs, w.size(), st);
+            if (pe) (void)hipEventRecord(pe[1], st);
+            return e == hipSuccess ? SIG_OK : hip_fail(e);
+        }
+    }
     float* sub = (float*)workspace;
     hipError_t e = sig::window_gather(path, B, n_points, w.d, windows, K, n_sub, sub, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
@@ -1191,6 +1217,29 @@ int sig_backward_windows(const sig_wordset* ws, const float* path, const float* 
     const size_t sb = win_sub_bytes(w, B, K, n_sub);
     if (!workspace || workspace_bytes < sig_backward_windows_workspace_bytes(ws, B, n_points, K, max_window_len)) return SIG_EWORKSPACE;
     if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
+    // straight-line specialised kernels: rows = windows, increments and their gradients in the transposed layout, the
+    // chain rule adds every window's gradient into grad_path (needs 2 arrays of the transposed layout: less than asked)
+    if (windows_rows_jit(w, B * K) && n_points > 1 && max_window_len > 0) {
+        const sig::Plan* jp = nullptr;
+        if (sig::JitKernel* jk = ensure_jit(w, 1, B * K, Build::compile_and_load, &jp)) {
+            CallTimer whole(1, st);
+            sig::WindowList wl;
+            wl.win = windows; wl.K = K; wl.max_len = max_window_len;
+            const size_t t_bytes = jit_dxt_bytes(w, B * K, n_sub, 1);
+            float* gdx = (float*)workspace;
+            float* dxT = (float*)((unsigned char*)workspace + t_bytes);
+            const int64_t Lpad = jit_lpad(w, n_sub, 1);
+            e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, gdx, st, wl);
+            if (e != hipSuccess) return hip_fail(e);
+            hipEvent_t* pe = g_prof.next(1);
+            if (pe) (void)hipEventRecord(pe[0], st);
+            e = launch_jit_backward(*jk, *jp, dxT, coeffs, grad_coeffs, B * K, max_window_len, Lpad / jk->tile, w.size(), gdx, st);
+            if (pe) (void)hipEventRecord(pe[1], st);
+            if (e != hipSuccess) return hip_fail(e);
+            e = sig::grad_points_transposed(gdx, B, n_points, w.d, Lpad, grad_path, st, wl);
+            return e == hipSuccess ? SIG_OK : hip_fail(e);
+        }
+    }
     float* sub = (float*)workspace;
     float* gsub = (float*)((unsigned char*)workspace + sb);
     e = sig::window_gather(path, B, n_points, w.d, windows, K, n_sub, sub, st);

@@ -46,11 +46,8 @@ struct GenericArgs {
 size_t generic_bwd_lds_bytes(int d, int max_slots, int tile_steps);
 hipError_t generic_forward(const GenericArgs& a, int max_len, hipStream_t stream);
 hipError_t generic_backward(const GenericArgs& a, int max_len, hipStream_t stream);
-// zeroed: nullptr, or an array of the layout of dxT that the kernel clears on the way (the increment gradients)
-hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d, int64_t Lpad, float* dxT, float* zeroed,
-                                 hipStream_t stream);
-// chain rule from increment gradients in the layout of increments_transposed to grad_path [B][P][d]
-hipError_t grad_points_transposed(const float* g, int64_t B, int64_t P, int d, int64_t Lpad, float* grad_path, hipStream_t stream);
+
+
 hipError_t fill_zero(float* p, int64_t n, hipStream_t stream);
 hipError_t leadlag(const float* path, int64_t B, int64_t P, int d, float* out, hipStream_t stream);            // out [B, 2P-1, 2d]
 hipError_t leadlag_backward(const float* gout, int64_t B, int64_t P, int d, float* gpath, hipStream_t stream);
@@ -80,6 +77,16 @@ struct WindowList {
     int64_t K = 0;
     int64_t max_len = 0;
 };
+
+// Increments of B paths (or, with a window list, of the B * K windows of the paths: one row per (path, window) pair,
+// read straight from the path), differenced and transposed for the specialised kernels; Lpad: padded segments per row.
+// zeroed: nullptr, or an array of the layout of dxT that the kernel clears on the way (the increment gradients).
+hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d, int64_t Lpad, float* dxT, float* zeroed,
+                                 hipStream_t stream, const WindowList& wl = WindowList());
+// chain rule from increment gradients in the layout of increments_transposed to grad_path [B][P][d]; with a window list
+// the rows are windows and their gradients are added into grad_path (zeroed by the caller)
+hipError_t grad_points_transposed(const float* g, int64_t B, int64_t P, int d, int64_t Lpad, float* grad_path, hipStream_t stream,
+                                  const WindowList& wl = WindowList());
 
 // Register-resident kernels for full truncations (kernels_trunc.hip)
 bool trunc_forward_available(int d, int depth);

@@ -260,30 +260,54 @@ __global__ __launch_bounds__(kWave) void bwd_generic_kernel(const UnitDesc* __re
     }
 }
 
-// Increments, differenced and transposed for the run-time specialised kernels (lane = path):
-//   dxT[((g * Lpad + j) * d + i) * 64 + lane] = X[b][j+1][i] - X[b][j][i],  b = 64 g + lane,
-// zero for padded segments j >= L and for b >= B.
-// One workgroup takes 64 paths x TS segments: a wavefront reads runs of consecutive floats of its 16 paths
-// (coalesced), the differences go to an LDS tile [segment * d + letter][path] and leave it as rows of 64 paths.
-__global__ void increments_transposed_kernel(const float* __restrict__ path, int64_t B, int64_t P, int d, int64_t Lpad, int TS,
-                                             int64_t tiles, float* __restrict__ dxT, float* __restrict__ zeroed)
+// Row r of the specialised kernels: a whole path (no window list: path r, all P - 1 segments) or window r % K of path
+// r / K, between the points win[2 k] and win[2 k + 1] clamped to the path, at most max_len segments.
+__device__ __forceinline__ void lane_row(const WindowList& wl, int64_t r, int64_t P, int64_t& b, int64_t& first, int64_t& len)
+{
+    if (wl.win == nullptr) {
+        b = r;
+        first = 0;
+        len = P - 1;
+    } else {
+        b = r / wl.K;
+        const int64_t k = r - b * wl.K;
+        int64_t l = wl.win[2 * k], e = wl.win[2 * k + 1];
+        l = l < 0 ? 0 : (l > P - 1 ? P - 1 : l);
+        e = e < l ? l : (e > P - 1 ? P - 1 : e);
+        first = l;
+        len = e - l < wl.max_len ? e - l : wl.max_len;
+    }
+}
+
+// Increments, differenced and transposed for the run-time specialised kernels (lane = row):
+//   dxT[((g * Lpad + j) * d + i) * 64 + lane] = X[b][first + j + 1][i] - X[b][first + j][i],  row 64 g + lane,
+// zero for padded segments j >= the row's length and for rows past the last.
+// One workgroup takes 64 rows x TS segments: a wavefront reads runs of consecutive floats of its 16 rows
+// (coalesced), the differences go to an LDS tile [segment * d + letter][row] and leave it as rows of 64 lanes.
+__global__ void increments_transposed_kernel(const float* __restrict__ path, int64_t R_rows, int64_t P, int d, int64_t Lpad, int TS,
+                                             int64_t tiles, WindowList wl, float* __restrict__ dxT, float* __restrict__ zeroed)
 {
     extern __shared__ float tile[];                       // [TS * d][65]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = 4;
     const int64_t g = blockIdx.x / tiles;
     const int64_t j0 = (blockIdx.x % tiles) * TS;
     const int R = TS * d;
-    const int64_t L = P - 1;
-    // 16 paths per wavefront (workgroups of 256 threads); the loads of all of them are issued before the first is used
+    // 16 rows per wavefront (workgroups of 256 threads); the loads of all of them are issued before the first is used
     for (int e0 = 0; e0 < R; e0 += kWave) {
         const int e = e0 + lane;
-        const bool live = e < R && j0 + e / d < L;
         float v[16];
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
-            const int64_t b = g * kWave + wave * 16 + q;
-            const float* row = path + (b * P + j0) * d;
-            v[q] = (live && b < B) ? row[e + d] - row[e] : 0.0f;
+            const int64_t r = g * kWave + wave * 16 + q;
+            v[q] = 0.0f;
+            if (r < R_rows && e < R) {
+                int64_t b, first, len;
+                lane_row(wl, r, P, b, first, len);
+                if (j0 + e / d < len) {
+                    const float* row = path + (b * P + first + j0) * d;
+                    v[q] = row[e + d] - row[e];
+                }
+            }
         }
         if (e < R) {
 #pragma unroll
@@ -373,56 +397,69 @@ hipError_t generic_backward(const GenericArgs& a, int max_len, hipStream_t strea
 }
 
 hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d, int64_t Lpad, float* dxT, float* zeroed,
-                                 hipStream_t stream)
+                                 hipStream_t stream, const WindowList& wl)
 {
-    const int64_t groups = (B + kWave - 1) / kWave;
+    const int64_t rows = B * (wl.win ? wl.K : 1);
+    const int64_t groups = (rows + kWave - 1) / kWave;
     if (groups <= 0 || Lpad <= 0 || d <= 0) return hipSuccess;
     const int TS = std::max(1, 64 / d);
     const size_t lds = (size_t)TS * d * 65 * sizeof(float);
     const int64_t tiles = (Lpad + TS - 1) / TS;
     if (lds > 64 * 1024 || tiles > 0x7fffffff / groups) return hipErrorInvalidValue;
-    increments_transposed_kernel<<<(unsigned)(tiles * groups), 256, lds, stream>>>(path, B, P, d, Lpad, TS, tiles, dxT, zeroed);
+    increments_transposed_kernel<<<(unsigned)(tiles * groups), 256, lds, stream>>>(path, rows, P, d, Lpad, TS, tiles, wl, dxT, zeroed);
     return hipGetLastError();
 }
 
 // Chain rule for the specialised kernels, whose increment gradients lie in the layout of their increments,
 // g[((grp * Lpad + j) * d + i) * 64 + lane]:  dLoss/dX_j = dLoss/d dX_j - dLoss/d dX_{j+1}  (Section 4.1), written to
-// grad_path [B][P][d].  A workgroup takes 64 paths x TS points: rows of 64 paths in, through an LDS tile
-// [(TS + 1) * d][65], runs of consecutive floats of one path out.
-__global__ void grad_points_transposed_kernel(const float* __restrict__ g, int64_t B, int64_t P, int d, int64_t Lpad, int TS,
-                                              int64_t tiles, float* __restrict__ grad_path)
+// grad_path [B][P][d].  A workgroup takes 64 rows x TS points: rows of 64 lanes in, through an LDS tile
+// [(TS + 1) * d][65], runs of consecutive floats of one path out.  With a window list a row is a window of its path:
+// its points are those of the path from the window's first point on, and the gradients of overlapping windows are
+// added up in grad_path (zeroed by the caller) with floating-point atomics.
+__global__ void grad_points_transposed_kernel(const float* __restrict__ g, int64_t R_rows, int64_t P, int d, int64_t Lpad, int TS,
+                                              int64_t tiles, WindowList wl, float* __restrict__ grad_path)
 {
     extern __shared__ float tile[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = 4;
     const int64_t grp = blockIdx.x / tiles;
-    const int64_t j0 = (blockIdx.x % tiles) * TS;            // points j0 .. j0 + TS - 1; tile row r: segment j0 - 1 + r / d
-    const int64_t L = P - 1;
+    const int64_t j0 = (blockIdx.x % tiles) * TS;            // points j0 .. j0 + TS - 1 of every row; tile row r: segment j0 - 1 + r / d
     const int rows = (TS + 1) * d;
+    int64_t my_b, my_first, my_len = 0;                      // this lane's row: segments past its length count as zero
+    if (grp * kWave + lane < R_rows) lane_row(wl, grp * kWave + lane, P, my_b, my_first, my_len);
     for (int r = wave; r < rows; r += nwaves) {
         const int64_t j = j0 - 1 + r / d;
-        tile[r * 65 + lane] = (j >= 0 && j < L) ? g[((grp * Lpad + j) * d + r % d) * kWave + lane] : 0.0f;
+        tile[r * 65 + lane] = (j >= 0 && j < my_len) ? g[((grp * Lpad + j) * d + r % d) * kWave + lane] : 0.0f;
     }
     __syncthreads();
     for (int q = 0; q < 16; ++q) {
         const int p = wave * 16 + q;
-        const int64_t b = grp * kWave + p;
-        if (b >= B) break;
+        const int64_t row = grp * kWave + p;
+        if (row >= R_rows) break;
+        int64_t b, first, len;
+        lane_row(wl, row, P, b, first, len);
+        float* out = grad_path + (b * P + first + j0) * d;
         for (int e = lane; e < TS * d; e += kWave) {
-            const int64_t pt = j0 + e / d;
-            if (pt < P) grad_path[(b * P + j0) * d + e] = tile[e * 65 + p] - tile[(e + d) * 65 + p];
+            if (j0 + e / d <= len) {                          // the row has len + 1 points
+                const float v = tile[e * 65 + p] - tile[(e + d) * 65 + p];
+                if (wl.win) unsafeAtomicAdd(out + e, v);
+                else out[e] = v;
+            }
         }
     }
 }
 
-hipError_t grad_points_transposed(const float* g, int64_t B, int64_t P, int d, int64_t Lpad, float* grad_path, hipStream_t stream)
+hipError_t grad_points_transposed(const float* g, int64_t B, int64_t P, int d, int64_t Lpad, float* grad_path, hipStream_t stream,
+                                  const WindowList& wl)
 {
-    const int64_t groups = (B + kWave - 1) / kWave;
-    if (groups <= 0 || P <= 0 || d <= 0) return hipSuccess;
+    const int64_t n_rows = B * (wl.win ? wl.K : 1);
+    const int64_t groups = (n_rows + kWave - 1) / kWave;
+    const int64_t points = (wl.win ? wl.max_len : P - 1) + 1;          // points a row can have
+    if (groups <= 0 || points <= 0 || d <= 0) return hipSuccess;
     const int TS = std::max(1, 64 / d);
     const size_t lds = (size_t)(TS + 1) * d * 65 * sizeof(float);
-    const int64_t tiles = (P + TS - 1) / TS;
+    const int64_t tiles = (points + TS - 1) / TS;
     if (lds > 64 * 1024 || tiles > 0x7fffffff / groups) return hipErrorInvalidValue;
-    grad_points_transposed_kernel<<<(unsigned)(tiles * groups), 256, lds, stream>>>(g, B, P, d, Lpad, TS, tiles, grad_path);
+    grad_points_transposed_kernel<<<(unsigned)(tiles * groups), 256, lds, stream>>>(g, n_rows, P, d, Lpad, TS, tiles, wl, grad_path);
     return hipGetLastError();
 }
 

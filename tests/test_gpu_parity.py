@@ -450,8 +450,9 @@ WINDOW_SETS = [
 ]
 
 
+@pytest.mark.parametrize("B", [5, 13])
 @pytest.mark.parametrize("case", range(len(WINDOW_SETS)))
-def test_windows(case):
+def test_windows(case, B):
     """Signatures over user-given windows (expanding, sliding, overlapping, single-segment, empty, whole path) against
     one oracle evaluation per window, forward and backward."""
     import torch
@@ -459,7 +460,7 @@ def test_windows(case):
     d = kw["d"]
     words = random_prefix_closed_words(400 + case, d, kw["n_words"], kw["max_len"]) if kind == "words" else None
     ws, W = build_both(kind, d, depth=kw.get("depth"), weights=kw.get("weights"), cutoff=kw.get("cutoff"), words=words)
-    B, L = 5, 40
+    L = 40                      # B = 13: 143 (path, window) rows, more than two wavefronts of rows for the lane = row kernels
     X = make_path("iid", 410 + case, B, L, d)
     windows = [(0, L), (0, 1), (0, 7), (0, 23), (5, 15), (10, 20), (15, 25), (39, 40), (17, 17), (3, 38), (5, 15)]
     K = len(windows)
