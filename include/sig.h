@@ -287,11 +287,12 @@ int     sig_logsig_backward(const sig_wordset* ws, const float* coeffs, const fl
  *          the sum over the windows (floating-point atomics).
  * All windows of all paths advance side by side in one launch.  Full truncations with a precompiled kernel (d, depth)
  * in {(4, 6), (8, 5), (16, 4)} read every window straight from the path as a row of its own (no copy, a short window
- * ends early, the gradients of overlapping windows are added up in the increment-gradient array); word sets that run
- * through the straight-line specialised kernels take their rows' increments straight from the path as well (a short
- * window is padded with zero increments) and add the rows' gradients into grad_path; full truncations of other
- * shapes gather every (path, window) pair into a path of max_window_len + 1 points (shorter windows padded with
- * their last point) and scatter the gradient back.  Workspace sizes from the two functions below (256-byte aligned). */
+ * ends early, the gradients of overlapping windows are added up in the increment-gradient array), and so do the
+ * word-per-lane kernels of the other full truncations; word sets that run through the straight-line specialised
+ * kernels take their rows' increments straight from the path as well (a short window is padded with zero increments)
+ * and add the rows' gradients into grad_path.  Only the table-driven fallback gathers every (path, window) pair into a
+ * path of max_window_len + 1 points (shorter windows padded with their last point) and scatters the gradient back.
+ * Workspace sizes from the two functions below (256-byte aligned). */
 size_t sig_forward_windows_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points, int64_t K, int64_t max_window_len);
 size_t sig_backward_windows_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points, int64_t K, int64_t max_window_len);
 int sig_forward_windows(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, const int64_t* windows, int64_t K,

@@ -421,16 +421,21 @@ sig::JitKernel* ensure_lanes(const sig::WordSet& cw, int dir, const sig::LanesSh
     });
 }
 
+// rows: the B paths, or with a window list the B * K (path, window) pairs, read straight from the path
 hipError_t launch_lanes(sig::JitKernel& k, const sig::LanesShape& s, const float* path, const float* coeffs_in, const float* grad,
-                        int64_t B, int64_t n_points, float* out, hipStream_t st)
+                        int64_t B, int64_t n_points, float* out, hipStream_t st, const sig::WindowList& wl = sig::WindowList())
 {
-    long lB = (long)B, lP = (long)n_points;
-    const int64_t blocks = (B * s.waves + k.nw - 1) / k.nw;
+    long lB = (long)B, lP = (long)n_points, lK = (long)wl.K, lM = (long)wl.max_len;
+    const int64_t* win = wl.win;
+    const int64_t rows = B * (wl.win ? wl.K : 1);
+    const int64_t blocks = (rows * s.waves + k.nw - 1) / k.nw;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     if (grad) {
-        void* args[] = {(void*)&path, (void*)&coeffs_in, (void*)&grad, (void*)&lB, (void*)&lP, (void*)&out};
+        void* args[] = {(void*)&path, (void*)&coeffs_in, (void*)&grad, (void*)&lB, (void*)&lP, (void*)&out, (void*)&win, (void*)&lK,
+                        (void*)&lM};
         return hipModuleLaunchKernel(k.fn, (unsigned)blocks, 1, 1, (unsigned)k.nw * 64, 1, 1, 0, st, args, nullptr);
     }
-    void* args[] = {(void*)&path, (void*)&lB, (void*)&lP, (void*)&out};
+    void* args[] = {(void*)&path, (void*)&lB, (void*)&lP, (void*)&out, (void*)&win, (void*)&lK, (void*)&lM};
     return hipModuleLaunchKernel(k.fn, (unsigned)blocks, 1, 1, (unsigned)k.nw * 64, 1, 1, 0, st, args, nullptr);
 }
 }  // namespace
@@ -1122,7 +1127,10 @@ size_t sig_backward_windows_workspace_bytes(const sig_wordset* ws, int64_t B, in
     if (!ws || B <= 0 || K <= 0 || n_points < 1 || max_window_len < 0) return 0;
     if (windows_direct(*W(ws), B, K, 1)) return n_points > 1 ? gdx_bytes_of(*W(ws), B, n_points) : 0;
     const int64_t n_sub = max_window_len + 1;
-    return 2 * win_sub_bytes(*W(ws), B, K, n_sub) + sig_backward_workspace_bytes(ws, B * K, n_sub);
+    // the gather form; the forms that take windows as rows need less, or (a word per lane) the increment gradients of
+    // the whole paths
+    const size_t gather = 2 * win_sub_bytes(*W(ws), B, K, n_sub) + sig_backward_workspace_bytes(ws, B * K, n_sub);
+    return n_points > 1 ? std::max(gather, gdx_bytes_of(*W(ws), B, n_points)) : gather;
 }
 
 int sig_forward_windows(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, const int64_t* windows, int64_t K,
@@ -1154,6 +1162,21 @@ int sig_forward_windows(const sig_wordset* ws, const float* path, int64_t B, int
     const size_t sb = win_sub_bytes(w, B, K, n_sub);
     if (!workspace || workspace_bytes < sig_forward_windows_workspace_bytes(ws, B, n_points, K, max_window_len)) return SIG_EWORKSPACE;
     if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
+    // a word per lane (full truncations of any alphabet size): every (path, window) row reads its window of the path
+    if (!use_trunc_forward(w, B * K) && use_lanes(w, B * K) && n_points > 1 && max_window_len > 0) {
+        const sig::LanesShape ls = lanes_shape_for(w, 0, B * K);
+        if (sig::JitKernel* lk = ensure_lanes(w, 0, ls, Build::compile_and_load)) {
+            hipStream_t st = (hipStream_t)stream;
+            CallTimer whole(0, st);
+            sig::WindowList wl;
+            wl.win = windows; wl.K = K; wl.max_len = max_window_len;
+            hipEvent_t* pe = g_prof.next(0);
+            if (pe) (void)hipEventRecord(pe[0], st);
+            hipError_t e = launch_lanes(*lk, ls, path, nullptr, nullptr, B, n_points, coeffs, st, wl);
+            if (pe) (void)hipEventRecord(pe[1], st);
+            return e == hipSuccess ? SIG_OK : hip_fail(e);
+        }
+    }
     // straight-line specialised kernels: the rows' increments are transposed straight from the path, window by window
     if (windows_rows_jit(w, B * K) && n_points > 1 && max_window_len > 0) {
         const sig::Plan* jp = nullptr;
@@ -1217,6 +1240,27 @@ int sig_backward_windows(const sig_wordset* ws, const float* path, const float* 
     const size_t sb = win_sub_bytes(w, B, K, n_sub);
     if (!workspace || workspace_bytes < sig_backward_windows_workspace_bytes(ws, B, n_points, K, max_window_len)) return SIG_EWORKSPACE;
     if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
+    // a word per lane: rows = windows read straight from the path, their increment gradients added up in gdx [B][L][d]
+    // (at the start of the workspace, which is larger than that)
+    if (!use_trunc_backward(w, B * K) && use_lanes(w, B * K) && n_points > 1 && max_window_len > 0 &&
+        workspace_bytes >= gdx_bytes_of(w, B, n_points)) {
+        const sig::LanesShape ls = lanes_shape_for(w, 1, B * K);
+        if (sig::JitKernel* lk = ensure_lanes(w, 1, ls, Build::compile_and_load)) {
+            CallTimer whole(1, st);
+            sig::WindowList wl;
+            wl.win = windows; wl.K = K; wl.max_len = max_window_len;
+            float* gdx = (float*)workspace;
+            e = sig::fill_zero(gdx, B * (n_points - 1) * w.d, st);
+            if (e != hipSuccess) return hip_fail(e);
+            hipEvent_t* pe = g_prof.next(1);
+            if (pe) (void)hipEventRecord(pe[0], st);
+            e = launch_lanes(*lk, ls, path, coeffs, grad_coeffs, B, n_points, gdx, st, wl);
+            if (pe) (void)hipEventRecord(pe[1], st);
+            if (e != hipSuccess) return hip_fail(e);
+            e = sig::grad_points(gdx, B, n_points, w.d, grad_path, st);
+            return e == hipSuccess ? SIG_OK : hip_fail(e);
+        }
+    }
     // straight-line specialised kernels: rows = windows, increments and their gradients in the transposed layout, the
     // chain rule adds every window's gradient into grad_path (needs 2 arrays of the transposed layout: less than asked)
     if (windows_rows_jit(w, B * K) && n_points > 1 && max_window_len > 0) {

@@ -105,19 +105,42 @@ __device__ __forceinline__ void load_row(const float* row, float (&e)[DP])
     }
 }
 
+// Row r: a whole path (win == nullptr: path r) or window r % KW of path r / KW, between the points win[2 k] and
+// win[2 k + 1] clamped to the path, at most max_len segments; read straight from the path.
+__device__ __forceinline__ void row_of(const long* __restrict__ win, long KW, long max_len, long r, long P, long& b, long& first,
+                                       long& L)
+{
+    if (win == nullptr) {
+        b = r;
+        first = 0;
+        L = P - 1;
+    } else {
+        b = r / KW;
+        const long k = r - b * KW;
+        long l = win[2 * k], e = win[2 * k + 1];
+        l = l < 0 ? 0 : (l > P - 1 ? P - 1 : l);
+        e = e < l ? l : (e > P - 1 ? P - 1 : e);
+        first = l;
+        L = e - l < max_len ? e - l : max_len;
+    }
+}
+
 #if !BACKWARD
 extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float* __restrict__ path, long B, long P,
-                                                                      float* __restrict__ coeffs)
+                                                                      float* __restrict__ coeffs, const long* __restrict__ win,
+                                                                      long KW, long max_len)
 {
     __shared__ __attribute__((aligned(16))) float smem[NWB * TILE_F];
     const int lane = threadIdx.x & 63;
     const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long wave = (long)blockIdx.x * NWB + wib;
-    if (wave >= B * WAVES) return;                       // wavefronts share nothing: no barrier is skipped
+    if (wave >= B * (win ? KW : 1) * WAVES) return;      // wavefronts share nothing: no barrier is skipped
     float* Ec = smem + wib * TILE_F;
     const float* E0 = Ec + TS * D * NC;
-    const long b = wave / WAVES;
-    const int p0 = __builtin_amdgcn_readfirstlane((int)(wave - b * WAVES) * 64);
+    const long row = wave / WAVES;
+    long b, first, L;
+    row_of(win, KW, max_len, row, P, b, first, L);
+    const int p0 = __builtin_amdgcn_readfirstlane((int)(wave - row * WAVES) * 64);
     const bool valid = p0 + lane < NL;
     const int p = valid ? p0 + lane : NL - 1;
     int letter[K];
@@ -126,8 +149,7 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float
 #pragma unroll
         for (int k = K - 1; k >= 0; --k) { letter[k] = q % D; q /= D; }
     }
-    const float* X = path + b * P * D;
-    const long L = P - 1;
+    const float* X = path + (b * P + first) * D;
 
     float Sc[K], S1[D];
 #pragma unroll
@@ -144,7 +166,9 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float
 
     const long ntiles = (L + TS - 1) / TS;
     float dxn[EPL];
-    fetch_increments(X, 0, L, lane, dxn);
+#pragma unroll
+    for (int q = 0; q < EPL; ++q) dxn[q] = 0.0f;
+    if (L > 0) fetch_increments(X, 0, L, lane, dxn);     // an empty window reads nothing and stores the zero signature
     for (long n = 0; n < ntiles; ++n) {
         wave_lds_fence();
         stage_increments(Ec, dxn, lane);
@@ -182,7 +206,7 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_fwd_lanes(const float
     }
 
     if (!valid) return;
-    float* out = coeffs + b * NWORDS;
+    float* out = coeffs + row * NWORDS;
 #pragma unroll
     for (int k = 1; k <= K; ++k)
         if (p % ipow(D, K - k) == 0) out[level_start(k) + p / ipow(D, K - k)] = Sc[k - 1];
@@ -221,18 +245,21 @@ __device__ __forceinline__ float row_sum(const float* row, int lane)
 }
 
 extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float* __restrict__ path,
-        const float* __restrict__ coeffs, const float* __restrict__ grad, long B, long P, float* gdx)
+        const float* __restrict__ coeffs, const float* __restrict__ grad, long B, long P, float* gdx,
+        const long* __restrict__ win, long KW, long max_len)
 {
     __shared__ __attribute__((aligned(16))) float smem[NWB * BW_PER_WAVE];
     const int lane = threadIdx.x & 63;
     const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long wave = (long)blockIdx.x * NWB + wib;
-    if (wave >= B * WAVES) return;
+    if (wave >= B * (win ? KW : 1) * WAVES) return;
     float* Ec = smem + wib * BW_PER_WAVE;
     const float* E0 = Ec + TS * D * NC;
     float* Vb = Ec + TILE_F;
-    const long b = wave / WAVES;
-    const int p0 = __builtin_amdgcn_readfirstlane((int)(wave - b * WAVES) * 64);
+    const long row = wave / WAVES;
+    long b, first, L;
+    row_of(win, KW, max_len, row, P, b, first, L);
+    const int p0 = __builtin_amdgcn_readfirstlane((int)(wave - row * WAVES) * 64);
     const bool valid = p0 + lane < NL;
     const int p = valid ? p0 + lane : NL - 1;
     int letter[K];
@@ -241,10 +268,11 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
 #pragma unroll
         for (int k = K - 1; k >= 0; --k) { letter[k] = q % D; q /= D; }
     }
-    const float* X = path + b * P * D;
-    const long L = P - 1;
-    const float* cf = coeffs + b * NWORDS;
-    const float* gr = grad + b * NWORDS;
+    if (L <= 0) return;                                  // an empty window: no gradient (wavefronts share no barrier)
+    const float* X = path + (b * P + first) * D;
+    const float* cf = coeffs + row * NWORDS;
+    const float* gr = grad + row * NWORDS;
+    float* const gdx_row = gdx + (b * (P - 1) + first) * D;     // the gradients of overlapping windows add up here
 
     // signature and adjoints at the end of the path; a word shared by several lanes has its adjoint in the first
     float Sc[K], Ac[K], A1[D];
@@ -398,7 +426,7 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
                     }
             }
             const long sg = n * T + t;
-            if (sg < L) __hip_atomic_fetch_add(gdx + (b * L + sg) * D + j, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (sg < L) __hip_atomic_fetch_add(gdx_row + sg * D + j, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
 #pragma unroll
         for (int base = 0; base < 3 * NU * T; base += 64) {
@@ -413,7 +441,7 @@ extern "C" __global__ __launch_bounds__(64 * NWB) void sig_bwd_lanes(const float
                 if (sg < L && r % 3 < nr) {
                     const float acc = row_sum(Vb + ((D + r) * T + t) * 64, lane);
                     const int j = (fl + r % 3) % D;
-                    __hip_atomic_fetch_add(gdx + (b * L + sg) * D + j, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_fetch_add(gdx_row + sg * D + j, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
         }

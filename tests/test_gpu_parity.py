@@ -445,6 +445,8 @@ WINDOW_SETS = [
     ("truncated", dict(d=3, depth=4)),
     ("truncated", dict(d=4, depth=6)),
     ("truncated", dict(d=5, depth=4)),
+    ("truncated", dict(d=6, depth=4)),           # a word per lane: 36 words of length 2
+    ("truncated", dict(d=3, depth=6)),           # a word per lane: 81 words of length 4, two wavefronts per row
     ("anisotropic", dict(d=4, weights=(1.0, 1.0, 2.0, 3.0), cutoff=5.0)),
     ("words", dict(d=6, n_words=500, max_len=5)),
 ]
@@ -460,6 +462,8 @@ def test_windows(case, B):
     d = kw["d"]
     words = random_prefix_closed_words(400 + case, d, kw["n_words"], kw["max_len"]) if kind == "words" else None
     ws, W = build_both(kind, d, depth=kw.get("depth"), weights=kw.get("weights"), cutoff=kw.get("cutoff"), words=words)
+    if kind == "truncated" and (d, kw["depth"]) in ((6, 4), (3, 6)):
+        assert ws.kernel_name(True, B * 11, 41) == "sig_bwd_lanes"
     L = 40                      # B = 13: 143 (path, window) rows, more than two wavefronts of rows for the lane = row kernels
     X = make_path("iid", 410 + case, B, L, d)
     windows = [(0, L), (0, 1), (0, 7), (0, 23), (5, 15), (10, 20), (15, 25), (39, 40), (17, 17), (3, 38), (5, 15)]
