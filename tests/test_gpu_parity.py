@@ -452,9 +452,10 @@ WINDOW_SETS = [
 ]
 
 
-@pytest.mark.parametrize("B", [5, 13])
+# table_driven: the fallback kernels, whose windows are gathered into padded sub-paths and scattered back
+@pytest.mark.parametrize("B,table_driven", [(5, False), (13, False), (5, True)])
 @pytest.mark.parametrize("case", range(len(WINDOW_SETS)))
-def test_windows(case, B):
+def test_windows(case, B, table_driven):
     """Signatures over user-given windows (expanding, sliding, overlapping, single-segment, empty, whole path) against
     one oracle evaluation per window, forward and backward."""
     import torch
@@ -462,7 +463,11 @@ def test_windows(case, B):
     d = kw["d"]
     words = random_prefix_closed_words(400 + case, d, kw["n_words"], kw["max_len"]) if kind == "words" else None
     ws, W = build_both(kind, d, depth=kw.get("depth"), weights=kw.get("weights"), cutoff=kw.get("cutoff"), words=words)
-    if kind == "truncated" and (d, kw["depth"]) in ((6, 4), (3, 6)):
+    if table_driven:
+        ws.set_option("no_jit", 1)
+        if ws.kernel_name(True, B * 11, 41) != "bwd_generic_kernel":
+            pytest.skip("a precompiled kernel serves this shape")
+    if not table_driven and kind == "truncated" and (d, kw["depth"]) in ((6, 4), (3, 6)):
         assert ws.kernel_name(True, B * 11, 41) == "sig_bwd_lanes"
     L = 40                      # B = 13: 143 (path, window) rows, more than two wavefronts of rows for the lane = row kernels
     X = make_path("iid", 410 + case, B, L, d)
