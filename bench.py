@@ -162,6 +162,15 @@ def roofline_entry(flops, ms, kernel=""):
             "traffic": None}
 
 
+def device_report(torch):
+    """What the device says of itself, and the FP32 vector rate that follows from its compute-unit count at the
+    published 2.4 GHz (x 4 SIMDs x 16 lanes x 2 flops x 2 for the packed / dual-issue forms): the roofline's peak."""
+    p = torch.cuda.get_device_properties(0)
+    cus = int(p.multi_processor_count)
+    return {"name": p.name, "arch": getattr(p, "gcnArchName", ""), "compute_units": cus,
+            "fp32_vector_tflops_at_2400_mhz": round(cus * 4 * 16 * 2 * 2 * 2.4e9 / 1e12, 1), "memory_bytes": int(p.total_memory)}
+
+
 def counter_traffic(kernel, workload):
     """HBM bytes per launch of `kernel` on `workload` from the rocprofv3 counter runs summarised under profiles/
     (FETCH_SIZE and WRITE_SIZE of a run of this program, scaled by a copy kernel of known size); None when that
@@ -353,6 +362,7 @@ def main():
         "roofline": dominant,
         "memory": {"peak_device_bytes": peak_mem, "mem_out_bytes": 4 * wl.B * ws.size,
                    "note": "inputs, outputs and workspaces of forward + backward held at once"},
+        "device": device_report(torch),
     }
     if wl.kind == "truncated" and ws.kernel_name(True).startswith("trunc_"):
         # reconstruction drift: the terminal signature stepped back through all L segments should end at zero
