@@ -101,6 +101,15 @@ const int32_t* sig_wordset_parent(const sig_wordset* ws);       /* host [|W|] */
 const int32_t* sig_wordset_letter(const sig_wordset* ws);       /* host [|W|] */
 const int32_t* sig_wordset_level_start(const sig_wordset* ws);  /* host [max_len + 2] */
 const int64_t* sig_wordset_user_index(const sig_wordset* ws);   /* host [n_user] or NULL */
+/* Sets other than full truncations that are closed under suffixes as well as prefixes (every anisotropic set of
+ * Definition 7.1; word lists that happen to be): the product of Section 2.1 restricted to such a set needs no word
+ * outside it, which is what the checkpointed calls below need.  sig_wordset_suffix_closed: 1 / 0 (-1 if ws NULL; 0 for
+ * full truncations, which have product kernels of their own).  sig_wordset_tail_table: host tables or NULL; for a
+ * word w of length n >= 2 and m = 1 .. n - 1, the index of w without its first m letters is
+ * tail_tab[tail_off[n] + (m - 1) * (level_start[n + 1] - level_start[n]) + (w - level_start[n])]; tail_off has
+ * max_len + 2 entries. */
+int            sig_wordset_suffix_closed(const sig_wordset* ws);
+const int32_t* sig_wordset_tail_table(const sig_wordset* ws, const int32_t** tail_off);
 
 /* Launch-shape knobs of a word set.  They are filled once, when the set is built, from the environment variables in
  * brackets, and changed afterwards only through sig_wordset_set_option; sig_forward / sig_backward never read the
@@ -235,9 +244,12 @@ int    sig_backward_residual(const sig_wordset* ws, const float* path, const flo
  * with the right factor taken at a chunk boundary), and inside a chunk the recursion is that of sig_backward
  * (Proposition 4.6).  Nothing is recomputed; the price is C times the memory of coeffs between the two calls, where
  * sig_forward / sig_backward keep the terminal signature alone (Section 4.2).  The library picks C for the batch
- * (2 .. 4, for full truncations whose backward kernel would otherwise leave SIMDs with a single wavefront: few
- * paths with many segments); where it sees no gain sig_checkpoint_bytes is 0, `checkpoint` is not touched and the
- * two calls are sig_forward / sig_backward.  Results agree with sig_forward / sig_backward to rounding. */
+ * (2 .. 4): for full truncations whose backward kernel would otherwise leave SIMDs with a single wavefront (few
+ * paths with many segments), and for suffix-closed sets (sig_wordset_suffix_closed) of up to 13,653 words that run
+ * through the run-time specialised kernels, which gain from more rows (four chunks for up to 128 paths, two up to
+ * 1,024, chunks of at least 64 segments).  Where it sees no gain sig_checkpoint_bytes is 0, `checkpoint` is not touched and
+ * the two calls are sig_forward / sig_backward; the same holds when a specialised kernel cannot be compiled (then
+ * `checkpoint` is left alone by both calls).  Results agree with sig_forward / sig_backward to rounding. */
 size_t sig_checkpoint_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
 size_t sig_forward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
 size_t sig_backward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);

@@ -73,6 +73,8 @@ def load_library():
     sig("sig_wordset_letter", c_p, [c_p])
     sig("sig_wordset_level_start", c_p, [c_p])
     sig("sig_wordset_user_index", c_p, [c_p])
+    sig("sig_wordset_suffix_closed", c_int, [c_p])
+    sig("sig_wordset_tail_table", c_p, [c_p, PP])
     sig("sig_wordset_min_fma_per_step", c_i64, [c_p])
     sig("sig_wordset_kernel_fma_per_step", c_i64, [c_p, c_int])
     sig("sig_wordset_plan_count", c_int, [c_p, c_int])
@@ -168,6 +170,21 @@ class WordSet:
     def user_index(self) -> np.ndarray:
         n = int(self._lib.sig_wordset_n_user(self._h))
         return _np_from_ptr(self._lib.sig_wordset_user_index(self._h), n, np.int64)
+
+    @property
+    def suffix_closed(self) -> bool:
+        return int(self._lib.sig_wordset_suffix_closed(self._h)) == 1
+
+    def tail_table(self):
+        """(tail_tab, tail_off) of a suffix-closed set, or None: see sig_wordset_tail_table."""
+        off = ctypes.c_void_p()
+        tab = self._lib.sig_wordset_tail_table(self._h, ctypes.byref(off))
+        if not tab:
+            return None
+        tail_off = _np_from_ptr(off.value, self.max_len + 2, np.int32)
+        ls = self.level_start
+        total = sum((n - 1) * int(ls[n + 1] - ls[n]) for n in range(2, self.max_len + 1))
+        return _np_from_ptr(tab, max(total, 1), np.int32), tail_off
 
     @property
     def lengths(self) -> np.ndarray:

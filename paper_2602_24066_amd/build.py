@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsig_mi355x.so")
-SOURCES = ["api.cpp", "wordset.cpp", "jit.cpp", "jit_lanes.cpp", "kernels_generic.hip", "kernels_trunc.hip", "kernels_chunk.hip"]
+SOURCES = ["api.cpp", "wordset.cpp", "jit.cpp", "jit_lanes.cpp", "kernels_generic.hip", "kernels_trunc.hip", "kernels_chunk.hip", "kernels_words.hip"]
 # -packed-fp32-ops is switched off on purpose: the packed FP32 forms are not used by this library.
 HIPCC_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
                "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument",

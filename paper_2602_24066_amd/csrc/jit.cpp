@@ -328,13 +328,18 @@ std::string jit_backward_source(const WordSet& ws, const Plan& plan, int NW, int
     const int nu = (int)plan.units.size();
     for (int u = 0; u < nu; ++u) emit_backward_unit(o, plan, u, ws.d);
     o << "extern \"C\" __global__ __launch_bounds__(NW * 64) void sig_bwd_jit(const float* __restrict__ dxT,\n"
-         "        const float* __restrict__ coeffs, const float* __restrict__ grad, long B, long L, long ntiles, long nW, float* gdx)\n{\n";
+         "        const float* __restrict__ coeffs, const float* __restrict__ grad, long B, long L, long ntiles, long nW, float* gdx,\n"
+         "        const float* __restrict__ coeffs_last, const float* __restrict__ grad_last, long C)\n{\n";
     o << "    __shared__ __attribute__((aligned(16))) float tile[T * D * 64];\n    __shared__ float gt[NW * GT_F];\n";
     o << "    const int lane = threadIdx.x & 63;\n    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);\n";
     o << "    const long b0 = (long)blockIdx.y * 64;\n    const long b = b0 + lane;\n    const long bc = b < B ? b : B - 1;\n";
     o << "    const float* dxg = dxT + (long)blockIdx.y * ntiles * (T * D * 64);\n";
     o << "    gdx += (long)blockIdx.y * ntiles * (T * D * 64);\n";
-    o << "    const float* cf = coeffs + bc * nW;\n    const float* gr = grad + bc * nW;\n";
+    // rows are the C time chunks of B / C paths: the last chunk of a path starts from the terminal signature and the
+    // gradient themselves (arrays of one row per path), the others from rows of the per-chunk arrays; C = 1: whole paths
+    o << "    const long pb = bc / C;\n    const bool last = bc - pb * C == C - 1;\n";
+    o << "    const float* cf = last ? coeffs_last + pb * nW : coeffs + bc * nW;\n";
+    o << "    const float* gr = last ? grad_last + pb * nW : grad + bc * nW;\n";
     o << "    const int unit = blockIdx.x * NW + wib;\n    switch (unit) {\n";
     for (int u = 0; u < nu; ++u)
         o << "        case " << u << ": bwd_unit_" << u << "(dxg, ntiles, L, tile, gt, gdx, b0, B, lane, wib, cf, gr); break;\n";

@@ -72,10 +72,14 @@ hipError_t grad_points(const float* gdx, int64_t B, int64_t P, int d, float* gra
 
 // Window list of a launch (signatures over windows): K windows per path, window k between the points win[2 k] and
 // win[2 k + 1] (device array, clamped to the path by the kernels), at most max_len segments; win == nullptr: no windows.
+// A list without windows but with K > 1 cuts every path into K time chunks of max_len segments (the last one shorter):
+// the rows of a launch over all (path, chunk) pairs.
 struct WindowList {
     const int64_t* win = nullptr;
     int64_t K = 0;
     int64_t max_len = 0;
+    __host__ __device__ bool several_rows() const { return win != nullptr || K > 1; }   // rows of one path share points
+    __host__ __device__ int64_t rows_per_path() const { return several_rows() ? K : 1; }
 };
 
 // Increments of B paths (or, with a window list, of the B * K windows of the paths: one row per (path, window) pair,
@@ -87,6 +91,25 @@ hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d,
 // the rows are windows and their gradients are added into grad_path (zeroed by the caller)
 hipError_t grad_points_transposed(const float* g, int64_t B, int64_t P, int d, int64_t Lpad, float* grad_path, hipStream_t stream,
                                   const WindowList& wl = WindowList());
+
+// Time chunks for word sets closed under prefixes and suffixes (kernels_words.hip).  Device tables of such a set:
+struct WordTables {
+    const uint32_t* prod_pairs = nullptr;   // terms of the product by word, see WordSet::prod_pairs
+    const uint32_t* adj_pairs = nullptr;    // the same terms by prefix, see WordSet::adj_pairs
+    const uint32_t* adj_key = nullptr;      // the prefix of every entry of adj_pairs (W: padding)
+    int adj_groups = 0;                     // entries of adj_pairs / 256
+    int32_t level_start[16] = {};           // [N + 2]
+    int32_t tail_off[16] = {};              // [N + 2]
+    int N = 0;                              // longest word (<= 14)
+    int W = 0;                              // number of words (<= 65,535)
+};
+size_t words_scan_lds_bytes(int64_t W);
+// S [B][C][W] chunk signatures.  Forward scan: rows[b][c] = S_0 (x) .. (x) S_c (if rows), last[b] = the product of all
+// (if last).  Reverse scan: rows[b][c] = S_{c+1} (x) .. (x) S_{C-1} for c <= C - 2 (row C - 1 is left alone).
+hipError_t words_scan(const WordTables& t, const float* S, int64_t B, int C, bool reverse, float* rows, float* last,
+                      hipStream_t stream);
+// Abar[b][c](u) = grad[b](u) + sum_v grad[b](u v) Q[b][c](v) for c <= C - 2; Q, Abar [B][C][W], rows C - 1 left alone
+hipError_t words_adjoint(const WordTables& t, const float* grad, const float* Q, int64_t B, int C, float* Abar, hipStream_t stream);
 
 // Register-resident kernels for full truncations (kernels_trunc.hip)
 bool trunc_forward_available(int d, int depth);

@@ -260,14 +260,20 @@ __global__ __launch_bounds__(kWave) void bwd_generic_kernel(const UnitDesc* __re
     }
 }
 
-// Row r of the specialised kernels: a whole path (no window list: path r, all P - 1 segments) or window r % K of path
-// r / K, between the points win[2 k] and win[2 k + 1] clamped to the path, at most max_len segments.
+// Row r of the specialised kernels: a whole path (no window list: path r, all P - 1 segments), time chunk r % K of path
+// r / K (K > 1 without windows: segments from (r % K) max_len on), or window r % K of path r / K, between the points
+// win[2 k] and win[2 k + 1] clamped to the path, at most max_len segments.
 __device__ __forceinline__ void lane_row(const WindowList& wl, int64_t r, int64_t P, int64_t& b, int64_t& first, int64_t& len)
 {
-    if (wl.win == nullptr) {
+    if (!wl.several_rows()) {
         b = r;
         first = 0;
         len = P - 1;
+    } else if (wl.win == nullptr) {                   // time chunk r % K of path r / K
+        b = r / wl.K;
+        first = (r - b * wl.K) * wl.max_len;
+        len = P - 1 - first < wl.max_len ? P - 1 - first : wl.max_len;
+        if (len < 0) len = 0;
     } else {
         b = r / wl.K;
         const int64_t k = r - b * wl.K;
@@ -399,7 +405,7 @@ hipError_t generic_backward(const GenericArgs& a, int max_len, hipStream_t strea
 hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d, int64_t Lpad, float* dxT, float* zeroed,
                                  hipStream_t stream, const WindowList& wl)
 {
-    const int64_t rows = B * (wl.win ? wl.K : 1);
+    const int64_t rows = B * wl.rows_per_path();
     const int64_t groups = (rows + kWave - 1) / kWave;
     if (groups <= 0 || Lpad <= 0 || d <= 0) return hipSuccess;
     const int TS = std::max(1, 64 / d);
@@ -441,7 +447,7 @@ __global__ void grad_points_transposed_kernel(const float* __restrict__ g, int64
         for (int e = lane; e < TS * d; e += kWave) {
             if (j0 + e / d <= len) {                          // the row has len + 1 points
                 const float v = tile[e * 65 + p] - tile[(e + d) * 65 + p];
-                if (wl.win) unsafeAtomicAdd(out + e, v);
+                if (wl.several_rows()) unsafeAtomicAdd(out + e, v);
                 else out[e] = v;
             }
         }
@@ -451,9 +457,9 @@ __global__ void grad_points_transposed_kernel(const float* __restrict__ g, int64
 hipError_t grad_points_transposed(const float* g, int64_t B, int64_t P, int d, int64_t Lpad, float* grad_path, hipStream_t stream,
                                   const WindowList& wl)
 {
-    const int64_t n_rows = B * (wl.win ? wl.K : 1);
+    const int64_t n_rows = B * wl.rows_per_path();
     const int64_t groups = (n_rows + kWave - 1) / kWave;
-    const int64_t points = (wl.win ? wl.max_len : P - 1) + 1;          // points a row can have
+    const int64_t points = (wl.several_rows() ? wl.max_len : P - 1) + 1;          // points a row can have
     if (groups <= 0 || points <= 0 || d <= 0) return hipSuccess;
     const int TS = std::max(1, 64 / d);
     const size_t lds = (size_t)(TS + 1) * d * 65 * sizeof(float);

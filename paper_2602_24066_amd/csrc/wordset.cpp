@@ -19,6 +19,102 @@ namespace sig {
 
 static const int64_t kMaxWords = (int64_t)SIG_MAX_WORDS;
 
+// Suffix structure of sets that are not full truncations (those have kernels and product rules of their own): the
+// word without its first letter, found through the word without first letter of the parent; if every such word is
+// in the set, the tables for products of signatures restricted to the set are appended to the device image (sets of
+// up to 65,535 words).
+static void suffix_tables(WordSet* ws)
+{
+    ws->suffix_closed = false;
+    ws->pair_tables = false;
+    const int64_t n = ws->size();
+    if (ws->kind == 0 || !ws->kernels_supported || n == 0 || n > 0x3fffffff) return;
+    for (int64_t k = 0; k < n; ++k)
+        if (ws->child_list[(size_t)k] != (int32_t)k) return;          // children of every word contiguous and in order
+    // child of word q (q = -1: the empty word) with last letter i, or -1
+    auto child = [&](int32_t q, int32_t i) -> int32_t {
+        for (int32_t k = ws->child_off[(size_t)(q + 1)]; k < ws->child_off[(size_t)(q + 2)]; ++k)
+            if (ws->letter[(size_t)k] == i) return k;
+        return -1;
+    };
+    std::vector<int32_t> tail((size_t)n, -1);                         // -1: the empty word (words of length 1)
+    for (int64_t w = 0; w < n; ++w) {
+        const int32_t p = ws->parent[(size_t)w];
+        if (p < 0) continue;
+        const int32_t t = child(tail[(size_t)p], ws->letter[(size_t)w]);   // parents precede their children
+        if (t < 0) return;                                             // a suffix is missing: not closed
+        tail[(size_t)w] = t;
+    }
+    ws->tail_off.assign((size_t)ws->max_len + 2, 0);
+    size_t total = 0;
+    for (int len = 2; len <= ws->max_len; ++len) {
+        ws->tail_off[(size_t)len] = (int32_t)total;
+        total += (size_t)(len - 1) * (size_t)(ws->level_start[(size_t)len + 1] - ws->level_start[(size_t)len]);
+    }
+    if (total > 0x7fffffff) return;
+    ws->tail_tab.assign(std::max<size_t>(total, 1), 0);
+    for (int len = 2; len <= ws->max_len; ++len) {
+        const int64_t lo = ws->level_start[(size_t)len], cnt = ws->level_start[(size_t)len + 1] - lo;
+        for (int64_t i = 0; i < cnt; ++i) {
+            int32_t t = (int32_t)(lo + i);
+            for (int m = 1; m < len; ++m) {
+                t = tail[(size_t)t];
+                ws->tail_tab[(size_t)ws->tail_off[(size_t)len] + (size_t)(m - 1) * (size_t)cnt + (size_t)i] = t;
+            }
+        }
+    }
+    ws->suffix_closed = true;
+    if (n > 0xffff) return;                                            // two word indices share an entry of the tables below
+    // Terms of the product (a (x) b)(w) = a(w) + b(w) + sum_m a(w_1..w_m) b(w_{m+1}..w_n), in two orders:
+    // prod_pairs, laid out like tail_tab (word-major per length: entry (m, w) = prefix | suffix << 16), for the product
+    // itself, and adj_pairs, grouped by the prefix u (entries adj_off[u] .. adj_off[u + 1]: w | suffix << 16, by length
+    // of w, then w; adj_key holds u for every entry), for sums over all words that extend u.
+    ws->prod_pairs.assign(ws->tail_tab.size(), 0);
+    ws->adj_off.assign((size_t)n + 1, 0);
+    for (int len = 2; len <= ws->max_len; ++len) {
+        const int64_t lo = ws->level_start[(size_t)len], cnt = ws->level_start[(size_t)len + 1] - lo;
+        for (int64_t i = 0; i < cnt; ++i) {
+            int32_t p = (int32_t)(lo + i);
+            for (int m = len - 1; m >= 1; --m) {
+                p = ws->parent[(size_t)p];                             // the prefix of m letters
+                const size_t at = (size_t)ws->tail_off[(size_t)len] + (size_t)(m - 1) * (size_t)cnt + (size_t)i;
+                ws->prod_pairs[at] = (uint32_t)p | ((uint32_t)ws->tail_tab[at] << 16);
+                ws->adj_off[(size_t)p + 1]++;
+            }
+        }
+    }
+    for (int64_t u = 0; u < n; ++u) ws->adj_off[(size_t)u + 1] += ws->adj_off[(size_t)u];
+    // padded to whole groups of 256 terms with terms of the dummy prefix n, so that the kernel needs no bounds checks
+    const size_t n_terms = ((size_t)ws->adj_off[(size_t)n] + 255) / 256 * 256;
+    ws->adj_pairs.assign(std::max<size_t>(n_terms, 256), 0);
+    ws->adj_key.assign(ws->adj_pairs.size(), (uint32_t)n);
+    {
+        std::vector<int32_t> fill(ws->adj_off.begin(), ws->adj_off.end() - 1);
+        for (int len = 2; len <= ws->max_len; ++len) {
+            const int64_t lo = ws->level_start[(size_t)len], cnt = ws->level_start[(size_t)len + 1] - lo;
+            for (int64_t i = 0; i < cnt; ++i) {
+                int32_t p = (int32_t)(lo + i);
+                for (int m = len - 1; m >= 1; --m) {
+                    p = ws->parent[(size_t)p];
+                    const size_t at = (size_t)ws->tail_off[(size_t)len] + (size_t)(m - 1) * (size_t)cnt + (size_t)i;
+                    ws->adj_key[(size_t)fill[(size_t)p]] = (uint32_t)p;
+                    ws->adj_pairs[(size_t)fill[(size_t)p]++] = (uint32_t)(lo + i) | ((uint32_t)ws->tail_tab[at] << 16);
+                }
+            }
+        }
+    }
+    auto append = [&](const void* src, size_t bytes) {
+        const size_t off = (ws->image.size() + 255) & ~(size_t)255;
+        ws->image.resize(off + ((bytes + 255) & ~(size_t)255), 0);
+        std::memcpy(&ws->image[off], src, bytes);
+        return off;
+    };
+    ws->dev_prod_off = append(ws->prod_pairs.data(), ws->prod_pairs.size() * sizeof(uint32_t));
+    ws->dev_adj_key_off = append(ws->adj_key.data(), ws->adj_key.size() * sizeof(uint32_t));
+    ws->dev_adj_pairs_off = append(ws->adj_pairs.data(), ws->adj_pairs.size() * sizeof(uint32_t));
+    ws->pair_tables = true;
+}
+
 // Fills everything that follows from (parent, letter, level_start).
 static int finish(WordSet* ws)
 {
@@ -81,6 +177,7 @@ static int finish(WordSet* ws)
             if (!p.ops.empty()) std::memcpy(&ws->image[po.ops], p.ops.data(), p.ops.size() * sizeof(uint32_t));
             if (!p.slot_word.empty()) std::memcpy(&ws->image[po.slots], p.slot_word.data(), p.slot_word.size() * sizeof(int32_t));
         }
+    suffix_tables(ws);
     return SIG_OK;
 }
 

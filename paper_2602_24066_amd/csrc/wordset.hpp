@@ -76,6 +76,19 @@ struct WordSet {
     int lyn_pairs = 0;
     std::vector<int32_t> lyn_inv_off, lyn_inv;
     size_t lyn_len_off = 0, lyn_sub_off = 0, lyn_inv_off_off = 0, lyn_inv_ent_off = 0;    // offsets in the device image
+    // Sets closed under suffixes as well (every anisotropic set; word lists that happen to be): the tensor product of
+    // two elements restricted to the set needs nothing outside it, (a (x) b)(w) = sum_k a(w_1..k) b(w_k+1..n), so the
+    // segments of a path can be cut into time chunks whose signatures are multiplied afterwards (Chen's relation).
+    // tail_tab: for every length n >= 2 and m = 1..n-1, the index of each word of length n without its first m
+    // letters, at tail_tab[tail_off[n] + (m - 1) * (words of length n) + (w - level_start[n])].
+    bool suffix_closed = false;
+    std::vector<int32_t> tail_tab;
+    std::vector<int32_t> tail_off;     // [max_len + 2]
+    // the terms of the product in the two orders the kernels read, two 16-bit word indices per entry (see wordset.cpp)
+    bool pair_tables = false;
+    std::vector<uint32_t> prod_pairs, adj_pairs, adj_key;
+    std::vector<int32_t> adj_off;      // [|W| + 1] (host only)
+    size_t dev_prod_off = 0, dev_adj_key_off = 0, dev_adj_pairs_off = 0;    // offsets in the device image (pair_tables only)
     void* dev = nullptr;
     int dev_id = -1;                   // device the image was uploaded to (a word-set object serves one device)
     // Launch-shape knobs.  Filled once when the set is built (from the SIG_* environment variables of that moment) and

@@ -160,6 +160,69 @@ def test_checkpointed_forward_and_backward(d, depth, B, L, chunks):
     assert gerr.max() <= BWD_TOL, f"checkpointed backward: {gerr.max():.3e}"
 
 
+def _no_repeat_words(d, n):
+    """Words of up to n letters in which no letter follows itself: closed under prefixes and suffixes."""
+    out, level = [], [(i,) for i in range(d)]
+    for _ in range(n):
+        out += level
+        level = [w + (i,) for w in level for i in range(d) if i != w[-1]]
+    return out
+
+
+# The same pair of calls on word sets closed under suffixes (anisotropic sets; a word list that is): chunk counts by the
+# library's rule and forced, chunk lengths that do not divide L, a batch of more than one lane group, against the
+# oracle; and a list that lacks suffixes, which takes no chunks.  (Every length of these sets has several words: a length
+# with a single word is ill-conditioned under the forward error measure for any summation order.)
+WORD_CHUNK_CASES = {
+    "aniso3": ("anisotropic", 3, (1.0, 1.25, 1.5), 4.5, None, 5, 200, 0, 3),
+    "aniso6": ("anisotropic", 6, (1, 1, 2, 2, 3, 3), 8.0, None, 70, 257, 0, 4),
+    "aniso2-forced": ("anisotropic", 2, (0.3, 0.4), 1.6, None, 3, 300, 2, 2),
+    "no-repeat": ("list", 3, None, None, "no-repeat", 9, 130, 0, 2),
+    "random": ("list", 4, None, None, "random", 4, 200, 0, 0),
+}
+
+
+@pytest.mark.parametrize("case", list(WORD_CHUNK_CASES))
+def test_checkpointed_word_sets(case):
+    import torch
+    kind, d, weights, cutoff, which, B, L, forced, expect_chunks = WORD_CHUNK_CASES[case]
+    words = None
+    if which == "no-repeat":
+        words = _no_repeat_words(d, 5)
+    elif which == "random":
+        words = random_prefix_closed_words(11, d, 80, 5)
+    ws, W = build_both(kind, d, weights=weights, cutoff=cutoff, words=words)
+    if forced:
+        ws.set_option("ckpt_chunks", forced)
+    assert ws.suffix_closed == (which != "random")
+    lib = S.load_library()
+    nck = int(lib.sig_checkpoint_bytes(ws._h, B, L + 1))
+    assert nck == (4 * B * expect_chunks * ws.size + 255) // 256 * 256
+    X = make_path("iid", 5100 + L, B, L, d)
+    G = make_grad_coeffs(5200 + L, B, ws.size)
+    xp, grad = torch.from_numpy(X).cuda(), torch.from_numpy(G).cuda()
+    coeffs, ck = S.sig_forward_checkpointed(ws, xp)
+    gp = S.sig_backward_checkpointed(ws, xp, coeffs, grad, ck)
+    plain = S.sig_forward(ws, xp)
+    gplain = S.sig_backward(ws, xp, plain, grad)
+    torch.cuda.synchronize()
+    if expect_chunks:                      # the checkpoint holds the signatures of the chunks: the first is that of the first Lc segments
+        Lc = -(-L // expect_chunks)
+        first = ck.view(torch.float32)[: B * expect_chunks * ws.size].view(B, expect_chunks, ws.size)[:, 0].cpu().numpy()
+        ref_first = O.forward_words(np.ascontiguousarray(X[:, : Lc + 1]), W)
+        for n, e in O.level_errors(first, ref_first, np.array([len(w) for w in W])).items():
+            assert e <= FWD_TOL, f"{case}: first chunk signature, level {n}: {e:.3e}"
+    coeffs, gp = coeffs.cpu().numpy(), gp.cpu().numpy()
+    lengths = np.array([len(w) for w in W])
+    ref = O.forward_words(X, W)
+    for n, e in O.level_errors(coeffs, ref, lengths).items():
+        assert e <= FWD_TOL, f"{case}: checkpointed forward, level {n}: {e:.3e}"
+    gref = O.backward_words(X, W, G.astype(np.float64))
+    gerr = O.grad_errors(gp, gref)
+    assert gerr.max() <= BWD_TOL, f"{case}: checkpointed backward: {gerr.max():.3e}"
+    assert O.grad_errors(gplain.cpu().numpy(), gref).max() <= BWD_TOL
+
+
 # Every tile shape of the d = 16 and d = 8 backward kernels, forced on batches far too small to take them by themselves:
 # tiles that do not divide the number of segments, a single ragged tile, with and without time chunks
 @pytest.mark.parametrize("d,depth,tile", [(16, 4, 4), (16, 4, 8), (16, 4, 12), (16, 4, 16), (8, 5, 4), (8, 5, 8), (8, 5, 16)])
@@ -713,9 +776,9 @@ FULL = {
 }
 
 
-# (name, checkpointed): the benchmark times the checkpointed pair of calls where the library offers it (c3, c5) and
-# the plain pair beside it
-@pytest.mark.parametrize("name,checkpointed", [(n, False) for n in FULL] + [("c3", True), ("c5", True)])
+# (name, checkpointed): the benchmark times the checkpointed pair of calls where the library offers it (c3, c4a, c5)
+# and the plain pair beside it
+@pytest.mark.parametrize("name,checkpointed", [(n, False) for n in FULL] + [("c3", True), ("c4a", True), ("c5", True)])
 def test_full_size_workloads(name, checkpointed):
     wl = WORKLOADS[name]
     ws, W = build_for_workload(wl)

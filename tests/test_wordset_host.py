@@ -391,6 +391,65 @@ def test_time_chunk_workspace():
     assert lib.sig_backward_workspace_bytes(ws._h, 2, 1025) == gdx       # backward is not chunked by itself
 
 
+def _no_repeat_words(d, n):
+    """Words of up to n letters in which no letter follows itself: closed under prefixes and suffixes."""
+    out, level = [], [(i,) for i in range(d)]
+    for _ in range(n):
+        out += level
+        level = [w + (i,) for w in level for i in range(d) if i != w[-1]]
+    return out
+
+
+@pytest.mark.parametrize("case", ["anisotropic", "anisotropic-c4", "no-repeat list", "random list", "truncation"])
+def test_suffix_tables(case):
+    """Sets closed under suffixes carry, for every word, the indices of the word without its first m letters; the
+    table is checked against the words written out as tuples.  Sets that lack a suffix, and full truncations (which
+    have product kernels of their own), carry none."""
+    if case == "anisotropic":
+        ws, words = S.sig_wordset_build_anisotropic(3, (1.0, 2.0, 1.5), 4.0), O.anisotropic_words(3, (1.0, 2.0, 1.5), 4.0)
+    elif case == "anisotropic-c4":
+        ws, words = S.sig_wordset_build_anisotropic(6, (1, 1, 2, 2, 3, 3), 8.0), O.anisotropic_words(6, (1, 1, 2, 2, 3, 3), 8.0)
+    elif case == "no-repeat list":
+        given = _no_repeat_words(3, 5)
+        ws, words = S.sig_wordset_build(3, given), O.prefix_closure(given)
+    elif case == "random list":
+        given = random_prefix_closed_words(7, 4, 60, 5)
+        ws, words = S.sig_wordset_build(4, given), O.prefix_closure(given)
+        index = {tuple(w): k for k, w in enumerate(words)}
+        assert any(tuple(w[1:]) not in index for w in words if len(w) > 1)      # the case is what it says
+        assert not ws.suffix_closed and ws.tail_table() is None
+        assert S.load_library().sig_checkpoint_bytes(ws._h, 64, 513) == 0
+        return
+    else:
+        ws = S.sig_wordset_build_truncated(3, 4)
+        assert not ws.suffix_closed and ws.tail_table() is None
+        return
+    assert ws.suffix_closed
+    index = {tuple(w): k for k, w in enumerate(words)}
+    tab, off = ws.tail_table()
+    ls = ws.level_start
+    seen = 0
+    for k, w in enumerate(words):
+        n = len(w)
+        cnt = int(ls[n + 1] - ls[n])
+        for m in range(1, n):
+            assert tab[off[n] + (m - 1) * cnt + (k - ls[n])] == index[tuple(w[m:])]
+            seen += 1
+    assert seen == sum(len(w) - 1 for w in words) and seen > 0
+    # the checkpointed calls offer time chunks for such a set: four up to 128 paths, two up to 1,024, chunks of at least 64 segments
+    lib = S.load_library()
+    per_row = 4 * ws.size
+    assert lib.sig_checkpoint_bytes(ws._h, 128, 513) == (per_row * 128 * 4 + 255) // 256 * 256
+    assert lib.sig_checkpoint_bytes(ws._h, 512, 513) == (per_row * 512 * 2 + 255) // 256 * 256
+    assert lib.sig_checkpoint_bytes(ws._h, 1024, 513) == (per_row * 1024 * 2 + 255) // 256 * 256
+    assert lib.sig_checkpoint_bytes(ws._h, 2048, 513) == 0 and lib.sig_checkpoint_bytes(ws._h, 512, 101) == 0
+    assert lib.sig_checkpoint_bytes(ws._h, 5, 201) == (per_row * 5 * 3 + 255) // 256 * 256
+    assert lib.sig_forward_checkpointed_workspace_bytes(ws._h, 512, 513) >= lib.sig_forward_workspace_bytes(ws._h, 512, 513)
+    assert lib.sig_backward_checkpointed_workspace_bytes(ws._h, 512, 513) >= lib.sig_backward_workspace_bytes(ws._h, 512, 513)
+    ws.set_option("no_jit", 1)                                                 # the table-driven kernels take whole paths
+    assert lib.sig_checkpoint_bytes(ws._h, 512, 513) == 0
+
+
 GRAPHS = [
     (4, [(a, b) for a in range(4) for b in range(4)], 4),                      # complete graph with loops: the truncation
     (5, [(i, i + 1) for i in range(4)], 5),                                    # a chain
