@@ -110,6 +110,13 @@ const int64_t* sig_wordset_user_index(const sig_wordset* ws);   /* host [n_user]
  * max_len + 2 entries. */
 int            sig_wordset_suffix_closed(const sig_wordset* ws);
 const int32_t* sig_wordset_tail_table(const sig_wordset* ws, const int32_t** tail_off);
+/* The terms (w, m) of the product (a (x) b)(w) = a(w) + b(w) + sum_m a(w_1..w_m) b(w_m+1..w_n) as the kernels of the
+ * checkpointed calls read them (suffix-closed sets of up to 65,535 words; returns -1 otherwise), host arrays:
+ * prod_pairs, laid out like the tail table, entry (m, w) = prefix | suffix << 16; adj_pairs / adj_key, the same terms
+ * sorted by their prefix u = w_1..w_m: adj_pairs = w | suffix << 16, adj_key = u, *n_adj entries, a multiple of 256
+ * (padding entries carry the key |W|).  Returns the number of entries of prod_pairs. */
+int64_t        sig_wordset_term_tables(const sig_wordset* ws, const uint32_t** prod_pairs, const uint32_t** adj_pairs,
+                                       const uint32_t** adj_key, int64_t* n_adj);
 
 /* Launch-shape knobs of a word set.  They are filled once, when the set is built, from the environment variables in
  * brackets, and changed afterwards only through sig_wordset_set_option; sig_forward / sig_backward never read the

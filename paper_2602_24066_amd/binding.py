@@ -75,6 +75,7 @@ def load_library():
     sig("sig_wordset_user_index", c_p, [c_p])
     sig("sig_wordset_suffix_closed", c_int, [c_p])
     sig("sig_wordset_tail_table", c_p, [c_p, PP])
+    sig("sig_wordset_term_tables", c_i64, [c_p, PP, PP, PP, ctypes.POINTER(c_i64)])
     sig("sig_wordset_min_fma_per_step", c_i64, [c_p])
     sig("sig_wordset_kernel_fma_per_step", c_i64, [c_p, c_int])
     sig("sig_wordset_plan_count", c_int, [c_p, c_int])
@@ -185,6 +186,15 @@ class WordSet:
         ls = self.level_start
         total = sum((n - 1) * int(ls[n + 1] - ls[n]) for n in range(2, self.max_len + 1))
         return _np_from_ptr(tab, max(total, 1), np.int32), tail_off
+
+    def term_tables(self):
+        """(prod_pairs, adj_pairs, adj_key) of a suffix-closed set, or None: see sig_wordset_term_tables."""
+        pp, ap, ak, n_adj = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_int64()
+        n = int(self._lib.sig_wordset_term_tables(self._h, ctypes.byref(pp), ctypes.byref(ap), ctypes.byref(ak), ctypes.byref(n_adj)))
+        if n < 0:
+            return None
+        return (_np_from_ptr(pp.value, n, np.uint32), _np_from_ptr(ap.value, n_adj.value, np.uint32),
+                _np_from_ptr(ak.value, n_adj.value, np.uint32))
 
     @property
     def lengths(self) -> np.ndarray:

@@ -644,6 +644,16 @@ const int32_t* sig_wordset_tail_table(const sig_wordset* ws, const int32_t** tai
     if (tail_off) *tail_off = W(ws)->tail_off.data();
     return W(ws)->tail_tab.data();
 }
+int64_t sig_wordset_term_tables(const sig_wordset* ws, const uint32_t** prod_pairs, const uint32_t** adj_pairs,
+                                const uint32_t** adj_key, int64_t* n_adj)
+{
+    if (!ws || !W(ws)->pair_tables) return -1;
+    if (prod_pairs) *prod_pairs = W(ws)->prod_pairs.data();
+    if (adj_pairs) *adj_pairs = W(ws)->adj_pairs.data();
+    if (adj_key) *adj_key = W(ws)->adj_key.data();
+    if (n_adj) *n_adj = (int64_t)W(ws)->adj_pairs.size();
+    return (int64_t)W(ws)->prod_pairs.size();
+}
 int64_t sig_wordset_min_fma_per_step(const sig_wordset* ws) { return ws ? W(ws)->min_fma : -1; }
 
 int64_t sig_wordset_kernel_fma_per_step(const sig_wordset* ws, int backward)

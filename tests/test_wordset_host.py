@@ -450,6 +450,54 @@ def test_suffix_tables(case):
     assert lib.sig_checkpoint_bytes(ws._h, 512, 513) == 0
 
 
+@pytest.mark.parametrize("case", ["anisotropic", "no-repeat list"])
+def test_term_tables_reproduce_chens_relation(case):
+    """The term tables the chunk kernels read, applied in numpy to oracle signatures of two pieces of a path, give the
+    oracle signature of the whole path (eq. 2 restricted to the set); the prefix-sorted copy of the terms gives the
+    derivative of <g, a (x) q> with respect to a (Proposition 4.1 at a chunk boundary)."""
+    if case == "anisotropic":
+        d = 3
+        ws, words = S.sig_wordset_build_anisotropic(d, (1.0, 1.25, 1.5), 4.5), O.anisotropic_words(d, (1.0, 1.25, 1.5), 4.5)
+    else:
+        d = 3
+        given = _no_repeat_words(d, 5)
+        ws, words = S.sig_wordset_build(d, given), O.prefix_closure(given)
+    n = len(words)
+    prod, adj, key = ws.term_tables()
+    ls, (_, tail_off) = ws.level_start, ws.tail_table()
+    lengths = ws.lengths
+    assert len(adj) % 256 == 0 and (key[np.count_nonzero(key < n):] == n).all() and (np.diff(key.astype(np.int64)) >= 0).all()
+    assert np.count_nonzero(key < n) == int((lengths - 1).sum())
+
+    def product(a, b):
+        out = a + b
+        for k in range(n):
+            ln = int(lengths[k])
+            cnt = int(ls[ln + 1] - ls[ln])
+            for m in range(ln - 1):
+                pr = int(prod[tail_off[ln] + m * cnt + (k - ls[ln])])
+                out[k] += a[pr & 0xffff] * b[pr >> 16]
+        return out
+
+    X = make_path("iid", 77, 1, 40, d).astype(np.float64)
+    X = X.astype(np.float32)
+    a = O.forward_words(np.ascontiguousarray(X[:, :16]), words)[0]
+    b = O.forward_words(np.ascontiguousarray(X[:, 15:]), words)[0]
+    whole = O.forward_words(X, words)[0]
+    np.testing.assert_allclose(product(a, b), whole, rtol=1e-10, atol=1e-12)
+    # not commutative: the tables hold prefix and suffix in this order
+    assert np.abs(product(b, a) - whole).max() > 1e-6
+    rng = np.random.default_rng(5)
+    g, a2 = rng.standard_normal(n), rng.standard_normal(n)
+    abar = g.copy()
+    for t in range(len(adj)):
+        if key[t] < n:
+            abar[key[t]] += g[adj[t] & 0xffff] * b[adj[t] >> 16]
+    lhs = float(abar @ (a - a2))
+    rhs = float(g @ (product(a, b) - product(a2, b)))
+    assert abs(lhs - rhs) <= 1e-10 * max(1.0, abs(rhs))
+
+
 GRAPHS = [
     (4, [(a, b) for a in range(4) for b in range(4)], 4),                      # complete graph with loops: the truncation
     (5, [(i, i + 1) for i in range(4)], 5),                                    # a chain
