@@ -298,26 +298,31 @@ __global__ void increments_transposed_kernel(const float* __restrict__ path, int
     const int64_t g = blockIdx.x / tiles;
     const int64_t j0 = (blockIdx.x % tiles) * TS;
     const int R = TS * d;
-    // 16 rows per wavefront (workgroups of 256 threads); the loads of all of them are issued before the first is used
+    // 16 rows per wavefront (workgroups of 256 threads).  Every load is issued unconditionally, from a clamped
+    // address, before the first value is used: behind a branch per row the sixteen round trips to memory would run one
+    // after the other.
     for (int e0 = 0; e0 < R; e0 += kWave) {
         const int e = e0 + lane;
-        float v[16];
+        const int64_t seg = j0 + e / d;
+        int64_t off[16];
+        bool ok[16];
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
             const int64_t r = g * kWave + wave * 16 + q;
-            v[q] = 0.0f;
-            if (r < R_rows && e < R) {
-                int64_t b, first, len;
-                lane_row(wl, r, P, b, first, len);
-                if (j0 + e / d < len) {
-                    const float* row = path + (b * P + first + j0) * d;
-                    v[q] = row[e + d] - row[e];
-                }
-            }
+            int64_t b = 0, first = 0, len = 0;
+            if (r < R_rows) lane_row(wl, r, P, b, first, len);             // uniform over the wavefront
+            ok[q] = e < R && seg < len;                                    // then point first + seg + 1 <= P - 1
+            off[q] = ok[q] ? (b * P + first + j0) * d + e : 0;             // path[0], path[d] exist: P >= 2
+        }
+        float hi[16], lo[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            hi[q] = path[off[q] + d];
+            lo[q] = path[off[q]];
         }
         if (e < R) {
 #pragma unroll
-            for (int q = 0; q < 16; ++q) tile[e * 65 + wave * 16 + q] = v[q];
+            for (int q = 0; q < 16; ++q) tile[e * 65 + wave * 16 + q] = ok[q] ? hi[q] - lo[q] : 0.0f;
         }
     }
     __syncthreads();
@@ -432,9 +437,22 @@ __global__ void grad_points_transposed_kernel(const float* __restrict__ g, int64
     const int rows = (TS + 1) * d;
     int64_t my_b, my_first, my_len = 0;                      // this lane's row: segments past its length count as zero
     if (grp * kWave + lane < R_rows) lane_row(wl, grp * kWave + lane, P, my_b, my_first, my_len);
-    for (int r = wave; r < rows; r += nwaves) {
-        const int64_t j = j0 - 1 + r / d;
-        tile[r * 65 + lane] = (j >= 0 && j < my_len) ? g[((grp * Lpad + j) * d + r % d) * kWave + lane] : 0.0f;
+    // eight loads in flight per lane, each from a clamped address (every segment below Lpad exists in g)
+    for (int r0 = wave; r0 < rows; r0 += nwaves * 8) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int r = r0 + k * nwaves;
+            const int64_t j = j0 - 1 + r / d;
+            const int64_t jc = j < 0 ? 0 : (j >= Lpad ? Lpad - 1 : j);
+            v[k] = g[((grp * Lpad + jc) * d + r % d) * kWave + lane];
+            if (j < 0 || j >= my_len) v[k] = 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int r = r0 + k * nwaves;
+            if (r < rows) tile[r * 65 + lane] = v[k];
+        }
     }
     __syncthreads();
     for (int q = 0; q < 16; ++q) {

@@ -656,6 +656,58 @@ def test_step_captured_in_a_graph(kind, d, depth, B, L):
             assert O.grad_errors(g_graph, O.backward_words(X, W, G.astype(np.float64))).max() <= BWD_TOL
 
 
+@pytest.mark.parametrize("kind,d,depth,B,L", [("anisotropic", 3, None, 5, 200), ("anisotropic", 3, None, 3, 130), ("truncated", 8, 5, 2, 200)])
+def test_checkpointed_step_captured_in_a_graph(kind, d, depth, B, L):
+    """The pair of calls that keeps the time-chunk signatures, recorded into a HIP graph with its checkpoint and
+    workspaces (kernels only: the clearing is a kernel, the products and boundary adjoints are kernels) and replayed
+    on new inputs with eager work between the replays."""
+    import torch
+    ws, W = build_both(kind, d, depth=depth, weights=(1.0, 1.25, 1.5), cutoff=4.5)
+    lib = S.load_library()
+    nck = int(lib.sig_checkpoint_bytes(ws._h, B, L + 1))
+    assert nck > 0
+    xp = torch.from_numpy(make_path("iid", 1800, B, L, d)).cuda()
+    grad = torch.from_numpy(make_grad_coeffs(1801, B, ws.size)).cuda()
+    coeffs = torch.empty((B, ws.size), dtype=torch.float32, device="cuda")
+    gpath = torch.empty((B, L + 1, d), dtype=torch.float32, device="cuda")
+    ck = torch.empty(nck, dtype=torch.uint8, device="cuda")
+    wf = torch.empty(max(int(lib.sig_forward_checkpointed_workspace_bytes(ws._h, B, L + 1)), 256), dtype=torch.uint8, device="cuda")
+    wb = torch.empty(max(int(lib.sig_backward_checkpointed_workspace_bytes(ws._h, B, L + 1)), 256), dtype=torch.uint8, device="cuda")
+
+    def step():
+        S.sig_forward_checkpointed(ws, xp, out=coeffs, checkpoint=ck, workspace=wf)
+        S.sig_backward_checkpointed(ws, xp, coeffs, grad, ck, out=gpath, workspace=wb)
+
+    step()                                   # compiles / sets kernel attributes outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    lengths = np.array([len(w) for w in W])
+    for rep in range(3):
+        X = make_path("iid", 1810 + rep, B, L, d)
+        G = make_grad_coeffs(1820 + rep, B, ws.size)
+        xp.copy_(torch.from_numpy(X).cuda())
+        grad.copy_(torch.from_numpy(G).cuda())
+        coeffs.zero_()
+        gpath.fill_(7.0)
+        ck.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        c_graph, g_graph = coeffs.cpu().numpy(), gpath.cpu().numpy()
+        c_eager, ck_eager = S.sig_forward_checkpointed(ws, xp)
+        g_eager = S.sig_backward_checkpointed(ws, xp, c_eager, grad, ck_eager)
+        torch.cuda.synchronize()
+        assert np.array_equal(c_graph, c_eager.cpu().numpy()), f"replay {rep}: forward differs from the eager call"
+        assert O.grad_errors(g_graph, g_eager.cpu().numpy().astype(np.float64)).max() <= 1e-5, f"replay {rep}"
+        if rep == 0:
+            ref = O.forward_dense(X, depth) if kind == "truncated" else O.forward_words(X, W)
+            for n, e in O.level_errors(c_graph, ref, lengths).items():
+                assert e <= FWD_TOL, (n, e)
+            gref = O.backward_dense(X, depth, G.astype(np.float64)) if kind == "truncated" else O.backward_words(X, W, G.astype(np.float64))
+            assert O.grad_errors(g_graph, gref).max() <= BWD_TOL
+
+
 def test_code_object_from_the_disk_cache_runs(tmp_path, monkeypatch):
     """A kernel loaded from SIG_JIT_CACHE instead of compiled gives the results of the compiled one, bit for bit."""
     import torch
