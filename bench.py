@@ -335,7 +335,9 @@ def main():
                           "mfma8_16x16x4": round(S.sig_probe_issue_ns(2, w), 1),
                           "fma64_and_mfma8_interleaved": round(S.sig_probe_issue_ns(3, w), 1),
                           "fma64_sources_in_one_register_bank": round(S.sig_probe_issue_ns(4, w), 1),
-                          "fma64_sources_in_three_register_banks": round(S.sig_probe_issue_ns(5, w), 1)} for w in (1, 2, 4)}
+                          "fma64_sources_in_three_register_banks": round(S.sig_probe_issue_ns(5, w), 1),
+                          "fma64_accumulator_and_multiplier_in_one_bank": round(S.sig_probe_issue_ns(6, w), 1),
+                          "fma64_multiplier_and_addend_in_one_bank": round(S.sig_probe_issue_ns(7, w), 1)} for w in (1, 2, 4)}
 
     out = {
         "metric": "signature coeff-steps/sec (fwd, fwd+bwd) + % of FP32 vector roofline, 1 GPU",

@@ -352,7 +352,9 @@ int sig_probe_fma(void* out /*device*/, size_t out_bytes, int blocks, int iters,
  *   0: 64 multiply-adds whose operands are all vector registers      1: 64 multiply-adds with a scalar-register multiplier
  *   2: 8 matrix instructions 16x16x4 (fp32)                            3: the 64 multiply-adds of 0 interleaved with the 8 of 2
  *   4: 64 multiply-adds whose three source registers share a register bank (register number mod 4)
- *   5: the same with the three source registers in three different banks (4 and 5 name their registers in the instruction)
+ *   5: the same with the three source registers in three different banks
+ *   6: accumulator and multiplier in one bank, the addend in another      7: multiplier and addend in one bank, the accumulator in another
+ *      (4 .. 7 name their registers in the instruction)
  * out: device, blocks * 256 floats.  The caller times the launch; with 256 blocks a SIMD holds one wavefront, with 512 two. */
 int sig_probe_issue(void* out /*device*/, size_t out_bytes, int blocks, int iters, int mode, void* stream);
 

@@ -1513,7 +1513,7 @@ int sig_probe_fma(void* out, size_t out_bytes, int blocks, int iters, void* stre
 
 int sig_probe_issue(void* out, size_t out_bytes, int blocks, int iters, int mode, void* stream)
 {
-    if (!out || blocks < 1 || iters < 1 || mode < 0 || mode > 5) return SIG_EINVAL;
+    if (!out || blocks < 1 || iters < 1 || mode < 0 || mode > 7) return SIG_EINVAL;
     if (out_bytes < (size_t)blocks * 256 * sizeof(float)) return SIG_EWORKSPACE;
     hipError_t e = sig::issue_probe((float*)out, blocks, iters, mode, (hipStream_t)stream);
     return e == hipSuccess ? SIG_OK : hip_fail(e);

@@ -872,7 +872,7 @@ __global__ __launch_bounds__(256) void issue_probe_kernel(float* out, int iters,
 // Modes 4 and 5: the same 64 multiply-adds per iteration with the registers named in the instruction, so that the
 // three source operands of every instruction lie in one register bank (register number mod 4; mode 4) or in three
 // different banks (mode 5).  Compiled code cannot choose: its operands fall into banks as the allocator places them.
-#define SIG_PROBE_CLOBBERS "v32", "v36", "v40", "v44", "v48", "v52", "v56", "v60", "v64", "v65", "v68", "v70"
+#define SIG_PROBE_CLOBBERS "v32", "v36", "v40", "v44", "v48", "v52", "v56", "v60", "v64", "v65", "v68", "v69", "v70"
 #define SIG_PROBE_ROUND(M, A)                                                                                          \
     "v_fma_f32 v32, v32, " M ", " A "\n v_fma_f32 v36, v36, " M ", " A "\n v_fma_f32 v40, v40, " M ", " A "\n"           \
     "v_fma_f32 v44, v44, " M ", " A "\n v_fma_f32 v48, v48, " M ", " A "\n v_fma_f32 v52, v52, " M ", " A "\n"           \
@@ -880,17 +880,22 @@ __global__ __launch_bounds__(256) void issue_probe_kernel(float* out, int iters,
 #define SIG_PROBE_BODY(M, A)                                                                                           \
     SIG_PROBE_ROUND(M, A) SIG_PROBE_ROUND(M, A) SIG_PROBE_ROUND(M, A) SIG_PROBE_ROUND(M, A)                           \
     SIG_PROBE_ROUND(M, A) SIG_PROBE_ROUND(M, A) SIG_PROBE_ROUND(M, A) SIG_PROBE_ROUND(M, A)
-template <bool ONE_BANK>
+// VARIANT 0: all three sources in bank 0; 1: three banks; 2: accumulator and multiplier share bank 0, addend in bank 2;
+// 3: multiplier and addend share bank 1, accumulator in bank 0
+template <int VARIANT>
 __global__ __launch_bounds__(256) void bank_probe_kernel(float* out, int iters)
 {
-    // accumulators 1.0, multipliers 0.999, addends 0.001 (v64 / v68: bank 0 like the accumulators; v65 / v70: banks 1, 2)
+    // accumulators 1.0, multipliers 0.999, addends 0.001 (v64 / v68: bank 0 like the accumulators; v65 / v69: bank 1; v70: bank 2)
     asm volatile("v_mov_b32 v32, 1.0\n v_mov_b32 v36, 1.0\n v_mov_b32 v40, 1.0\n v_mov_b32 v44, 1.0\n"
                  "v_mov_b32 v48, 1.0\n v_mov_b32 v52, 1.0\n v_mov_b32 v56, 1.0\n v_mov_b32 v60, 1.0\n"
                  "v_mov_b32 v64, 0x3f7fbe77\n v_mov_b32 v65, 0x3f7fbe77\n v_mov_b32 v68, 0x3a83126f\n v_mov_b32 v70, 0x3a83126f\n"
+                 "v_mov_b32 v69, 0x3a83126f\n"
                  ::: SIG_PROBE_CLOBBERS);
     for (int it = 0; it < iters; ++it) {
-        if (ONE_BANK) asm volatile(SIG_PROBE_BODY("v64", "v68") ::: SIG_PROBE_CLOBBERS);
-        else asm volatile(SIG_PROBE_BODY("v65", "v70") ::: SIG_PROBE_CLOBBERS);
+        if (VARIANT == 0) asm volatile(SIG_PROBE_BODY("v64", "v68") ::: SIG_PROBE_CLOBBERS);
+        else if (VARIANT == 1) asm volatile(SIG_PROBE_BODY("v65", "v70") ::: SIG_PROBE_CLOBBERS);
+        else if (VARIANT == 2) asm volatile(SIG_PROBE_BODY("v64", "v70") ::: SIG_PROBE_CLOBBERS);
+        else asm volatile(SIG_PROBE_BODY("v65", "v69") ::: SIG_PROBE_CLOBBERS);
     }
     float s;
     asm volatile("v_add_f32 %0, v32, v60\n" : "=v"(s) :: SIG_PROBE_CLOBBERS);
@@ -899,9 +904,11 @@ __global__ __launch_bounds__(256) void bank_probe_kernel(float* out, int iters)
 
 hipError_t issue_probe(float* out, int blocks, int iters, int mode, hipStream_t stream)
 {
-    if (blocks <= 0 || iters <= 0 || mode < 0 || mode > 5) return hipErrorInvalidValue;
-    if (mode == 4) bank_probe_kernel<true><<<(unsigned)blocks, 256, 0, stream>>>(out, iters);
-    if (mode == 5) bank_probe_kernel<false><<<(unsigned)blocks, 256, 0, stream>>>(out, iters);
+    if (blocks <= 0 || iters <= 0 || mode < 0 || mode > 7) return hipErrorInvalidValue;
+    if (mode == 4) bank_probe_kernel<0><<<(unsigned)blocks, 256, 0, stream>>>(out, iters);
+    if (mode == 5) bank_probe_kernel<1><<<(unsigned)blocks, 256, 0, stream>>>(out, iters);
+    if (mode == 6) bank_probe_kernel<2><<<(unsigned)blocks, 256, 0, stream>>>(out, iters);
+    if (mode == 7) bank_probe_kernel<3><<<(unsigned)blocks, 256, 0, stream>>>(out, iters);
     if (mode >= 4) return hipGetLastError();
     switch (mode) {
         case 0: issue_probe_kernel<0><<<(unsigned)blocks, 256, 0, stream>>>(out, iters, 0.999f, 0.001f); break;
