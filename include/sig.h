@@ -258,6 +258,10 @@ int    sig_backward_residual(const sig_wordset* ws, const float* path, const flo
  * the two calls are sig_forward / sig_backward; the same holds when a specialised kernel cannot be compiled (then
  * `checkpoint` is left alone by both calls).  Results agree with sig_forward / sig_backward to rounding. */
 size_t sig_checkpoint_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
+/* The number of time chunks C the two calls take for this batch (1: none, the calls are sig_forward / sig_backward).
+ * For a suffix-closed set the specialised kernels of the checkpointed calls run B * C rows: compile them ahead of time
+ * with sig_wordset_jit_prepare(ws, backward, B * C). */
+int64_t sig_checkpoint_chunks(const sig_wordset* ws, int64_t B, int64_t n_points);
 size_t sig_forward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
 size_t sig_backward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
 int    sig_forward_checkpointed(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs,

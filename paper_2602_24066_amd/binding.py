@@ -84,6 +84,7 @@ def load_library():
     sig("sig_wordset_jit_plan_get", c_int, [c_p, c_int, c_i64, PP, ctypes.POINTER(c_i64), PP, ctypes.POINTER(c_i64), PP,
                                              ctypes.POINTER(c_i64), ctypes.POINTER(c_i64)])
     sig("sig_wordset_jit_prepare", c_int, [c_p, c_int, c_i64])
+    sig("sig_checkpoint_chunks", c_i64, [c_p, c_i64, c_i64])
     sig("sig_wordset_jit_source", c_sz, [c_p, c_int, c_i64, c_p, c_sz])
     sig("sig_wordset_device_bytes", c_sz, [c_p])
     sig("sig_wordset_upload", c_int, [c_p, c_p, c_sz, c_p])

@@ -1079,6 +1079,13 @@ size_t sig_checkpoint_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
     return ch.C >= 2 ? chunk_array_bytes(*W(ws), B, ch.C) : 0;
 }
 
+int64_t sig_checkpoint_chunks(const sig_wordset* ws, int64_t B, int64_t n_points)
+{
+    if (!ws || B <= 0 || n_points <= 1) return 1;
+    const Chunks ch = checkpoint_chunks(*W(ws), B, n_points);
+    return ch.C >= 2 ? ch.C : 1;
+}
+
 size_t sig_forward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
 {
     if (!ws || B <= 0 || n_points <= 1) return 0;

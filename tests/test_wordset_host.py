@@ -444,6 +444,9 @@ def test_suffix_tables(case):
     assert lib.sig_checkpoint_bytes(ws._h, 1024, 513) == (per_row * 1024 * 2 + 255) // 256 * 256
     assert lib.sig_checkpoint_bytes(ws._h, 2048, 513) == 0 and lib.sig_checkpoint_bytes(ws._h, 512, 101) == 0
     assert lib.sig_checkpoint_bytes(ws._h, 5, 201) == (per_row * 5 * 3 + 255) // 256 * 256
+    assert lib.sig_checkpoint_chunks(ws._h, 5, 201) == 3 and lib.sig_checkpoint_chunks(ws._h, 2048, 513) == 1
+    if case == "anisotropic":                                                  # the kernels of the B * C rows, ahead of time
+        assert ws.jit_prepare(False, 5 * 3) == 0 and ws.jit_prepare(True, 5 * 3) == 0
     assert lib.sig_forward_checkpointed_workspace_bytes(ws._h, 512, 513) >= lib.sig_forward_workspace_bytes(ws._h, 512, 513)
     assert lib.sig_backward_checkpointed_workspace_bytes(ws._h, 512, 513) >= lib.sig_backward_workspace_bytes(ws._h, 512, 513)
     ws.set_option("no_jit", 1)                                                 # the table-driven kernels take whole paths
