@@ -1123,7 +1123,7 @@ int sig_forward_checkpointed(const sig_wordset* ws, const float* path, int64_t B
         const sig::Plan *fp = nullptr, *bp = nullptr;
         if (!words_kernels(w, B * ch.C, &fk, &fp, &bk, &bp))
             return sig_forward(ws, path, B, n_points, coeffs, workspace, workspace_bytes, stream);
-        if (!workspace || workspace_bytes < words_forward_ckpt_workspace(w, B, ch)) return SIG_EWORKSPACE;
+        if (!workspace || workspace_bytes < sig_forward_checkpointed_workspace_bytes(ws, B, n_points)) return SIG_EWORKSPACE;
         if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
         hipStream_t st = (hipStream_t)stream;
         CallTimer whole(0, st);
@@ -1175,7 +1175,7 @@ int sig_backward_checkpointed(const sig_wordset* ws, const float* path, const fl
         const sig::Plan *fp = nullptr, *bp = nullptr;
         if (!words_kernels(w, B * ch.C, &fk, &fp, &bk, &bp))
             return sig_backward(ws, path, coeffs, grad_coeffs, B, n_points, grad_path, workspace, workspace_bytes, stream);
-        if (!workspace || workspace_bytes < words_backward_ckpt_workspace(w, B, ch)) return SIG_EWORKSPACE;
+        if (!workspace || workspace_bytes < sig_backward_checkpointed_workspace_bytes(ws, B, n_points)) return SIG_EWORKSPACE;
         if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)checkpoint & 255) != 0) return SIG_EINVAL;
         hipStream_t st = (hipStream_t)stream;
         CallTimer whole(1, st);

@@ -223,6 +223,48 @@ def test_checkpointed_word_sets(case):
     assert O.grad_errors(gplain.cpu().numpy(), gref).max() <= BWD_TOL
 
 
+def test_checkpointed_word_sets_reject_bad_buffers():
+    """Buffers that are missing, too small or misaligned are refused with an error code before anything is launched."""
+    import ctypes
+    import torch
+    ws, W = build_both("anisotropic", 3, weights=(1.0, 1.25, 1.5), cutoff=4.5)
+    lib = S.load_library()
+    B, L = 5, 200
+    nck = int(lib.sig_checkpoint_bytes(ws._h, B, L + 1))
+    nf = int(lib.sig_forward_checkpointed_workspace_bytes(ws._h, B, L + 1))
+    nb = int(lib.sig_backward_checkpointed_workspace_bytes(ws._h, B, L + 1))
+    assert nck > 0 and nf > 0 and nb > 0
+    xp = torch.from_numpy(make_path("iid", 5300, B, L, 3)).cuda()
+    grad = torch.from_numpy(make_grad_coeffs(5301, B, ws.size)).cuda()
+    coeffs = torch.full((B, ws.size), 3.0, dtype=torch.float32, device="cuda")
+    gpath = torch.full((B, L + 1, 3), 3.0, dtype=torch.float32, device="cuda")
+    ck = torch.zeros(nck + 256, dtype=torch.uint8, device="cuda")
+    wk = torch.zeros(max(nf, nb) + 256, dtype=torch.uint8, device="cuda")
+    assert ck.data_ptr() % 256 == 0 and wk.data_ptr() % 256 == 0
+    P = ctypes.c_void_p
+
+    def fwd(ckp, ckn, wp, wn):
+        return lib.sig_forward_checkpointed(ws._h, P(xp.data_ptr()), B, L + 1, P(coeffs.data_ptr()), P(ckp), ckn, P(wp), wn, None)
+
+    def bwd(ckp, ckn, wp, wn):
+        return lib.sig_backward_checkpointed(ws._h, P(xp.data_ptr()), P(coeffs.data_ptr()), P(grad.data_ptr()), P(ckp), ckn, B, L + 1,
+                                             P(gpath.data_ptr()), P(wp), wn, None)
+
+    for call, need in ((fwd, nf), (bwd, nb)):
+        assert call(ck.data_ptr(), nck - 1, wk.data_ptr(), need) == -5
+        assert call(0, nck, wk.data_ptr(), need) == -5
+        assert call(ck.data_ptr(), nck, wk.data_ptr(), need - 1) == -5
+        assert call(ck.data_ptr(), nck, 0, need) == -5
+        assert call(ck.data_ptr() + 4, nck, wk.data_ptr(), need) == -1
+        assert call(ck.data_ptr(), nck, wk.data_ptr() + 4, need) == -1
+    torch.cuda.synchronize()
+    assert (coeffs == 3.0).all() and (gpath == 3.0).all() and (ck == 0).all()      # nothing ran
+    assert fwd(ck.data_ptr(), nck, wk.data_ptr(), nf) == 0 and bwd(ck.data_ptr(), nck, wk.data_ptr(), nb) == 0
+    torch.cuda.synchronize()
+    gref = O.backward_words(xp.cpu().numpy(), W, grad.cpu().numpy().astype(np.float64))
+    assert O.grad_errors(gpath.cpu().numpy(), gref).max() <= BWD_TOL
+
+
 # Every tile shape of the d = 16 and d = 8 backward kernels, forced on batches far too small to take them by themselves:
 # tiles that do not divide the number of segments, a single ragged tile, with and without time chunks
 @pytest.mark.parametrize("d,depth,tile", [(16, 4, 4), (16, 4, 8), (16, 4, 12), (16, 4, 16), (8, 5, 4), (8, 5, 8), (8, 5, 16)])
