@@ -1189,18 +1189,19 @@ int sig_backward_checkpointed(const sig_wordset* ws, const float* path, const fl
         const float* Pfx = Sc;
         const sig::WordTables tab = word_tables(w);
         const int64_t Lpad = jit_lpad(w, ch.Lc + 1, 1);
-        // rows of one path share the points between their chunks: the chain rule adds into grad_path
-        hipError_t e = sig::fill_zero(grad_path, B * n_points * w.d, st);
-        if (e == hipSuccess) e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, gdx, st, rows);
+        // rows of one path share the points between their chunks: the chain rule adds into grad_path, which the adjoint
+        // kernel clears on the way
+        const int64_t n_gp = B * n_points * w.d;
+        hipError_t e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, gdx, st, rows);
         if (ch.C == 2) {
             // two chunks: the signature at the end of the first is the first chunk's own, what follows it the second's
             // (row c + 1 of the checkpoint, read as row c of an array that starts one row later)
-            if (e == hipSuccess) e = sig::words_adjoint(tab, grad_coeffs, Sc + w.size(), B, 2, Abar, st);
+            if (e == hipSuccess) e = sig::words_adjoint(tab, grad_coeffs, Sc + w.size(), B, 2, Abar, grad_path, n_gp, st);
         } else {
             float* P = (float*)((unsigned char*)workspace + 2 * t_bytes + nb);
             if (e == hipSuccess) e = sig::words_scan(tab, Sc, B, (int)ch.C, false, P, nullptr, st);
             if (e == hipSuccess) e = sig::words_scan(tab, Sc, B, (int)ch.C, true, Abar, nullptr, st);
-            if (e == hipSuccess) e = sig::words_adjoint(tab, grad_coeffs, Abar, B, (int)ch.C, Abar, st);   // in place, row by row
+            if (e == hipSuccess) e = sig::words_adjoint(tab, grad_coeffs, Abar, B, (int)ch.C, Abar, grad_path, n_gp, st);   // in place, row by row
             Pfx = P;
         }
         if (e != hipSuccess) return hip_fail(e);

@@ -126,8 +126,15 @@ __device__ __forceinline__ void seg_step(float& v, uint32_t key)
 // such groups in flight), sums runs of equal u within each row of 16 lanes and adds every run's sum to u's accumulator
 // in LDS.
 __global__ __launch_bounds__(kWordsThreads) void words_adjoint_kernel(WordTables t, const float* __restrict__ grad, const float* Q,
-                                                                      int C, float* Abar)
+                                                                      int C, float* Abar, float* __restrict__ zeroed, int64_t n_zeroed)
 {
+    // an array the caller wants cleared on the way (the gradient of the path, which the chain rule adds into): every
+    // workgroup clears its share
+    if (zeroed) {
+        const int64_t per = (n_zeroed + gridDim.x - 1) / gridDim.x, lo = per * blockIdx.x;
+        const int64_t hi = lo + per < n_zeroed ? lo + per : n_zeroed;
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kWordsThreads) zeroed[i] = 0.0f;
+    }
     extern __shared__ float sm[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int NWAVES = kWordsThreads / 64, UN = 4;
@@ -195,7 +202,8 @@ hipError_t words_scan(const WordTables& t, const float* S, int64_t B, int C, boo
     return hipGetLastError();
 }
 
-hipError_t words_adjoint(const WordTables& t, const float* grad, const float* Q, int64_t B, int C, float* Abar, hipStream_t stream)
+hipError_t words_adjoint(const WordTables& t, const float* grad, const float* Q, int64_t B, int C, float* Abar, float* zeroed,
+                         int64_t n_zeroed, hipStream_t stream)
 {
     if (B < 1 || C < 2 || B * (C - 1) > 0x7fffffff || t.W < 1 || t.W > 0xffff) return hipErrorInvalidValue;
     const size_t lds = (3 * (size_t)t.W + 1) * sizeof(float);
@@ -204,7 +212,7 @@ hipError_t words_adjoint(const WordTables& t, const float* grad, const float* Q,
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&words_adjoint_kernel), (int)(160 * 1024));
         if (e != hipSuccess) return e;
     }
-    words_adjoint_kernel<<<(unsigned)(B * (C - 1)), kWordsThreads, lds, stream>>>(t, grad, Q, C, Abar);
+    words_adjoint_kernel<<<(unsigned)(B * (C - 1)), kWordsThreads, lds, stream>>>(t, grad, Q, C, Abar, zeroed, n_zeroed);
     return hipGetLastError();
 }
 
