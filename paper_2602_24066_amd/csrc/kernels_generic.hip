@@ -290,7 +290,7 @@ __device__ __forceinline__ void lane_row(const WindowList& wl, int64_t r, int64_
 // zero for padded segments j >= the row's length and for rows past the last.
 // One workgroup takes 64 rows x TS segments: a wavefront reads runs of consecutive floats of its 16 rows
 // (coalesced), the differences go to an LDS tile [segment * d + letter][row] and leave it as rows of 64 lanes.
-__global__ void increments_transposed_kernel(const float* __restrict__ path, int64_t R_rows, int64_t P, int d, int64_t Lpad, int TS,
+__global__ __launch_bounds__(256) void increments_transposed_kernel(const float* __restrict__ path, int64_t R_rows, int64_t P, int d, int64_t Lpad, int TS,
                                              int64_t tiles, WindowList wl, float* __restrict__ dxT, float* __restrict__ zeroed)
 {
     extern __shared__ float tile[];                       // [TS * d][65]
@@ -304,25 +304,30 @@ __global__ void increments_transposed_kernel(const float* __restrict__ path, int
     for (int e0 = 0; e0 < R; e0 += kWave) {
         const int e = e0 + lane;
         const int64_t seg = j0 + e / d;
-        int64_t off[16];
-        bool ok[16];
+        // eight rows at a time (sixteen loads in flight): offsets, values and flags of all sixteen rows at once
+        // would not fit the registers of the workgroup
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int64_t r = g * kWave + wave * 16 + q;
-            int64_t b = 0, first = 0, len = 0;
-            if (r < R_rows) lane_row(wl, r, P, b, first, len);             // uniform over the wavefront
-            ok[q] = e < R && seg < len;                                    // then point first + seg + 1 <= P - 1
-            off[q] = ok[q] ? (b * P + first + j0) * d + e : 0;             // path[0], path[d] exist: P >= 2
-        }
-        float hi[16], lo[16];
+        for (int q0 = 0; q0 < 16; q0 += 8) {
+            int64_t off[8];
+            bool ok[8];
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            hi[q] = path[off[q] + d];
-            lo[q] = path[off[q]];
-        }
-        if (e < R) {
+            for (int q = 0; q < 8; ++q) {
+                const int64_t r = g * kWave + wave * 16 + q0 + q;
+                int64_t b = 0, first = 0, len = 0;
+                if (r < R_rows) lane_row(wl, r, P, b, first, len);         // uniform over the wavefront
+                ok[q] = e < R && seg < len;                                // then point first + seg + 1 <= P - 1
+                off[q] = ok[q] ? (b * P + first + j0) * d + e : 0;         // path[0], path[d] exist: P >= 2
+            }
+            float hi[8], lo[8];
 #pragma unroll
-            for (int q = 0; q < 16; ++q) tile[e * 65 + wave * 16 + q] = ok[q] ? hi[q] - lo[q] : 0.0f;
+            for (int q = 0; q < 8; ++q) {
+                hi[q] = path[off[q] + d];
+                lo[q] = path[off[q]];
+            }
+            if (e < R) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) tile[e * 65 + wave * 16 + q0 + q] = ok[q] ? hi[q] - lo[q] : 0.0f;
+            }
         }
     }
     __syncthreads();
@@ -427,7 +432,7 @@ hipError_t increments_transposed(const float* path, int64_t B, int64_t P, int d,
 // [(TS + 1) * d][65], runs of consecutive floats of one path out.  With a window list a row is a window of its path:
 // its points are those of the path from the window's first point on, and the gradients of overlapping windows are
 // added up in grad_path (zeroed by the caller) with floating-point atomics.
-__global__ void grad_points_transposed_kernel(const float* __restrict__ g, int64_t R_rows, int64_t P, int d, int64_t Lpad, int TS,
+__global__ __launch_bounds__(256) void grad_points_transposed_kernel(const float* __restrict__ g, int64_t R_rows, int64_t P, int d, int64_t Lpad, int TS,
                                               int64_t tiles, WindowList wl, float* __restrict__ grad_path)
 {
     extern __shared__ float tile[];
