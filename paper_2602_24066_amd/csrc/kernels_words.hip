@@ -6,7 +6,8 @@
 //   Abar_c(u) = grad(u) + sum_{v: u v in W} grad(u v) Q_c(v),   Q_c = S_{c+1} (x) .. (x) S_{C-1}
 // (Proposition 4.1 with the right factor taken at a chunk boundary).  Both sums run over the same terms (w, m); the
 // host lists them once per order of use, two 16-bit word indices per entry: by word w for the product, by prefix
-// u = w_1..w_m (with u beside every term) for the adjoint.  The signatures lie in LDS (one path per workgroup), the tables stream from L2.
+// u = w_1..w_m (with u beside every term) for the adjoint.  The signatures lie in LDS (one path per workgroup), the
+// tables stream from L2.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
