@@ -182,8 +182,10 @@ BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points
 // straight-line specialised kernels (lane = row) take the same form: Chen's relation restricted to such a set stays
 // inside it.  Those kernels gain from rows up to about 2,048 (32 lane groups: fewer, larger units, so less
 // recomputation of shared ancestors per group), but every chunk boundary costs a product and an adjoint sum over the
-// set, gathers that run at a fraction of the rate of the kernels.  Measured on 5,754 words, 512 segments: four chunks
-// win up to 128 paths, two from there to 1,024 (step time -34 % at 64 paths, -20 % at 512, -5 % at 1,024).
+// set, gathers that run at a fraction of the rate of the kernels.  Measured on 5,754 words for 64 .. 1,024 paths of
+// 512 .. 4,096 segments (step time against the plain calls: -75 % for 64 paths x 4,096 segments with eight chunks,
+// -35 % for 512 x 2,048 with four, -20 % for 512 x 512 with two, -5 % for 1,024 x 512 with two); more than 2,048 rows
+// lose.  "ckpt_chunks" forces a count of up to 16 (chunks of at least 64 segments).
 bool jit_enabled(const sig::WordSet& w);
 bool words_time_chunks(const sig::WordSet& w)
 {
@@ -194,8 +196,16 @@ Chunks checkpoint_chunks(const sig::WordSet& w, int64_t B, int64_t n_points)
     const int64_t L = n_points - 1;
     int64_t C = 1;
     if (B >= 1 && words_time_chunks(w)) {
-        C = w.opt.ckpt_chunks > 0 ? std::min<int64_t>(w.opt.ckpt_chunks, 4) : (B <= 128 ? 4 : (B <= 1024 ? 2 : 1));
-        C = std::max<int64_t>(1, std::min<int64_t>(C, L / 64));
+        if (w.opt.ckpt_chunks > 0) {
+            C = std::min<int64_t>(std::min<int64_t>(w.opt.ckpt_chunks, 16), L / 64);
+        } else {
+            // at most 2,048 rows and chunks of at least 256 segments; batches that stay at 512 rows or below take chunks
+            // down to 128 segments; never more than eight
+            C = std::min<int64_t>(2048 / B, L / 256);
+            if (B * std::max<int64_t>(C, 1) <= 512) C = std::min<int64_t>(2048 / B, L / 128);
+            C = std::min<int64_t>(C, 8);
+        }
+        C = std::max<int64_t>(1, C);
         if (B * C > (int64_t)65535 * 64) C = 1;
     }
     if (w.kind == 0 && B >= 1 && B <= 65535 && sig::trunc_backward_available(w.d, w.depth) && sig::chunking_available(w.d, w.depth) &&

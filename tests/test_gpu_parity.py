@@ -170,14 +170,16 @@ def _no_repeat_words(d, n):
 
 
 # The same pair of calls on word sets closed under suffixes (anisotropic sets; a word list that is): chunk counts by the
-# library's rule and forced, chunk lengths that do not divide L, a batch of more than one lane group, against the
+# library's rule (two and eight) and forced (two, three, four), chunk lengths that do not divide L, a batch of more than one lane group, against the
 # oracle; and a list that lacks suffixes, which takes no chunks.  (Every length of these sets has several words: a length
 # with a single word is ill-conditioned under the forward error measure for any summation order.)
 WORD_CHUNK_CASES = {
-    "aniso3": ("anisotropic", 3, (1.0, 1.25, 1.5), 4.5, None, 5, 200, 0, 3),
-    "aniso6": ("anisotropic", 6, (1, 1, 2, 2, 3, 3), 8.0, None, 70, 257, 0, 4),
+    "aniso3": ("anisotropic", 3, (1.0, 1.25, 1.5), 4.5, None, 5, 200, 3, 3),
+    "aniso6": ("anisotropic", 6, (1, 1, 2, 2, 3, 3), 8.0, None, 70, 257, 0, 2),
+    "aniso6-forced": ("anisotropic", 6, (1, 1, 2, 2, 3, 3), 8.0, None, 70, 257, 4, 4),
+    "aniso3-rule": ("anisotropic", 3, (1.0, 1.25, 1.5), 4.5, None, 2, 1030, 0, 8),
     "aniso2-forced": ("anisotropic", 2, (0.3, 0.4), 1.6, None, 3, 300, 2, 2),
-    "no-repeat": ("list", 3, None, None, "no-repeat", 9, 130, 0, 2),
+    "no-repeat": ("list", 3, None, None, "no-repeat", 9, 130, 2, 2),
     "random": ("list", 4, None, None, "random", 4, 200, 0, 0),
 }
 
@@ -228,6 +230,7 @@ def test_checkpointed_word_sets_reject_bad_buffers():
     import ctypes
     import torch
     ws, W = build_both("anisotropic", 3, weights=(1.0, 1.25, 1.5), cutoff=4.5)
+    ws.set_option("ckpt_chunks", 3)
     lib = S.load_library()
     B, L = 5, 200
     nck = int(lib.sig_checkpoint_bytes(ws._h, B, L + 1))
@@ -705,6 +708,8 @@ def test_checkpointed_step_captured_in_a_graph(kind, d, depth, B, L):
     on new inputs with eager work between the replays."""
     import torch
     ws, W = build_both(kind, d, depth=depth, weights=(1.0, 1.25, 1.5), cutoff=4.5)
+    if kind == "anisotropic":
+        ws.set_option("ckpt_chunks", 3 if L >= 192 else 2)
     lib = S.load_library()
     nck = int(lib.sig_checkpoint_bytes(ws._h, B, L + 1))
     assert nck > 0

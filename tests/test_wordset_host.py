@@ -436,17 +436,23 @@ def test_suffix_tables(case):
             assert tab[off[n] + (m - 1) * cnt + (k - ls[n])] == index[tuple(w[m:])]
             seen += 1
     assert seen == sum(len(w) - 1 for w in words) and seen > 0
-    # the checkpointed calls offer time chunks for such a set: four up to 128 paths, two up to 1,024, chunks of at least 64 segments
+    # the checkpointed calls offer time chunks for such a set: up to 2,048 rows, chunks of at least 256 segments (128 for few rows)
     lib = S.load_library()
     per_row = 4 * ws.size
     assert lib.sig_checkpoint_bytes(ws._h, 128, 513) == (per_row * 128 * 4 + 255) // 256 * 256
     assert lib.sig_checkpoint_bytes(ws._h, 512, 513) == (per_row * 512 * 2 + 255) // 256 * 256
     assert lib.sig_checkpoint_bytes(ws._h, 1024, 513) == (per_row * 1024 * 2 + 255) // 256 * 256
     assert lib.sig_checkpoint_bytes(ws._h, 2048, 513) == 0 and lib.sig_checkpoint_bytes(ws._h, 512, 101) == 0
-    assert lib.sig_checkpoint_bytes(ws._h, 5, 201) == (per_row * 5 * 3 + 255) // 256 * 256
-    assert lib.sig_checkpoint_chunks(ws._h, 5, 201) == 3 and lib.sig_checkpoint_chunks(ws._h, 2048, 513) == 1
+    assert lib.sig_checkpoint_bytes(ws._h, 5, 201) == 0
+    assert lib.sig_checkpoint_bytes(ws._h, 5, 257) == (per_row * 5 * 2 + 255) // 256 * 256
+    assert lib.sig_checkpoint_chunks(ws._h, 5, 257) == 2 and lib.sig_checkpoint_chunks(ws._h, 2048, 513) == 1
+    assert lib.sig_checkpoint_chunks(ws._h, 64, 4097) == 8 and lib.sig_checkpoint_chunks(ws._h, 128, 2049) == 8
+    assert lib.sig_checkpoint_chunks(ws._h, 512, 2049) == 4 and lib.sig_checkpoint_chunks(ws._h, 256, 1025) == 4
+    ws.set_option("ckpt_chunks", 3)
+    assert lib.sig_checkpoint_chunks(ws._h, 5, 201) == 3 and lib.sig_checkpoint_chunks(ws._h, 5, 150) == 2
+    ws.set_option("ckpt_chunks", 0)
     if case == "anisotropic":                                                  # the kernels of the B * C rows, ahead of time
-        assert ws.jit_prepare(False, 5 * 3) == 0 and ws.jit_prepare(True, 5 * 3) == 0
+        assert ws.jit_prepare(False, 5 * 2) == 0 and ws.jit_prepare(True, 5 * 2) == 0
     assert lib.sig_forward_checkpointed_workspace_bytes(ws._h, 512, 513) >= lib.sig_forward_workspace_bytes(ws._h, 512, 513)
     assert lib.sig_backward_checkpointed_workspace_bytes(ws._h, 512, 513) >= lib.sig_backward_workspace_bytes(ws._h, 512, 513)
     ws.set_option("no_jit", 1)                                                 # the table-driven kernels take whole paths
