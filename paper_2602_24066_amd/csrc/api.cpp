@@ -174,8 +174,8 @@ BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points
 // Checkpointed form (sig_forward_checkpointed / sig_backward_checkpointed): the forward pass leaves the signatures of C
 // time chunks of every path in a buffer the caller keeps, and the backward pass walks the C chunks side by side
 // without recomputing them.  Taken where the backward kernel of a full truncation has too few rows to put two
-// wavefronts on every SIMD (eight wavefronts per row for d = 8, sixteen for d = 16); C = 2 .. 4, chunks of at least 64
-// segments.
+// wavefronts on every SIMD (eight wavefronts per row for d = 8, sixteen for d = 16); C = 2 .. 8, chunks of at least 64
+// segments (measured: 8 paths x 8,192 segments, d = 16: step 4.1 ms plain, 1.43 ms with four chunks, 1.00 ms with eight).
 // "ckpt_chunks" forces a count (0: this rule, 1: off).
 //
 // Word sets closed under suffixes as well as prefixes (anisotropic sets, Definition 7.1) that run through the
@@ -211,10 +211,10 @@ Chunks checkpoint_chunks(const sig::WordSet& w, int64_t B, int64_t n_points)
     if (w.kind == 0 && B >= 1 && B <= 65535 && sig::trunc_backward_available(w.d, w.depth) && sig::chunking_available(w.d, w.depth) &&
         !sig::trunc_backward_tails_available(w.d, w.depth)) {
         if (w.opt.ckpt_chunks > 0) {
-            C = std::min<int64_t>(w.opt.ckpt_chunks, 4);
+            C = std::min<int64_t>(w.opt.ckpt_chunks, 8);
         } else {
             const int64_t rows_wanted = 2048 / sig::trunc_waves_per_row(w.d, w.depth, 1);
-            C = std::min<int64_t>(4, (rows_wanted + B - 1) / B);
+            C = std::min<int64_t>(8, (rows_wanted + B - 1) / B);
         }
         C = std::max<int64_t>(1, std::min<int64_t>(C, L / 64));
     }
