@@ -212,7 +212,9 @@ int    sig_wordset_upload(sig_wordset* ws, void* dev_buf /*device*/, size_t dev_
  *            contents undefined before and after.
  * Full truncations with few paths are cut into time chunks that run side by side and are multiplied together
  * afterwards (Chen's relation, eq. 2, is associative); sig_backward does the same and recomputes the chunk
- * signatures from the path.
+ * signatures from the path.  Word sets closed under suffixes (sig_wordset_suffix_closed) that run through the
+ * run-time specialised kernels take the chunks of the checkpointed calls below in sig_forward as well, with the
+ * chunk signatures in the workspace (sig_backward does not: it would have to recompute them).
  * n_points == 1 gives all-zero coeffs (S_{0,0} = 1 has no non-empty-word part).  B == 0 is a no-op. */
 size_t sig_forward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
 int    sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs,

@@ -440,6 +440,23 @@ size_t words_forward_ckpt_workspace(const sig::WordSet& w, int64_t B, const Chun
 }
 // increment gradients and increments of all rows in the transposed layout | boundary adjoints (for more than two chunks
 // first what follows every chunk, overwritten in place) | for more than two chunks: signatures at the chunk ends
+// The chunked forward pass: transposed increments of all (path, chunk) rows, their signatures into Sc [B][C][|W|], the
+// product of every path's chunk signatures into coeffs.
+hipError_t words_forward_chunked(const sig::WordSet& w, const float* path, int64_t B, int64_t n_points, const Chunks& ch,
+                                 sig::JitKernel& fk, const sig::Plan& fp, float* dxT, float* Sc, float* coeffs, hipStream_t st)
+{
+    sig::WindowList rows;
+    rows.K = ch.C; rows.max_len = ch.Lc;
+    const int64_t Lpad = jit_lpad(w, ch.Lc + 1, 0);
+    hipError_t e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, nullptr, st, rows);
+    if (e != hipSuccess) return e;
+    hipEvent_t* pe = g_prof.next(0);
+    if (pe) (void)hipEventRecord(pe[0], st);
+    e = launch_jit_forward(fk, fp, dxT, B * ch.C, Lpad / fk.tile, Sc, w.size(), st);
+    if (pe) (void)hipEventRecord(pe[1], st);
+    if (e == hipSuccess) e = sig::words_scan(word_tables(w), Sc, B, (int)ch.C, false, nullptr, coeffs, st);
+    return e;
+}
 size_t words_backward_ckpt_workspace(const sig::WordSet& w, int64_t B, const Chunks& ch)
 {
     return 2 * jit_dxt_bytes(w, B * ch.C, ch.Lc + 1, 1) + (ch.C == 2 ? 1 : 2) * chunk_array_bytes(w, B, ch.C);
@@ -776,7 +793,13 @@ size_t sig_forward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_p
         return ch.C > 1 ? forward_chunk_arrays(w, ch.C) * chunk_array_bytes(w, B, ch.C) : 0;
     }
     if (!jit_enabled(w)) return 0;
-    return jit_dxt_bytes(w, B, n_points, 0);
+    size_t n = jit_dxt_bytes(w, B, n_points, 0);
+    if (w.kind != 0) {
+        // sets closed under suffixes: time chunks as in the checkpointed calls, the chunk signatures in the workspace
+        const Chunks ch = checkpoint_chunks(w, B, n_points);
+        if (ch.C >= 2) n = std::max(n, words_forward_ckpt_workspace(w, B, ch) + chunk_array_bytes(w, B, ch.C));
+    }
+    return n;
 }
 
 size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
@@ -807,8 +830,10 @@ static int check_common(const sig_wordset* ws, const void* path, int64_t B, int6
     return SIG_OK;
 }
 
-int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs, void* workspace,
-                size_t workspace_bytes, void* stream)
+// sig_forward; word_chunks = false keeps a suffix-closed set from taking time chunks of its own (the checkpointed call
+// that falls back to this one has sized its workspace for whole paths)
+static int forward_impl(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs, void* workspace,
+                        size_t workspace_bytes, void* stream, bool word_chunks)
 {
     int rc = check_common(ws, path, B, n_points);
     if (rc != SIG_OK) return rc;
@@ -858,6 +883,20 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
             return e == hipSuccess ? SIG_OK : hip_fail(e);
         }
     }
+    if (w.kind != 0 && word_chunks) {
+        // sets closed under suffixes: the time chunks of the checkpointed calls, with the chunk signatures in the workspace
+        const Chunks ch = checkpoint_chunks(w, B, n_points);
+        const sig::Plan* cp = nullptr;
+        sig::JitKernel* ck = ch.C >= 2 ? ensure_jit(w, 0, B * ch.C, Build::compile_and_load, &cp) : nullptr;
+        if (ck) {
+            if (!workspace || workspace_bytes < sig_forward_workspace_bytes(ws, B, n_points)) return SIG_EWORKSPACE;
+            if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
+            float* dxT = (float*)workspace;
+            float* Sc = (float*)((unsigned char*)workspace + words_forward_ckpt_workspace(w, B, ch));
+            hipError_t e = words_forward_chunked(w, path, B, n_points, ch, *ck, *cp, dxT, Sc, coeffs, st);
+            return e == hipSuccess ? SIG_OK : hip_fail(e);
+        }
+    }
     const sig::Plan* jp = nullptr;
     if (sig::JitKernel* jk = ensure_jit(w, 0, B, Build::compile_and_load, &jp)) {
         if (!workspace || workspace_bytes < jit_dxt_bytes(w, B, n_points, 0)) return SIG_EWORKSPACE;
@@ -889,6 +928,12 @@ int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_p
     hipError_t e = sig::generic_forward(a, w.max_len, st);
     if (pe) (void)hipEventRecord(pe[1], st);
     return e == hipSuccess ? SIG_OK : hip_fail(e);
+}
+
+int sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs, void* workspace,
+                size_t workspace_bytes, void* stream)
+{
+    return forward_impl(ws, path, B, n_points, coeffs, workspace, workspace_bytes, stream, true);
 }
 
 // sig_backward and sig_backward_static: the same kernels on the caller's workspace or on the static scratch array;
@@ -1101,7 +1146,7 @@ size_t sig_forward_checkpointed_workspace_bytes(const sig_wordset* ws, int64_t B
     if (!ws || B <= 0 || n_points <= 1) return 0;
     const Chunks ch = checkpoint_chunks(*W(ws), B, n_points);
     if (ch.C < 2) return sig_forward_workspace_bytes(ws, B, n_points);
-    if (W(ws)->kind != 0) return std::max(words_forward_ckpt_workspace(*W(ws), B, ch), sig_forward_workspace_bytes(ws, B, n_points));
+    if (W(ws)->kind != 0) return std::max(words_forward_ckpt_workspace(*W(ws), B, ch), jit_dxt_bytes(*W(ws), B, n_points, 0));
     return forward_chunk_arrays(*W(ws), ch.C) > 1 ? chunk_array_bytes(*W(ws), B, ch.C) : 0;   // partial products of four chunks
 }
 
@@ -1132,23 +1177,12 @@ int sig_forward_checkpointed(const sig_wordset* ws, const float* path, int64_t B
         sig::JitKernel *fk, *bk;
         const sig::Plan *fp = nullptr, *bp = nullptr;
         if (!words_kernels(w, B * ch.C, &fk, &fp, &bk, &bp))
-            return sig_forward(ws, path, B, n_points, coeffs, workspace, workspace_bytes, stream);
+            return forward_impl(ws, path, B, n_points, coeffs, workspace, workspace_bytes, stream, false);
         if (!workspace || workspace_bytes < sig_forward_checkpointed_workspace_bytes(ws, B, n_points)) return SIG_EWORKSPACE;
         if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
         hipStream_t st = (hipStream_t)stream;
         CallTimer whole(0, st);
-        sig::WindowList rows;
-        rows.K = ch.C; rows.max_len = ch.Lc;
-        float* dxT = (float*)workspace;
-        float* Sc = (float*)checkpoint;
-        const int64_t Lpad = jit_lpad(w, ch.Lc + 1, 0);
-        hipError_t e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, nullptr, st, rows);
-        if (e != hipSuccess) return hip_fail(e);
-        hipEvent_t* pe = g_prof.next(0);
-        if (pe) (void)hipEventRecord(pe[0], st);
-        e = launch_jit_forward(*fk, *fp, dxT, B * ch.C, Lpad / fk->tile, Sc, w.size(), st);
-        if (pe) (void)hipEventRecord(pe[1], st);
-        if (e == hipSuccess) e = sig::words_scan(word_tables(w), Sc, B, (int)ch.C, false, nullptr, coeffs, st);
+        hipError_t e = words_forward_chunked(w, path, B, n_points, ch, *fk, *fp, (float*)workspace, (float*)checkpoint, coeffs, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
     if (((uintptr_t)checkpoint & 255) != 0 || ((uintptr_t)coeffs & 15) != 0) return SIG_EINVAL;

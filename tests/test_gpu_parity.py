@@ -225,6 +225,9 @@ def test_checkpointed_word_sets(case):
     gerr = O.grad_errors(gp, gref)
     assert gerr.max() <= BWD_TOL, f"{case}: checkpointed backward: {gerr.max():.3e}"
     assert O.grad_errors(gplain.cpu().numpy(), gref).max() <= BWD_TOL
+    # sig_forward takes the same chunks, with the chunk signatures in its workspace
+    for n, e in O.level_errors(plain.cpu().numpy(), ref, lengths).items():
+        assert e <= FWD_TOL, f"{case}: sig_forward, level {n}: {e:.3e}"
 
 
 def test_checkpointed_word_sets_reject_bad_buffers():
