@@ -214,7 +214,8 @@ int    sig_wordset_upload(sig_wordset* ws, void* dev_buf /*device*/, size_t dev_
  * afterwards (Chen's relation, eq. 2, is associative); sig_backward does the same and recomputes the chunk
  * signatures from the path.  Word sets closed under suffixes (sig_wordset_suffix_closed) that run through the
  * run-time specialised kernels take the chunks of the checkpointed calls below in sig_forward as well, with the
- * chunk signatures in the workspace (sig_backward does not: it would have to recompute them).
+ * chunk signatures in the workspace; sig_backward recomputes them and does the same from four chunks on (few long
+ * paths), where that still beats walking whole paths.
  * n_points == 1 gives all-zero coeffs (S_{0,0} = 1 has no non-empty-word part).  B == 0 is a no-op. */
 size_t sig_forward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points);
 int    sig_forward(const sig_wordset* ws, const float* path, int64_t B, int64_t n_points, float* coeffs,

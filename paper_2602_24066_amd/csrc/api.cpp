@@ -441,7 +441,7 @@ size_t words_forward_ckpt_workspace(const sig::WordSet& w, int64_t B, const Chun
 // increment gradients and increments of all rows in the transposed layout | boundary adjoints (for more than two chunks
 // first what follows every chunk, overwritten in place) | for more than two chunks: signatures at the chunk ends
 // The chunked forward pass: transposed increments of all (path, chunk) rows, their signatures into Sc [B][C][|W|], the
-// product of every path's chunk signatures into coeffs.
+// product of every path's chunk signatures into coeffs (nullptr: the chunk signatures alone).
 hipError_t words_forward_chunked(const sig::WordSet& w, const float* path, int64_t B, int64_t n_points, const Chunks& ch,
                                  sig::JitKernel& fk, const sig::Plan& fp, float* dxT, float* Sc, float* coeffs, hipStream_t st)
 {
@@ -454,12 +454,65 @@ hipError_t words_forward_chunked(const sig::WordSet& w, const float* path, int64
     if (pe) (void)hipEventRecord(pe[0], st);
     e = launch_jit_forward(fk, fp, dxT, B * ch.C, Lpad / fk.tile, Sc, w.size(), st);
     if (pe) (void)hipEventRecord(pe[1], st);
-    if (e == hipSuccess) e = sig::words_scan(word_tables(w), Sc, B, (int)ch.C, false, nullptr, coeffs, st);
+    if (e == hipSuccess && coeffs) e = sig::words_scan(word_tables(w), Sc, B, (int)ch.C, false, nullptr, coeffs, st);
     return e;
 }
 size_t words_backward_ckpt_workspace(const sig::WordSet& w, int64_t B, const Chunks& ch)
 {
     return 2 * jit_dxt_bytes(w, B * ch.C, ch.Lc + 1, 1) + (ch.C == 2 ? 1 : 2) * chunk_array_bytes(w, B, ch.C);
+}
+// The backward pass over the (path, chunk) rows of a suffix-closed set, from the chunk signatures Sc [B][C][|W|]:
+// boundary adjoints (and, beyond two chunks, the signatures at the chunk ends) from products over the set, one launch
+// of the specialised kernel over all rows, chain rule.  workspace: words_backward_ckpt_workspace bytes.
+hipError_t words_backward_chunked(const sig::WordSet& w, const float* path, const float* coeffs, const float* grad_coeffs,
+                                  const float* Sc, const Chunks& ch, int64_t B, int64_t n_points, float* grad_path, void* workspace,
+                                  sig::JitKernel& bk, const sig::Plan& bp, hipStream_t st)
+{
+    sig::WindowList rows;
+    rows.K = ch.C; rows.max_len = ch.Lc;
+    const size_t t_bytes = jit_dxt_bytes(w, B * ch.C, ch.Lc + 1, 1), nb = chunk_array_bytes(w, B, ch.C);
+    float* gdx = (float*)workspace;
+    float* dxT = (float*)((unsigned char*)workspace + t_bytes);
+    float* Abar = (float*)((unsigned char*)workspace + 2 * t_bytes);
+    const float* Pfx = Sc;
+    const sig::WordTables tab = word_tables(w);
+    const int64_t Lpad = jit_lpad(w, ch.Lc + 1, 1);
+    // rows of one path share the points between their chunks: the chain rule adds into grad_path, which the adjoint
+    // kernel clears on the way
+    const int64_t n_gp = B * n_points * w.d;
+    hipError_t e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, gdx, st, rows);
+    if (ch.C == 2) {
+        // two chunks: the signature at the end of the first is the first chunk's own, what follows it the second's
+        // (row c + 1 of the chunk signatures, read as row c of an array that starts one row later)
+        if (e == hipSuccess) e = sig::words_adjoint(tab, grad_coeffs, Sc + w.size(), B, 2, Abar, grad_path, n_gp, st);
+    } else {
+        float* P = (float*)((unsigned char*)workspace + 2 * t_bytes + nb);
+        if (e == hipSuccess) e = sig::words_scan(tab, Sc, B, (int)ch.C, false, P, nullptr, st);
+        if (e == hipSuccess) e = sig::words_scan(tab, Sc, B, (int)ch.C, true, Abar, nullptr, st);
+        if (e == hipSuccess) e = sig::words_adjoint(tab, grad_coeffs, Abar, B, (int)ch.C, Abar, grad_path, n_gp, st);   // in place, row by row
+        Pfx = P;
+    }
+    if (e != hipSuccess) return e;
+    hipEvent_t* pe = g_prof.next(1);
+    if (pe) (void)hipEventRecord(pe[0], st);
+    // the rows of the last chunk are the caller's terminal signature and gradient themselves
+    e = launch_jit_backward(bk, bp, dxT, Pfx, Abar, B * ch.C, ch.Lc, Lpad / bk.tile, w.size(), gdx, st, coeffs, grad_coeffs, ch.C);
+    if (pe) (void)hipEventRecord(pe[1], st);
+    if (e != hipSuccess) return e;
+    return sig::grad_points_transposed(gdx, B, n_points, w.d, Lpad, grad_path, st, rows);
+}
+// sig_backward on a suffix-closed set recomputes the chunk signatures and takes the same route where that still wins:
+// from four chunks on by the rule of the checkpointed calls (measured: 64 paths x 4,096 segments 2.36 -> 0.67 ms,
+// 512 x 2,048 1.57 -> 1.24 ms; with two chunks the second forward pass eats the gain).
+// workspace: | backward part (its first bytes serve the forward's transposed increments before) | chunk signatures |
+bool words_backward_recomputes(const sig::WordSet& w, const Chunks& ch) { return w.kind != 0 && ch.C >= 4; }
+size_t words_backward_recompute_first(const sig::WordSet& w, int64_t B, const Chunks& ch)
+{
+    return std::max(words_backward_ckpt_workspace(w, B, ch), words_forward_ckpt_workspace(w, B, ch));
+}
+size_t words_backward_recompute_workspace(const sig::WordSet& w, int64_t B, const Chunks& ch)
+{
+    return words_backward_recompute_first(w, B, ch) + chunk_array_bytes(w, B, ch.C);
 }
 
 // ---- full truncations without a register-resident kernel of their own: lanes = words -----------------------
@@ -802,7 +855,8 @@ size_t sig_forward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_p
     return n;
 }
 
-size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
+// what sig_backward needs when a suffix-closed set does not take time chunks of its own (sig_backward_static)
+static size_t backward_workspace_whole_paths(const sig_wordset* ws, int64_t B, int64_t n_points)
 {
     if (!ws || B <= 0 || n_points <= 1) return 0;
     const sig::WordSet& w = *W(ws);
@@ -815,6 +869,18 @@ size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_
         // the specialised kernels keep the increment gradients in the (padded) layout of their transposed increments
         const size_t t = jit_dxt_bytes(w, B, n_points, 1);
         n = std::max(n, t) + t;
+    }
+    return n;
+}
+
+size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
+{
+    size_t n = backward_workspace_whole_paths(ws, B, n_points);
+    if (n == 0) return 0;
+    const sig::WordSet& w = *W(ws);
+    if (w.kind != 0 && jit_enabled(w)) {
+        const Chunks ch = checkpoint_chunks(w, B, n_points);
+        if (words_backward_recomputes(w, ch)) n = std::max(n, words_backward_recompute_workspace(w, B, ch));
     }
     return n;
 }
@@ -984,7 +1050,7 @@ static int backward_checkpointed(const sig::WordSet& w, const float* path, const
 
 static int backward_impl(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
                          int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes, void* stream, Build how,
-                         float* residual = nullptr)
+                         float* residual = nullptr, bool word_chunks = true)
 {
     int rc = check_common(ws, path, B, n_points);
     if (rc != SIG_OK) return rc;
@@ -996,11 +1062,24 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
         hipError_t e = sig::fill_zero(grad_path, B * w.d, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
-    const size_t need = sig_backward_workspace_bytes(ws, B, n_points);
+    const size_t need = word_chunks ? sig_backward_workspace_bytes(ws, B, n_points) : backward_workspace_whole_paths(ws, B, n_points);
     if (!workspace || workspace_bytes < need) return SIG_EWORKSPACE;
     if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
     float* gdx = (float*)workspace;
     CallTimer whole(1, st);
+    if (word_chunks && w.kind != 0 && jit_enabled(w) && !residual) {
+        // suffix-closed set, few long paths: chunk signatures recomputed, then the route of the checkpointed call
+        const Chunks wc = checkpoint_chunks(w, B, n_points);
+        sig::JitKernel *fk, *bk;
+        const sig::Plan *fp = nullptr, *bp = nullptr;
+        if (words_backward_recomputes(w, wc) && words_kernels(w, B * wc.C, &fk, &fp, &bk, &bp)) {
+            float* Sc = (float*)((unsigned char*)workspace + words_backward_recompute_first(w, B, wc));
+            hipError_t ce = words_forward_chunked(w, path, B, n_points, wc, *fk, *fp, (float*)workspace, Sc, nullptr, st);
+            if (ce == hipSuccess)
+                ce = words_backward_chunked(w, path, coeffs, grad_coeffs, Sc, wc, B, n_points, grad_path, workspace, *bk, *bp, st);
+            return ce == hipSuccess ? SIG_OK : hip_fail(ce);
+        }
+    }
     hipError_t e = hipSuccess;
     const bool trunc = use_trunc_backward(w, B);
     BwdShape ch = trunc ? trunc_backward_shape(w, B, n_points) : BwdShape{false, false, 1, n_points - 1};
@@ -1223,40 +1302,8 @@ int sig_backward_checkpointed(const sig_wordset* ws, const float* path, const fl
         if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)checkpoint & 255) != 0) return SIG_EINVAL;
         hipStream_t st = (hipStream_t)stream;
         CallTimer whole(1, st);
-        sig::WindowList rows;
-        rows.K = ch.C; rows.max_len = ch.Lc;
-        const size_t t_bytes = jit_dxt_bytes(w, B * ch.C, ch.Lc + 1, 1), nb = chunk_array_bytes(w, B, ch.C);
-        float* gdx = (float*)workspace;
-        float* dxT = (float*)((unsigned char*)workspace + t_bytes);
-        float* Abar = (float*)((unsigned char*)workspace + 2 * t_bytes);
-        const float* Sc = (const float*)checkpoint;
-        const float* Pfx = Sc;
-        const sig::WordTables tab = word_tables(w);
-        const int64_t Lpad = jit_lpad(w, ch.Lc + 1, 1);
-        // rows of one path share the points between their chunks: the chain rule adds into grad_path, which the adjoint
-        // kernel clears on the way
-        const int64_t n_gp = B * n_points * w.d;
-        hipError_t e = sig::increments_transposed(path, B, n_points, w.d, Lpad, dxT, gdx, st, rows);
-        if (ch.C == 2) {
-            // two chunks: the signature at the end of the first is the first chunk's own, what follows it the second's
-            // (row c + 1 of the checkpoint, read as row c of an array that starts one row later)
-            if (e == hipSuccess) e = sig::words_adjoint(tab, grad_coeffs, Sc + w.size(), B, 2, Abar, grad_path, n_gp, st);
-        } else {
-            float* P = (float*)((unsigned char*)workspace + 2 * t_bytes + nb);
-            if (e == hipSuccess) e = sig::words_scan(tab, Sc, B, (int)ch.C, false, P, nullptr, st);
-            if (e == hipSuccess) e = sig::words_scan(tab, Sc, B, (int)ch.C, true, Abar, nullptr, st);
-            if (e == hipSuccess) e = sig::words_adjoint(tab, grad_coeffs, Abar, B, (int)ch.C, Abar, grad_path, n_gp, st);   // in place, row by row
-            Pfx = P;
-        }
-        if (e != hipSuccess) return hip_fail(e);
-        hipEvent_t* pe = g_prof.next(1);
-        if (pe) (void)hipEventRecord(pe[0], st);
-        // the rows of the last chunk are the caller's terminal signature and gradient themselves
-        e = launch_jit_backward(*bk, *bp, dxT, Pfx, Abar, B * ch.C, ch.Lc, Lpad / bk->tile, w.size(), gdx, st, coeffs, grad_coeffs,
-                                ch.C);
-        if (pe) (void)hipEventRecord(pe[1], st);
-        if (e != hipSuccess) return hip_fail(e);
-        e = sig::grad_points_transposed(gdx, B, n_points, w.d, Lpad, grad_path, st, rows);
+        hipError_t e = words_backward_chunked(w, path, coeffs, grad_coeffs, (const float*)checkpoint, ch, B, n_points, grad_path,
+                                              workspace, *bk, *bp, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
     if (!workspace || workspace_bytes < sig_backward_checkpointed_workspace_bytes(ws, B, n_points)) return SIG_EWORKSPACE;
@@ -1283,12 +1330,12 @@ int sig_backward_static(const sig_wordset* ws, const float* path, const float* c
 {
     int rc = check_common(ws, path, B, n_points);
     if (rc != SIG_OK) return rc;
-    if (sig_backward_workspace_bytes(ws, B, n_points) > (size_t)SIG_STATIC_SCRATCH_BYTES) return SIG_ETOOLARGE;
+    if (backward_workspace_whole_paths(ws, B, n_points) > (size_t)SIG_STATIC_SCRATCH_BYTES) return SIG_ETOOLARGE;
     void* scratch_ptr = nullptr;                         // this device's copy of the static array
     hipError_t e = sig::static_scratch(&scratch_ptr);
     if (e != hipSuccess) return hip_fail(e);
     return backward_impl(ws, path, coeffs, grad_coeffs, B, n_points, grad_path, scratch_ptr, (size_t)SIG_STATIC_SCRATCH_BYTES, stream,
-                         Build::loaded_only);
+                         Build::loaded_only, nullptr, false);
 }
 
 // ---- windows: every (path, window) pair is gathered into a path of its own (padded with its last point), the
