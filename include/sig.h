@@ -211,8 +211,8 @@ int    sig_wordset_upload(sig_wordset* ws, void* dev_buf /*device*/, size_t dev_
  * workspace: device, sig_forward_workspace_bytes bytes (may be 0 -> NULL allowed), 256-byte aligned,
  *            contents undefined before and after.
  * Full truncations with few paths are cut into time chunks that run side by side and are multiplied together
- * afterwards (Chen's relation, eq. 2, is associative); sig_backward does the same and recomputes the chunk
- * signatures from the path.  Word sets closed under suffixes (sig_wordset_suffix_closed) that run through the
+ * afterwards (Chen's relation, eq. 2, is associative); sig_backward does the same where four or more chunks fit
+ * (or on request, option "chunks") and recomputes the chunk signatures from the path.  Word sets closed under suffixes (sig_wordset_suffix_closed) that run through the
  * run-time specialised kernels take the chunks of the checkpointed calls below in sig_forward as well, with the
  * chunk signatures in the workspace; sig_backward recomputes them and does the same from four chunks on (few long
  * paths), where that still beats walking whole paths.

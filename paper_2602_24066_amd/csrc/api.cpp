@@ -104,10 +104,13 @@ struct CallTimer {
 // relation.  Measured on the three instantiated shapes this pays off for the forward kernels once a chunk is a
 // few hundred segments long (the chunk products and the second launch cost about as much as 100 segments); a
 // chunked backward pass that starts from the terminal signature alone has to recompute the chunk signatures, a forward
-// pass of its own, so sig_backward chunks only on request (option "chunks", used by the tests) and the checkpointed
-// calls, which keep the chunk signatures, are the way to more rows.
+// pass of its own, so sig_backward chunks on request (option "chunks") and, by itself, only where four or more chunks
+// fit (few long paths, see below); otherwise the checkpointed calls, which keep the chunk signatures, are the way to
+// more rows.
 struct Chunks { int64_t C, Lc; };
-Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points)
+// own_chunks = false: sig_backward does not chunk by itself (sig_backward_static, whose scratch array is sized for
+// whole paths).
+Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points, bool own_chunks = true)
 {
     const int64_t L = n_points - 1;
     int64_t C = 1;
@@ -118,6 +121,14 @@ Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points)
             const int64_t slots = (int64_t)1024 * sig::trunc_occupancy(w.d, w.depth, dir);
             C = slots / sig::trunc_waves_per_row(w.d, w.depth, dir) / std::max<int64_t>(B, 1);
             C = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(C, 64), L / 256));
+        } else if (own_chunks && !sig::trunc_backward_tails_available(w.d, w.depth)) {
+            // few long paths: even with the chunk signatures recomputed, four or eight chunks side by side beat a walk
+            // over whole paths that leaves most SIMDs empty (measured, d = 16: 8 paths x 8,192 segments 3.92 -> 1.00 ms,
+            // 32 x 4,096 2.00 -> 1.09 ms; d = 8: 16 x 4,096 2.63 -> 0.67 ms, 64 x 2,048 1.33 -> 0.74 ms); with two
+            // chunks the second forward pass eats the gain
+            const int64_t rows_wanted = 2048 / sig::trunc_waves_per_row(w.d, w.depth, 1);
+            C = std::min<int64_t>(std::min<int64_t>(8, rows_wanted / std::max<int64_t>(B, 1)), L / 256);
+            if (C < 4) C = 1;
         }
     }
     const int64_t Lc = (L + C - 1) / C;
@@ -155,10 +166,10 @@ int64_t trunc_forward_fused_chunks(const sig::WordSet& w, int64_t B, int64_t n_p
 // The option "bwd_tails" = 0 switches it off, = 1 takes the unfused form with chunk arrays in HBM ("chunks" chunks),
 // =2 / =4 / =8 force the fused form with that many chunks.
 struct BwdShape { bool tails, fused; int64_t C, Lc; };
-BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points)
+BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points, bool own_chunks = true)
 {
     const int64_t L = n_points - 1;
-    const Chunks ch = trunc_chunks(w, 1, B, n_points);
+    const Chunks ch = trunc_chunks(w, 1, B, n_points, own_chunks);
     BwdShape s{false, false, ch.C, ch.Lc};
     if (!sig::trunc_backward_tails_available(w.d, w.depth)) return s;
     const int f = w.opt.bwd_tails;
@@ -855,15 +866,15 @@ size_t sig_forward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_p
     return n;
 }
 
-// what sig_backward needs when a suffix-closed set does not take time chunks of its own (sig_backward_static)
-static size_t backward_workspace_whole_paths(const sig_wordset* ws, int64_t B, int64_t n_points)
+// what sig_backward needs; own_chunks = false: when it takes no time chunks of its own (sig_backward_static)
+static size_t backward_workspace(const sig_wordset* ws, int64_t B, int64_t n_points, bool own_chunks)
 {
     if (!ws || B <= 0 || n_points <= 1) return 0;
     const sig::WordSet& w = *W(ws);
     size_t n = (size_t)B * (size_t)(n_points - 1) * (size_t)w.d * sizeof(float);
     n = (n + 255) & ~(size_t)255;                                   // gradient with respect to the increments
     if (use_trunc_backward(w, B)) {
-        const BwdShape ch = trunc_backward_shape(w, B, n_points);
+        const BwdShape ch = trunc_backward_shape(w, B, n_points, own_chunks);
         if (ch.C > 1 && !ch.fused) n += 4 * chunk_array_bytes(w, B, ch.C);   // chunk signatures, prefixes, suffixes, adjoints
     } else if (jit_enabled(w)) {
         // the specialised kernels keep the increment gradients in the (padded) layout of their transposed increments
@@ -875,7 +886,7 @@ static size_t backward_workspace_whole_paths(const sig_wordset* ws, int64_t B, i
 
 size_t sig_backward_workspace_bytes(const sig_wordset* ws, int64_t B, int64_t n_points)
 {
-    size_t n = backward_workspace_whole_paths(ws, B, n_points);
+    size_t n = backward_workspace(ws, B, n_points, true);
     if (n == 0) return 0;
     const sig::WordSet& w = *W(ws);
     if (w.kind != 0 && jit_enabled(w)) {
@@ -1050,7 +1061,7 @@ static int backward_checkpointed(const sig::WordSet& w, const float* path, const
 
 static int backward_impl(const sig_wordset* ws, const float* path, const float* coeffs, const float* grad_coeffs, int64_t B,
                          int64_t n_points, float* grad_path, void* workspace, size_t workspace_bytes, void* stream, Build how,
-                         float* residual = nullptr, bool word_chunks = true)
+                         float* residual = nullptr, bool word_chunks = true /* false: no time chunks of its own */)
 {
     int rc = check_common(ws, path, B, n_points);
     if (rc != SIG_OK) return rc;
@@ -1062,7 +1073,7 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
         hipError_t e = sig::fill_zero(grad_path, B * w.d, st);
         return e == hipSuccess ? SIG_OK : hip_fail(e);
     }
-    const size_t need = word_chunks ? sig_backward_workspace_bytes(ws, B, n_points) : backward_workspace_whole_paths(ws, B, n_points);
+    const size_t need = word_chunks ? sig_backward_workspace_bytes(ws, B, n_points) : backward_workspace(ws, B, n_points, false);
     if (!workspace || workspace_bytes < need) return SIG_EWORKSPACE;
     if (((uintptr_t)workspace & 255) != 0) return SIG_EINVAL;
     float* gdx = (float*)workspace;
@@ -1082,7 +1093,7 @@ static int backward_impl(const sig_wordset* ws, const float* path, const float* 
     }
     hipError_t e = hipSuccess;
     const bool trunc = use_trunc_backward(w, B);
-    BwdShape ch = trunc ? trunc_backward_shape(w, B, n_points) : BwdShape{false, false, 1, n_points - 1};
+    BwdShape ch = trunc ? trunc_backward_shape(w, B, n_points, word_chunks) : BwdShape{false, false, 1, n_points - 1};
     if (residual) {                      // reported by the kernels that walk whole paths with several wavefronts per row
         if (!trunc) return SIG_EUNSUPPORTED;
         ch = BwdShape{false, false, 1, n_points - 1};
@@ -1330,7 +1341,7 @@ int sig_backward_static(const sig_wordset* ws, const float* path, const float* c
 {
     int rc = check_common(ws, path, B, n_points);
     if (rc != SIG_OK) return rc;
-    if (backward_workspace_whole_paths(ws, B, n_points) > (size_t)SIG_STATIC_SCRATCH_BYTES) return SIG_ETOOLARGE;
+    if (backward_workspace(ws, B, n_points, false) > (size_t)SIG_STATIC_SCRATCH_BYTES) return SIG_ETOOLARGE;
     void* scratch_ptr = nullptr;                         // this device's copy of the static array
     hipError_t e = sig::static_scratch(&scratch_ptr);
     if (e != hipSuccess) return hip_fail(e);

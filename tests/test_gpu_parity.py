@@ -230,6 +230,34 @@ def test_checkpointed_word_sets(case):
         assert e <= FWD_TOL, f"{case}: sig_forward, level {n}: {e:.3e}"
 
 
+@pytest.mark.parametrize("d,depth,B,L", [(8, 5, 3, 1100), (16, 4, 2, 1030)])
+def test_plain_backward_takes_time_chunks_for_few_long_paths(d, depth, B, L):
+    """sig_backward on few long paths of a full truncation recomputes the chunk signatures and walks four chunks side
+    by side (its workspace then holds four chunk arrays); the result is the oracle's, and that of the entry point
+    with the static scratch array, which always walks whole paths."""
+    import torch
+    ws, W = build_both("truncated", d, depth=depth)
+    lib = S.load_library()
+    gdx = (4 * B * L * d + 255) // 256 * 256
+    per_array = (4 * B * 4 * ws.size + 255) // 256 * 256
+    assert lib.sig_backward_workspace_bytes(ws._h, B, L + 1) == gdx + 4 * per_array
+    X = make_path("iid", 6100 + L, B, L, d)
+    G = make_grad_coeffs(6200 + L, B, ws.size)
+    xp, grad = torch.from_numpy(X).cuda(), torch.from_numpy(G).cuda()
+    coeffs = S.sig_forward(ws, xp)
+    gp = S.sig_backward(ws, xp, coeffs, grad)
+    gs = torch.empty_like(xp)
+    S.sig_backward_static(ws, xp, coeffs, grad, gs)
+    torch.cuda.synchronize()
+    O.set_threads(2)
+    try:
+        gref = O.backward_dense(X, depth, G.astype(np.float64))
+    finally:
+        O.set_threads(16)
+    assert O.grad_errors(gp.cpu().numpy(), gref).max() <= BWD_TOL
+    assert O.grad_errors(gs.cpu().numpy(), gref).max() <= BWD_TOL
+
+
 def test_checkpointed_word_sets_reject_bad_buffers():
     """Buffers that are missing, too small or misaligned are refused with an error code before anything is launched."""
     import ctypes
