@@ -500,6 +500,22 @@ def main():
                 "kernels": [wsp.kernel_name(False, Bp, Mp), wsp.kernel_name(True, Bp, Mp)]}
         out["paper_table_shapes"] = table
 
+        # few long paths: sig_backward cuts every path into time chunks by itself (Chen's relation, eq. 2; the chunk
+        # signatures are recomputed); beside it the same backward pass over whole paths (sig_backward_static never chunks)
+        c5w = WORKLOADS["c5"]
+        wsf = S.sig_wordset_build_truncated(c5w.d, c5w.depth)
+        wsf.upload("cuda:0")
+        Bf, Lf = 8, 8192
+        Xf = torch.from_numpy(make_path("iid", 91, Bf, Lf, wsf.dim)).cuda()
+        cf = S.sig_forward(wsf, Xf)
+        gf = torch.randn_like(cf)
+        gpf = torch.empty_like(Xf)
+        out["few_long_paths"] = {
+            "workload": f"c5 word set, B={Bf} L={Lf}", "coeffs": wsf.size,
+            "fwd_ms": round(gpu_ms(lambda: S.sig_forward(wsf, Xf, out=cf), 50), 4),
+            "bwd_ms": round(gpu_ms(lambda: S.sig_backward(wsf, Xf, cf, gf, out=gpf), 50), 4),
+            "bwd_ms_whole_paths": round(gpu_ms(lambda: S.sig_backward_static(wsf, Xf, cf, gf, gpf), 20), 4)}
+
         # the other word-set builders (host only): graph-induced set and the sparse lead-lag set of a 5-dimensional path
         t0 = time.perf_counter()
         g = S.sig_wordset_build_graph(10, [(a, b) for a in range(10) for b in range(10) if 0 < b - a <= 3], 6)
