@@ -498,8 +498,7 @@ hipError_t words_backward_chunked(const sig::WordSet& w, const float* path, cons
         if (e == hipSuccess) e = sig::words_adjoint(tab, grad_coeffs, Sc + w.size(), B, 2, Abar, grad_path, n_gp, st);
     } else {
         float* P = (float*)((unsigned char*)workspace + 2 * t_bytes + nb);
-        if (e == hipSuccess) e = sig::words_scan(tab, Sc, B, (int)ch.C, false, P, nullptr, st);
-        if (e == hipSuccess) e = sig::words_scan(tab, Sc, B, (int)ch.C, true, Abar, nullptr, st);
+        if (e == hipSuccess) e = sig::words_scan_both(tab, Sc, B, (int)ch.C, P, Abar, st);
         if (e == hipSuccess) e = sig::words_adjoint(tab, grad_coeffs, Abar, B, (int)ch.C, Abar, grad_path, n_gp, st);   // in place, row by row
         Pfx = P;
     }
@@ -513,7 +512,7 @@ hipError_t words_backward_chunked(const sig::WordSet& w, const float* path, cons
     return sig::grad_points_transposed(gdx, B, n_points, w.d, Lpad, grad_path, st, rows);
 }
 // sig_backward on a suffix-closed set recomputes the chunk signatures and takes the same route where that still wins:
-// from four chunks on by the rule of the checkpointed calls (measured: 64 paths x 4,096 segments 2.36 -> 0.67 ms,
+// from four chunks on by the rule of the checkpointed calls (measured: 64 paths x 4,096 segments 2.36 -> 0.62 ms,
 // 512 x 2,048 1.57 -> 1.24 ms; with two chunks the second forward pass eats the gain).
 // workspace: | backward part (its first bytes serve the forward's transposed increments before) | chunk signatures |
 bool words_backward_recomputes(const sig::WordSet& w, const Chunks& ch) { return w.kind != 0 && ch.C >= 4; }

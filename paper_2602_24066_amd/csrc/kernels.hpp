@@ -109,6 +109,9 @@ size_t words_scan_lds_bytes(int64_t W);
 hipError_t words_scan(const WordTables& t, const float* S, int64_t B, int C, bool reverse, float* rows, float* last,
                       hipStream_t stream);
 // Abar[b][c](u) = grad[b](u) + sum_v grad[b](u v) Q[b][c](v) for c <= C - 2; Q, Abar [B][C][W], rows C - 1 left alone
+// both scans in one launch (two layers of workgroups): rows_forward as the forward scan's rows, rows_reverse as the reverse scan's
+hipError_t words_scan_both(const WordTables& t, const float* S, int64_t B, int C, float* rows_forward, float* rows_reverse,
+                           hipStream_t stream);
 // zeroed: nullptr, or an array of n_zeroed floats that the kernel clears on the way
 hipError_t words_adjoint(const WordTables& t, const float* grad, const float* Q, int64_t B, int C, float* Abar, float* zeroed,
                          int64_t n_zeroed, hipStream_t stream);

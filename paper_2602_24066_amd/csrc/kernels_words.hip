@@ -70,10 +70,17 @@ __device__ __forceinline__ void copy_row(const float* src, float* dst, int n, in
 // signature at the end of chunk c, to row c of `rows` [B][C][W] if given; the last product also to `last` [B][W] if
 // given.  Reverse scan: Q_c = S_{c+1} (x) .. (x) S_{C-1} for c = C-2 .. 0 to row c of `rows` (row C-1 is not written).
 __global__ __launch_bounds__(kWordsThreads) void words_scan_kernel(WordTables t, const float* __restrict__ S, int C, int reverse,
-                                                                   float* __restrict__ rows, float* __restrict__ last)
+                                                                   float* __restrict__ rows, float* __restrict__ last,
+                                                                   float* __restrict__ rows_reverse)
 {
     extern __shared__ float sm[];
     const int tid = threadIdx.x;
+    // both scans in one launch: the second layer of workgroups runs the reverse scan into rows_reverse
+    if (blockIdx.y == 1) {
+        reverse = 1;
+        rows = rows_reverse;
+        last = nullptr;
+    }
     const int64_t b = blockIdx.x;
     const int W = t.W;
     float* acc = sm;
@@ -199,7 +206,21 @@ hipError_t words_scan(const WordTables& t, const float* S, int64_t B, int C, boo
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&words_scan_kernel), (int)(160 * 1024));
         if (e != hipSuccess) return e;
     }
-    words_scan_kernel<<<(unsigned)B, kWordsThreads, lds, stream>>>(t, S, C, reverse ? 1 : 0, rows, last);
+    words_scan_kernel<<<(unsigned)B, kWordsThreads, lds, stream>>>(t, S, C, reverse ? 1 : 0, rows, last, nullptr);
+    return hipGetLastError();
+}
+
+hipError_t words_scan_both(const WordTables& t, const float* S, int64_t B, int C, float* rows_forward, float* rows_reverse,
+                           hipStream_t stream)
+{
+    if (B < 1 || C < 2 || B > 0x7fffffff || t.W < 1 || t.W > 0xffff || !rows_forward || !rows_reverse) return hipErrorInvalidValue;
+    const size_t lds = words_scan_lds_bytes(t.W);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    if (lds > 64 * 1024) {
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&words_scan_kernel), (int)(160 * 1024));
+        if (e != hipSuccess) return e;
+    }
+    words_scan_kernel<<<dim3((unsigned)B, 2), kWordsThreads, lds, stream>>>(t, S, C, 0, rows_forward, nullptr, rows_reverse);
     return hipGetLastError();
 }
 
