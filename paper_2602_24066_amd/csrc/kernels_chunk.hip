@@ -162,17 +162,23 @@ __global__ __launch_bounds__(1024) void chunk_scan_kernel(const float* __restric
             }
         }
     } else {
-        copy_row(S, P, nullptr, (int)W);
-        if (bwd) {
-            copy_row(terminal + b * W, P + (int64_t)(C - 1) * W, nullptr, (int)W);
-            copy_row(S + (int64_t)(C - 1) * W, Qb + (int64_t)(C - 2) * W, nullptr, (int)W);
+        // signatures too large for LDS: products in global memory; with gridDim.y == 2 (backward) workgroup 0 of a
+        // path does the products from the left, workgroup 1 those from the right, side by side
+        const bool do_prefix = gridDim.y == 1 || blockIdx.y == 0;
+        const bool do_suffix = bwd && (gridDim.y == 1 || blockIdx.y == 1);
+        if (do_prefix) {
+            copy_row(S, P, nullptr, (int)W);
+            if (bwd) copy_row(terminal + b * W, P + (int64_t)(C - 1) * W, nullptr, (int)W);
         }
+        if (do_suffix) copy_row(S + (int64_t)(C - 1) * W, Qb + (int64_t)(C - 2) * W, nullptr, (int)W);
         const int last = bwd ? C - 2 : C - 1;
         for (int s = 1; s <= last; ++s) {
             __syncthreads();
-            float* dst = (!bwd && s == C - 1) ? coeffs_out + b * W : P + (int64_t)s * W;
-            tensor_product(P + (int64_t)(s - 1) * W, S + (int64_t)s * W, dst, nullptr, g);
-            if (bwd) {
+            if (do_prefix) {
+                float* dst = (!bwd && s == C - 1) ? coeffs_out + b * W : P + (int64_t)s * W;
+                tensor_product(P + (int64_t)(s - 1) * W, S + (int64_t)s * W, dst, nullptr, g);
+            }
+            if (do_suffix) {
                 const int q = C - 2 - s;              // >= 0 because s <= C - 2
                 tensor_product(S + (int64_t)(q + 1) * W, Qb + (int64_t)(q + 1) * W, Qb + (int64_t)q * W, nullptr, g);
             }
@@ -433,7 +439,8 @@ hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, c
             acc_stride = dst_stride;
         }
     } else {
-        chunk_scan_kernel<false><<<(unsigned)B, 1024, 0, stream>>>(Sc, Pfx, Q, terminal, coeffs_out, nullptr, nullptr, C, g);
+        chunk_scan_kernel<false><<<dim3((unsigned)B, Q != nullptr ? 2 : 1), 1024, 0, stream>>>(Sc, Pfx, Q, terminal, coeffs_out, nullptr,
+                                                                                          nullptr, C, g);
     }
     return hipGetLastError();
 }
