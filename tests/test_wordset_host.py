@@ -459,6 +459,11 @@ def test_suffix_tables(case):
     assert lib.sig_backward_checkpointed_workspace_bytes(ws._h, 512, 513) >= lib.sig_backward_workspace_bytes(ws._h, 512, 513)
     ws.set_option("no_jit", 1)                                                 # the table-driven kernels take whole paths
     assert lib.sig_checkpoint_bytes(ws._h, 512, 513) == 0
+    if case == "anisotropic-c4":
+        # a suffix-closed set too large for three signatures in LDS (16,802 words) takes whole paths as well
+        big = S.sig_wordset_build_anisotropic(6, (1, 1, 2, 2, 3, 3), 9.0)
+        assert big.size == 16802 and big.suffix_closed and big.term_tables() is not None
+        assert lib.sig_checkpoint_bytes(big._h, 64, 4097) == 0 and lib.sig_checkpoint_chunks(big._h, 64, 4097) == 1
 
 
 @pytest.mark.parametrize("case", ["anisotropic", "no-repeat list"])
