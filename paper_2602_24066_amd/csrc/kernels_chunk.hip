@@ -200,6 +200,15 @@ __global__ __launch_bounds__(256) void chunk_product_kernel(const float* __restr
     *(f4*)(out + b * out_stride + o) = quad_product(a + b * a_stride, bfac + b * b_stride, g, n, o - g.ls[n]);
 }
 
+// dst[b] = src[b] for every path, rows of W floats (a multiple of 4) at the given strides
+__global__ __launch_bounds__(256) void chunk_copy_rows_kernel(const float* __restrict__ src, int64_t src_stride, float* __restrict__ dst,
+                                                              int64_t dst_stride, int W)
+{
+    const int o = 4 * (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (o >= W) return;
+    *(f4*)(dst + (int64_t)blockIdx.y * dst_stride + o) = *(const f4*)(src + (int64_t)blockIdx.y * src_stride + o);
+}
+
 // coefficient of one word (length n, index i inside the level) of a (x) b
 __device__ __forceinline__ float word_product(const float* a, const float* b, const Levels& g, int n, int i)
 {
@@ -437,6 +446,21 @@ hipError_t chunk_scan(int d, int depth, const float* Sc, float* Pfx, float* Q, c
                                                            dst_stride, g);
             acc = dst;
             acc_stride = dst_stride;
+        }
+    } else if (Q != nullptr && coeffs_out == nullptr && B <= 64 && g.W % 4 == 0) {
+        // backward with large signatures and few paths: a workgroup or two per path would leave the chip idle, so every
+        // product is spread over the whole grid (a launch per chunk boundary and direction)
+        const int64_t W = g.W, row = (int64_t)C * W;
+        const dim3 grid((unsigned)((W / 4 + 255) / 256), (unsigned)B);
+        chunk_copy_rows_kernel<<<grid, 256, 0, stream>>>(Sc, row, Pfx, row, (int)W);
+        chunk_copy_rows_kernel<<<grid, 256, 0, stream>>>(terminal, W, Pfx + (int64_t)(C - 1) * W, row, (int)W);
+        chunk_copy_rows_kernel<<<grid, 256, 0, stream>>>(Sc + (int64_t)(C - 1) * W, row, Q + (int64_t)(C - 2) * W, row, (int)W);
+        for (int s = 1; s <= C - 2; ++s) {
+            chunk_product_kernel<<<grid, 256, 0, stream>>>(Pfx + (int64_t)(s - 1) * W, row, Sc + (int64_t)s * W, row,
+                                                           Pfx + (int64_t)s * W, row, g);
+            const int q = C - 2 - s;
+            chunk_product_kernel<<<grid, 256, 0, stream>>>(Sc + (int64_t)(q + 1) * W, row, Q + (int64_t)(q + 1) * W, row,
+                                                           Q + (int64_t)q * W, row, g);
         }
     } else {
         chunk_scan_kernel<false><<<dim3((unsigned)B, Q != nullptr ? 2 : 1), 1024, 0, stream>>>(Sc, Pfx, Q, terminal, coeffs_out, nullptr,
