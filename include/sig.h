@@ -133,7 +133,7 @@ int64_t        sig_wordset_term_tables(const sig_wordset* ws, const uint32_t** p
  *   "bwd_tile"      [SIG_BWD_TILE]       LDS tile of the backward kernels, 0 = launcher's rule.  d = 8: 4, 8 or 16 segments;
  *                                        d = 16: 8, 12 or 16 segments, or 4 = 16 segments with the gradient sources
  *                                        summed every 4 (the form that fits two workgroups on a compute unit)
- *   "ckpt_chunks"   [SIG_CKPT_CHUNKS]    time chunks of the checkpointed calls: 0 launcher's rule, 1 off, 2..8 forced (..16 for word sets)
+ *   "ckpt_chunks"   [SIG_CKPT_CHUNKS]    time chunks of the checkpointed calls: 0 launcher's rule, 1 off, 2..16 forced
  *   "jit_fwd_tile"  [SIG_JIT_FWD_TILE]   segments per LDS tile of the specialised forward kernels: 0 default, 1..32
  * Workspace sizes depend on the knobs: query them again after a change.  Returns SIG_EINVAL for an unknown name.
  * Not to be called while another thread runs sig_forward / sig_backward on the same word set. */
@@ -254,7 +254,7 @@ int    sig_backward_residual(const sig_wordset* ws, const float* path, const flo
  * with the right factor taken at a chunk boundary), and inside a chunk the recursion is that of sig_backward
  * (Proposition 4.6).  Nothing is recomputed; the price is C times the memory of coeffs between the two calls, where
  * sig_forward / sig_backward keep the terminal signature alone (Section 4.2).  The library picks C for the batch
- * (2 .. 8): for full truncations whose backward kernel would otherwise leave SIMDs with a single wavefront (few
+ * (2 .. 16): for full truncations whose backward kernel would otherwise leave SIMDs with a single wavefront (few
  * paths with many segments), and for suffix-closed sets (sig_wordset_suffix_closed) of up to 13,653 words that run
  * through the run-time specialised kernels, which gain from more rows (up to eight chunks: at most 2,048 rows,
  * chunks of at least 256 segments, 128 for batches that stay at 512 rows or below).  Where it sees no gain sig_checkpoint_bytes is 0, `checkpoint` is not touched and

@@ -122,13 +122,13 @@ Chunks trunc_chunks(const sig::WordSet& w, int dir, int64_t B, int64_t n_points,
             C = slots / sig::trunc_waves_per_row(w.d, w.depth, dir) / std::max<int64_t>(B, 1);
             C = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(C, 64), L / 256));
         } else if (own_chunks && !sig::trunc_backward_tails_available(w.d, w.depth)) {
-            // few long paths: even with the chunk signatures recomputed, four or eight chunks side by side beat a walk
+            // few long paths: even with the chunk signatures recomputed, four to sixteen chunks side by side beat a walk
             // over whole paths that leaves most SIMDs empty (measured, d = 16: 8 paths x 8,192 segments 3.92 -> 1.00 ms,
             // 32 x 4,096 2.00 -> 1.09 ms; d = 8: 16 x 4,096 2.63 -> 0.67 ms, 64 x 2,048 1.33 -> 0.74 ms); with two
             // chunks the second forward pass eats the gain
             const int64_t rows_wanted = 2048 / sig::trunc_waves_per_row(w.d, w.depth, 1);
-            C = std::min<int64_t>(std::min<int64_t>(8, rows_wanted / std::max<int64_t>(B, 1)), L / 256);
-            if (C < 4) C = 1;
+            C = std::min<int64_t>(std::min<int64_t>(16, rows_wanted / std::max<int64_t>(B, 1)), L / 256);
+            C = C >= 16 ? 16 : (C >= 8 ? 8 : (C >= 4 ? 4 : 1));     // whole wavefronts per SIMD: 12 chunks lost to 8 when measured
         }
     }
     const int64_t Lc = (L + C - 1) / C;
@@ -185,7 +185,7 @@ BwdShape trunc_backward_shape(const sig::WordSet& w, int64_t B, int64_t n_points
 // Checkpointed form (sig_forward_checkpointed / sig_backward_checkpointed): the forward pass leaves the signatures of C
 // time chunks of every path in a buffer the caller keeps, and the backward pass walks the C chunks side by side
 // without recomputing them.  Taken where the backward kernel of a full truncation has too few rows to put two
-// wavefronts on every SIMD (eight wavefronts per row for d = 8, sixteen for d = 16); C = 2 .. 8, chunks of at least 64
+// wavefronts on every SIMD (eight wavefronts per row for d = 8, sixteen for d = 16); C = 2 .. 16, chunks of at least 64
 // segments (measured: 8 paths x 8,192 segments, d = 16: step 4.1 ms plain, 1.43 ms with four chunks, 1.00 ms with eight).
 // "ckpt_chunks" forces a count (0: this rule, 1: off).
 //
@@ -222,10 +222,11 @@ Chunks checkpoint_chunks(const sig::WordSet& w, int64_t B, int64_t n_points)
     if (w.kind == 0 && B >= 1 && B <= 65535 && sig::trunc_backward_available(w.d, w.depth) && sig::chunking_available(w.d, w.depth) &&
         !sig::trunc_backward_tails_available(w.d, w.depth)) {
         if (w.opt.ckpt_chunks > 0) {
-            C = std::min<int64_t>(w.opt.ckpt_chunks, 8);
+            C = std::min<int64_t>(w.opt.ckpt_chunks, 16);
         } else {
             const int64_t rows_wanted = 2048 / sig::trunc_waves_per_row(w.d, w.depth, 1);
-            C = std::min<int64_t>(8, (rows_wanted + B - 1) / B);
+            C = std::min<int64_t>(std::min<int64_t>(16, (rows_wanted + B - 1) / B), L / 64);
+            if (C > 4) C = C >= 16 ? 16 : (C >= 8 ? 8 : 4);         // beyond four: powers of two (whole wavefronts per SIMD)
         }
         C = std::max<int64_t>(1, std::min<int64_t>(C, L / 64));
     }

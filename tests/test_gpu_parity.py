@@ -134,7 +134,7 @@ def test_forward_chunks_in_one_workgroup(monkeypatch, B, L, chunks):
 # count, chunk lengths that do not divide L, the launcher's own choice, and shapes where it takes no chunks at all
 @pytest.mark.parametrize("d,depth,B,L,chunks", [(8, 5, 2, 200, 0), (8, 5, 3, 131, 2), (8, 5, 2, 197, 3), (8, 5, 1, 260, 4),
                                                 (16, 4, 2, 150, 2), (16, 4, 1, 200, 3), (16, 4, 2, 333, 0), (8, 5, 2, 40, 0),
-                                                (16, 4, 1, 530, 0), (8, 5, 2, 600, 7), (8, 5, 40, 300, 0),
+                                                (16, 4, 1, 530, 0), (8, 5, 2, 600, 7), (8, 5, 40, 300, 0), (8, 5, 1, 1100, 0),
                                                 (4, 6, 3, 300, 0),
                                                 (3, 4, 5, 100, 0)])
 def test_checkpointed_forward_and_backward(d, depth, B, L, chunks):
@@ -145,7 +145,9 @@ def test_checkpointed_forward_and_backward(d, depth, B, L, chunks):
     lib = S.load_library()
     nck = int(lib.sig_checkpoint_bytes(ws._h, B, L + 1))
     wanted = {8: 256, 16: 128}.get(d, 0)                  # rows that fill the chip with two wavefronts per SIMD
-    expect_chunks = chunks if chunks else (min(8, -(-wanted // B), L // 64) if d in (8, 16) and L >= 128 else 0)
+    expect_chunks = chunks if chunks else (min(16, -(-wanted // B), L // 64) if d in (8, 16) and L >= 128 else 0)
+    if not chunks and expect_chunks > 4:
+        expect_chunks = 16 if expect_chunks >= 16 else (8 if expect_chunks >= 8 else 4)    # beyond four: powers of two
     assert nck == (4 * B * expect_chunks * ws.size + 255) // 256 * 256
     X = make_path("iid", 2500 + L, B, L, d)
     G = make_grad_coeffs(2600 + L, B, ws.size)
